@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the sub-sampled Newton hot path on one MI355X.
+
+A step is one full SSN iteration on the image-like dense workload (60000 x 784, C = 10): full gradient
+and objective, Hessian sample of 5 % of the rows, <= 10 CG products H_S v, Armijo line search, update.
+Headline value: sub-sampled Hessian-vector products per second (back-to-back ssn_hess_apply on resident
+data).  Also reported: time per SSN iteration, the HBM roofline of the dominant kernel (HIP events inside
+the library), call-level effective bandwidth of objective / gradient / H_S v, and the CPU oracle timed on
+a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X datasheet HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--dtype", choices=["f64", "f32"], default="f64")
+    ap.add_argument("--config", type=int, default=1, help="index into the workload list (1 = image-like dense)")
+    ap.add_argument("--n", type=int, default=None, help="override the number of rows (debugging)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-other-dtype", action="store_true", help="skip the secondary-dtype figures")
+    ap.add_argument("--hv-calls", type=int, default=200)
+    return ap.parse_args()
+
+
+def kernel_bytes(n, p, K, nS, e):
+    """Algorithmic bytes one launch of each timed kernel has to move (X counted once per kernel)."""
+    return {
+        0: n * p * e + 4 * n + p * K * e,                       # margins + loss
+        1: n * p * e + 4 * n + p * K * e + n * K * e,           # margins + U out
+        2: n * p * e + n * K * e,                               # X^T U (full)
+        3: nS * p * e + 4 * nS + p * K * e + 2 * nS * K * e,    # sampled margins, P in, U out
+        4: nS * p * e + 4 * nS + nS * K * e,                    # sampled X^T U
+    }
+
+
+def call_bytes(n, p, K, nS, e):
+    """Algorithmic bytes per call: X is counted ONCE per call whatever the kernel count."""
+    return {
+        "objective": n * p * e + 4 * n + p * K * e,
+        "gradient": n * p * e + 4 * n + 2 * p * K * e,
+        "hess_apply": nS * p * e + 4 * nS + nS * K * e + 2 * p * K * e,
+    }
+
+
+KERNEL_NAMES = {0: "dense_rows_kernel<OBJ>", 1: "dense_rows_kernel<GRAD>", 2: "dense_xtu_kernel (n rows)",
+                3: "dense_rows_kernel<APPLY>", 4: "dense_xtu_kernel (|S| rows)"}
+
+
+def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
+    import numpy as np
+    import torch
+    from paper_1802_09113_amd import synth
+    from paper_1802_09113_amd.binding import Context
+
+    tdt = torch.float64 if dtype_name == "f64" else torch.float32
+    e = 8 if dtype_name == "f64" else 4
+    n, p, C, K, nS = data["n"], data["p"], data["C"], data["K"], data["nS"]
+    dev = "cuda:0"
+    X = torch.from_numpy(data["X"]).to(dev).to(tdt)
+    labels = torch.from_numpy(data["labels"]).to(dev)
+    ctx = Context(labels, C, data["lam"], X=X)
+    W = torch.zeros((p, K), dtype=tdt, device=dev)
+    out = {}
+    S_all = torch.from_numpy(synth.sample_schedule(n, nS, warmup + steps)).to(dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    if full_step:
+        if warmup > 0:
+            ctx.ssn_solve(W, S_all[:warmup].contiguous(), theta=1e-4, T=data["T"])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        recs, done = ctx.ssn_solve(W, S_all[warmup:].contiguous(), theta=1e-4, T=data["T"])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        assert done == steps
+        out["ms_per_step"] = (t1 - t0) * 1e3 / steps
+        out["products_in_steps"] = sum(r["cg_iters"] for r in recs)
+        out["hv_per_s_inside_cg"] = out["products_in_steps"] / max(sum(r["ms_cg"] for r in recs) * 1e-3, 1e-12)
+        out["phase_ms"] = {k: statistics.mean(r[k] for r in recs)
+                           for k in ("ms_grad", "ms_prepare", "ms_cg", "ms_linesearch", "ms_update")}
+        out["ls_evals_mean"] = statistics.mean(r["ls_evals"] for r in recs)
+        out["final_f"] = recs[-1]["f"]
+    else:
+        W.copy_(torch.from_numpy(synth.probe(p, K, sub=1, scale=0.05)).to(dev).to(tdt))
+
+    # back-to-back H_S v: rotating direction / result buffers, 5 batches, median
+    S = S_all[-1].contiguous()
+    ctx.ssn_hess_prepare(W, S)
+    V = [torch.from_numpy(synth.probe(p, K, sub=10 + i)).to(dev).to(tdt) for i in range(2)]
+    HV = [torch.empty_like(V[0]) for _ in range(2)]
+    for i in range(10):
+        ctx.ssn_hess_apply(V[i & 1], HV[i & 1])
+    torch.cuda.synchronize()
+    rates = []
+    for b in range(5):
+        a, z = ev(), ev()
+        a.record()
+        for i in range(hv_calls):
+            ctx.ssn_hess_apply(V[i & 1], HV[i & 1])
+        z.record()
+        torch.cuda.synchronize()
+        rates.append(hv_calls / (a.elapsed_time(z) * 1e-3))
+    out["hv_per_s"] = statistics.median(rates)
+
+    # gradient (asynchronous, no scalar read-back) and objective (returns a scalar: includes one sync)
+    G = torch.empty_like(W)
+    for _ in range(3):
+        ctx.ssn_gradient(W, G, want_f=False)
+    torch.cuda.synchronize()
+    a, z = ev(), ev()
+    a.record()
+    for _ in range(20):
+        ctx.ssn_gradient(W, G, want_f=False)
+    z.record()
+    torch.cuda.synchronize()
+    ms_grad = a.elapsed_time(z) / 20
+    t0 = time.perf_counter()
+    for _ in range(20):
+        ctx.ssn_objective(W)
+    ms_obj = (time.perf_counter() - t0) * 1e3 / 20
+    cb = call_bytes(n, p, K, nS, e)
+    ms_call = {"objective": ms_obj, "gradient": ms_grad, "hess_apply": 1e3 / out["hv_per_s"]}
+    out["calls"] = {k: {"ms": ms_call[k], "algorithmic_GB": cb[k] / 1e9,
+                        "GBps": cb[k] / ms_call[k] / 1e6, "frac_of_hbm_peak": cb[k] / ms_call[k] / 1e6 / HBM_PEAK_GBS}
+                    for k in cb}
+
+    # per-kernel durations from HIP events recorded by the library on its own stream
+    kb = kernel_bytes(n, p, K, nS, e)
+    kern = {}
+    for which in (0, 1, 2, 3, 4):
+        reps = 20 if which < 3 else 200
+        ctx.ssn_time_kernel(which, V[0] if which >= 3 else W, 3)
+        ms = ctx.ssn_time_kernel(which, V[0] if which >= 3 else W, reps)
+        kern[which] = {"kernel": KERNEL_NAMES[which], "ms": ms, "algorithmic_GB": kb[which] / 1e9,
+                       "GBps": kb[which] / ms / 1e6, "frac": kb[which] / ms / 1e6 / HBM_PEAK_GBS}
+    out["kernels"] = kern
+    ctx.close()
+    return out
+
+
+def cpu_baseline(data, budget_s=12.0):
+    """The oracle as it stands, single thread, on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle.oracle import Problem
+    from paper_1802_09113_amd import synth
+    pr = Problem(data["labels"], data["C"], data["lam"], X=data["X"])
+    W = np.zeros((pr.p, pr.K))
+    S = synth.sample_rows(pr.n, data["nS"])
+    V = synth.probe(pr.p, pr.K, sub=10)
+    t0 = time.perf_counter()
+    pr.hessvec(W, S, V)
+    one = time.perf_counter() - t0
+    reps = max(3, min(100, int(budget_s * 0.6 / max(one, 1e-6))))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        pr.hessvec(W, S, V)
+    hv_s = reps / (time.perf_counter() - t0)
+    t0 = time.perf_counter()
+    pr.ssn(W, S[None, :], theta=1e-4, T=data["T"])
+    iter_s = time.perf_counter() - t0
+    return {"value": hv_s, "unit": "Hess-vec products/s", "cores": 1, "kind": "oracle",
+            "sample": f"{reps} products H_S v (|S|={S.size} of n={pr.n}, p={pr.p}, C={pr.C}) at W=0, plus one full "
+                      f"SSN iteration of the same workload ({iter_s:.2f} s); gcc -O2, fp64 with long-double row sums",
+            "ssn_iteration_s": iter_s}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1\n")
+        sys.exit(2)
+    import torch
+    from paper_1802_09113_amd import synth
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    t_gen = time.perf_counter()
+    data = synth.make(args.config, n=args.n)
+    assert data["layout"] == "dense", "bench.py times the dense workloads"
+    sys.stderr.write(f"[bench] generated {data['name']} {data['n']}x{data['p']} C={data['C']} in "
+                     f"{time.perf_counter() - t_gen:.1f}s\n")
+    main_res = measure(data, args.dtype, args.steps, args.warmup, args.hv_calls)
+    sys.stderr.write(f"[bench] {args.dtype} measured\n")
+    other = None
+    if not args.no_other_dtype:
+        od = "f32" if args.dtype == "f64" else "f64"
+        other = measure(data, od, args.steps, args.warmup, args.hv_calls)
+        sys.stderr.write(f"[bench] {od} measured\n")
+    cpu = None if args.no_cpu else cpu_baseline(data)
+
+    # dominant kernel of a step: the launch with the largest share of the step's kernel time
+    k = main_res["kernels"]
+    per_step = {0: main_res["ls_evals_mean"] * k[0]["ms"], 1: k[1]["ms"], 2: k[2]["ms"],
+                3: data["T"] * k[3]["ms"], 4: data["T"] * k[4]["ms"]}
+    dom = max(per_step, key=per_step.get)
+    roof = {"bound": "hbm", "kernel": k[dom]["kernel"], "achieved": k[dom]["GBps"], "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": k[dom]["frac"], "traffic": None,
+            "ms_per_launch": k[dom]["ms"], "algorithmic_bytes_per_launch": k[dom]["algorithmic_GB"] * 1e9,
+            "share_of_step_kernel_time": per_step[dom] / sum(per_step.values())}
+    line = {
+        "metric": "sub-sampled Hess-vec products/s", "value": main_res["hv_per_s"], "unit": "products/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"{data['name']}: dense {data['n']}x{data['p']}, C={data['C']}, lambda={data['lam']}, "
+                               f"|S|={data['nS']} (5%), CG T={data['T']}, theta=1e-4, Armijo beta=1e-4 rho=0.5; "
+                               f"step = one SSN iteration", "config_index": args.config},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "time_per_ssn_iteration_ms": main_res["ms_per_step"],
+        "hv_per_s_inside_cg": main_res["hv_per_s_inside_cg"],
+        "phase_ms": main_res["phase_ms"],
+        "calls": main_res["calls"],
+        "kernels": {v["kernel"]: {kk: vv for kk, vv in v.items() if kk != "kernel"} for v in k.values()},
+        "final_f": main_res["final_f"],
+    }
+    if other is not None:
+        od = "f32" if args.dtype == "f64" else "f64"
+        line["other_dtype"] = {"dtype": od, "hv_per_s": other["hv_per_s"], "ms_per_step": other["ms_per_step"],
+                               "calls": other["calls"],
+                               "kernels": {v["kernel"]: {"ms": v["ms"], "GBps": v["GBps"], "frac": v["frac"]}
+                                           for v in other["kernels"].values()}}
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

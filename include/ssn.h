@@ -1,0 +1,198 @@
+/*
+ * ssn.h -- C ABI of the MI355X (gfx950) sub-sampled Newton hot path for
+ * L2-regularised multinomial logistic regression, after "GPU Accelerated
+ * Sub-Sampled Newton's Method" (arXiv 1802.09113).
+ *
+ * Problem (Sec. 3.3, eq. (5)): data matrix A (here X) with n rows and p
+ * features, labels b_i in {0..C-1}, weights x = [x_1;...;x_{C-1}] (here the
+ * p-by-K matrix W, K = C-1).  Label C-1 is the reference class whose margin is
+ * identically zero.
+ *
+ * Conventions common to every entry point
+ *   - Every function returns an int status: SSN_OK (0) or a negative SSN_E_*.
+ *     No exception crosses this boundary; ssn_strerror() names a status and
+ *     ssn_last_error() returns the context's last detailed message.
+ *   - Pointers marked [dev] are DEVICE pointers owned by the caller and only
+ *     borrowed: X / CSR arrays / labels for the life of the context, all other
+ *     arguments for the duration of the call.  Pointers marked [host] are
+ *     HOST pointers.  The library owns only the workspace inside ssn_ctx.
+ *   - Work is enqueued on the context's stream (a hipStream_t passed as
+ *     void*; NULL = the default stream).  Calls that return a scalar through
+ *     a [host] pointer wait for the stream before returning; all other calls
+ *     are asynchronous.
+ *   - Element type T is float (SSN_F32) or double (SSN_F64) for X/vals, W, V,
+ *     G, HV, P.  Sums over rows are carried in fp64 in both cases.
+ *   - W, V, G, HV, P (direction) are p-by-K, row-major, class index fastest,
+ *     leading dimension ldw >= K elements: entry (j,c) at [j*ldw + c].  This
+ *     is the paper's vec(.) ordering up to a fixed permutation, so norms and
+ *     inner products agree with the paper's d-vector.
+ *   - Scaling (SSN_SCALE_MEAN, the default): f and grad f carry 1/n on the
+ *     data term and the sampled Hessian 1/|S|.  SSN_SCALE_SUM reproduces the
+ *     paper's eq. (1) and (2b): factors 1 and n/|S|.  The regulariser
+ *     (lambda/2)||W||^2 is never scaled.
+ *   - Dense MFMA kernels handle 2 <= C <= 33 (K <= 32); CSR kernels 2 <= C <= 65.
+ */
+#ifndef SSN_H
+#define SSN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ssn_ctx ssn_ctx;
+
+typedef enum { SSN_F32 = 0, SSN_F64 = 1 } ssn_dtype;
+typedef enum { SSN_DENSE_ROWMAJOR = 0, SSN_CSR = 1 } ssn_layout;
+typedef enum { SSN_SCALE_MEAN = 0, SSN_SCALE_SUM = 1 } ssn_scale;
+
+enum {
+    SSN_OK = 0,
+    SSN_E_INVALID_ARG = -1,   /* NULL pointer, size < 1, lambda < 0, ld too small, misaligned ...   */
+    SSN_E_BAD_LABEL = -2,     /* a label outside [0,C)                                           */
+    SSN_E_BAD_INDEX = -3,     /* a sample index outside [0,n) or a CSR column outside [0,p)      */
+    SSN_E_NOT_PREPARED = -4,  /* ssn_hess_apply / ssn_cg before ssn_hess_prepare                 */
+    SSN_E_ALLOC = -5,         /* device allocation failed                                        */
+    SSN_E_HIP = -6,           /* a HIP runtime call failed                                       */
+    SSN_E_NONFINITE = -7,     /* objective evaluated to NaN/Inf                                  */
+    SSN_E_UNSUPPORTED = -8    /* shape outside the supported range (e.g. C too large)            */
+};
+
+/* Problem description.  Copied by ssn_create; the arrays it points to are borrowed. */
+typedef struct {
+    int64_t n, p;             /* rows, features                                                  */
+    int32_t C;                /* classes (K = C-1 weight columns)                                */
+    int32_t dtype;            /* ssn_dtype                                                       */
+    int32_t layout;           /* ssn_layout                                                      */
+    int32_t scale;            /* ssn_scale                                                       */
+    double lambda;            /* L2 regularisation, >= 0                                         */
+    const void *X;            /* [dev] dense: n-by-p row-major, element (i,j) at [i*ldx + j]     */
+    int64_t ldx;              /*       leading dimension in elements, >= p                       */
+    const int32_t *rowptr;    /* [dev] CSR: n+1 offsets                                          */
+    const int32_t *colidx;    /* [dev] CSR: nnz column ids in [0,p), ascending inside a row      */
+    const void *vals;         /* [dev] CSR: nnz values of type T                                 */
+    int64_t nnz;              /*       CSR: number of stored entries (< 2^31)                    */
+    const int32_t *labels;    /* [dev] n labels in [0,C)                                         */
+    int64_t ldw;              /* leading dimension of W, V, G, HV, P in elements, >= K           */
+    void *stream;             /* hipStream_t, or NULL                                            */
+} ssn_desc;
+
+/* Result of ssn_cg (Alg. 2). */
+typedef struct {
+    int32_t iters;            /* Hessian-vector products made (<= T)                             */
+    int32_t flags;            /* bit0: stopped by ||r|| <= theta ||g||; bit1: s^T H s <= 0 met   */
+    double rel_res;           /* ||r_best|| / ||g||                                              */
+    double gnorm;             /* ||g||                                                           */
+} ssn_cg_info;
+
+/* Parameters of ssn_solve (Alg. 1, 2, 3).  The paper gives no numeric values for beta, rho,
+ * i_max; textbook values are the defaults chosen by callers. */
+typedef struct {
+    int32_t iters;            /* SSN iterations to run (the paper ran a fixed count)             */
+    int32_t T;                /* max CG products per iteration                                   */
+    int32_t imax;             /* line search: give up after more than imax step reductions       */
+    int32_t reserved;
+    int64_t nS;               /* Hessian sample size per iteration                               */
+    double eps;               /* stop when ||g|| < eps                                           */
+    double theta;             /* CG relative residual tolerance                                  */
+    double beta;              /* Armijo constant                                                 */
+    double rho;               /* back-tracking factor                                            */
+    const int32_t *S_all;     /* [dev] iters*nS sample indices, iteration k uses [k*nS,(k+1)*nS) */
+    ssn_ctx *test;            /* optional context holding held-out rows: accuracy per iteration  */
+} ssn_params;
+
+/* One record per SSN iteration, written by ssn_solve to a [host] array. */
+typedef struct {
+    double f;                 /* objective at the iterate the iteration started from             */
+    double gnorm;             /* ||grad f|| there                                                */
+    double cg_rel_res;        /* relative residual of the direction taken                        */
+    double alpha;             /* step length                                                     */
+    double test_acc;          /* accuracy on params.test after the update (NaN if none)          */
+    double ms_grad, ms_prepare, ms_cg, ms_linesearch, ms_update;   /* host wall-clock per phase  */
+    int32_t cg_iters;         /* Hessian-vector products                                         */
+    int32_t ls_evals;         /* objective evaluations in the line search                        */
+    int32_t ls_ok;            /* 1 iff the Armijo condition held at the returned step            */
+    int32_t reserved;
+} ssn_iter_record;
+
+const char *ssn_strerror(int status);
+const char *ssn_last_error(const ssn_ctx *ctx);
+
+/* Create a context for one data set.  Validates the description (C >= 2, n,p >= 1, lambda >= 0,
+ * ldx >= p, ldw >= K, labels in range, CSR columns in range; one device pass over labels / CSR
+ * indices) and allocates the workspace.  Synchronises the stream. */
+int ssn_create(ssn_ctx **out, const ssn_desc *desc);
+int ssn_destroy(ssn_ctx *ctx);
+int ssn_set_stream(ssn_ctx *ctx, void *stream);
+
+/* Objective, eq. (5) with the stable log-sum-exp of eq. (8), (9) and the four-part form of
+ * Alg. 5 / eqs. (14)-(17):
+ *   f = s * sum_i [ M_i + log(alpha_i) - sum_c 1(b_i = c) z_ic ] + (lambda/2) ||W||_F^2 ,  z_i = W^T x_i.
+ * W [dev] p-by-K; f [host].  One pass over X. */
+int ssn_objective(ssn_ctx *ctx, const void *W, double *f);
+
+/* Gradient, eq. (6) / Alg. 6:  G = s * X^T (P - Y) + lambda W, P the row-wise class
+ * probabilities, Y the one-hot labels without the reference class.
+ * W [dev], G [dev] p-by-K out; f [host], may be NULL -- if given, also receives f(W) from the
+ * same pass and the call synchronises. */
+int ssn_gradient(ssn_ctx *ctx, const void *W, void *G, double *f);
+
+/* Sub-sampled Hessian (eq. (2b)) at W on the index multiset S [dev] (nS entries in [0,n),
+ * repeats allowed, any order): computes and caches the probabilities of the sampled rows (the
+ * matrix W of eq. (11); it depends on the weights only, so all CG products of one SSN
+ * iteration reuse it).  S is borrowed until the next prepare.  Validates S. */
+int ssn_hess_prepare(ssn_ctx *ctx, const void *W, const int32_t *S, int64_t nS);
+
+/* Hessian-vector product, eqs. (10)-(13) / Alg. 7, 8 on the prepared sample:
+ *   HV = s_S * X_S^T U + lambda V,  U_i = (diag(p_i) - p_i p_i^T)(V^T x_i).
+ * V [dev] in, HV [dev] out (must not alias V). */
+int ssn_hess_apply(ssn_ctx *ctx, const void *V, void *HV);
+
+/* ssn_hess_prepare followed by ssn_hess_apply. */
+int ssn_hessvec(ssn_ctx *ctx, const void *W, const int32_t *S, int64_t nS, const void *V, void *HV);
+
+/* Conjugate gradient with best-iterate memory, Alg. 2, on H_S p = -g for the prepared H_S.
+ * G [dev] right-hand side gradient; P_out [dev] receives p_best; at most T products.
+ * trace [host, nullable, 3*T doubles]: per product k the step alpha_k, ||r_{k+1}||, s_k^T H s_k.
+ * The whole loop runs on the device without host round trips; the call synchronises once at
+ * the end to fill info / trace. */
+int ssn_cg(ssn_ctx *ctx, const void *G, double theta, int32_t T, void *P_out,
+           ssn_cg_info *info, double *trace);
+
+/* Back-tracking line search, Alg. 3 / eq. (3c): alpha = 1; while f(W + alpha P) > fW +
+ * alpha*beta*<P,G>: if i > imax stop; i++; alpha *= rho.
+ * W, P, G [dev]; alpha, f_new, n_eval, ok [host] outputs (ok = 1 iff Armijo held at exit). */
+int ssn_linesearch(ssn_ctx *ctx, const void *W, const void *P, const void *G, double fW,
+                   double beta, double rho, int32_t imax,
+                   double *alpha, double *f_new, int32_t *n_eval, int32_t *ok);
+
+/* Classification rule (end of Sec. 3.3): argmax over [z_0..z_{K-1}, 0], ties to the lowest
+ * class index.  pred [dev, nullable] n int32; acc [host, nullable] = mean(pred == labels). */
+int ssn_predict(ssn_ctx *ctx, const void *W, int32_t *pred, double *acc);
+
+/* Sub-sampled Newton, Alg. 1 with the full gradient and a sampled Hessian:
+ * per iteration f,g at W; stop if ||g|| < eps; prepare H_S; CG; line search; W += alpha P.
+ * W_inout [dev]; log [host, nullable] receives min(iterations, max_log) records;
+ * iters_done [host, nullable]. */
+int ssn_solve(ssn_ctx *ctx, void *W_inout, const ssn_params *params,
+              ssn_iter_record *log, int32_t max_log, int32_t *iters_done);
+
+/* y = a*x + y style helper used by callers that drive Alg. 1 themselves: W += alpha * P. */
+int ssn_axpy(ssn_ctx *ctx, double alpha, const void *P, void *W_inout);
+
+/* Measurement aid for benchmarks: launches ONE kernel of the hot path `reps` times back to back on the
+ * context's stream between two HIP events and returns the mean duration of a launch in milliseconds.
+ *   which = 0  margins + loss over all rows            (the kernel of ssn_objective)
+ *           1  margins + U = P - Y over all rows       (first kernel of ssn_gradient)
+ *           2  X^T U over all rows                     (second kernel of ssn_gradient; dense: per-chunk partials)
+ *           3  sampled margins + U of eq. (12)         (first kernel of ssn_hess_apply; needs a prepared sample)
+ *           4  sampled X_S^T U                         (second kernel of ssn_hess_apply)
+ * M [dev] is the p-by-K right operand (W or V).  which = 2 / 4 reuse the U left by which = 1 / 3, so
+ * call those first.  ms [host].  Synchronises the stream. */
+int ssn_time_kernel(ssn_ctx *ctx, int32_t which, const void *M, int32_t reps, double *ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSN_H */

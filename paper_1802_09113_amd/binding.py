@@ -1,0 +1,249 @@
+"""Thin ctypes binding of libssn_hip.so (C ABI in include/ssn.h).
+
+Argument marshalling only: torch tensors supply device pointers and the current HIP stream, every
+step of the method runs inside the library's kernels.  There is no fallback: if the library has not
+been built (python -m paper_1802_09113_amd.build) importing this module's `lib()` raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libssn_hip.so")
+
+SSN_F32, SSN_F64 = 0, 1
+SSN_DENSE_ROWMAJOR, SSN_CSR = 0, 1
+SSN_SCALE_MEAN, SSN_SCALE_SUM = 0, 1
+SSN_OK = 0
+SSN_E_INVALID_ARG, SSN_E_BAD_LABEL, SSN_E_BAD_INDEX, SSN_E_NOT_PREPARED = -1, -2, -3, -4
+SSN_E_ALLOC, SSN_E_HIP, SSN_E_NONFINITE, SSN_E_UNSUPPORTED = -5, -6, -7, -8
+
+EXPORTS = [
+    "ssn_strerror", "ssn_last_error", "ssn_create", "ssn_destroy", "ssn_set_stream", "ssn_objective",
+    "ssn_gradient", "ssn_hess_prepare", "ssn_hess_apply", "ssn_hessvec", "ssn_cg", "ssn_linesearch",
+    "ssn_predict", "ssn_solve", "ssn_axpy", "ssn_time_kernel",
+]
+
+
+class ssn_desc(ctypes.Structure):
+    _fields_ = [
+        ("n", ctypes.c_int64), ("p", ctypes.c_int64),
+        ("C", ctypes.c_int32), ("dtype", ctypes.c_int32), ("layout", ctypes.c_int32), ("scale", ctypes.c_int32),
+        ("lam", ctypes.c_double),
+        ("X", ctypes.c_void_p), ("ldx", ctypes.c_int64),
+        ("rowptr", ctypes.c_void_p), ("colidx", ctypes.c_void_p), ("vals", ctypes.c_void_p), ("nnz", ctypes.c_int64),
+        ("labels", ctypes.c_void_p),
+        ("ldw", ctypes.c_int64),
+        ("stream", ctypes.c_void_p),
+    ]
+
+
+class ssn_cg_info(ctypes.Structure):
+    _fields_ = [("iters", ctypes.c_int32), ("flags", ctypes.c_int32), ("rel_res", ctypes.c_double),
+                ("gnorm", ctypes.c_double)]
+
+
+class ssn_params(ctypes.Structure):
+    _fields_ = [
+        ("iters", ctypes.c_int32), ("T", ctypes.c_int32), ("imax", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("nS", ctypes.c_int64),
+        ("eps", ctypes.c_double), ("theta", ctypes.c_double), ("beta", ctypes.c_double), ("rho", ctypes.c_double),
+        ("S_all", ctypes.c_void_p), ("test", ctypes.c_void_p),
+    ]
+
+
+class ssn_iter_record(ctypes.Structure):
+    _fields_ = [
+        ("f", ctypes.c_double), ("gnorm", ctypes.c_double), ("cg_rel_res", ctypes.c_double), ("alpha", ctypes.c_double),
+        ("test_acc", ctypes.c_double),
+        ("ms_grad", ctypes.c_double), ("ms_prepare", ctypes.c_double), ("ms_cg", ctypes.c_double),
+        ("ms_linesearch", ctypes.c_double), ("ms_update", ctypes.c_double),
+        ("cg_iters", ctypes.c_int32), ("ls_evals", ctypes.c_int32), ("ls_ok", ctypes.c_int32), ("reserved", ctypes.c_int32),
+    ]
+
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library; fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_1802_09113_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        L.ssn_strerror.restype = ctypes.c_char_p
+        L.ssn_strerror.argtypes = [ctypes.c_int]
+        L.ssn_last_error.restype = ctypes.c_char_p
+        L.ssn_last_error.argtypes = [ctypes.c_void_p]
+        vp, dp, ip = ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
+        L.ssn_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(ssn_desc)]
+        L.ssn_destroy.argtypes = [vp]
+        L.ssn_set_stream.argtypes = [vp, vp]
+        L.ssn_objective.argtypes = [vp, vp, dp]
+        L.ssn_gradient.argtypes = [vp, vp, vp, dp]
+        L.ssn_hess_prepare.argtypes = [vp, vp, vp, ctypes.c_int64]
+        L.ssn_hess_apply.argtypes = [vp, vp, vp]
+        L.ssn_hessvec.argtypes = [vp, vp, vp, ctypes.c_int64, vp, vp]
+        L.ssn_cg.argtypes = [vp, vp, ctypes.c_double, ctypes.c_int32, vp, ctypes.POINTER(ssn_cg_info), dp]
+        L.ssn_linesearch.argtypes = [vp, vp, vp, vp, ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_int32,
+                                     dp, dp, ip, ip]
+        L.ssn_predict.argtypes = [vp, vp, vp, dp]
+        L.ssn_solve.argtypes = [vp, vp, ctypes.POINTER(ssn_params), ctypes.POINTER(ssn_iter_record), ctypes.c_int32, ip]
+        L.ssn_axpy.argtypes = [vp, ctypes.c_double, vp, vp]
+        L.ssn_time_kernel.argtypes = [vp, ctypes.c_int32, vp, ctypes.c_int32, dp]
+        for name in EXPORTS:
+            fn = getattr(L, name)
+            if fn.restype is not ctypes.c_char_p:
+                fn.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+class SsnError(RuntimeError):
+    def __init__(self, status, detail=""):
+        self.status = status
+        name = lib().ssn_strerror(status).decode()
+        super().__init__(f"ssn status {status} ({name}) {detail}")
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+class Context:
+    """One data set resident on the GPU.  Methods carry the names of the C entry points."""
+
+    def __init__(self, labels, C, lam, X=None, csr=None, p=None, scale="mean", ldw=None, stream=None):
+        assert labels.is_cuda and labels.dtype == torch.int32
+        self._keep = [labels]
+        d = ssn_desc()
+        d.n, d.C, d.lam = labels.shape[0], C, lam
+        d.scale = {"mean": SSN_SCALE_MEAN, "sum": SSN_SCALE_SUM}[scale]
+        d.labels = labels.data_ptr()
+        if X is not None:
+            assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+            d.layout, d.X, d.ldx, d.p = SSN_DENSE_ROWMAJOR, X.data_ptr(), X.stride(0), X.shape[1]
+            self.tdtype = X.dtype
+            self._keep.append(X)
+        else:
+            rowptr, colidx, vals = csr
+            assert rowptr.dtype == torch.int32 and colidx.dtype == torch.int32
+            d.layout, d.p, d.nnz = SSN_CSR, p, vals.shape[0]
+            d.rowptr, d.colidx, d.vals = rowptr.data_ptr(), colidx.data_ptr(), vals.data_ptr()
+            self.tdtype = vals.dtype
+            self._keep += [rowptr, colidx, vals]
+        d.dtype = {torch.float32: SSN_F32, torch.float64: SSN_F64}[self.tdtype]
+        self.n, self.p, self.C, self.K = int(d.n), int(d.p), int(C), int(C) - 1
+        self.ldw = int(ldw) if ldw is not None else self.K
+        d.ldw = self.ldw
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        d.stream = stream
+        self.device = labels.device
+        self._h = ctypes.c_void_p()
+        st = lib().ssn_create(ctypes.byref(self._h), ctypes.byref(d))
+        if st != SSN_OK:
+            self._h = None
+            raise SsnError(st, "in ssn_create")
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().ssn_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st):
+        if st != SSN_OK:
+            raise SsnError(st, lib().ssn_last_error(self._h).decode())
+
+    def new_block(self):
+        """An uninitialised p x ldw block of the context's dtype."""
+        return torch.empty((self.p, self.ldw), dtype=self.tdtype, device=self.device)
+
+    def _blk(self, t):
+        assert t.is_cuda and t.dtype == self.tdtype and t.shape[0] == self.p and t.stride(0) == self.ldw and t.stride(1) == 1
+        return _ptr(t)
+
+    def ssn_objective(self, W):
+        f = ctypes.c_double()
+        self._check(lib().ssn_objective(self._h, self._blk(W), ctypes.byref(f)))
+        return f.value
+
+    def ssn_gradient(self, W, G=None, want_f=True):
+        G = self.new_block() if G is None else G
+        f = ctypes.c_double()
+        self._check(lib().ssn_gradient(self._h, self._blk(W), self._blk(G), ctypes.byref(f) if want_f else None))
+        return G, (f.value if want_f else None)
+
+    def ssn_hess_prepare(self, W, S):
+        assert S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()
+        self._S = S
+        self._check(lib().ssn_hess_prepare(self._h, self._blk(W), _ptr(S), S.shape[0]))
+
+    def ssn_hess_apply(self, V, HV=None):
+        HV = self.new_block() if HV is None else HV
+        self._check(lib().ssn_hess_apply(self._h, self._blk(V), self._blk(HV)))
+        return HV
+
+    def ssn_hessvec(self, W, S, V, HV=None):
+        assert S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()
+        self._S = S
+        HV = self.new_block() if HV is None else HV
+        self._check(lib().ssn_hessvec(self._h, self._blk(W), _ptr(S), S.shape[0], self._blk(V), self._blk(HV)))
+        return HV
+
+    def ssn_cg(self, G, theta, T, P=None, want_trace=True):
+        P = self.new_block() if P is None else P
+        info = ssn_cg_info()
+        tr = (ctypes.c_double * (3 * max(T, 1)))()
+        self._check(lib().ssn_cg(self._h, self._blk(G), theta, T, self._blk(P), ctypes.byref(info),
+                                 tr if want_trace else None))
+        it = info.iters
+        out = dict(p=P, iters=it, flags=info.flags, rel_res=info.rel_res, gnorm=info.gnorm)
+        if want_trace:
+            out.update(alpha=[tr[3 * k] for k in range(it)], rnorm=[tr[3 * k + 1] for k in range(it)],
+                       sHs=[tr[3 * k + 2] for k in range(it)])
+        return out
+
+    def ssn_linesearch(self, W, P, G, fW, beta=1e-4, rho=0.5, imax=10):
+        a, fn = ctypes.c_double(), ctypes.c_double()
+        ne, ok = ctypes.c_int32(), ctypes.c_int32()
+        self._check(lib().ssn_linesearch(self._h, self._blk(W), self._blk(P), self._blk(G), fW, beta, rho, imax,
+                                         ctypes.byref(a), ctypes.byref(fn), ctypes.byref(ne), ctypes.byref(ok)))
+        return dict(alpha=a.value, f_new=fn.value, n_eval=ne.value, ok=ok.value)
+
+    def ssn_predict(self, W, want_pred=True):
+        pred = torch.empty(self.n, dtype=torch.int32, device=self.device) if want_pred else None
+        acc = ctypes.c_double()
+        self._check(lib().ssn_predict(self._h, self._blk(W), _ptr(pred), ctypes.byref(acc)))
+        return pred, acc.value
+
+    def ssn_axpy(self, alpha, P, W):
+        self._check(lib().ssn_axpy(self._h, alpha, self._blk(P), self._blk(W)))
+
+    def ssn_time_kernel(self, which, M, reps):
+        ms = ctypes.c_double()
+        self._check(lib().ssn_time_kernel(self._h, which, self._blk(M), reps, ctypes.byref(ms)))
+        return ms.value
+
+    def ssn_solve(self, W, S_all, eps=0.0, theta=1e-4, T=10, beta=1e-4, rho=0.5, imax=10, test=None):
+        """S_all: (iters, nS) int32 device tensor.  W is updated in place; returns (records, iterations done)."""
+        assert S_all.is_cuda and S_all.dtype == torch.int32 and S_all.is_contiguous() and S_all.dim() == 2
+        pr = ssn_params()
+        pr.iters, pr.nS = S_all.shape
+        pr.T, pr.imax, pr.eps, pr.theta, pr.beta, pr.rho = T, imax, eps, theta, beta, rho
+        pr.S_all = S_all.data_ptr()
+        pr.test = test._h if test is not None else None
+        log = (ssn_iter_record * max(int(pr.iters), 1))()
+        done = ctypes.c_int32()
+        self._check(lib().ssn_solve(self._h, self._blk(W), ctypes.byref(pr), log, int(pr.iters), ctypes.byref(done)))
+        fields = [f[0] for f in ssn_iter_record._fields_ if f[0] != "reserved"]
+        nrec = min(done.value + 1, int(pr.iters))
+        return [{k: getattr(log[i], k) for k in fields} for i in range(nrec)], done.value

@@ -1,0 +1,166 @@
+// CSR kernels: row-per-wavefront SpMM with the per-row epilogue fused in, and the transposed
+// product X_rows^T U.
+//
+// rows kernel: one wavefront owns one row at a time.  Lanes are split as (slot, class): NS = 64/K
+// stored entries are processed per step, lane (s,c) gathers M[col_s, c] -- the K values of one feature
+// are contiguous (feature-major weights), so one stored entry fetches one contiguous K-vector.
+#include "ssn_internal.h"
+
+#include <limits>
+
+namespace ssn {
+
+__device__ __forceinline__ float c_exp(float x) { return expf(x); }
+__device__ __forceinline__ double c_exp(double x) { return exp(x); }
+__device__ __forceinline__ float c_log(float x) { return logf(x); }
+__device__ __forceinline__ double c_log(double x) { return log(x); }
+
+template <typename T> __device__ __forceinline__ T wave_sum(T x)
+{
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+    return x;
+}
+template <typename T> __device__ __forceinline__ T wave_max(T x)
+{
+    for (int off = 32; off > 0; off >>= 1) x = fmax(x, __shfl_xor(x, off));
+    return x;
+}
+__device__ __forceinline__ int wave_min_int(int x)
+{
+    for (int off = 32; off > 0; off >>= 1) x = min(x, __shfl_xor(x, off));
+    return x;
+}
+
+// z_c = sum over the row's stored entries of x * M[col, c]; result valid in lanes c < K.
+template <typename T>
+__device__ __forceinline__ T csr_row_margin(const RowsArgs &a, int64_t row, int lane, int K, int NS)
+{
+    const int s = lane / K, c = lane - s * K;
+    const bool act = s < NS;
+    const T *vals = (const T *)a.vals;
+    const T *M = (const T *)a.M;
+    const int64_t b = a.rowptr[row], e = a.rowptr[row + 1];
+    T acc = 0;
+    for (int64_t t = b + s; t < e && act; t += NS) {
+        const int64_t col = a.colidx[t];
+        acc += vals[t] * M[col * a.ldm + c];
+    }
+    // fold the NS slots onto slot 0
+    T tot = acc;
+    for (int k = 1; k < NS; ++k) {
+        const T o = __shfl(acc, (lane + k * K) & 63);
+        tot += o;
+    }
+    return (lane < K) ? tot : T(0);
+}
+
+template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void csr_rows_kernel(RowsArgs a)
+{
+    if (a.skip && *a.skip) return;
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const int64_t nwaves = (int64_t)gridDim.x * ROWS_WAVES_PER_BLOCK;
+    const int64_t wave = (int64_t)blockIdx.x * ROWS_WAVES_PER_BLOCK + wib;
+    const int K = a.K;
+    const int NS = 64 / K;
+    const bool cv = lane < K;
+    const T NEG = -std::numeric_limits<T>::infinity();
+    double loss = 0.0;
+    int hits = 0;
+
+    for (int64_t sv = wave; sv < a.nrows; sv += nwaves) {
+        const int64_t row = a.S ? a.S[sv] : sv;
+        const T z = csr_row_margin<T>(a, row, lane, K, NS);
+        if constexpr (MODE == ROW_APPLY) {
+            const T pin = cv ? ((const T *)a.Pin)[sv * a.KP + lane] : T(0);
+            const T t = wave_sum(pin * z);
+            if (cv) ((T *)a.UP)[sv * a.KP + lane] = pin * z - pin * t;
+            continue;
+        }
+        const T zmax = wave_max(cv ? z : NEG);
+        if constexpr (MODE == ROW_PRED) {
+            const int lab = a.labels[row];
+            const int cand = wave_min_int((cv && z == zmax) ? lane : 0x7fffffff);
+            const int pr = (T(0) > zmax) ? K : cand;
+            if (lane == 0) {
+                if (a.pred) a.pred[sv] = pr;
+                hits += (pr == lab);
+            }
+            continue;
+        }
+        const T Mx = fmax(T(0), zmax);
+        const T ex = cv ? c_exp(z - Mx) : T(0);
+        const T alpha = c_exp(-Mx) + wave_sum(ex);
+        if constexpr (MODE == ROW_PREP) {
+            if (cv) ((T *)a.UP)[sv * a.KP + lane] = ex / alpha;
+            continue;
+        }
+        const int lab = a.labels[row];
+        const T lin = wave_sum((cv && lane == lab) ? z : T(0));
+        if (lane == 0) loss += (double)Mx + (double)c_log(alpha) - (double)lin;
+        if (MODE == ROW_GRAD && cv) ((T *)a.UP)[sv * a.KP + lane] = ex / alpha - ((lane == lab) ? T(1) : T(0));
+    }
+    if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD) {
+        if (lane == 0) a.loss_part[wave] = loss;
+    } else if constexpr (MODE == ROW_PRED) {
+        if (lane == 0) a.hit_part[wave] = hits;
+    }
+}
+
+template <typename T> static hipError_t csr_rows_dispatch(const RowsArgs &a, int blocks, hipStream_t st)
+{
+    dim3 grid(blocks), block(64 * ROWS_WAVES_PER_BLOCK);
+    switch (a.mode) {
+    case ROW_OBJ: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_OBJ>), grid, block, 0, st, a); break;
+    case ROW_GRAD: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_GRAD>), grid, block, 0, st, a); break;
+    case ROW_PREP: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_PREP>), grid, block, 0, st, a); break;
+    case ROW_APPLY: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_APPLY>), grid, block, 0, st, a); break;
+    case ROW_PRED: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_PRED>), grid, block, 0, st, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_csr_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st)
+{
+    return dtype == SSN_F32 ? csr_rows_dispatch<float>(a, blocks, st) : csr_rows_dispatch<double>(a, blocks, st);
+}
+
+// out[col, c] += scale * x * U[sv, c] for every stored entry of the selected rows.
+// out must already hold lambda * M.  Hardware floating-point atomics on device memory: the summation
+// order, and therefore the last bits, vary from run to run.
+template <typename T>
+__global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void csr_scatter_kernel(XtuArgs a, double scale, T *out, int64_t ldo)
+{
+    if (a.skip && *a.skip) return;
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const int64_t nwaves = (int64_t)gridDim.x * ROWS_WAVES_PER_BLOCK;
+    const int64_t wave = (int64_t)blockIdx.x * ROWS_WAVES_PER_BLOCK + wib;
+    const int K = a.K;
+    const int NS = 64 / K;
+    const int s = lane / K, c = lane - s * K;
+    if (s >= NS) return;
+    const T *vals = (const T *)a.vals;
+    const T *U = (const T *)a.U;
+    const T sc = (T)scale;
+    for (int64_t sv = wave; sv < a.nrows; sv += nwaves) {
+        const int64_t row = a.S ? a.S[sv] : sv;
+        const T u = sc * U[sv * a.KP + c];
+        const int64_t b = a.rowptr[row], e = a.rowptr[row + 1];
+        for (int64_t t = b + s; t < e; t += NS) {
+            const int64_t col = a.colidx[t];
+            unsafeAtomicAdd(out + col * ldo + c, vals[t] * u);
+        }
+    }
+}
+
+hipError_t launch_csr_scatter(int dtype, const XtuArgs &a, double scale, void *out, int64_t ldo, hipStream_t st)
+{
+    int64_t blocks = (a.nrows + ROWS_WAVES_PER_BLOCK - 1) / ROWS_WAVES_PER_BLOCK;
+    if (blocks > 8192) blocks = 8192;
+    dim3 grid((unsigned)blocks), block(64 * ROWS_WAVES_PER_BLOCK);
+    if (dtype == SSN_F32) hipLaunchKernelGGL(csr_scatter_kernel<float>, grid, block, 0, st, a, scale, (float *)out, ldo);
+    else hipLaunchKernelGGL(csr_scatter_kernel<double>, grid, block, 0, st, a, scale, (double *)out, ldo);
+    return hipGetLastError();
+}
+
+}  // namespace ssn

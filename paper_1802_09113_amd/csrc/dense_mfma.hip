@@ -1,0 +1,396 @@
+// Dense row-major kernels on the gfx950 matrix cores.
+//
+// Both products of the method are tall-and-skinny contractions against a K-column block
+// (K = C-1 <= 32, padded to 16-column MFMA tiles):
+//   rows kernel : Z = X_rows * M   (Alg. 5 l.3, Alg. 6 l.3, Alg. 7 l.3) with the per-row work of
+//                 Alg. 4 / eq. (8),(9),(14)-(17) / Alg. 8 fused in as an epilogue on the MFMA
+//                 accumulators, so the n x K margin matrix never goes to memory;
+//   xtu kernel  : part = X_rows^T * U (Alg. 6 l.4, Alg. 7 l.6) as per-row-chunk partial sums that a
+//                 finalize kernel adds in a fixed order (deterministic, no atomics).
+//
+// MFMA tile used throughout: v_mfma_{f32,f64}_16x16x4 -- D(16x16) += A(16x4) * B(4x16), wave64:
+//   lane l supplies A[l%16][l/16] and B[l/16][l%16]; lane l holds D[4*(l/16)+v][l%16], v = 0..3.
+#include "ssn_internal.h"
+
+#include <limits>
+
+namespace ssn {
+
+template <typename T> struct V4;
+template <> struct V4<float> { typedef float type __attribute__((ext_vector_type(4))); };
+template <> struct V4<double> { typedef double type __attribute__((ext_vector_type(4))); };
+
+__device__ __forceinline__ V4<double>::type mfma16(double a, double b, V4<double>::type c)
+{
+    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ V4<float>::type mfma16(float a, float b, V4<float>::type c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+template <typename T, int VEC> struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; };
+
+__device__ __forceinline__ float t_exp(float x) { return expf(x); }
+__device__ __forceinline__ double t_exp(double x) { return exp(x); }
+__device__ __forceinline__ float t_log(float x) { return logf(x); }
+__device__ __forceinline__ double t_log(double x) { return log(x); }
+
+// butterfly over the 16 lanes that hold the 16 class columns of one row
+template <typename T> __device__ __forceinline__ T row16_sum(T x)
+{
+    x += __shfl_xor(x, 8);
+    x += __shfl_xor(x, 4);
+    x += __shfl_xor(x, 2);
+    x += __shfl_xor(x, 1);
+    return x;
+}
+template <typename T> __device__ __forceinline__ T row16_max(T x)
+{
+    x = fmax(x, __shfl_xor(x, 8));
+    x = fmax(x, __shfl_xor(x, 4));
+    x = fmax(x, __shfl_xor(x, 2));
+    x = fmax(x, __shfl_xor(x, 1));
+    return x;
+}
+__device__ __forceinline__ int row16_min(int x)
+{
+    x = min(x, __shfl_xor(x, 8));
+    x = min(x, __shfl_xor(x, 4));
+    x = min(x, __shfl_xor(x, 2));
+    x = min(x, __shfl_xor(x, 1));
+    return x;
+}
+
+// Per-row work on a 16-row block of margins held in MFMA accumulator layout:
+// acc[nb][v] = z(row 4*(lane/16)+v, class 16*nb + lane%16).
+template <typename T, int NB, int MODE>
+__device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[NB], const RowsArgs &a,
+                                             int64_t rb, int lane, double &loss, int &hits)
+{
+    const int q = lane & 15, g = lane >> 4;
+    const int K = a.K;
+    const T NEG = -std::numeric_limits<T>::infinity();
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int64_t sv = rb * 16 + 4 * g + v;
+        const bool valid = sv < a.nrows;
+        const int64_t svc = valid ? sv : a.nrows - 1;
+        T z[NB];
+        bool cv[NB];
+        T zmax = NEG;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            cv[nb] = (nb * 16 + q) < K;
+            z[nb] = acc[nb][v];
+            zmax = fmax(zmax, cv[nb] ? z[nb] : NEG);
+        }
+        zmax = row16_max(zmax);
+        if constexpr (MODE == ROW_PRED) {
+            const int64_t xr = a.S ? a.S[svc] : svc;
+            const int lab = a.labels[xr];
+            int cand = 0x7fffffff;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                if (cv[nb] && z[nb] == zmax) cand = min(cand, nb * 16 + q);
+            cand = row16_min(cand);
+            const int pr = (T(0) > zmax) ? K : cand;     // the reference class wins only strictly
+            if (valid && q == 0) {
+                if (a.pred) a.pred[sv] = pr;
+                hits += (pr == lab);
+            }
+            continue;
+        }
+        if constexpr (MODE == ROW_APPLY) {
+            // eq. (12): u = p .* vhat - p * <p, vhat>
+            const T *Pin = (const T *)a.Pin;
+            T pin[NB];
+            T t = 0;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                pin[nb] = Pin[svc * a.KP + nb * 16 + q];      // zero in padded columns
+                t += pin[nb] * z[nb];
+            }
+            t = row16_sum(t);
+            T *U = (T *)a.UP;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                U[sv * a.KP + nb * 16 + q] = valid ? (pin[nb] * z[nb] - pin[nb] * t) : T(0);
+            continue;
+        }
+        // eq. (8), (9): M = max{0, z}, alpha = e^{-M} + sum_c e^{z_c - M}
+        const T Mx = fmax(T(0), zmax);
+        T e[NB];
+        T se = 0;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            e[nb] = cv[nb] ? t_exp(z[nb] - Mx) : T(0);
+            se += e[nb];
+        }
+        se = row16_sum(se);
+        const T alpha = t_exp(-Mx) + se;
+        if constexpr (MODE == ROW_PREP) {
+            T *P = (T *)a.UP;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                P[sv * a.KP + nb * 16 + q] = valid ? e[nb] / alpha : T(0);
+            continue;
+        }
+        // ROW_OBJ / ROW_GRAD: eqs. (14)-(17)
+        const int64_t xr = a.S ? a.S[svc] : svc;
+        const int lab = a.labels[xr];
+        T lin = 0;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+            lin += (cv[nb] && (nb * 16 + q) == lab) ? z[nb] : T(0);
+        lin = row16_sum(lin);
+        if (valid && q == 0) loss += (double)Mx + (double)t_log(alpha) - (double)lin;
+        if constexpr (MODE == ROW_GRAD) {
+            T *U = (T *)a.UP;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const T ind = ((nb * 16 + q) == lab) ? T(1) : T(0);
+                U[sv * a.KP + nb * 16 + q] = (valid && cv[nb]) ? (e[nb] / alpha - ind) : T(0);
+            }
+        }
+    }
+}
+
+// One wave per 16-row block; grid-stride over row blocks.  UP / Pin have ceil(nrows/16)*16 rows.
+template <typename T, int NB, int VEC, int MODE>
+__global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void dense_rows_kernel(RowsArgs a)
+{
+    if (a.skip && *a.skip) return;
+    typedef typename V4<T>::type v4;
+    typedef Pack<T, VEC> pack;
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const int q = lane & 15, g = lane >> 4;
+    const int64_t nwaves = (int64_t)gridDim.x * ROWS_WAVES_PER_BLOCK;
+    const int64_t wave = (int64_t)blockIdx.x * ROWS_WAVES_PER_BLOCK + wib;
+    const T *X = (const T *)a.X;
+    const T *M = (const T *)a.M;
+    const int K = a.K;
+    const int64_t p = a.p, ldm = a.ldm;
+
+    bool cval[NB];
+    const T *mcol[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int c = nb * 16 + q;
+        cval[nb] = c < K;
+        mcol[nb] = M + (cval[nb] ? c : K - 1);
+    }
+
+    double loss = 0.0;
+    int hits = 0;
+    const int64_t nblk = (a.nrows + 15) / 16;
+    constexpr int STEP = 4 * VEC;     // features consumed per vector load (4 k-groups of VEC)
+    constexpr int UNR = 4;
+
+    for (int64_t rb = wave; rb < nblk; rb += nwaves) {
+        int64_t si = rb * 16 + q;
+        if (si >= a.nrows) si = a.nrows - 1;          // clamped rows are masked in the epilogue
+        const int64_t xr = a.S ? a.S[si] : si;
+        const T *xrow = X + xr * a.ldx;
+        v4 acc[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[nb] = v4{0, 0, 0, 0};
+
+        int64_t f0 = 0;
+        for (; f0 + STEP * UNR <= p; f0 += STEP * UNR) {
+            pack xv[UNR];
+            T wv[UNR][VEC][NB];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int64_t f = f0 + u * STEP + VEC * g;
+                xv[u] = *(const pack *)(xrow + f);
+#pragma unroll
+                for (int m = 0; m < VEC; ++m)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) wv[u][m][nb] = mcol[nb][(f + m) * ldm];
+            }
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+                for (int m = 0; m < VEC; ++m)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[nb] = mfma16(xv[u].v[m], cval[nb] ? wv[u][m][nb] : T(0), acc[nb]);
+        }
+        for (; f0 < p; f0 += STEP) {                   // guarded tail
+            const int64_t f = f0 + VEC * g;
+#pragma unroll
+            for (int m = 0; m < VEC; ++m) {
+                const bool ok = (f + m) < p;
+                const T x = ok ? xrow[f + m] : T(0);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const T w = (ok && cval[nb]) ? mcol[nb][(f + m) * ldm] : T(0);
+                    acc[nb] = mfma16(x, w, acc[nb]);
+                }
+            }
+        }
+        row_epilogue<T, NB, MODE>(acc, a, rb, lane, loss, hits);
+    }
+
+    if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD) {
+        for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off);
+        if (lane == 0) a.loss_part[wave] = loss;
+    } else if constexpr (MODE == ROW_PRED) {
+        for (int off = 32; off > 0; off >>= 1) hits += __shfl_xor(hits, off);
+        if (lane == 0) a.hit_part[wave] = hits;
+    }
+}
+
+// part[chunk] (p x K) = sum over the chunk's rows of x_row^T u_row.
+// Block = 4 waves, each wave owns 64 consecutive features; blockIdx.y = row chunk.
+// A vector load of VEC consecutive features per lane feeds VEC MFMAs whose output rows are the
+// features {base + VEC*i + m : i = 0..15}.
+template <typename T, int NB, int VEC>
+__global__ __launch_bounds__(256) void dense_xtu_kernel(XtuArgs a)
+{
+    if (a.skip && *a.skip) return;
+    typedef typename V4<T>::type v4;
+    typedef Pack<T, VEC> pack;
+    constexpr int FT = 64;
+    constexpr int NL = FT / (16 * VEC);
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const int q = lane & 15, g = lane >> 4;
+    const int64_t p = a.p;
+    const int K = a.K;
+    const int64_t f0 = ((int64_t)blockIdx.x * 4 + wib) * FT;
+    if (f0 >= p) return;
+    const int64_t chunk = blockIdx.y;
+    const int64_t r_begin = chunk * a.rows_per_chunk;
+    const int64_t r_end = min(a.nrows, r_begin + a.rows_per_chunk);
+    const T *X = (const T *)a.X;
+    const T *U = (const T *)a.U;
+    const bool full = (f0 + FT) <= p;
+
+    v4 acc[NL * VEC][NB];
+#pragma unroll
+    for (int t = 0; t < NL * VEC; ++t)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[t][nb] = v4{0, 0, 0, 0};
+
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += 4) {
+        const int64_t si = r0 + g;
+        const bool rv = si < r_end;
+        const int64_t sc = rv ? si : r_begin;
+        const int64_t xr = a.S ? a.S[sc] : sc;
+        const T *xrow = X + xr * a.ldx + f0;
+        T ub[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const T u = U[sc * a.KP + nb * 16 + q];
+            ub[nb] = rv ? u : T(0);
+        }
+#pragma unroll
+        for (int ld = 0; ld < NL; ++ld) {
+            const int fl = ld * 16 * VEC + VEC * q;
+            pack xv;
+            if (full) {
+                xv = *(const pack *)(xrow + fl);
+            } else {
+#pragma unroll
+                for (int m = 0; m < VEC; ++m) xv.v[m] = (f0 + fl + m) < p ? xrow[fl + m] : T(0);
+            }
+#pragma unroll
+            for (int m = 0; m < VEC; ++m) {
+                const T x = rv ? xv.v[m] : T(0);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) acc[ld * VEC + m][nb] = mfma16(x, ub[nb], acc[ld * VEC + m][nb]);
+            }
+        }
+    }
+
+    T *part = (T *)a.part + chunk * p * K;
+#pragma unroll
+    for (int ld = 0; ld < NL; ++ld)
+#pragma unroll
+        for (int m = 0; m < VEC; ++m)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int64_t f = f0 + ld * 16 * VEC + VEC * (4 * g + v) + m;
+                    const int c = nb * 16 + q;
+                    if (f < p && c < K) part[f * K + c] = acc[ld * VEC + m][nb][v];
+                }
+}
+
+int rows_grid_blocks(int64_t nrows, int num_cus)
+{
+    const int64_t nblk = (nrows + 15) / 16;
+    int64_t blocks = (nblk + ROWS_WAVES_PER_BLOCK - 1) / ROWS_WAVES_PER_BLOCK;
+    const int64_t cap = (int64_t)num_cus * 8;
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    return (int)blocks;
+}
+
+template <typename T> static bool vec_ok(const void *X, int64_t ldx)
+{
+    constexpr int VEC = 16 / sizeof(T);
+    return ((uintptr_t)X % 16 == 0) && (ldx % VEC == 0);
+}
+
+template <typename T, int MODE> static hipError_t rows_dispatch_mode(const RowsArgs &a, int blocks, hipStream_t st)
+{
+    constexpr int VEC = 16 / sizeof(T);
+    const int nb = (a.K + 15) / 16;
+    const bool v = vec_ok<T>(a.X, a.ldx);
+    dim3 grid(blocks), block(64 * ROWS_WAVES_PER_BLOCK);
+    if (nb == 1) {
+        if (v) hipLaunchKernelGGL((dense_rows_kernel<T, 1, VEC, MODE>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((dense_rows_kernel<T, 1, 1, MODE>), grid, block, 0, st, a);
+    } else if (nb == 2) {
+        if (v) hipLaunchKernelGGL((dense_rows_kernel<T, 2, VEC, MODE>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((dense_rows_kernel<T, 2, 1, MODE>), grid, block, 0, st, a);
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+template <typename T> static hipError_t rows_dispatch(const RowsArgs &a, int blocks, hipStream_t st)
+{
+    switch (a.mode) {
+    case ROW_OBJ: return rows_dispatch_mode<T, ROW_OBJ>(a, blocks, st);
+    case ROW_GRAD: return rows_dispatch_mode<T, ROW_GRAD>(a, blocks, st);
+    case ROW_PREP: return rows_dispatch_mode<T, ROW_PREP>(a, blocks, st);
+    case ROW_APPLY: return rows_dispatch_mode<T, ROW_APPLY>(a, blocks, st);
+    case ROW_PRED: return rows_dispatch_mode<T, ROW_PRED>(a, blocks, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_dense_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st)
+{
+    return dtype == SSN_F32 ? rows_dispatch<float>(a, blocks, st) : rows_dispatch<double>(a, blocks, st);
+}
+
+template <typename T> static hipError_t xtu_dispatch(const XtuArgs &a, hipStream_t st)
+{
+    constexpr int VEC = 16 / sizeof(T);
+    const int nb = (a.K + 15) / 16;
+    const bool v = vec_ok<T>(a.X, a.ldx);
+    dim3 grid((unsigned)((a.p + 255) / 256), (unsigned)a.nchunks), block(256);
+    if (nb == 1) {
+        if (v) hipLaunchKernelGGL((dense_xtu_kernel<T, 1, VEC>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((dense_xtu_kernel<T, 1, 1>), grid, block, 0, st, a);
+    } else if (nb == 2) {
+        if (v) hipLaunchKernelGGL((dense_xtu_kernel<T, 2, VEC>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((dense_xtu_kernel<T, 2, 1>), grid, block, 0, st, a);
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st)
+{
+    return dtype == SSN_F32 ? xtu_dispatch<float>(a, st) : xtu_dispatch<double>(a, st);
+}
+
+}  // namespace ssn

@@ -1,0 +1,669 @@
+// extern "C" entry points of libssn_hip.so (declared in include/ssn.h): argument checking, workspace
+// ownership, kernel sequencing, and the host-side control flow of Alg. 1 and Alg. 3.  Every arithmetic
+// step runs in the kernels of dense_mfma.hip / csr.hip / vecops.hip.
+#include "ssn_internal.h"
+
+#include <chrono>
+#include <cmath>
+#include <cstddef>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace ssn;
+
+struct ssn_ctx {
+    ssn_desc d{};
+    int K = 0, KP = 0;
+    size_t es = 0;
+    hipStream_t st = nullptr;
+    int num_cus = 256;
+    std::string err;
+
+    // per-row buffers (row stride KP): U of the current product, P of the prepared sample
+    void *Ubuf = nullptr;
+    int64_t U_rows = 0;
+    void *Pbuf = nullptr;
+    int64_t P_rows = 0;
+    // per-chunk partial sums of X^T U (dense path)
+    void *part = nullptr;
+    int64_t part_elems = 0;
+    int max_chunks = 0;
+    // reduction scratch
+    double *loss_part = nullptr;
+    int32_t *hit_part = nullptr;
+    int wave_parts = 0;
+    double *red_a = nullptr, *red_b = nullptr;
+    double *scal_dev = nullptr;
+    int32_t *int_dev = nullptr;
+    double *host_pin = nullptr;   // pinned staging for scalar results
+    // prepared Hessian sample
+    const int32_t *S = nullptr;
+    int64_t nS = 0;
+    bool prepared = false;
+    // CG / line-search vectors (p x ldw each)
+    void *cg_p = nullptr, *cg_r = nullptr, *cg_s = nullptr, *cg_Hs = nullptr, *trial = nullptr;
+    void *grad = nullptr, *dir = nullptr;      // ssn_solve's gradient and direction
+    CgSlot *slots = nullptr;
+    int slots_cap = 0;
+    double *trace_dev = nullptr;
+};
+
+namespace {
+
+#define SSN_HIP(ctx, call)                                                                         \
+    do {                                                                                           \
+        hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess) {                                                                    \
+            (ctx)->err = std::string(#call) + ": " + hipGetErrorString(e_);                        \
+            return (e_ == hipErrorOutOfMemory) ? SSN_E_ALLOC : SSN_E_HIP;                          \
+        }                                                                                          \
+    } while (0)
+
+#define SSN_TRY(expr)                                                                              \
+    do {                                                                                           \
+        int s_ = (expr);                                                                           \
+        if (s_ != SSN_OK) return s_;                                                               \
+    } while (0)
+
+int fail(ssn_ctx *c, int code, const std::string &msg)
+{
+    if (c) c->err = msg;
+    return code;
+}
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+inline bool is_dense(const ssn_ctx *c) { return c->d.layout == SSN_DENSE_ROWMAJOR; }
+
+double scale_full(const ssn_ctx *c) { return c->d.scale == SSN_SCALE_SUM ? 1.0 : 1.0 / (double)c->d.n; }
+double scale_sample(const ssn_ctx *c)
+{
+    return c->d.scale == SSN_SCALE_SUM ? (double)c->d.n / (double)c->nS : 1.0 / (double)c->nS;
+}
+
+int vec_bytes_alloc(ssn_ctx *c, void **ptr)
+{
+    SSN_HIP(c, hipMalloc(ptr, (size_t)c->d.p * (size_t)c->d.ldw * c->es));
+    return SSN_OK;
+}
+
+// make sure a per-row buffer has at least `rows` rows
+int ensure_rows(ssn_ctx *c, void **buf, int64_t *have, int64_t rows)
+{
+    if (*have >= rows) return SSN_OK;
+    if (*buf) {
+        SSN_HIP(c, hipStreamSynchronize(c->st));
+        SSN_HIP(c, hipFree(*buf));
+        *buf = nullptr;
+        *have = 0;
+    }
+    SSN_HIP(c, hipMalloc(buf, (size_t)rows * (size_t)c->KP * c->es));
+    *have = rows;
+    return SSN_OK;
+}
+
+RowsArgs rows_base(const ssn_ctx *c)
+{
+    RowsArgs a{};
+    a.X = c->d.X;
+    a.ldx = c->d.ldx;
+    a.rowptr = c->d.rowptr;
+    a.colidx = c->d.colidx;
+    a.vals = c->d.vals;
+    a.n = c->d.n;
+    a.p = c->d.p;
+    a.K = c->K;
+    a.labels = c->d.labels;
+    a.KP = c->KP;
+    a.ldm = c->d.ldw;
+    a.loss_part = c->loss_part;
+    a.hit_part = c->hit_part;
+    return a;
+}
+
+XtuArgs xtu_base(const ssn_ctx *c)
+{
+    XtuArgs a{};
+    a.X = c->d.X;
+    a.ldx = c->d.ldx;
+    a.rowptr = c->d.rowptr;
+    a.colidx = c->d.colidx;
+    a.vals = c->d.vals;
+    a.n = c->d.n;
+    a.p = c->d.p;
+    a.K = c->K;
+    a.KP = c->KP;
+    a.part = c->part;
+    return a;
+}
+
+int launch_rows(ssn_ctx *c, const RowsArgs &a, int *nparts)
+{
+    // dense: one wave per 16-row block; CSR: one wave per row
+    const int blocks = rows_grid_blocks(is_dense(c) ? a.nrows : a.nrows * 16, c->num_cus);
+    if (blocks * ROWS_WAVES_PER_BLOCK > c->wave_parts) return fail(c, SSN_E_INVALID_ARG, "internal: wave partial overflow");
+    if (is_dense(c)) SSN_HIP(c, launch_dense_rows(c->d.dtype, a, blocks, c->st));
+    else SSN_HIP(c, launch_csr_rows(c->d.dtype, a, blocks, c->st));
+    if (nparts) *nparts = blocks * ROWS_WAVES_PER_BLOCK;
+    return SSN_OK;
+}
+
+// choose the row chunking of the dense transposed product
+void choose_chunks(const ssn_ctx *c, int64_t nrows, int64_t *rpc, int *nch)
+{
+    const int64_t nft = (c->d.p + 63) / 64;
+    const int64_t target = (int64_t)c->num_cus * 8;
+    int64_t n = (target + nft - 1) / nft;
+    const int64_t maxn = (nrows + 15) / 16;
+    if (n > maxn) n = maxn;
+    if (n > c->max_chunks) n = c->max_chunks;
+    if (n < 1) n = 1;
+    int64_t r = round_up((nrows + n - 1) / n, 16);
+    *rpc = r;
+    *nch = (int)((nrows + r - 1) / r);
+}
+
+// out = scale * X_rows^T U + lambda * M ; optionally partials of <out, M> into red_b (count in *ndot)
+int transposed_product(ssn_ctx *c, const int32_t *S, int64_t nrows, double scale, const void *M, void *out,
+                       bool want_dot, int *ndot, const int32_t *skip)
+{
+    XtuArgs x = xtu_base(c);
+    x.S = S;
+    x.nrows = nrows;
+    x.U = c->Ubuf;
+    x.skip = skip;
+    if (is_dense(c)) {
+        choose_chunks(c, nrows, &x.rows_per_chunk, &x.nchunks);
+        SSN_HIP(c, launch_dense_xtu(c->d.dtype, x, c->st));
+        FinArgs f{};
+        f.part = c->part;
+        f.nchunks = x.nchunks;
+        f.p = c->d.p;
+        f.K = c->K;
+        f.scale = scale;
+        f.lambda = c->d.lambda;
+        f.M = M;
+        f.ldm = c->d.ldw;
+        f.out = out;
+        f.ldo = c->d.ldw;
+        f.dot_part = want_dot ? c->red_b : nullptr;
+        f.skip = skip;
+        const int fb = finalize_blocks(c->d.p, c->K);
+        SSN_HIP(c, launch_finalize(c->d.dtype, f, fb, c->st));
+        if (ndot) *ndot = fb;
+    } else {
+        SSN_HIP(c, launch_scale_copy(c->d.dtype, c->d.p, c->K, c->d.lambda, M, c->d.ldw, out, c->d.ldw, skip, c->st));
+        SSN_HIP(c, launch_csr_scatter(c->d.dtype, x, scale, out, c->d.ldw, c->st));
+        if (want_dot) {
+            const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+            SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, out, c->d.ldw, M, c->d.ldw, c->red_b, vb, skip, c->st));
+            if (ndot) *ndot = vb;
+        }
+    }
+    return SSN_OK;
+}
+
+int read_scalar(ssn_ctx *c, const double *dev, double *host_out)
+{
+    SSN_HIP(c, hipMemcpyAsync(c->host_pin, dev, sizeof(double), hipMemcpyDeviceToHost, c->st));
+    SSN_HIP(c, hipStreamSynchronize(c->st));
+    *host_out = c->host_pin[0];
+    return SSN_OK;
+}
+
+int read_int(ssn_ctx *c, const int32_t *dev, int32_t *host_out)
+{
+    SSN_HIP(c, hipMemcpyAsync(c->host_pin, dev, sizeof(int32_t), hipMemcpyDeviceToHost, c->st));
+    SSN_HIP(c, hipStreamSynchronize(c->st));
+    *host_out = *(const int32_t *)c->host_pin;
+    return SSN_OK;
+}
+
+// enqueue f(W) into scal_dev[slot]; loss partials must already be in loss_part[0..nparts)
+int enqueue_objective_value(ssn_ctx *c, const void *W, int nparts, int slot)
+{
+    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+    SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, W, c->d.ldw, W, c->d.ldw, c->red_a, vb, nullptr, c->st));
+    SSN_HIP(c, launch_combine(c->loss_part, nparts, scale_full(c), c->red_a, vb, 0.5 * c->d.lambda, c->scal_dev + slot,
+                              c->st));
+    return SSN_OK;
+}
+
+int objective_impl(ssn_ctx *c, const void *W, double *f)
+{
+    RowsArgs a = rows_base(c);
+    a.nrows = c->d.n;
+    a.M = W;
+    a.mode = ROW_OBJ;
+    int nparts = 0;
+    SSN_TRY(launch_rows(c, a, &nparts));
+    SSN_TRY(enqueue_objective_value(c, W, nparts, 0));
+    SSN_TRY(read_scalar(c, c->scal_dev, f));
+    if (!std::isfinite(*f)) return fail(c, SSN_E_NONFINITE, "objective is not finite");
+    return SSN_OK;
+}
+
+int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f)
+{
+    SSN_TRY(ensure_rows(c, &c->Ubuf, &c->U_rows, round_up(c->d.n, 16)));
+    RowsArgs a = rows_base(c);
+    a.nrows = c->d.n;
+    a.M = W;
+    a.mode = ROW_GRAD;
+    a.UP = c->Ubuf;
+    int nparts = 0;
+    SSN_TRY(launch_rows(c, a, &nparts));
+    SSN_TRY(transposed_product(c, nullptr, c->d.n, scale_full(c), W, G, false, nullptr, nullptr));
+    if (f) {
+        SSN_TRY(enqueue_objective_value(c, W, nparts, 0));
+        SSN_TRY(read_scalar(c, c->scal_dev, f));
+        if (!std::isfinite(*f)) return fail(c, SSN_E_NONFINITE, "objective is not finite");
+    }
+    return SSN_OK;
+}
+
+int hess_apply_impl(ssn_ctx *c, const void *V, void *HV, bool want_dot, int *ndot, const int32_t *skip)
+{
+    RowsArgs a = rows_base(c);
+    a.S = c->S;
+    a.nrows = c->nS;
+    a.M = V;
+    a.mode = ROW_APPLY;
+    a.Pin = c->Pbuf;
+    a.UP = c->Ubuf;
+    a.skip = skip;
+    SSN_TRY(launch_rows(c, a, nullptr));
+    return transposed_product(c, c->S, c->nS, scale_sample(c), V, HV, want_dot, ndot, skip);
+}
+
+double now_ms()
+{
+    using namespace std::chrono;
+    return duration<double, std::milli>(steady_clock::now().time_since_epoch()).count();
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ssn_strerror(int status)
+{
+    switch (status) {
+    case SSN_OK: return "ok";
+    case SSN_E_INVALID_ARG: return "invalid argument";
+    case SSN_E_BAD_LABEL: return "label outside [0,C)";
+    case SSN_E_BAD_INDEX: return "index out of range";
+    case SSN_E_NOT_PREPARED: return "Hessian sample not prepared";
+    case SSN_E_ALLOC: return "device allocation failed";
+    case SSN_E_HIP: return "HIP runtime error";
+    case SSN_E_NONFINITE: return "non-finite objective";
+    case SSN_E_UNSUPPORTED: return "unsupported shape";
+    default: return "unknown status";
+    }
+}
+
+const char *ssn_last_error(const ssn_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int ssn_destroy(ssn_ctx *c)
+{
+    if (!c) return SSN_E_INVALID_ARG;
+    (void)hipStreamSynchronize(c->st);
+    void *dev[] = {c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->scal_dev, c->int_dev,
+                   c->cg_p, c->cg_r, c->cg_s, c->cg_Hs, c->trial, c->grad, c->dir, c->slots, c->trace_dev};
+    for (void *p : dev)
+        if (p) (void)hipFree(p);
+    if (c->host_pin) (void)hipHostFree(c->host_pin);
+    delete c;
+    return SSN_OK;
+}
+
+int ssn_create(ssn_ctx **out, const ssn_desc *d)
+{
+    if (!out || !d) return SSN_E_INVALID_ARG;
+    *out = nullptr;
+    if (d->n < 1 || d->p < 1 || d->C < 2 || !(d->lambda >= 0.0) || !d->labels) return SSN_E_INVALID_ARG;
+    if (d->dtype != SSN_F32 && d->dtype != SSN_F64) return SSN_E_INVALID_ARG;
+    if (d->scale != SSN_SCALE_MEAN && d->scale != SSN_SCALE_SUM) return SSN_E_INVALID_ARG;
+    const int K = d->C - 1;
+    if (d->ldw < K) return SSN_E_INVALID_ARG;
+    if (d->n >= (int64_t)1 << 31 || d->p >= (int64_t)1 << 31) return SSN_E_UNSUPPORTED;
+    if (d->layout == SSN_DENSE_ROWMAJOR) {
+        if (!d->X || d->ldx < d->p) return SSN_E_INVALID_ARG;
+        if (K > 32) return SSN_E_UNSUPPORTED;
+    } else if (d->layout == SSN_CSR) {
+        if (!d->rowptr || d->nnz < 0 || (d->nnz > 0 && (!d->colidx || !d->vals))) return SSN_E_INVALID_ARG;
+        if (d->nnz >= (int64_t)1 << 31) return SSN_E_UNSUPPORTED;
+        if (K > 64) return SSN_E_UNSUPPORTED;
+    } else {
+        return SSN_E_INVALID_ARG;
+    }
+
+    ssn_ctx *c = new (std::nothrow) ssn_ctx();
+    if (!c) return SSN_E_ALLOC;
+    c->d = *d;
+    c->K = K;
+    c->es = d->dtype == SSN_F32 ? 4 : 8;
+    c->KP = d->layout == SSN_DENSE_ROWMAJOR ? (K + 15) / 16 * 16 : K;
+    c->st = (hipStream_t)d->stream;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+        c->num_cus = prop.multiProcessorCount;
+
+    auto bail = [&](int code) {
+        ssn_destroy(c);
+        return code;
+    };
+#define CREATE_HIP(call)                                                                           \
+    do {                                                                                           \
+        hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess) return bail(e_ == hipErrorOutOfMemory ? SSN_E_ALLOC : SSN_E_HIP);   \
+    } while (0)
+
+    c->wave_parts = c->num_cus * 8 * ROWS_WAVES_PER_BLOCK;
+    CREATE_HIP(hipMalloc((void **)&c->loss_part, sizeof(double) * c->wave_parts));
+    CREATE_HIP(hipMalloc((void **)&c->hit_part, sizeof(int32_t) * c->wave_parts));
+    CREATE_HIP(hipMalloc((void **)&c->red_a, sizeof(double) * RED_MAX_PARTS));
+    CREATE_HIP(hipMalloc((void **)&c->red_b, sizeof(double) * RED_MAX_PARTS));
+    CREATE_HIP(hipMalloc((void **)&c->scal_dev, sizeof(double) * 8));
+    CREATE_HIP(hipMalloc((void **)&c->int_dev, sizeof(int32_t) * 8));
+    CREATE_HIP(hipHostMalloc((void **)&c->host_pin, 4096));
+    if (d->layout == SSN_DENSE_ROWMAJOR) {
+        const int64_t nft = (d->p + 63) / 64;
+        c->max_chunks = (int)(((int64_t)c->num_cus * 8 + nft - 1) / nft);
+        c->part_elems = (int64_t)c->max_chunks * d->p * K;
+        CREATE_HIP(hipMalloc(&c->part, (size_t)c->part_elems * c->es));
+    }
+
+    // validation: one device pass over the labels and, for CSR, over the index arrays
+    int32_t bad = 0;
+    CREATE_HIP(launch_check_range(d->labels, d->n, 0, d->C, c->int_dev, c->st));
+    if (read_int(c, c->int_dev, &bad) != SSN_OK) return bail(SSN_E_HIP);
+    if (bad) return bail(SSN_E_BAD_LABEL);
+    if (d->layout == SSN_CSR) {
+        CREATE_HIP(launch_check_rowptr(d->rowptr, d->n, d->nnz, c->int_dev, c->st));
+        if (read_int(c, c->int_dev, &bad) != SSN_OK) return bail(SSN_E_HIP);
+        if (bad) return bail(SSN_E_INVALID_ARG);
+        if (d->nnz > 0) {
+            CREATE_HIP(launch_check_range(d->colidx, d->nnz, 0, d->p, c->int_dev, c->st));
+            if (read_int(c, c->int_dev, &bad) != SSN_OK) return bail(SSN_E_HIP);
+            if (bad) return bail(SSN_E_BAD_INDEX);
+        }
+    }
+#undef CREATE_HIP
+    *out = c;
+    return SSN_OK;
+}
+
+int ssn_set_stream(ssn_ctx *c, void *stream)
+{
+    if (!c) return SSN_E_INVALID_ARG;
+    SSN_HIP(c, hipStreamSynchronize(c->st));
+    c->st = (hipStream_t)stream;
+    return SSN_OK;
+}
+
+int ssn_objective(ssn_ctx *c, const void *W, double *f)
+{
+    if (!c || !W || !f) return fail(c, SSN_E_INVALID_ARG, "ssn_objective: null argument");
+    return objective_impl(c, W, f);
+}
+
+int ssn_gradient(ssn_ctx *c, const void *W, void *G, double *f)
+{
+    if (!c || !W || !G || W == G) return fail(c, SSN_E_INVALID_ARG, "ssn_gradient: null or aliased argument");
+    return gradient_impl(c, W, G, f);
+}
+
+int ssn_hess_prepare(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS)
+{
+    if (!c || !W || !S || nS < 1) return fail(c, SSN_E_INVALID_ARG, "ssn_hess_prepare: null argument or nS < 1");
+    c->prepared = false;
+    int32_t bad = 0;
+    SSN_HIP(c, launch_check_range(S, nS, 0, c->d.n, c->int_dev, c->st));
+    SSN_TRY(read_int(c, c->int_dev, &bad));
+    if (bad) return fail(c, SSN_E_BAD_INDEX, "ssn_hess_prepare: sample index outside [0,n)");
+    const int64_t rows = round_up(nS, 16);
+    SSN_TRY(ensure_rows(c, &c->Pbuf, &c->P_rows, rows));
+    SSN_TRY(ensure_rows(c, &c->Ubuf, &c->U_rows, rows));
+    RowsArgs a = rows_base(c);
+    a.S = S;
+    a.nrows = nS;
+    a.M = W;
+    a.mode = ROW_PREP;
+    a.UP = c->Pbuf;
+    SSN_TRY(launch_rows(c, a, nullptr));
+    c->S = S;
+    c->nS = nS;
+    c->prepared = true;
+    return SSN_OK;
+}
+
+int ssn_hess_apply(ssn_ctx *c, const void *V, void *HV)
+{
+    if (!c || !V || !HV || V == HV) return fail(c, SSN_E_INVALID_ARG, "ssn_hess_apply: null or aliased argument");
+    if (!c->prepared) return fail(c, SSN_E_NOT_PREPARED, "ssn_hess_apply before ssn_hess_prepare");
+    return hess_apply_impl(c, V, HV, false, nullptr, nullptr);
+}
+
+int ssn_hessvec(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS, const void *V, void *HV)
+{
+    SSN_TRY(ssn_hess_prepare(c, W, S, nS));
+    return ssn_hess_apply(c, V, HV);
+}
+
+int ssn_cg(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out, ssn_cg_info *info, double *trace)
+{
+    if (!c || !G || !P_out || T < 0 || G == P_out) return fail(c, SSN_E_INVALID_ARG, "ssn_cg: bad argument");
+    if (!c->prepared) return fail(c, SSN_E_NOT_PREPARED, "ssn_cg before ssn_hess_prepare");
+    if (!c->cg_p) {
+        SSN_TRY(vec_bytes_alloc(c, &c->cg_p));
+        SSN_TRY(vec_bytes_alloc(c, &c->cg_r));
+        SSN_TRY(vec_bytes_alloc(c, &c->cg_s));
+        SSN_TRY(vec_bytes_alloc(c, &c->cg_Hs));
+    }
+    if (c->slots_cap < T + 1) {
+        SSN_HIP(c, hipStreamSynchronize(c->st));
+        if (c->slots) (void)hipFree(c->slots);
+        if (c->trace_dev) (void)hipFree(c->trace_dev);
+        c->slots = nullptr;
+        c->trace_dev = nullptr;
+        SSN_HIP(c, hipMalloc((void **)&c->slots, sizeof(CgSlot) * (size_t)(T + 1)));
+        SSN_HIP(c, hipMalloc((void **)&c->trace_dev, sizeof(double) * 3 * (size_t)(T + 1)));
+        c->slots_cap = T + 1;
+    }
+    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+    CgVecs v{};
+    v.p = c->d.p;
+    v.K = c->K;
+    v.ld = c->d.ldw;
+    v.G = G;
+    v.pv = c->cg_p;
+    v.r = c->cg_r;
+    v.s = c->cg_s;
+    v.Hs = c->cg_Hs;
+    v.pbest = P_out;
+    SSN_HIP(c, launch_cg_init(c->d.dtype, v, c->red_a, vb, c->st));
+    SSN_HIP(c, launch_cg_init_state(c->red_a, vb, c->slots, c->st));
+    for (int k = 0; k < T; ++k) {
+        const int32_t *skip = (const int32_t *)((const char *)(c->slots + k) + offsetof(CgSlot, done));
+        int ndot = 0;
+        SSN_TRY(hess_apply_impl(c, c->cg_s, c->cg_Hs, true, &ndot, skip));
+        SSN_HIP(c, launch_cg_step1(c->d.dtype, v, c->slots + k, c->red_b, ndot, c->red_a, c->trace_dev + 3 * k, vb, c->st));
+        SSN_HIP(c, launch_cg_step2(c->d.dtype, v, c->slots + k, c->slots + k + 1, c->red_a, vb, theta,
+                                   c->trace_dev + 3 * k, vb, c->st));
+    }
+    CgSlot fin;
+    std::vector<double> tr((size_t)3 * (T > 0 ? T : 1));
+    SSN_HIP(c, hipMemcpyAsync(&fin, c->slots + T, sizeof(CgSlot), hipMemcpyDeviceToHost, c->st));
+    if (trace && T > 0)
+        SSN_HIP(c, hipMemcpyAsync(tr.data(), c->trace_dev, sizeof(double) * 3 * (size_t)T, hipMemcpyDeviceToHost, c->st));
+    SSN_HIP(c, hipStreamSynchronize(c->st));
+    if (trace)
+        for (int k = 0; k < 3 * fin.iters && k < 3 * T; ++k) trace[k] = tr[k];
+    if (info) {
+        info->iters = fin.iters;
+        info->flags = fin.flags;
+        info->gnorm = fin.gnorm;
+        info->rel_res = fin.gnorm > 0.0 ? fin.rbest / fin.gnorm : 0.0;
+    }
+    return SSN_OK;
+}
+
+int ssn_axpy(ssn_ctx *c, double alpha, const void *P, void *W)
+{
+    if (!c || !P || !W) return fail(c, SSN_E_INVALID_ARG, "ssn_axpy: null argument");
+    SSN_HIP(c, launch_axpy(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, W, c->d.ldw, c->st));
+    return SSN_OK;
+}
+
+int ssn_linesearch(ssn_ctx *c, const void *W, const void *P, const void *G, double fW, double beta, double rho,
+                   int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok)
+{
+    if (!c || !W || !P || !G || !alpha_out || !f_new) return fail(c, SSN_E_INVALID_ARG, "ssn_linesearch: null argument");
+    if (!c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
+    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+    double slope = 0.0;
+    SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, P, c->d.ldw, G, c->d.ldw, c->red_a, vb, nullptr, c->st));
+    SSN_HIP(c, launch_combine(c->red_a, vb, 1.0, nullptr, 0, 0.0, c->scal_dev + 1, c->st));
+    SSN_TRY(read_scalar(c, c->scal_dev + 1, &slope));
+    double alpha = 1.0, ft = 0.0;
+    int i = 0, evals = 0, good = 0;
+    for (;;) {
+        SSN_HIP(c, launch_axpy(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, c->trial, c->d.ldw, c->st));
+        const int s = objective_impl(c, c->trial, &ft);
+        if (s != SSN_OK && s != SSN_E_NONFINITE) return s;
+        ++evals;
+        if (s == SSN_OK && !(ft > fW + alpha * beta * slope)) { good = 1; break; }
+        if (i > imax) break;
+        ++i;
+        alpha *= rho;
+    }
+    *alpha_out = alpha;
+    *f_new = ft;
+    if (n_eval) *n_eval = evals;
+    if (ok) *ok = good;
+    return SSN_OK;
+}
+
+int ssn_predict(ssn_ctx *c, const void *W, int32_t *pred, double *acc)
+{
+    if (!c || !W) return fail(c, SSN_E_INVALID_ARG, "ssn_predict: null argument");
+    RowsArgs a = rows_base(c);
+    a.nrows = c->d.n;
+    a.M = W;
+    a.mode = ROW_PRED;
+    a.pred = pred;
+    int nparts = 0;
+    SSN_TRY(launch_rows(c, a, &nparts));
+    if (acc) {
+        int32_t hits = 0;
+        SSN_HIP(c, launch_sum_int(c->hit_part, nparts, c->int_dev + 1, c->st));
+        SSN_TRY(read_int(c, c->int_dev + 1, &hits));
+        *acc = (double)hits / (double)c->d.n;
+    }
+    return SSN_OK;
+}
+
+int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, int32_t max_log, int32_t *iters_done)
+{
+    if (!c || !W || !pr || !pr->S_all || pr->nS < 1 || pr->iters < 0)
+        return fail(c, SSN_E_INVALID_ARG, "ssn_solve: bad argument");
+    if (!c->grad) SSN_TRY(vec_bytes_alloc(c, &c->grad));
+    if (!c->dir) SSN_TRY(vec_bytes_alloc(c, &c->dir));
+    int k = 0;
+    for (; k < pr->iters; ++k) {
+        ssn_iter_record rec{};
+        rec.test_acc = std::nan("");
+        double t0 = now_ms();
+        SSN_TRY(gradient_impl(c, W, c->grad, &rec.f));
+        const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+        double gg = 0.0;
+        SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, c->grad, c->d.ldw, c->grad, c->d.ldw, c->red_a, vb, nullptr,
+                                   c->st));
+        SSN_HIP(c, launch_combine(c->red_a, vb, 1.0, nullptr, 0, 0.0, c->scal_dev + 2, c->st));
+        SSN_TRY(read_scalar(c, c->scal_dev + 2, &gg));
+        rec.gnorm = std::sqrt(gg);
+        double t1 = now_ms();
+        rec.ms_grad = t1 - t0;
+        if (rec.gnorm < pr->eps) {
+            if (log && k < max_log) log[k] = rec;
+            break;
+        }
+        SSN_TRY(ssn_hess_prepare(c, W, pr->S_all + (int64_t)k * pr->nS, pr->nS));
+        SSN_HIP(c, hipStreamSynchronize(c->st));
+        double t2 = now_ms();
+        rec.ms_prepare = t2 - t1;
+        ssn_cg_info info{};
+        SSN_TRY(ssn_cg(c, c->grad, pr->theta, pr->T, c->dir, &info, nullptr));
+        double t3 = now_ms();
+        rec.ms_cg = t3 - t2;
+        rec.cg_iters = info.iters;
+        rec.cg_rel_res = info.rel_res;
+        double fn = 0.0;
+        SSN_TRY(ssn_linesearch(c, W, c->dir, c->grad, rec.f, pr->beta, pr->rho, pr->imax, &rec.alpha, &fn, &rec.ls_evals,
+                               &rec.ls_ok));
+        double t4 = now_ms();
+        rec.ms_linesearch = t4 - t3;
+        SSN_TRY(ssn_axpy(c, rec.alpha, c->dir, W));
+        if (pr->test) {
+            // the held-out context runs on its own stream: wait for the update first
+            SSN_HIP(c, hipStreamSynchronize(c->st));
+            SSN_TRY(ssn_predict(pr->test, W, nullptr, &rec.test_acc));
+        }
+        SSN_HIP(c, hipStreamSynchronize(c->st));
+        rec.ms_update = now_ms() - t4;
+        if (log && k < max_log) log[k] = rec;
+    }
+    if (iters_done) *iters_done = k;
+    return SSN_OK;
+}
+
+int ssn_time_kernel(ssn_ctx *c, int32_t which, const void *M, int32_t reps, double *ms)
+{
+    if (!c || !M || !ms || reps < 1 || which < 0 || which > 4) return fail(c, SSN_E_INVALID_ARG, "ssn_time_kernel: bad argument");
+    const bool sampled = which >= 3;
+    if (sampled && !c->prepared) return fail(c, SSN_E_NOT_PREPARED, "ssn_time_kernel: no prepared sample");
+    const int64_t nrows = sampled ? c->nS : c->d.n;
+    SSN_TRY(ensure_rows(c, &c->Ubuf, &c->U_rows, round_up(nrows, 16)));
+    RowsArgs a = rows_base(c);
+    a.S = sampled ? c->S : nullptr;
+    a.nrows = nrows;
+    a.M = M;
+    a.UP = c->Ubuf;
+    a.Pin = c->Pbuf;
+    a.mode = which == 0 ? ROW_OBJ : (which == 1 ? ROW_GRAD : ROW_APPLY);
+    XtuArgs x = xtu_base(c);
+    x.S = a.S;
+    x.nrows = nrows;
+    x.U = c->Ubuf;
+    if (is_dense(c)) choose_chunks(c, nrows, &x.rows_per_chunk, &x.nchunks);
+    if (!is_dense(c) && (which == 2 || which == 4) && !c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
+    hipEvent_t e0, e1;
+    SSN_HIP(c, hipEventCreate(&e0));
+    SSN_HIP(c, hipEventCreate(&e1));
+    int status = SSN_OK;
+    hipError_t he = hipEventRecord(e0, c->st);
+    for (int r = 0; r < reps && status == SSN_OK && he == hipSuccess; ++r) {
+        if (which == 2 || which == 4) {
+            if (is_dense(c)) he = launch_dense_xtu(c->d.dtype, x, c->st);
+            else he = launch_csr_scatter(c->d.dtype, x, sampled ? scale_sample(c) : scale_full(c), c->trial, c->d.ldw, c->st);
+        } else {
+            status = launch_rows(c, a, nullptr);
+        }
+    }
+    if (he == hipSuccess) he = hipEventRecord(e1, c->st);
+    if (he == hipSuccess) he = hipEventSynchronize(e1);
+    float t = 0.f;
+    if (he == hipSuccess) he = hipEventElapsedTime(&t, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (status != SSN_OK) return status;
+    SSN_HIP(c, he);
+    *ms = (double)t / reps;
+    return SSN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,145 @@
+// Internal declarations shared by the translation units of libssn_hip.so.
+// Nothing here is part of the public C ABI (that is include/ssn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+
+#include "ssn.h"
+
+namespace ssn {
+
+// ---- per-row epilogue selector of the row-block kernels -------------------------------
+enum RowMode : int {
+    ROW_OBJ = 0,    // loss only                                   (Alg. 5)
+    ROW_GRAD = 1,   // loss + U = P - Y                            (Alg. 6)
+    ROW_PREP = 2,   // store P                                     (eq. (11))
+    ROW_APPLY = 3,  // U = P .* Vhat - P .* ((P .* Vhat) e e^T)    (eq. (12), Alg. 8)
+    ROW_PRED = 4    // argmax classification + hit count
+};
+
+// Arguments of the "rows" kernels: Z = X_rows * M followed by a per-row epilogue.
+struct RowsArgs {
+    // data (dense or CSR)
+    const void *X;
+    int64_t ldx;
+    const int32_t *rowptr, *colidx;
+    const void *vals;
+    int64_t n, p;
+    int32_t K;
+    const int32_t *labels;
+    // which rows: S == nullptr -> rows 0..nrows-1, else rows S[0..nrows-1]
+    const int32_t *S;
+    int64_t nrows;
+    // right operand, p x K, leading dimension ldm
+    const void *M;
+    int64_t ldm;
+    // per-row buffers with row stride KP (padded K): Pin read by ROW_APPLY, UP written by GRAD/PREP/APPLY
+    const void *Pin;
+    void *UP;
+    int32_t KP;
+    // outputs
+    double *loss_part;   // one partial per wave (OBJ, GRAD)
+    int32_t *pred;       // nullable (PRED)
+    int32_t *hit_part;   // one partial per wave (PRED)
+    int32_t mode;
+    const int32_t *skip; // nullable device flag: non-zero -> the launch does nothing
+};
+
+// Arguments of the transposed product: part[chunk] = X_rows(chunk)^T * U(chunk).
+struct XtuArgs {
+    const void *X;
+    int64_t ldx;
+    const int32_t *rowptr, *colidx;
+    const void *vals;
+    int64_t n, p;
+    int32_t K;
+    const int32_t *S;
+    int64_t nrows;
+    const void *U;       // nrows_pad x KP
+    int32_t KP;
+    void *part;          // nchunks x p x K (element type T)
+    int64_t rows_per_chunk;
+    int32_t nchunks;
+    const int32_t *skip;
+};
+
+// out = scale * sum_chunks part + lambda * M ; optional per-block partials of <out, M>.
+struct FinArgs {
+    const void *part;
+    int32_t nchunks;
+    int64_t p;
+    int32_t K;
+    double scale, lambda;
+    const void *M;
+    int64_t ldm;
+    void *out;
+    int64_t ldo;
+    double *dot_part;    // nullable; FIN_BLOCKS entries
+    const int32_t *skip;
+};
+
+constexpr int ROWS_WAVES_PER_BLOCK = 4;
+constexpr int RED_MAX_PARTS = 1024;   // upper bound on partial-sum arrays consumed by single-block reducers
+constexpr int VEC_BLOCK = 256;
+
+// grid sizes: blocks of the rows kernels (4 wave partials each), of the level-1 kernels (one partial
+// each, <= RED_MAX_PARTS) and of the finalize kernel (one <.,.> partial each, <= RED_MAX_PARTS)
+int rows_grid_blocks(int64_t nrows, int num_cus);
+int vec_blocks(int64_t total);
+int finalize_blocks(int64_t p, int K);
+
+// ---- launchers (dense_mfma.hip / csr.hip / vecops.hip) ---------------------------------
+hipError_t launch_dense_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
+hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st);
+hipError_t launch_csr_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
+hipError_t launch_csr_scatter(int dtype, const XtuArgs &a, double scale, void *out, int64_t ldo, hipStream_t st);
+hipError_t launch_finalize(int dtype, const FinArgs &a, int blocks, hipStream_t st);
+
+// out = lambda * M (p x K), with optional <.,.> partials disabled; used by the CSR path before scattering
+hipError_t launch_scale_copy(int dtype, int64_t p, int K, double lambda, const void *M, int64_t ldm,
+                             void *out, int64_t ldo, const int32_t *skip, hipStream_t st);
+
+// partials of <A, B> over the p x K block: part[b] for b < blocks
+hipError_t launch_dot_part(int dtype, int64_t p, int K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                           double *part, int blocks, const int32_t *skip, hipStream_t st);
+// Y = alpha * X + Z (Y may alias Z)
+hipError_t launch_axpy(int dtype, int64_t p, int K, double alpha, const void *X, int64_t ldx_,
+                       const void *Z, int64_t ldz, void *Y, int64_t ldy, hipStream_t st);
+// *out = scale * sum(a[0..na)) + coef * sum(b[0..nb))   (single block, fixed order)
+hipError_t launch_combine(const double *a, int na, double scale, const double *b, int nb, double coef,
+                          double *out, hipStream_t st);
+hipError_t launch_sum_int(const int32_t *a, int na, int32_t *out, hipStream_t st);
+
+// validation passes: *bad receives the number of offending entries
+hipError_t launch_check_range(const int32_t *v, int64_t count, int64_t lo, int64_t hi, int32_t *bad, hipStream_t st);
+hipError_t launch_check_rowptr(const int32_t *rowptr, int64_t n, int64_t nnz, int32_t *bad, hipStream_t st);
+
+// ---- device-resident CG (Alg. 2) ---------------------------------------------------------
+struct CgSlot {          // state before product k
+    double rr;           // r_k^T r_k
+    double rbest;        // ||r_best||
+    double gnorm;        // ||g||
+    int32_t done;        // loop has ended (theta test, breakdown, zero gradient)
+    int32_t iters;       // products made so far
+    int32_t flags;
+    int32_t brk;         // written by step1 of product k when s^T H s <= 0
+};
+
+struct CgVecs {
+    int64_t p;
+    int32_t K;
+    int64_t ld;          // leading dimension of every vector below
+    const void *G;
+    void *pv, *r, *s, *Hs, *pbest;
+};
+
+hipError_t launch_cg_init(int dtype, const CgVecs &v, double *gg_part, int blocks, hipStream_t st);
+hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0, hipStream_t st);
+hipError_t launch_cg_step1(int dtype, const CgVecs &v, const CgSlot *cur, const double *sHs_part, int n_sHs,
+                           double *rr_part, double *trace_k, int blocks, hipStream_t st);
+hipError_t launch_cg_step2(int dtype, const CgVecs &v, const CgSlot *cur, CgSlot *next, const double *rr_part,
+                           int n_rr, double theta, double *trace_k, int blocks, hipStream_t st);
+
+}  // namespace ssn

@@ -1,0 +1,409 @@
+// Level-1 style kernels on p x K blocks (the paper's d-vectors), the fixed-order reducers, the
+// validation passes and the device-resident conjugate-gradient steps of Alg. 2.
+//
+// All reductions are two-stage and deterministic: every block writes one partial, consumers add the
+// partials in one fixed order.  Scalars of Alg. 2 never visit the host: each kernel of product k reads
+// the state slot k and block 0 writes slot k+1, so no slot is read and written by the same launch.
+#include "ssn_internal.h"
+
+namespace ssn {
+
+__device__ __forceinline__ double block_sum(double v)
+{
+    __shared__ double sm[VEC_BLOCK];
+    const int t = threadIdx.x;
+    sm[t] = v;
+    __syncthreads();
+    for (int s = VEC_BLOCK / 2; s > 0; s >>= 1) {
+        if (t < s) sm[t] += sm[t + s];
+        __syncthreads();
+    }
+    const double r = sm[0];
+    __syncthreads();
+    return r;
+}
+
+__device__ __forceinline__ double sum_parts(const double *part, int n)
+{
+    double v = 0.0;
+    for (int i = threadIdx.x; i < n; i += VEC_BLOCK) v += part[i];
+    return block_sum(v);
+}
+
+// offset of element e of a p x K block with leading dimension ld
+__device__ __forceinline__ int64_t off_of(int64_t e, int K, int64_t ld)
+{
+    if (ld == K) return e;
+    const int64_t j = e / K;
+    return j * ld + (e - j * K);
+}
+
+int vec_blocks(int64_t total)
+{
+    int64_t b = (total + VEC_BLOCK * 4 - 1) / (VEC_BLOCK * 4);
+    if (b > RED_MAX_PARTS) b = RED_MAX_PARTS;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+// ---- finalize: out = scale * sum_chunks part + lambda * M -----------------------------------
+// A block owns EL consecutive elements at a time; its 256/EL thread rows split the chunk sum and are
+// folded through LDS in a fixed order.
+template <typename T, int EL> __global__ __launch_bounds__(VEC_BLOCK) void finalize_kernel(FinArgs a)
+{
+    if (a.skip && *a.skip) return;
+    constexpr int CLN = VEC_BLOCK / EL;
+    __shared__ double sm[VEC_BLOCK];
+    const int el = threadIdx.x % EL, cl = threadIdx.x / EL;
+    const int64_t total = a.p * a.K;
+    const int64_t ngroups = (total + EL - 1) / EL;
+    const T *part = (const T *)a.part;
+    const T *M = (const T *)a.M;
+    T *out = (T *)a.out;
+    double local = 0.0;
+    for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
+        const int64_t e = grp * EL + el;
+        double s = 0.0;
+        if (e < total)
+            for (int c = cl; c < a.nchunks; c += CLN) s += (double)part[(int64_t)c * total + e];
+        sm[threadIdx.x] = s;
+        __syncthreads();
+        if (cl == 0 && e < total) {
+            double t = 0.0;
+#pragma unroll
+            for (int k = 0; k < CLN; ++k) t += sm[k * EL + el];
+            const double m = (double)M[off_of(e, a.K, a.ldm)];
+            const T o = (T)(a.scale * t + a.lambda * m);
+            out[off_of(e, a.K, a.ldo)] = o;
+            local += (double)o * m;
+        }
+        __syncthreads();
+    }
+    if (a.dot_part) {
+        const double r = block_sum(local);
+        if (threadIdx.x == 0) a.dot_part[blockIdx.x] = r;
+    }
+}
+
+int finalize_blocks(int64_t p, int K)
+{
+    const int64_t total = p * K;
+    const int el = (total >= 32 * 256) ? 32 : 4;
+    int64_t b = (total + el - 1) / el;
+    if (b > RED_MAX_PARTS) b = RED_MAX_PARTS;
+    return (int)b;
+}
+
+hipError_t launch_finalize(int dtype, const FinArgs &a, int blocks, hipStream_t st)
+{
+    const bool wide = (a.p * a.K >= 32 * 256);
+    if (dtype == SSN_F32) {
+        if (wide) hipLaunchKernelGGL((finalize_kernel<float, 32>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a);
+        else hipLaunchKernelGGL((finalize_kernel<float, 4>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a);
+    } else {
+        if (wide) hipLaunchKernelGGL((finalize_kernel<double, 32>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a);
+        else hipLaunchKernelGGL((finalize_kernel<double, 4>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a);
+    }
+    return hipGetLastError();
+}
+
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void scale_copy_kernel(int64_t p, int K, double lambda, const T *M, int64_t ldm,
+                                                                T *out, int64_t ldo, const int32_t *skip)
+{
+    if (skip && *skip) return;
+    const int64_t total = p * K;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK)
+        out[off_of(e, K, ldo)] = (T)(lambda * (double)M[off_of(e, K, ldm)]);
+}
+
+hipError_t launch_scale_copy(int dtype, int64_t p, int K, double lambda, const void *M, int64_t ldm, void *out,
+                             int64_t ldo, const int32_t *skip, hipStream_t st)
+{
+    const int blocks = vec_blocks(p * K) * 4 > 4096 ? 4096 : vec_blocks(p * K) * 4;
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(scale_copy_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, p, K, lambda, (const float *)M,
+                           ldm, (float *)out, ldo, skip);
+    else
+        hipLaunchKernelGGL(scale_copy_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, p, K, lambda,
+                           (const double *)M, ldm, (double *)out, ldo, skip);
+    return hipGetLastError();
+}
+
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void dot_part_kernel(int64_t p, int K, const T *A, int64_t lda, const T *B,
+                                                              int64_t ldb, double *part, const int32_t *skip)
+{
+    if (skip && *skip) return;
+    const int64_t total = p * K;
+    double local = 0.0;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK)
+        local += (double)A[off_of(e, K, lda)] * (double)B[off_of(e, K, ldb)];
+    const double r = block_sum(local);
+    if (threadIdx.x == 0) part[blockIdx.x] = r;
+}
+
+hipError_t launch_dot_part(int dtype, int64_t p, int K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                           double *part, int blocks, const int32_t *skip, hipStream_t st)
+{
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(dot_part_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, p, K, (const float *)A, lda,
+                           (const float *)B, ldb, part, skip);
+    else
+        hipLaunchKernelGGL(dot_part_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, p, K, (const double *)A, lda,
+                           (const double *)B, ldb, part, skip);
+    return hipGetLastError();
+}
+
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void axpy_kernel(int64_t p, int K, double alpha, const T *X, int64_t ldx,
+                                                          const T *Z, int64_t ldz, T *Y, int64_t ldy)
+{
+    const int64_t total = p * K;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK)
+        Y[off_of(e, K, ldy)] = (T)(alpha * (double)X[off_of(e, K, ldx)] + (double)Z[off_of(e, K, ldz)]);
+}
+
+hipError_t launch_axpy(int dtype, int64_t p, int K, double alpha, const void *X, int64_t ldx_, const void *Z,
+                       int64_t ldz, void *Y, int64_t ldy, hipStream_t st)
+{
+    const int blocks = vec_blocks(p * K) * 4 > 4096 ? 4096 : vec_blocks(p * K) * 4;
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(axpy_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, p, K, alpha, (const float *)X, ldx_,
+                           (const float *)Z, ldz, (float *)Y, ldy);
+    else
+        hipLaunchKernelGGL(axpy_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, p, K, alpha, (const double *)X,
+                           ldx_, (const double *)Z, ldz, (double *)Y, ldy);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(VEC_BLOCK) void combine_kernel(const double *a, int na, double scale, const double *b,
+                                                             int nb, double coef, double *out)
+{
+    const double sa = sum_parts(a, na);
+    const double sb = (b != nullptr) ? sum_parts(b, nb) : 0.0;
+    if (threadIdx.x == 0) *out = scale * sa + coef * sb;
+}
+
+hipError_t launch_combine(const double *a, int na, double scale, const double *b, int nb, double coef, double *out,
+                          hipStream_t st)
+{
+    hipLaunchKernelGGL(combine_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, a, na, scale, b, nb, coef, out);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(VEC_BLOCK) void sum_int_kernel(const int32_t *a, int na, int32_t *out)
+{
+    __shared__ long long sm[VEC_BLOCK];
+    long long v = 0;
+    for (int i = threadIdx.x; i < na; i += VEC_BLOCK) v += a[i];
+    sm[threadIdx.x] = v;
+    __syncthreads();
+    for (int s = VEC_BLOCK / 2; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sm[threadIdx.x] += sm[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = (int32_t)sm[0];
+}
+
+hipError_t launch_sum_int(const int32_t *a, int na, int32_t *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(sum_int_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, a, na, out);
+    return hipGetLastError();
+}
+
+// ---- validation ---------------------------------------------------------------------------
+__global__ void zero_int_kernel(int32_t *x) { *x = 0; }
+
+__global__ __launch_bounds__(VEC_BLOCK) void check_range_kernel(const int32_t *v, int64_t count, int64_t lo, int64_t hi,
+                                                                 int32_t *bad)
+{
+    int local = 0;
+    for (int64_t i = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; i < count; i += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int64_t x = v[i];
+        local += (x < lo || x >= hi);
+    }
+    if (local) atomicAdd(bad, local);
+}
+
+hipError_t launch_check_range(const int32_t *v, int64_t count, int64_t lo, int64_t hi, int32_t *bad, hipStream_t st)
+{
+    hipLaunchKernelGGL(zero_int_kernel, dim3(1), dim3(1), 0, st, bad);
+    hipLaunchKernelGGL(check_range_kernel, dim3(vec_blocks(count)), dim3(VEC_BLOCK), 0, st, v, count, lo, hi, bad);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(VEC_BLOCK) void check_rowptr_kernel(const int32_t *rowptr, int64_t n, int64_t nnz,
+                                                                  int32_t *bad)
+{
+    int local = 0;
+    for (int64_t i = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; i < n; i += (int64_t)gridDim.x * VEC_BLOCK)
+        local += (rowptr[i + 1] < rowptr[i]);
+    if (blockIdx.x == 0 && threadIdx.x == 0) local += (rowptr[0] != 0) + ((int64_t)rowptr[n] != nnz);
+    if (local) atomicAdd(bad, local);
+}
+
+hipError_t launch_check_rowptr(const int32_t *rowptr, int64_t n, int64_t nnz, int32_t *bad, hipStream_t st)
+{
+    hipLaunchKernelGGL(zero_int_kernel, dim3(1), dim3(1), 0, st, bad);
+    hipLaunchKernelGGL(check_rowptr_kernel, dim3(vec_blocks(n)), dim3(VEC_BLOCK), 0, st, rowptr, n, nnz, bad);
+    return hipGetLastError();
+}
+
+// ---- Alg. 2 on the device -------------------------------------------------------------------
+// lines 1-5: p = 0, r = -g, s = r, p_best = s; partials of g.g
+template <typename T> __global__ __launch_bounds__(VEC_BLOCK) void cg_init_kernel(CgVecs v, double *gg_part)
+{
+    const int64_t total = v.p * v.K;
+    const T *G = (const T *)v.G;
+    T *pv = (T *)v.pv, *r = (T *)v.r, *s = (T *)v.s, *pb = (T *)v.pbest;
+    double local = 0.0;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int64_t o = off_of(e, v.K, v.ld);
+        const T gv = G[o];
+        pv[o] = T(0);
+        r[o] = -gv;
+        s[o] = -gv;
+        pb[o] = -gv;
+        local += (double)gv * (double)gv;
+    }
+    const double t = block_sum(local);
+    if (threadIdx.x == 0) gg_part[blockIdx.x] = t;
+}
+
+hipError_t launch_cg_init(int dtype, const CgVecs &v, double *gg_part, int blocks, hipStream_t st)
+{
+    if (dtype == SSN_F32) hipLaunchKernelGGL(cg_init_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, gg_part);
+    else hipLaunchKernelGGL(cg_init_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, gg_part);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(VEC_BLOCK) void cg_init_state_kernel(const double *gg_part, int nparts, CgSlot *slot0)
+{
+    const double gg = sum_parts(gg_part, nparts);
+    if (threadIdx.x == 0) {
+        CgSlot s;
+        s.rr = gg;
+        s.rbest = sqrt(gg);
+        s.gnorm = sqrt(gg);
+        s.done = (gg == 0.0) ? 1 : 0;
+        s.iters = 0;
+        s.flags = 0;
+        s.brk = 0;
+        *slot0 = s;
+    }
+}
+
+hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0, hipStream_t st)
+{
+    hipLaunchKernelGGL(cg_init_state_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, gg_part, nparts, slot0);
+    return hipGetLastError();
+}
+
+// lines 7-9: alpha = r.r / s.Hs ; p += alpha s ; r -= alpha Hs ; partials of the new r.r
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void cg_step1_kernel(CgVecs v, CgSlot *cur, const double *sHs_part, int n_sHs,
+                                                              double *rr_part, double *trace_k)
+{
+    if (cur->done) return;
+    const double sHs = sum_parts(sHs_part, n_sHs);
+    const double rr = cur->rr;
+    if (!(sHs > 0.0)) {                      // not positive definite in floating point: stop, keep p_best
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            cur->brk = 1;                    // read only by step 2 of this product
+            if (trace_k) { trace_k[0] = 0.0; trace_k[1] = sqrt(rr); trace_k[2] = sHs; }
+        }
+        return;
+    }
+    const double alpha = rr / sHs;
+    const int64_t total = v.p * v.K;
+    T *pv = (T *)v.pv, *r = (T *)v.r;
+    const T *s = (const T *)v.s, *Hs = (const T *)v.Hs;
+    double local = 0.0;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int64_t o = off_of(e, v.K, v.ld);
+        pv[o] = (T)((double)pv[o] + alpha * (double)s[o]);
+        const T rn = (T)((double)r[o] - alpha * (double)Hs[o]);
+        r[o] = rn;
+        local += (double)rn * (double)rn;
+    }
+    const double t = block_sum(local);
+    if (threadIdx.x == 0) {
+        rr_part[blockIdx.x] = t;
+        if (blockIdx.x == 0 && trace_k) { trace_k[0] = alpha; trace_k[2] = sHs; }
+    }
+}
+
+hipError_t launch_cg_step1(int dtype, const CgVecs &v, const CgSlot *cur, const double *sHs_part, int n_sHs,
+                           double *rr_part, double *trace_k, int blocks, hipStream_t st)
+{
+    CgSlot *c = const_cast<CgSlot *>(cur);
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(cg_step1_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, c, sHs_part, n_sHs, rr_part,
+                           trace_k);
+    else
+        hipLaunchKernelGGL(cg_step1_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, c, sHs_part, n_sHs, rr_part,
+                           trace_k);
+    return hipGetLastError();
+}
+
+// lines 10-12: best-iterate memory, theta test, new search direction
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgSlot *cur, CgSlot *next,
+                                                              const double *rr_part, int n_rr, double theta,
+                                                              double *trace_k)
+{
+    const CgSlot c = *cur;
+    if (c.done || c.brk) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            CgSlot n = c;
+            if (c.brk && !c.done) { n.flags |= 2; n.iters = c.iters + 1; }
+            n.done = 1;
+            n.brk = 0;
+            *next = n;
+        }
+        return;
+    }
+    const double rr_new = sum_parts(rr_part, n_rr);
+    const double rnorm = sqrt(rr_new);
+    const bool better = rnorm <= c.rbest;
+    const bool stop = rnorm <= theta * c.gnorm;
+    const double b = rr_new / c.rr;
+    const int64_t total = v.p * v.K;
+    const T *pv = (const T *)v.pv, *r = (const T *)v.r;
+    T *s = (T *)v.s, *pb = (T *)v.pbest;
+    if (better || !stop) {
+        for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total;
+             e += (int64_t)gridDim.x * VEC_BLOCK) {
+            const int64_t o = off_of(e, v.K, v.ld);
+            if (better) pb[o] = pv[o];
+            if (!stop) s[o] = (T)((double)r[o] + b * (double)s[o]);
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        CgSlot n;
+        n.rr = rr_new;
+        n.rbest = better ? rnorm : c.rbest;
+        n.gnorm = c.gnorm;
+        n.done = stop ? 1 : 0;
+        n.iters = c.iters + 1;
+        n.flags = c.flags | (stop ? 1 : 0);
+        n.brk = 0;
+        *next = n;
+        if (trace_k) trace_k[1] = rnorm;
+    }
+}
+
+hipError_t launch_cg_step2(int dtype, const CgVecs &v, const CgSlot *cur, CgSlot *next, const double *rr_part, int n_rr,
+                           double theta, double *trace_k, int blocks, hipStream_t st)
+{
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(cg_step2_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, cur, next, rr_part, n_rr, theta,
+                           trace_k);
+    else
+        hipLaunchKernelGGL(cg_step2_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, cur, next, rr_part, n_rr,
+                           theta, trace_k);
+    return hipGetLastError();
+}
+
+}  // namespace ssn

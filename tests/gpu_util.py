@@ -1,0 +1,78 @@
+"""Helpers of the GPU parity tests: build one workload for both sides (oracle on the host, HIP library on
+the device) from the shared seeded generators, and the error measures used in the comparisons."""
+import numpy as np
+import torch
+
+from oracle.oracle import Problem
+from paper_1802_09113_amd import synth
+from paper_1802_09113_amd.binding import Context
+
+TOL = {torch.float64: 1e-10, torch.float32: 1e-4}      # relative, stated by the benchmark spec
+
+
+def np_dtype(dt):
+    return np.float64 if dt == torch.float64 else np.float32
+
+
+def rel_err(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def rel_scalar(a, b):
+    return abs(a - b) / max(abs(b), 1e-300)
+
+
+class Pair:
+    """One workload on both sides.  For fp32 the oracle reads the fp32-rounded data widened to fp64."""
+
+    def __init__(self, data, dtype, scale="mean", ldw=None, ldx=None, lam=None, dev="cuda"):
+        self.dtype = dtype
+        nd = np_dtype(dtype)
+        self.C, self.K = data["C"], data["C"] - 1
+        self.p, self.n = data["p"], data["n"]
+        lam = data["lam"] if lam is None else lam
+        labels = data["labels"]
+        self.labels = labels
+        self.dev = dev
+        lab_d = torch.from_numpy(labels).to(dev)
+        if data["layout"] == "dense":
+            Xr = data["X"].astype(nd)
+            self.oracle = Problem(labels, self.C, lam, X=Xr.astype(np.float64), scale=scale)
+            if ldx is None:
+                Xd = torch.from_numpy(Xr).to(dev)
+            else:
+                buf = torch.full((self.n, ldx), float("nan"), dtype=dtype, device=dev)
+                buf[:, : self.p] = torch.from_numpy(Xr).to(dev)
+                Xd = buf[:, : self.p]
+            self.gpu = Context(lab_d, self.C, lam, X=Xd, scale=scale, ldw=ldw)
+        else:
+            vals = data["vals"].astype(nd)
+            self.oracle = Problem(labels, self.C, lam, csr=(data["rowptr"], data["colidx"], vals.astype(np.float64)),
+                                  p=self.p, scale=scale)
+            rp = torch.from_numpy(data["rowptr"].astype(np.int32)).to(dev)
+            ci = torch.from_numpy(data["colidx"]).to(dev)
+            vd = torch.from_numpy(vals).to(dev)
+            self.gpu = Context(lab_d, self.C, lam, csr=(rp, ci, vd), p=self.p, scale=scale, ldw=ldw)
+        self.ldw = self.gpu.ldw
+
+    def block(self, host):
+        """host p x K array -> (rounded host fp64 copy for the oracle, device p x ldw block)."""
+        r = np.asarray(host).astype(np_dtype(self.dtype))
+        t = torch.full((self.p, self.ldw), float("nan"), dtype=self.dtype, device=self.dev)
+        t[:, : self.K] = torch.from_numpy(r).to(self.dev)
+        return r.astype(np.float64), t
+
+    def host(self, t):
+        return t[:, : self.K].double().cpu().numpy()
+
+    def idx(self, S):
+        return torch.from_numpy(np.ascontiguousarray(S, dtype=np.int32)).to(self.dev)
+
+    def close(self):
+        self.gpu.close()
+
+
+def workload(cfg, n, **kw):
+    return synth.make(cfg, n=n, **kw)

@@ -1,0 +1,40 @@
+"""The C-ABI library loads on a machine without a GPU and exports every symbol include/ssn.h declares."""
+import ctypes
+import os
+import re
+
+from paper_1802_09113_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ssn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ssn_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    assert declared_symbols() == sorted(binding.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    assert os.path.exists(binding.LIB_PATH), "build first: python -m paper_1802_09113_amd.build"
+    L = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared_symbols():
+        assert hasattr(L, name), name
+
+
+def test_status_strings_and_null_arguments_without_a_gpu():
+    L = binding.lib()
+    assert L.ssn_strerror(0) == b"ok"
+    for code in range(-8, 0):
+        assert L.ssn_strerror(code) not in (b"ok", b"unknown status")
+    assert L.ssn_strerror(-99) == b"unknown status"
+    # argument checks come before any device work
+    assert L.ssn_create(None, None) == binding.SSN_E_INVALID_ARG
+    h = ctypes.c_void_p()
+    d = binding.ssn_desc()
+    assert L.ssn_create(ctypes.byref(h), ctypes.byref(d)) == binding.SSN_E_INVALID_ARG
+    assert L.ssn_destroy(None) == binding.SSN_E_INVALID_ARG
+    assert L.ssn_objective(None, None, None) == binding.SSN_E_INVALID_ARG

@@ -1,0 +1,203 @@
+"""GPU parity of the iterations: CG (Alg. 2), line search (Alg. 3), the SSN loop (Alg. 1), and the C-ABI
+error paths.  Iterations are followed step by step against the oracle."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from paper_1802_09113_amd import binding, synth
+from paper_1802_09113_amd.binding import Context, SsnError
+from tests.gpu_util import TOL, Pair, rel_err, rel_scalar, workload
+
+pytestmark = pytest.mark.gpu
+
+F64, F32 = torch.float64, torch.float32
+DTYPES = [F64, F32]
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    return workload(0, 2000)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+@pytest.mark.parametrize("cfg,n", [(0, 2000), (1, 3001), (4, 403)])
+def test_cg_follows_the_oracle_step_by_step(cfg, n, dtype):
+    d = workload(cfg, n)
+    pair = Pair(d, dtype)
+    Wh, Wd = pair.block(synth.probe(pair.p, pair.K, sub=1, scale=0.1))
+    S = synth.sample_rows(n, d["nS"])
+    G_ref, _ = pair.oracle.gradient(Wh)
+    Gh, Gd = pair.block(G_ref)                      # both sides start from the same right-hand side
+    pair.gpu.ssn_hess_prepare(Wd, pair.idx(S))
+    # trajectory tolerance: CG amplifies rounding differences step by step
+    ttol = 1e-8 if dtype == F64 else 5e-3
+    for theta, T in [(1e-4, 10), (0.3, 10), (1e-30, 3)]:
+        print(f"[case] cg cfg={cfg} dtype={dtype} theta={theta} T={T}", flush=True)
+        ref = pair.oracle.cg(Wh, S, Gh, theta, T)
+        out = pair.gpu.ssn_cg(Gd, theta, T)
+        torch.cuda.synchronize()
+        assert out["iters"] == ref["iters"]
+        assert out["flags"] == ref["flags"]
+        np.testing.assert_allclose(out["alpha"], ref["alpha"], rtol=ttol)
+        np.testing.assert_allclose(out["rnorm"], ref["rnorm"], rtol=ttol)
+        np.testing.assert_allclose(out["sHs"], ref["sHs"], rtol=ttol)
+        assert rel_scalar(out["rel_res"], ref["rel_res"]) <= ttol
+        assert rel_err(pair.host(out["p"]), ref["p"]) <= ttol
+        # the returned direction satisfies what it reports: ||H p + g|| / ||g|| = rel_res
+        Hp = pair.gpu.ssn_hess_apply(out["p"])
+        torch.cuda.synchronize()
+        res = np.linalg.norm(pair.host(Hp) + Gh) / np.linalg.norm(Gh)
+        assert rel_scalar(res, out["rel_res"]) <= (1e-7 if dtype == F64 else 2e-2)
+    pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_cg_zero_budget_and_zero_gradient(tiny, dtype):
+    pair = Pair(tiny, dtype)
+    Wh, Wd = pair.block(synth.probe(pair.p, pair.K, sub=1, scale=0.1))
+    S = synth.sample_rows(2000, 100)
+    pair.gpu.ssn_hess_prepare(Wd, pair.idx(S))
+    Gh, Gd = pair.block(pair.oracle.gradient(Wh)[0])
+    out = pair.gpu.ssn_cg(Gd, 1e-4, 0)
+    torch.cuda.synchronize()
+    assert out["iters"] == 0
+    np.testing.assert_array_equal(pair.host(out["p"]), -Gh)
+    Zh, Zd = pair.block(np.zeros((pair.p, pair.K)))
+    out = pair.gpu.ssn_cg(Zd, 1e-4, 5)
+    torch.cuda.synchronize()
+    assert out["iters"] == 0 and np.all(pair.host(out["p"]) == 0)
+    pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_linesearch_matches_oracle(tiny, dtype):
+    pair = Pair(tiny, dtype)
+    Wh, Wd = pair.block(synth.probe(pair.p, pair.K, sub=2, scale=0.5))
+    G_ref, f_ref = pair.oracle.gradient(Wh)
+    Gh, Gd = pair.block(G_ref)
+    f = pair.gpu.ssn_objective(Wd)
+    for stretch, imax in [(1.0, 10), (300.0, 40), (5000.0, 40), (-1.0, 3)]:
+        Ph, Pd = pair.block(-stretch * Gh)
+        print(f"[case] linesearch stretch={stretch} dtype={dtype}", flush=True)
+        ref = pair.oracle.linesearch(Wh, Ph, Gh, f_ref, imax=imax)
+        out = pair.gpu.ssn_linesearch(Wd, Pd, Gd, f, imax=imax)
+        assert out["ok"] == ref["ok"] and out["n_eval"] == ref["n_eval"]
+        assert out["alpha"] == ref["alpha"]
+        assert rel_scalar(out["f_new"], ref["f_new"]) <= TOL[dtype]
+    assert out["ok"] == 0 and out["n_eval"] == 5         # the ascent direction is never accepted
+    pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_ssn_fixed_schedule_tiny_config(tiny, dtype):
+    d = tiny
+    pair = Pair(d, dtype)
+    test = workload(0, 2000, part="test")
+    tpair = Pair(test, dtype)
+    S_all = synth.sample_schedule(2000, d["nS"], d["iters"])
+    W0h, W0d = pair.block(np.zeros((pair.p, pair.K)))
+    Wref, log_ref, done_ref = pair.oracle.ssn(W0h, S_all, theta=1e-4, T=d["T"])
+    recs, done = pair.gpu.ssn_solve(W0d, torch.from_numpy(S_all).cuda(), theta=1e-4, T=d["T"], test=tpair.gpu)
+    torch.cuda.synchronize()
+    assert done == done_ref == d["iters"]
+    f_gpu = np.array([r["f"] for r in recs])
+    ftol = 1e-8 if dtype == F64 else 1e-3
+    np.testing.assert_allclose(f_gpu, log_ref[:, 0], rtol=ftol)
+    assert f_gpu[0] == pytest.approx(np.log(pair.C), rel=TOL[dtype])
+    assert np.all(np.diff(f_gpu) < 0)
+    assert [r["cg_iters"] for r in recs] == [int(x) for x in log_ref[:, 2]]
+    assert [r["alpha"] for r in recs] == list(log_ref[:, 4])
+    assert rel_err(pair.host(W0d), Wref) <= (1e-7 if dtype == F64 else 2e-2)
+    acc_ref = tpair.oracle.accuracy(Wref)
+    assert abs(recs[-1]["test_acc"] - acc_ref) <= 1e-3
+    _, acc_now = tpair.gpu.ssn_predict(W0d)
+    assert acc_now == recs[-1]["test_acc"]
+    pair.close()
+    tpair.close()
+
+
+def test_error_paths(tiny):
+    d = tiny
+    dev = "cuda"
+    X = torch.from_numpy(d["X"]).to(dev)
+    labels = torch.from_numpy(d["labels"]).to(dev)
+    bad = labels.clone()
+    bad[123] = d["C"]
+    with pytest.raises(SsnError) as e:
+        Context(bad, d["C"], 1e-3, X=X)
+    assert e.value.status == binding.SSN_E_BAD_LABEL
+    bad[123] = -1
+    with pytest.raises(SsnError) as e:
+        Context(bad, d["C"], 1e-3, X=X)
+    assert e.value.status == binding.SSN_E_BAD_LABEL
+    with pytest.raises(SsnError) as e:
+        Context(labels, 1, 1e-3, X=X)
+    assert e.value.status == binding.SSN_E_INVALID_ARG
+    with pytest.raises(SsnError) as e:
+        Context(labels, d["C"], -1.0, X=X)
+    assert e.value.status == binding.SSN_E_INVALID_ARG
+    with pytest.raises(SsnError) as e:
+        Context(labels, 40, 1e-3, X=X)           # K = 39 > 32 on the dense path
+    assert e.value.status == binding.SSN_E_UNSUPPORTED
+    ctx = Context(labels, d["C"], 1e-3, X=X)
+    W = torch.zeros((ctx.p, ctx.K), dtype=torch.float64, device=dev)
+    V = torch.ones_like(W)
+    with pytest.raises(SsnError) as e:
+        ctx.ssn_hess_apply(V)
+    assert e.value.status == binding.SSN_E_NOT_PREPARED
+    with pytest.raises(SsnError) as e:
+        ctx.ssn_cg(V, 1e-4, 3)
+    assert e.value.status == binding.SSN_E_NOT_PREPARED
+    for badS in ([0, 5, 2000], [-1, 3]):
+        with pytest.raises(SsnError) as e:
+            ctx.ssn_hess_prepare(W, torch.tensor(badS, dtype=torch.int32, device=dev))
+        assert e.value.status == binding.SSN_E_BAD_INDEX
+    # a failed prepare leaves the context unprepared, a good one repairs it
+    with pytest.raises(SsnError):
+        ctx.ssn_hess_apply(V)
+    ctx.ssn_hess_prepare(W, torch.tensor([1, 2, 3], dtype=torch.int32, device=dev))
+    ctx.ssn_hess_apply(V)
+    # NaN weights surface as a status, not as a silent NaN
+    Wn = W.clone()
+    Wn[0, 0] = float("nan")
+    with pytest.raises(SsnError) as e:
+        ctx.ssn_objective(Wn)
+    assert e.value.status == binding.SSN_E_NONFINITE
+    L = binding.lib()
+    assert L.ssn_objective(None, None, None) == binding.SSN_E_INVALID_ARG
+    assert L.ssn_destroy(None) == binding.SSN_E_INVALID_ARG
+    ctx.close()
+    # CSR: column index out of range, broken rowptr
+    rp = torch.tensor([0, 2, 3], dtype=torch.int32, device=dev)
+    ci = torch.tensor([0, 7, 2], dtype=torch.int32, device=dev)
+    vals = torch.ones(3, dtype=torch.float64, device=dev)
+    lab2 = torch.tensor([0, 1], dtype=torch.int32, device=dev)
+    with pytest.raises(SsnError) as e:
+        Context(lab2, 2, 0.0, csr=(rp, ci, vals), p=5)
+    assert e.value.status == binding.SSN_E_BAD_INDEX
+    rp_bad = torch.tensor([0, 3, 2], dtype=torch.int32, device=dev)
+    with pytest.raises(SsnError) as e:
+        Context(lab2, 2, 0.0, csr=(rp_bad, ci, vals), p=8)
+    assert e.value.status == binding.SSN_E_INVALID_ARG
+    ok = Context(lab2, 2, 0.0, csr=(rp, ci, vals), p=8)
+    ok.close()
+
+
+def test_results_are_deterministic_on_the_dense_path(tiny):
+    pair = Pair(tiny, F64)
+    Wh, Wd = pair.block(synth.probe(pair.p, pair.K, sub=1, scale=0.2))
+    Vh, Vd = pair.block(synth.probe(pair.p, pair.K, sub=2))
+    Sd = pair.idx(synth.sample_rows(2000, 100))
+    runs = []
+    for _ in range(2):
+        f = pair.gpu.ssn_objective(Wd)
+        G, _ = pair.gpu.ssn_gradient(Wd)
+        HV = pair.gpu.ssn_hessvec(Wd, Sd, Vd)
+        torch.cuda.synchronize()
+        runs.append((f, G.clone(), HV.clone()))
+    assert runs[0][0] == runs[1][0]
+    assert torch.equal(runs[0][1][:, : pair.K], runs[1][1][:, : pair.K])
+    assert torch.equal(runs[0][2][:, : pair.K], runs[1][2][:, : pair.K])
+    pair.close()
