@@ -9,7 +9,8 @@
 //                 finalize kernel adds in a fixed order (deterministic, no atomics).
 //
 // MFMA tile used throughout: v_mfma_{f32,f64}_16x16x4 -- D(16x16) += A(16x4) * B(4x16), wave64:
-//   lane l supplies A[l%16][l/16] and B[l/16][l%16]; lane l holds D[4*(l/16)+v][l%16], v = 0..3.
+//   lane l supplies A[l%16][l/16] and B[l/16][l%16]; accumulator element v (0..3) of lane l is
+//   D[4*(l/16)+v][l%16] for the f32 instruction and D[4*v+l/16][l%16] for the f64 one (d_row below).
 #include "ssn_internal.h"
 
 #include <limits>
@@ -28,6 +29,11 @@ __device__ __forceinline__ V4<float>::type mfma16(float a, float b, V4<float>::t
 {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
+
+// row of the 16x16 output tile held in accumulator element v of a lane in 16-lane group g
+template <typename T> __device__ __forceinline__ int d_row(int g, int v);
+template <> __device__ __forceinline__ int d_row<float>(int g, int v) { return 4 * g + v; }
+template <> __device__ __forceinline__ int d_row<double>(int g, int v) { return 4 * v + g; }
 
 template <typename T, int VEC> struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; };
 
@@ -63,7 +69,7 @@ __device__ __forceinline__ int row16_min(int x)
 }
 
 // Per-row work on a 16-row block of margins held in MFMA accumulator layout:
-// acc[nb][v] = z(row 4*(lane/16)+v, class 16*nb + lane%16).
+// acc[nb][v] = z(row d_row<T>(lane/16, v), class 16*nb + lane%16).
 template <typename T, int NB, int MODE>
 __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[NB], const RowsArgs &a,
                                              int64_t rb, int lane, double &loss, int &hits)
@@ -73,7 +79,7 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
     const T NEG = -std::numeric_limits<T>::infinity();
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-        const int64_t sv = rb * 16 + 4 * g + v;
+        const int64_t sv = rb * 16 + d_row<T>(g, v);
         const bool valid = sv < a.nrows;
         const int64_t svc = valid ? sv : a.nrows - 1;
         T z[NB];
@@ -313,7 +319,7 @@ __global__ __launch_bounds__(256) void dense_xtu_kernel(XtuArgs a)
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int64_t f = f0 + ld * 16 * VEC + VEC * (4 * g + v) + m;
+                    const int64_t f = f0 + ld * 16 * VEC + VEC * d_row<T>(g, v) + m;
                     const int c = nb * 16 + q;
                     if (f < p && c < K) part[f * K + c] = acc[ld * VEC + m][nb][v];
                 }
