@@ -70,9 +70,12 @@ __device__ __forceinline__ int row16_min(int x)
 
 // Per-row work on a 16-row block of margins held in MFMA accumulator layout:
 // acc[nb][v] = z(row d_row<T>(lane/16, v), class 16*nb + lane%16).
-template <typename T, int NB, int MODE>
+// TOREG: U (ROW_GRAD / ROW_APPLY) is returned in `uout` in the same accumulator layout instead of being
+// stored; `primary` is false for waves that only need U (they skip loss, hit counts and stores).
+template <typename T, int NB, int MODE, bool TOREG = false>
 __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[NB], const RowsArgs &a,
-                                             int64_t rb, int lane, double &loss, int &hits)
+                                             int64_t rb, int lane, double &loss, int &hits,
+                                             typename V4<T>::type *uout = nullptr, bool primary = true)
 {
     const int q = lane & 15, g = lane >> 4;
     const int K = a.K;
@@ -101,7 +104,7 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
                 if (cv[nb] && z[nb] == zmax) cand = min(cand, nb * 16 + q);
             cand = row16_min(cand);
             const int pr = (T(0) > zmax) ? K : cand;     // the reference class wins only strictly
-            if (valid && q == 0) {
+            if (primary && valid && q == 0) {
                 if (a.pred) a.pred[sv] = pr;
                 hits += (pr == lab);
             }
@@ -120,8 +123,11 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
             t = row16_sum(t);
             T *U = (T *)a.UP;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                U[sv * a.KP + nb * 16 + q] = valid ? (pin[nb] * z[nb] - pin[nb] * t) : T(0);
+            for (int nb = 0; nb < NB; ++nb) {
+                const T u = valid ? (pin[nb] * z[nb] - pin[nb] * t) : T(0);
+                if constexpr (TOREG) uout[nb][v] = u;
+                else U[sv * a.KP + nb * 16 + q] = u;
+            }
             continue;
         }
         // eq. (8), (9): M = max{0, z}, alpha = e^{-M} + sum_c e^{z_c - M}
@@ -139,7 +145,7 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
             T *P = (T *)a.UP;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
-                P[sv * a.KP + nb * 16 + q] = valid ? e[nb] / alpha : T(0);
+                if (primary) P[sv * a.KP + nb * 16 + q] = valid ? e[nb] / alpha : T(0);
             continue;
         }
         // ROW_OBJ / ROW_GRAD: eqs. (14)-(17)
@@ -150,13 +156,15 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
         for (int nb = 0; nb < NB; ++nb)
             lin += (cv[nb] && (nb * 16 + q) == lab) ? z[nb] : T(0);
         lin = row16_sum(lin);
-        if (valid && q == 0) loss += (double)Mx + (double)t_log(alpha) - (double)lin;
+        if (primary && valid && q == 0) loss += (double)Mx + (double)t_log(alpha) - (double)lin;
         if constexpr (MODE == ROW_GRAD) {
             T *U = (T *)a.UP;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const T ind = ((nb * 16 + q) == lab) ? T(1) : T(0);
-                U[sv * a.KP + nb * 16 + q] = (valid && cv[nb]) ? (e[nb] / alpha - ind) : T(0);
+                const T u = (valid && cv[nb]) ? (e[nb] / alpha - ind) : T(0);
+                if constexpr (TOREG) uout[nb][v] = u;
+                else U[sv * a.KP + nb * 16 + q] = u;
             }
         }
     }
@@ -397,6 +405,234 @@ template <typename T> static hipError_t xtu_dispatch(const XtuArgs &a, hipStream
 hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st)
 {
     return dtype == SSN_F32 ? xtu_dispatch<float>(a, st) : xtu_dispatch<double>(a, st);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fused one-pass kernel: margins, per-row epilogue and (for ROW_GRAD / ROW_APPLY) the transposed
+// product, reading every row of X exactly once (eqs. (10)-(13) with both products of Alg. 7 in one
+// sweep; same for Alg. 6).
+//
+// A workgroup owns whole 16-row blocks; its waves split the features, 16*NT per wave.  Per row block:
+//   1. every lane already holds its part of the wave's 16 x (16*NT) tile of X in the A-operand layout
+//      (prefetched into registers while the previous block was processed);
+//   2. phase A: Z_partial (16x16) += X_tile * W_slice, W operands from an LDS copy of M;
+//   3. the partial margins of the waves are added through LDS in a fixed order (two barriers);
+//   4. every wave runs the epilogue on the full margins and keeps U in accumulator layout, which is
+//      exactly the B-operand layout of the transposed product;
+//   5. phase C: the wave's X tile is transposed through a wave-private LDS scratch (rows become the
+//      contraction index) and G_slice (16*NT x 16) += X_tile^T * U accumulates in registers.
+// At the end each workgroup writes its p x K partial; the finalize kernel adds them in a fixed order.
+template <typename T, int MODE, int NT>
+__global__ __launch_bounds__(1024) void dense_fused_kernel(RowsArgs a)
+{
+    if (a.skip && *a.skip) return;
+    typedef typename V4<T>::type v4;
+    constexpr int VEC = 16 / sizeof(T);
+    typedef Pack<T, VEC> pack;
+    constexpr int FW = 16 * NT;              // features per wave
+    constexpr int NLD = FW / (4 * VEC);      // vector loads per lane per row block
+    constexpr int SBF = 16 * VEC;            // features per transposition sub-block
+    constexpr int NSB = FW / SBF;
+    constexpr int STR = SBF + VEC;           // scratch row stride (elements): 16 bytes of padding
+    constexpr bool HAS_C = (MODE == ROW_GRAD || MODE == ROW_APPLY);
+    static_assert(NT % VEC == 0, "a wave's feature slice must be a whole number of transposition sub-blocks");
+
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, nw = blockDim.x >> 6;
+    const int q = lane & 15, g = lane >> 4;
+    const int K = a.K;
+    const int64_t p = a.p;
+    const int p_pad = nw * FW;
+    T *wl = (T *)smem_raw;                                   // p_pad x K copy of M, zero beyond p
+    T *zpart = wl + (((size_t)p_pad * K + 1) & ~(size_t)1);  // nw x 4 x 64 partial margins
+    T *zfull = zpart + (size_t)nw * 256;                     // 4 x 64 summed margins
+    T *scr = zfull + 256 + (size_t)w * 16 * STR;             // wave-private transposition scratch
+
+    {
+        const T *M = (const T *)a.M;
+        for (int idx = tid; idx < p_pad * K; idx += blockDim.x) {
+            const int f = idx / K, c = idx - f * K;
+            wl[idx] = (f < p) ? M[(int64_t)f * a.ldm + c] : T(0);
+        }
+    }
+    __syncthreads();
+
+    const T *X = (const T *)a.X;
+    const int fs = w * FW;
+    const int qc = (q < K) ? q : K - 1;
+    const bool cvalid = q < K;
+    const int64_t nblk = (a.nrows + 15) / 16;
+
+    auto load_block = [&](int64_t rb, pack(&x)[NLD]) {
+        int64_t si = rb * 16 + q;
+        if (si >= a.nrows) si = a.nrows - 1;
+        const int64_t xr = a.S ? a.S[si] : si;
+        const T *xrow = X + xr * a.ldx;
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int64_t f = fs + 4 * VEC * j + VEC * g;
+            if (f + VEC <= p) {
+                x[j] = *(const pack *)(xrow + f);
+            } else {
+#pragma unroll
+                for (int m = 0; m < VEC; ++m) x[j].v[m] = (f + m < p) ? xrow[f + m] : T(0);
+            }
+        }
+    };
+
+    v4 G[HAS_C ? NT : 1];
+#pragma unroll
+    for (int t = 0; t < (HAS_C ? NT : 1); ++t) G[t] = v4{0, 0, 0, 0};
+    double loss = 0.0;
+    int hits = 0;
+
+    pack xn[NLD];
+    int64_t rb = blockIdx.x;
+    if (rb < nblk) load_block(rb, xn);
+    for (; rb < nblk; rb += gridDim.x) {
+        pack xc[NLD];
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) xc[j] = xn[j];
+        const int64_t rbn = rb + gridDim.x;
+        if (rbn < nblk) load_block(rbn, xn);
+
+        // phase A: two accumulators break the dependent MFMA chain
+        v4 z0 = v4{0, 0, 0, 0}, z1 = v4{0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < NLD; ++j)
+#pragma unroll
+            for (int m = 0; m < VEC; ++m) {
+                const int f = fs + 4 * VEC * j + VEC * g + m;
+                const T bw = wl[f * K + qc];
+                const T b = cvalid ? bw : T(0);
+                if ((j * VEC + m) & 1) z1 = mfma16(xc[j].v[m], b, z1);
+                else z0 = mfma16(xc[j].v[m], b, z0);
+            }
+        v4 z[1];
+        z[0] = z0 + z1;
+        if (nw > 1) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) zpart[(w * 4 + v) * 64 + lane] = z[0][v];
+            __syncthreads();
+            for (int slot = tid; slot < 256; slot += blockDim.x) {
+                T s = 0;
+                for (int ww = 0; ww < nw; ++ww) s += zpart[ww * 256 + slot];
+                zfull[slot] = s;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < 4; ++v) z[0][v] = zfull[v * 64 + lane];
+        }
+
+        v4 u[1];
+        u[0] = v4{0, 0, 0, 0};
+        row_epilogue<T, 1, MODE, true>(z, a, rb, lane, loss, hits, u, w == 0);
+
+        if constexpr (HAS_C) {
+#pragma unroll
+            for (int h = 0; h < NSB; ++h) {
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    *(pack *)(scr + q * STR + 4 * VEC * jj + VEC * g) = xc[4 * h + jj];
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const pack c = *(const pack *)(scr + d_row<T>(g, i) * STR + VEC * q);
+#pragma unroll
+                    for (int m = 0; m < VEC; ++m) G[h * VEC + m] = mfma16(c.v[m], u[0][i], G[h * VEC + m]);
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    }
+
+    if constexpr (HAS_C) {
+        T *part = (T *)a.part + (int64_t)blockIdx.x * p * K;
+#pragma unroll
+        for (int h = 0; h < NSB; ++h)
+#pragma unroll
+            for (int m = 0; m < VEC; ++m)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int64_t f = fs + h * SBF + VEC * d_row<T>(g, v) + m;
+                    if (f < p && q < K) part[f * K + q] = G[h * VEC + m][v];
+                }
+    }
+    if (w == 0) {
+        if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD) {
+            for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off);
+            if (lane == 0) a.loss_part[blockIdx.x] = loss;
+        } else if constexpr (MODE == ROW_PRED) {
+            for (int off = 32; off > 0; off >>= 1) hits += __shfl_xor(hits, off);
+            if (lane == 0) a.hit_part[blockIdx.x] = hits;
+        }
+    }
+}
+
+template <typename T> static size_t fused_lds_bytes(int nw, int K, bool has_c)
+{
+    constexpr int VEC = 16 / sizeof(T);
+    constexpr int NT = 4, FW = 16 * NT, STR = 16 * VEC + VEC;
+    size_t elems = (((size_t)nw * FW * K + 1) & ~(size_t)1) + (size_t)nw * 256 + 256;
+    if (has_c) elems += (size_t)nw * 16 * STR;
+    return elems * sizeof(T);
+}
+
+// Can the one-pass kernel serve this shape?  (one 16-column class tile, 16-byte aligned rows,
+// at most 16 waves of 64 features, LDS within the 160 KB of a gfx950 compute unit)
+bool dense_fused_supported(int dtype, const RowsArgs &a)
+{
+    if (a.K > 16) return false;
+    const int nw = (int)((a.p + 63) / 64);
+    if (nw > 16) return false;
+    if (dtype == SSN_F32) return vec_ok<float>(a.X, a.ldx) && fused_lds_bytes<float>(nw, a.K, true) <= 160 * 1024;
+    return vec_ok<double>(a.X, a.ldx) && fused_lds_bytes<double>(nw, a.K, true) <= 160 * 1024;
+}
+
+int dense_fused_grid(const RowsArgs &a, int num_cus)
+{
+    const int nw = (int)((a.p + 63) / 64);
+    int per_cu = 16 / nw;
+    if (per_cu < 1) per_cu = 1;
+    if (per_cu > 8) per_cu = 8;
+    const int64_t nblk = (a.nrows + 15) / 16;
+    int64_t grid = (int64_t)num_cus * per_cu;
+    if (grid > nblk) grid = nblk;
+    if (grid < 1) grid = 1;
+    return (int)grid;
+}
+
+template <typename T, int MODE> static hipError_t fused_launch_mode(const RowsArgs &a, int grid, hipStream_t st)
+{
+    const int nw = (int)((a.p + 63) / 64);
+    constexpr bool has_c = (MODE == ROW_GRAD || MODE == ROW_APPLY);
+    const size_t lds = fused_lds_bytes<T>(nw, a.K, has_c);
+    auto kern = dense_fused_kernel<T, MODE, 4>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * nw), lds, st, a);
+    return hipGetLastError();
+}
+
+template <typename T> static hipError_t fused_dispatch(const RowsArgs &a, int grid, hipStream_t st)
+{
+    switch (a.mode) {
+    case ROW_OBJ: return fused_launch_mode<T, ROW_OBJ>(a, grid, st);
+    case ROW_GRAD: return fused_launch_mode<T, ROW_GRAD>(a, grid, st);
+    case ROW_PREP: return fused_launch_mode<T, ROW_PREP>(a, grid, st);
+    case ROW_APPLY: return fused_launch_mode<T, ROW_APPLY>(a, grid, st);
+    case ROW_PRED: return fused_launch_mode<T, ROW_PRED>(a, grid, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// Launch the one-pass kernel on `grid` workgroups; ROW_GRAD / ROW_APPLY leave `grid` partials in a.part,
+// ROW_OBJ / ROW_GRAD `grid` loss partials, ROW_PRED `grid` hit partials.
+hipError_t launch_dense_fused(int dtype, const RowsArgs &a, int grid, hipStream_t st)
+{
+    return dtype == SSN_F32 ? fused_dispatch<float>(a, grid, st) : fused_dispatch<double>(a, grid, st);
 }
 
 }  // namespace ssn

@@ -45,6 +45,7 @@ struct RowsArgs {
     int32_t *hit_part;   // one partial per wave (PRED)
     int32_t mode;
     const int32_t *skip; // nullable device flag: non-zero -> the launch does nothing
+    void *part;          // one-pass kernel only: per-workgroup p x K partial sums of X^T U
 };
 
 // Arguments of the transposed product: part[chunk] = X_rows(chunk)^T * U(chunk).
@@ -93,6 +94,9 @@ int finalize_blocks(int64_t p, int K);
 // ---- launchers (dense_mfma.hip / csr.hip / vecops.hip) ---------------------------------
 hipError_t launch_dense_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
 hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st);
+bool dense_fused_supported(int dtype, const RowsArgs &a);
+int dense_fused_grid(const RowsArgs &a, int num_cus);
+hipError_t launch_dense_fused(int dtype, const RowsArgs &a, int grid, hipStream_t st);
 hipError_t launch_csr_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
 hipError_t launch_csr_scatter(int dtype, const XtuArgs &a, double scale, void *out, int64_t ldo, hipStream_t st);
 hipError_t launch_finalize(int dtype, const FinArgs &a, int blocks, hipStream_t st);
