@@ -22,7 +22,7 @@ SSN_E_ALLOC, SSN_E_HIP, SSN_E_NONFINITE, SSN_E_UNSUPPORTED = -5, -6, -7, -8
 EXPORTS = [
     "ssn_strerror", "ssn_last_error", "ssn_create", "ssn_destroy", "ssn_set_stream", "ssn_objective",
     "ssn_gradient", "ssn_hess_prepare", "ssn_hess_apply", "ssn_hessvec", "ssn_cg", "ssn_linesearch",
-    "ssn_predict", "ssn_solve", "ssn_axpy", "ssn_time_kernel",
+    "ssn_predict", "ssn_solve", "ssn_axpy", "ssn_time_kernel", "ssn_dense_path",
 ]
 
 
@@ -93,6 +93,7 @@ def lib():
         L.ssn_solve.argtypes = [vp, vp, ctypes.POINTER(ssn_params), ctypes.POINTER(ssn_iter_record), ctypes.c_int32, ip]
         L.ssn_axpy.argtypes = [vp, ctypes.c_double, vp, vp]
         L.ssn_time_kernel.argtypes = [vp, ctypes.c_int32, vp, ctypes.c_int32, dp]
+        L.ssn_dense_path.argtypes = [vp]
         for name in EXPORTS:
             fn = getattr(L, name)
             if fn.restype is not ctypes.c_char_p:
@@ -227,6 +228,9 @@ class Context:
 
     def ssn_axpy(self, alpha, P, W):
         self._check(lib().ssn_axpy(self._h, alpha, self._blk(P), self._blk(W)))
+
+    def ssn_dense_path(self):
+        return lib().ssn_dense_path(self._h)
 
     def ssn_time_kernel(self, which, M, reps):
         ms = ctypes.c_double()

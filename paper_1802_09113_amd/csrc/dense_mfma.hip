@@ -71,17 +71,22 @@ __device__ __forceinline__ int row16_min(int x)
 // Per-row work on a 16-row block of margins held in MFMA accumulator layout:
 // acc[nb][v] = z(row d_row<T>(lane/16, v), class 16*nb + lane%16).
 // TOREG: U (ROW_GRAD / ROW_APPLY) is returned in `uout` in the same accumulator layout instead of being
-// stored; `primary` is false for waves that only need U (they skip loss, hit counts and stores).
+// stored.  vmask selects which of the 4 accumulator elements (row groups) this wave works on.
 template <typename T, int NB, int MODE, bool TOREG = false>
 __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[NB], const RowsArgs &a,
                                              int64_t rb, int lane, double &loss, int &hits,
-                                             typename V4<T>::type *uout = nullptr, bool primary = true)
+                                             typename V4<T>::type *uout = nullptr, int vmask = 15,
+                                             const int *lab_pre = nullptr, const T *pin_pre = nullptr)
 {
+    // lab_pre / pin_pre (one-pass kernel, NB == 1): label and probability of each accumulator element,
+    // loaded by the caller ahead of its X prefetch so that waiting for them does not drain that prefetch
+    constexpr bool primary = true;
     const int q = lane & 15, g = lane >> 4;
     const int K = a.K;
     const T NEG = -std::numeric_limits<T>::infinity();
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
+        if (!((vmask >> v) & 1)) continue;
         const int64_t sv = rb * 16 + d_row<T>(g, v);
         const bool valid = sv < a.nrows;
         const int64_t svc = valid ? sv : a.nrows - 1;
@@ -96,8 +101,9 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
         }
         zmax = row16_max(zmax);
         if constexpr (MODE == ROW_PRED) {
-            const int64_t xr = a.S ? a.S[svc] : svc;
-            const int lab = a.labels[xr];
+            int lab;
+            if (lab_pre) lab = lab_pre[v];
+            else lab = a.labels[a.S ? a.S[svc] : svc];
             int cand = 0x7fffffff;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
@@ -117,7 +123,7 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
             T t = 0;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                pin[nb] = Pin[svc * a.KP + nb * 16 + q];      // zero in padded columns
+                pin[nb] = pin_pre ? pin_pre[v] : Pin[svc * a.KP + nb * 16 + q];      // zero in padded columns
                 t += pin[nb] * z[nb];
             }
             t = row16_sum(t);
@@ -149,8 +155,9 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
             continue;
         }
         // ROW_OBJ / ROW_GRAD: eqs. (14)-(17)
-        const int64_t xr = a.S ? a.S[svc] : svc;
-        const int lab = a.labels[xr];
+        int lab;
+        if (lab_pre) lab = lab_pre[v];
+        else lab = a.labels[a.S ? a.S[svc] : svc];
         T lin = 0;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
@@ -412,73 +419,100 @@ hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st)
 // product, reading every row of X exactly once (eqs. (10)-(13) with both products of Alg. 7 in one
 // sweep; same for Alg. 6).
 //
-// A workgroup owns whole 16-row blocks; its waves split the features, 16*NT per wave.  Per row block:
-//   1. every lane already holds its part of the wave's 16 x (16*NT) tile of X in the A-operand layout
+// A workgroup owns whole 16-row blocks; its waves split the features into slices of a.fw features
+// (a.fw <= 16*NT, a multiple of the vector width).  Per row block:
+//   1. every lane already holds its part of the wave's 16 x fw tile of X in the A-operand layout
 //      (prefetched into registers while the previous block was processed);
 //   2. phase A: Z_partial (16x16) += X_tile * W_slice, W operands from an LDS copy of M;
 //   3. the partial margins of the waves are added through LDS in a fixed order (two barriers);
 //   4. every wave runs the epilogue on the full margins and keeps U in accumulator layout, which is
 //      exactly the B-operand layout of the transposed product;
 //   5. phase C: the wave's X tile is transposed through a wave-private LDS scratch (rows become the
-//      contraction index) and G_slice (16*NT x 16) += X_tile^T * U accumulates in registers.
+//      contraction index) and G_slice (fw x 16) += X_tile^T * U accumulates in registers.
 // At the end each workgroup writes its p x K partial; the finalize kernel adds them in a fixed order.
-template <typename T, int MODE, int NT>
-__global__ __launch_bounds__(1024) void dense_fused_kernel(RowsArgs a)
+template <typename T, int MODE, int NLD, int NSB>
+__global__ __launch_bounds__(512) void dense_fused_kernel(RowsArgs a)
 {
     if (a.skip && *a.skip) return;
     typedef typename V4<T>::type v4;
     constexpr int VEC = 16 / sizeof(T);
     typedef Pack<T, VEC> pack;
-    constexpr int FW = 16 * NT;              // features per wave
-    constexpr int NLD = FW / (4 * VEC);      // vector loads per lane per row block
+    // NLD: vector loads per lane per row block the instantiation can hold (LF features each);
+    // NSB: transposition sub-blocks (SBF features each) it can hold.  a.fw <= min(NLD*LF, NSB*SBF).
+    constexpr int LF = 4 * VEC;              // features covered by one vector load of the wave
     constexpr int SBF = 16 * VEC;            // features per transposition sub-block
-    constexpr int NSB = FW / SBF;
+    constexpr int NT = NSB * VEC;            // 16-feature output tiles of the transposed product
     constexpr int STR = SBF + VEC;           // scratch row stride (elements): 16 bytes of padding
     constexpr bool HAS_C = (MODE == ROW_GRAD || MODE == ROW_APPLY);
-    static_assert(NT % VEC == 0, "a wave's feature slice must be a whole number of transposition sub-blocks");
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, nw = blockDim.x >> 6;
     const int q = lane & 15, g = lane >> 4;
     const int K = a.K;
     const int64_t p = a.p;
-    const int p_pad = nw * FW;
-    T *wl = (T *)smem_raw;                                   // p_pad x K copy of M, zero beyond p
-    T *zpart = wl + (((size_t)p_pad * K + 1) & ~(size_t)1);  // nw x 4 x 64 partial margins
-    T *zfull = zpart + (size_t)nw * 256;                     // 4 x 64 summed margins
+    const int fw = a.fw;
+    const int nld = (fw + LF - 1) / LF;                      // loads this launch really needs
+    const int nsb = (fw + SBF - 1) / SBF;
+    const int wrows = (nw - 1) * fw + nld * LF;              // rows of the LDS copy of M (zero beyond p)
+    T *wl = (T *)smem_raw;
+    T *zpart = wl + ((size_t)wrows * K + VEC - 1) / VEC * VEC;   // nw x 4 x 64 partial margins (16-byte aligned)
+    T *zfull = zpart + (size_t)nw * 256 * (HAS_C ? 1 : 2);   // U of the block (modes with a transposed product)
     T *scr = zfull + 256 + (size_t)w * 16 * STR;             // wave-private transposition scratch
 
     {
         const T *M = (const T *)a.M;
-        for (int idx = tid; idx < p_pad * K; idx += blockDim.x) {
-            const int f = idx / K, c = idx - f * K;
-            wl[idx] = (f < p) ? M[(int64_t)f * a.ldm + c] : T(0);
+        // batches of 8 independent loads per thread, so the copy costs one or two memory round trips
+        const int total = wrows * K;
+        for (int base = 0; base < total; base += 8 * (int)blockDim.x) {
+            T tmp[8];
+#pragma unroll
+            for (int uu = 0; uu < 8; ++uu) {
+                const int idx = base + uu * (int)blockDim.x + tid;
+                const int f = idx / K, c = idx - f * K;
+                tmp[uu] = (idx < total && f < p) ? M[(int64_t)f * a.ldm + c] : T(0);
+            }
+#pragma unroll
+            for (int uu = 0; uu < 8; ++uu) {
+                const int idx = base + uu * (int)blockDim.x + tid;
+                if (idx < total) wl[idx] = tmp[uu];
+            }
         }
     }
     __syncthreads();
 
     const T *X = (const T *)a.X;
-    const int fs = w * FW;
+    const int fs = w * fw;
+    const int64_t fend = (fs + fw < p) ? (int64_t)(fs + fw) : p;   // features [fs, fend) belong to this wave
     const int qc = (q < K) ? q : K - 1;
     const bool cvalid = q < K;
     const int64_t nblk = (a.nrows + 15) / 16;
 
-    auto load_block = [&](int64_t rb, pack(&x)[NLD]) {
+    // sample position -> data row of the lane's A-operand row of block rb
+    auto block_row = [&](int64_t rb) -> int64_t {
         int64_t si = rb * 16 + q;
         if (si >= a.nrows) si = a.nrows - 1;
-        const int64_t xr = a.S ? a.S[si] : si;
+        return a.S ? (int64_t)a.S[si] : si;
+    };
+    auto load_block = [&](int64_t xr, pack(&x)[NLD]) {
         const T *xrow = X + xr * a.ldx;
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
-            const int64_t f = fs + 4 * VEC * j + VEC * g;
-            if (f + VEC <= p) {
-                x[j] = *(const pack *)(xrow + f);
-            } else {
+            if (j < nld) {
+                const int64_t f = fs + LF * j + VEC * g;
+                if (f + VEC <= fend) {
+                    x[j] = *(const pack *)(xrow + f);
+                } else {
 #pragma unroll
-                for (int m = 0; m < VEC; ++m) x[j].v[m] = (f + m < p) ? xrow[f + m] : T(0);
+                    for (int m = 0; m < VEC; ++m) x[j].v[m] = (f + m < fend) ? xrow[f + m] : T(0);
+                }
             }
         }
     };
+    // accumulator elements (row groups) whose per-row work this wave does
+    int vmask = 0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+        if (nw == 1 || v % nw == w) vmask |= 1 << v;
 
     v4 G[HAS_C ? NT : 1];
 #pragma unroll
@@ -486,62 +520,101 @@ __global__ __launch_bounds__(1024) void dense_fused_kernel(RowsArgs a)
     double loss = 0.0;
     int hits = 0;
 
+    int it = 0;
     pack xn[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) xn[j] = pack{};          // loads beyond the slice stay zero
     int64_t rb = blockIdx.x;
-    if (rb < nblk) load_block(rb, xn);
+    if (rb < nblk) load_block(block_row(rb), xn);
     for (; rb < nblk; rb += gridDim.x) {
         pack xc[NLD];
 #pragma unroll
         for (int j = 0; j < NLD; ++j) xc[j] = xn[j];
+        // Small loads first (row index of the next block, labels / probabilities of this block), the X
+        // prefetch after them: the memory counter retires in order, so the epilogue's wait for its inputs
+        // then leaves the prefetch in flight.
         const int64_t rbn = rb + gridDim.x;
-        if (rbn < nblk) load_block(rbn, xn);
+        const int64_t xr_next = (rbn < nblk) ? block_row(rbn) : 0;
+        int lab_pre[4];
+        T pin_pre[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            lab_pre[v] = 0;
+            pin_pre[v] = T(0);
+            if ((vmask >> v) & 1) {
+                int64_t sv = rb * 16 + d_row<T>(g, v);
+                if (sv >= a.nrows) sv = a.nrows - 1;
+                if constexpr (MODE == ROW_APPLY) pin_pre[v] = ((const T *)a.Pin)[sv * a.KP + q];
+                else if constexpr (MODE != ROW_PREP) lab_pre[v] = a.labels[a.S ? (int64_t)a.S[sv] : sv];
+            }
+        }
+        if (rbn < nblk) load_block(xr_next, xn);
 
         // phase A: two accumulators break the dependent MFMA chain
         v4 z0 = v4{0, 0, 0, 0}, z1 = v4{0, 0, 0, 0};
 #pragma unroll
-        for (int j = 0; j < NLD; ++j)
+        for (int j = 0; j < NLD; ++j) {
+            if (j < nld) {
 #pragma unroll
-            for (int m = 0; m < VEC; ++m) {
-                const int f = fs + 4 * VEC * j + VEC * g + m;
-                const T bw = wl[f * K + qc];
-                const T b = cvalid ? bw : T(0);
-                if ((j * VEC + m) & 1) z1 = mfma16(xc[j].v[m], b, z1);
-                else z0 = mfma16(xc[j].v[m], b, z0);
+                for (int m = 0; m < VEC; ++m) {
+                    const int f = fs + LF * j + VEC * g + m;
+                    const T bw = wl[f * K + qc];
+                    const T b = cvalid ? bw : T(0);
+                    if ((j * VEC + m) & 1) z1 = mfma16(xc[j].v[m], b, z1);
+                    else z0 = mfma16(xc[j].v[m], b, z0);
+                }
             }
-        v4 z[1];
-        z[0] = z0 + z1;
-        if (nw > 1) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) zpart[(w * 4 + v) * 64 + lane] = z[0][v];
-            __syncthreads();
-            for (int slot = tid; slot < 256; slot += blockDim.x) {
-                T s = 0;
-                for (int ww = 0; ww < nw; ++ww) s += zpart[ww * 256 + slot];
-                zfull[slot] = s;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int v = 0; v < 4; ++v) z[0][v] = zfull[v * 64 + lane];
+            if ((j & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // keep the W operand reads from piling up
         }
-
-        v4 u[1];
+        v4 z[1], u[1];
+        z[0] = z0 + z1;
         u[0] = v4{0, 0, 0, 0};
-        row_epilogue<T, 1, MODE, true>(z, a, rb, lane, loss, hits, u, w == 0);
+        if (nw == 1) {
+            row_epilogue<T, 1, MODE, true>(z, a, rb, lane, loss, hits, u, 15, lab_pre, pin_pre);
+        } else {
+            // partial margins -> LDS; wave w sums accumulator element v = w (, w+nw, ..) over the waves in a
+            // fixed order and runs the per-row work for it, so the epilogue is done once per row block
+            T *zp = zpart + (HAS_C ? 0 : (size_t)(it & 1) * nw * 256);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) zp[(w * 4 + v) * 64 + lane] = z[0][v];
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                if ((vmask >> v) & 1) {
+                    T sacc = 0;
+                    for (int ww = 0; ww < nw; ++ww) sacc += zp[(ww * 4 + v) * 64 + lane];
+                    z[0][v] = sacc;
+                }
+            }
+            if (vmask) row_epilogue<T, 1, MODE, true>(z, a, rb, lane, loss, hits, u, vmask, lab_pre, pin_pre);
+            if constexpr (HAS_C) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if ((vmask >> v) & 1) zfull[v * 64 + lane] = u[0][v];
+                __syncthreads();
+#pragma unroll
+                for (int v = 0; v < 4; ++v) u[0][v] = zfull[v * 64 + lane];
+            }
+        }
+        ++it;
 
         if constexpr (HAS_C) {
 #pragma unroll
             for (int h = 0; h < NSB; ++h) {
+                if (h < nsb) {
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
-                    *(pack *)(scr + q * STR + 4 * VEC * jj + VEC * g) = xc[4 * h + jj];
-                __builtin_amdgcn_wave_barrier();
+                    for (int jj = 0; jj < 4; ++jj)
+                        if (4 * h + jj < NLD) *(pack *)(scr + q * STR + LF * jj + VEC * g) = xc[4 * h + jj];
+                        else *(pack *)(scr + q * STR + LF * jj + VEC * g) = pack{};
+                    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const pack c = *(const pack *)(scr + d_row<T>(g, i) * STR + VEC * q);
+                    for (int i = 0; i < 4; ++i) {
+                        const pack c = *(const pack *)(scr + d_row<T>(g, i) * STR + VEC * q);
 #pragma unroll
-                    for (int m = 0; m < VEC; ++m) G[h * VEC + m] = mfma16(c.v[m], u[0][i], G[h * VEC + m]);
+                        for (int m = 0; m < VEC; ++m) G[h * VEC + m] = mfma16(c.v[m], u[0][i], G[h * VEC + m]);
+                    }
+                    __builtin_amdgcn_wave_barrier();
                 }
-                __builtin_amdgcn_wave_barrier();
             }
         }
     }
@@ -555,46 +628,71 @@ __global__ __launch_bounds__(1024) void dense_fused_kernel(RowsArgs a)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int64_t f = fs + h * SBF + VEC * d_row<T>(g, v) + m;
-                    if (f < p && q < K) part[f * K + q] = G[h * VEC + m][v];
+                    if (h < nsb && f < fend && q < K) part[f * K + q] = G[h * VEC + m][v];
                 }
     }
-    if (w == 0) {
+    // four partials per workgroup: wave w < 4 owns the rows of accumulator element w
+    if (w < 4) {
         if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD) {
             for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off);
-            if (lane == 0) a.loss_part[blockIdx.x] = loss;
+            if (lane == 0) a.loss_part[blockIdx.x * 4 + w] = loss;
+            if (w == 0 && lane > 0 && lane < 4 && lane >= nw) a.loss_part[blockIdx.x * 4 + lane] = 0.0;
         } else if constexpr (MODE == ROW_PRED) {
             for (int off = 32; off > 0; off >>= 1) hits += __shfl_xor(hits, off);
-            if (lane == 0) a.hit_part[blockIdx.x] = hits;
+            if (lane == 0) a.hit_part[blockIdx.x * 4 + w] = hits;
+            if (w == 0 && lane > 0 && lane < 4 && lane >= nw) a.hit_part[blockIdx.x * 4 + lane] = 0;
         }
     }
 }
 
-template <typename T> static size_t fused_lds_bytes(int nw, int K, bool has_c)
+constexpr int FUSED_MAX_FW = 128;    // features per wave the largest instantiation holds
+constexpr int FUSED_MAX_WAVES = 8;   // 2 waves per SIMD: 256 registers each
+
+// Split p features over nw waves of fw features each (fw a multiple of the vector width).
+template <typename T> static void fused_shape(int64_t p, int *nw, int *fw)
 {
     constexpr int VEC = 16 / sizeof(T);
-    constexpr int NT = 4, FW = 16 * NT, STR = 16 * VEC + VEC;
-    size_t elems = (((size_t)nw * FW * K + 1) & ~(size_t)1) + (size_t)nw * 256 + 256;
+    int n = (int)((p + FUSED_MAX_FW - 1) / FUSED_MAX_FW);
+    if (n > 2) n = (n + 3) / 4 * 4;                 // same number of waves on each of the 4 SIMDs
+    int f = (int)((p + n - 1) / n);
+    f = (f + VEC - 1) / VEC * VEC;
+    *nw = n;
+    *fw = f;
+}
+
+template <typename T> static size_t fused_lds_bytes(int nw, int fw, int K, bool has_c)
+{
+    constexpr int VEC = 16 / sizeof(T);
+    constexpr int LF = 4 * VEC, STR = 16 * VEC + VEC;
+    const int nld = (fw + LF - 1) / LF;
+    const size_t wrows = (size_t)(nw - 1) * fw + (size_t)nld * LF;
+    size_t elems = (wrows * K + VEC - 1) / VEC * VEC + (size_t)nw * 256 * (has_c ? 1 : 2) + 256;
     if (has_c) elems += (size_t)nw * 16 * STR;
     return elems * sizeof(T);
 }
 
-// Can the one-pass kernel serve this shape?  (one 16-column class tile, 16-byte aligned rows,
-// at most 16 waves of 64 features, LDS within the 160 KB of a gfx950 compute unit)
-bool dense_fused_supported(int dtype, const RowsArgs &a)
+template <typename T> static bool fused_ok(const RowsArgs &a)
 {
-    if (a.K > 16) return false;
-    const int nw = (int)((a.p + 63) / 64);
-    if (nw > 16) return false;
-    if (dtype == SSN_F32) return vec_ok<float>(a.X, a.ldx) && fused_lds_bytes<float>(nw, a.K, true) <= 160 * 1024;
-    return vec_ok<double>(a.X, a.ldx) && fused_lds_bytes<double>(nw, a.K, true) <= 160 * 1024;
+    if (a.K > 16 || !vec_ok<T>(a.X, a.ldx)) return false;
+    int nw, fw;
+    fused_shape<T>(a.p, &nw, &fw);
+    return nw <= FUSED_MAX_WAVES && fw <= FUSED_MAX_FW && fused_lds_bytes<T>(nw, fw, a.K, true) <= 160 * 1024;
 }
 
-int dense_fused_grid(const RowsArgs &a, int num_cus)
+// Can the one-pass kernel serve this shape?  (one 16-column class tile, 16-byte aligned rows, at most
+// 8 waves of 128 features, LDS within the 160 KB of a gfx950 compute unit)
+bool dense_fused_supported(int dtype, const RowsArgs &a)
 {
-    const int nw = (int)((a.p + 63) / 64);
-    int per_cu = 16 / nw;
+    return dtype == SSN_F32 ? fused_ok<float>(a) : fused_ok<double>(a);
+}
+
+int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus)
+{
+    int nw, fw;
+    if (dtype == SSN_F32) fused_shape<float>(a.p, &nw, &fw);
+    else fused_shape<double>(a.p, &nw, &fw);
+    int per_cu = 8 / nw;                          // aim at 8 waves per compute unit
     if (per_cu < 1) per_cu = 1;
-    if (per_cu > 8) per_cu = 8;
     const int64_t nblk = (a.nrows + 15) / 16;
     int64_t grid = (int64_t)num_cus * per_cu;
     if (grid > nblk) grid = nblk;
@@ -602,18 +700,34 @@ int dense_fused_grid(const RowsArgs &a, int num_cus)
     return (int)grid;
 }
 
-template <typename T, int MODE> static hipError_t fused_launch_mode(const RowsArgs &a, int grid, hipStream_t st)
+template <typename T, int MODE, int NLD, int NSB>
+static hipError_t fused_launch_inst(const RowsArgs &a, int grid, int nw, size_t lds, hipStream_t st)
 {
-    const int nw = (int)((a.p + 63) / 64);
-    constexpr bool has_c = (MODE == ROW_GRAD || MODE == ROW_APPLY);
-    const size_t lds = fused_lds_bytes<T>(nw, a.K, has_c);
-    auto kern = dense_fused_kernel<T, MODE, 4>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    auto kern = dense_fused_kernel<T, MODE, NLD, NSB>;
+    static size_t lds_allowed = 48 * 1024;          // raise the dynamic LDS limit once per instantiation
+    if (lds > lds_allowed) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
+        lds_allowed = 160 * 1024;
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * nw), lds, st, a);
     return hipGetLastError();
+}
+
+template <typename T, int MODE> static hipError_t fused_launch_mode(RowsArgs a, int grid, hipStream_t st)
+{
+    constexpr int VEC = 16 / sizeof(T);
+    constexpr int LF = 4 * VEC, SBF = 16 * VEC;
+    int nw, fw;
+    fused_shape<T>(a.p, &nw, &fw);
+    a.fw = fw;
+    constexpr bool has_c = (MODE == ROW_GRAD || MODE == ROW_APPLY);
+    const size_t lds = fused_lds_bytes<T>(nw, fw, a.K, has_c);
+    // three register footprints: <= 64, <= 104 (f64) / 112 (f32), <= 128 features per wave
+    constexpr int MID_LD = (sizeof(T) == 8) ? 13 : 7;
+    if (fw <= 64) return fused_launch_inst<T, MODE, 64 / LF, 64 / SBF>(a, grid, nw, lds, st);
+    if (fw <= MID_LD * LF) return fused_launch_inst<T, MODE, MID_LD, 128 / SBF>(a, grid, nw, lds, st);
+    return fused_launch_inst<T, MODE, 128 / LF, 128 / SBF>(a, grid, nw, lds, st);
 }
 
 template <typename T> static hipError_t fused_dispatch(const RowsArgs &a, int grid, hipStream_t st)

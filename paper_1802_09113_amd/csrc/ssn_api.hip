@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstddef>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -30,6 +31,7 @@ struct ssn_ctx {
     void *part = nullptr;
     int64_t part_elems = 0;
     int max_chunks = 0;
+    bool fused = false;           // dense: the one-pass kernel serves this shape
     // reduction scratch
     double *loss_part = nullptr;
     int32_t *hit_part = nullptr;
@@ -141,6 +143,13 @@ XtuArgs xtu_base(const ssn_ctx *c)
 
 int launch_rows(ssn_ctx *c, const RowsArgs &a, int *nparts)
 {
+    if (c->fused) {
+        const int grid = dense_fused_grid(c->d.dtype, a, c->num_cus);
+        if (grid * 4 > c->wave_parts || grid > c->max_chunks) return fail(c, SSN_E_INVALID_ARG, "internal: partial overflow");
+        SSN_HIP(c, launch_dense_fused(c->d.dtype, a, grid, c->st));
+        if (nparts) *nparts = grid * 4;          // loss / hit partials; the X^T U partials number `grid`
+        return SSN_OK;
+    }
     // dense: one wave per 16-row block; CSR: one wave per row
     const int blocks = rows_grid_blocks(is_dense(c) ? a.nrows : a.nrows * 16, c->num_cus);
     if (blocks * ROWS_WAVES_PER_BLOCK > c->wave_parts) return fail(c, SSN_E_INVALID_ARG, "internal: wave partial overflow");
@@ -165,6 +174,29 @@ void choose_chunks(const ssn_ctx *c, int64_t nrows, int64_t *rpc, int *nch)
     *nch = (int)((nrows + r - 1) / r);
 }
 
+// out = scale * sum of the `nchunks` partials in c->part + lambda * M ; optionally partials of <out, M>
+int finalize_dense(ssn_ctx *c, int nchunks, double scale, const void *M, void *out, bool want_dot, int *ndot,
+                   const int32_t *skip)
+{
+    FinArgs f{};
+    f.part = c->part;
+    f.nchunks = nchunks;
+    f.p = c->d.p;
+    f.K = c->K;
+    f.scale = scale;
+    f.lambda = c->d.lambda;
+    f.M = M;
+    f.ldm = c->d.ldw;
+    f.out = out;
+    f.ldo = c->d.ldw;
+    f.dot_part = want_dot ? c->red_b : nullptr;
+    f.skip = skip;
+    const int fb = finalize_blocks(c->d.p, c->K);
+    SSN_HIP(c, launch_finalize(c->d.dtype, f, fb, c->st));
+    if (ndot) *ndot = fb;
+    return SSN_OK;
+}
+
 // out = scale * X_rows^T U + lambda * M ; optionally partials of <out, M> into red_b (count in *ndot)
 int transposed_product(ssn_ctx *c, const int32_t *S, int64_t nrows, double scale, const void *M, void *out,
                        bool want_dot, int *ndot, const int32_t *skip)
@@ -177,22 +209,7 @@ int transposed_product(ssn_ctx *c, const int32_t *S, int64_t nrows, double scale
     if (is_dense(c)) {
         choose_chunks(c, nrows, &x.rows_per_chunk, &x.nchunks);
         SSN_HIP(c, launch_dense_xtu(c->d.dtype, x, c->st));
-        FinArgs f{};
-        f.part = c->part;
-        f.nchunks = x.nchunks;
-        f.p = c->d.p;
-        f.K = c->K;
-        f.scale = scale;
-        f.lambda = c->d.lambda;
-        f.M = M;
-        f.ldm = c->d.ldw;
-        f.out = out;
-        f.ldo = c->d.ldw;
-        f.dot_part = want_dot ? c->red_b : nullptr;
-        f.skip = skip;
-        const int fb = finalize_blocks(c->d.p, c->K);
-        SSN_HIP(c, launch_finalize(c->d.dtype, f, fb, c->st));
-        if (ndot) *ndot = fb;
+        SSN_TRY(finalize_dense(c, x.nchunks, scale, M, out, want_dot, ndot, skip));
     } else {
         SSN_HIP(c, launch_scale_copy(c->d.dtype, c->d.p, c->K, c->d.lambda, M, c->d.ldw, out, c->d.ldw, skip, c->st));
         SSN_HIP(c, launch_csr_scatter(c->d.dtype, x, scale, out, c->d.ldw, c->st));
@@ -247,15 +264,17 @@ int objective_impl(ssn_ctx *c, const void *W, double *f)
 
 int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f)
 {
-    SSN_TRY(ensure_rows(c, &c->Ubuf, &c->U_rows, round_up(c->d.n, 16)));
+    if (!c->fused) SSN_TRY(ensure_rows(c, &c->Ubuf, &c->U_rows, round_up(c->d.n, 16)));
     RowsArgs a = rows_base(c);
     a.nrows = c->d.n;
     a.M = W;
     a.mode = ROW_GRAD;
     a.UP = c->Ubuf;
     int nparts = 0;
+    a.part = c->part;
     SSN_TRY(launch_rows(c, a, &nparts));
-    SSN_TRY(transposed_product(c, nullptr, c->d.n, scale_full(c), W, G, false, nullptr, nullptr));
+    if (c->fused) SSN_TRY(finalize_dense(c, nparts / 4, scale_full(c), W, G, false, nullptr, nullptr));
+    else SSN_TRY(transposed_product(c, nullptr, c->d.n, scale_full(c), W, G, false, nullptr, nullptr));
     if (f) {
         SSN_TRY(enqueue_objective_value(c, W, nparts, 0));
         SSN_TRY(read_scalar(c, c->scal_dev, f));
@@ -274,7 +293,10 @@ int hess_apply_impl(ssn_ctx *c, const void *V, void *HV, bool want_dot, int *ndo
     a.Pin = c->Pbuf;
     a.UP = c->Ubuf;
     a.skip = skip;
-    SSN_TRY(launch_rows(c, a, nullptr));
+    a.part = c->part;
+    int nparts = 0;
+    SSN_TRY(launch_rows(c, a, &nparts));
+    if (c->fused) return finalize_dense(c, nparts / 4, scale_sample(c), V, HV, want_dot, ndot, skip);
     return transposed_product(c, c->S, c->nS, scale_sample(c), V, HV, want_dot, ndot, skip);
 }
 
@@ -373,6 +395,14 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
     if (d->layout == SSN_DENSE_ROWMAJOR) {
         const int64_t nft = (d->p + 63) / 64;
         c->max_chunks = (int)(((int64_t)c->num_cus * 8 + nft - 1) / nft);
+        RowsArgs probe = rows_base(c);
+        probe.nrows = (int64_t)1 << 40;
+        const char *force = getenv("SSN_DENSE_PATH");          // "split" forces the two-kernel path
+        c->fused = dense_fused_supported(d->dtype, probe) && !(force && strcmp(force, "split") == 0);
+        if (c->fused) {
+            const int g = dense_fused_grid(d->dtype, probe, c->num_cus);
+            if (g > c->max_chunks) c->max_chunks = g;
+        }
         c->part_elems = (int64_t)c->max_chunks * d->p * K;
         CREATE_HIP(hipMalloc(&c->part, (size_t)c->part_elems * c->es));
     }
@@ -623,7 +653,28 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
 
 int ssn_time_kernel(ssn_ctx *c, int32_t which, const void *M, int32_t reps, double *ms)
 {
-    if (!c || !M || !ms || reps < 1 || which < 0 || which > 4) return fail(c, SSN_E_INVALID_ARG, "ssn_time_kernel: bad argument");
+    if (!c || !M || !ms || reps < 1 || which < 0 || which > 5) return fail(c, SSN_E_INVALID_ARG, "ssn_time_kernel: bad argument");
+    if (which == 5) {
+        // plain streaming read of the data matrix (dense: n*ldx elements; CSR: the value array)
+        const void *src = is_dense(c) ? c->d.X : c->d.vals;
+        int64_t bytes = (is_dense(c) ? c->d.n * c->d.ldx : c->d.nnz) * (int64_t)c->es;
+        bytes -= bytes % 16;
+        if (!src || bytes < 16 || (uintptr_t)src % 16) return fail(c, SSN_E_INVALID_ARG, "ssn_time_kernel: buffer not streamable");
+        hipEvent_t s0, s1;
+        SSN_HIP(c, hipEventCreate(&s0));
+        SSN_HIP(c, hipEventCreate(&s1));
+        hipError_t e = hipEventRecord(s0, c->st);
+        for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch_stream_read(src, bytes, c->loss_part, c->num_cus * 8, c->st);
+        if (e == hipSuccess) e = hipEventRecord(s1, c->st);
+        if (e == hipSuccess) e = hipEventSynchronize(s1);
+        float tt = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&tt, s0, s1);
+        (void)hipEventDestroy(s0);
+        (void)hipEventDestroy(s1);
+        SSN_HIP(c, e);
+        *ms = (double)tt / reps;
+        return SSN_OK;
+    }
     const bool sampled = which >= 3;
     if (sampled && !c->prepared) return fail(c, SSN_E_NOT_PREPARED, "ssn_time_kernel: no prepared sample");
     const int64_t nrows = sampled ? c->nS : c->d.n;
@@ -635,12 +686,14 @@ int ssn_time_kernel(ssn_ctx *c, int32_t which, const void *M, int32_t reps, doub
     a.UP = c->Ubuf;
     a.Pin = c->Pbuf;
     a.mode = which == 0 ? ROW_OBJ : (which == 1 ? ROW_GRAD : ROW_APPLY);
+    a.part = c->part;
     XtuArgs x = xtu_base(c);
     x.S = a.S;
     x.nrows = nrows;
     x.U = c->Ubuf;
     if (is_dense(c)) choose_chunks(c, nrows, &x.rows_per_chunk, &x.nchunks);
-    if (!is_dense(c) && (which == 2 || which == 4) && !c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
+    if ((!is_dense(c) || c->fused) && (which == 2 || which == 4) && !c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
+    const int fused_parts = c->fused ? dense_fused_grid(c->d.dtype, a, c->num_cus) : 0;
     hipEvent_t e0, e1;
     SSN_HIP(c, hipEventCreate(&e0));
     SSN_HIP(c, hipEventCreate(&e1));
@@ -648,7 +701,8 @@ int ssn_time_kernel(ssn_ctx *c, int32_t which, const void *M, int32_t reps, doub
     hipError_t he = hipEventRecord(e0, c->st);
     for (int r = 0; r < reps && status == SSN_OK && he == hipSuccess; ++r) {
         if (which == 2 || which == 4) {
-            if (is_dense(c)) he = launch_dense_xtu(c->d.dtype, x, c->st);
+            if (c->fused) status = finalize_dense(c, fused_parts, sampled ? scale_sample(c) : scale_full(c), M, c->trial, false, nullptr, nullptr);
+            else if (is_dense(c)) he = launch_dense_xtu(c->d.dtype, x, c->st);
             else he = launch_csr_scatter(c->d.dtype, x, sampled ? scale_sample(c) : scale_full(c), c->trial, c->d.ldw, c->st);
         } else {
             status = launch_rows(c, a, nullptr);
@@ -664,6 +718,13 @@ int ssn_time_kernel(ssn_ctx *c, int32_t which, const void *M, int32_t reps, doub
     SSN_HIP(c, he);
     *ms = (double)t / reps;
     return SSN_OK;
+}
+
+int ssn_dense_path(const ssn_ctx *c)
+{
+    if (!c) return SSN_E_INVALID_ARG;
+    if (!is_dense(c)) return 0;
+    return c->fused ? 2 : 1;
 }
 
 }  // extern "C"

@@ -46,6 +46,7 @@ struct RowsArgs {
     int32_t mode;
     const int32_t *skip; // nullable device flag: non-zero -> the launch does nothing
     void *part;          // one-pass kernel only: per-workgroup p x K partial sums of X^T U
+    int32_t fw;          // one-pass kernel only: features per wave (set by the launcher)
 };
 
 // Arguments of the transposed product: part[chunk] = X_rows(chunk)^T * U(chunk).
@@ -95,7 +96,7 @@ int finalize_blocks(int64_t p, int K);
 hipError_t launch_dense_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
 hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st);
 bool dense_fused_supported(int dtype, const RowsArgs &a);
-int dense_fused_grid(const RowsArgs &a, int num_cus);
+int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus);
 hipError_t launch_dense_fused(int dtype, const RowsArgs &a, int grid, hipStream_t st);
 hipError_t launch_csr_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
 hipError_t launch_csr_scatter(int dtype, const XtuArgs &a, double scale, void *out, int64_t ldo, hipStream_t st);
@@ -114,6 +115,8 @@ hipError_t launch_axpy(int dtype, int64_t p, int K, double alpha, const void *X,
 // *out = scale * sum(a[0..na)) + coef * sum(b[0..nb))   (single block, fixed order)
 hipError_t launch_combine(const double *a, int na, double scale, const double *b, int nb, double coef,
                           double *out, hipStream_t st);
+// streaming read of `bytes` (multiple of 16, 16-byte aligned); one checksum partial per block
+hipError_t launch_stream_read(const void *src, int64_t bytes, double *part, int blocks, hipStream_t st);
 hipError_t launch_sum_int(const int32_t *a, int na, int32_t *out, hipStream_t st);
 
 // validation passes: *bad receives the number of offending entries

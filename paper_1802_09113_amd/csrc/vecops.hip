@@ -85,25 +85,31 @@ template <typename T, int EL> __global__ __launch_bounds__(VEC_BLOCK) void final
     }
 }
 
+// elements per block: wide rows of partials are read in long contiguous runs, small ones use more
+// chunk lanes per element
+static int finalize_el(int64_t total) { return total >= 32768 ? 32 : (total >= 2048 ? 16 : 4); }
+
 int finalize_blocks(int64_t p, int K)
 {
     const int64_t total = p * K;
-    const int el = (total >= 32 * 256) ? 32 : 4;
+    const int el = finalize_el(total);
     int64_t b = (total + el - 1) / el;
     if (b > RED_MAX_PARTS) b = RED_MAX_PARTS;
     return (int)b;
 }
 
+template <typename T> static void finalize_launch(const FinArgs &a, int blocks, hipStream_t st)
+{
+    const int el = finalize_el(a.p * a.K);
+    if (el == 32) hipLaunchKernelGGL((finalize_kernel<T, 32>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a);
+    else if (el == 16) hipLaunchKernelGGL((finalize_kernel<T, 16>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a);
+    else hipLaunchKernelGGL((finalize_kernel<T, 4>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a);
+}
+
 hipError_t launch_finalize(int dtype, const FinArgs &a, int blocks, hipStream_t st)
 {
-    const bool wide = (a.p * a.K >= 32 * 256);
-    if (dtype == SSN_F32) {
-        if (wide) hipLaunchKernelGGL((finalize_kernel<float, 32>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a);
-        else hipLaunchKernelGGL((finalize_kernel<float, 4>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a);
-    } else {
-        if (wide) hipLaunchKernelGGL((finalize_kernel<double, 32>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a);
-        else hipLaunchKernelGGL((finalize_kernel<double, 4>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a);
-    }
+    if (dtype == SSN_F32) finalize_launch<float>(a, blocks, st);
+    else finalize_launch<double>(a, blocks, st);
     return hipGetLastError();
 }
 
@@ -209,6 +215,30 @@ __global__ __launch_bounds__(VEC_BLOCK) void sum_int_kernel(const int32_t *a, in
 hipError_t launch_sum_int(const int32_t *a, int na, int32_t *out, hipStream_t st)
 {
     hipLaunchKernelGGL(sum_int_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, a, na, out);
+    return hipGetLastError();
+}
+
+// ---- plain streaming read of a buffer: the practical HBM ceiling next to which the kernels are judged ----
+__global__ __launch_bounds__(VEC_BLOCK) void stream_read_kernel(const uint4 *src, int64_t nvec, double *part)
+{
+    unsigned acc = 0;
+    const int64_t stride = (int64_t)gridDim.x * VEC_BLOCK;
+    int64_t i = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x;
+    for (; i + 3 * stride < nvec; i += 4 * stride) {
+        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc += (a.x ^ a.y ^ a.z ^ a.w) + (b.x ^ b.y ^ b.z ^ b.w) + (c.x ^ c.y ^ c.z ^ c.w) + (d.x ^ d.y ^ d.z ^ d.w);
+    }
+    for (; i < nvec; i += stride) {
+        const uint4 a = src[i];
+        acc += a.x ^ a.y ^ a.z ^ a.w;
+    }
+    const double r = block_sum((double)acc);
+    if (threadIdx.x == 0) part[blockIdx.x] = r;
+}
+
+hipError_t launch_stream_read(const void *src, int64_t bytes, double *part, int blocks, hipStream_t st)
+{
+    hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(VEC_BLOCK), 0, st, (const uint4 *)src, bytes / 16, part);
     return hipGetLastError();
 }
 
