@@ -36,8 +36,18 @@ def parse():
     return ap.parse_args()
 
 
-def kernel_bytes(n, p, K, nS, e):
-    """Algorithmic bytes one launch of each timed kernel has to move (X counted once per kernel)."""
+def kernel_bytes(n, p, K, nS, e, path):
+    """Algorithmic bytes one launch of each timed kernel has to move (X counted once per kernel).
+    path 1: margins kernel then X^T U kernel; path 2: one sweep does both, kernel 2 / 4 only add up the
+    per-workgroup partial sums (no pass over X: no HBM roofline entry)."""
+    if path == 2:
+        return {
+            0: n * p * e + 4 * n + p * K * e,                       # margins + loss
+            1: n * p * e + 4 * n + p * K * e,                       # margins + U + X^T U partials, one sweep
+            2: None,
+            3: nS * p * e + 4 * nS + nS * K * e + p * K * e,        # sampled: margins, P in, X_S^T U partials
+            4: None,
+        }
     return {
         0: n * p * e + 4 * n + p * K * e,                       # margins + loss
         1: n * p * e + 4 * n + p * K * e + n * K * e,           # margins + U out
@@ -56,8 +66,12 @@ def call_bytes(n, p, K, nS, e):
     }
 
 
-KERNEL_NAMES = {0: "dense_rows_kernel<OBJ>", 1: "dense_rows_kernel<GRAD>", 2: "dense_xtu_kernel (n rows)",
-                3: "dense_rows_kernel<APPLY>", 4: "dense_xtu_kernel (|S| rows)"}
+KERNEL_NAMES = {
+    1: {0: "dense_rows_kernel<OBJ>", 1: "dense_rows_kernel<GRAD>", 2: "dense_xtu_kernel (n rows)",
+        3: "dense_rows_kernel<APPLY>", 4: "dense_xtu_kernel (|S| rows)"},
+    2: {0: "dense_fused_kernel<OBJ>", 1: "dense_fused_kernel<GRAD>", 2: "finalize_kernel (gradient partials)",
+        3: "dense_fused_kernel<APPLY>", 4: "finalize_kernel (H_S v partials)"},
+}
 
 
 def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
@@ -139,15 +153,24 @@ def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
                     for k in cb}
 
     # per-kernel durations from HIP events recorded by the library on its own stream
-    kb = kernel_bytes(n, p, K, nS, e)
+    path = ctx.ssn_dense_path()
+    out["dense_path"] = path
+    kb = kernel_bytes(n, p, K, nS, e, path)
     kern = {}
     for which in (0, 1, 2, 3, 4):
         reps = 20 if which < 3 else 200
         ctx.ssn_time_kernel(which, V[0] if which >= 3 else W, 3)
         ms = ctx.ssn_time_kernel(which, V[0] if which >= 3 else W, reps)
-        kern[which] = {"kernel": KERNEL_NAMES[which], "ms": ms, "algorithmic_GB": kb[which] / 1e9,
-                       "GBps": kb[which] / ms / 1e6, "frac": kb[which] / ms / 1e6 / HBM_PEAK_GBS}
+        ent = {"kernel": KERNEL_NAMES[path][which], "ms": ms}
+        if kb[which] is not None:
+            ent.update({"algorithmic_GB": kb[which] / 1e9, "GBps": kb[which] / ms / 1e6,
+                        "frac": kb[which] / ms / 1e6 / HBM_PEAK_GBS})
+        kern[which] = ent
     out["kernels"] = kern
+    # plain streaming read of X (no arithmetic): what this chip delivers to a trivial kernel
+    ctx.ssn_time_kernel(5, W, 3)
+    ms = ctx.ssn_time_kernel(5, W, 20)
+    out["stream_read"] = {"ms": ms, "GBps": n * p * e / ms / 1e6, "frac": n * p * e / ms / 1e6 / HBM_PEAK_GBS}
     ctx.close()
     return out
 
@@ -204,11 +227,13 @@ def main():
     k = main_res["kernels"]
     per_step = {0: main_res["ls_evals_mean"] * k[0]["ms"], 1: k[1]["ms"], 2: k[2]["ms"],
                 3: data["T"] * k[3]["ms"], 4: data["T"] * k[4]["ms"]}
-    dom = max(per_step, key=per_step.get)
+    dom = max((w for w in per_step if "GBps" in k[w]), key=per_step.get)
     roof = {"bound": "hbm", "kernel": k[dom]["kernel"], "achieved": k[dom]["GBps"], "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": k[dom]["frac"], "traffic": None,
             "ms_per_launch": k[dom]["ms"], "algorithmic_bytes_per_launch": k[dom]["algorithmic_GB"] * 1e9,
-            "share_of_step_kernel_time": per_step[dom] / sum(per_step.values())}
+            "share_of_step_kernel_time": per_step[dom] / sum(per_step.values()),
+            "stream_read_GBps": main_res["stream_read"]["GBps"],
+            "frac_of_stream_read": k[dom]["GBps"] / main_res["stream_read"]["GBps"]}
     line = {
         "metric": "sub-sampled Hess-vec products/s", "value": main_res["hv_per_s"], "unit": "products/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
@@ -222,6 +247,8 @@ def main():
         "hv_per_s_inside_cg": main_res["hv_per_s_inside_cg"],
         "phase_ms": main_res["phase_ms"],
         "calls": main_res["calls"],
+        "dense_path": main_res["dense_path"],
+        "stream_read": main_res["stream_read"],
         "kernels": {v["kernel"]: {kk: vv for kk, vv in v.items() if kk != "kernel"} for v in k.values()},
         "final_f": main_res["final_f"],
     }
@@ -229,7 +256,8 @@ def main():
         od = "f32" if args.dtype == "f64" else "f64"
         line["other_dtype"] = {"dtype": od, "hv_per_s": other["hv_per_s"], "ms_per_step": other["ms_per_step"],
                                "calls": other["calls"],
-                               "kernels": {v["kernel"]: {"ms": v["ms"], "GBps": v["GBps"], "frac": v["frac"]}
+                               "stream_read": other["stream_read"],
+                               "kernels": {v["kernel"]: {kk: vv for kk, vv in v.items() if kk != "kernel"}
                                            for v in other["kernels"].values()}}
     print(json.dumps(line))
 

@@ -13,6 +13,7 @@
 //   D[4*(l/16)+v][l%16] for the f32 instruction and D[4*v+l/16][l%16] for the f64 one (d_row below).
 #include "ssn_internal.h"
 
+#include <cstdlib>
 #include <limits>
 
 namespace ssn {
@@ -37,10 +38,56 @@ template <> __device__ __forceinline__ int d_row<double>(int g, int v) { return 
 
 template <typename T, int VEC> struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; };
 
+// The stable log-sum-exp of eq. (8), (9) only ever exponentiates non-positive numbers and only takes the
+// logarithm of alpha in [1, C].  On those ranges short fp64 routines (argument reduction + Taylor /
+// atanh series, errors of a few 1e-16) need far fewer registers than the general library calls, which
+// matters inside the MFMA kernels.
+__device__ __forceinline__ double exp_nonpos(double x)
+{
+    if (x < -745.2) return 0.0;                                   // underflow, and -inf
+    const double n = rint(x * 1.4426950408889634);
+    double r = fma(n, -6.93147180369123816490e-01, x);            // x - n*ln2, ln2 split in two parts
+    r = fma(n, -1.90821492927058770002e-10, r);
+    double t = 1.0 / 6227020800.0;                                // sum_{k<=13} r^k / k!, |r| <= ln2/2
+    t = fma(t, r, 1.0 / 479001600.0);
+    t = fma(t, r, 1.0 / 39916800.0);
+    t = fma(t, r, 1.0 / 3628800.0);
+    t = fma(t, r, 1.0 / 362880.0);
+    t = fma(t, r, 1.0 / 40320.0);
+    t = fma(t, r, 1.0 / 5040.0);
+    t = fma(t, r, 1.0 / 720.0);
+    t = fma(t, r, 1.0 / 120.0);
+    t = fma(t, r, 1.0 / 24.0);
+    t = fma(t, r, 1.0 / 6.0);
+    t = fma(t, r, 0.5);
+    t = fma(t, r, 1.0);
+    t = fma(t, r, 1.0);
+    return ldexp(t, (int)n);
+}
+__device__ __forceinline__ double log_ge1(double a)
+{
+    int k;
+    double m = frexp(a, &k);                                      // a = m * 2^k, m in [0.5, 1)
+    if (m < 0.70710678118654752) { m *= 2.0; k -= 1; }            // m in [sqrt(1/2), sqrt(2))
+    const double s = (m - 1.0) / (m + 1.0), s2 = s * s;           // log m = 2 atanh(s), |s| <= 0.1716
+    double t = 1.0 / 23.0;
+    t = fma(t, s2, 1.0 / 21.0);
+    t = fma(t, s2, 1.0 / 19.0);
+    t = fma(t, s2, 1.0 / 17.0);
+    t = fma(t, s2, 1.0 / 15.0);
+    t = fma(t, s2, 1.0 / 13.0);
+    t = fma(t, s2, 1.0 / 11.0);
+    t = fma(t, s2, 1.0 / 9.0);
+    t = fma(t, s2, 1.0 / 7.0);
+    t = fma(t, s2, 1.0 / 5.0);
+    t = fma(t, s2, 1.0 / 3.0);
+    t = fma(t, s2, 1.0);
+    return fma((double)k, 0.69314718055994530942, 2.0 * s * t);
+}
 __device__ __forceinline__ float t_exp(float x) { return expf(x); }
-__device__ __forceinline__ double t_exp(double x) { return exp(x); }
+__device__ __forceinline__ double t_exp(double x) { return exp_nonpos(x); }
 __device__ __forceinline__ float t_log(float x) { return logf(x); }
-__device__ __forceinline__ double t_log(double x) { return log(x); }
+__device__ __forceinline__ double t_log(double x) { return log_ge1(x); }
 
 // butterfly over the 16 lanes that hold the 16 class columns of one row
 template <typename T> __device__ __forceinline__ T row16_sum(T x)
@@ -415,35 +462,74 @@ hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Per-row work of the one-pass kernel on ONE accumulator element: the 16 lanes of a row group hold the
+// 16 class columns of sample row sv.  lab / pin are that row's label and this lane's probability,
+// loaded by the caller.  Returns U (ROW_GRAD: eq. (6) residual p - y; ROW_APPLY: eq. (12)).
+template <typename T, int MODE>
+__device__ __forceinline__ T slot_epilogue(T z, const RowsArgs &a, int64_t sv, int q, int lab, T pin, double &loss,
+                                           int &hits)
+{
+    const int K = a.K;
+    const bool valid = sv < a.nrows;
+    const bool cv = q < K;
+    const T NEG = -std::numeric_limits<T>::infinity();
+    if constexpr (MODE == ROW_APPLY) {
+        const T t = row16_sum(pin * z);                    // pin is zero in padded columns
+        return valid ? (pin * z - pin * t) : T(0);
+    }
+    const T zmax = row16_max(cv ? z : NEG);
+    if constexpr (MODE == ROW_PRED) {
+        const int cand = row16_min((cv && z == zmax) ? q : 0x7fffffff);
+        const int pr = (T(0) > zmax) ? K : cand;           // the reference class wins only strictly
+        if (valid && q == 0) {
+            if (a.pred) a.pred[sv] = pr;
+            hits += (pr == lab);
+        }
+        return T(0);
+    }
+    const T Mx = fmax(T(0), zmax);                         // eq. (8)
+    const T e = cv ? t_exp(z - Mx) : T(0);
+    const T alpha = t_exp(-Mx) + row16_sum(e);             // eq. (9)
+    if constexpr (MODE == ROW_PREP) {
+        ((T *)a.UP)[sv * a.KP + q] = valid ? e / alpha : T(0);
+        return T(0);
+    }
+    const T lin = row16_sum((cv && q == lab) ? z : T(0));
+    if (valid && q == 0) loss += (double)Mx + (double)t_log(alpha) - (double)lin;   // eqs. (14)-(17)
+    if constexpr (MODE == ROW_GRAD) return (valid && cv) ? (e / alpha - ((q == lab) ? T(1) : T(0))) : T(0);
+    return T(0);
+}
+
 // Fused one-pass kernel: margins, per-row epilogue and (for ROW_GRAD / ROW_APPLY) the transposed
 // product, reading every row of X exactly once (eqs. (10)-(13) with both products of Alg. 7 in one
 // sweep; same for Alg. 6).
 //
 // A workgroup owns whole 16-row blocks; its waves split the features into slices of a.fw features
-// (a.fw <= 16*NT, a multiple of the vector width).  Per row block:
+// (a.fw <= min(NLD*LF, NSB*SBF), a multiple of the vector width).  Per row block:
 //   1. every lane already holds its part of the wave's 16 x fw tile of X in the A-operand layout
-//      (prefetched into registers while the previous block was processed);
+//      (prefetched into registers while the previous block was processed; all loads are unconditional --
+//      out-of-slice lanes read a safe address and are zeroed -- so they stay in flight together);
 //   2. phase A: Z_partial (16x16) += X_tile * W_slice, W operands from an LDS copy of M;
-//   3. the partial margins of the waves are added through LDS in a fixed order (two barriers);
-//   4. every wave runs the epilogue on the full margins and keeps U in accumulator layout, which is
-//      exactly the B-operand layout of the transposed product;
+//   3. the partial margins go to LDS; wave w adds accumulator element v = w (, w + nw, ..) over the waves
+//      in a fixed order and does the per-row work for it, so the epilogue runs once per row block;
+//   4. U comes back through LDS in accumulator layout, which is the B-operand layout of the transposed
+//      product;
 //   5. phase C: the wave's X tile is transposed through a wave-private LDS scratch (rows become the
 //      contraction index) and G_slice (fw x 16) += X_tile^T * U accumulates in registers.
 // At the end each workgroup writes its p x K partial; the finalize kernel adds them in a fixed order.
-template <typename T, int MODE, int NLD, int NSB>
-__global__ __launch_bounds__(512) void dense_fused_kernel(RowsArgs a)
+template <typename T, int MODE, int NLD, int NSB, int MAXW>
+__global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
 {
     if (a.skip && *a.skip) return;
     typedef typename V4<T>::type v4;
     constexpr int VEC = 16 / sizeof(T);
     typedef Pack<T, VEC> pack;
-    // NLD: vector loads per lane per row block the instantiation can hold (LF features each);
-    // NSB: transposition sub-blocks (SBF features each) it can hold.  a.fw <= min(NLD*LF, NSB*SBF).
     constexpr int LF = 4 * VEC;              // features covered by one vector load of the wave
     constexpr int SBF = 16 * VEC;            // features per transposition sub-block
     constexpr int NT = NSB * VEC;            // 16-feature output tiles of the transposed product
     constexpr int STR = SBF + VEC;           // scratch row stride (elements): 16 bytes of padding
     constexpr bool HAS_C = (MODE == ROW_GRAD || MODE == ROW_APPLY);
+    constexpr bool NEED_LAB = (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_PRED);
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, nw = blockDim.x >> 6;
@@ -451,40 +537,21 @@ __global__ __launch_bounds__(512) void dense_fused_kernel(RowsArgs a)
     const int K = a.K;
     const int64_t p = a.p;
     const int fw = a.fw;
-    const int nld = (fw + LF - 1) / LF;                      // loads this launch really needs
-    const int nsb = (fw + SBF - 1) / SBF;
-    const int wrows = (nw - 1) * fw + nld * LF;              // rows of the LDS copy of M (zero beyond p)
+    // LDS copy of M, class-major (wl[c * ws + f], zero beyond p): a lane's operands then sit at constant
+    // offsets from one base address.  ws is odd so the class rows start in different banks.
+    const int wrows = (nw - 1) * fw + NLD * LF;
+    const int ws = wrows | 1;
     T *wl = (T *)smem_raw;
-    T *zpart = wl + ((size_t)wrows * K + VEC - 1) / VEC * VEC;   // nw x 4 x 64 partial margins (16-byte aligned)
-    T *zfull = zpart + (size_t)nw * 256 * (HAS_C ? 1 : 2);   // U of the block (modes with a transposed product)
+    T *zpart = wl + ((size_t)ws * K + VEC - 1) / VEC * VEC;  // MAXW x 4 x 64 partial margins (16-byte aligned)
+    T *zfull = zpart + (size_t)MAXW * 256 * (HAS_C ? 1 : 2); // U of the block (modes with a transposed product)
     T *scr = zfull + 256 + (size_t)w * 16 * STR;             // wave-private transposition scratch
-
-    {
-        const T *M = (const T *)a.M;
-        // batches of 8 independent loads per thread, so the copy costs one or two memory round trips
-        const int total = wrows * K;
-        for (int base = 0; base < total; base += 8 * (int)blockDim.x) {
-            T tmp[8];
-#pragma unroll
-            for (int uu = 0; uu < 8; ++uu) {
-                const int idx = base + uu * (int)blockDim.x + tid;
-                const int f = idx / K, c = idx - f * K;
-                tmp[uu] = (idx < total && f < p) ? M[(int64_t)f * a.ldm + c] : T(0);
-            }
-#pragma unroll
-            for (int uu = 0; uu < 8; ++uu) {
-                const int idx = base + uu * (int)blockDim.x + tid;
-                if (idx < total) wl[idx] = tmp[uu];
-            }
-        }
-    }
-    __syncthreads();
 
     const T *X = (const T *)a.X;
     const int fs = w * fw;
     const int64_t fend = (fs + fw < p) ? (int64_t)(fs + fw) : p;   // features [fs, fend) belong to this wave
     const int qc = (q < K) ? q : K - 1;
     const bool cvalid = q < K;
+    const T *wlane = wl + qc * ws + fs + VEC * g;            // this lane's B operands: wlane[LF * j + m]
     const int64_t nblk = (a.nrows + 15) / 16;
 
     // sample position -> data row of the lane's A-operand row of block rb
@@ -493,143 +560,226 @@ __global__ __launch_bounds__(512) void dense_fused_kernel(RowsArgs a)
         if (si >= a.nrows) si = a.nrows - 1;
         return a.S ? (int64_t)a.S[si] : si;
     };
+    // tile load: one base address per lane, constant offsets per load; a load is skipped (register keeps its
+    // old, finite-or-not contents, which mask_block then replaces) only where it would leave the row's
+    // storage of ldx elements, so every issued load is in bounds and none depends on another
     auto load_block = [&](int64_t xr, pack(&x)[NLD]) {
-        const T *xrow = X + xr * a.ldx;
+        const T *xbase = X + xr * a.ldx + fs + VEC * g;
+        const int64_t room = a.ldx - fs - VEC * g;           // elements from xbase to the end of the row
+#pragma unroll
+        for (int j = 0; j < NLD; ++j)
+            if (LF * j + VEC <= room) x[j] = *(const pack *)(xbase + LF * j);
+    };
+    // one vector of the next tile; issued one at a time between the MFMAs of the current block, because a
+    // compute unit cannot hold a whole tile of outstanding loads and a wave stalls at issue when it is full
+    auto load_one = [&](const T *xbase, int64_t room, int j, pack(&x)[NLD]) {
+        if (LF * j + VEC <= room) x[j] = *(const pack *)(xbase + LF * j);
+    };
+    auto mask_block = [&](pack(&x)[NLD]) {
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
-            if (j < nld) {
-                const int64_t f = fs + LF * j + VEC * g;
-                if (f + VEC <= fend) {
-                    x[j] = *(const pack *)(xrow + f);
-                } else {
+            const int64_t f = fs + LF * j + VEC * g;
 #pragma unroll
-                    for (int m = 0; m < VEC; ++m) x[j].v[m] = (f + m < fend) ? xrow[f + m] : T(0);
-                }
+            for (int m = 0; m < VEC; ++m) x[j].v[m] = (f + m < fend) ? x[j].v[m] : T(0);
+        }
+    };
+
+    pack xn[NLD];
+    int64_t rb = blockIdx.x;
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) xn[j] = pack{};
+    if (rb < nblk) load_block(block_row(rb), xn);
+    // accumulator elements whose per-row work this wave does.  MAXW == 1: the single wave does all four in
+    // registers.  Otherwise the workgroup has at least four waves and wave w < 4 does element w.
+    constexpr int SLOTS = (MAXW == 1) ? 4 : 1;
+    const int nslot = (MAXW == 1) ? 4 : ((w < 4) ? 1 : 0);
+    // label / probability of the rows of block rbq this wave's slots cover
+    int lab_n[SLOTS];
+    T pin_n[SLOTS];
+    auto load_meta = [&](int64_t rbq) {
+#pragma unroll
+        for (int k = 0; k < SLOTS; ++k) {
+            lab_n[k] = 0;
+            pin_n[k] = T(0);
+            if (k < nslot && rbq < nblk) {
+                const int v = (MAXW == 1) ? k : w;
+                int64_t sv = rbq * 16 + d_row<T>(g, v);
+                if (sv >= a.nrows) sv = a.nrows - 1;
+                if constexpr (MODE == ROW_APPLY) pin_n[k] = ((const T *)a.Pin)[sv * a.KP + q];
+                if constexpr (NEED_LAB) lab_n[k] = a.labels[a.S ? (int64_t)a.S[sv] : sv];
             }
         }
     };
-    // accumulator elements (row groups) whose per-row work this wave does
-    int vmask = 0;
+    load_meta(rb);
+    // data row of this lane's A-operand row in the NEXT block (needed when that block's loads are issued)
+    int64_t xr_n = (rb + gridDim.x < nblk) ? block_row(rb + gridDim.x) : 0;
+
+    {
+        // LDS copy of M: batches of 8 independent loads per thread
+        const T *M = (const T *)a.M;
+        const int total = wrows * K;
+        for (int base = 0; base < total; base += 8 * (int)blockDim.x) {
+            T tmp[8];
 #pragma unroll
-    for (int v = 0; v < 4; ++v)
-        if (nw == 1 || v % nw == w) vmask |= 1 << v;
+            for (int uu = 0; uu < 8; ++uu) {
+                const int idx = base + uu * (int)blockDim.x + tid;
+                const int f = idx / K, c = idx - f * K;
+                const bool ok = idx < total && f < p;
+                const T val = M[ok ? ((int64_t)f * a.ldm + c) : 0];
+                tmp[uu] = ok ? val : T(0);
+            }
+#pragma unroll
+            for (int uu = 0; uu < 8; ++uu) {
+                const int idx = base + uu * (int)blockDim.x + tid;
+                if (idx < total) wl[(idx % K) * ws + idx / K] = tmp[uu];
+            }
+        }
+    }
+    __syncthreads();
 
     v4 G[HAS_C ? NT : 1];
 #pragma unroll
     for (int t = 0; t < (HAS_C ? NT : 1); ++t) G[t] = v4{0, 0, 0, 0};
     double loss = 0.0;
     int hits = 0;
-
     int it = 0;
-    pack xn[NLD];
-#pragma unroll
-    for (int j = 0; j < NLD; ++j) xn[j] = pack{};          // loads beyond the slice stay zero
-    int64_t rb = blockIdx.x;
-    if (rb < nblk) load_block(block_row(rb), xn);
+
+#ifdef SSN_PROFILE_PHASES
+    long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define SSN_TICK(i) do { __builtin_amdgcn_sched_barrier(0); const long long t_ = clock64(); tph[i] += t_ - tlast; tlast = t_; __builtin_amdgcn_sched_barrier(0); } while (0)
+    long long tlast = clock64();
+#else
+#define SSN_TICK(i) do { } while (0)
+#endif
     for (; rb < nblk; rb += gridDim.x) {
+#ifdef SSN_PROFILE_PHASES
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): time spent waiting for the prefetched tile
+        SSN_TICK(0);
+#endif
         pack xc[NLD];
 #pragma unroll
         for (int j = 0; j < NLD; ++j) xc[j] = xn[j];
-        // Small loads first (row index of the next block, labels / probabilities of this block), the X
-        // prefetch after them: the memory counter retires in order, so the epilogue's wait for its inputs
-        // then leaves the prefetch in flight.
+        mask_block(xc);
+        // The memory counter of a wave retires in order, so a small load issued after bulk prefetch loads
+        // would wait for all of them.  Everything small is therefore fetched one block ahead and BEFORE the
+        // prefetch of that block is issued: labels / probabilities of block rb+G and the row index of block
+        // rb+2G now, the tile of block rb+G (row index already in xr_n) spread over the MFMAs below.
         const int64_t rbn = rb + gridDim.x;
-        const int64_t xr_next = (rbn < nblk) ? block_row(rbn) : 0;
-        int lab_pre[4];
-        T pin_pre[4];
+        const bool has_next = rbn < nblk;
+        const int64_t xr_next = xr_n;
+        int lab_pre[SLOTS];
+        T pin_pre[SLOTS];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            lab_pre[v] = 0;
-            pin_pre[v] = T(0);
-            if ((vmask >> v) & 1) {
-                int64_t sv = rb * 16 + d_row<T>(g, v);
-                if (sv >= a.nrows) sv = a.nrows - 1;
-                if constexpr (MODE == ROW_APPLY) pin_pre[v] = ((const T *)a.Pin)[sv * a.KP + q];
-                else if constexpr (MODE != ROW_PREP) lab_pre[v] = a.labels[a.S ? (int64_t)a.S[sv] : sv];
-            }
+        for (int k = 0; k < SLOTS; ++k) {
+            lab_pre[k] = lab_n[k];
+            pin_pre[k] = pin_n[k];
         }
-        if (rbn < nblk) load_block(xr_next, xn);
+        load_meta(rbn);
+        xr_n = (rbn + gridDim.x < nblk) ? block_row(rbn + gridDim.x) : 0;
+        const T *xbase_n = X + xr_next * a.ldx + fs + VEC * g;
+        const int64_t room_n = has_next ? (a.ldx - fs - VEC * g) : 0;      // no next block: every load is skipped
+        constexpr int LOADS_A = HAS_C ? (NLD + 1) / 2 : NLD;              // issued during phase A, the rest in phase C
+        constexpr int LOADS_C = (NLD - LOADS_A + NSB - 1) / NSB;          // per transposition sub-block
+        SSN_TICK(1);
 
-        // phase A: two accumulators break the dependent MFMA chain
+        // phase A (fp32: two accumulators break the dependent MFMA chain; fp64 has no registers to spare)
+        constexpr bool TWO_ACC = sizeof(T) == 4;
         v4 z0 = v4{0, 0, 0, 0}, z1 = v4{0, 0, 0, 0};
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
-            if (j < nld) {
 #pragma unroll
-                for (int m = 0; m < VEC; ++m) {
-                    const int f = fs + LF * j + VEC * g + m;
-                    const T bw = wl[f * K + qc];
-                    const T b = cvalid ? bw : T(0);
-                    if ((j * VEC + m) & 1) z1 = mfma16(xc[j].v[m], b, z1);
-                    else z0 = mfma16(xc[j].v[m], b, z0);
-                }
+            for (int m = 0; m < VEC; ++m) {
+                const T bw = wlane[LF * j + m];
+                const T b = cvalid ? bw : T(0);
+                if (TWO_ACC && ((j * VEC + m) & 1)) z1 = mfma16(xc[j].v[m], b, z1);
+                else z0 = mfma16(xc[j].v[m], b, z0);
             }
-            if ((j & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // keep the W operand reads from piling up
+            if (j < LOADS_A) load_one(xbase_n, room_n, j, xn);
+            __builtin_amdgcn_sched_barrier(0);       // keep this interleaving (and the W reads from piling up)
         }
-        v4 z[1], u[1];
-        z[0] = z0 + z1;
-        u[0] = v4{0, 0, 0, 0};
-        if (nw == 1) {
-            row_epilogue<T, 1, MODE, true>(z, a, rb, lane, loss, hits, u, 15, lab_pre, pin_pre);
+        v4 z = TWO_ACC ? (z0 + z1) : z0, u = v4{0, 0, 0, 0};
+        SSN_TICK(2);
+        if constexpr (MAXW == 1) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                u[v] = slot_epilogue<T, MODE>(z[v], a, rb * 16 + d_row<T>(g, v), q, lab_pre[v], pin_pre[v], loss, hits);
         } else {
-            // partial margins -> LDS; wave w sums accumulator element v = w (, w+nw, ..) over the waves in a
-            // fixed order and runs the per-row work for it, so the epilogue is done once per row block
-            T *zp = zpart + (HAS_C ? 0 : (size_t)(it & 1) * nw * 256);
+            T *zp = zpart + (HAS_C ? 0 : (size_t)(it & 1) * MAXW * 256);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) zp[(w * 4 + v) * 64 + lane] = z[0][v];
+            for (int v = 0; v < 4; ++v) zp[(w * 4 + v) * 64 + lane] = z[v];
             __syncthreads();
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                if ((vmask >> v) & 1) {
+            SSN_TICK(3);
+            {
+                if (nslot) {
+                    constexpr int k = 0;
+                    const int v = w;
                     T sacc = 0;
-                    for (int ww = 0; ww < nw; ++ww) sacc += zp[(ww * 4 + v) * 64 + lane];
-                    z[0][v] = sacc;
+#pragma unroll
+                    for (int ww = 0; ww < MAXW; ++ww) {       // fixed order; waves beyond nw contribute zero
+                        const T val = zp[v * 64 + lane + ww * 256];      // slots of absent waves hold stale data
+                        sacc += (ww < nw) ? val : T(0);
+                    }
+                    const T uv = slot_epilogue<T, MODE>(sacc, a, rb * 16 + d_row<T>(g, v), q, lab_pre[k], pin_pre[k],
+                                                        loss, hits);
+                    if constexpr (HAS_C) zfull[v * 64 + lane] = uv;
                 }
             }
-            if (vmask) row_epilogue<T, 1, MODE, true>(z, a, rb, lane, loss, hits, u, vmask, lab_pre, pin_pre);
+            SSN_TICK(4);
             if constexpr (HAS_C) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if ((vmask >> v) & 1) zfull[v * 64 + lane] = u[0][v];
                 __syncthreads();
 #pragma unroll
-                for (int v = 0; v < 4; ++v) u[0][v] = zfull[v * 64 + lane];
+                for (int v = 0; v < 4; ++v) u[v] = zfull[v * 64 + lane];
             }
+            SSN_TICK(5);
         }
         ++it;
 
         if constexpr (HAS_C) {
 #pragma unroll
             for (int h = 0; h < NSB; ++h) {
-                if (h < nsb) {
 #pragma unroll
-                    for (int jj = 0; jj < 4; ++jj)
-                        if (4 * h + jj < NLD) *(pack *)(scr + q * STR + LF * jj + VEC * g) = xc[4 * h + jj];
-                        else *(pack *)(scr + q * STR + LF * jj + VEC * g) = pack{};
-                    __builtin_amdgcn_wave_barrier();
+                for (int jj = 0; jj < 4; ++jj)
+                    if (4 * h + jj < NLD) *(pack *)(scr + q * STR + LF * jj + VEC * g) = xc[4 * h + jj];
+                    else *(pack *)(scr + q * STR + LF * jj + VEC * g) = pack{};
+                __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const pack c = *(const pack *)(scr + d_row<T>(g, i) * STR + VEC * q);
+                for (int i = 0; i < 4; ++i) {
+                    const pack c = *(const pack *)(scr + d_row<T>(g, i) * STR + VEC * q);
 #pragma unroll
-                        for (int m = 0; m < VEC; ++m) G[h * VEC + m] = mfma16(c.v[m], u[0][i], G[h * VEC + m]);
-                    }
-                    __builtin_amdgcn_wave_barrier();
+                    for (int m = 0; m < VEC; ++m) G[h * VEC + m] = mfma16(c.v[m], u[i], G[h * VEC + m]);
                 }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int l = 0; l < LOADS_C; ++l)
+                    if (LOADS_A + h * LOADS_C + l < NLD) load_one(xbase_n, room_n, LOADS_A + h * LOADS_C + l, xn);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+        SSN_TICK(6);
     }
+#ifdef SSN_PROFILE_PHASES
+    if (blockIdx.x == 3 && lane == 0 && (w == 0 || w == 5))
+        printf("[phases] mode %d wave %d blocks %d: wait %lld issue %lld A %lld bar1 %lld epi %lld bar2 %lld C %lld cycles\n", MODE,
+               w, it, tph[0], tph[1], tph[2], tph[3], tph[4], tph[5], tph[6]);
+#endif
 
     if constexpr (HAS_C) {
-        T *part = (T *)a.part + (int64_t)blockIdx.x * p * K;
+        // feature of accumulator element v of tile (h, m): fs + h*SBF + VEC*d_row(g, v) + m; the lane part of it
+        // goes into one base pointer, the rest is a uniform offset
+        const int lane_row = d_row<T>(g, 0);                 // d_row(g, v) = lane_row + d_row(0, v)
+        T *pl = (T *)a.part + (int64_t)blockIdx.x * p * K + ((int64_t)fs + VEC * lane_row) * K + q;
+        const int64_t flane = fs + VEC * lane_row;
 #pragma unroll
-        for (int h = 0; h < NSB; ++h)
+        for (int h = 0; h < NSB; ++h) {
 #pragma unroll
             for (int m = 0; m < VEC; ++m)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int64_t f = fs + h * SBF + VEC * d_row<T>(g, v) + m;
-                    if (h < nsb && f < fend && q < K) part[f * K + q] = G[h * VEC + m][v];
+                    const int fo = h * SBF + VEC * d_row<T>(0, v) + m;       // uniform
+                    if (flane + fo < fend && q < K) pl[(int64_t)fo * K] = G[h * VEC + m][v];
                 }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
     // four partials per workgroup: wave w < 4 owns the rows of accumulator element w
     if (w < 4) {
@@ -645,53 +795,97 @@ __global__ __launch_bounds__(512) void dense_fused_kernel(RowsArgs a)
     }
 }
 
-constexpr int FUSED_MAX_FW = 128;    // features per wave the largest instantiation holds
-constexpr int FUSED_MAX_WAVES = 8;   // 2 waves per SIMD: 256 registers each
+// Register footprints the one-pass kernel is compiled for.  NLD vector loads and NSB transposition
+// sub-blocks bound the features a wave can own; MAXW waves per workgroup fix the register budget
+// (512 / ceil(MAXW/4) per lane).  Shapes are tried in this order.
+struct FusedShape { int nld, nsb, maxw; };
+template <typename T> struct FusedTable;
+template <> struct FusedTable<double> {
+    static constexpr int N = 3;
+    static constexpr int FIRST_C = 1;     // with a transposed product the 12-wave footprint spills: start at the 8-wave one
+    static constexpr FusedShape shape[N] = {{9, 3, 12}, {13, 4, 8}, {16, 4, 8}};     // 72 / 104 / 128 features per wave
+};
+template <> struct FusedTable<float> {
+    static constexpr int N = 3;
+    static constexpr int FIRST_C = 0;
+    static constexpr FusedShape shape[N] = {{4, 1, 8}, {7, 2, 8}, {8, 2, 8}};        // 64 / 112 / 128 features per wave
+};
+constexpr FusedShape FusedTable<double>::shape[];
+constexpr FusedShape FusedTable<float>::shape[];
 
-// Split p features over nw waves of fw features each (fw a multiple of the vector width).
-template <typename T> static void fused_shape(int64_t p, int *nw, int *fw)
+// Split p features over nw waves of fw features each (fw a multiple of the vector width) and pick the
+// instantiation; returns its index in FusedTable<T>, or -1 when no shape fits.
+template <typename T> static int fused_shape(int64_t p, bool has_c, int *nw, int *fw)
 {
     constexpr int VEC = 16 / sizeof(T);
-    int n = (int)((p + FUSED_MAX_FW - 1) / FUSED_MAX_FW);
-    if (n > 2) n = (n + 3) / 4 * 4;                 // same number of waves on each of the 4 SIMDs
-    int f = (int)((p + n - 1) / n);
-    f = (f + VEC - 1) / VEC * VEC;
-    *nw = n;
-    *fw = f;
+    constexpr int LF = 4 * VEC, SBF = 16 * VEC;
+    // single-wave shapes (p <= 128) have registers to spare with any footprint
+    for (int i = (has_c && p > 128) ? FusedTable<T>::FIRST_C : 0; i < FusedTable<T>::N; ++i) {
+        const FusedShape sh = FusedTable<T>::shape[i];
+        const int cap = (sh.nld * LF < sh.nsb * SBF) ? sh.nld * LF : sh.nsb * SBF;
+        int64_t n = (p + cap - 1) / cap;
+        if (n > 1) n = (n + 3) / 4 * 4;              // same number of waves on each of the 4 SIMDs
+        if (n > sh.maxw) continue;
+        int f = (int)((p + n - 1) / n);
+        f = (f + VEC - 1) / VEC * VEC;
+        if (f > cap) continue;
+        *nw = (int)n;
+        *fw = f;
+        return i;
+    }
+    return -1;
 }
 
-template <typename T> static size_t fused_lds_bytes(int nw, int fw, int K, bool has_c)
+template <typename T> static size_t fused_lds_bytes(int nw, int fw, int nld, int maxw, int K, bool has_c)
 {
     constexpr int VEC = 16 / sizeof(T);
     constexpr int LF = 4 * VEC, STR = 16 * VEC + VEC;
-    const int nld = (fw + LF - 1) / LF;
-    const size_t wrows = (size_t)(nw - 1) * fw + (size_t)nld * LF;
-    size_t elems = (wrows * K + VEC - 1) / VEC * VEC + (size_t)nw * 256 * (has_c ? 1 : 2) + 256;
+    const size_t ws = ((size_t)(nw - 1) * fw + (size_t)nld * LF) | 1;
+    size_t elems = (ws * K + VEC - 1) / VEC * VEC + (size_t)maxw * 256 * (has_c ? 1 : 2) + 256;
     if (has_c) elems += (size_t)nw * 16 * STR;
     return elems * sizeof(T);
 }
 
 template <typename T> static bool fused_ok(const RowsArgs &a)
 {
+    constexpr int VEC = 16 / sizeof(T);
     if (a.K > 16 || !vec_ok<T>(a.X, a.ldx)) return false;
-    int nw, fw;
-    fused_shape<T>(a.p, &nw, &fw);
-    return nw <= FUSED_MAX_WAVES && fw <= FUSED_MAX_FW && fused_lds_bytes<T>(nw, fw, a.K, true) <= 160 * 1024;
+    // whole-vector loads must stay inside a row's storage
+    if (a.p % VEC != 0 && a.ldx < (a.p + VEC - 1) / VEC * VEC) return false;
+    for (int c = 0; c < 2; ++c) {            // both kernel families (with / without transposed product) must fit
+        int nw, fw;
+        const int i = fused_shape<T>(a.p, c == 1, &nw, &fw);
+        if (i < 0) return false;
+        if (fused_lds_bytes<T>(nw, fw, FusedTable<T>::shape[i].nld, FusedTable<T>::shape[i].maxw, a.K, c == 1) > 160 * 1024)
+            return false;
+    }
+    return true;
 }
 
-// Can the one-pass kernel serve this shape?  (one 16-column class tile, 16-byte aligned rows, at most
-// 8 waves of 128 features, LDS within the 160 KB of a gfx950 compute unit)
+// Can the one-pass kernel serve this shape?  (one 16-column class tile, 16-byte aligned rows, a feature
+// split that fits one of the compiled register footprints, LDS within the 160 KB of a gfx950 compute unit)
 bool dense_fused_supported(int dtype, const RowsArgs &a)
 {
     return dtype == SSN_F32 ? fused_ok<float>(a) : fused_ok<double>(a);
 }
 
+// waves per workgroup the one-pass kernel would use for a.mode
+int dense_fused_waves(int dtype, const RowsArgs &a)
+{
+    int nw = 1, fw = 0;
+    const bool has_c = (a.mode == ROW_GRAD || a.mode == ROW_APPLY);
+    if (dtype == SSN_F32) fused_shape<float>(a.p, has_c, &nw, &fw);
+    else fused_shape<double>(a.p, has_c, &nw, &fw);
+    return nw;
+}
+
 int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus)
 {
-    int nw, fw;
-    if (dtype == SSN_F32) fused_shape<float>(a.p, &nw, &fw);
-    else fused_shape<double>(a.p, &nw, &fw);
-    int per_cu = 8 / nw;                          // aim at 8 waves per compute unit
+    int nw = 1, fw = 0;
+    const bool has_c = (a.mode == ROW_GRAD || a.mode == ROW_APPLY);
+    if (dtype == SSN_F32) fused_shape<float>(a.p, has_c, &nw, &fw);
+    else fused_shape<double>(a.p, has_c, &nw, &fw);
+    int per_cu = 8 / nw;                          // aim at 8 or more waves per compute unit
     if (per_cu < 1) per_cu = 1;
     const int64_t nblk = (a.nrows + 15) / 16;
     int64_t grid = (int64_t)num_cus * per_cu;
@@ -700,10 +894,10 @@ int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus)
     return (int)grid;
 }
 
-template <typename T, int MODE, int NLD, int NSB>
+template <typename T, int MODE, int NLD, int NSB, int MAXW>
 static hipError_t fused_launch_inst(const RowsArgs &a, int grid, int nw, size_t lds, hipStream_t st)
 {
-    auto kern = dense_fused_kernel<T, MODE, NLD, NSB>;
+    auto kern = dense_fused_kernel<T, MODE, NLD, NSB, MAXW>;
     static size_t lds_allowed = 48 * 1024;          // raise the dynamic LDS limit once per instantiation
     if (lds > lds_allowed) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -716,18 +910,21 @@ static hipError_t fused_launch_inst(const RowsArgs &a, int grid, int nw, size_t 
 
 template <typename T, int MODE> static hipError_t fused_launch_mode(RowsArgs a, int grid, hipStream_t st)
 {
-    constexpr int VEC = 16 / sizeof(T);
-    constexpr int LF = 4 * VEC, SBF = 16 * VEC;
+    typedef FusedTable<T> TB;
     int nw, fw;
-    fused_shape<T>(a.p, &nw, &fw);
-    a.fw = fw;
     constexpr bool has_c = (MODE == ROW_GRAD || MODE == ROW_APPLY);
-    const size_t lds = fused_lds_bytes<T>(nw, fw, a.K, has_c);
-    // three register footprints: <= 64, <= 104 (f64) / 112 (f32), <= 128 features per wave
-    constexpr int MID_LD = (sizeof(T) == 8) ? 13 : 7;
-    if (fw <= 64) return fused_launch_inst<T, MODE, 64 / LF, 64 / SBF>(a, grid, nw, lds, st);
-    if (fw <= MID_LD * LF) return fused_launch_inst<T, MODE, MID_LD, 128 / SBF>(a, grid, nw, lds, st);
-    return fused_launch_inst<T, MODE, 128 / LF, 128 / SBF>(a, grid, nw, lds, st);
+    const int i = fused_shape<T>(a.p, has_c, &nw, &fw);
+    if (i < 0) return hipErrorInvalidValue;
+    a.fw = fw;
+    const size_t lds = fused_lds_bytes<T>(nw, fw, TB::shape[i].nld, TB::shape[i].maxw, a.K, has_c);
+    if (nw == 1) {      // single-wave workgroups: no cross-wave reduction compiled in
+        if (i == 0) return fused_launch_inst<T, MODE, TB::shape[0].nld, TB::shape[0].nsb, 1>(a, grid, nw, lds, st);
+        if (i == 1) return fused_launch_inst<T, MODE, TB::shape[1].nld, TB::shape[1].nsb, 1>(a, grid, nw, lds, st);
+        return fused_launch_inst<T, MODE, TB::shape[2].nld, TB::shape[2].nsb, 1>(a, grid, nw, lds, st);
+    }
+    if (i == 0) return fused_launch_inst<T, MODE, TB::shape[0].nld, TB::shape[0].nsb, TB::shape[0].maxw>(a, grid, nw, lds, st);
+    if (i == 1) return fused_launch_inst<T, MODE, TB::shape[1].nld, TB::shape[1].nsb, TB::shape[1].maxw>(a, grid, nw, lds, st);
+    return fused_launch_inst<T, MODE, TB::shape[2].nld, TB::shape[2].nsb, TB::shape[2].maxw>(a, grid, nw, lds, st);
 }
 
 template <typename T> static hipError_t fused_dispatch(const RowsArgs &a, int grid, hipStream_t st)

@@ -141,9 +141,19 @@ XtuArgs xtu_base(const ssn_ctx *c)
     return a;
 }
 
+// The one-pass kernel serves a launch when the shape allows it and it pays: always for the modes with a
+// transposed product; for the margins-only modes only with a multi-wave feature split (for narrow
+// matrices the wave-per-row-block kernel is faster).
+bool use_fused(const ssn_ctx *c, const RowsArgs &a)
+{
+    if (!c->fused) return false;
+    if (a.mode == ROW_GRAD || a.mode == ROW_APPLY) return true;
+    return dense_fused_waves(c->d.dtype, a) > 1;
+}
+
 int launch_rows(ssn_ctx *c, const RowsArgs &a, int *nparts)
 {
-    if (c->fused) {
+    if (use_fused(c, a)) {
         const int grid = dense_fused_grid(c->d.dtype, a, c->num_cus);
         if (grid * 4 > c->wave_parts || grid > c->max_chunks) return fail(c, SSN_E_INVALID_ARG, "internal: partial overflow");
         SSN_HIP(c, launch_dense_fused(c->d.dtype, a, grid, c->st));
@@ -397,6 +407,7 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
         c->max_chunks = (int)(((int64_t)c->num_cus * 8 + nft - 1) / nft);
         RowsArgs probe = rows_base(c);
         probe.nrows = (int64_t)1 << 40;
+        probe.mode = ROW_GRAD;                                 // the family that writes partials
         const char *force = getenv("SSN_DENSE_PATH");          // "split" forces the two-kernel path
         c->fused = dense_fused_supported(d->dtype, probe) && !(force && strcmp(force, "split") == 0);
         if (c->fused) {

@@ -97,6 +97,7 @@ hipError_t launch_dense_rows(int dtype, const RowsArgs &a, int blocks, hipStream
 hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st);
 bool dense_fused_supported(int dtype, const RowsArgs &a);
 int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus);
+int dense_fused_waves(int dtype, const RowsArgs &a);
 hipError_t launch_dense_fused(int dtype, const RowsArgs &a, int grid, hipStream_t st);
 hipError_t launch_csr_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
 hipError_t launch_csr_scatter(int dtype, const XtuArgs &a, double scale, void *out, int64_t ldo, hipStream_t st);
