@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-other-dtype", action="store_true", help="skip the secondary-dtype figures")
     ap.add_argument("--hv-calls", type=int, default=200)
+    ap.add_argument("--pmc", action="store_true",
+                    help="counter-collection mode for `rocprofv3 --pmc`: a few launches of every hot kernel, a plain "
+                         "streaming read of X and a plain copy of X (calibration), nothing else")
     return ap.parse_args()
 
 
@@ -175,6 +178,29 @@ def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
     return out
 
 
+def pmc_sequence(data, dtype_name):
+    """Three launches of each hot kernel plus two calibration kernels of known traffic (read n*p*e bytes;
+    read and write n*p*e bytes), for per-dispatch hardware counters."""
+    import torch
+    from paper_1802_09113_amd import synth
+    from paper_1802_09113_amd.binding import Context
+    tdt = torch.float64 if dtype_name == "f64" else torch.float32
+    n, p, C, K, nS = data["n"], data["p"], data["C"], data["K"], data["nS"]
+    X = torch.from_numpy(data["X"]).to("cuda:0").to(tdt)
+    labels = torch.from_numpy(data["labels"]).to("cuda:0")
+    ctx = Context(labels, C, data["lam"], X=X)
+    W = torch.from_numpy(synth.probe(p, K, sub=1, scale=0.05)).to("cuda:0").to(tdt)
+    V = torch.from_numpy(synth.probe(p, K, sub=2)).to("cuda:0").to(tdt)
+    ctx.ssn_hess_prepare(W, torch.from_numpy(synth.sample_rows(n, nS)).to("cuda:0"))
+    for which in (0, 1, 2, 3, 4, 5):
+        ctx.ssn_time_kernel(which, V if which in (3, 4) else W, 3)
+    Y = torch.empty_like(X)
+    for _ in range(3):
+        Y.copy_(X)
+    torch.cuda.synchronize()
+    ctx.close()
+
+
 def cpu_baseline(data, budget_s=12.0):
     """The oracle as it stands, single thread, on a bounded sample of the same workload."""
     import numpy as np
@@ -214,6 +240,9 @@ def main():
     assert data["layout"] == "dense", "bench.py times the dense workloads"
     sys.stderr.write(f"[bench] generated {data['name']} {data['n']}x{data['p']} C={data['C']} in "
                      f"{time.perf_counter() - t_gen:.1f}s\n")
+    if args.pmc:
+        pmc_sequence(data, args.dtype)
+        return
     main_res = measure(data, args.dtype, args.steps, args.warmup, args.hv_calls)
     sys.stderr.write(f"[bench] {args.dtype} measured\n")
     other = None
