@@ -21,6 +21,15 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X datasheet HBM3E bandwidth
 
+# HBM bytes per launch (fetched + written) measured with `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` on the
+# default workload, scaled by the calibration kernels (profiles/dense_one_pass_image_like_f64_hbm_traffic_pmc.md).
+# Counters cannot be read from inside this script; other workloads / dtypes report null.
+MEASURED_TRAFFIC = {
+    ("image_like", "f64", "dense_fused_kernel<OBJ>"): 377.7e6,
+    ("image_like", "f64", "dense_fused_kernel<GRAD>"): 426.0e6 + 24.9e6,
+    ("image_like", "f64", "dense_fused_kernel<APPLY>"): 19.9e6 + 10.6e6,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -258,7 +267,8 @@ def main():
                 3: data["T"] * k[3]["ms"], 4: data["T"] * k[4]["ms"]}
     dom = max((w for w in per_step if "GBps" in k[w]), key=per_step.get)
     roof = {"bound": "hbm", "kernel": k[dom]["kernel"], "achieved": k[dom]["GBps"], "peak": HBM_PEAK_GBS,
-            "unit": "GB/s", "frac": k[dom]["frac"], "traffic": None,
+            "unit": "GB/s", "frac": k[dom]["frac"],
+            "traffic": MEASURED_TRAFFIC.get((data["name"], args.dtype, k[dom]["kernel"])) if args.n is None else None,
             "ms_per_launch": k[dom]["ms"], "algorithmic_bytes_per_launch": k[dom]["algorithmic_GB"] * 1e9,
             "share_of_step_kernel_time": per_step[dom] / sum(per_step.values()),
             "stream_read_GBps": main_res["stream_read"]["GBps"],
