@@ -517,7 +517,11 @@ __device__ __forceinline__ T slot_epilogue(T z, const RowsArgs &a, int64_t sv, i
 //   5. phase C: the wave's X tile is transposed through a wave-private LDS scratch (rows become the
 //      contraction index) and G_slice (fw x 16) += X_tile^T * U accumulates in registers.
 // At the end each workgroup writes its p x K partial; the finalize kernel adds them in a fixed order.
-template <typename T, int MODE, int NLD, int NSB, int MAXW>
+//
+// ONE: every workgroup has at most one row block (sampled products on a few thousand rows).  Each element
+// of M is then used once per workgroup, so the lanes load their W operands straight from global memory
+// into registers instead of staging M in LDS, and nothing is prefetched for a next block.
+template <typename T, int MODE, int NLD, int NSB, int MAXW, bool ONE>
 __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
 {
     if (a.skip && *a.skip) return;
@@ -531,6 +535,9 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     constexpr bool HAS_C = (MODE == ROW_GRAD || MODE == ROW_APPLY);
     constexpr bool NEED_LAB = (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_PRED);
 
+#ifdef SSN_PROFILE_PHASES
+    const long long t_entry = clock64();
+#endif
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, nw = blockDim.x >> 6;
     const int q = lane & 15, g = lane >> 4;
@@ -588,7 +595,81 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     int64_t rb = blockIdx.x;
 #pragma unroll
     for (int j = 0; j < NLD; ++j) xn[j] = pack{};
-    if (rb < nblk) load_block(block_row(rb), xn);
+    // A wave's memory counter retires in order, so the prologue issues its loads in the order their results
+    // are needed: the row index of the first block, the first batch of M (independent of everything), the
+    // first tile (needs the row index), then the small per-row data.
+    const int64_t xr0 = (rb < nblk) ? block_row(rb) : 0;
+
+    // LDS copy of M: thread t copies elements t, t + blockDim, .. of the row-major wrows x K block, WB loads in
+    // flight at a time; (wf, wc) is the feature / class of the element it copies next
+    constexpr int WB = 16;
+    const T *M = (const T *)a.M;
+    const int wtotal = wrows * K;
+    const int wstep_f = (int)blockDim.x / K, wstep_c = (int)blockDim.x - wstep_f * K;
+    int wf = tid / K, wc = tid - wf * K, widx = tid;
+    // source offset and LDS position of that element, advanced by additions only
+    int64_t wsrc = (int64_t)wf * a.ldm + wc;
+    int wpos = wc * ws + wf;
+    const int64_t wsrc_step = (int64_t)wstep_f * a.ldm + wstep_c, wsrc_wrap = a.ldm - K;
+    const int wpos_step = wstep_c * ws + wstep_f, wpos_wrap = 1 - K * ws;
+    T wtmp[WB];
+    int wdst[WB];
+    auto w_load = [&]() {
+#pragma unroll
+        for (int uu = 0; uu < WB; ++uu) {
+            const bool in = widx < wtotal;
+            const bool ok = in && wf < p;
+            wtmp[uu] = M[ok ? wsrc : 0];
+            wdst[uu] = in ? (ok ? wpos : -2 - wpos) : -1;    // >= 0: copy; <= -2: store zero; -1: nothing
+            widx += (int)blockDim.x;
+            wc += wstep_c;
+            wf += wstep_f;
+            wsrc += wsrc_step;
+            wpos += wpos_step;
+            if (wc >= K) {
+                wc -= K;
+                ++wf;
+                wsrc += wsrc_wrap;
+                wpos += wpos_wrap;
+            }
+        }
+    };
+    auto w_store = [&]() {
+#pragma unroll
+        for (int uu = 0; uu < WB; ++uu) {
+            if (wdst[uu] >= 0) wl[wdst[uu]] = wtmp[uu];
+            else if (wdst[uu] <= -2) wl[-2 - wdst[uu]] = T(0);
+        }
+    };
+#ifdef SSN_PROFILE_PHASES
+    const long long tp0 = clock64();
+#endif
+    // ONE: this lane's W operands, M[fs + LF*j + VEC*g + m][qc], zero beyond p
+    T bd[ONE ? NLD : 1][VEC];
+    if constexpr (ONE) {
+        const int64_t f0 = fs + VEC * g;
+#pragma unroll
+        for (int j = 0; j < NLD; ++j)
+#pragma unroll
+            for (int m = 0; m < VEC; ++m) {
+                const int64_t ff = f0 + LF * j + m;
+                bd[j][m] = M[(ff < p) ? (ff * a.ldm + qc) : 0];
+            }
+    } else {
+        w_load();
+    }
+#ifdef SSN_PROFILE_PHASES
+    __builtin_amdgcn_sched_barrier(0);
+    const long long tp1 = clock64();
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+    if (rb < nblk) load_block(xr0, xn);
+#ifdef SSN_PROFILE_PHASES
+    __builtin_amdgcn_sched_barrier(0);
+    const long long tp2 = clock64();
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+
     // accumulator elements whose per-row work this wave does.  MAXW == 1: the single wave does all four in
     // registers.  Otherwise the workgroup has at least four waves and wave w < 4 does element w.
     constexpr int SLOTS = (MAXW == 1) ? 4 : 1;
@@ -614,28 +695,30 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     // data row of this lane's A-operand row in the NEXT block (needed when that block's loads are issued)
     int64_t xr_n = (rb + gridDim.x < nblk) ? block_row(rb + gridDim.x) : 0;
 
-    {
-        // LDS copy of M: batches of 8 independent loads per thread
-        const T *M = (const T *)a.M;
-        const int total = wrows * K;
-        for (int base = 0; base < total; base += 8 * (int)blockDim.x) {
-            T tmp[8];
+#ifdef SSN_PROFILE_PHASES
+    __builtin_amdgcn_sched_barrier(0);
+    const long long tp3 = clock64();
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+    if constexpr (ONE) {
+        const int64_t f0 = fs + VEC * g;
 #pragma unroll
-            for (int uu = 0; uu < 8; ++uu) {
-                const int idx = base + uu * (int)blockDim.x + tid;
-                const int f = idx / K, c = idx - f * K;
-                const bool ok = idx < total && f < p;
-                const T val = M[ok ? ((int64_t)f * a.ldm + c) : 0];
-                tmp[uu] = ok ? val : T(0);
-            }
+        for (int j = 0; j < NLD; ++j)
 #pragma unroll
-            for (int uu = 0; uu < 8; ++uu) {
-                const int idx = base + uu * (int)blockDim.x + tid;
-                if (idx < total) wl[(idx % K) * ws + idx / K] = tmp[uu];
-            }
+            for (int m = 0; m < VEC; ++m) bd[j][m] = (cvalid && f0 + LF * j + m < p) ? bd[j][m] : T(0);
+    } else {
+        w_store();
+        for (int base = WB * (int)blockDim.x; base < wtotal; base += WB * (int)blockDim.x) {
+            w_load();
+            w_store();
         }
     }
-    __syncthreads();
+#ifdef SSN_PROFILE_PHASES
+    __builtin_amdgcn_sched_barrier(0);
+    const long long tp4 = clock64();
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+    if constexpr (!ONE) __syncthreads();
 
     v4 G[HAS_C ? NT : 1];
 #pragma unroll
@@ -648,6 +731,7 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #define SSN_TICK(i) do { __builtin_amdgcn_sched_barrier(0); const long long t_ = clock64(); tph[i] += t_ - tlast; tlast = t_; __builtin_amdgcn_sched_barrier(0); } while (0)
     long long tlast = clock64();
+    const long long t_loop = tlast;
 #else
 #define SSN_TICK(i) do { } while (0)
 #endif
@@ -674,8 +758,10 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
             lab_pre[k] = lab_n[k];
             pin_pre[k] = pin_n[k];
         }
-        load_meta(rbn);
-        xr_n = (rbn + gridDim.x < nblk) ? block_row(rbn + gridDim.x) : 0;
+        if constexpr (!ONE) {
+            load_meta(rbn);
+            xr_n = (rbn + gridDim.x < nblk) ? block_row(rbn + gridDim.x) : 0;
+        }
         const T *xbase_n = X + xr_next * a.ldx + fs + VEC * g;
         const int64_t room_n = has_next ? (a.ldx - fs - VEC * g) : 0;      // no next block: every load is skipped
         constexpr int LOADS_A = HAS_C ? (NLD + 1) / 2 : NLD;              // issued during phase A, the rest in phase C
@@ -685,17 +771,32 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
         // phase A (fp32: two accumulators break the dependent MFMA chain; fp64 has no registers to spare)
         constexpr bool TWO_ACC = sizeof(T) == 4;
         v4 z0 = v4{0, 0, 0, 0}, z1 = v4{0, 0, 0, 0};
+        // W operands come from LDS two steps ahead of the MFMAs that use them (a ring of three register sets)
+        T bq[3][VEC];
+        if constexpr (!ONE) {
+#pragma unroll
+            for (int jj = 0; jj < 2 && jj < NLD; ++jj)
+#pragma unroll
+                for (int m = 0; m < VEC; ++m) bq[jj][m] = wlane[LF * jj + m];
+        }
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
+            if constexpr (!ONE) {
+                if (j + 2 < NLD) {
+#pragma unroll
+                    for (int m = 0; m < VEC; ++m) bq[(j + 2) % 3][m] = wlane[LF * (j + 2) + m];
+                }
+            }
 #pragma unroll
             for (int m = 0; m < VEC; ++m) {
-                const T bw = wlane[LF * j + m];
-                const T b = cvalid ? bw : T(0);
+                const T b = ONE ? bd[j][m] : (cvalid ? bq[j % 3][m] : T(0));
                 if (TWO_ACC && ((j * VEC + m) & 1)) z1 = mfma16(xc[j].v[m], b, z1);
                 else z0 = mfma16(xc[j].v[m], b, z0);
             }
-            if (j < LOADS_A) load_one(xbase_n, room_n, j, xn);
-            __builtin_amdgcn_sched_barrier(0);       // keep this interleaving (and the W reads from piling up)
+            if constexpr (!ONE) {
+                if (j < LOADS_A) load_one(xbase_n, room_n, j, xn);
+                __builtin_amdgcn_sched_barrier(0);   // keep this interleaving (and the W reads from piling up)
+            }
         }
         v4 z = TWO_ACC ? (z0 + z1) : z0, u = v4{0, 0, 0, 0};
         SSN_TICK(2);
@@ -749,18 +850,18 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
                     for (int m = 0; m < VEC; ++m) G[h * VEC + m] = mfma16(c.v[m], u[i], G[h * VEC + m]);
                 }
                 __builtin_amdgcn_wave_barrier();
+                if constexpr (!ONE) {
 #pragma unroll
-                for (int l = 0; l < LOADS_C; ++l)
-                    if (LOADS_A + h * LOADS_C + l < NLD) load_one(xbase_n, room_n, LOADS_A + h * LOADS_C + l, xn);
+                    for (int l = 0; l < LOADS_C; ++l)
+                        if (LOADS_A + h * LOADS_C + l < NLD) load_one(xbase_n, room_n, LOADS_A + h * LOADS_C + l, xn);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
         SSN_TICK(6);
     }
 #ifdef SSN_PROFILE_PHASES
-    if (blockIdx.x == 3 && lane == 0 && (w == 0 || w == 5))
-        printf("[phases] mode %d wave %d blocks %d: wait %lld issue %lld A %lld bar1 %lld epi %lld bar2 %lld C %lld cycles\n", MODE,
-               w, it, tph[0], tph[1], tph[2], tph[3], tph[4], tph[5], tph[6]);
+    const long long t_loop_end = clock64();
 #endif
 
     if constexpr (HAS_C) {
@@ -793,6 +894,17 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
             if (w == 0 && lane > 0 && lane < 4 && lane >= nw) a.hit_part[blockIdx.x * 4 + lane] = 0;
         }
     }
+#ifdef SSN_PROFILE_PHASES
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    const long long t_end = clock64();
+    if (blockIdx.x == 3 && lane == 0 && (w == 0 || w == 5)) {
+        printf("[phases] mode %d wave %d blocks %d: wait %lld issue %lld A %lld bar1 %lld epi %lld bar2 %lld C %lld cycles\n", MODE,
+               w, it, tph[0], tph[1], tph[2], tph[3], tph[4], tph[5], tph[6]);
+        printf("[timeline] mode %d wave %d: prologue %lld (to M loads %lld, issue M %lld, issue tile %lld, meta %lld, M to LDS %lld, sync %lld) loop %lld store %lld cycles\n",
+               MODE, w, t_loop - t_entry, tp0 - t_entry, tp1 - tp0, tp2 - tp1, tp3 - tp2, tp4 - tp3, t_loop - tp4,
+               t_loop_end - t_loop, t_end - t_loop_end);
+    }
+#endif
 }
 
 // Register footprints the one-pass kernel is compiled for.  NLD vector loads and NSB transposition
@@ -894,10 +1006,10 @@ int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus)
     return (int)grid;
 }
 
-template <typename T, int MODE, int NLD, int NSB, int MAXW>
-static hipError_t fused_launch_inst(const RowsArgs &a, int grid, int nw, size_t lds, hipStream_t st)
+template <typename T, int MODE, int NLD, int NSB, int MAXW, bool ONE>
+static hipError_t fused_launch_kern(const RowsArgs &a, int grid, int nw, size_t lds, hipStream_t st)
 {
-    auto kern = dense_fused_kernel<T, MODE, NLD, NSB, MAXW>;
+    auto kern = dense_fused_kernel<T, MODE, NLD, NSB, MAXW, ONE>;
     static size_t lds_allowed = 48 * 1024;          // raise the dynamic LDS limit once per instantiation
     if (lds > lds_allowed) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -906,6 +1018,16 @@ static hipError_t fused_launch_inst(const RowsArgs &a, int grid, int nw, size_t 
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * nw), lds, st, a);
     return hipGetLastError();
+}
+
+template <typename T, int MODE, int NLD, int NSB, int MAXW>
+static hipError_t fused_launch_inst(const RowsArgs &a, int grid, int nw, size_t lds, hipStream_t st)
+{
+    // the one-block-per-workgroup variant exists for the modes that run on a Hessian sample
+    if constexpr (MODE == ROW_APPLY || MODE == ROW_PREP) {
+        if ((a.nrows + 15) / 16 <= grid) return fused_launch_kern<T, MODE, NLD, NSB, MAXW, true>(a, grid, nw, lds, st);
+    }
+    return fused_launch_kern<T, MODE, NLD, NSB, MAXW, false>(a, grid, nw, lds, st);
 }
 
 template <typename T, int MODE> static hipError_t fused_launch_mode(RowsArgs a, int grid, hipStream_t st)

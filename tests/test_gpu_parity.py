@@ -94,6 +94,24 @@ def test_hessvec_multiset_sample_and_single_row(data_cache, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_hessvec_sample_of_several_row_blocks_per_workgroup(data_cache, dtype):
+    # 6000 sample rows = 375 row blocks, more than one per workgroup of the one-pass kernel (whose
+    # one-block-per-workgroup variant serves the smaller samples of the other tests)
+    d = data_cache(1, 5000)
+    pair = Pair(d, dtype)
+    rng = np.random.default_rng(5)
+    S = np.concatenate([rng.permutation(5000), rng.permutation(5000)[:1000]]).astype(np.int32)
+    Wh, Wd = _weights(pair, 1, 0.1)
+    Vh, Vd = _weights(pair, 2, 1.0)
+    print(f"[case] several blocks per workgroup nS={S.size} dtype={dtype}", flush=True)
+    HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+    torch.cuda.synchronize()
+    ref = pair.oracle.hessvec(Wh, S, Vh)
+    assert rel_err(pair.host(HV), ref) <= TOL[dtype]
+    pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 @pytest.mark.parametrize("scale", ["mean", "sum"])
 def test_scaling_modes_and_padded_leading_dimensions(data_cache, scale, dtype):
     d = data_cache(0, 2000)
