@@ -475,7 +475,11 @@ __device__ __forceinline__ T slot_epilogue(T z, const RowsArgs &a, int64_t sv, i
     const T NEG = -std::numeric_limits<T>::infinity();
     if constexpr (MODE == ROW_APPLY) {
         const T t = row16_sum(pin * z);                    // pin is zero in padded columns
-        return valid ? (pin * z - pin * t) : T(0);
+        const T u = valid ? (pin * z - pin * t) : T(0);
+        // z_i . u_i of the row: summed over the sample it is V^T (X_S^T U), the curvature term CG needs
+        const T zu = row16_sum(z * u);
+        if (valid && q == 0) loss += (double)zu;
+        return u;
     }
     const T zmax = row16_max(cv ? z : NEG);
     if constexpr (MODE == ROW_PRED) {
@@ -884,7 +888,7 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     }
     // four partials per workgroup: wave w < 4 owns the rows of accumulator element w
     if (w < 4) {
-        if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD) {
+        if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_APPLY) {
             for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off);
             if (lane == 0) a.loss_part[blockIdx.x * 4 + w] = loss;
             if (w == 0 && lane > 0 && lane < 4 && lane >= nw) a.loss_part[blockIdx.x * 4 + lane] = 0.0;
@@ -1062,7 +1066,7 @@ template <typename T> static hipError_t fused_dispatch(const RowsArgs &a, int gr
 }
 
 // Launch the one-pass kernel on `grid` workgroups; ROW_GRAD / ROW_APPLY leave `grid` partials in a.part,
-// ROW_OBJ / ROW_GRAD `grid` loss partials, ROW_PRED `grid` hit partials.
+// ROW_OBJ / ROW_GRAD 4 * `grid` loss partials (ROW_APPLY: of sum_i z_i . u_i there), ROW_PRED 4 * `grid` hit partials.
 hipError_t launch_dense_fused(int dtype, const RowsArgs &a, int grid, hipStream_t st)
 {
     return dtype == SSN_F32 ? fused_dispatch<float>(a, grid, st) : fused_dispatch<double>(a, grid, st);

@@ -36,7 +36,7 @@ struct ssn_ctx {
     double *loss_part = nullptr;
     int32_t *hit_part = nullptr;
     int wave_parts = 0;
-    double *red_a = nullptr, *red_b = nullptr;
+    double *red_a = nullptr, *red_b = nullptr, *red_c = nullptr;
     double *scal_dev = nullptr;
     int32_t *int_dev = nullptr;
     double *host_pin = nullptr;   // pinned staging for scalar results
@@ -293,7 +293,19 @@ int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f)
     return SSN_OK;
 }
 
-int hess_apply_impl(ssn_ctx *c, const void *V, void *HV, bool want_dot, int *ndot, const int32_t *skip)
+// state of the CG iteration a product may carry behind it on the one-pass path (Alg. 2 lines 7-9)
+struct CgFuse {
+    CgSlot *cur;
+    void *pv, *r;
+    int n_ss;                // partials of s.s waiting in red_c
+    double *trace;
+};
+
+// HV = H_S V.  want_dot: partials of <HV, V> into red_b (count in *ndot).  cg (nullable): V is the CG
+// direction s; on the one-pass path the sum of the partials then also does lines 7-9 (HV is not stored,
+// partials of the new r.r go to red_a, their count to *ndot) and *cg_done is set.
+int hess_apply_impl(ssn_ctx *c, const void *V, void *HV, bool want_dot, int *ndot, const int32_t *skip,
+                    const CgFuse *cg = nullptr, bool *cg_done = nullptr)
 {
     RowsArgs a = rows_base(c);
     a.S = c->S;
@@ -305,7 +317,34 @@ int hess_apply_impl(ssn_ctx *c, const void *V, void *HV, bool want_dot, int *ndo
     a.skip = skip;
     a.part = c->part;
     int nparts = 0;
+    if (cg_done) *cg_done = false;
     SSN_TRY(launch_rows(c, a, &nparts));
+    if (c->fused && cg) {
+        FinArgs f{};
+        f.part = c->part;
+        f.nchunks = nparts / 4;
+        f.p = c->d.p;
+        f.K = c->K;
+        f.scale = scale_sample(c);
+        f.lambda = c->d.lambda;
+        f.M = V;
+        f.ldm = c->d.ldw;
+        FinCgArgs g{};
+        g.cur = cg->cur;
+        g.pv = cg->pv;
+        g.r = cg->r;
+        g.zu_part = c->loss_part;
+        g.n_zu = nparts;
+        g.ss_part = c->red_c;
+        g.n_ss = cg->n_ss;
+        g.rr_part = c->red_a;
+        g.trace_k = cg->trace;
+        const int fb = finalize_blocks(c->d.p, c->K);
+        SSN_HIP(c, launch_finalize_cg(c->d.dtype, f, g, fb, c->st));
+        if (ndot) *ndot = fb;
+        if (cg_done) *cg_done = true;
+        return SSN_OK;
+    }
     if (c->fused) return finalize_dense(c, nparts / 4, scale_sample(c), V, HV, want_dot, ndot, skip);
     return transposed_product(c, c->S, c->nS, scale_sample(c), V, HV, want_dot, ndot, skip);
 }
@@ -342,7 +381,7 @@ int ssn_destroy(ssn_ctx *c)
 {
     if (!c) return SSN_E_INVALID_ARG;
     (void)hipStreamSynchronize(c->st);
-    void *dev[] = {c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->scal_dev, c->int_dev,
+    void *dev[] = {c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->red_c, c->scal_dev, c->int_dev,
                    c->cg_p, c->cg_r, c->cg_s, c->cg_Hs, c->trial, c->grad, c->dir, c->slots, c->trace_dev};
     for (void *p : dev)
         if (p) (void)hipFree(p);
@@ -399,6 +438,7 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
     CREATE_HIP(hipMalloc((void **)&c->hit_part, sizeof(int32_t) * c->wave_parts));
     CREATE_HIP(hipMalloc((void **)&c->red_a, sizeof(double) * RED_MAX_PARTS));
     CREATE_HIP(hipMalloc((void **)&c->red_b, sizeof(double) * RED_MAX_PARTS));
+    CREATE_HIP(hipMalloc((void **)&c->red_c, sizeof(double) * RED_MAX_PARTS));
     CREATE_HIP(hipMalloc((void **)&c->scal_dev, sizeof(double) * 8));
     CREATE_HIP(hipMalloc((void **)&c->int_dev, sizeof(int32_t) * 8));
     CREATE_HIP(hipHostMalloc((void **)&c->host_pin, 4096));
@@ -526,15 +566,19 @@ int ssn_cg(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out, ssn_
     v.s = c->cg_s;
     v.Hs = c->cg_Hs;
     v.pbest = P_out;
-    SSN_HIP(c, launch_cg_init(c->d.dtype, v, c->red_a, vb, c->st));
+    SSN_HIP(c, launch_cg_init(c->d.dtype, v, c->red_a, c->red_c, vb, c->st));
     SSN_HIP(c, launch_cg_init_state(c->red_a, vb, c->slots, c->st));
     for (int k = 0; k < T; ++k) {
         const int32_t *skip = (const int32_t *)((const char *)(c->slots + k) + offsetof(CgSlot, done));
         int ndot = 0;
-        SSN_TRY(hess_apply_impl(c, c->cg_s, c->cg_Hs, true, &ndot, skip));
-        SSN_HIP(c, launch_cg_step1(c->d.dtype, v, c->slots + k, c->red_b, ndot, c->red_a, c->trace_dev + 3 * k, vb, c->st));
-        SSN_HIP(c, launch_cg_step2(c->d.dtype, v, c->slots + k, c->slots + k + 1, c->red_a, vb, theta,
-                                   c->trace_dev + 3 * k, vb, c->st));
+        bool stepped = false;
+        const CgFuse cf{c->slots + k, c->cg_p, c->cg_r, vb, c->trace_dev + 3 * k};
+        SSN_TRY(hess_apply_impl(c, c->cg_s, c->cg_Hs, true, &ndot, skip, &cf, &stepped));
+        // one-pass path: lines 7-9 are done and red_a holds ndot partials of the new r.r
+        if (!stepped)
+            SSN_HIP(c, launch_cg_step1(c->d.dtype, v, c->slots + k, c->red_b, ndot, c->red_a, c->trace_dev + 3 * k, vb, c->st));
+        SSN_HIP(c, launch_cg_step2(c->d.dtype, v, c->slots + k, c->slots + k + 1, c->red_a, stepped ? ndot : vb, theta,
+                                   c->trace_dev + 3 * k, c->red_c, vb, c->st));
     }
     CgSlot fin;
     std::vector<double> tr((size_t)3 * (T > 0 ? T : 1));

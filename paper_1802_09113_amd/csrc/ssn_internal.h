@@ -143,11 +143,26 @@ struct CgVecs {
     void *pv, *r, *s, *Hs, *pbest;
 };
 
-hipError_t launch_cg_init(int dtype, const CgVecs &v, double *gg_part, int blocks, hipStream_t st);
+// ss_part (nullable) receives the same partials again: s_0 = -g
+hipError_t launch_cg_init(int dtype, const CgVecs &v, double *gg_part, double *ss_part, int blocks, hipStream_t st);
 hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0, hipStream_t st);
 hipError_t launch_cg_step1(int dtype, const CgVecs &v, const CgSlot *cur, const double *sHs_part, int n_sHs,
                            double *rr_part, double *trace_k, int blocks, hipStream_t st);
+// ss_part (nullable): one partial of s.s per block for the new direction
 hipError_t launch_cg_step2(int dtype, const CgVecs &v, const CgSlot *cur, CgSlot *next, const double *rr_part,
-                           int n_rr, double theta, double *trace_k, int blocks, hipStream_t st);
+                           int n_rr, double theta, double *trace_k, double *ss_part, int blocks, hipStream_t st);
+
+// one-pass path: sum of the product's partials fused with lines 7-9 (see finalize_cg_kernel)
+struct FinCgArgs {
+    CgSlot *cur;
+    void *pv, *r;            // on the leading dimension FinArgs::ldm, like s = FinArgs::M
+    const double *zu_part;   // per-wave partials of sum_i z_i . u_i left by the product's launch
+    int n_zu;
+    const double *ss_part;   // partials of s.s
+    int n_ss;
+    double *rr_part;         // out: one partial of the new r.r per block
+    double *trace_k;         // nullable
+};
+hipError_t launch_finalize_cg(int dtype, const FinArgs &a, const FinCgArgs &g, int blocks, hipStream_t st);
 
 }  // namespace ssn

@@ -8,17 +8,17 @@
 
 namespace ssn {
 
+// sum over the block's VEC_BLOCK threads, the same bits in every thread: a butterfly inside each wave,
+// then the four wave sums in order
 __device__ __forceinline__ double block_sum(double v)
 {
-    __shared__ double sm[VEC_BLOCK];
-    const int t = threadIdx.x;
-    sm[t] = v;
+    __shared__ double sm[VEC_BLOCK / 64];
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
     __syncthreads();
-    for (int s = VEC_BLOCK / 2; s > 0; s >>= 1) {
-        if (t < s) sm[t] += sm[t + s];
-        __syncthreads();
-    }
-    const double r = sm[0];
+    double r = sm[0];
+#pragma unroll
+    for (int k = 1; k < VEC_BLOCK / 64; ++k) r += sm[k];
     __syncthreads();
     return r;
 }
@@ -110,6 +110,79 @@ hipError_t launch_finalize(int dtype, const FinArgs &a, int blocks, hipStream_t 
 {
     if (dtype == SSN_F32) finalize_launch<float>(a, blocks, st);
     else finalize_launch<double>(a, blocks, st);
+    return hipGetLastError();
+}
+
+// The sum of the one-pass kernel's partials and lines 7-9 of Alg. 2 in one launch.  The curvature
+// s^T H s does not wait for H s: with Z = X_S s and U the rows of eq. (12), s^T (X_S^T U) is the sum over
+// the sample rows of z_i . u_i, which the product's own launch leaves as per-wave partials (zu_part), and
+// s^T s comes as partials from the kernel that made s.  Each block therefore knows alpha before it adds
+// up its elements of H s = scale * sum part + lambda s, and updates p and r for them at once; H s itself
+// is not stored.
+template <typename T, int EL> __global__ __launch_bounds__(VEC_BLOCK) void finalize_cg_kernel(FinArgs a, FinCgArgs g)
+{
+    const CgSlot c = *g.cur;
+    if (c.done) return;
+    const double zu = sum_parts(g.zu_part, g.n_zu);
+    const double ss = sum_parts(g.ss_part, g.n_ss);
+    const double sHs = a.scale * zu + a.lambda * ss;
+    if (!(sHs > 0.0)) {                      // not positive definite in floating point: stop, keep p_best
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            g.cur->brk = 1;                  // read only by step 2 of this product
+            if (g.trace_k) { g.trace_k[0] = 0.0; g.trace_k[1] = sqrt(c.rr); g.trace_k[2] = sHs; }
+        }
+        return;
+    }
+    const double alpha = c.rr / sHs;
+    constexpr int CLN = VEC_BLOCK / EL;
+    __shared__ double sm[VEC_BLOCK];
+    const int el = threadIdx.x % EL, cl = threadIdx.x / EL;
+    const int64_t total = a.p * a.K;
+    const int64_t ngroups = (total + EL - 1) / EL;
+    const T *part = (const T *)a.part;
+    const T *sv = (const T *)a.M;
+    T *pv = (T *)g.pv, *r = (T *)g.r;
+    double local = 0.0;
+    for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
+        const int64_t e = grp * EL + el;
+        double t = 0.0;
+        if (e < total)
+            for (int ch = cl; ch < a.nchunks; ch += CLN) t += (double)part[(int64_t)ch * total + e];
+        sm[threadIdx.x] = t;
+        __syncthreads();
+        if (cl == 0 && e < total) {
+            double tt = 0.0;
+#pragma unroll
+            for (int k = 0; k < CLN; ++k) tt += sm[k * EL + el];
+            const int64_t o = off_of(e, a.K, a.ldm);
+            const double m = (double)sv[o];
+            const T hs = (T)(a.scale * tt + a.lambda * m);           // the element of H s, rounded as if stored
+            pv[o] = (T)((double)pv[o] + alpha * m);
+            const T rn = (T)((double)r[o] - alpha * (double)hs);
+            r[o] = rn;
+            local += (double)rn * (double)rn;
+        }
+        __syncthreads();
+    }
+    const double rr = block_sum(local);
+    if (threadIdx.x == 0) {
+        g.rr_part[blockIdx.x] = rr;
+        if (blockIdx.x == 0 && g.trace_k) { g.trace_k[0] = alpha; g.trace_k[2] = sHs; }
+    }
+}
+
+template <typename T> static void finalize_cg_launch(const FinArgs &a, const FinCgArgs &g, int blocks, hipStream_t st)
+{
+    const int el = finalize_el(a.p * a.K);
+    if (el == 32) hipLaunchKernelGGL((finalize_cg_kernel<T, 32>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a, g);
+    else if (el == 16) hipLaunchKernelGGL((finalize_cg_kernel<T, 16>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a, g);
+    else hipLaunchKernelGGL((finalize_cg_kernel<T, 4>), dim3(blocks), dim3(VEC_BLOCK), 0, st, a, g);
+}
+
+hipError_t launch_finalize_cg(int dtype, const FinArgs &a, const FinCgArgs &g, int blocks, hipStream_t st)
+{
+    if (dtype == SSN_F32) finalize_cg_launch<float>(a, g, blocks, st);
+    else finalize_cg_launch<double>(a, g, blocks, st);
     return hipGetLastError();
 }
 
@@ -282,7 +355,8 @@ hipError_t launch_check_rowptr(const int32_t *rowptr, int64_t n, int64_t nnz, in
 
 // ---- Alg. 2 on the device -------------------------------------------------------------------
 // lines 1-5: p = 0, r = -g, s = r, p_best = s; partials of g.g
-template <typename T> __global__ __launch_bounds__(VEC_BLOCK) void cg_init_kernel(CgVecs v, double *gg_part)
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void cg_init_kernel(CgVecs v, double *gg_part, double *ss_part)
 {
     const int64_t total = v.p * v.K;
     const T *G = (const T *)v.G;
@@ -298,13 +372,18 @@ template <typename T> __global__ __launch_bounds__(VEC_BLOCK) void cg_init_kerne
         local += (double)gv * (double)gv;
     }
     const double t = block_sum(local);
-    if (threadIdx.x == 0) gg_part[blockIdx.x] = t;
+    if (threadIdx.x == 0) {
+        gg_part[blockIdx.x] = t;
+        if (ss_part) ss_part[blockIdx.x] = t;        // s_0 = -g: the same partials serve s.s
+    }
 }
 
-hipError_t launch_cg_init(int dtype, const CgVecs &v, double *gg_part, int blocks, hipStream_t st)
+hipError_t launch_cg_init(int dtype, const CgVecs &v, double *gg_part, double *ss_part, int blocks, hipStream_t st)
 {
-    if (dtype == SSN_F32) hipLaunchKernelGGL(cg_init_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, gg_part);
-    else hipLaunchKernelGGL(cg_init_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, gg_part);
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(cg_init_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, gg_part, ss_part);
+    else
+        hipLaunchKernelGGL(cg_init_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, gg_part, ss_part);
     return hipGetLastError();
 }
 
@@ -381,7 +460,7 @@ hipError_t launch_cg_step1(int dtype, const CgVecs &v, const CgSlot *cur, const 
 template <typename T>
 __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgSlot *cur, CgSlot *next,
                                                               const double *rr_part, int n_rr, double theta,
-                                                              double *trace_k)
+                                                              double *trace_k, double *ss_part)
 {
     const CgSlot c = *cur;
     if (c.done || c.brk) {
@@ -402,13 +481,22 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgS
     const int64_t total = v.p * v.K;
     const T *pv = (const T *)v.pv, *r = (const T *)v.r;
     T *s = (T *)v.s, *pb = (T *)v.pbest;
+    double ss = 0.0;
     if (better || !stop) {
         for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total;
              e += (int64_t)gridDim.x * VEC_BLOCK) {
             const int64_t o = off_of(e, v.K, v.ld);
             if (better) pb[o] = pv[o];
-            if (!stop) s[o] = (T)((double)r[o] + b * (double)s[o]);
+            if (!stop) {
+                const T sn = (T)((double)r[o] + b * (double)s[o]);
+                s[o] = sn;
+                ss += (double)sn * (double)sn;
+            }
         }
+    }
+    if (ss_part) {                           // partials of s.s for the next product's curvature
+        ss = block_sum(ss);
+        if (threadIdx.x == 0) ss_part[blockIdx.x] = ss;
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         CgSlot n;
@@ -425,14 +513,14 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgS
 }
 
 hipError_t launch_cg_step2(int dtype, const CgVecs &v, const CgSlot *cur, CgSlot *next, const double *rr_part, int n_rr,
-                           double theta, double *trace_k, int blocks, hipStream_t st)
+                           double theta, double *trace_k, double *ss_part, int blocks, hipStream_t st)
 {
     if (dtype == SSN_F32)
         hipLaunchKernelGGL(cg_step2_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, cur, next, rr_part, n_rr, theta,
-                           trace_k);
+                           trace_k, ss_part);
     else
         hipLaunchKernelGGL(cg_step2_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, cur, next, rr_part, n_rr,
-                           theta, trace_k);
+                           theta, trace_k, ss_part);
     return hipGetLastError();
 }
 
