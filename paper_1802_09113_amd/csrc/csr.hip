@@ -40,10 +40,23 @@ __device__ __forceinline__ T csr_row_margin(const RowsArgs &a, int64_t row, int 
     const T *vals = (const T *)a.vals;
     const T *M = (const T *)a.M;
     const int64_t b = a.rowptr[row], e = a.rowptr[row + 1];
+    // four stored entries per lane in flight: a row's gathers depend on its column indices, and a single chain
+    // of index -> gather round trips is what bounds a wave that owns a whole row
     T acc = 0;
-    for (int64_t t = b + s; t < e && act; t += NS) {
-        const int64_t col = a.colidx[t];
-        acc += vals[t] * M[col * a.ldm + c];
+    if (act) {
+        T a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+        int64_t t = b + s;
+        for (; t + 3 * NS < e; t += 4 * NS) {
+            const int64_t c0 = a.colidx[t], c1 = a.colidx[t + NS], c2 = a.colidx[t + 2 * NS], c3 = a.colidx[t + 3 * NS];
+            const T v0 = vals[t], v1 = vals[t + NS], v2 = vals[t + 2 * NS], v3 = vals[t + 3 * NS];
+            const T m0 = M[c0 * a.ldm + c], m1 = M[c1 * a.ldm + c], m2 = M[c2 * a.ldm + c], m3 = M[c3 * a.ldm + c];
+            a0 += v0 * m0;
+            a1 += v1 * m1;
+            a2 += v2 * m2;
+            a3 += v3 * m3;
+        }
+        for (; t < e; t += NS) a0 += vals[t] * M[(int64_t)a.colidx[t] * a.ldm + c];
+        acc = (a0 + a1) + (a2 + a3);
     }
     // fold the NS slots onto slot 0
     T tot = acc;
@@ -73,7 +86,11 @@ template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER
         if constexpr (MODE == ROW_APPLY) {
             const T pin = cv ? ((const T *)a.Pin)[sv * a.KP + lane] : T(0);
             const T t = wave_sum(pin * z);
-            if (cv) ((T *)a.UP)[sv * a.KP + lane] = pin * z - pin * t;
+            const T u = pin * z - pin * t;
+            if (cv) ((T *)a.UP)[sv * a.KP + lane] = u;
+            // z_i . u_i of the row: summed over the sample it is V^T (X_S^T U), the curvature term CG needs
+            const T zu = wave_sum(cv ? z * u : T(0));
+            if (lane == 0) loss += (double)zu;
             continue;
         }
         const T zmax = wave_max(cv ? z : NEG);
@@ -99,7 +116,7 @@ template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER
         if (lane == 0) loss += (double)Mx + (double)c_log(alpha) - (double)lin;
         if (MODE == ROW_GRAD && cv) ((T *)a.UP)[sv * a.KP + lane] = ex / alpha - ((lane == lab) ? T(1) : T(0));
     }
-    if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD) {
+    if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_APPLY) {
         if (lane == 0) a.loss_part[wave] = loss;
     } else if constexpr (MODE == ROW_PRED) {
         if (lane == 0) a.hit_part[wave] = hits;
@@ -128,10 +145,17 @@ hipError_t launch_csr_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t
 // out[col, c] += scale * x * U[sv, c] for every stored entry of the selected rows.
 // out must already hold lambda * M.  Hardware floating-point atomics on device memory: the summation
 // order, and therefore the last bits, vary from run to run.
+// slot (nullable): the scatter is the sparse part of the CG residual update r -= alpha * scale * X_S^T U of
+// a product whose step length waits in the slot; nothing happens when that CG loop has ended.
 template <typename T>
-__global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void csr_scatter_kernel(XtuArgs a, double scale, T *out, int64_t ldo)
+__global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void csr_scatter_kernel(XtuArgs a, double scale, T *out, int64_t ldo,
+                                                                                const CgSlot *slot)
 {
     if (a.skip && *a.skip) return;
+    if (slot) {
+        if (slot->done || slot->brk) return;
+        scale *= -slot->alpha;
+    }
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     const int64_t nwaves = (int64_t)gridDim.x * ROWS_WAVES_PER_BLOCK;
     const int64_t wave = (int64_t)blockIdx.x * ROWS_WAVES_PER_BLOCK + wib;
@@ -153,13 +177,16 @@ __global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void csr_scatter_kernel(
     }
 }
 
-hipError_t launch_csr_scatter(int dtype, const XtuArgs &a, double scale, void *out, int64_t ldo, hipStream_t st)
+hipError_t launch_csr_scatter(int dtype, const XtuArgs &a, double scale, void *out, int64_t ldo, const CgSlot *slot,
+                              hipStream_t st)
 {
     int64_t blocks = (a.nrows + ROWS_WAVES_PER_BLOCK - 1) / ROWS_WAVES_PER_BLOCK;
     if (blocks > 8192) blocks = 8192;
     dim3 grid((unsigned)blocks), block(64 * ROWS_WAVES_PER_BLOCK);
-    if (dtype == SSN_F32) hipLaunchKernelGGL(csr_scatter_kernel<float>, grid, block, 0, st, a, scale, (float *)out, ldo);
-    else hipLaunchKernelGGL(csr_scatter_kernel<double>, grid, block, 0, st, a, scale, (double *)out, ldo);
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(csr_scatter_kernel<float>, grid, block, 0, st, a, scale, (float *)out, ldo, slot);
+    else
+        hipLaunchKernelGGL(csr_scatter_kernel<double>, grid, block, 0, st, a, scale, (double *)out, ldo, slot);
     return hipGetLastError();
 }
 

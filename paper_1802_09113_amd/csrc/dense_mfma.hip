@@ -175,12 +175,17 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
             }
             t = row16_sum(t);
             T *U = (T *)a.UP;
+            T zu = 0;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const T u = valid ? (pin[nb] * z[nb] - pin[nb] * t) : T(0);
+                zu += z[nb] * u;
                 if constexpr (TOREG) uout[nb][v] = u;
                 else U[sv * a.KP + nb * 16 + q] = u;
             }
+            // z_i . u_i of the row: summed over the sample it is V^T (X_S^T U), the curvature term CG needs
+            zu = row16_sum(zu);
+            if (valid && q == 0) loss += (double)zu;
             continue;
         }
         // eq. (8), (9): M = max{0, z}, alpha = e^{-M} + sum_c e^{z_c - M}
@@ -301,7 +306,7 @@ __global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void dense_rows_kernel(R
         row_epilogue<T, NB, MODE>(acc, a, rb, lane, loss, hits);
     }
 
-    if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD) {
+    if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_APPLY) {
         for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off);
         if (lane == 0) a.loss_part[wave] = loss;
     } else if constexpr (MODE == ROW_PRED) {

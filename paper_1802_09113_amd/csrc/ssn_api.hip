@@ -45,7 +45,7 @@ struct ssn_ctx {
     int64_t nS = 0;
     bool prepared = false;
     // CG / line-search vectors (p x ldw each)
-    void *cg_p = nullptr, *cg_r = nullptr, *cg_s = nullptr, *cg_Hs = nullptr, *trial = nullptr;
+    void *cg_p = nullptr, *cg_r = nullptr, *cg_s = nullptr, *trial = nullptr;
     void *grad = nullptr, *dir = nullptr;      // ssn_solve's gradient and direction
     CgSlot *slots = nullptr;
     int slots_cap = 0;
@@ -222,7 +222,7 @@ int transposed_product(ssn_ctx *c, const int32_t *S, int64_t nrows, double scale
         SSN_TRY(finalize_dense(c, x.nchunks, scale, M, out, want_dot, ndot, skip));
     } else {
         SSN_HIP(c, launch_scale_copy(c->d.dtype, c->d.p, c->K, c->d.lambda, M, c->d.ldw, out, c->d.ldw, skip, c->st));
-        SSN_HIP(c, launch_csr_scatter(c->d.dtype, x, scale, out, c->d.ldw, c->st));
+        SSN_HIP(c, launch_csr_scatter(c->d.dtype, x, scale, out, c->d.ldw, nullptr, c->st));
         if (want_dot) {
             const int vb = vec_blocks(c->d.p * (int64_t)c->K);
             SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, out, c->d.ldw, M, c->d.ldw, c->red_b, vb, skip, c->st));
@@ -293,19 +293,8 @@ int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f)
     return SSN_OK;
 }
 
-// state of the CG iteration a product may carry behind it on the one-pass path (Alg. 2 lines 7-9)
-struct CgFuse {
-    CgSlot *cur;
-    void *pv, *r;
-    int n_ss;                // partials of s.s waiting in red_c
-    double *trace;
-};
-
-// HV = H_S V.  want_dot: partials of <HV, V> into red_b (count in *ndot).  cg (nullable): V is the CG
-// direction s; on the one-pass path the sum of the partials then also does lines 7-9 (HV is not stored,
-// partials of the new r.r go to red_a, their count to *ndot) and *cg_done is set.
-int hess_apply_impl(ssn_ctx *c, const void *V, void *HV, bool want_dot, int *ndot, const int32_t *skip,
-                    const CgFuse *cg = nullptr, bool *cg_done = nullptr)
+// HV = H_S V.  want_dot: partials of <HV, V> into red_b (count in *ndot).
+int hess_apply_impl(ssn_ctx *c, const void *V, void *HV, bool want_dot, int *ndot, const int32_t *skip)
 {
     RowsArgs a = rows_base(c);
     a.S = c->S;
@@ -317,36 +306,80 @@ int hess_apply_impl(ssn_ctx *c, const void *V, void *HV, bool want_dot, int *ndo
     a.skip = skip;
     a.part = c->part;
     int nparts = 0;
-    if (cg_done) *cg_done = false;
     SSN_TRY(launch_rows(c, a, &nparts));
-    if (c->fused && cg) {
+    if (c->fused) return finalize_dense(c, nparts / 4, scale_sample(c), V, HV, want_dot, ndot, skip);
+    return transposed_product(c, c->S, c->nS, scale_sample(c), V, HV, want_dot, ndot, skip);
+}
+
+// Product k of the CG loop with lines 7-9 of Alg. 2 behind it: alpha, r -= alpha H s and, on the dense
+// paths, p += alpha s (the CSR path leaves that to step 2, *p_pending).  H s is never stored.  The
+// curvature s^T H s = scale * sum_i z_i . u_i + lambda * s.s comes from the per-wave partials the rows
+// kernel leaves in loss_part and the partials of s.s in red_c (n_ss of them).  On return red_a holds *n_rr
+// partials of the new r.r.
+int cg_product_step(ssn_ctx *c, const CgVecs &v, CgSlot *cur, int n_ss, double *trace_k, int *n_rr, bool *p_pending)
+{
+    const int32_t *skip = (const int32_t *)((const char *)cur + offsetof(CgSlot, done));
+    RowsArgs a = rows_base(c);
+    a.S = c->S;
+    a.nrows = c->nS;
+    a.M = v.s;
+    a.mode = ROW_APPLY;
+    a.Pin = c->Pbuf;
+    a.UP = c->Ubuf;
+    a.skip = skip;
+    a.part = c->part;
+    int nparts = 0;
+    SSN_TRY(launch_rows(c, a, &nparts));
+    *p_pending = false;
+    if (is_dense(c)) {
+        int nchunks = nparts / 4;
+        if (!c->fused) {
+            XtuArgs x = xtu_base(c);
+            x.S = c->S;
+            x.nrows = c->nS;
+            x.U = c->Ubuf;
+            x.skip = skip;
+            choose_chunks(c, c->nS, &x.rows_per_chunk, &x.nchunks);
+            SSN_HIP(c, launch_dense_xtu(c->d.dtype, x, c->st));
+            nchunks = x.nchunks;
+        }
         FinArgs f{};
         f.part = c->part;
-        f.nchunks = nparts / 4;
+        f.nchunks = nchunks;
         f.p = c->d.p;
         f.K = c->K;
         f.scale = scale_sample(c);
         f.lambda = c->d.lambda;
-        f.M = V;
+        f.M = v.s;
         f.ldm = c->d.ldw;
         FinCgArgs g{};
-        g.cur = cg->cur;
-        g.pv = cg->pv;
-        g.r = cg->r;
+        g.cur = cur;
+        g.pv = v.pv;
+        g.r = v.r;
         g.zu_part = c->loss_part;
         g.n_zu = nparts;
         g.ss_part = c->red_c;
-        g.n_ss = cg->n_ss;
+        g.n_ss = n_ss;
         g.rr_part = c->red_a;
-        g.trace_k = cg->trace;
+        g.trace_k = trace_k;
         const int fb = finalize_blocks(c->d.p, c->K);
         SSN_HIP(c, launch_finalize_cg(c->d.dtype, f, g, fb, c->st));
-        if (ndot) *ndot = fb;
-        if (cg_done) *cg_done = true;
+        *n_rr = fb;
         return SSN_OK;
     }
-    if (c->fused) return finalize_dense(c, nparts / 4, scale_sample(c), V, HV, want_dot, ndot, skip);
-    return transposed_product(c, c->S, c->nS, scale_sample(c), V, HV, want_dot, ndot, skip);
+    // CSR: alpha first, then the few entries of r the sample's columns touch, then one dense pass over r and s
+    SSN_HIP(c, launch_cg_alpha(cur, c->loss_part, nparts, c->red_c, n_ss, scale_sample(c), c->d.lambda, trace_k, c->st));
+    XtuArgs x = xtu_base(c);
+    x.S = c->S;
+    x.nrows = c->nS;
+    x.U = c->Ubuf;
+    x.skip = skip;
+    SSN_HIP(c, launch_csr_scatter(c->d.dtype, x, scale_sample(c), v.r, c->d.ldw, cur, c->st));
+    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+    SSN_HIP(c, launch_cg_r_update(c->d.dtype, v, cur, c->d.lambda, c->red_a, vb, c->st));
+    *n_rr = vb;
+    *p_pending = true;
+    return SSN_OK;
 }
 
 double now_ms()
@@ -382,7 +415,7 @@ int ssn_destroy(ssn_ctx *c)
     if (!c) return SSN_E_INVALID_ARG;
     (void)hipStreamSynchronize(c->st);
     void *dev[] = {c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->red_c, c->scal_dev, c->int_dev,
-                   c->cg_p, c->cg_r, c->cg_s, c->cg_Hs, c->trial, c->grad, c->dir, c->slots, c->trace_dev};
+                   c->cg_p, c->cg_r, c->cg_s, c->trial, c->grad, c->dir, c->slots, c->trace_dev};
     for (void *p : dev)
         if (p) (void)hipFree(p);
     if (c->host_pin) (void)hipHostFree(c->host_pin);
@@ -543,7 +576,6 @@ int ssn_cg(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out, ssn_
         SSN_TRY(vec_bytes_alloc(c, &c->cg_p));
         SSN_TRY(vec_bytes_alloc(c, &c->cg_r));
         SSN_TRY(vec_bytes_alloc(c, &c->cg_s));
-        SSN_TRY(vec_bytes_alloc(c, &c->cg_Hs));
     }
     if (c->slots_cap < T + 1) {
         SSN_HIP(c, hipStreamSynchronize(c->st));
@@ -564,21 +596,15 @@ int ssn_cg(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out, ssn_
     v.pv = c->cg_p;
     v.r = c->cg_r;
     v.s = c->cg_s;
-    v.Hs = c->cg_Hs;
     v.pbest = P_out;
     SSN_HIP(c, launch_cg_init(c->d.dtype, v, c->red_a, c->red_c, vb, c->st));
     SSN_HIP(c, launch_cg_init_state(c->red_a, vb, c->slots, c->st));
     for (int k = 0; k < T; ++k) {
-        const int32_t *skip = (const int32_t *)((const char *)(c->slots + k) + offsetof(CgSlot, done));
-        int ndot = 0;
-        bool stepped = false;
-        const CgFuse cf{c->slots + k, c->cg_p, c->cg_r, vb, c->trace_dev + 3 * k};
-        SSN_TRY(hess_apply_impl(c, c->cg_s, c->cg_Hs, true, &ndot, skip, &cf, &stepped));
-        // one-pass path: lines 7-9 are done and red_a holds ndot partials of the new r.r
-        if (!stepped)
-            SSN_HIP(c, launch_cg_step1(c->d.dtype, v, c->slots + k, c->red_b, ndot, c->red_a, c->trace_dev + 3 * k, vb, c->st));
-        SSN_HIP(c, launch_cg_step2(c->d.dtype, v, c->slots + k, c->slots + k + 1, c->red_a, stepped ? ndot : vb, theta,
-                                   c->trace_dev + 3 * k, c->red_c, vb, c->st));
+        int n_rr = 0;
+        bool p_pending = false;
+        SSN_TRY(cg_product_step(c, v, c->slots + k, vb, c->trace_dev + 3 * k, &n_rr, &p_pending));
+        SSN_HIP(c, launch_cg_step2(c->d.dtype, v, c->slots + k, c->slots + k + 1, c->red_a, n_rr, theta,
+                                   c->trace_dev + 3 * k, c->red_c, p_pending, vb, c->st));
     }
     CgSlot fin;
     std::vector<double> tr((size_t)3 * (T > 0 ? T : 1));
@@ -758,7 +784,7 @@ int ssn_time_kernel(ssn_ctx *c, int32_t which, const void *M, int32_t reps, doub
         if (which == 2 || which == 4) {
             if (c->fused) status = finalize_dense(c, fused_parts, sampled ? scale_sample(c) : scale_full(c), M, c->trial, false, nullptr, nullptr);
             else if (is_dense(c)) he = launch_dense_xtu(c->d.dtype, x, c->st);
-            else he = launch_csr_scatter(c->d.dtype, x, sampled ? scale_sample(c) : scale_full(c), c->trial, c->d.ldw, c->st);
+            else he = launch_csr_scatter(c->d.dtype, x, sampled ? scale_sample(c) : scale_full(c), c->trial, c->d.ldw, nullptr, c->st);
         } else {
             status = launch_rows(c, a, nullptr);
         }

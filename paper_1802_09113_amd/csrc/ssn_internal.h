@@ -10,6 +10,8 @@
 
 namespace ssn {
 
+struct CgSlot;
+
 // ---- per-row epilogue selector of the row-block kernels -------------------------------
 enum RowMode : int {
     ROW_OBJ = 0,    // loss only                                   (Alg. 5)
@@ -100,7 +102,9 @@ int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus);
 int dense_fused_waves(int dtype, const RowsArgs &a);
 hipError_t launch_dense_fused(int dtype, const RowsArgs &a, int grid, hipStream_t st);
 hipError_t launch_csr_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
-hipError_t launch_csr_scatter(int dtype, const XtuArgs &a, double scale, void *out, int64_t ldo, hipStream_t st);
+// slot (nullable): multiply by -slot->alpha and do nothing when that CG loop has ended
+hipError_t launch_csr_scatter(int dtype, const XtuArgs &a, double scale, void *out, int64_t ldo, const CgSlot *slot,
+                              hipStream_t st);
 hipError_t launch_finalize(int dtype, const FinArgs &a, int blocks, hipStream_t st);
 
 // out = lambda * M (p x K), with optional <.,.> partials disabled; used by the CSR path before scattering
@@ -132,7 +136,8 @@ struct CgSlot {          // state before product k
     int32_t done;        // loop has ended (theta test, breakdown, zero gradient)
     int32_t iters;       // products made so far
     int32_t flags;
-    int32_t brk;         // written by step1 of product k when s^T H s <= 0
+    int32_t brk;         // set during product k when s^T H s <= 0
+    double alpha;        // step length of product k, where a kernel of its own computes it (CSR path)
 };
 
 struct CgVecs {
@@ -140,17 +145,23 @@ struct CgVecs {
     int32_t K;
     int64_t ld;          // leading dimension of every vector below
     const void *G;
-    void *pv, *r, *s, *Hs, *pbest;
+    void *pv, *r, *s, *pbest;
 };
 
 // ss_part (nullable) receives the same partials again: s_0 = -g
 hipError_t launch_cg_init(int dtype, const CgVecs &v, double *gg_part, double *ss_part, int blocks, hipStream_t st);
 hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0, hipStream_t st);
-hipError_t launch_cg_step1(int dtype, const CgVecs &v, const CgSlot *cur, const double *sHs_part, int n_sHs,
-                           double *rr_part, double *trace_k, int blocks, hipStream_t st);
-// ss_part (nullable): one partial of s.s per block for the new direction
+// ss_part (nullable): one partial of s.s per block for the new direction; update_p: also p += cur->alpha * s
 hipError_t launch_cg_step2(int dtype, const CgVecs &v, const CgSlot *cur, CgSlot *next, const double *rr_part,
-                           int n_rr, double theta, double *trace_k, double *ss_part, int blocks, hipStream_t st);
+                           int n_rr, double theta, double *trace_k, double *ss_part, bool update_p, int blocks,
+                           hipStream_t st);
+// CSR path, lines 7-9 in pieces: cur->alpha from the partials of sum_i z_i . u_i and of s.s (one block); then the
+// sparse part of r -= alpha H s goes through launch_csr_scatter and the dense part, r -= alpha lambda s with the
+// partials of the new r.r, through launch_cg_r_update
+hipError_t launch_cg_alpha(CgSlot *cur, const double *zu_part, int n_zu, const double *ss_part, int n_ss, double scale,
+                           double lambda, double *trace_k, hipStream_t st);
+hipError_t launch_cg_r_update(int dtype, const CgVecs &v, const CgSlot *cur, double lambda, double *rr_part, int blocks,
+                              hipStream_t st);
 
 // one-pass path: sum of the product's partials fused with lines 7-9 (see finalize_cg_kernel)
 struct FinCgArgs {

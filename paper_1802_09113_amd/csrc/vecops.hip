@@ -399,6 +399,7 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_init_state_kernel(const double *
         s.iters = 0;
         s.flags = 0;
         s.brk = 0;
+        s.alpha = 0.0;
         *slot0 = s;
     }
 }
@@ -409,58 +410,11 @@ hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0
     return hipGetLastError();
 }
 
-// lines 7-9: alpha = r.r / s.Hs ; p += alpha s ; r -= alpha Hs ; partials of the new r.r
-template <typename T>
-__global__ __launch_bounds__(VEC_BLOCK) void cg_step1_kernel(CgVecs v, CgSlot *cur, const double *sHs_part, int n_sHs,
-                                                              double *rr_part, double *trace_k)
-{
-    if (cur->done) return;
-    const double sHs = sum_parts(sHs_part, n_sHs);
-    const double rr = cur->rr;
-    if (!(sHs > 0.0)) {                      // not positive definite in floating point: stop, keep p_best
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            cur->brk = 1;                    // read only by step 2 of this product
-            if (trace_k) { trace_k[0] = 0.0; trace_k[1] = sqrt(rr); trace_k[2] = sHs; }
-        }
-        return;
-    }
-    const double alpha = rr / sHs;
-    const int64_t total = v.p * v.K;
-    T *pv = (T *)v.pv, *r = (T *)v.r;
-    const T *s = (const T *)v.s, *Hs = (const T *)v.Hs;
-    double local = 0.0;
-    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
-        const int64_t o = off_of(e, v.K, v.ld);
-        pv[o] = (T)((double)pv[o] + alpha * (double)s[o]);
-        const T rn = (T)((double)r[o] - alpha * (double)Hs[o]);
-        r[o] = rn;
-        local += (double)rn * (double)rn;
-    }
-    const double t = block_sum(local);
-    if (threadIdx.x == 0) {
-        rr_part[blockIdx.x] = t;
-        if (blockIdx.x == 0 && trace_k) { trace_k[0] = alpha; trace_k[2] = sHs; }
-    }
-}
-
-hipError_t launch_cg_step1(int dtype, const CgVecs &v, const CgSlot *cur, const double *sHs_part, int n_sHs,
-                           double *rr_part, double *trace_k, int blocks, hipStream_t st)
-{
-    CgSlot *c = const_cast<CgSlot *>(cur);
-    if (dtype == SSN_F32)
-        hipLaunchKernelGGL(cg_step1_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, c, sHs_part, n_sHs, rr_part,
-                           trace_k);
-    else
-        hipLaunchKernelGGL(cg_step1_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, c, sHs_part, n_sHs, rr_part,
-                           trace_k);
-    return hipGetLastError();
-}
-
 // lines 10-12: best-iterate memory, theta test, new search direction
 template <typename T>
 __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgSlot *cur, CgSlot *next,
                                                               const double *rr_part, int n_rr, double theta,
-                                                              double *trace_k, double *ss_part)
+                                                              double *trace_k, double *ss_part, bool update_p)
 {
     const CgSlot c = *cur;
     if (c.done || c.brk) {
@@ -482,7 +436,22 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgS
     const T *pv = (const T *)v.pv, *r = (const T *)v.r;
     T *s = (T *)v.s, *pb = (T *)v.pbest;
     double ss = 0.0;
-    if (better || !stop) {
+    if (update_p) {                          // line 8 was left to this pass: p += alpha s with the old s
+        T *pw = (T *)v.pv;
+        for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total;
+             e += (int64_t)gridDim.x * VEC_BLOCK) {
+            const int64_t o = off_of(e, v.K, v.ld);
+            const T so = s[o];
+            const T pn = (T)((double)pw[o] + c.alpha * (double)so);
+            pw[o] = pn;
+            if (better) pb[o] = pn;
+            if (!stop) {
+                const T sn = (T)((double)r[o] + b * (double)so);
+                s[o] = sn;
+                ss += (double)sn * (double)sn;
+            }
+        }
+    } else if (better || !stop) {
         for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total;
              e += (int64_t)gridDim.x * VEC_BLOCK) {
             const int64_t o = off_of(e, v.K, v.ld);
@@ -507,20 +476,78 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgS
         n.iters = c.iters + 1;
         n.flags = c.flags | (stop ? 1 : 0);
         n.brk = 0;
+        n.alpha = 0.0;
         *next = n;
         if (trace_k) trace_k[1] = rnorm;
     }
 }
 
 hipError_t launch_cg_step2(int dtype, const CgVecs &v, const CgSlot *cur, CgSlot *next, const double *rr_part, int n_rr,
-                           double theta, double *trace_k, double *ss_part, int blocks, hipStream_t st)
+                           double theta, double *trace_k, double *ss_part, bool update_p, int blocks, hipStream_t st)
 {
     if (dtype == SSN_F32)
         hipLaunchKernelGGL(cg_step2_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, cur, next, rr_part, n_rr, theta,
-                           trace_k, ss_part);
+                           trace_k, ss_part, update_p);
     else
         hipLaunchKernelGGL(cg_step2_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, cur, next, rr_part, n_rr,
-                           theta, trace_k, ss_part);
+                           theta, trace_k, ss_part, update_p);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(VEC_BLOCK) void cg_alpha_kernel(CgSlot *cur, const double *zu_part, int n_zu,
+                                                              const double *ss_part, int n_ss, double scale, double lambda,
+                                                              double *trace_k)
+{
+    const CgSlot c = *cur;
+    if (c.done) return;
+    const double zu = sum_parts(zu_part, n_zu);
+    const double ss = sum_parts(ss_part, n_ss);
+    const double sHs = scale * zu + lambda * ss;
+    if (threadIdx.x != 0) return;
+    if (!(sHs > 0.0)) {                      // not positive definite in floating point: stop, keep p_best
+        cur->brk = 1;
+        if (trace_k) { trace_k[0] = 0.0; trace_k[1] = sqrt(c.rr); trace_k[2] = sHs; }
+    } else {
+        cur->alpha = c.rr / sHs;
+        if (trace_k) { trace_k[0] = c.rr / sHs; trace_k[2] = sHs; }
+    }
+}
+
+hipError_t launch_cg_alpha(CgSlot *cur, const double *zu_part, int n_zu, const double *ss_part, int n_ss, double scale,
+                           double lambda, double *trace_k, hipStream_t st)
+{
+    hipLaunchKernelGGL(cg_alpha_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, cur, zu_part, n_zu, ss_part, n_ss, scale, lambda,
+                       trace_k);
+    return hipGetLastError();
+}
+
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void cg_r_update_kernel(CgVecs v, const CgSlot *cur, double lambda, double *rr_part)
+{
+    const CgSlot c = *cur;
+    if (c.done || c.brk) return;
+    const double coef = c.alpha * lambda;
+    const int64_t total = v.p * v.K;
+    T *r = (T *)v.r;
+    const T *s = (const T *)v.s;
+    double local = 0.0;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int64_t o = off_of(e, v.K, v.ld);
+        const T rn = (T)((double)r[o] - coef * (double)s[o]);
+        r[o] = rn;
+        local += (double)rn * (double)rn;
+    }
+    const double t = block_sum(local);
+    if (threadIdx.x == 0) rr_part[blockIdx.x] = t;
+}
+
+hipError_t launch_cg_r_update(int dtype, const CgVecs &v, const CgSlot *cur, double lambda, double *rr_part, int blocks,
+                              hipStream_t st)
+{
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(cg_r_update_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, cur, lambda, rr_part);
+    else
+        hipLaunchKernelGGL(cg_r_update_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, cur, lambda, rr_part);
     return hipGetLastError();
 }
 
