@@ -1,0 +1,366 @@
+// Column-sorted view of a set of CSR rows and the transposed product X_rows^T U on it.
+//
+// The transposed product of eq. (13) / Alg. 6 adds x_ij * u_i into row j of the result for every stored
+// entry.  Scattering from the CSR rows would need floating-point atomics (an order of summation that
+// changes from run to run); instead the entries of the selected rows are sorted by column once -- when
+// the context first needs the whole matrix, and at every ssn_hess_prepare for the sample -- and each
+// product then GATHERS: the entries of a column are consecutive, rows of U are read, and every result
+// element has exactly one writer and one order of summation.
+//
+// Work is cut into pieces: a piece ends where the column changes and at every PIECE_LEN-th entry, so hot
+// columns (a few appear in almost every row of text-like data) are spread over many lane groups.  A
+// piece that is a whole column adds into the result directly; the pieces of a longer column leave
+// partial sums that a second kernel adds in piece order.
+//
+// The one-off construction uses hipCUB's device radix sort and prefix sums; the product kernels are
+// hand-written.
+#include "ssn_internal.h"
+
+#include <hipcub/hipcub.hpp>
+
+namespace ssn {
+
+constexpr int PIECE_LEN = 64;
+
+// ---- construction ---------------------------------------------------------------------------
+__global__ __launch_bounds__(VEC_BLOCK) void csc_row_len_kernel(const int32_t *rowptr, const int32_t *S, int64_t nrows,
+                                                                 int32_t *len)
+{
+    for (int64_t i = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; i <= nrows; i += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int64_t r = (i < nrows) ? (S ? (int64_t)S[i] : i) : 0;
+        len[i] = (i < nrows) ? rowptr[r + 1] - rowptr[r] : 0;
+    }
+}
+
+// one wave per selected row: copy its entries to positions off[sv].. with the sample position as payload
+template <typename T>
+__global__ __launch_bounds__(256) void csc_expand_kernel(const int32_t *rowptr, const int32_t *colidx, const T *vals,
+                                                         const int32_t *S, int64_t nrows, const int32_t *off,
+                                                         int32_t *key_in, int32_t *idx_in, int32_t *row_in, T *val_in)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t nw = (int64_t)gridDim.x * 4;
+    for (int64_t sv = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); sv < nrows; sv += nw) {
+        const int64_t r = S ? S[sv] : sv;
+        const int64_t b = rowptr[r], e = rowptr[r + 1];
+        const int64_t o = off[sv];
+        for (int64_t t = b + lane; t < e; t += 64) {
+            const int64_t d = o + (t - b);
+            key_in[d] = colidx[t];
+            idx_in[d] = (int32_t)d;
+            row_in[d] = (int32_t)sv;
+            val_in[d] = vals[t];
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void csc_permute_kernel(const int32_t *idx, const int32_t *row_in, const T *val_in,
+                                                                 int64_t nnz, int32_t *row, T *val)
+{
+    for (int64_t t = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; t < nnz; t += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int32_t e = idx[t];
+        row[t] = row_in[e];
+        val[t] = val_in[e];
+    }
+}
+
+// flag[t] = 1 where a piece starts: first entry of a column, or every PIECE_LEN-th entry
+__global__ __launch_bounds__(VEC_BLOCK) void csc_piece_flag_kernel(const int32_t *key, int64_t nnz, int32_t *flag)
+{
+    for (int64_t t = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; t < nnz; t += (int64_t)gridDim.x * VEC_BLOCK)
+        flag[t] = (t == 0 || key[t] != key[t - 1] || (t % PIECE_LEN) == 0) ? 1 : 0;
+}
+
+// piece_start[k] / piece_col[k]: first entry and column of piece k; piece_start ends with nnz, piece_col with
+// four sentinels (-1) so that readers may look a few pieces ahead
+__global__ __launch_bounds__(VEC_BLOCK) void csc_piece_start_kernel(const int32_t *flag, const int32_t *pid, const int32_t *key,
+                                                                    int64_t nnz, int32_t *piece_start, int32_t *piece_col,
+                                                                    int32_t *npieces_out)
+{
+    for (int64_t t = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; t < nnz; t += (int64_t)gridDim.x * VEC_BLOCK) {
+        if (flag[t]) {
+            piece_start[pid[t]] = (int32_t)t;
+            piece_col[pid[t]] = key[t];
+        }
+        if (t == nnz - 1) {
+            const int32_t np = pid[t] + flag[t];
+            piece_start[np] = (int32_t)nnz;
+            for (int k = 0; k < 4; ++k) piece_col[np + k] = -1;
+            *npieces_out = np;
+        }
+    }
+}
+
+static int grid_for(int64_t n)
+{
+    int64_t b = (n + VEC_BLOCK - 1) / VEC_BLOCK;
+    if (b > 65536) b = 65536;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+#define CSC_HIP(call)                                   \
+    do {                                                \
+        hipError_t e_ = (call);                         \
+        if (e_ != hipSuccess) return e_;                \
+    } while (0)
+
+static hipError_t grow(void **ptr, int64_t *cap, int64_t need, size_t elem)
+{
+    if (*cap >= need) return hipSuccess;
+    if (*ptr) CSC_HIP(hipFree(*ptr));
+    *ptr = nullptr;
+    *cap = 0;
+    const int64_t want = need + need / 8 + 64;
+    CSC_HIP(hipMalloc(ptr, (size_t)want * elem));
+    *cap = want;
+    return hipSuccess;
+}
+
+void csc_free(CscView *v)
+{
+    void *all[] = {v->key, v->row, v->val, v->piece_start, v->piece_col, v->piece_part, v->off, v->key_in, v->idx_in, v->idx_out,
+                   v->row_in, v->val_in, v->flag, v->pid, v->cub_tmp, v->count_dev};
+    for (void *q : all)
+        if (q) (void)hipFree(q);
+    *v = CscView{};
+}
+
+void csc_free_scratch(CscView *v)
+{
+    void *all[] = {v->key_in, v->idx_in, v->idx_out, v->row_in, v->val_in, v->flag, v->pid, v->cub_tmp};
+    for (void *q : all)
+        if (q) (void)hipFree(q);
+    v->key_in = v->idx_in = v->idx_out = v->row_in = v->flag = v->pid = nullptr;
+    v->val_in = v->cub_tmp = nullptr;
+    v->cap_in = v->cap_flag = v->cap_pid = 0;
+    v->cub_bytes = 0;
+}
+
+// Build the view of rows S[0..nrows) (S == nullptr: rows 0..nrows-1) of the CSR matrix.  Synchronises the
+// stream twice (entry count and piece count come back to size the buffers).
+hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t *colidx, const void *vals,
+                     const int32_t *S, int64_t nrows, int64_t p, int K, hipStream_t st)
+{
+    const size_t es = dtype == SSN_F32 ? 4 : 8;
+    v->nnz = 0;
+    v->npieces = 0;
+    if (!v->count_dev) CSC_HIP(hipMalloc((void **)&v->count_dev, 2 * sizeof(int32_t)));
+
+    auto cub_need = [&](size_t bytes) -> hipError_t {
+        if (bytes <= v->cub_bytes) return hipSuccess;
+        if (v->cub_tmp) CSC_HIP(hipFree(v->cub_tmp));
+        v->cub_tmp = nullptr;
+        v->cub_bytes = 0;
+        CSC_HIP(hipMalloc(&v->cub_tmp, bytes + 256));
+        v->cub_bytes = bytes + 256;
+        return hipSuccess;
+    };
+
+    // 1. offsets of the selected rows in the expanded entry list
+    CSC_HIP(grow((void **)&v->off, &v->cap_off, nrows + 1, sizeof(int32_t)));
+    CSC_HIP(grow((void **)&v->flag, &v->cap_flag, nrows + 1, sizeof(int32_t)));     // row lengths, for now
+    CSC_HIP(grow((void **)&v->pid, &v->cap_pid, nrows + 1, sizeof(int32_t)));
+    hipLaunchKernelGGL(csc_row_len_kernel, dim3(grid_for(nrows + 1)), dim3(VEC_BLOCK), 0, st, rowptr, S, nrows, v->flag);
+    size_t bytes = 0;
+    CSC_HIP(hipcub::DeviceScan::ExclusiveSum(nullptr, bytes, v->flag, v->off, (int)(nrows + 1), st));
+    CSC_HIP(cub_need(bytes));
+    bytes = v->cub_bytes;
+    CSC_HIP(hipcub::DeviceScan::ExclusiveSum(v->cub_tmp, bytes, v->flag, v->off, (int)(nrows + 1), st));
+    int32_t total32 = 0;
+    CSC_HIP(hipMemcpyAsync(&total32, v->off + nrows, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    CSC_HIP(hipStreamSynchronize(st));
+    const int64_t nnz = total32;
+    if (nnz < 0) return hipErrorInvalidValue;          // more than 2^31 entries selected
+    if (nnz == 0) return hipSuccess;
+
+    // 2. expand (column, position, sample row, value), sort by column (stable: rows stay in sample order)
+    CSC_HIP(grow((void **)&v->key, &v->cap, nnz, sizeof(int32_t)));
+    CSC_HIP(grow((void **)&v->row, &v->cap_row, nnz, sizeof(int32_t)));
+    CSC_HIP(grow(&v->val, &v->cap_val, nnz, es));
+    {
+        int64_t c0 = v->cap_in, c1 = v->cap_in, c2 = v->cap_in, c3 = v->cap_in, c4 = v->cap_in;
+        CSC_HIP(grow((void **)&v->key_in, &c0, nnz, sizeof(int32_t)));
+        CSC_HIP(grow((void **)&v->idx_in, &c1, nnz, sizeof(int32_t)));
+        CSC_HIP(grow((void **)&v->idx_out, &c2, nnz, sizeof(int32_t)));
+        CSC_HIP(grow((void **)&v->row_in, &c3, nnz, sizeof(int32_t)));
+        CSC_HIP(grow(&v->val_in, &c4, nnz, es));
+        v->cap_in = c0;
+    }
+    CSC_HIP(grow((void **)&v->flag, &v->cap_flag, nnz, sizeof(int32_t)));
+    CSC_HIP(grow((void **)&v->pid, &v->cap_pid, nnz, sizeof(int32_t)));
+    int64_t eb = (nrows + 3) / 4;
+    if (eb > 16384) eb = 16384;
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(csc_expand_kernel<float>, dim3((unsigned)eb), dim3(256), 0, st, rowptr, colidx, (const float *)vals,
+                           S, nrows, v->off, v->key_in, v->idx_in, v->row_in, (float *)v->val_in);
+    else
+        hipLaunchKernelGGL(csc_expand_kernel<double>, dim3((unsigned)eb), dim3(256), 0, st, rowptr, colidx,
+                           (const double *)vals, S, nrows, v->off, v->key_in, v->idx_in, v->row_in, (double *)v->val_in);
+    int bits = 1;
+    while (bits < 31 && ((int64_t)1 << bits) < p) ++bits;
+    bytes = 0;
+    CSC_HIP(hipcub::DeviceRadixSort::SortPairs(nullptr, bytes, v->key_in, v->key, v->idx_in, v->idx_out, (int)nnz, 0, bits, st));
+    CSC_HIP(cub_need(bytes));
+    bytes = v->cub_bytes;
+    CSC_HIP(hipcub::DeviceRadixSort::SortPairs(v->cub_tmp, bytes, v->key_in, v->key, v->idx_in, v->idx_out, (int)nnz, 0, bits,
+                                               st));
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(csc_permute_kernel<float>, dim3(grid_for(nnz)), dim3(VEC_BLOCK), 0, st, v->idx_out, v->row_in,
+                           (const float *)v->val_in, nnz, v->row, (float *)v->val);
+    else
+        hipLaunchKernelGGL(csc_permute_kernel<double>, dim3(grid_for(nnz)), dim3(VEC_BLOCK), 0, st, v->idx_out, v->row_in,
+                           (const double *)v->val_in, nnz, v->row, (double *)v->val);
+
+    // 3. pieces
+    hipLaunchKernelGGL(csc_piece_flag_kernel, dim3(grid_for(nnz)), dim3(VEC_BLOCK), 0, st, v->key, nnz, v->flag);
+    bytes = 0;
+    CSC_HIP(hipcub::DeviceScan::ExclusiveSum(nullptr, bytes, v->flag, v->pid, (int)nnz, st));
+    CSC_HIP(cub_need(bytes));
+    bytes = v->cub_bytes;
+    CSC_HIP(hipcub::DeviceScan::ExclusiveSum(v->cub_tmp, bytes, v->flag, v->pid, (int)nnz, st));
+    // there are at most nnz pieces: size the piece arrays from that bound, before the count is known
+    CSC_HIP(grow((void **)&v->piece_start, &v->cap_piece, nnz + 1, sizeof(int32_t)));
+    CSC_HIP(grow((void **)&v->piece_col, &v->cap_pcol, nnz + 4, sizeof(int32_t)));
+    hipLaunchKernelGGL(csc_piece_start_kernel, dim3(grid_for(nnz)), dim3(VEC_BLOCK), 0, st, v->flag, v->pid, v->key, nnz,
+                       v->piece_start, v->piece_col, v->count_dev);
+    int32_t np = 0;
+    CSC_HIP(hipMemcpyAsync(&np, v->count_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    CSC_HIP(hipStreamSynchronize(st));
+    CSC_HIP(grow(&v->piece_part, &v->cap_part, (int64_t)np * K, es));
+    CSC_HIP(hipGetLastError());
+    v->nnz = nnz;
+    v->npieces = np;
+    return hipSuccess;
+}
+
+// ---- the product ----------------------------------------------------------------------------
+struct CscApply {
+    const int32_t *row, *piece_start, *piece_col;
+    const void *val;
+    int32_t npieces;
+    int64_t nnz;
+    int32_t K, KP;
+    const void *U;           // rows indexed by the view's sample positions, stride KP
+    void *out;               // p x ldo, receives += coef * X^T U
+    int64_t ldo;
+    double coef;
+    const CgSlot *slot;      // nullable: coef *= -slot->alpha; nothing happens once that CG loop has ended
+    void *piece_part;
+    const int32_t *skip;
+};
+
+// lane group (slot) g of a wave = K lanes, one per class; NS = 64 / K groups per wave, one piece per group
+template <typename T> __global__ __launch_bounds__(256) void csc_piece_kernel(CscApply a)
+{
+    if (a.skip && *a.skip) return;
+    double coef = a.coef;
+    if (a.slot) {
+        if (a.slot->done || a.slot->brk) return;
+        coef *= -a.slot->alpha;
+    }
+    const int lane = threadIdx.x & 63;
+    const int K = a.K, NS = 64 / K;
+    const int s = lane / K, c = lane - s * K;
+    if (s >= NS) return;
+    const int64_t pid = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * NS + s;
+    if (pid >= a.npieces) return;
+    const T *val = (const T *)a.val;
+    const T *U = (const T *)a.U;
+    const int64_t t0 = a.piece_start[pid], t1 = a.piece_start[pid + 1];
+    const int col = a.piece_col[pid];
+    const bool head = (pid == 0) || (a.piece_col[pid - 1] != col);
+    const bool more = a.piece_col[pid + 1] == col;
+    T a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    int64_t t = t0;
+    for (; t + 3 < t1; t += 4) {             // four independent gathers in flight
+        const int64_t r0 = a.row[t], r1 = a.row[t + 1], r2 = a.row[t + 2], r3 = a.row[t + 3];
+        const T v0 = val[t], v1 = val[t + 1], v2 = val[t + 2], v3 = val[t + 3];
+        const T u0 = U[r0 * a.KP + c], u1 = U[r1 * a.KP + c], u2 = U[r2 * a.KP + c], u3 = U[r3 * a.KP + c];
+        a0 += v0 * u0;
+        a1 += v1 * u1;
+        a2 += v2 * u2;
+        a3 += v3 * u3;
+    }
+    for (; t < t1; ++t) a0 += val[t] * U[(int64_t)a.row[t] * a.KP + c];
+    const T acc = (a0 + a1) + (a2 + a3);
+    if (head && !more) {
+        T *o = (T *)a.out + (int64_t)col * a.ldo + c;
+        *o = (T)((double)*o + coef * (double)acc);
+    } else {
+        ((T *)a.piece_part)[pid * K + c] = acc;
+    }
+}
+
+// columns of several pieces: the group of the column's first piece adds the partial sums in piece order
+template <typename T> __global__ __launch_bounds__(256) void csc_combine_kernel(CscApply a)
+{
+    if (a.skip && *a.skip) return;
+    double coef = a.coef;
+    if (a.slot) {
+        if (a.slot->done || a.slot->brk) return;
+        coef *= -a.slot->alpha;
+    }
+    const int lane = threadIdx.x & 63;
+    const int K = a.K, NS = 64 / K;
+    const int s = lane / K, c = lane - s * K;
+    if (s >= NS) return;
+    const int64_t pid = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * NS + s;
+    if (pid >= a.npieces) return;
+    const int col = a.piece_col[pid];
+    const bool head = (pid == 0) || (a.piece_col[pid - 1] != col);
+    if (!head || a.piece_col[pid + 1] != col) return;
+    const T *pp = (const T *)a.piece_part;
+    T acc = pp[pid * K + c];
+    for (int64_t j = pid + 1;; j += 4) {     // four pieces per round; the adds keep the piece order
+        const bool m0 = a.piece_col[j] == col, m1 = m0 && a.piece_col[j + 1] == col;
+        const bool m2 = m1 && a.piece_col[j + 2] == col, m3 = m2 && a.piece_col[j + 3] == col;
+        const T p0 = m0 ? pp[j * K + c] : T(0), p1 = m1 ? pp[(j + 1) * K + c] : T(0);
+        const T p2 = m2 ? pp[(j + 2) * K + c] : T(0), p3 = m3 ? pp[(j + 3) * K + c] : T(0);
+        acc += p0;
+        acc += p1;
+        acc += p2;
+        acc += p3;
+        if (!m3) break;
+    }
+    T *o = (T *)a.out + (int64_t)col * a.ldo + c;
+    *o = (T)((double)*o + coef * (double)acc);
+}
+
+// out += coef * X_view^T U  (out already holds whatever the product is added to: lambda * M, or the CG
+// residual).  K <= 64.
+hipError_t launch_csc_apply(int dtype, const CscView &v, int K, int KP, const void *U, double coef, void *out, int64_t ldo,
+                            const CgSlot *slot, const int32_t *skip, hipStream_t st)
+{
+    if (v.npieces == 0) return hipSuccess;
+    CscApply a{};
+    a.row = v.row;
+    a.piece_start = v.piece_start;
+    a.piece_col = v.piece_col;
+    a.val = v.val;
+    a.npieces = v.npieces;
+    a.nnz = v.nnz;
+    a.K = K;
+    a.KP = KP;
+    a.U = U;
+    a.out = out;
+    a.ldo = ldo;
+    a.coef = coef;
+    a.slot = slot;
+    a.piece_part = v.piece_part;
+    a.skip = skip;
+    const int NS = 64 / K;
+    const int64_t waves = ((int64_t)v.npieces + NS - 1) / NS;
+    const unsigned blocks = (unsigned)((waves + 3) / 4);
+    if (dtype == SSN_F32) {
+        hipLaunchKernelGGL(csc_piece_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(csc_combine_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
+    } else {
+        hipLaunchKernelGGL(csc_piece_kernel<double>, dim3(blocks), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(csc_combine_kernel<double>, dim3(blocks), dim3(256), 0, st, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace ssn

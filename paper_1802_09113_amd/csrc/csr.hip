@@ -1,5 +1,5 @@
-// CSR kernels: row-per-wavefront SpMM with the per-row epilogue fused in, and the transposed
-// product X_rows^T U.
+// CSR kernels: row-per-wavefront SpMM with the per-row epilogue fused in (the transposed product is in
+// csc.hip).
 //
 // rows kernel: one wavefront owns one row at a time.  Lanes are split as (slot, class): NS = 64/K
 // stored entries are processed per step, lane (s,c) gathers M[col_s, c] -- the K values of one feature
@@ -140,54 +140,6 @@ template <typename T> static hipError_t csr_rows_dispatch(const RowsArgs &a, int
 hipError_t launch_csr_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st)
 {
     return dtype == SSN_F32 ? csr_rows_dispatch<float>(a, blocks, st) : csr_rows_dispatch<double>(a, blocks, st);
-}
-
-// out[col, c] += scale * x * U[sv, c] for every stored entry of the selected rows.
-// out must already hold lambda * M.  Hardware floating-point atomics on device memory: the summation
-// order, and therefore the last bits, vary from run to run.
-// slot (nullable): the scatter is the sparse part of the CG residual update r -= alpha * scale * X_S^T U of
-// a product whose step length waits in the slot; nothing happens when that CG loop has ended.
-template <typename T>
-__global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void csr_scatter_kernel(XtuArgs a, double scale, T *out, int64_t ldo,
-                                                                                const CgSlot *slot)
-{
-    if (a.skip && *a.skip) return;
-    if (slot) {
-        if (slot->done || slot->brk) return;
-        scale *= -slot->alpha;
-    }
-    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    const int64_t nwaves = (int64_t)gridDim.x * ROWS_WAVES_PER_BLOCK;
-    const int64_t wave = (int64_t)blockIdx.x * ROWS_WAVES_PER_BLOCK + wib;
-    const int K = a.K;
-    const int NS = 64 / K;
-    const int s = lane / K, c = lane - s * K;
-    if (s >= NS) return;
-    const T *vals = (const T *)a.vals;
-    const T *U = (const T *)a.U;
-    const T sc = (T)scale;
-    for (int64_t sv = wave; sv < a.nrows; sv += nwaves) {
-        const int64_t row = a.S ? a.S[sv] : sv;
-        const T u = sc * U[sv * a.KP + c];
-        const int64_t b = a.rowptr[row], e = a.rowptr[row + 1];
-        for (int64_t t = b + s; t < e; t += NS) {
-            const int64_t col = a.colidx[t];
-            unsafeAtomicAdd(out + col * ldo + c, vals[t] * u);
-        }
-    }
-}
-
-hipError_t launch_csr_scatter(int dtype, const XtuArgs &a, double scale, void *out, int64_t ldo, const CgSlot *slot,
-                              hipStream_t st)
-{
-    int64_t blocks = (a.nrows + ROWS_WAVES_PER_BLOCK - 1) / ROWS_WAVES_PER_BLOCK;
-    if (blocks > 8192) blocks = 8192;
-    dim3 grid((unsigned)blocks), block(64 * ROWS_WAVES_PER_BLOCK);
-    if (dtype == SSN_F32)
-        hipLaunchKernelGGL(csr_scatter_kernel<float>, grid, block, 0, st, a, scale, (float *)out, ldo, slot);
-    else
-        hipLaunchKernelGGL(csr_scatter_kernel<double>, grid, block, 0, st, a, scale, (double *)out, ldo, slot);
-    return hipGetLastError();
 }
 
 }  // namespace ssn

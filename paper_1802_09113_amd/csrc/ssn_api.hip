@@ -32,6 +32,10 @@ struct ssn_ctx {
     int64_t part_elems = 0;
     int max_chunks = 0;
     bool fused = false;           // dense: the one-pass kernel serves this shape
+    // CSR: column-sorted views for the transposed products (whole matrix: built at the first gradient;
+    // sample: rebuilt by every ssn_hess_prepare)
+    CscView csc_full, csc_samp;
+    bool csc_full_built = false;
     // reduction scratch
     double *loss_part = nullptr;
     int32_t *hit_part = nullptr;
@@ -207,6 +211,24 @@ int finalize_dense(ssn_ctx *c, int nchunks, double scale, const void *M, void *o
     return SSN_OK;
 }
 
+// CSR: the column-sorted view of the rows a transposed product runs over (S == nullptr: the whole matrix,
+// built on first use; otherwise the prepared sample's)
+int csc_view_for(ssn_ctx *c, const int32_t *S, const CscView **view)
+{
+    if (S) {
+        *view = &c->csc_samp;
+        return SSN_OK;
+    }
+    if (!c->csc_full_built) {
+        SSN_HIP(c, csc_build(&c->csc_full, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, nullptr, c->d.n, c->d.p, c->K,
+                             c->st));
+        csc_free_scratch(&c->csc_full);
+        c->csc_full_built = true;
+    }
+    *view = &c->csc_full;
+    return SSN_OK;
+}
+
 // out = scale * X_rows^T U + lambda * M ; optionally partials of <out, M> into red_b (count in *ndot)
 int transposed_product(ssn_ctx *c, const int32_t *S, int64_t nrows, double scale, const void *M, void *out,
                        bool want_dot, int *ndot, const int32_t *skip)
@@ -221,8 +243,10 @@ int transposed_product(ssn_ctx *c, const int32_t *S, int64_t nrows, double scale
         SSN_HIP(c, launch_dense_xtu(c->d.dtype, x, c->st));
         SSN_TRY(finalize_dense(c, x.nchunks, scale, M, out, want_dot, ndot, skip));
     } else {
+        const CscView *view = nullptr;
+        SSN_TRY(csc_view_for(c, S, &view));
         SSN_HIP(c, launch_scale_copy(c->d.dtype, c->d.p, c->K, c->d.lambda, M, c->d.ldw, out, c->d.ldw, skip, c->st));
-        SSN_HIP(c, launch_csr_scatter(c->d.dtype, x, scale, out, c->d.ldw, nullptr, c->st));
+        SSN_HIP(c, launch_csc_apply(c->d.dtype, *view, c->K, c->KP, c->Ubuf, scale, out, c->d.ldw, nullptr, skip, c->st));
         if (want_dot) {
             const int vb = vec_blocks(c->d.p * (int64_t)c->K);
             SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, out, c->d.ldw, M, c->d.ldw, c->red_b, vb, skip, c->st));
@@ -369,12 +393,8 @@ int cg_product_step(ssn_ctx *c, const CgVecs &v, CgSlot *cur, int n_ss, double *
     }
     // CSR: alpha first, then the few entries of r the sample's columns touch, then one dense pass over r and s
     SSN_HIP(c, launch_cg_alpha(cur, c->loss_part, nparts, c->red_c, n_ss, scale_sample(c), c->d.lambda, trace_k, c->st));
-    XtuArgs x = xtu_base(c);
-    x.S = c->S;
-    x.nrows = c->nS;
-    x.U = c->Ubuf;
-    x.skip = skip;
-    SSN_HIP(c, launch_csr_scatter(c->d.dtype, x, scale_sample(c), v.r, c->d.ldw, cur, c->st));
+    SSN_HIP(c, launch_csc_apply(c->d.dtype, c->csc_samp, c->K, c->KP, c->Ubuf, scale_sample(c), v.r, c->d.ldw, cur, skip,
+                                c->st));
     const int vb = vec_blocks(c->d.p * (int64_t)c->K);
     SSN_HIP(c, launch_cg_r_update(c->d.dtype, v, cur, c->d.lambda, c->red_a, vb, c->st));
     *n_rr = vb;
@@ -419,6 +439,8 @@ int ssn_destroy(ssn_ctx *c)
     for (void *p : dev)
         if (p) (void)hipFree(p);
     if (c->host_pin) (void)hipHostFree(c->host_pin);
+    csc_free(&c->csc_full);
+    csc_free(&c->csc_samp);
     delete c;
     return SSN_OK;
 }
@@ -549,6 +571,8 @@ int ssn_hess_prepare(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS)
     a.mode = ROW_PREP;
     a.UP = c->Pbuf;
     SSN_TRY(launch_rows(c, a, nullptr));
+    if (!is_dense(c))
+        SSN_HIP(c, csc_build(&c->csc_samp, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.p, c->K, c->st));
     c->S = S;
     c->nS = nS;
     c->prepared = true;
@@ -784,7 +808,13 @@ int ssn_time_kernel(ssn_ctx *c, int32_t which, const void *M, int32_t reps, doub
         if (which == 2 || which == 4) {
             if (c->fused) status = finalize_dense(c, fused_parts, sampled ? scale_sample(c) : scale_full(c), M, c->trial, false, nullptr, nullptr);
             else if (is_dense(c)) he = launch_dense_xtu(c->d.dtype, x, c->st);
-            else he = launch_csr_scatter(c->d.dtype, x, sampled ? scale_sample(c) : scale_full(c), c->trial, c->d.ldw, nullptr, c->st);
+            else {
+                const CscView *view = nullptr;
+                status = csc_view_for(c, a.S, &view);
+                if (status == SSN_OK)
+                    he = launch_csc_apply(c->d.dtype, *view, c->K, c->KP, c->Ubuf, sampled ? scale_sample(c) : scale_full(c),
+                                          c->trial, c->d.ldw, nullptr, nullptr, c->st);
+            }
         } else {
             status = launch_rows(c, a, nullptr);
         }

@@ -102,9 +102,6 @@ int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus);
 int dense_fused_waves(int dtype, const RowsArgs &a);
 hipError_t launch_dense_fused(int dtype, const RowsArgs &a, int grid, hipStream_t st);
 hipError_t launch_csr_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
-// slot (nullable): multiply by -slot->alpha and do nothing when that CG loop has ended
-hipError_t launch_csr_scatter(int dtype, const XtuArgs &a, double scale, void *out, int64_t ldo, const CgSlot *slot,
-                              hipStream_t st);
 hipError_t launch_finalize(int dtype, const FinArgs &a, int blocks, hipStream_t st);
 
 // out = lambda * M (p x K), with optional <.,.> partials disabled; used by the CSR path before scattering
@@ -127,6 +124,35 @@ hipError_t launch_sum_int(const int32_t *a, int na, int32_t *out, hipStream_t st
 // validation passes: *bad receives the number of offending entries
 hipError_t launch_check_range(const int32_t *v, int64_t count, int64_t lo, int64_t hi, int32_t *bad, hipStream_t st);
 hipError_t launch_check_rowptr(const int32_t *rowptr, int64_t n, int64_t nnz, int32_t *bad, hipStream_t st);
+
+// ---- column-sorted view of a set of CSR rows (csc.hip) --------------------------------------------
+struct CscView {
+    int64_t nnz = 0;                 // entries in the view
+    int32_t npieces = 0;
+    int32_t *key = nullptr;          // column of entry t, ascending
+    int32_t *row = nullptr;          // position of entry t's row in the row selection the view was built from
+    void *val = nullptr;
+    int32_t *piece_start = nullptr;  // npieces + 1
+    int32_t *piece_col = nullptr;    // npieces + 4 (sentinels -1)
+    void *piece_part = nullptr;      // npieces x K partial sums of the pieces of multi-piece columns
+    // construction scratch (kept by the sample view, which is rebuilt at every ssn_hess_prepare)
+    int32_t *off = nullptr, *key_in = nullptr, *idx_in = nullptr, *idx_out = nullptr, *row_in = nullptr;
+    void *val_in = nullptr;
+    int32_t *flag = nullptr, *pid = nullptr;
+    void *cub_tmp = nullptr;
+    size_t cub_bytes = 0;
+    int32_t *count_dev = nullptr;
+    int64_t cap = 0, cap_row = 0, cap_val = 0, cap_piece = 0, cap_pcol = 0, cap_part = 0, cap_off = 0, cap_in = 0,
+            cap_flag = 0, cap_pid = 0;
+};
+hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t *colidx, const void *vals,
+                     const int32_t *S, int64_t nrows, int64_t p, int K, hipStream_t st);
+void csc_free(CscView *v);
+void csc_free_scratch(CscView *v);
+// out += coef * X_view^T U (U rows indexed like the view's row selection); slot (nullable): multiply by
+// -slot->alpha and do nothing once that CG loop has ended
+hipError_t launch_csc_apply(int dtype, const CscView &v, int K, int KP, const void *U, double coef, void *out, int64_t ldo,
+                            const CgSlot *slot, const int32_t *skip, hipStream_t st);
 
 // ---- device-resident CG (Alg. 2) ---------------------------------------------------------
 struct CgSlot {          // state before product k

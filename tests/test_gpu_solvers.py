@@ -185,19 +185,27 @@ def test_error_paths(tiny):
     ok.close()
 
 
-def test_results_are_deterministic_on_the_dense_path(tiny):
-    pair = Pair(tiny, F64)
+@pytest.mark.parametrize("cfg,n", [(0, 2000), (1, 3001), (2, 1003), (4, 403)],
+                         ids=["narrow", "one_pass", "two_kernel", "csr"])
+def test_results_are_deterministic(cfg, n):
+    # every reduction has a fixed order on every path (the CSR transposed product gathers by column
+    # instead of scattering with atomics), so two runs give the same bits
+    d = workload(cfg, n)
+    pair = Pair(d, F64)
     Wh, Wd = pair.block(synth.probe(pair.p, pair.K, sub=1, scale=0.2))
     Vh, Vd = pair.block(synth.probe(pair.p, pair.K, sub=2))
-    Sd = pair.idx(synth.sample_rows(2000, 100))
+    Sd = pair.idx(synth.sample_rows(n, max(100, d["nS"])))
     runs = []
     for _ in range(2):
+        print(f"[case] determinism cfg={cfg} n={n}", flush=True)
         f = pair.gpu.ssn_objective(Wd)
         G, _ = pair.gpu.ssn_gradient(Wd)
         HV = pair.gpu.ssn_hessvec(Wd, Sd, Vd)
+        out = pair.gpu.ssn_cg(G, 1e-6, 8, want_trace=True)
         torch.cuda.synchronize()
-        runs.append((f, G.clone(), HV.clone()))
+        runs.append((f, G.clone(), HV.clone(), out["p"].clone(), np.array(out["alpha"] + out["rnorm"] + out["sHs"])))
     assert runs[0][0] == runs[1][0]
-    assert torch.equal(runs[0][1][:, : pair.K], runs[1][1][:, : pair.K])
-    assert torch.equal(runs[0][2][:, : pair.K], runs[1][2][:, : pair.K])
+    for k in (1, 2, 3):
+        assert torch.equal(runs[0][k][:, : pair.K], runs[1][k][:, : pair.K]), k
+    assert np.array_equal(runs[0][4], runs[1][4])
     pair.close()
