@@ -230,16 +230,23 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
 }
 
 // One wave per 16-row block; grid-stride over row blocks.  UP / Pin have ceil(nrows/16)*16 rows.
-template <typename T, int NB, int VEC, int MODE>
-__global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void dense_rows_kernel(RowsArgs a)
+//
+// SPLIT: for a few thousand rows there are too few row blocks to fill the chip with one wave each, and a
+// wave that walks all p features alone is a long chain of dependent loads.  Then a whole workgroup (8 or
+// 16 waves) shares one row block: the waves take the feature groups in turn, their partial margins are
+// added through LDS in wave order, and wave 0 does the per-row work.
+template <typename T, int NB, int VEC, int MODE, bool SPLIT>
+__global__ __launch_bounds__(SPLIT ? 1024 : 64 * ROWS_WAVES_PER_BLOCK) void dense_rows_kernel(RowsArgs a)
 {
     if (a.skip && *a.skip) return;
     typedef typename V4<T>::type v4;
     typedef Pack<T, VEC> pack;
+    extern __shared__ __align__(16) unsigned char rows_smem[];
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const int nsw = blockDim.x >> 6;                  // SPLIT: waves sharing the row block
     const int q = lane & 15, g = lane >> 4;
-    const int64_t nwaves = (int64_t)gridDim.x * ROWS_WAVES_PER_BLOCK;
-    const int64_t wave = (int64_t)blockIdx.x * ROWS_WAVES_PER_BLOCK + wib;
+    const int64_t nwaves = SPLIT ? (int64_t)gridDim.x : (int64_t)gridDim.x * ROWS_WAVES_PER_BLOCK;
+    const int64_t wave = SPLIT ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * ROWS_WAVES_PER_BLOCK + wib;
     const T *X = (const T *)a.X;
     const T *M = (const T *)a.M;
     const int K = a.K;
@@ -269,8 +276,9 @@ __global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void dense_rows_kernel(R
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[nb] = v4{0, 0, 0, 0};
 
-        int64_t f0 = 0;
-        for (; f0 + STEP * UNR <= p; f0 += STEP * UNR) {
+        int64_t f0 = SPLIT ? (int64_t)wib * (STEP * UNR) : 0;
+        const int64_t fstride = SPLIT ? (int64_t)nsw * (STEP * UNR) : STEP * UNR;
+        for (; f0 + STEP * UNR <= p; f0 += fstride) {
             pack xv[UNR];
             T wv[UNR][VEC][NB];
 #pragma unroll
@@ -290,6 +298,8 @@ __global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void dense_rows_kernel(R
                     for (int nb = 0; nb < NB; ++nb)
                         acc[nb] = mfma16(xv[u].v[m], cval[nb] ? wv[u][m][nb] : T(0), acc[nb]);
         }
+        f0 = p / (STEP * UNR) * (STEP * UNR);
+        if (SPLIT && wib != 0) f0 = p;                 // the tail belongs to wave 0
         for (; f0 < p; f0 += STEP) {                   // guarded tail
             const int64_t f = f0 + VEC * g;
 #pragma unroll
@@ -303,15 +313,43 @@ __global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void dense_rows_kernel(R
                 }
             }
         }
-        row_epilogue<T, NB, MODE>(acc, a, rb, lane, loss, hits);
+        if constexpr (SPLIT) {
+            T *zs = (T *)rows_smem;                    // nsw x NB x 4 x 64
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) zs[((wib * NB + nb) * 4 + v) * 64 + lane] = acc[nb][v];
+            __syncthreads();
+            if (wib == 0) {
+                for (int ww = 1; ww < nsw; ++ww)       // fixed order
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[nb][v] += zs[((ww * NB + nb) * 4 + v) * 64 + lane];
+                row_epilogue<T, NB, MODE>(acc, a, rb, lane, loss, hits);
+            }
+            __syncthreads();
+        } else {
+            row_epilogue<T, NB, MODE>(acc, a, rb, lane, loss, hits);
+        }
     }
 
+    // one partial per wave; SPLIT: the block's four partial slots are wave 0's sum and three zeros
+    if (SPLIT && wib != 0) return;
     if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_APPLY) {
         for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off);
-        if (lane == 0) a.loss_part[wave] = loss;
+        if constexpr (SPLIT) {
+            if (lane < ROWS_WAVES_PER_BLOCK) a.loss_part[wave * ROWS_WAVES_PER_BLOCK + lane] = (lane == 0) ? loss : 0.0;
+        } else {
+            if (lane == 0) a.loss_part[wave] = loss;
+        }
     } else if constexpr (MODE == ROW_PRED) {
         for (int off = 32; off > 0; off >>= 1) hits += __shfl_xor(hits, off);
-        if (lane == 0) a.hit_part[wave] = hits;
+        if constexpr (SPLIT) {
+            if (lane < ROWS_WAVES_PER_BLOCK) a.hit_part[wave * ROWS_WAVES_PER_BLOCK + lane] = (lane == 0) ? hits : 0;
+        } else {
+            if (lane == 0) a.hit_part[wave] = hits;
+        }
     }
 }
 
@@ -408,39 +446,64 @@ template <typename T> static bool vec_ok(const void *X, int64_t ldx)
     return ((uintptr_t)X % 16 == 0) && (ldx % VEC == 0);
 }
 
-template <typename T, int MODE> static hipError_t rows_dispatch_mode(const RowsArgs &a, int blocks, hipStream_t st)
+// Workgroups and waves per workgroup of the wave-per-row-block kernel: *split_waves == 0 is the plain
+// form (4 waves, one row block each); otherwise each workgroup of *split_waves waves shares a row block.
+void dense_rows_plan(int dtype, int64_t nrows, int64_t p, int K, int num_cus, int *blocks, int *split_waves)
+{
+    const int64_t nblk = (nrows + 15) / 16;
+    const size_t es = dtype == SSN_F32 ? 4 : 8;
+    const int nb = (K + 15) / 16;
+    *split_waves = 0;
+    *blocks = rows_grid_blocks(nrows, num_cus);
+    if (nblk <= (int64_t)num_cus * 2 && p >= 512) {
+        int w = p >= 2048 ? 16 : 8;
+        if ((size_t)w * nb * 256 * es > 32768) w = 8;
+        *split_waves = w;
+        *blocks = (int)(nblk < 1 ? 1 : nblk);
+    }
+}
+
+template <typename T, int MODE>
+static hipError_t rows_dispatch_mode(const RowsArgs &a, int blocks, int split_waves, hipStream_t st)
 {
     constexpr int VEC = 16 / sizeof(T);
     const int nb = (a.K + 15) / 16;
     const bool v = vec_ok<T>(a.X, a.ldx);
+    if (nb != 1 && nb != 2) return hipErrorInvalidValue;
+    if (split_waves > 0 && v) {
+        dim3 grid(blocks), block(64 * split_waves);
+        const size_t lds = (size_t)split_waves * nb * 256 * sizeof(T);
+        if (nb == 1) hipLaunchKernelGGL((dense_rows_kernel<T, 1, VEC, MODE, true>), grid, block, lds, st, a);
+        else hipLaunchKernelGGL((dense_rows_kernel<T, 2, VEC, MODE, true>), grid, block, lds, st, a);
+        return hipGetLastError();
+    }
+    if (split_waves > 0) return hipErrorInvalidValue;      // the planner splits only 16-byte aligned rows
     dim3 grid(blocks), block(64 * ROWS_WAVES_PER_BLOCK);
     if (nb == 1) {
-        if (v) hipLaunchKernelGGL((dense_rows_kernel<T, 1, VEC, MODE>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((dense_rows_kernel<T, 1, 1, MODE>), grid, block, 0, st, a);
-    } else if (nb == 2) {
-        if (v) hipLaunchKernelGGL((dense_rows_kernel<T, 2, VEC, MODE>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((dense_rows_kernel<T, 2, 1, MODE>), grid, block, 0, st, a);
+        if (v) hipLaunchKernelGGL((dense_rows_kernel<T, 1, VEC, MODE, false>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((dense_rows_kernel<T, 1, 1, MODE, false>), grid, block, 0, st, a);
     } else {
-        return hipErrorInvalidValue;
+        if (v) hipLaunchKernelGGL((dense_rows_kernel<T, 2, VEC, MODE, false>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((dense_rows_kernel<T, 2, 1, MODE, false>), grid, block, 0, st, a);
     }
     return hipGetLastError();
 }
 
-template <typename T> static hipError_t rows_dispatch(const RowsArgs &a, int blocks, hipStream_t st)
+template <typename T> static hipError_t rows_dispatch(const RowsArgs &a, int blocks, int split_waves, hipStream_t st)
 {
     switch (a.mode) {
-    case ROW_OBJ: return rows_dispatch_mode<T, ROW_OBJ>(a, blocks, st);
-    case ROW_GRAD: return rows_dispatch_mode<T, ROW_GRAD>(a, blocks, st);
-    case ROW_PREP: return rows_dispatch_mode<T, ROW_PREP>(a, blocks, st);
-    case ROW_APPLY: return rows_dispatch_mode<T, ROW_APPLY>(a, blocks, st);
-    case ROW_PRED: return rows_dispatch_mode<T, ROW_PRED>(a, blocks, st);
+    case ROW_OBJ: return rows_dispatch_mode<T, ROW_OBJ>(a, blocks, split_waves, st);
+    case ROW_GRAD: return rows_dispatch_mode<T, ROW_GRAD>(a, blocks, split_waves, st);
+    case ROW_PREP: return rows_dispatch_mode<T, ROW_PREP>(a, blocks, split_waves, st);
+    case ROW_APPLY: return rows_dispatch_mode<T, ROW_APPLY>(a, blocks, split_waves, st);
+    case ROW_PRED: return rows_dispatch_mode<T, ROW_PRED>(a, blocks, split_waves, st);
     default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_dense_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st)
+hipError_t launch_dense_rows(int dtype, const RowsArgs &a, int blocks, int split_waves, hipStream_t st)
 {
-    return dtype == SSN_F32 ? rows_dispatch<float>(a, blocks, st) : rows_dispatch<double>(a, blocks, st);
+    return dtype == SSN_F32 ? rows_dispatch<float>(a, blocks, split_waves, st) : rows_dispatch<double>(a, blocks, split_waves, st);
 }
 
 template <typename T> static hipError_t xtu_dispatch(const XtuArgs &a, hipStream_t st)

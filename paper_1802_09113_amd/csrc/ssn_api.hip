@@ -165,9 +165,12 @@ int launch_rows(ssn_ctx *c, const RowsArgs &a, int *nparts)
         return SSN_OK;
     }
     // dense: one wave per 16-row block; CSR: one wave per row
-    const int blocks = rows_grid_blocks(is_dense(c) ? a.nrows : a.nrows * 16, c->num_cus);
+    int blocks = rows_grid_blocks(is_dense(c) ? a.nrows : a.nrows * 16, c->num_cus), split_waves = 0;
+    // few row blocks of a wide matrix: a workgroup per row block (needs 16-byte aligned rows)
+    if (is_dense(c) && (uintptr_t)c->d.X % 16 == 0 && (c->d.ldx * (int64_t)c->es) % 16 == 0)
+        dense_rows_plan(c->d.dtype, a.nrows, c->d.p, c->K, c->num_cus, &blocks, &split_waves);
     if (blocks * ROWS_WAVES_PER_BLOCK > c->wave_parts) return fail(c, SSN_E_INVALID_ARG, "internal: wave partial overflow");
-    if (is_dense(c)) SSN_HIP(c, launch_dense_rows(c->d.dtype, a, blocks, c->st));
+    if (is_dense(c)) SSN_HIP(c, launch_dense_rows(c->d.dtype, a, blocks, split_waves, c->st));
     else SSN_HIP(c, launch_csr_rows(c->d.dtype, a, blocks, c->st));
     if (nparts) *nparts = blocks * ROWS_WAVES_PER_BLOCK;
     return SSN_OK;

@@ -95,7 +95,8 @@ int vec_blocks(int64_t total);
 int finalize_blocks(int64_t p, int K);
 
 // ---- launchers (dense_mfma.hip / csr.hip / vecops.hip) ---------------------------------
-hipError_t launch_dense_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
+void dense_rows_plan(int dtype, int64_t nrows, int64_t p, int K, int num_cus, int *blocks, int *split_waves);
+hipError_t launch_dense_rows(int dtype, const RowsArgs &a, int blocks, int split_waves, hipStream_t st);
 hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st);
 bool dense_fused_supported(int dtype, const RowsArgs &a);
 int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus);
