@@ -89,29 +89,57 @@ __device__ __forceinline__ double t_exp(double x) { return exp_nonpos(x); }
 __device__ __forceinline__ float t_log(float x) { return logf(x); }
 __device__ __forceinline__ double t_log(double x) { return log_ge1(x); }
 
-// butterfly over the 16 lanes that hold the 16 class columns of one row
+// Reductions over the 16 lanes that hold the 16 class columns of one row: four rotate-and-combine steps
+// inside the row (DPP row_ror 8, 4, 2, 1 -- register-to-register, no trip through the LDS crossbar),
+// after which every lane of the row holds the result.
+template <int ROT> __device__ __forceinline__ int dpp_ror(int x)
+{
+    return __builtin_amdgcn_update_dpp(x, x, 0x120 + ROT, 0xF, 0xF, false);
+}
+template <int ROT> __device__ __forceinline__ float row_ror(float x) { return __int_as_float(dpp_ror<ROT>(__float_as_int(x))); }
+template <int ROT> __device__ __forceinline__ double row_ror(double x)
+{
+    return __hiloint2double(dpp_ror<ROT>(__double2hiint(x)), dpp_ror<ROT>(__double2loint(x)));
+}
+template <int ROT> __device__ __forceinline__ int row_ror(int x) { return dpp_ror<ROT>(x); }
 template <typename T> __device__ __forceinline__ T row16_sum(T x)
 {
-    x += __shfl_xor(x, 8);
-    x += __shfl_xor(x, 4);
-    x += __shfl_xor(x, 2);
-    x += __shfl_xor(x, 1);
+    x += row_ror<8>(x);
+    x += row_ror<4>(x);
+    x += row_ror<2>(x);
+    x += row_ror<1>(x);
     return x;
 }
 template <typename T> __device__ __forceinline__ T row16_max(T x)
 {
-    x = fmax(x, __shfl_xor(x, 8));
-    x = fmax(x, __shfl_xor(x, 4));
-    x = fmax(x, __shfl_xor(x, 2));
-    x = fmax(x, __shfl_xor(x, 1));
+    x = fmax(x, row_ror<8>(x));
+    x = fmax(x, row_ror<4>(x));
+    x = fmax(x, row_ror<2>(x));
+    x = fmax(x, row_ror<1>(x));
     return x;
 }
 __device__ __forceinline__ int row16_min(int x)
 {
-    x = min(x, __shfl_xor(x, 8));
-    x = min(x, __shfl_xor(x, 4));
-    x = min(x, __shfl_xor(x, 2));
-    x = min(x, __shfl_xor(x, 1));
+    x = min(x, row_ror<8>(x));
+    x = min(x, row_ror<4>(x));
+    x = min(x, row_ror<2>(x));
+    x = min(x, row_ror<1>(x));
+    return x;
+}
+
+// 1 / a for a in [1, 17]: hardware estimate plus two Newton steps (about one ulp), a fraction of the
+// instructions of an IEEE division
+__device__ __forceinline__ double fast_rcp(double a)
+{
+    double x = __builtin_amdgcn_rcp(a);
+    x = fma(fma(-a, x, 1.0), x, x);
+    x = fma(fma(-a, x, 1.0), x, x);
+    return x;
+}
+__device__ __forceinline__ float fast_rcp(float a)
+{
+    float x = __builtin_amdgcn_rcpf(a);
+    x = fmaf(fmaf(-a, x, 1.0f), x, x);
     return x;
 }
 
@@ -535,7 +563,7 @@ hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st)
 // loaded by the caller.  Returns U (ROW_GRAD: eq. (6) residual p - y; ROW_APPLY: eq. (12)).
 template <typename T, int MODE>
 __device__ __forceinline__ T slot_epilogue(T z, const RowsArgs &a, int64_t sv, int q, int lab, T pin, double &loss,
-                                           int &hits)
+                                           double &lprod, int &hits)
 {
     const int K = a.K;
     const bool valid = sv < a.nrows;
@@ -549,8 +577,8 @@ __device__ __forceinline__ T slot_epilogue(T z, const RowsArgs &a, int64_t sv, i
         if (valid && q == 0) loss += (double)zu;
         return u;
     }
-    const T zmax = row16_max(cv ? z : NEG);
     if constexpr (MODE == ROW_PRED) {
+        const T zmax = row16_max(cv ? z : NEG);
         const int cand = row16_min((cv && z == zmax) ? q : 0x7fffffff);
         const int pr = (T(0) > zmax) ? K : cand;           // the reference class wins only strictly
         if (valid && q == 0) {
@@ -559,16 +587,37 @@ __device__ __forceinline__ T slot_epilogue(T z, const RowsArgs &a, int64_t sv, i
         }
         return T(0);
     }
-    const T Mx = fmax(T(0), zmax);                         // eq. (8)
-    const T e = cv ? t_exp(z - Mx) : T(0);
-    const T alpha = t_exp(-Mx) + row16_sum(e);             // eq. (9)
+    // eqs. (8), (9).  With K < 16 the lane of column K is free: it plays the reference class (margin 0), so
+    // M = max{0, z} is one row maximum and alpha = e^{-M} + sum_c e^{z_c - M} one row sum of one
+    // exponential per lane.
+    const bool ref_lane = K < 16;
+    const T zz = (q == K) ? T(0) : z;
+    const bool ce = ref_lane ? (q <= K) : cv;
+    const T zmax = row16_max(ce ? zz : NEG);
+    const T Mx = ref_lane ? zmax : fmax(T(0), zmax);
+    const T e = ce ? t_exp(zz - Mx) : T(0);
+    T alpha = row16_sum(e);
+    if (!ref_lane) alpha += t_exp(-Mx);
+    const T inv = fast_rcp(alpha);
     if constexpr (MODE == ROW_PREP) {
-        ((T *)a.UP)[sv * a.KP + q] = valid ? e / alpha : T(0);
+        ((T *)a.UP)[sv * a.KP + q] = (valid && cv) ? e * inv : T(0);
         return T(0);
     }
-    const T lin = row16_sum((cv && q == lab) ? z : T(0));
-    if (valid && q == 0) loss += (double)Mx + (double)t_log(alpha) - (double)lin;   // eqs. (14)-(17)
-    if constexpr (MODE == ROW_GRAD) return (valid && cv) ? (e / alpha - ((q == lab) ? T(1) : T(0))) : T(0);
+    // margin of the label's class, read from the lane that holds it (0 for the reference class)
+    const T zl = __shfl(z, (threadIdx.x & 48) | (lab & 15));
+    const T lin = (lab < K) ? zl : T(0);
+    // eqs. (14)-(17): the row adds M + log(alpha) - z_label.  The logarithms are taken of a running product
+    // of the alphas (each in [1, C]) instead of one by one; the product is folded into the sum before it
+    // can overflow, and once more at the end of the kernel.
+    if (valid && q == 0) {
+        loss += (double)Mx - (double)lin;
+        lprod *= (double)alpha;
+    }
+    if (lprod > 1e250) {
+        loss += log(lprod);
+        lprod = 1.0;
+    }
+    if constexpr (MODE == ROW_GRAD) return (valid && cv) ? (e * inv - ((q == lab) ? T(1) : T(0))) : T(0);
     return T(0);
 }
 
@@ -609,6 +658,7 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
 
 #ifdef SSN_PROFILE_PHASES
     const long long t_entry = clock64();
+    const long long w_entry = wall_clock64();
 #endif
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, nw = blockDim.x >> 6;
@@ -795,7 +845,7 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     v4 G[HAS_C ? NT : 1];
 #pragma unroll
     for (int t = 0; t < (HAS_C ? NT : 1); ++t) G[t] = v4{0, 0, 0, 0};
-    double loss = 0.0;
+    double loss = 0.0, lprod = 1.0;         // sum of the row terms without log(alpha); product of the alphas
     int hits = 0;
     int it = 0;
 
@@ -875,7 +925,7 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
         if constexpr (MAXW == 1) {
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                u[v] = slot_epilogue<T, MODE>(z[v], a, rb * 16 + d_row<T>(g, v), q, lab_pre[v], pin_pre[v], loss, hits);
+                u[v] = slot_epilogue<T, MODE>(z[v], a, rb * 16 + d_row<T>(g, v), q, lab_pre[v], pin_pre[v], loss, lprod, hits);
         } else {
             T *zp = zpart + (HAS_C ? 0 : (size_t)(it & 1) * MAXW * 256);
 #pragma unroll
@@ -893,7 +943,7 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
                         sacc += (ww < nw) ? val : T(0);
                     }
                     const T uv = slot_epilogue<T, MODE>(sacc, a, rb * 16 + d_row<T>(g, v), q, lab_pre[k], pin_pre[k],
-                                                        loss, hits);
+                                                        loss, lprod, hits);
                     if constexpr (HAS_C) zfull[v * 64 + lane] = uv;
                 }
             }
@@ -957,6 +1007,7 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     // four partials per workgroup: wave w < 4 owns the rows of accumulator element w
     if (w < 4) {
         if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_APPLY) {
+            if constexpr (MODE != ROW_APPLY) loss += log(lprod);
             for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off);
             if (lane == 0) a.loss_part[blockIdx.x * 4 + w] = loss;
             if (w == 0 && lane > 0 && lane < 4 && lane >= nw) a.loss_part[blockIdx.x * 4 + lane] = 0.0;
@@ -969,9 +1020,11 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
 #ifdef SSN_PROFILE_PHASES
     __builtin_amdgcn_s_waitcnt(0x0F70);
     const long long t_end = clock64();
+    const long long w_end = wall_clock64();
     if (blockIdx.x == 3 && lane == 0 && (w == 0 || w == 5)) {
         printf("[phases] mode %d wave %d blocks %d: wait %lld issue %lld A %lld bar1 %lld epi %lld bar2 %lld C %lld cycles\n", MODE,
                w, it, tph[0], tph[1], tph[2], tph[3], tph[4], tph[5], tph[6]);
+        printf("[clock] mode %d wave %d: %lld cycles in %lld ns\n", MODE, w, t_end - t_entry, (w_end - w_entry) * 10);
         printf("[timeline] mode %d wave %d: prologue %lld (to M loads %lld, issue M %lld, issue tile %lld, meta %lld, M to LDS %lld, sync %lld) loop %lld store %lld cycles\n",
                MODE, w, t_loop - t_entry, tp0 - t_entry, tp1 - tp0, tp2 - tp1, tp3 - tp2, tp4 - tp3, t_loop - tp4,
                t_loop_end - t_loop, t_end - t_loop_end);
