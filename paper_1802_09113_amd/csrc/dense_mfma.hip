@@ -958,20 +958,28 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
         ++it;
 
         if constexpr (HAS_C) {
-#pragma unroll
-            for (int h = 0; h < NSB; ++h) {
+            // sub-block h of the tile goes through the wave's scratch: rows in, columns out.  LDS serves a wave's
+            // requests in order, so sub-block h+1 is written as soon as the reads of h are issued and its trip
+            // overlaps the MFMAs of h.
+            auto scr_write = [&](int h) {
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj)
                     if (4 * h + jj < NLD) *(pack *)(scr + q * STR + LF * jj + VEC * g) = xc[4 * h + jj];
                     else *(pack *)(scr + q * STR + LF * jj + VEC * g) = pack{};
-                __builtin_amdgcn_wave_barrier();
+            };
+            scr_write(0);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const pack c = *(const pack *)(scr + d_row<T>(g, i) * STR + VEC * q);
-#pragma unroll
-                    for (int m = 0; m < VEC; ++m) G[h * VEC + m] = mfma16(c.v[m], u[i], G[h * VEC + m]);
-                }
+            for (int h = 0; h < NSB; ++h) {
                 __builtin_amdgcn_wave_barrier();
+                pack c[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) c[i] = *(const pack *)(scr + d_row<T>(g, i) * STR + VEC * q);
+                __builtin_amdgcn_wave_barrier();
+                if (h + 1 < NSB) scr_write(h + 1);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int m = 0; m < VEC; ++m) G[h * VEC + m] = mfma16(c[i].v[m], u[i], G[h * VEC + m]);
                 if constexpr (!ONE) {
 #pragma unroll
                     for (int l = 0; l < LOADS_C; ++l)
