@@ -299,7 +299,8 @@ int objective_impl(ssn_ctx *c, const void *W, double *f)
     return SSN_OK;
 }
 
-int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f)
+// defer_f: leave f(W) in scal_dev[0] without reading it back (the caller synchronises later)
+int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f, bool defer_f = false)
 {
     if (!c->fused) SSN_TRY(ensure_rows(c, &c->Ubuf, &c->U_rows, round_up(c->d.n, 16)));
     RowsArgs a = rows_base(c);
@@ -312,8 +313,8 @@ int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f)
     SSN_TRY(launch_rows(c, a, &nparts));
     if (c->fused) SSN_TRY(finalize_dense(c, nparts / 4, scale_full(c), W, G, false, nullptr, nullptr));
     else SSN_TRY(transposed_product(c, nullptr, c->d.n, scale_full(c), W, G, false, nullptr, nullptr));
-    if (f) {
-        SSN_TRY(enqueue_objective_value(c, W, nparts, 0));
+    if (f || defer_f) SSN_TRY(enqueue_objective_value(c, W, nparts, 0));
+    if (f && !defer_f) {
         SSN_TRY(read_scalar(c, c->scal_dev, f));
         if (!std::isfinite(*f)) return fail(c, SSN_E_NONFINITE, "objective is not finite");
     }
@@ -556,14 +557,16 @@ int ssn_gradient(ssn_ctx *c, const void *W, void *G, double *f)
     return gradient_impl(c, W, G, f);
 }
 
-int ssn_hess_prepare(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS)
+// validate: check the sample indices first (one pass and one synchronisation)
+static int hess_prepare_impl(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS, bool validate)
 {
-    if (!c || !W || !S || nS < 1) return fail(c, SSN_E_INVALID_ARG, "ssn_hess_prepare: null argument or nS < 1");
     c->prepared = false;
-    int32_t bad = 0;
-    SSN_HIP(c, launch_check_range(S, nS, 0, c->d.n, c->int_dev, c->st));
-    SSN_TRY(read_int(c, c->int_dev, &bad));
-    if (bad) return fail(c, SSN_E_BAD_INDEX, "ssn_hess_prepare: sample index outside [0,n)");
+    if (validate) {
+        int32_t bad = 0;
+        SSN_HIP(c, launch_check_range(S, nS, 0, c->d.n, c->int_dev, c->st));
+        SSN_TRY(read_int(c, c->int_dev, &bad));
+        if (bad) return fail(c, SSN_E_BAD_INDEX, "ssn_hess_prepare: sample index outside [0,n)");
+    }
     const int64_t rows = round_up(nS, 16);
     SSN_TRY(ensure_rows(c, &c->Pbuf, &c->P_rows, rows));
     SSN_TRY(ensure_rows(c, &c->Ubuf, &c->U_rows, rows));
@@ -582,6 +585,12 @@ int ssn_hess_prepare(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS)
     return SSN_OK;
 }
 
+int ssn_hess_prepare(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS)
+{
+    if (!c || !W || !S || nS < 1) return fail(c, SSN_E_INVALID_ARG, "ssn_hess_prepare: null argument or nS < 1");
+    return hess_prepare_impl(c, W, S, nS, true);
+}
+
 int ssn_hess_apply(ssn_ctx *c, const void *V, void *HV)
 {
     if (!c || !V || !HV || V == HV) return fail(c, SSN_E_INVALID_ARG, "ssn_hess_apply: null or aliased argument");
@@ -595,10 +604,9 @@ int ssn_hessvec(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS, const v
     return ssn_hess_apply(c, V, HV);
 }
 
-int ssn_cg(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out, ssn_cg_info *info, double *trace)
+// every launch of Alg. 2; the final state waits in slots[T]
+static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out)
 {
-    if (!c || !G || !P_out || T < 0 || G == P_out) return fail(c, SSN_E_INVALID_ARG, "ssn_cg: bad argument");
-    if (!c->prepared) return fail(c, SSN_E_NOT_PREPARED, "ssn_cg before ssn_hess_prepare");
     if (!c->cg_p) {
         SSN_TRY(vec_bytes_alloc(c, &c->cg_p));
         SSN_TRY(vec_bytes_alloc(c, &c->cg_r));
@@ -633,6 +641,22 @@ int ssn_cg(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out, ssn_
         SSN_HIP(c, launch_cg_step2(c->d.dtype, v, c->slots + k, c->slots + k + 1, c->red_a, n_rr, theta,
                                    c->trace_dev + 3 * k, c->red_c, p_pending, vb, c->st));
     }
+    return SSN_OK;
+}
+
+static void cg_fill_info(const CgSlot &fin, ssn_cg_info *info)
+{
+    info->iters = fin.iters;
+    info->flags = fin.flags;
+    info->gnorm = fin.gnorm;
+    info->rel_res = fin.gnorm > 0.0 ? fin.rbest / fin.gnorm : 0.0;
+}
+
+int ssn_cg(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out, ssn_cg_info *info, double *trace)
+{
+    if (!c || !G || !P_out || T < 0 || G == P_out) return fail(c, SSN_E_INVALID_ARG, "ssn_cg: bad argument");
+    if (!c->prepared) return fail(c, SSN_E_NOT_PREPARED, "ssn_cg before ssn_hess_prepare");
+    SSN_TRY(cg_enqueue(c, G, theta, T, P_out));
     CgSlot fin;
     std::vector<double> tr((size_t)3 * (T > 0 ? T : 1));
     SSN_HIP(c, hipMemcpyAsync(&fin, c->slots + T, sizeof(CgSlot), hipMemcpyDeviceToHost, c->st));
@@ -641,12 +665,7 @@ int ssn_cg(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out, ssn_
     SSN_HIP(c, hipStreamSynchronize(c->st));
     if (trace)
         for (int k = 0; k < 3 * fin.iters && k < 3 * T; ++k) trace[k] = tr[k];
-    if (info) {
-        info->iters = fin.iters;
-        info->flags = fin.flags;
-        info->gnorm = fin.gnorm;
-        info->rel_res = fin.gnorm > 0.0 ? fin.rbest / fin.gnorm : 0.0;
-    }
+    if (info) cg_fill_info(fin, info);
     return SSN_OK;
 }
 
@@ -657,16 +676,33 @@ int ssn_axpy(ssn_ctx *c, double alpha, const void *P, void *W)
     return SSN_OK;
 }
 
+// <P, G> into scal_dev[1]
+static int enqueue_slope(ssn_ctx *c, const void *P, const void *G)
+{
+    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+    SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, P, c->d.ldw, G, c->d.ldw, c->red_a, vb, nullptr, c->st));
+    SSN_HIP(c, launch_combine(c->red_a, vb, 1.0, nullptr, 0, 0.0, c->scal_dev + 1, c->st));
+    return SSN_OK;
+}
+
+int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
+                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok);
+
 int ssn_linesearch(ssn_ctx *c, const void *W, const void *P, const void *G, double fW, double beta, double rho,
                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok)
 {
     if (!c || !W || !P || !G || !alpha_out || !f_new) return fail(c, SSN_E_INVALID_ARG, "ssn_linesearch: null argument");
-    if (!c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
-    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
     double slope = 0.0;
-    SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, P, c->d.ldw, G, c->d.ldw, c->red_a, vb, nullptr, c->st));
-    SSN_HIP(c, launch_combine(c->red_a, vb, 1.0, nullptr, 0, 0.0, c->scal_dev + 1, c->st));
+    SSN_TRY(enqueue_slope(c, P, G));
     SSN_TRY(read_scalar(c, c->scal_dev + 1, &slope));
+    return linesearch_impl(c, W, P, fW, slope, beta, rho, imax, alpha_out, f_new, n_eval, ok);
+}
+
+// Alg. 3 with the slope <P, G> already on the host
+int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
+                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok)
+{
+    if (!c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
     double alpha = 1.0, ft = 0.0;
     int i = 0, evals = 0, good = 0;
     for (;;) {
@@ -711,52 +747,117 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         return fail(c, SSN_E_INVALID_ARG, "ssn_solve: bad argument");
     if (!c->grad) SSN_TRY(vec_bytes_alloc(c, &c->grad));
     if (!c->dir) SSN_TRY(vec_bytes_alloc(c, &c->dir));
+    // the whole sample schedule is checked once, not sample by sample
+    if (pr->iters > 0) {
+        int32_t bad = 0;
+        SSN_HIP(c, launch_check_range(pr->S_all, (int64_t)pr->iters * pr->nS, 0, c->d.n, c->int_dev, c->st));
+        SSN_TRY(read_int(c, c->int_dev, &bad));
+        if (bad) return fail(c, SSN_E_BAD_INDEX, "ssn_solve: sample index outside [0,n)");
+    }
+    // Phase times come from events on the stream; the host waits for the device once per iteration (f, |g|,
+    // the slope and the CG state come back together) plus once per line-search evaluation.  The last two
+    // phases of an iteration are read one synchronisation later.
+    constexpr int NE = 6;
+    hipEvent_t ev[2][NE];
+    for (auto &set : ev)
+        for (auto &e : set) SSN_HIP(c, hipEventCreate(&e));
+    auto ms_between = [&](hipEvent_t a, hipEvent_t b) {
+        float t = 0.f;
+        return hipEventElapsedTime(&t, a, b) == hipSuccess ? (double)t : std::nan("");
+    };
+    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+    int status = SSN_OK;
+    int pending = -1;                        // iteration whose line-search / update times are still to be read
+    ssn_iter_record pend_rec{};
+    auto flush_pending = [&]() {
+        if (pending < 0) return;
+        hipEvent_t *E = ev[pending & 1];
+        pend_rec.ms_linesearch = ms_between(E[3], E[4]);
+        pend_rec.ms_update = ms_between(E[4], E[5]);
+        if (log && pending < max_log) log[pending] = pend_rec;
+        pending = -1;
+    };
     int k = 0;
+#define SOLVE_TRY(expr)                     \
+    do {                                    \
+        status = (expr);                    \
+        if (status != SSN_OK) goto done;    \
+    } while (0)
+#define SOLVE_HIP(call)                                                                            \
+    do {                                                                                           \
+        hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess) {                                                                    \
+            c->err = std::string(#call) + ": " + hipGetErrorString(e_);                            \
+            status = SSN_E_HIP;                                                                    \
+            goto done;                                                                             \
+        }                                                                                          \
+    } while (0)
     for (; k < pr->iters; ++k) {
+        hipEvent_t *E = ev[k & 1];
         ssn_iter_record rec{};
         rec.test_acc = std::nan("");
-        double t0 = now_ms();
-        SSN_TRY(gradient_impl(c, W, c->grad, &rec.f));
-        const int vb = vec_blocks(c->d.p * (int64_t)c->K);
-        double gg = 0.0;
-        SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, c->grad, c->d.ldw, c->grad, c->d.ldw, c->red_a, vb, nullptr,
-                                   c->st));
-        SSN_HIP(c, launch_combine(c->red_a, vb, 1.0, nullptr, 0, 0.0, c->scal_dev + 2, c->st));
-        SSN_TRY(read_scalar(c, c->scal_dev + 2, &gg));
-        rec.gnorm = std::sqrt(gg);
-        double t1 = now_ms();
-        rec.ms_grad = t1 - t0;
-        if (rec.gnorm < pr->eps) {
-            if (log && k < max_log) log[k] = rec;
-            break;
+        SOLVE_HIP(hipEventRecord(E[0], c->st));
+        SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, true));
+        SOLVE_HIP(launch_dot_part(c->d.dtype, c->d.p, c->K, c->grad, c->d.ldw, c->grad, c->d.ldw, c->red_a, vb, nullptr,
+                                  c->st));
+        SOLVE_HIP(launch_combine(c->red_a, vb, 1.0, nullptr, 0, 0.0, c->scal_dev + 2, c->st));
+        SOLVE_HIP(hipEventRecord(E[1], c->st));
+        SOLVE_TRY(hess_prepare_impl(c, W, pr->S_all + (int64_t)k * pr->nS, pr->nS, false));
+        SOLVE_HIP(hipEventRecord(E[2], c->st));
+        SOLVE_TRY(cg_enqueue(c, c->grad, pr->theta, pr->T, c->dir));
+        SOLVE_TRY(enqueue_slope(c, c->dir, c->grad));
+        SOLVE_HIP(hipEventRecord(E[3], c->st));
+        // one round trip: f, <dir, g>, g.g and the final CG state
+        SOLVE_HIP(hipMemcpyAsync(c->host_pin, c->scal_dev, 3 * sizeof(double), hipMemcpyDeviceToHost, c->st));
+        SOLVE_HIP(hipMemcpyAsync(c->host_pin + 8, c->slots + pr->T, sizeof(CgSlot), hipMemcpyDeviceToHost, c->st));
+        SOLVE_HIP(hipStreamSynchronize(c->st));
+        flush_pending();
+        {
+            rec.f = c->host_pin[0];
+            const double slope = c->host_pin[1];
+            rec.gnorm = std::sqrt(c->host_pin[2]);
+            CgSlot fin;
+            memcpy(&fin, c->host_pin + 8, sizeof(CgSlot));
+            rec.ms_grad = ms_between(E[0], E[1]);
+            rec.ms_prepare = ms_between(E[1], E[2]);
+            rec.ms_cg = ms_between(E[2], E[3]);
+            if (!std::isfinite(rec.f)) {
+                status = fail(c, SSN_E_NONFINITE, "objective is not finite");
+                goto done;
+            }
+            if (rec.gnorm < pr->eps) {       // converged: the direction computed above is discarded
+                rec.ms_prepare = rec.ms_cg = 0.0;
+                if (log && k < max_log) log[k] = rec;
+                break;
+            }
+            ssn_cg_info info{};
+            cg_fill_info(fin, &info);
+            rec.cg_iters = info.iters;
+            rec.cg_rel_res = info.rel_res;
+            double fn = 0.0;
+            SOLVE_TRY(linesearch_impl(c, W, c->dir, rec.f, slope, pr->beta, pr->rho, pr->imax, &rec.alpha, &fn, &rec.ls_evals,
+                                      &rec.ls_ok));
         }
-        SSN_TRY(ssn_hess_prepare(c, W, pr->S_all + (int64_t)k * pr->nS, pr->nS));
-        SSN_HIP(c, hipStreamSynchronize(c->st));
-        double t2 = now_ms();
-        rec.ms_prepare = t2 - t1;
-        ssn_cg_info info{};
-        SSN_TRY(ssn_cg(c, c->grad, pr->theta, pr->T, c->dir, &info, nullptr));
-        double t3 = now_ms();
-        rec.ms_cg = t3 - t2;
-        rec.cg_iters = info.iters;
-        rec.cg_rel_res = info.rel_res;
-        double fn = 0.0;
-        SSN_TRY(ssn_linesearch(c, W, c->dir, c->grad, rec.f, pr->beta, pr->rho, pr->imax, &rec.alpha, &fn, &rec.ls_evals,
-                               &rec.ls_ok));
-        double t4 = now_ms();
-        rec.ms_linesearch = t4 - t3;
-        SSN_TRY(ssn_axpy(c, rec.alpha, c->dir, W));
+        SOLVE_HIP(hipEventRecord(E[4], c->st));
+        SOLVE_TRY(ssn_axpy(c, rec.alpha, c->dir, W));
         if (pr->test) {
             // the held-out context runs on its own stream: wait for the update first
-            SSN_HIP(c, hipStreamSynchronize(c->st));
-            SSN_TRY(ssn_predict(pr->test, W, nullptr, &rec.test_acc));
+            SOLVE_HIP(hipStreamSynchronize(c->st));
+            SOLVE_TRY(ssn_predict(pr->test, W, nullptr, &rec.test_acc));
         }
-        SSN_HIP(c, hipStreamSynchronize(c->st));
-        rec.ms_update = now_ms() - t4;
-        if (log && k < max_log) log[k] = rec;
+        SOLVE_HIP(hipEventRecord(E[5], c->st));
+        pending = k;
+        pend_rec = rec;
     }
+done:
+#undef SOLVE_TRY
+#undef SOLVE_HIP
+    (void)hipStreamSynchronize(c->st);
+    flush_pending();
+    for (auto &set : ev)
+        for (auto &e : set) (void)hipEventDestroy(e);
     if (iters_done) *iters_done = k;
-    return SSN_OK;
+    return status;
 }
 
 int ssn_time_kernel(ssn_ctx *c, int32_t which, const void *M, int32_t reps, double *ms)
