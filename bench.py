@@ -48,6 +48,19 @@ def parse():
     return ap.parse_args()
 
 
+def csr_kernel_bytes(n, p, K, nS, e, nnz, nnzS):
+    """CSR: stored entries cost value + column index in the rows kernels, value + row position in the
+    column-sorted gather; W / V is read once (gathers beyond that are cache traffic)."""
+    touched, touched_S = min(p, nnz), min(p, nnzS)          # rows of the p x K block a gather can reach
+    return {
+        0: nnz * (e + 4) + 4 * (n + 1) + 4 * n + p * K * e,
+        1: nnz * (e + 4) + 4 * (n + 1) + 4 * n + p * K * e + n * K * e,
+        2: nnz * (e + 4) + n * K * e + 2 * touched * K * e,         # gather by column, read-modify-write of the result
+        3: nnzS * (e + 4) + 8 * nS + 2 * nS * K * e + touched_S * K * e,
+        4: nnzS * (e + 4) + nS * K * e + 2 * touched_S * K * e,
+    }
+
+
 def kernel_bytes(n, p, K, nS, e, path):
     """Algorithmic bytes one launch of each timed kernel has to move (X counted once per kernel).
     path 1: margins kernel then X^T U kernel; path 2: one sweep does both, kernel 2 / 4 only add up the
@@ -69,8 +82,14 @@ def kernel_bytes(n, p, K, nS, e, path):
     }
 
 
-def call_bytes(n, p, K, nS, e):
+def call_bytes(n, p, K, nS, e, nnz=None, nnzS=None):
     """Algorithmic bytes per call: X is counted ONCE per call whatever the kernel count."""
+    if nnz is not None:
+        return {
+            "objective": nnz * (e + 4) + 4 * (n + 1) + 4 * n + p * K * e,
+            "gradient": nnz * (e + 4) + 4 * (n + 1) + 4 * n + 2 * p * K * e,
+            "hess_apply": nnzS * (e + 4) + 8 * nS + nS * K * e + 2 * p * K * e,
+        }
     return {
         "objective": n * p * e + 4 * n + p * K * e,
         "gradient": n * p * e + 4 * n + 2 * p * K * e,
@@ -79,6 +98,8 @@ def call_bytes(n, p, K, nS, e):
 
 
 KERNEL_NAMES = {
+    0: {0: "csr_rows_kernel<OBJ>", 1: "csr_rows_kernel<GRAD>", 2: "csc_piece_kernel + csc_combine_kernel (n rows)",
+        3: "csr_rows_kernel<APPLY>", 4: "csc_piece_kernel + csc_combine_kernel (|S| rows)"},
     1: {0: "dense_rows_kernel<OBJ>", 1: "dense_rows_kernel<GRAD>", 2: "dense_xtu_kernel (n rows)",
         3: "dense_rows_kernel<APPLY>", 4: "dense_xtu_kernel (|S| rows)"},
     2: {0: "dense_fused_kernel<OBJ>", 1: "dense_fused_kernel<GRAD>", 2: "finalize_kernel (gradient partials)",
@@ -96,9 +117,17 @@ def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
     e = 8 if dtype_name == "f64" else 4
     n, p, C, K, nS = data["n"], data["p"], data["C"], data["K"], data["nS"]
     dev = "cuda:0"
-    X = torch.from_numpy(data["X"]).to(dev).to(tdt)
     labels = torch.from_numpy(data["labels"]).to(dev)
-    ctx = Context(labels, C, data["lam"], X=X)
+    sparse = data["layout"] == "csr"
+    if sparse:
+        csr = (torch.from_numpy(data["rowptr"].astype(np.int32)).to(dev), torch.from_numpy(data["colidx"]).to(dev),
+               torch.from_numpy(data["vals"]).to(dev).to(tdt))
+        ctx = Context(labels, C, data["lam"], csr=csr, p=p)
+        nnz = int(data["nnz"])
+    else:
+        X = torch.from_numpy(data["X"]).to(dev).to(tdt)
+        ctx = Context(labels, C, data["lam"], X=X)
+        nnz = None
     W = torch.zeros((p, K), dtype=tdt, device=dev)
     out = {}
     S_all = torch.from_numpy(synth.sample_schedule(n, nS, warmup + steps)).to(dev)
@@ -158,7 +187,11 @@ def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
     for _ in range(20):
         ctx.ssn_objective(W)
     ms_obj = (time.perf_counter() - t0) * 1e3 / 20
-    cb = call_bytes(n, p, K, nS, e)
+    nnzS = None
+    if sparse:
+        rl = data["rowptr"][1:] - data["rowptr"][:-1]
+        nnzS = int(rl[S.cpu().numpy()].sum())
+    cb = call_bytes(n, p, K, nS, e, nnz, nnzS)
     ms_call = {"objective": ms_obj, "gradient": ms_grad, "hess_apply": 1e3 / out["hv_per_s"]}
     out["calls"] = {k: {"ms": ms_call[k], "algorithmic_GB": cb[k] / 1e9,
                         "GBps": cb[k] / ms_call[k] / 1e6, "frac_of_hbm_peak": cb[k] / ms_call[k] / 1e6 / HBM_PEAK_GBS}
@@ -167,7 +200,7 @@ def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
     # per-kernel durations from HIP events recorded by the library on its own stream
     path = ctx.ssn_dense_path()
     out["dense_path"] = path
-    kb = kernel_bytes(n, p, K, nS, e, path)
+    kb = csr_kernel_bytes(n, p, K, nS, e, nnz, nnzS) if sparse else kernel_bytes(n, p, K, nS, e, path)
     kern = {}
     for which in (0, 1, 2, 3, 4):
         reps = 20 if which < 3 else 200
@@ -182,7 +215,24 @@ def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
     # plain streaming read of X (no arithmetic): what this chip delivers to a trivial kernel
     ctx.ssn_time_kernel(5, W, 3)
     ms = ctx.ssn_time_kernel(5, W, 20)
-    out["stream_read"] = {"ms": ms, "GBps": n * p * e / ms / 1e6, "frac": n * p * e / ms / 1e6 / HBM_PEAK_GBS}
+    sbytes = (nnz if sparse else n * p) * e
+    out["stream_read"] = {"ms": ms, "GBps": sbytes / ms / 1e6, "frac": sbytes / ms / 1e6 / HBM_PEAK_GBS}
+    # the product kernels on ALL rows (the FullNewton shape, |S| = n): the streaming data point of H_S v
+    S_full = torch.arange(n, dtype=torch.int32, device=dev)
+    ctx.ssn_hess_prepare(W, S_full)
+    for _ in range(3):
+        ctx.ssn_hess_apply(V[0], HV[0])
+    torch.cuda.synchronize()
+    a, z = ev(), ev()
+    a.record()
+    for _ in range(10):
+        ctx.ssn_hess_apply(V[0], HV[0])
+    z.record()
+    torch.cuda.synchronize()
+    ms_full = a.elapsed_time(z) / 10
+    cbf = call_bytes(n, p, K, n, e, nnz, nnz)["hess_apply"]
+    out["hess_apply_all_rows"] = {"ms": ms_full, "algorithmic_GB": cbf / 1e9, "GBps": cbf / ms_full / 1e6,
+                                  "frac_of_hbm_peak": cbf / ms_full / 1e6 / HBM_PEAK_GBS}
     ctx.close()
     return out
 
@@ -195,6 +245,7 @@ def pmc_sequence(data, dtype_name):
     from paper_1802_09113_amd.binding import Context
     tdt = torch.float64 if dtype_name == "f64" else torch.float32
     n, p, C, K, nS = data["n"], data["p"], data["C"], data["K"], data["nS"]
+    assert data["layout"] == "dense", "the counter sequence covers the dense workloads"
     X = torch.from_numpy(data["X"]).to("cuda:0").to(tdt)
     labels = torch.from_numpy(data["labels"]).to("cuda:0")
     ctx = Context(labels, C, data["lam"], X=X)
@@ -215,7 +266,10 @@ def cpu_baseline(data, budget_s=12.0):
     import numpy as np
     from oracle.oracle import Problem
     from paper_1802_09113_amd import synth
-    pr = Problem(data["labels"], data["C"], data["lam"], X=data["X"])
+    if data["layout"] == "csr":
+        pr = Problem(data["labels"], data["C"], data["lam"], csr=(data["rowptr"], data["colidx"], data["vals"]), p=data["p"])
+    else:
+        pr = Problem(data["labels"], data["C"], data["lam"], X=data["X"])
     W = np.zeros((pr.p, pr.K))
     S = synth.sample_rows(pr.n, data["nS"])
     V = synth.probe(pr.p, pr.K, sub=10)
@@ -246,7 +300,6 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     t_gen = time.perf_counter()
     data = synth.make(args.config, n=args.n)
-    assert data["layout"] == "dense", "bench.py times the dense workloads"
     sys.stderr.write(f"[bench] generated {data['name']} {data['n']}x{data['p']} C={data['C']} in "
                      f"{time.perf_counter() - t_gen:.1f}s\n")
     if args.pmc:
@@ -277,7 +330,9 @@ def main():
         "metric": "sub-sampled Hess-vec products/s", "value": main_res["hv_per_s"], "unit": "products/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": f"{data['name']}: dense {data['n']}x{data['p']}, C={data['C']}, lambda={data['lam']}, "
+        "config": {"workload": f"{data['name']}: {data['layout']} {data['n']}x{data['p']}"
+                               + (f" nnz={data['nnz']}" if data["layout"] == "csr" else "")
+                               + f", C={data['C']}, lambda={data['lam']}, "
                                f"|S|={data['nS']} (5%), CG T={data['T']}, theta=1e-4, Armijo beta=1e-4 rho=0.5; "
                                f"step = one SSN iteration", "config_index": args.config},
         "roofline": roof,
@@ -288,6 +343,7 @@ def main():
         "calls": main_res["calls"],
         "dense_path": main_res["dense_path"],
         "stream_read": main_res["stream_read"],
+        "hess_apply_all_rows": main_res["hess_apply_all_rows"],
         "kernels": {v["kernel"]: {kk: vv for kk, vv in v.items() if kk != "kernel"} for v in k.values()},
         "final_f": main_res["final_f"],
     }
@@ -296,6 +352,8 @@ def main():
         line["other_dtype"] = {"dtype": od, "hv_per_s": other["hv_per_s"], "ms_per_step": other["ms_per_step"],
                                "calls": other["calls"],
                                "stream_read": other["stream_read"],
+                               "hess_apply_all_rows": other["hess_apply_all_rows"],
+                               "phase_ms": other["phase_ms"],
                                "kernels": {v["kernel"]: {kk: vv for kk, vv in v.items() if kk != "kernel"}
                                            for v in other["kernels"].values()}}
     print(json.dumps(line))
