@@ -54,6 +54,7 @@ def _load():
         lib.orc_cg.restype = ctypes.c_int
         lib.orc_linesearch.restype = ctypes.c_int
         lib.orc_ssn.restype = ctypes.c_int
+        lib.orc_ssn_sg.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -125,6 +126,17 @@ class Problem:
         _load().orc_gradient(self._ref(), _ptr(W), _ptr(G), ctypes.byref(f))
         return G, f.value
 
+    # ---- eq. (2a): sub-sampled gradient ----------------------------------
+    def gradient_sampled(self, W, S):
+        """Returns (G, f_S): gradient and objective of the sample S (a multiset of rows)."""
+        W = self._w(W)
+        S = np.ascontiguousarray(S, dtype=np.int32)
+        assert S.size > 0 and S.min() >= 0 and S.max() < self.n
+        G = np.empty_like(W)
+        f = ctypes.c_double()
+        _load().orc_gradient_sampled(self._ref(), _ptr(W), _ptr(S), ctypes.c_int64(S.shape[0]), _ptr(G), ctypes.byref(f))
+        return G, f.value
+
     # ---- eqs. (10)-(13), Alg. 7/8 ---------------------------------------
     def sample_probs(self, W, S):
         W = self._w(W)
@@ -187,4 +199,18 @@ class Problem:
         done = _load().orc_ssn(self._ref(), _ptr(W), ctypes.c_int(iters), _ptr(S_all), ctypes.c_int64(nS),
                                ctypes.c_double(eps), ctypes.c_double(theta), ctypes.c_int(T),
                                ctypes.c_double(beta), ctypes.c_double(rho), ctypes.c_int(imax), _ptr(log))
+        return W, log, int(done)
+
+    def ssn_sg(self, W0, Sg_all, S_all, eps=0.0, theta=1e-4, T=10, beta=1e-4, rho=0.5, imax=10):
+        """Alg. 1 with sub-sampled gradient (Sg_all: (iters, nSg)) and Hessian (S_all: (iters, nS))."""
+        W = self._w(W0).copy()
+        Sg_all = np.ascontiguousarray(Sg_all, dtype=np.int32)
+        S_all = np.ascontiguousarray(S_all, dtype=np.int32)
+        iters, nS = S_all.shape
+        assert Sg_all.shape[0] == iters
+        log = np.zeros((iters, 6))
+        done = _load().orc_ssn_sg(self._ref(), _ptr(W), ctypes.c_int(iters), _ptr(Sg_all), ctypes.c_int64(Sg_all.shape[1]),
+                                  _ptr(S_all), ctypes.c_int64(nS), ctypes.c_double(eps), ctypes.c_double(theta),
+                                  ctypes.c_int(T), ctypes.c_double(beta), ctypes.c_double(rho), ctypes.c_int(imax),
+                                  _ptr(log))
         return W, log, int(done)

@@ -14,6 +14,7 @@
  *   gradient ............................. eq. (6); Alg. 6
  *   Hessian-vector product ............... eqs. (10)-(13); Alg. 7, Alg. 8
  *   sub-sampled Hessian .................. eq. (2b)
+ *   sub-sampled gradient ................. eq. (2a)
  *   conjugate gradient ................... Alg. 2
  *   back-tracking line search ............ Alg. 3, eq. (3c)
  *   sub-sampled Newton iteration ......... Alg. 1, eq. (3a)
@@ -193,6 +194,37 @@ void orc_gradient(const orc_problem *pr, const double *W, double *G, double *f_o
         G[t] = (double)(s * acc[t] + (long double)pr->lambda * (long double)W[t]);
     if (f_out)
         *f_out = (double)(s * total + half_lambda_sqnorm(pr, W));
+    free(acc); free(prob); free(z);
+}
+
+/* Sub-sampled gradient, eq. (2a): G = scale_S * sum_{i in S} a_i (p_i - y_i)^T + lambda W with the
+ * sample scaling of the Hessian (n/|S| in the paper's sum form, 1/|S| in the mean form).  S is a
+ * multiset.  f_out (optional) receives the objective of the same sample,
+ * scale_S * sum_{i in S} f_i(W) + (lambda/2)||W||^2, whose gradient G is. */
+void orc_gradient_sampled(const orc_problem *pr, const double *W, const int32_t *S, int64_t nS,
+                          double *G, double *f_out)
+{
+    const int K = pr->C - 1;
+    const int64_t d = pr->p * (int64_t)K;
+    double *z = (double *)malloc(sizeof(double) * (size_t)K);
+    double *prob = (double *)malloc(sizeof(double) * (size_t)K);
+    long double *acc = (long double *)calloc((size_t)d, sizeof(long double));
+    long double total = 0.0L;
+    for (int64_t s = 0; s < nS; ++s) {
+        const int64_t i = S[s];
+        row_margins(pr, i, W, z);
+        double alpha;
+        const double M = stable_softmax(K, z, &alpha, prob);
+        const int b = pr->labels[i];
+        total += (long double)M + (long double)log(alpha) - (long double)((b < K) ? z[b] : 0.0);
+        if (b < K) prob[b] -= 1.0;
+        row_outer_add(pr, i, prob, acc);
+    }
+    const long double sc = (long double)data_scale_sample(pr, nS);
+    for (int64_t t = 0; t < d; ++t)
+        G[t] = (double)(sc * acc[t] + (long double)pr->lambda * (long double)W[t]);
+    if (f_out)
+        *f_out = (double)(sc * total + half_lambda_sqnorm(pr, W));
     free(acc); free(prob); free(z);
 }
 
@@ -391,6 +423,42 @@ int orc_ssn(const orc_problem *pr, double *W, int iters, const int32_t *S_all, i
         double alpha, fn; int32_t ok;
         const int ev = orc_linesearch(pr, W, dir, g, f, beta, rho, imax, &alpha, &fn, &ok);
         for (int64_t t = 0; t < d; ++t) W[t] += alpha * dir[t];
+        if (log) { log[6*k+2] = np; log[6*k+3] = rel; log[6*k+4] = alpha; log[6*k+5] = ok ? ev : -ev; }
+    }
+    free(dir); free(g);
+    return k;
+}
+
+/*
+ * Alg. 1 with BOTH the gradient and the Hessian sub-sampled (eqs. (2a), (2b); the paper's
+ * "SubsampledNewton-20" uses 20 % of the rows for g and 5 % for H).  Iteration k uses the gradient
+ * sample Sg_all[k*nSg ..) and the Hessian sample S_all[k*nS ..).  The Armijo test of Alg. 3 compares
+ * the FULL objective F; the paper does not say where F(x_k) comes from when no full gradient pass
+ * produces it: here it is evaluated once at the start and afterwards carried over from the accepted
+ * line-search trial of the previous iteration (the same number).  log as in orc_ssn, with ||g_k|| the
+ * norm of the sub-sampled gradient.
+ */
+int orc_ssn_sg(const orc_problem *pr, double *W, int iters, const int32_t *Sg_all, int64_t nSg,
+               const int32_t *S_all, int64_t nS, double eps, double theta, int T, double beta, double rho,
+               int imax, double *log)
+{
+    const int64_t d = pr->p * (int64_t)(pr->C - 1);
+    double *g = (double *)malloc(sizeof(double) * (size_t)d);
+    double *dir = (double *)malloc(sizeof(double) * (size_t)d);
+    double f = orc_objective(pr, W);
+    int k = 0;
+    for (; k < iters; ++k) {
+        orc_gradient_sampled(pr, W, Sg_all + (int64_t)k * nSg, nSg, g, NULL);
+        const double gn = sqrt((double)ldot(d, g, g));
+        if (log) { log[6*k] = f; log[6*k+1] = gn; log[6*k+2] = log[6*k+3] = log[6*k+4] = log[6*k+5] = 0.0; }
+        if (gn < eps) break;
+        const int32_t *S = S_all + (int64_t)k * nS;
+        double rel; int32_t fl;
+        const int np = orc_cg(pr, W, S, nS, g, theta, T, dir, &rel, &fl, NULL);
+        double alpha, fn; int32_t ok;
+        const int ev = orc_linesearch(pr, W, dir, g, f, beta, rho, imax, &alpha, &fn, &ok);
+        for (int64_t t = 0; t < d; ++t) W[t] += alpha * dir[t];
+        f = fn;
         if (log) { log[6*k+2] = np; log[6*k+3] = rel; log[6*k+4] = alpha; log[6*k+5] = ok ? ev : -ev; }
     }
     free(dir); free(g);
