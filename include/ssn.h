@@ -100,6 +100,9 @@ typedef struct {
     double rho;               /* back-tracking factor                                            */
     const int32_t *S_all;     /* [dev] iters*nS sample indices, iteration k uses [k*nS,(k+1)*nS) */
     ssn_ctx *test;            /* optional context holding held-out rows: accuracy per iteration  */
+    const int32_t *Sg_all;    /* [dev, nullable] iters*nSg gradient sample indices (eq. (2a)): iteration
+                                 k forms g on [k*nSg,(k+1)*nSg); NULL = full gradient of eq. (6)     */
+    int64_t nSg;              /* gradient sample size (ignored when Sg_all is NULL)                */
 } ssn_params;
 
 /* One record per SSN iteration, written by ssn_solve to a [host] array. */
@@ -138,6 +141,12 @@ int ssn_objective(ssn_ctx *ctx, const void *W, double *f);
  * same pass and the call synchronises. */
 int ssn_gradient(ssn_ctx *ctx, const void *W, void *G, double *f);
 
+/* Sub-sampled gradient, eq. (2a), on the index multiset S [dev] (nS entries in [0,n), repeats allowed):
+ *   G = s_S * X_S^T (P_S - Y_S) + lambda W,  s_S = 1/nS (mean scaling) or n/nS (sum scaling).
+ * Same kernels as ssn_gradient on the sampled rows.  f_S [host, nullable] receives the objective of the
+ * same sample, s_S * sum_{i in S} f_i(W) + (lambda/2)||W||^2 (then the call synchronises).  Validates S. */
+int ssn_gradient_sampled(ssn_ctx *ctx, const void *W, const int32_t *S, int64_t nS, void *G, double *f_S);
+
 /* Sub-sampled Hessian (eq. (2b)) at W on the index multiset S [dev] (nS entries in [0,n),
  * repeats allowed, any order): computes and caches the probabilities of the sampled rows (the
  * matrix W of eq. (11); it depends on the weights only, so all CG products of one SSN
@@ -173,6 +182,8 @@ int ssn_predict(ssn_ctx *ctx, const void *W, int32_t *pred, double *acc);
 
 /* Sub-sampled Newton, Alg. 1 with the full gradient and a sampled Hessian:
  * per iteration f,g at W; stop if ||g|| < eps; prepare H_S; CG; line search; W += alpha P.
+ * With params.Sg_all the gradient is the sub-sampled one of eq. (2a); the Armijo test still compares the
+ * full objective, evaluated once at the start and then carried over from the accepted trial.
  * W_inout [dev]; log [host, nullable] receives min(iterations, max_log) records;
  * iters_done [host, nullable]. */
 int ssn_solve(ssn_ctx *ctx, void *W_inout, const ssn_params *params,

@@ -21,7 +21,7 @@ SSN_E_ALLOC, SSN_E_HIP, SSN_E_NONFINITE, SSN_E_UNSUPPORTED = -5, -6, -7, -8
 
 EXPORTS = [
     "ssn_strerror", "ssn_last_error", "ssn_create", "ssn_destroy", "ssn_set_stream", "ssn_objective",
-    "ssn_gradient", "ssn_hess_prepare", "ssn_hess_apply", "ssn_hessvec", "ssn_cg", "ssn_linesearch",
+    "ssn_gradient", "ssn_gradient_sampled", "ssn_hess_prepare", "ssn_hess_apply", "ssn_hessvec", "ssn_cg", "ssn_linesearch",
     "ssn_predict", "ssn_solve", "ssn_axpy", "ssn_time_kernel", "ssn_dense_path",
 ]
 
@@ -50,6 +50,7 @@ class ssn_params(ctypes.Structure):
         ("nS", ctypes.c_int64),
         ("eps", ctypes.c_double), ("theta", ctypes.c_double), ("beta", ctypes.c_double), ("rho", ctypes.c_double),
         ("S_all", ctypes.c_void_p), ("test", ctypes.c_void_p),
+        ("Sg_all", ctypes.c_void_p), ("nSg", ctypes.c_int64),
     ]
 
 
@@ -83,6 +84,7 @@ def lib():
         L.ssn_set_stream.argtypes = [vp, vp]
         L.ssn_objective.argtypes = [vp, vp, dp]
         L.ssn_gradient.argtypes = [vp, vp, vp, dp]
+        L.ssn_gradient_sampled.argtypes = [vp, vp, vp, ctypes.c_int64, vp, dp]
         L.ssn_hess_prepare.argtypes = [vp, vp, vp, ctypes.c_int64]
         L.ssn_hess_apply.argtypes = [vp, vp, vp]
         L.ssn_hessvec.argtypes = [vp, vp, vp, ctypes.c_int64, vp, vp]
@@ -183,6 +185,14 @@ class Context:
         self._check(lib().ssn_gradient(self._h, self._blk(W), self._blk(G), ctypes.byref(f) if want_f else None))
         return G, (f.value if want_f else None)
 
+    def ssn_gradient_sampled(self, W, S, G=None, want_f=True):
+        assert S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()
+        G = self.new_block() if G is None else G
+        f = ctypes.c_double()
+        self._check(lib().ssn_gradient_sampled(self._h, self._blk(W), _ptr(S), S.shape[0], self._blk(G),
+                                               ctypes.byref(f) if want_f else None))
+        return G, (f.value if want_f else None)
+
     def ssn_hess_prepare(self, W, S):
         assert S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()
         self._S = S
@@ -237,10 +247,15 @@ class Context:
         self._check(lib().ssn_time_kernel(self._h, which, self._blk(M), reps, ctypes.byref(ms)))
         return ms.value
 
-    def ssn_solve(self, W, S_all, eps=0.0, theta=1e-4, T=10, beta=1e-4, rho=0.5, imax=10, test=None):
-        """S_all: (iters, nS) int32 device tensor.  W is updated in place; returns (records, iterations done)."""
+    def ssn_solve(self, W, S_all, eps=0.0, theta=1e-4, T=10, beta=1e-4, rho=0.5, imax=10, test=None, Sg_all=None):
+        """S_all: (iters, nS) int32 device tensor; Sg_all (optional): (iters, nSg) gradient samples.  W is updated
+        in place; returns (records, iterations done)."""
         assert S_all.is_cuda and S_all.dtype == torch.int32 and S_all.is_contiguous() and S_all.dim() == 2
         pr = ssn_params()
+        if Sg_all is not None:
+            assert Sg_all.is_cuda and Sg_all.dtype == torch.int32 and Sg_all.is_contiguous() and Sg_all.dim() == 2
+            assert Sg_all.shape[0] == S_all.shape[0]
+            pr.Sg_all, pr.nSg = Sg_all.data_ptr(), Sg_all.shape[1]
         pr.iters, pr.nS = S_all.shape
         pr.T, pr.imax, pr.eps, pr.theta, pr.beta, pr.rho = T, imax, eps, theta, beta, rho
         pr.S_all = S_all.data_ptr()

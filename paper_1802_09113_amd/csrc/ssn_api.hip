@@ -34,7 +34,7 @@ struct ssn_ctx {
     bool fused = false;           // dense: the one-pass kernel serves this shape
     // CSR: column-sorted views for the transposed products (whole matrix: built at the first gradient;
     // sample: rebuilt by every ssn_hess_prepare)
-    CscView csc_full, csc_samp;
+    CscView csc_full, csc_samp, csc_grad;      // csc_grad: the sample of the last sub-sampled gradient
     bool csc_full_built = false;
     // reduction scratch
     double *loss_part = nullptr;
@@ -84,6 +84,11 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 inline bool is_dense(const ssn_ctx *c) { return c->d.layout == SSN_DENSE_ROWMAJOR; }
 
 double scale_full(const ssn_ctx *c) { return c->d.scale == SSN_SCALE_SUM ? 1.0 : 1.0 / (double)c->d.n; }
+// data-term factor of a sum over nrows sampled rows (eqs. (2a), (2b))
+double scale_rows(const ssn_ctx *c, int64_t nrows)
+{
+    return c->d.scale == SSN_SCALE_SUM ? (double)c->d.n / (double)nrows : 1.0 / (double)nrows;
+}
 double scale_sample(const ssn_ctx *c)
 {
     return c->d.scale == SSN_SCALE_SUM ? (double)c->d.n / (double)c->nS : 1.0 / (double)c->nS;
@@ -234,7 +239,7 @@ int csc_view_for(ssn_ctx *c, const int32_t *S, const CscView **view)
 
 // out = scale * X_rows^T U + lambda * M ; optionally partials of <out, M> into red_b (count in *ndot)
 int transposed_product(ssn_ctx *c, const int32_t *S, int64_t nrows, double scale, const void *M, void *out,
-                       bool want_dot, int *ndot, const int32_t *skip)
+                       bool want_dot, int *ndot, const int32_t *skip, const CscView *view_in = nullptr)
 {
     XtuArgs x = xtu_base(c);
     x.S = S;
@@ -246,8 +251,8 @@ int transposed_product(ssn_ctx *c, const int32_t *S, int64_t nrows, double scale
         SSN_HIP(c, launch_dense_xtu(c->d.dtype, x, c->st));
         SSN_TRY(finalize_dense(c, x.nchunks, scale, M, out, want_dot, ndot, skip));
     } else {
-        const CscView *view = nullptr;
-        SSN_TRY(csc_view_for(c, S, &view));
+        const CscView *view = view_in;
+        if (!view) SSN_TRY(csc_view_for(c, S, &view));
         SSN_HIP(c, launch_scale_copy(c->d.dtype, c->d.p, c->K, c->d.lambda, M, c->d.ldw, out, c->d.ldw, skip, c->st));
         SSN_HIP(c, launch_csc_apply(c->d.dtype, *view, c->K, c->KP, c->Ubuf, scale, out, c->d.ldw, nullptr, skip, c->st));
         if (want_dot) {
@@ -276,11 +281,12 @@ int read_int(ssn_ctx *c, const int32_t *dev, int32_t *host_out)
 }
 
 // enqueue f(W) into scal_dev[slot]; loss partials must already be in loss_part[0..nparts)
-int enqueue_objective_value(ssn_ctx *c, const void *W, int nparts, int slot)
+int enqueue_objective_value(ssn_ctx *c, const void *W, int nparts, int slot, double scale = -1.0)
 {
     const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+    if (scale < 0.0) scale = scale_full(c);
     SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, W, c->d.ldw, W, c->d.ldw, c->red_a, vb, nullptr, c->st));
-    SSN_HIP(c, launch_combine(c->loss_part, nparts, scale_full(c), c->red_a, vb, 0.5 * c->d.lambda, c->scal_dev + slot,
+    SSN_HIP(c, launch_combine(c->loss_part, nparts, scale, c->red_a, vb, 0.5 * c->d.lambda, c->scal_dev + slot,
                               c->st));
     return SSN_OK;
 }
@@ -299,21 +305,34 @@ int objective_impl(ssn_ctx *c, const void *W, double *f)
     return SSN_OK;
 }
 
-// defer_f: leave f(W) in scal_dev[0] without reading it back (the caller synchronises later)
-int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f, bool defer_f = false)
+// defer_f: leave f(W) in scal_dev[0] without reading it back (the caller synchronises later).
+// S (nullable): the sub-sampled gradient of eq. (2a) on the nS rows S, with its sample scaling.
+int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f, bool defer_f = false, const int32_t *S = nullptr,
+                  int64_t nS = 0)
 {
-    if (!c->fused) SSN_TRY(ensure_rows(c, &c->Ubuf, &c->U_rows, round_up(c->d.n, 16)));
+    const int64_t nrows = S ? nS : c->d.n;
+    const double scale = S ? scale_rows(c, nS) : scale_full(c);
+    if (!c->fused) SSN_TRY(ensure_rows(c, &c->Ubuf, &c->U_rows, round_up(nrows, 16)));
     RowsArgs a = rows_base(c);
-    a.nrows = c->d.n;
+    a.S = S;
+    a.nrows = nrows;
     a.M = W;
     a.mode = ROW_GRAD;
     a.UP = c->Ubuf;
     int nparts = 0;
     a.part = c->part;
     SSN_TRY(launch_rows(c, a, &nparts));
-    if (c->fused) SSN_TRY(finalize_dense(c, nparts / 4, scale_full(c), W, G, false, nullptr, nullptr));
-    else SSN_TRY(transposed_product(c, nullptr, c->d.n, scale_full(c), W, G, false, nullptr, nullptr));
-    if (f || defer_f) SSN_TRY(enqueue_objective_value(c, W, nparts, 0));
+    if (c->fused) {
+        SSN_TRY(finalize_dense(c, nparts / 4, scale, W, G, false, nullptr, nullptr));
+    } else {
+        const CscView *view = nullptr;
+        if (!is_dense(c) && S) {             // a view of its own: the prepared Hessian sample keeps csc_samp
+            SSN_HIP(c, csc_build(&c->csc_grad, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.p, c->K, c->st));
+            view = &c->csc_grad;
+        }
+        SSN_TRY(transposed_product(c, S, nrows, scale, W, G, false, nullptr, nullptr, view));
+    }
+    if (f || defer_f) SSN_TRY(enqueue_objective_value(c, W, nparts, 0, scale));
     if (f && !defer_f) {
         SSN_TRY(read_scalar(c, c->scal_dev, f));
         if (!std::isfinite(*f)) return fail(c, SSN_E_NONFINITE, "objective is not finite");
@@ -445,6 +464,7 @@ int ssn_destroy(ssn_ctx *c)
     if (c->host_pin) (void)hipHostFree(c->host_pin);
     csc_free(&c->csc_full);
     csc_free(&c->csc_samp);
+    csc_free(&c->csc_grad);
     delete c;
     return SSN_OK;
 }
@@ -583,6 +603,17 @@ static int hess_prepare_impl(ssn_ctx *c, const void *W, const int32_t *S, int64_
     c->nS = nS;
     c->prepared = true;
     return SSN_OK;
+}
+
+int ssn_gradient_sampled(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS, void *G, double *f_S)
+{
+    if (!c || !W || !G || !S || nS < 1 || W == G)
+        return fail(c, SSN_E_INVALID_ARG, "ssn_gradient_sampled: null or aliased argument, or nS < 1");
+    int32_t bad = 0;
+    SSN_HIP(c, launch_check_range(S, nS, 0, c->d.n, c->int_dev, c->st));
+    SSN_TRY(read_int(c, c->int_dev, &bad));
+    if (bad) return fail(c, SSN_E_BAD_INDEX, "ssn_gradient_sampled: sample index outside [0,n)");
+    return gradient_impl(c, W, G, f_S, false, S, nS);
 }
 
 int ssn_hess_prepare(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS)
@@ -747,13 +778,23 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         return fail(c, SSN_E_INVALID_ARG, "ssn_solve: bad argument");
     if (!c->grad) SSN_TRY(vec_bytes_alloc(c, &c->grad));
     if (!c->dir) SSN_TRY(vec_bytes_alloc(c, &c->dir));
+    if (pr->Sg_all && pr->nSg < 1) return fail(c, SSN_E_INVALID_ARG, "ssn_solve: gradient sample size < 1");
     // the whole sample schedule is checked once, not sample by sample
     if (pr->iters > 0) {
         int32_t bad = 0;
         SSN_HIP(c, launch_check_range(pr->S_all, (int64_t)pr->iters * pr->nS, 0, c->d.n, c->int_dev, c->st));
         SSN_TRY(read_int(c, c->int_dev, &bad));
         if (bad) return fail(c, SSN_E_BAD_INDEX, "ssn_solve: sample index outside [0,n)");
+        if (pr->Sg_all) {
+            SSN_HIP(c, launch_check_range(pr->Sg_all, (int64_t)pr->iters * pr->nSg, 0, c->d.n, c->int_dev, c->st));
+            SSN_TRY(read_int(c, c->int_dev, &bad));
+            if (bad) return fail(c, SSN_E_BAD_INDEX, "ssn_solve: gradient sample index outside [0,n)");
+        }
     }
+    // sub-sampled gradient: no pass over all rows produces F(x_k); it is evaluated once here and then
+    // carried over from the accepted line-search trial
+    double f_carry = 0.0;
+    if (pr->Sg_all && pr->iters > 0) SSN_TRY(objective_impl(c, W, &f_carry));
     // Phase times come from events on the stream; the host waits for the device once per iteration (f, |g|,
     // the slope and the CG state come back together) plus once per line-search evaluation.  The last two
     // phases of an iteration are read one synchronisation later.
@@ -797,7 +838,8 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         ssn_iter_record rec{};
         rec.test_acc = std::nan("");
         SOLVE_HIP(hipEventRecord(E[0], c->st));
-        SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, true));
+        if (pr->Sg_all) SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, false, pr->Sg_all + (int64_t)k * pr->nSg, pr->nSg));
+        else SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, true));
         SOLVE_HIP(launch_dot_part(c->d.dtype, c->d.p, c->K, c->grad, c->d.ldw, c->grad, c->d.ldw, c->red_a, vb, nullptr,
                                   c->st));
         SOLVE_HIP(launch_combine(c->red_a, vb, 1.0, nullptr, 0, 0.0, c->scal_dev + 2, c->st));
@@ -813,7 +855,7 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         SOLVE_HIP(hipStreamSynchronize(c->st));
         flush_pending();
         {
-            rec.f = c->host_pin[0];
+            rec.f = pr->Sg_all ? f_carry : c->host_pin[0];
             const double slope = c->host_pin[1];
             rec.gnorm = std::sqrt(c->host_pin[2]);
             CgSlot fin;
@@ -837,6 +879,7 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
             double fn = 0.0;
             SOLVE_TRY(linesearch_impl(c, W, c->dir, rec.f, slope, pr->beta, pr->rho, pr->imax, &rec.alpha, &fn, &rec.ls_evals,
                                       &rec.ls_ok));
+            f_carry = fn;
         }
         SOLVE_HIP(hipEventRecord(E[4], c->st));
         SOLVE_TRY(ssn_axpy(c, rec.alpha, c->dir, W));

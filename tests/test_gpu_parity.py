@@ -78,6 +78,34 @@ def test_hessvec(data_cache, cfg, n, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+@pytest.mark.parametrize("cfg,n", CASES)
+def test_sampled_gradient(data_cache, cfg, n, dtype):
+    # eq. (2a): 20 % of the rows without replacement, and a multiset with repeats
+    d = data_cache(cfg, n)
+    pair = Pair(d, dtype)
+    tol = TOL[dtype]
+    rng = np.random.default_rng(11)
+    samples = [synth.sample_rows(n, max(1, n // 5), seed=77), rng.integers(0, n, size=max(3, n // 7)).astype(np.int32)]
+    Wh, Wd = _weights(pair, 1, 0.1)
+    for S in samples:
+        print(f"[case] sampled gradient cfg={cfg} n={n} dtype={dtype} nS={S.size}", flush=True)
+        G, fS = pair.gpu.ssn_gradient_sampled(Wd, pair.idx(S))
+        torch.cuda.synchronize()
+        G_ref, f_ref = pair.oracle.gradient_sampled(Wh, S)
+        assert rel_err(pair.host(G), G_ref) <= tol, rel_err(pair.host(G), G_ref)
+        assert rel_scalar(fS, f_ref) <= tol
+    # the Hessian sample prepared before a sampled gradient stays usable after it
+    Sh = synth.sample_rows(n, d["nS"])
+    Vh, Vd = _weights(pair, 7, 1.0)
+    pair.gpu.ssn_hess_prepare(Wd, pair.idx(Sh))
+    pair.gpu.ssn_gradient_sampled(Wd, pair.idx(samples[0]), want_f=False)
+    HV = pair.gpu.ssn_hess_apply(Vd)
+    torch.cuda.synchronize()
+    assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, Sh, Vh)) <= tol
+    pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 def test_hessvec_multiset_sample_and_single_row(data_cache, dtype):
     d = data_cache(0, 2000)
     pair = Pair(d, dtype)

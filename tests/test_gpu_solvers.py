@@ -118,6 +118,29 @@ def test_ssn_fixed_schedule_tiny_config(tiny, dtype):
     tpair.close()
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_ssn_with_sub_sampled_gradient(tiny, dtype):
+    # Alg. 1 with eq. (2a) and eq. (2b): 20 % of the rows for g, 5 % for H
+    d = tiny
+    pair = Pair(d, dtype)
+    iters = 6
+    S_all = synth.sample_schedule(2000, d["nS"], iters)
+    Sg_all = np.stack([synth.sample_rows(2000, 400, seed=900 + k) for k in range(iters)]).astype(np.int32)
+    W0h, W0d = pair.block(np.zeros((pair.p, pair.K)))
+    Wref, log_ref, done_ref = pair.oracle.ssn_sg(W0h, Sg_all, S_all, theta=1e-4, T=d["T"])
+    recs, done = pair.gpu.ssn_solve(W0d, torch.from_numpy(S_all).cuda(), theta=1e-4, T=d["T"],
+                                    Sg_all=torch.from_numpy(Sg_all).cuda())
+    torch.cuda.synchronize()
+    assert done == done_ref == iters
+    f_gpu = np.array([r["f"] for r in recs])
+    np.testing.assert_allclose(f_gpu, log_ref[:, 0], rtol=1e-8 if dtype == F64 else 1e-3)
+    np.testing.assert_allclose([r["gnorm"] for r in recs], log_ref[:, 1], rtol=1e-7 if dtype == F64 else 2e-2)
+    assert [r["cg_iters"] for r in recs] == [int(x) for x in log_ref[:, 2]]
+    assert [r["alpha"] for r in recs] == list(log_ref[:, 4])
+    assert rel_err(pair.host(W0d), Wref) <= (1e-7 if dtype == F64 else 2e-2)
+    pair.close()
+
+
 def test_error_paths(tiny):
     d = tiny
     dev = "cuda"
