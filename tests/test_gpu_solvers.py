@@ -53,6 +53,48 @@ def test_cg_follows_the_oracle_step_by_step(cfg, n, dtype):
     pair.close()
 
 
+def _shape_problem(n, p, C, lam, seed):
+    """Seeded dense stand-in of a given shape (N(0,1) features, labels from a random linear model)."""
+    g = np.random.default_rng(seed)
+    X = g.standard_normal((n, p))
+    Wt = g.standard_normal((p, C))
+    labels = np.argmax(X @ Wt / np.sqrt(p) + g.gumbel(size=(n, C)), axis=1).astype(np.int32)
+    return dict(layout="dense", X=X, labels=labels, n=n, p=p, C=C, K=C - 1, lam=lam, nS=n, T=10, iters=1, name="shape")
+
+
+@pytest.mark.parametrize("n,p,C,lam,theta,T", [(1500, 48, 11, 1e-3, 1e-9, 150), (640, 1000, 2, 1e-2, 1e-8, 300)],
+                         ids=["drive_like", "gisette_like_binary"])
+def test_full_newton_with_a_long_cg(n, p, C, lam, theta, T):
+    # the FullNewton variant of Sec. 4 (|S| = n, exact gradient and Hessian) with a CG budget far beyond
+    # the usual 10 products, on the two shapes the paper runs long CG on (11 classes / 48 features, and
+    # the binary case K = 1)
+    d = _shape_problem(n, p, C, lam, seed=41)
+    pair = Pair(d, F64)
+    Wh, Wd = pair.block(synth.probe(pair.p, pair.K, sub=1, scale=0.1))
+    S = np.arange(n, dtype=np.int32)
+    G_ref, _ = pair.oracle.gradient(Wh)
+    Gh, Gd = pair.block(G_ref)
+    pair.gpu.ssn_hess_prepare(Wd, pair.idx(S))
+    print(f"[case] full newton long cg n={n} p={p} C={C} T={T}", flush=True)
+    ref = pair.oracle.cg(Wh, S, Gh, theta, T)
+    out = pair.gpu.ssn_cg(Gd, theta, T)
+    torch.cuda.synchronize()
+    assert ref["flags"] & 1 and out["flags"] & 1                     # both reach the tolerance
+    assert abs(out["iters"] - ref["iters"]) <= 2                      # long recurrences drift by rounding
+    assert out["rel_res"] <= theta and ref["rel_res"] <= theta
+    k = min(out["iters"], ref["iters"], 25)
+    np.testing.assert_allclose(out["alpha"][:k], ref["alpha"][:k], rtol=1e-6)
+    assert rel_err(pair.host(out["p"]), ref["p"]) <= 1e-7               # the Newton direction itself
+    # one exact Newton iteration through the driver
+    W0h, W0d = pair.block(np.zeros((pair.p, pair.K)))
+    Wn, log_ref, _ = pair.oracle.ssn(W0h, S[None, :], theta=theta, T=T)
+    recs, done = pair.gpu.ssn_solve(W0d, pair.idx(S)[None, :].contiguous(), theta=theta, T=T)
+    torch.cuda.synchronize()
+    assert done == 1 and recs[0]["alpha"] == log_ref[0, 4]
+    assert rel_err(pair.host(W0d), Wn) <= 1e-7
+    pair.close()
+
+
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 def test_cg_zero_budget_and_zero_gradient(tiny, dtype):
     pair = Pair(tiny, dtype)
