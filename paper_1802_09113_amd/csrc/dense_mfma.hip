@@ -263,7 +263,12 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
 // wave that walks all p features alone is a long chain of dependent loads.  Then a whole workgroup (8 or
 // 16 waves) shares one row block: the waves take the feature groups in turn, their partial margins are
 // added through LDS in wave order, and wave 0 does the per-row work.
-template <typename T, int NB, int VEC, int MODE, bool SPLIT>
+//
+// PAIR: two row blocks per trip share every load of W, which otherwise costs the L1 as many bytes as X
+// itself (wide matrices; for narrow ones the per-row work dominates and more, smaller trips are better).
+// (A class-major copy of M, one vector load per lane for the W operands of consecutive features, was
+// tried: its loads touch 16 cache lines per instruction instead of 4-8 and the kernel got 30 % slower.)
+template <typename T, int NB, int VEC, int MODE, bool SPLIT, bool PAIR>
 __global__ __launch_bounds__(SPLIT ? 1024 : 64 * ROWS_WAVES_PER_BLOCK) void dense_rows_kernel(RowsArgs a)
 {
     if (a.skip && *a.skip) return;
@@ -295,24 +300,30 @@ __global__ __launch_bounds__(SPLIT ? 1024 : 64 * ROWS_WAVES_PER_BLOCK) void dens
     constexpr int STEP = 4 * VEC;     // features consumed per vector load (4 k-groups of VEC)
     constexpr int UNR = 4;
 
-    for (int64_t rb = wave; rb < nblk; rb += nwaves) {
-        int64_t si = rb * 16 + q;
-        if (si >= a.nrows) si = a.nrows - 1;          // clamped rows are masked in the epilogue
-        const int64_t xr = a.S ? a.S[si] : si;
-        const T *xrow = X + xr * a.ldx;
-        v4 acc[NB];
+    constexpr int RB = PAIR ? 2 : 1;
+    for (int64_t rb0 = wave * RB; rb0 < nblk; rb0 += nwaves * RB) {
+        const T *xrow[RB];
+        v4 acc[RB][NB];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) acc[nb] = v4{0, 0, 0, 0};
+        for (int k = 0; k < RB; ++k) {
+            int64_t si = (rb0 + k) * 16 + q;
+            if (si >= a.nrows) si = a.nrows - 1;      // clamped rows are masked in the epilogue
+            const int64_t xr = a.S ? a.S[si] : si;
+            xrow[k] = X + xr * a.ldx;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) acc[k][nb] = v4{0, 0, 0, 0};
+        }
 
         int64_t f0 = SPLIT ? (int64_t)wib * (STEP * UNR) : 0;
         const int64_t fstride = SPLIT ? (int64_t)nsw * (STEP * UNR) : STEP * UNR;
         for (; f0 + STEP * UNR <= p; f0 += fstride) {
-            pack xv[UNR];
+            pack xv[RB][UNR];
             T wv[UNR][VEC][NB];
 #pragma unroll
             for (int u = 0; u < UNR; ++u) {
                 const int64_t f = f0 + u * STEP + VEC * g;
-                xv[u] = *(const pack *)(xrow + f);
+#pragma unroll
+                for (int k = 0; k < RB; ++k) xv[k][u] = *(const pack *)(xrow[k] + f);
 #pragma unroll
                 for (int m = 0; m < VEC; ++m)
 #pragma unroll
@@ -323,8 +334,11 @@ __global__ __launch_bounds__(SPLIT ? 1024 : 64 * ROWS_WAVES_PER_BLOCK) void dens
 #pragma unroll
                 for (int m = 0; m < VEC; ++m)
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb)
-                        acc[nb] = mfma16(xv[u].v[m], cval[nb] ? wv[u][m][nb] : T(0), acc[nb]);
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const T w = cval[nb] ? wv[u][m][nb] : T(0);
+#pragma unroll
+                        for (int k = 0; k < RB; ++k) acc[k][nb] = mfma16(xv[k][u].v[m], w, acc[k][nb]);
+                    }
         }
         f0 = p / (STEP * UNR) * (STEP * UNR);
         if (SPLIT && wib != 0) f0 = p;                 // the tail belongs to wave 0
@@ -333,32 +347,38 @@ __global__ __launch_bounds__(SPLIT ? 1024 : 64 * ROWS_WAVES_PER_BLOCK) void dens
 #pragma unroll
             for (int m = 0; m < VEC; ++m) {
                 const bool ok = (f + m) < p;
-                const T x = ok ? xrow[f + m] : T(0);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     const T w = (ok && cval[nb]) ? mcol[nb][(f + m) * ldm] : T(0);
-                    acc[nb] = mfma16(x, w, acc[nb]);
+#pragma unroll
+                    for (int k = 0; k < RB; ++k) {
+                        const T x = ok ? xrow[k][f + m] : T(0);
+                        acc[k][nb] = mfma16(x, w, acc[k][nb]);
+                    }
                 }
             }
         }
         if constexpr (SPLIT) {
+            const int64_t rb = rb0;
             T *zs = (T *)rows_smem;                    // nsw x NB x 4 x 64
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) zs[((wib * NB + nb) * 4 + v) * 64 + lane] = acc[nb][v];
+                for (int v = 0; v < 4; ++v) zs[((wib * NB + nb) * 4 + v) * 64 + lane] = acc[0][nb][v];
             __syncthreads();
             if (wib == 0) {
                 for (int ww = 1; ww < nsw; ++ww)       // fixed order
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) acc[nb][v] += zs[((ww * NB + nb) * 4 + v) * 64 + lane];
-                row_epilogue<T, NB, MODE>(acc, a, rb, lane, loss, hits);
+                        for (int v = 0; v < 4; ++v) acc[0][nb][v] += zs[((ww * NB + nb) * 4 + v) * 64 + lane];
+                row_epilogue<T, NB, MODE>(acc[0], a, rb, lane, loss, hits);
             }
             __syncthreads();
         } else {
-            row_epilogue<T, NB, MODE>(acc, a, rb, lane, loss, hits);
+#pragma unroll
+            for (int k = 0; k < RB; ++k)
+                if (rb0 + k < nblk) row_epilogue<T, NB, MODE>(acc[k], a, rb0 + k, lane, loss, hits);
         }
     }
 
@@ -412,7 +432,36 @@ __global__ __launch_bounds__(256) void dense_xtu_kernel(XtuArgs a)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[t][nb] = v4{0, 0, 0, 0};
 
-    for (int64_t r0 = r_begin; r0 < r_end; r0 += 4) {
+    // main loop: 16 rows (four MFMA contraction steps) per trip, every load of the trip issued before its
+    // first MFMA; the guarded loop below takes the rest
+    constexpr int RU = 4;
+    int64_t r0 = r_begin;
+    if (full) {
+        for (; r0 + 4 * RU <= r_end; r0 += 4 * RU) {
+            pack xv[RU][NL];
+            T ub[RU][NB];
+#pragma unroll
+            for (int u = 0; u < RU; ++u) {
+                const int64_t sc = r0 + 4 * u + g;
+                const int64_t xr = a.S ? (int64_t)a.S[sc] : sc;
+                const T *xrow = X + xr * a.ldx + f0 + VEC * q;
+#pragma unroll
+                for (int ld = 0; ld < NL; ++ld) xv[u][ld] = *(const pack *)(xrow + ld * 16 * VEC);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) ub[u][nb] = U[sc * a.KP + nb * 16 + q];
+            }
+#pragma unroll
+            for (int u = 0; u < RU; ++u)
+#pragma unroll
+                for (int ld = 0; ld < NL; ++ld)
+#pragma unroll
+                    for (int m = 0; m < VEC; ++m)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[ld * VEC + m][nb] = mfma16(xv[u][ld].v[m], ub[u][nb], acc[ld * VEC + m][nb]);
+        }
+    }
+    for (; r0 < r_end; r0 += 4) {
         const int64_t si = r0 + g;
         const bool rv = si < r_end;
         const int64_t sc = rv ? si : r_begin;
@@ -501,18 +550,20 @@ static hipError_t rows_dispatch_mode(const RowsArgs &a, int blocks, int split_wa
     if (split_waves > 0 && v) {
         dim3 grid(blocks), block(64 * split_waves);
         const size_t lds = (size_t)split_waves * nb * 256 * sizeof(T);
-        if (nb == 1) hipLaunchKernelGGL((dense_rows_kernel<T, 1, VEC, MODE, true>), grid, block, lds, st, a);
-        else hipLaunchKernelGGL((dense_rows_kernel<T, 2, VEC, MODE, true>), grid, block, lds, st, a);
+        if (nb == 1) hipLaunchKernelGGL((dense_rows_kernel<T, 1, VEC, MODE, true, false>), grid, block, lds, st, a);
+        else hipLaunchKernelGGL((dense_rows_kernel<T, 2, VEC, MODE, true, false>), grid, block, lds, st, a);
         return hipGetLastError();
     }
     if (split_waves > 0) return hipErrorInvalidValue;      // the planner splits only 16-byte aligned rows
     dim3 grid(blocks), block(64 * ROWS_WAVES_PER_BLOCK);
+    const bool pair = v && nb == 1 && a.p >= 512;
     if (nb == 1) {
-        if (v) hipLaunchKernelGGL((dense_rows_kernel<T, 1, VEC, MODE, false>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((dense_rows_kernel<T, 1, 1, MODE, false>), grid, block, 0, st, a);
+        if (pair) hipLaunchKernelGGL((dense_rows_kernel<T, 1, VEC, MODE, false, true>), grid, block, 0, st, a);
+        else if (v) hipLaunchKernelGGL((dense_rows_kernel<T, 1, VEC, MODE, false, false>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((dense_rows_kernel<T, 1, 1, MODE, false, false>), grid, block, 0, st, a);
     } else {
-        if (v) hipLaunchKernelGGL((dense_rows_kernel<T, 2, VEC, MODE, false>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((dense_rows_kernel<T, 2, 1, MODE, false>), grid, block, 0, st, a);
+        if (v) hipLaunchKernelGGL((dense_rows_kernel<T, 2, VEC, MODE, false, false>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((dense_rows_kernel<T, 2, 1, MODE, false, false>), grid, block, 0, st, a);
     }
     return hipGetLastError();
 }

@@ -140,6 +140,31 @@ def test_hessvec_sample_of_several_row_blocks_per_workgroup(data_cache, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_wide_matrix_with_many_row_blocks(data_cache, dtype):
+    # 9001 rows of the 3072-feature workload: more row blocks than the workgroup-per-block variant takes, so
+    # the wave-per-block kernel runs in its two-blocks-per-trip form, with a ragged last block
+    d = data_cache(2, 9001)
+    pair = Pair(d, dtype)
+    tol = TOL[dtype]
+    Wh, Wd = _weights(pair, 1, 0.1)
+    print(f"[case] wide many blocks dtype={dtype}", flush=True)
+    f = pair.gpu.ssn_objective(Wd)
+    G, f2 = pair.gpu.ssn_gradient(Wd)
+    torch.cuda.synchronize()
+    G_ref, f_ref = pair.oracle.gradient(Wh)
+    assert rel_scalar(f, f_ref) <= tol and rel_scalar(f2, f_ref) <= tol
+    assert rel_err(pair.host(G), G_ref) <= tol
+    S = np.arange(9001, dtype=np.int32)[::-1].copy()                 # all rows, reversed: 563 blocks in the product too
+    Vh, Vd = _weights(pair, 2, 1.0)
+    HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+    torch.cuda.synchronize()
+    assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
+    _, acc = pair.gpu.ssn_predict(Wd)
+    assert abs(acc - pair.oracle.accuracy(Wh)) <= (1e-12 if dtype == F64 else 2e-3)
+    pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 @pytest.mark.parametrize("scale", ["mean", "sum"])
 def test_scaling_modes_and_padded_leading_dimensions(data_cache, scale, dtype):
     d = data_cache(0, 2000)
