@@ -143,28 +143,97 @@ __device__ __forceinline__ float fast_rcp(float a)
     return x;
 }
 
-// Per-row work on a 16-row block of margins held in MFMA accumulator layout:
-// acc[nb][v] = z(row d_row<T>(lane/16, v), class 16*nb + lane%16).
-// TOREG: U (ROW_GRAD / ROW_APPLY) is returned in `uout` in the same accumulator layout instead of being
-// stored.  vmask selects which of the 4 accumulator elements (row groups) this wave works on.
-template <typename T, int NB, int MODE, bool TOREG = false>
-__device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[NB], const RowsArgs &a,
-                                             int64_t rb, int lane, double &loss, int &hits,
-                                             typename V4<T>::type *uout = nullptr, int vmask = 15,
-                                             const int *lab_pre = nullptr, const T *pin_pre = nullptr)
+// ---------------------------------------------------------------------------------------------
+// Per-row work on ONE accumulator element of a 16-row block (K <= 16): the 16 lanes of a row group hold the
+// 16 class columns of sample row sv.  lab / pin are that row's label and this lane's probability,
+// loaded by the caller.  Returns U (ROW_GRAD: eq. (6) residual p - y; ROW_APPLY: eq. (12)).
+template <typename T, int MODE>
+__device__ __forceinline__ T slot_epilogue(T z, const RowsArgs &a, int64_t sv, int q, int lab, T pin, double &loss,
+                                           double &lprod, int &hits)
 {
-    // lab_pre / pin_pre (one-pass kernel, NB == 1): label and probability of each accumulator element,
-    // loaded by the caller ahead of its X prefetch so that waiting for them does not drain that prefetch
+    const int K = a.K;
+    const bool valid = sv < a.nrows;
+    const bool cv = q < K;
+    const T NEG = -std::numeric_limits<T>::infinity();
+    if constexpr (MODE == ROW_APPLY) {
+        const T t = row16_sum(pin * z);                    // pin is zero in padded columns
+        const T u = valid ? (pin * z - pin * t) : T(0);
+        // z_i . u_i of the row: summed over the sample it is V^T (X_S^T U), the curvature term CG needs
+        const T zu = row16_sum(z * u);
+        if (valid && q == 0) loss += (double)zu;
+        return u;
+    }
+    if constexpr (MODE == ROW_PRED) {
+        const T zmax = row16_max(cv ? z : NEG);
+        const int cand = row16_min((cv && z == zmax) ? q : 0x7fffffff);
+        const int pr = (T(0) > zmax) ? K : cand;           // the reference class wins only strictly
+        if (valid && q == 0) {
+            if (a.pred) a.pred[sv] = pr;
+            hits += (pr == lab);
+        }
+        return T(0);
+    }
+    // eqs. (8), (9).  With K < 16 the lane of column K is free: it plays the reference class (margin 0), so
+    // M = max{0, z} is one row maximum and alpha = e^{-M} + sum_c e^{z_c - M} one row sum of one
+    // exponential per lane.
+    const bool ref_lane = K < 16;
+    const T zz = (q == K) ? T(0) : z;
+    const bool ce = ref_lane ? (q <= K) : cv;
+    const T zmax = row16_max(ce ? zz : NEG);
+    const T Mx = ref_lane ? zmax : fmax(T(0), zmax);
+    const T e = ce ? t_exp(zz - Mx) : T(0);
+    T alpha = row16_sum(e);
+    if (!ref_lane) alpha += t_exp(-Mx);
+    const T inv = fast_rcp(alpha);
+    if constexpr (MODE == ROW_PREP) {
+        ((T *)a.UP)[sv * a.KP + q] = (valid && cv) ? e * inv : T(0);
+        return T(0);
+    }
+    // margin of the label's class, read from the lane that holds it (0 for the reference class)
+    const T zl = __shfl(z, (threadIdx.x & 48) | (lab & 15));
+    const T lin = (lab < K) ? zl : T(0);
+    // eqs. (14)-(17): the row adds M + log(alpha) - z_label.  The logarithms are taken of a running product
+    // of the alphas (each in [1, C]) instead of one by one; the product is folded into the sum before it
+    // can overflow, and once more at the end of the kernel.
+    if (valid && q == 0) {
+        loss += (double)Mx - (double)lin;
+        lprod *= (double)alpha;
+    }
+    if (lprod > 1e250) {
+        loss += log(lprod);
+        lprod = 1.0;
+    }
+    if constexpr (MODE == ROW_GRAD) return (valid && cv) ? (e * inv - ((q == lab) ? T(1) : T(0))) : T(0);
+    return T(0);
+}
+
+// Per-row work on a 16-row block of margins held in MFMA accumulator layout:
+// acc[nb][v] = z(row d_row<T>(lane/16, v), class 16*nb + lane%16).  With one class tile (K <= 16) the
+// modes that exponentiate go through slot_epilogue, element by element.
+template <typename T, int NB, int MODE>
+__device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[NB], const RowsArgs &a,
+                                             int64_t rb, int lane, double &loss, double &lprod, int &hits)
+{
     constexpr bool primary = true;
+    constexpr bool TOREG = false;
+    typename V4<T>::type *uout = nullptr;
+    const int *lab_pre = nullptr;
+    const T *pin_pre = nullptr;
     const int q = lane & 15, g = lane >> 4;
     const int K = a.K;
     const T NEG = -std::numeric_limits<T>::infinity();
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-        if (!((vmask >> v) & 1)) continue;
         const int64_t sv = rb * 16 + d_row<T>(g, v);
         const bool valid = sv < a.nrows;
         const int64_t svc = valid ? sv : a.nrows - 1;
+        if constexpr (NB == 1 && (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_PREP)) {
+            int lab = 0;
+            if constexpr (MODE != ROW_PREP) lab = a.labels[a.S ? a.S[svc] : svc];
+            const T u = slot_epilogue<T, MODE>(acc[0][v], a, sv, q, lab, T(0), loss, lprod, hits);
+            if constexpr (MODE == ROW_GRAD) ((T *)a.UP)[sv * a.KP + q] = u;
+            continue;
+        }
         T z[NB];
         bool cv[NB];
         T zmax = NEG;
@@ -294,7 +363,7 @@ __global__ __launch_bounds__(SPLIT ? 1024 : 64 * ROWS_WAVES_PER_BLOCK) void dens
         mcol[nb] = M + (cval[nb] ? c : K - 1);
     }
 
-    double loss = 0.0;
+    double loss = 0.0, lprod = 1.0;         // sum of the row terms without log(alpha); product of the alphas
     int hits = 0;
     const int64_t nblk = (a.nrows + 15) / 16;
     constexpr int STEP = 4 * VEC;     // features consumed per vector load (4 k-groups of VEC)
@@ -372,19 +441,20 @@ __global__ __launch_bounds__(SPLIT ? 1024 : 64 * ROWS_WAVES_PER_BLOCK) void dens
                     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                         for (int v = 0; v < 4; ++v) acc[0][nb][v] += zs[((ww * NB + nb) * 4 + v) * 64 + lane];
-                row_epilogue<T, NB, MODE>(acc[0], a, rb, lane, loss, hits);
+                row_epilogue<T, NB, MODE>(acc[0], a, rb, lane, loss, lprod, hits);
             }
             __syncthreads();
         } else {
 #pragma unroll
             for (int k = 0; k < RB; ++k)
-                if (rb0 + k < nblk) row_epilogue<T, NB, MODE>(acc[k], a, rb0 + k, lane, loss, hits);
+                if (rb0 + k < nblk) row_epilogue<T, NB, MODE>(acc[k], a, rb0 + k, lane, loss, lprod, hits);
         }
     }
 
     // one partial per wave; SPLIT: the block's four partial slots are wave 0's sum and three zeros
     if (SPLIT && wib != 0) return;
     if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_APPLY) {
+        if constexpr (MODE != ROW_APPLY) loss += log(lprod);
         for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off);
         if constexpr (SPLIT) {
             if (lane < ROWS_WAVES_PER_BLOCK) a.loss_part[wave * ROWS_WAVES_PER_BLOCK + lane] = (lane == 0) ? loss : 0.0;
@@ -606,70 +676,6 @@ template <typename T> static hipError_t xtu_dispatch(const XtuArgs &a, hipStream
 hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st)
 {
     return dtype == SSN_F32 ? xtu_dispatch<float>(a, st) : xtu_dispatch<double>(a, st);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Per-row work of the one-pass kernel on ONE accumulator element: the 16 lanes of a row group hold the
-// 16 class columns of sample row sv.  lab / pin are that row's label and this lane's probability,
-// loaded by the caller.  Returns U (ROW_GRAD: eq. (6) residual p - y; ROW_APPLY: eq. (12)).
-template <typename T, int MODE>
-__device__ __forceinline__ T slot_epilogue(T z, const RowsArgs &a, int64_t sv, int q, int lab, T pin, double &loss,
-                                           double &lprod, int &hits)
-{
-    const int K = a.K;
-    const bool valid = sv < a.nrows;
-    const bool cv = q < K;
-    const T NEG = -std::numeric_limits<T>::infinity();
-    if constexpr (MODE == ROW_APPLY) {
-        const T t = row16_sum(pin * z);                    // pin is zero in padded columns
-        const T u = valid ? (pin * z - pin * t) : T(0);
-        // z_i . u_i of the row: summed over the sample it is V^T (X_S^T U), the curvature term CG needs
-        const T zu = row16_sum(z * u);
-        if (valid && q == 0) loss += (double)zu;
-        return u;
-    }
-    if constexpr (MODE == ROW_PRED) {
-        const T zmax = row16_max(cv ? z : NEG);
-        const int cand = row16_min((cv && z == zmax) ? q : 0x7fffffff);
-        const int pr = (T(0) > zmax) ? K : cand;           // the reference class wins only strictly
-        if (valid && q == 0) {
-            if (a.pred) a.pred[sv] = pr;
-            hits += (pr == lab);
-        }
-        return T(0);
-    }
-    // eqs. (8), (9).  With K < 16 the lane of column K is free: it plays the reference class (margin 0), so
-    // M = max{0, z} is one row maximum and alpha = e^{-M} + sum_c e^{z_c - M} one row sum of one
-    // exponential per lane.
-    const bool ref_lane = K < 16;
-    const T zz = (q == K) ? T(0) : z;
-    const bool ce = ref_lane ? (q <= K) : cv;
-    const T zmax = row16_max(ce ? zz : NEG);
-    const T Mx = ref_lane ? zmax : fmax(T(0), zmax);
-    const T e = ce ? t_exp(zz - Mx) : T(0);
-    T alpha = row16_sum(e);
-    if (!ref_lane) alpha += t_exp(-Mx);
-    const T inv = fast_rcp(alpha);
-    if constexpr (MODE == ROW_PREP) {
-        ((T *)a.UP)[sv * a.KP + q] = (valid && cv) ? e * inv : T(0);
-        return T(0);
-    }
-    // margin of the label's class, read from the lane that holds it (0 for the reference class)
-    const T zl = __shfl(z, (threadIdx.x & 48) | (lab & 15));
-    const T lin = (lab < K) ? zl : T(0);
-    // eqs. (14)-(17): the row adds M + log(alpha) - z_label.  The logarithms are taken of a running product
-    // of the alphas (each in [1, C]) instead of one by one; the product is folded into the sum before it
-    // can overflow, and once more at the end of the kernel.
-    if (valid && q == 0) {
-        loss += (double)Mx - (double)lin;
-        lprod *= (double)alpha;
-    }
-    if (lprod > 1e250) {
-        loss += log(lprod);
-        lprod = 1.0;
-    }
-    if constexpr (MODE == ROW_GRAD) return (valid && cv) ? (e * inv - ((q == lab) ? T(1) : T(0))) : T(0);
-    return T(0);
 }
 
 // Fused one-pass kernel: margins, per-row epilogue and (for ROW_GRAD / ROW_APPLY) the transposed
