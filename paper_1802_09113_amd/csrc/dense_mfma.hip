@@ -587,6 +587,12 @@ int rows_grid_blocks(int64_t nrows, int num_cus)
     return (int)blocks;
 }
 
+// fp32 rows that are only 8-byte aligned (e.g. 54 features): two-element vector loads
+static bool half_vec_ok(int dtype_size, const void *X, int64_t ldx)
+{
+    return dtype_size == 4 && ((uintptr_t)X % 8 == 0) && (ldx % 2 == 0);
+}
+
 template <typename T> static bool vec_ok(const void *X, int64_t ldx)
 {
     constexpr int VEC = 16 / sizeof(T);
@@ -627,6 +633,12 @@ static hipError_t rows_dispatch_mode(const RowsArgs &a, int blocks, int split_wa
     if (split_waves > 0) return hipErrorInvalidValue;      // the planner splits only 16-byte aligned rows
     dim3 grid(blocks), block(64 * ROWS_WAVES_PER_BLOCK);
     const bool pair = v && nb == 1 && a.p >= 512;
+    if constexpr (sizeof(T) == 4) {
+        if (!v && nb == 1 && half_vec_ok(4, a.X, a.ldx)) {
+            hipLaunchKernelGGL((dense_rows_kernel<T, 1, 2, MODE, false, false>), grid, block, 0, st, a);
+            return hipGetLastError();
+        }
+    }
     if (nb == 1) {
         if (pair) hipLaunchKernelGGL((dense_rows_kernel<T, 1, VEC, MODE, false, true>), grid, block, 0, st, a);
         else if (v) hipLaunchKernelGGL((dense_rows_kernel<T, 1, VEC, MODE, false, false>), grid, block, 0, st, a);
@@ -661,6 +673,12 @@ template <typename T> static hipError_t xtu_dispatch(const XtuArgs &a, hipStream
     const int nb = (a.K + 15) / 16;
     const bool v = vec_ok<T>(a.X, a.ldx);
     dim3 grid((unsigned)((a.p + 255) / 256), (unsigned)a.nchunks), block(256);
+    if constexpr (sizeof(T) == 4) {
+        if (!v && nb == 1 && half_vec_ok(4, a.X, a.ldx)) {
+            hipLaunchKernelGGL((dense_xtu_kernel<T, 1, 2>), grid, block, 0, st, a);
+            return hipGetLastError();
+        }
+    }
     if (nb == 1) {
         if (v) hipLaunchKernelGGL((dense_xtu_kernel<T, 1, VEC>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((dense_xtu_kernel<T, 1, 1>), grid, block, 0, st, a);

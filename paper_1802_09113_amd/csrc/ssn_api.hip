@@ -181,11 +181,16 @@ int launch_rows(ssn_ctx *c, const RowsArgs &a, int *nparts)
     return SSN_OK;
 }
 
+// Waves of the transposed-product kernel to aim at per compute unit.  A narrow matrix has a single
+// 64-feature tile, so all the parallelism comes from row chunks and each wave is a short chain of loads:
+// more, shorter chunks keep more loads in flight.
+int xtu_waves_per_cu(int64_t p) { return p <= 128 ? 32 : 8; }
+
 // choose the row chunking of the dense transposed product
 void choose_chunks(const ssn_ctx *c, int64_t nrows, int64_t *rpc, int *nch)
 {
     const int64_t nft = (c->d.p + 63) / 64;
-    const int64_t target = (int64_t)c->num_cus * 8;
+    const int64_t target = (int64_t)c->num_cus * xtu_waves_per_cu(c->d.p);
     int64_t n = (target + nft - 1) / nft;
     const int64_t maxn = (nrows + 15) / 16;
     if (n > maxn) n = maxn;
@@ -523,7 +528,7 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
     CREATE_HIP(hipHostMalloc((void **)&c->host_pin, 4096));
     if (d->layout == SSN_DENSE_ROWMAJOR) {
         const int64_t nft = (d->p + 63) / 64;
-        c->max_chunks = (int)(((int64_t)c->num_cus * 8 + nft - 1) / nft);
+        c->max_chunks = (int)(((int64_t)c->num_cus * xtu_waves_per_cu(d->p) + nft - 1) / nft);
         RowsArgs probe = rows_base(c);
         probe.nrows = (int64_t)1 << 40;
         probe.mode = ROW_GRAD;                                 // the family that writes partials

@@ -46,6 +46,25 @@ int vec_blocks(int64_t total)
     return (int)b;
 }
 
+// sum over chunks cl, cl + CLN, .. of element e of the per-chunk partials, eight loads in flight at a time,
+// added in chunk order
+template <typename T, int CLN>
+__device__ __forceinline__ double chunk_sum(const T *part, int nchunks, int64_t total, int64_t e, int cl)
+{
+    double s = 0.0;
+    for (int c = cl; c < nchunks; c += 8 * CLN) {
+        T v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int cc = c + u * CLN;
+            v[u] = part[(int64_t)(cc < nchunks ? cc : cl) * total + e];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (c + u * CLN < nchunks) ? (double)v[u] : 0.0;
+    }
+    return s;
+}
+
 // ---- finalize: out = scale * sum_chunks part + lambda * M -----------------------------------
 // A block owns EL consecutive elements at a time; its 256/EL thread rows split the chunk sum and are
 // folded through LDS in a fixed order.
@@ -64,8 +83,7 @@ template <typename T, int EL> __global__ __launch_bounds__(VEC_BLOCK) void final
     for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
         const int64_t e = grp * EL + el;
         double s = 0.0;
-        if (e < total)
-            for (int c = cl; c < a.nchunks; c += CLN) s += (double)part[(int64_t)c * total + e];
+        if (e < total) s = chunk_sum<T, CLN>(part, a.nchunks, total, e, cl);
         sm[threadIdx.x] = s;
         __syncthreads();
         if (cl == 0 && e < total) {
@@ -146,8 +164,7 @@ template <typename T, int EL> __global__ __launch_bounds__(VEC_BLOCK) void final
     for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
         const int64_t e = grp * EL + el;
         double t = 0.0;
-        if (e < total)
-            for (int ch = cl; ch < a.nchunks; ch += CLN) t += (double)part[(int64_t)ch * total + e];
+        if (e < total) t = chunk_sum<T, CLN>(part, a.nchunks, total, e, cl);
         sm[threadIdx.x] = t;
         __syncthreads();
         if (cl == 0 && e < total) {
