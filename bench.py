@@ -25,9 +25,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X datasheet HBM3E bandwidth
 # default workload, scaled by the calibration kernels (profiles/dense_one_pass_image_like_f64_hbm_traffic_pmc.md).
 # Counters cannot be read from inside this script; other workloads / dtypes report null.
 MEASURED_TRAFFIC = {
-    ("image_like", "f64", "dense_fused_kernel<OBJ>"): 377.7e6,
-    ("image_like", "f64", "dense_fused_kernel<GRAD>"): 426.0e6 + 24.9e6,
-    ("image_like", "f64", "dense_fused_kernel<APPLY>"): 19.9e6 + 10.6e6,
+    ("image_like", "f64", "dense_fused_kernel<OBJ>"): 377.5e6,
+    ("image_like", "f64", "dense_fused_kernel<GRAD>"): 393.1e6 + 18.7e6,
+    ("image_like", "f64", "dense_fused_kernel<APPLY>"): 19.8e6 + 10.6e6,
 }
 
 
