@@ -23,6 +23,29 @@ __device__ __forceinline__ double block_sum(double v)
     return r;
 }
 
+// two sums at once (same order of operations as block_sum for each)
+__device__ __forceinline__ void block_sum2(double a, double b, double &ra, double &rb)
+{
+    __shared__ double sm2[2 * (VEC_BLOCK / 64)];
+    for (int off = 32; off > 0; off >>= 1) {
+        a += __shfl_xor(a, off);
+        b += __shfl_xor(b, off);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        sm2[threadIdx.x >> 6] = a;
+        sm2[VEC_BLOCK / 64 + (threadIdx.x >> 6)] = b;
+    }
+    __syncthreads();
+    ra = sm2[0];
+    rb = sm2[VEC_BLOCK / 64];
+#pragma unroll
+    for (int k = 1; k < VEC_BLOCK / 64; ++k) {
+        ra += sm2[k];
+        rb += sm2[VEC_BLOCK / 64 + k];
+    }
+    __syncthreads();
+}
+
 __device__ __forceinline__ double sum_parts(const double *part, int n)
 {
     double v = 0.0;
@@ -40,7 +63,10 @@ __device__ __forceinline__ int64_t off_of(int64_t e, int K, int64_t ld)
 
 int vec_blocks(int64_t total)
 {
-    int64_t b = (total + VEC_BLOCK * 4 - 1) / (VEC_BLOCK * 4);
+    // small blocks: one element per thread (the kernels on them are chains of a few dependent round trips,
+    // not bandwidth); large ones: four per thread and a grid-stride loop beyond RED_MAX_PARTS blocks
+    const int per_thread = total <= (int64_t)VEC_BLOCK * 256 ? 1 : 4;
+    int64_t b = (total + VEC_BLOCK * per_thread - 1) / (VEC_BLOCK * per_thread);
     if (b > RED_MAX_PARTS) b = RED_MAX_PARTS;
     if (b < 1) b = 1;
     return (int)b;
@@ -48,11 +74,13 @@ int vec_blocks(int64_t total)
 
 // sum over chunks cl, cl + CLN, .. of element e of the per-chunk partials, eight loads in flight at a time,
 // added in chunk order
+// (skip, s0: the first `skip` of them are already added up in s0)
 template <typename T, int CLN>
-__device__ __forceinline__ double chunk_sum(const T *part, int nchunks, int64_t total, int64_t e, int cl)
+__device__ __forceinline__ double chunk_sum(const T *part, int nchunks, int64_t total, int64_t e, int cl, int skip = 0,
+                                            double s0 = 0.0)
 {
-    double s = 0.0;
-    for (int c = cl; c < nchunks; c += 8 * CLN) {
+    double s = s0;
+    for (int c = cl + skip * CLN; c < nchunks; c += 8 * CLN) {
         T v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -139,10 +167,40 @@ hipError_t launch_finalize(int dtype, const FinArgs &a, int blocks, hipStream_t 
 // is not stored.
 template <typename T, int EL> __global__ __launch_bounds__(VEC_BLOCK) void finalize_cg_kernel(FinArgs a, FinCgArgs g)
 {
+    // Loads first: the state slot, this thread's share of the z.u and s.s partials and the first batch of the
+    // block's chunk partials are all independent, so they go out together and the kernel waits once.
+    constexpr int CLN = VEC_BLOCK / EL;
+    const int el = threadIdx.x % EL, cl = threadIdx.x / EL;
+    const int64_t total = a.p * a.K;
+    const T *part = (const T *)a.part;
     const CgSlot c = *g.cur;
+    double vz = 0.0, vs = 0.0, tfirst = 0.0;     // tfirst: chunks cl, cl + CLN, .. (first eight) of the block's first group
+    {
+        double z4[4], s1;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = threadIdx.x + u * VEC_BLOCK;
+            z4[u] = g.zu_part[i < g.n_zu ? i : 0];
+        }
+        s1 = g.ss_part[(int)threadIdx.x < g.n_ss ? threadIdx.x : 0];
+        T first[8];
+        const int64_t ef = (int64_t)blockIdx.x * EL + el;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int cc = cl + u * CLN;
+            first[u] = part[(int64_t)(cc < a.nchunks ? cc : 0) * total + (ef < total ? ef : 0)];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) vz += (threadIdx.x + u * VEC_BLOCK < (unsigned)g.n_zu) ? z4[u] : 0.0;
+        for (int i = threadIdx.x + 4 * VEC_BLOCK; i < g.n_zu; i += VEC_BLOCK) vz += g.zu_part[i];
+        vs = ((int)threadIdx.x < g.n_ss) ? s1 : 0.0;
+        for (int i = threadIdx.x + VEC_BLOCK; i < g.n_ss; i += VEC_BLOCK) vs += g.ss_part[i];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) tfirst += (cl + u * CLN < a.nchunks) ? (double)first[u] : 0.0;
+    }
     if (c.done) return;
-    const double zu = sum_parts(g.zu_part, g.n_zu);
-    const double ss = sum_parts(g.ss_part, g.n_ss);
+    double zu, ss;
+    block_sum2(vz, vs, zu, ss);
     const double sHs = a.scale * zu + a.lambda * ss;
     if (!(sHs > 0.0)) {                      // not positive definite in floating point: stop, keep p_best
         if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -152,19 +210,18 @@ template <typename T, int EL> __global__ __launch_bounds__(VEC_BLOCK) void final
         return;
     }
     const double alpha = c.rr / sHs;
-    constexpr int CLN = VEC_BLOCK / EL;
     __shared__ double sm[VEC_BLOCK];
-    const int el = threadIdx.x % EL, cl = threadIdx.x / EL;
-    const int64_t total = a.p * a.K;
     const int64_t ngroups = (total + EL - 1) / EL;
-    const T *part = (const T *)a.part;
     const T *sv = (const T *)a.M;
     T *pv = (T *)g.pv, *r = (T *)g.r;
     double local = 0.0;
     for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
         const int64_t e = grp * EL + el;
         double t = 0.0;
-        if (e < total) t = chunk_sum<T, CLN>(part, a.nchunks, total, e, cl);
+        if (e < total) {
+            if (grp == blockIdx.x) t = chunk_sum<T, CLN>(part, a.nchunks, total, e, cl, 8, tfirst);
+            else t = chunk_sum<T, CLN>(part, a.nchunks, total, e, cl);
+        }
         sm[threadIdx.x] = t;
         __syncthreads();
         if (cl == 0 && e < total) {
@@ -433,6 +490,15 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgS
                                                               const double *rr_part, int n_rr, double theta,
                                                               double *trace_k, double *ss_part, bool update_p)
 {
+    // the first element of every thread is fetched before anything waits: on the small blocks of the dense
+    // workloads that is the only one, and the kernel is then two dependent round trips instead of three
+    const int64_t total = v.p * v.K;
+    const int64_t stride = (int64_t)gridDim.x * VEC_BLOCK;
+    const int64_t e0 = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x;
+    T *pw = (T *)v.pv, *s = (T *)v.s, *pb = (T *)v.pbest;
+    const T *r = (const T *)v.r;
+    const int64_t o0 = off_of(e0 < total ? e0 : 0, v.K, v.ld);
+    T p0 = pw[o0], r0 = r[o0], s0 = s[o0];
     const CgSlot c = *cur;
     if (c.done || c.brk) {
         if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -449,32 +515,23 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgS
     const bool better = rnorm <= c.rbest;
     const bool stop = rnorm <= theta * c.gnorm;
     const double b = rr_new / c.rr;
-    const int64_t total = v.p * v.K;
-    const T *pv = (const T *)v.pv, *r = (const T *)v.r;
-    T *s = (T *)v.s, *pb = (T *)v.pbest;
     double ss = 0.0;
-    if (update_p) {                          // line 8 was left to this pass: p += alpha s with the old s
-        T *pw = (T *)v.pv;
-        for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total;
-             e += (int64_t)gridDim.x * VEC_BLOCK) {
+    if (update_p || better || !stop) {
+        for (int64_t e = e0; e < total; e += stride) {
             const int64_t o = off_of(e, v.K, v.ld);
-            const T so = s[o];
-            const T pn = (T)((double)pw[o] + c.alpha * (double)so);
-            pw[o] = pn;
+            if (e != e0) {
+                p0 = pw[o];
+                r0 = r[o];
+                s0 = s[o];
+            }
+            T pn = p0;
+            if (update_p) {                  // line 8 was left to this pass: p += alpha s with the old s
+                pn = (T)((double)p0 + c.alpha * (double)s0);
+                pw[o] = pn;
+            }
             if (better) pb[o] = pn;
             if (!stop) {
-                const T sn = (T)((double)r[o] + b * (double)so);
-                s[o] = sn;
-                ss += (double)sn * (double)sn;
-            }
-        }
-    } else if (better || !stop) {
-        for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total;
-             e += (int64_t)gridDim.x * VEC_BLOCK) {
-            const int64_t o = off_of(e, v.K, v.ld);
-            if (better) pb[o] = pv[o];
-            if (!stop) {
-                const T sn = (T)((double)r[o] + b * (double)s[o]);
+                const T sn = (T)((double)r0 + b * (double)s0);
                 s[o] = sn;
                 ss += (double)sn * (double)sn;
             }
