@@ -214,3 +214,23 @@ class Problem:
                                   ctypes.c_int(T), ctypes.c_double(beta), ctypes.c_double(rho), ctypes.c_int(imax),
                                   _ptr(log))
         return W, log, int(done)
+
+
+def normalize_columns(X=None, csr=None, p=None):
+    """Sec. 4 preprocessing on a copy: returns (scaled X or scaled CSR values, column norms before scaling)."""
+    lib = _load()
+    if X is not None:
+        Xc = _f64(X).copy()
+        n, p = Xc.shape
+        norms = np.empty(p)
+        lib.orc_normalize_columns(ctypes.c_int64(n), ctypes.c_int64(p), _ptr(Xc), ctypes.c_int64(p), None, None, None,
+                                  _ptr(norms))
+        return Xc, norms
+    rowptr, colidx, vals = csr
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    vc = _f64(vals).copy()
+    norms = np.empty(int(p))
+    lib.orc_normalize_columns(ctypes.c_int64(rowptr.shape[0] - 1), ctypes.c_int64(int(p)), None, ctypes.c_int64(0),
+                              _ptr(rowptr), _ptr(colidx), _ptr(vc), _ptr(norms))
+    return vc, norms

@@ -19,6 +19,7 @@
  *   back-tracking line search ............ Alg. 3, eq. (3c)
  *   sub-sampled Newton iteration ......... Alg. 1, eq. (3a)
  *   classification rule .................. end of Sec. 3.3 (argmax over the C class probabilities)
+ *   unit-column-norm preprocessing ....... Sec. 4 (every column of the data matrix scaled to Euclidean norm one)
  *
  * Conventions (interface choices, stated here because the paper leaves them open):
  *   - n rows, p features, C classes, K = C-1.  Labels are 0-based in [0,C);
@@ -463,4 +464,34 @@ int orc_ssn_sg(const orc_problem *pr, double *W, int iters, const int32_t *Sg_al
     }
     free(dir); free(g);
     return k;
+}
+
+/*
+ * Preprocessing of Sec. 4: scale every column of the data matrix to Euclidean norm one, in place.
+ * Dense (X != NULL, n-by-p, leading dimension ldx) or CSR (rowptr / colidx / vals).  colnorm (p
+ * doubles) receives the norms BEFORE scaling; a column whose norm is zero is left as it is.
+ */
+void orc_normalize_columns(int64_t n, int64_t p, double *X, int64_t ldx, const int64_t *rowptr,
+                           const int32_t *colidx, double *vals, double *colnorm)
+{
+    long double *ss = (long double *)calloc((size_t)p, sizeof(long double));
+    if (X) {
+        for (int64_t i = 0; i < n; ++i)
+            for (int64_t j = 0; j < p; ++j)
+                ss[j] += (long double)X[i * ldx + j] * (long double)X[i * ldx + j];
+    } else {
+        for (int64_t t = rowptr[0]; t < rowptr[n]; ++t)
+            ss[colidx[t]] += (long double)vals[t] * (long double)vals[t];
+    }
+    for (int64_t j = 0; j < p; ++j)
+        colnorm[j] = (double)sqrtl(ss[j]);
+    if (X) {
+        for (int64_t i = 0; i < n; ++i)
+            for (int64_t j = 0; j < p; ++j)
+                if (colnorm[j] > 0.0) X[i * ldx + j] /= colnorm[j];
+    } else {
+        for (int64_t t = rowptr[0]; t < rowptr[n]; ++t)
+            if (colnorm[colidx[t]] > 0.0) vals[t] /= colnorm[colidx[t]];
+    }
+    free(ss);
 }
