@@ -122,6 +122,17 @@ typedef struct {
 const char *ssn_strerror(int status);
 const char *ssn_last_error(const ssn_ctx *ctx);
 
+/* Preprocessing of Sec. 4 ("each column of the data matrix has Euclidean norm one"), in place on the
+ * device, before ssn_create: dense X [dev] n-by-p with leading dimension ldx, or CSR rowptr / colidx /
+ * vals [dev] with nnz stored entries (the other layout's pointers are ignored).  colnorm [dev, p doubles]
+ * receives the column norms before scaling; a column of norm zero is left as it is.  Column indices of a
+ * CSR matrix must lie in [0,p) (not checked here; ssn_create checks them).  Sums in a fixed order.
+ * Allocates temporaries, synchronises the stream.  Returns SSN_OK, SSN_E_INVALID_ARG, SSN_E_ALLOC or
+ * SSN_E_HIP. */
+int ssn_normalize_columns(int32_t layout, int32_t dtype, int64_t n, int64_t p, void *X, int64_t ldx,
+                          const int32_t *rowptr, const int32_t *colidx, void *vals, int64_t nnz, double *colnorm,
+                          void *stream);
+
 /* Create a context for one data set.  Validates the description (C >= 2, n,p >= 1, lambda >= 0,
  * ldx >= p, ldw >= K, labels in range, CSR columns in range; one device pass over labels / CSR
  * indices) and allocates the workspace.  Synchronises the stream. */

@@ -22,7 +22,7 @@ SSN_E_ALLOC, SSN_E_HIP, SSN_E_NONFINITE, SSN_E_UNSUPPORTED = -5, -6, -7, -8
 EXPORTS = [
     "ssn_strerror", "ssn_last_error", "ssn_create", "ssn_destroy", "ssn_set_stream", "ssn_objective",
     "ssn_gradient", "ssn_gradient_sampled", "ssn_hess_prepare", "ssn_hess_apply", "ssn_hessvec", "ssn_cg", "ssn_linesearch",
-    "ssn_predict", "ssn_solve", "ssn_axpy", "ssn_time_kernel", "ssn_dense_path",
+    "ssn_predict", "ssn_solve", "ssn_axpy", "ssn_time_kernel", "ssn_dense_path", "ssn_normalize_columns",
 ]
 
 
@@ -96,12 +96,36 @@ def lib():
         L.ssn_axpy.argtypes = [vp, ctypes.c_double, vp, vp]
         L.ssn_time_kernel.argtypes = [vp, ctypes.c_int32, vp, ctypes.c_int32, dp]
         L.ssn_dense_path.argtypes = [vp]
+        L.ssn_normalize_columns.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_int64,
+                                            vp, vp, vp, ctypes.c_int64, vp, vp]
         for name in EXPORTS:
             fn = getattr(L, name)
             if fn.restype is not ctypes.c_char_p:
                 fn.restype = ctypes.c_int
         _lib = L
     return _lib
+
+
+def ssn_normalize_columns(X=None, csr=None, p=None):
+    """Unit-column-norm preprocessing of Sec. 4, in place on device tensors: X (n x p, row-major, float32 / float64)
+    or csr = (rowptr int32, colidx int32, vals).  Returns the column norms before scaling (float64, device)."""
+    if X is not None:
+        assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+        n, p = X.shape
+        norms = torch.empty(p, dtype=torch.float64, device=X.device)
+        dt = 0 if X.dtype == torch.float32 else 1
+        st = lib().ssn_normalize_columns(0, dt, n, p, _ptr(X), X.stride(0), None, None, None, 0, _ptr(norms), None)
+    else:
+        rowptr, colidx, vals = csr
+        assert rowptr.is_cuda and rowptr.dtype == torch.int32 and colidx.dtype == torch.int32
+        n = rowptr.shape[0] - 1
+        norms = torch.empty(int(p), dtype=torch.float64, device=vals.device)
+        dt = 0 if vals.dtype == torch.float32 else 1
+        st = lib().ssn_normalize_columns(1, dt, n, int(p), None, 0, _ptr(rowptr), _ptr(colidx), _ptr(vals), vals.shape[0],
+                                         _ptr(norms), None)
+    if st != 0:
+        raise SsnError(st, "ssn_normalize_columns")
+    return norms
 
 
 class SsnError(RuntimeError):

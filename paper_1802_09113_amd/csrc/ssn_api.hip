@@ -1,6 +1,6 @@
 // extern "C" entry points of libssn_hip.so (declared in include/ssn.h): argument checking, workspace
 // ownership, kernel sequencing, and the host-side control flow of Alg. 1 and Alg. 3.  Every arithmetic
-// step runs in the kernels of dense_mfma.hip / csr.hip / vecops.hip.
+// step runs in the kernels of dense_mfma.hip / csr.hip / csc.hip / vecops.hip / preprocess.hip.
 #include "ssn_internal.h"
 
 #include <chrono>
@@ -457,6 +457,24 @@ const char *ssn_strerror(int status)
 }
 
 const char *ssn_last_error(const ssn_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int ssn_normalize_columns(int32_t layout, int32_t dtype, int64_t n, int64_t p, void *X, int64_t ldx, const int32_t *rowptr,
+                          const int32_t *colidx, void *vals, int64_t nnz, double *colnorm, void *stream)
+{
+    if (n < 1 || p < 1 || !colnorm || (dtype != SSN_F32 && dtype != SSN_F64)) return SSN_E_INVALID_ARG;
+    if (n >= (int64_t)1 << 31 || p >= (int64_t)1 << 31) return SSN_E_UNSUPPORTED;
+    if (layout == SSN_DENSE_ROWMAJOR) {
+        if (!X || ldx < p) return SSN_E_INVALID_ARG;
+    } else if (layout == SSN_CSR) {
+        if (!rowptr || nnz < 0 || (nnz > 0 && (!colidx || !vals))) return SSN_E_INVALID_ARG;
+        if (nnz >= (int64_t)1 << 31) return SSN_E_UNSUPPORTED;
+    } else {
+        return SSN_E_INVALID_ARG;
+    }
+    const hipError_t e = normalize_columns(layout, dtype, n, p, X, ldx, rowptr, colidx, vals, nnz, colnorm, (hipStream_t)stream);
+    if (e == hipSuccess) return SSN_OK;
+    return e == hipErrorOutOfMemory ? SSN_E_ALLOC : SSN_E_HIP;
+}
 
 int ssn_destroy(ssn_ctx *c)
 {

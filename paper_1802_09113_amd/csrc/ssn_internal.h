@@ -155,6 +155,10 @@ void csc_free_scratch(CscView *v);
 hipError_t launch_csc_apply(int dtype, const CscView &v, int K, int KP, const void *U, double coef, void *out, int64_t ldo,
                             const CgSlot *slot, const int32_t *skip, hipStream_t st);
 
+// ---- unit-column-norm preprocessing (preprocess.hip); synchronises the stream ------------------------
+hipError_t normalize_columns(int layout, int dtype, int64_t n, int64_t p, void *X, int64_t ldx, const int32_t *rowptr,
+                             const int32_t *colidx, void *vals, int64_t nnz, double *colnorm, hipStream_t st);
+
 // ---- device-resident CG (Alg. 2) ---------------------------------------------------------
 struct CgSlot {          // state before product k
     double rr;           // r_k^T r_k
