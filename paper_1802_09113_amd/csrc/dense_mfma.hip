@@ -214,11 +214,6 @@ template <typename T, int NB, int MODE>
 __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[NB], const RowsArgs &a,
                                              int64_t rb, int lane, double &loss, double &lprod, int &hits)
 {
-    constexpr bool primary = true;
-    constexpr bool TOREG = false;
-    typename V4<T>::type *uout = nullptr;
-    const int *lab_pre = nullptr;
-    const T *pin_pre = nullptr;
     const int q = lane & 15, g = lane >> 4;
     const int K = a.K;
     const T NEG = -std::numeric_limits<T>::infinity();
@@ -245,16 +240,14 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
         }
         zmax = row16_max(zmax);
         if constexpr (MODE == ROW_PRED) {
-            int lab;
-            if (lab_pre) lab = lab_pre[v];
-            else lab = a.labels[a.S ? a.S[svc] : svc];
+            const int lab = a.labels[a.S ? a.S[svc] : svc];
             int cand = 0x7fffffff;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
                 if (cv[nb] && z[nb] == zmax) cand = min(cand, nb * 16 + q);
             cand = row16_min(cand);
             const int pr = (T(0) > zmax) ? K : cand;     // the reference class wins only strictly
-            if (primary && valid && q == 0) {
+            if (valid && q == 0) {
                 if (a.pred) a.pred[sv] = pr;
                 hits += (pr == lab);
             }
@@ -267,7 +260,7 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
             T t = 0;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                pin[nb] = pin_pre ? pin_pre[v] : Pin[svc * a.KP + nb * 16 + q];      // zero in padded columns
+                pin[nb] = Pin[svc * a.KP + nb * 16 + q];      // zero in padded columns
                 t += pin[nb] * z[nb];
             }
             t = row16_sum(t);
@@ -277,8 +270,7 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
             for (int nb = 0; nb < NB; ++nb) {
                 const T u = valid ? (pin[nb] * z[nb] - pin[nb] * t) : T(0);
                 zu += z[nb] * u;
-                if constexpr (TOREG) uout[nb][v] = u;
-                else U[sv * a.KP + nb * 16 + q] = u;
+                U[sv * a.KP + nb * 16 + q] = u;
             }
             // z_i . u_i of the row: summed over the sample it is V^T (X_S^T U), the curvature term CG needs
             zu = row16_sum(zu);
@@ -300,27 +292,24 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
             T *P = (T *)a.UP;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
-                if (primary) P[sv * a.KP + nb * 16 + q] = valid ? e[nb] / alpha : T(0);
+                P[sv * a.KP + nb * 16 + q] = valid ? e[nb] / alpha : T(0);
             continue;
         }
         // ROW_OBJ / ROW_GRAD: eqs. (14)-(17)
-        int lab;
-        if (lab_pre) lab = lab_pre[v];
-        else lab = a.labels[a.S ? a.S[svc] : svc];
+        const int lab = a.labels[a.S ? a.S[svc] : svc];
         T lin = 0;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
             lin += (cv[nb] && (nb * 16 + q) == lab) ? z[nb] : T(0);
         lin = row16_sum(lin);
-        if (primary && valid && q == 0) loss += (double)Mx + (double)t_log(alpha) - (double)lin;
+        if (valid && q == 0) loss += (double)Mx + (double)t_log(alpha) - (double)lin;
         if constexpr (MODE == ROW_GRAD) {
             T *U = (T *)a.UP;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const T ind = ((nb * 16 + q) == lab) ? T(1) : T(0);
                 const T u = (valid && cv[nb]) ? (e[nb] / alpha - ind) : T(0);
-                if constexpr (TOREG) uout[nb][v] = u;
-                else U[sv * a.KP + nb * 16 + q] = u;
+                U[sv * a.KP + nb * 16 + q] = u;
             }
         }
     }
