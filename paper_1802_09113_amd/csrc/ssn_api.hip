@@ -695,6 +695,8 @@ static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *
         SSN_HIP(c, launch_cg_step2(c->d.dtype, v, c->slots + k, c->slots + k + 1, c->red_a, n_rr, theta,
                                    c->trace_dev + 3 * k, c->red_c, p_pending, vb, c->st));
     }
+    // CSR path: the best iterate may still live only in p (it is copied lazily)
+    if (!is_dense(c) && T > 0) SSN_HIP(c, launch_cg_finish(c->d.dtype, v, c->slots + T, vb, c->st));
     return SSN_OK;
 }
 

@@ -169,6 +169,8 @@ struct CgSlot {          // state before product k
     int32_t flags;
     int32_t brk;         // set during product k when s^T H s <= 0
     double alpha;        // step length of product k, where a kernel of its own computes it (CSR path)
+    int32_t best_cur;    // CSR path: the best iterate is the CURRENT p and has not been copied to p_best yet
+    int32_t pad;
 };
 
 struct CgVecs {
@@ -182,13 +184,16 @@ struct CgVecs {
 // ss_part (nullable) receives the same partials again: s_0 = -g
 hipError_t launch_cg_init(int dtype, const CgVecs &v, double *gg_part, double *ss_part, int blocks, hipStream_t st);
 hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0, hipStream_t st);
-// ss_part (nullable): one partial of s.s per block for the new direction; update_p: also p += cur->alpha * s
+// ss_part (nullable): one partial of s.s per block for the new direction; update_p: also p += cur->alpha * s,
+// and p_best is then kept lazily (CgSlot::best_cur): launch_cg_finish after the last product completes it
 hipError_t launch_cg_step2(int dtype, const CgVecs &v, const CgSlot *cur, CgSlot *next, const double *rr_part,
                            int n_rr, double theta, double *trace_k, double *ss_part, bool update_p, int blocks,
                            hipStream_t st);
 // CSR path, lines 7-9 in pieces: cur->alpha from the partials of sum_i z_i . u_i and of s.s (one block); then the
 // sparse part of r -= alpha H s goes through launch_csr_scatter and the dense part, r -= alpha lambda s with the
 // partials of the new r.r, through launch_cg_r_update
+// p_best = p where the final state says the best iterate is still only in p
+hipError_t launch_cg_finish(int dtype, const CgVecs &v, const CgSlot *fin, int blocks, hipStream_t st);
 hipError_t launch_cg_alpha(CgSlot *cur, const double *zu_part, int n_zu, const double *ss_part, int n_ss, double scale,
                            double lambda, double *trace_k, hipStream_t st);
 hipError_t launch_cg_r_update(int dtype, const CgVecs &v, const CgSlot *cur, double lambda, double *rr_part, int blocks,

@@ -474,6 +474,8 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_init_state_kernel(const double *
         s.flags = 0;
         s.brk = 0;
         s.alpha = 0.0;
+        s.best_cur = 0;
+        s.pad = 0;
         *slot0 = s;
     }
 }
@@ -516,25 +518,42 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgS
     const bool stop = rnorm <= theta * c.gnorm;
     const double b = rr_new / c.rr;
     double ss = 0.0;
+    // one element: lines 8 (where it was left to this pass), 10 and 12
+    auto element = [&](int64_t o, T pe, T re, T se) {
+        T pn = pe;
+        if (update_p) {                      // p += alpha s with the old s
+            pn = (T)((double)pe + c.alpha * (double)se);
+            pw[o] = pn;
+            // lazy best-iterate memory: a better iterate is only marked; the copy happens when the next
+            // iterate is worse (then the best one is the p this pass has just read) or at the very end
+            if (!better && c.best_cur) pb[o] = pe;
+        } else if (better) {
+            pb[o] = pn;
+        }
+        if (!stop) {
+            const T sn = (T)((double)re + b * (double)se);
+            s[o] = sn;
+            ss += (double)sn * (double)sn;
+        }
+    };
     if (update_p || better || !stop) {
-        for (int64_t e = e0; e < total; e += stride) {
-            const int64_t o = off_of(e, v.K, v.ld);
-            if (e != e0) {
-                p0 = pw[o];
-                r0 = r[o];
-                s0 = s[o];
+        if (e0 < total) element(o0, p0, r0, s0);
+        // the rest of a large block: four elements per thread in flight at a time
+        constexpr int SB = 4;
+        for (int64_t e = e0 + stride; e < total; e += SB * stride) {
+            int64_t o[SB];
+            T pe[SB], re[SB], se[SB];
+#pragma unroll
+            for (int u = 0; u < SB; ++u) {
+                const int64_t eu = e + u * stride;
+                o[u] = off_of(eu < total ? eu : e, v.K, v.ld);
+                pe[u] = pw[o[u]];
+                re[u] = r[o[u]];
+                se[u] = s[o[u]];
             }
-            T pn = p0;
-            if (update_p) {                  // line 8 was left to this pass: p += alpha s with the old s
-                pn = (T)((double)p0 + c.alpha * (double)s0);
-                pw[o] = pn;
-            }
-            if (better) pb[o] = pn;
-            if (!stop) {
-                const T sn = (T)((double)r0 + b * (double)s0);
-                s[o] = sn;
-                ss += (double)sn * (double)sn;
-            }
+#pragma unroll
+            for (int u = 0; u < SB; ++u)
+                if (e + u * stride < total) element(o[u], pe[u], re[u], se[u]);
         }
     }
     if (ss_part) {                           // partials of s.s for the next product's curvature
@@ -551,6 +570,8 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgS
         n.flags = c.flags | (stop ? 1 : 0);
         n.brk = 0;
         n.alpha = 0.0;
+        n.best_cur = update_p ? (better ? 1 : 0) : 0;
+        n.pad = 0;
         *next = n;
         if (trace_k) trace_k[1] = rnorm;
     }
@@ -565,6 +586,25 @@ hipError_t launch_cg_step2(int dtype, const CgVecs &v, const CgSlot *cur, CgSlot
     else
         hipLaunchKernelGGL(cg_step2_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, cur, next, rr_part, n_rr,
                            theta, trace_k, ss_part, update_p);
+    return hipGetLastError();
+}
+
+template <typename T> __global__ __launch_bounds__(VEC_BLOCK) void cg_finish_kernel(CgVecs v, const CgSlot *fin)
+{
+    if (!fin->best_cur) return;
+    const int64_t total = v.p * v.K;
+    const T *pw = (const T *)v.pv;
+    T *pb = (T *)v.pbest;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int64_t o = off_of(e, v.K, v.ld);
+        pb[o] = pw[o];
+    }
+}
+
+hipError_t launch_cg_finish(int dtype, const CgVecs &v, const CgSlot *fin, int blocks, hipStream_t st)
+{
+    if (dtype == SSN_F32) hipLaunchKernelGGL(cg_finish_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, fin);
+    else hipLaunchKernelGGL(cg_finish_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, fin);
     return hipGetLastError();
 }
 
