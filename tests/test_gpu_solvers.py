@@ -95,6 +95,30 @@ def test_full_newton_with_a_long_cg(n, p, C, lam, theta, T):
     pair.close()
 
 
+def test_csr_cg_best_iterate_when_the_residual_goes_up_and_down():
+    # on this sample the residual norm of Alg. 2 rises every other product, so the best-iterate memory
+    # (kept lazily on the CSR path) is exercised in both directions, including a best iterate that is not
+    # the last one
+    d = workload(4, 403)
+    pair = Pair(d, F64)
+    Wh, Wd = pair.block(synth.probe(pair.p, pair.K, sub=1, scale=0.1))
+    S = synth.sample_rows(403, 100)
+    G_ref, _ = pair.oracle.gradient(Wh)
+    Gh, Gd = pair.block(G_ref)
+    pair.gpu.ssn_hess_prepare(Wd, pair.idx(S))
+    for T in (30, 11, 4):
+        print(f"[case] csr cg lazy best iterate T={T}", flush=True)
+        ref = pair.oracle.cg(Wh, S, Gh, 1e-30, T)
+        assert np.any(np.diff(ref["rnorm"]) > 0)
+        out = pair.gpu.ssn_cg(Gd, 1e-30, T)
+        torch.cuda.synchronize()
+        assert out["iters"] == ref["iters"] == T
+        np.testing.assert_allclose(out["rnorm"], ref["rnorm"], rtol=1e-7)
+        assert rel_scalar(out["rel_res"], ref["rel_res"]) <= 1e-7
+        assert rel_err(pair.host(out["p"]), ref["p"]) <= 1e-7
+    pair.close()
+
+
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 def test_cg_zero_budget_and_zero_gradient(tiny, dtype):
     pair = Pair(tiny, dtype)
