@@ -190,6 +190,10 @@ class Context:
         if st != SSN_OK:
             raise SsnError(st, lib().ssn_last_error(self._h).decode())
 
+    def ssn_set_stream(self, stream):
+        """stream: a hipStream_t handle as an integer (e.g. torch.cuda.Stream().cuda_stream), or None for the default."""
+        self._check(lib().ssn_set_stream(self._h, ctypes.c_void_p(stream) if stream else None))
+
     def new_block(self):
         """An uninitialised p x ldw block of the context's dtype."""
         return torch.empty((self.p, self.ldw), dtype=self.tdtype, device=self.device)

@@ -207,6 +207,38 @@ def test_ssn_with_sub_sampled_gradient(tiny, dtype):
     pair.close()
 
 
+def test_work_follows_the_stream_it_is_given(tiny):
+    # a context created on a side stream (default priority) and one moved there with ssn_set_stream: the
+    # library's launches are ordered with other work on that stream, not with the default stream
+    d = tiny
+    side = torch.cuda.Stream()
+    X = torch.from_numpy(d["X"]).cuda()
+    labels = torch.from_numpy(d["labels"]).cuda()
+    pair = Pair(d, F64)                                              # oracle side (its GPU context is not used)
+    Wh = synth.probe(pair.p, pair.K, sub=1, scale=0.2)
+    S = synth.sample_rows(2000, 100)
+    Sd = torch.from_numpy(S).cuda()
+    G_ref, f_ref = pair.oracle.gradient(Wh)
+    HV_ref = pair.oracle.hessvec(Wh, S, Wh)
+    torch.cuda.synchronize()
+    ctx_a = Context(labels, d["C"], d["lam"], X=X, stream=side.cuda_stream)
+    ctx_b = Context(labels, d["C"], d["lam"], X=X)
+    ctx_b.ssn_set_stream(side.cuda_stream)
+    for ctx in (ctx_a, ctx_b):
+        with torch.cuda.stream(side):
+            W = torch.zeros((pair.p, pair.K), dtype=F64, device="cuda")
+            W.copy_(torch.from_numpy(Wh).cuda(), non_blocking=True)  # produced on the side stream ...
+            G, f = ctx.ssn_gradient(W)                               # ... and consumed there by the library
+            HV = ctx.ssn_hessvec(W, Sd, W)
+            out = HV * 2.0                                           # torch work queued behind the library's
+        side.synchronize()
+        assert rel_scalar(f, f_ref) <= 1e-10
+        assert rel_err(G.cpu().numpy(), G_ref) <= 1e-10
+        assert rel_err(out.cpu().numpy(), 2.0 * HV_ref) <= 1e-10
+        ctx.close()
+    pair.close()
+
+
 def test_error_paths(tiny):
     d = tiny
     dev = "cuda"
