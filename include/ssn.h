@@ -166,7 +166,9 @@ int ssn_hess_prepare(ssn_ctx *ctx, const void *W, const int32_t *S, int64_t nS);
 
 /* Hessian-vector product, eqs. (10)-(13) / Alg. 7, 8 on the prepared sample:
  *   HV = s_S * X_S^T U + lambda V,  U_i = (diag(p_i) - p_i p_i^T)(V^T x_i).
- * V [dev] in, HV [dev] out (must not alias V). */
+ * V [dev] in, HV [dev] out (must not alias V).  Enqueues kernels only: no allocation, no wait for the
+ * device, so the call may be recorded into a HIP graph on the context's stream (so may ssn_gradient with
+ * f == NULL on a dense matrix, and ssn_axpy). */
 int ssn_hess_apply(ssn_ctx *ctx, const void *V, void *HV);
 
 /* ssn_hess_prepare followed by ssn_hess_apply. */
