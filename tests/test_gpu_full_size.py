@@ -54,12 +54,12 @@ def test_image_like_full():
 
 
 def test_tall_narrow_full():
-    _check(3, [F64])
+    _check(3, [F64, F32])
 
 
 def test_wide_full():
-    _check(2, [F32])
+    _check(2, [F32, F64])
 
 
 def test_sparse_full():
-    _check(4, [F64])
+    _check(4, [F64, F32])
