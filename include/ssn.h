@@ -178,7 +178,8 @@ int ssn_hessvec(ssn_ctx *ctx, const void *W, const int32_t *S, int64_t nS, const
  * G [dev] right-hand side gradient; P_out [dev] receives p_best; at most T products.
  * trace [host, nullable, 3*T doubles]: per product k the step alpha_k, ||r_{k+1}||, s_k^T H s_k.
  * The whole loop runs on the device without host round trips; the call synchronises once at
- * the end to fill info / trace. */
+ * the end to fill info / trace.  The curvature s^T H s is formed as s_S * sum_i z_i . u_i + lambda s.s
+ * (Z = X_S s, U of eq. (12)), the same number as s^T (H s) up to rounding, and H s itself is not stored. */
 int ssn_cg(ssn_ctx *ctx, const void *G, double theta, int32_t T, void *P_out,
            ssn_cg_info *info, double *trace);
 
