@@ -44,6 +44,8 @@ struct ssn_ctx {
     double *scal_dev = nullptr;
     int32_t *int_dev = nullptr;
     double *host_pin = nullptr;   // pinned staging for scalar results
+    double *f_host = nullptr;     // host-visible word kernels write objective values to (inside host_pin's allocation)
+    double *f_host_dev = nullptr; // its device address
     // prepared Hessian sample
     const int32_t *S = nullptr;
     int64_t nS = 0;
@@ -286,13 +288,35 @@ int read_int(ssn_ctx *c, const int32_t *dev, int32_t *host_out)
 }
 
 // enqueue f(W) into scal_dev[slot]; loss partials must already be in loss_part[0..nparts)
-int enqueue_objective_value(ssn_ctx *c, const void *W, int nparts, int slot, double scale = -1.0)
+// f(W) into scal_dev[slot] from the loss partials the rows kernel left.  *mirrored (nullable) tells whether the
+// value also lands in the host-visible word c->f_host (small blocks: one launch does everything).
+int enqueue_objective_value(ssn_ctx *c, const void *W, int nparts, int slot, double scale = -1.0, bool *mirrored = nullptr)
 {
-    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
     if (scale < 0.0) scale = scale_full(c);
+    if (mirrored) *mirrored = false;
+    if (c->d.p * (int64_t)c->K <= OBJ_VALUE_ELEMS) {
+        SSN_HIP(c, launch_objective_value(c->d.dtype, c->loss_part, nparts, scale, W, c->d.p, c->K, c->d.ldw,
+                                          0.5 * c->d.lambda, c->scal_dev + slot, c->f_host_dev, c->st));
+        if (mirrored) *mirrored = c->f_host_dev != nullptr;
+        return SSN_OK;
+    }
+    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
     SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, W, c->d.ldw, W, c->d.ldw, c->red_a, vb, nullptr, c->st));
     SSN_HIP(c, launch_combine(c->loss_part, nparts, scale, c->red_a, vb, 0.5 * c->d.lambda, c->scal_dev + slot,
                               c->st));
+    return SSN_OK;
+}
+
+// wait for f(W) enqueued by enqueue_objective_value into scal_dev[0]
+int read_objective(ssn_ctx *c, bool mirrored, double *f)
+{
+    if (mirrored) {
+        SSN_HIP(c, hipStreamSynchronize(c->st));
+        *f = *(volatile double *)c->f_host;
+    } else {
+        SSN_TRY(read_scalar(c, c->scal_dev, f));
+    }
+    if (!std::isfinite(*f)) return fail(c, SSN_E_NONFINITE, "objective is not finite");
     return SSN_OK;
 }
 
@@ -303,11 +327,10 @@ int objective_impl(ssn_ctx *c, const void *W, double *f)
     a.M = W;
     a.mode = ROW_OBJ;
     int nparts = 0;
+    bool mirrored = false;
     SSN_TRY(launch_rows(c, a, &nparts));
-    SSN_TRY(enqueue_objective_value(c, W, nparts, 0));
-    SSN_TRY(read_scalar(c, c->scal_dev, f));
-    if (!std::isfinite(*f)) return fail(c, SSN_E_NONFINITE, "objective is not finite");
-    return SSN_OK;
+    SSN_TRY(enqueue_objective_value(c, W, nparts, 0, -1.0, &mirrored));
+    return read_objective(c, mirrored, f);
 }
 
 // defer_f: leave f(W) in scal_dev[0] without reading it back (the caller synchronises later).
@@ -337,11 +360,9 @@ int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f, bool defer_f = 
         }
         SSN_TRY(transposed_product(c, S, nrows, scale, W, G, false, nullptr, nullptr, view));
     }
-    if (f || defer_f) SSN_TRY(enqueue_objective_value(c, W, nparts, 0, scale));
-    if (f && !defer_f) {
-        SSN_TRY(read_scalar(c, c->scal_dev, f));
-        if (!std::isfinite(*f)) return fail(c, SSN_E_NONFINITE, "objective is not finite");
-    }
+    bool mirrored = false;
+    if (f || defer_f) SSN_TRY(enqueue_objective_value(c, W, nparts, 0, scale, &mirrored));
+    if (f && !defer_f) SSN_TRY(read_objective(c, mirrored, f));
     return SSN_OK;
 }
 
@@ -544,6 +565,12 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
     CREATE_HIP(hipMalloc((void **)&c->scal_dev, sizeof(double) * 8));
     CREATE_HIP(hipMalloc((void **)&c->int_dev, sizeof(int32_t) * 8));
     CREATE_HIP(hipHostMalloc((void **)&c->host_pin, 4096));
+    c->f_host = c->host_pin + 256;                                   // bytes 2048.. of the pinned page
+    *c->f_host = 0.0;
+    {
+        void *dp = nullptr;
+        if (hipHostGetDevicePointer(&dp, c->f_host, 0) == hipSuccess) c->f_host_dev = (double *)dp;
+    }
     if (d->layout == SSN_DENSE_ROWMAJOR) {
         const int64_t nft = (d->p + 63) / 64;
         c->max_chunks = (int)(((int64_t)c->num_cus * xtu_waves_per_cu(d->p) + nft - 1) / nft);

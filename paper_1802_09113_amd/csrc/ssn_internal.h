@@ -116,6 +116,11 @@ hipError_t launch_dot_part(int dtype, int64_t p, int K, const void *A, int64_t l
 hipError_t launch_axpy(int dtype, int64_t p, int K, double alpha, const void *X, int64_t ldx_,
                        const void *Z, int64_t ldz, void *Y, int64_t ldy, hipStream_t st);
 // *out = scale * sum(a[0..na)) + coef * sum(b[0..nb))   (single block, fixed order)
+// *out (and *out_host, nullable, host-visible) = scale * sum(loss_part) + half_lambda * ||W||_F^2 ; one block, for
+// blocks of up to OBJ_VALUE_ELEMS elements
+hipError_t launch_objective_value(int dtype, const double *loss_part, int nparts, double scale, const void *W, int64_t p,
+                                  int K, int64_t ldw, double half_lambda, double *out, double *out_host, hipStream_t st);
+constexpr int64_t OBJ_VALUE_ELEMS = 32768;
 hipError_t launch_combine(const double *a, int na, double scale, const double *b, int nb, double coef,
                           double *out, hipStream_t st);
 // streaming read of `bytes` (multiple of 16, 16-byte aligned); one checksum partial per block

@@ -338,6 +338,50 @@ __global__ __launch_bounds__(VEC_BLOCK) void combine_kernel(const double *a, int
     if (threadIdx.x == 0) *out = scale * sa + coef * sb;
 }
 
+// f = scale * sum(loss partials) + half_lambda * ||W||^2 in ONE launch for small blocks: the single block adds
+// up the squares of W itself (eight elements per thread in flight), and mirrors the value into host-visible
+// memory (nullable) so that the caller only has to wait for the stream, not for a copy
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void objective_value_kernel(const double *loss_part, int nparts, double scale,
+                                                                     const T *W, int64_t p, int K, int64_t ldw,
+                                                                     double half_lambda, double *out, double *out_host)
+{
+    const int64_t total = p * K;
+    double sq = 0.0;
+    for (int64_t e0 = threadIdx.x; e0 < total; e0 += 8 * VEC_BLOCK) {
+        T w[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t e = e0 + (int64_t)u * VEC_BLOCK;
+            w[u] = W[off_of(e < total ? e : e0, K, ldw)];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (e0 + (int64_t)u * VEC_BLOCK < total) sq += (double)w[u] * (double)w[u];
+    }
+    double loss = 0.0;
+    for (int i = threadIdx.x; i < nparts; i += VEC_BLOCK) loss += loss_part[i];
+    double sl, ss;
+    block_sum2(loss, sq, sl, ss);
+    if (threadIdx.x == 0) {
+        const double f = scale * sl + half_lambda * ss;
+        *out = f;
+        if (out_host) *out_host = f;
+    }
+}
+
+hipError_t launch_objective_value(int dtype, const double *loss_part, int nparts, double scale, const void *W, int64_t p,
+                                  int K, int64_t ldw, double half_lambda, double *out, double *out_host, hipStream_t st)
+{
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(objective_value_kernel<float>, dim3(1), dim3(VEC_BLOCK), 0, st, loss_part, nparts, scale,
+                           (const float *)W, p, K, ldw, half_lambda, out, out_host);
+    else
+        hipLaunchKernelGGL(objective_value_kernel<double>, dim3(1), dim3(VEC_BLOCK), 0, st, loss_part, nparts, scale,
+                           (const double *)W, p, K, ldw, half_lambda, out, out_host);
+    return hipGetLastError();
+}
+
 hipError_t launch_combine(const double *a, int na, double scale, const double *b, int nb, double coef, double *out,
                           hipStream_t st)
 {
