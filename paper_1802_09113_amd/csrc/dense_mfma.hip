@@ -1107,17 +1107,18 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
 // Register footprints the one-pass kernel is compiled for.  NLD vector loads and NSB transposition
 // sub-blocks bound the features a wave can own; MAXW waves per workgroup fix the register budget
 // (512 / ceil(MAXW/4) per lane).  Shapes are tried in this order.
-struct FusedShape { int nld, nsb, maxw; };
+struct FusedShape { int nld, nsb, maxw, flags; };
+constexpr int SHAPE_NO_C_MULTI = 1;       // multi-wave use only without a transposed product (it would spill)
+constexpr int SHAPE_SINGLE_WAVE = 2;      // single-wave workgroups only (a footprint for narrow matrices)
 template <typename T> struct FusedTable;
 template <> struct FusedTable<double> {
-    static constexpr int N = 3;
-    static constexpr int FIRST_C = 1;     // with a transposed product the 12-wave footprint spills: start at the 8-wave one
-    static constexpr FusedShape shape[N] = {{9, 3, 12}, {13, 4, 8}, {16, 4, 8}};     // 72 / 104 / 128 features per wave
+    static constexpr int N = 4;
+    // 56 / 72 / 104 / 128 features per wave; ordered by footprint, the first shape that fits serves
+    static constexpr FusedShape shape[N] = {{7, 2, 8, SHAPE_SINGLE_WAVE}, {9, 3, 12, SHAPE_NO_C_MULTI}, {13, 4, 8, 0}, {16, 4, 8, 0}};
 };
 template <> struct FusedTable<float> {
     static constexpr int N = 3;
-    static constexpr int FIRST_C = 0;
-    static constexpr FusedShape shape[N] = {{4, 1, 8}, {7, 2, 8}, {8, 2, 8}};        // 64 / 112 / 128 features per wave
+    static constexpr FusedShape shape[N] = {{4, 1, 8, 0}, {7, 2, 8, 0}, {8, 2, 8, 0}};        // 64 / 112 / 128 features per wave
 };
 constexpr FusedShape FusedTable<double>::shape[];
 constexpr FusedShape FusedTable<float>::shape[];
@@ -1128,13 +1129,14 @@ template <typename T> static int fused_shape(int64_t p, bool has_c, int *nw, int
 {
     constexpr int VEC = 16 / sizeof(T);
     constexpr int LF = 4 * VEC, SBF = 16 * VEC;
-    // single-wave shapes (p <= 128) have registers to spare with any footprint
-    for (int i = (has_c && p > 128) ? FusedTable<T>::FIRST_C : 0; i < FusedTable<T>::N; ++i) {
+    for (int i = 0; i < FusedTable<T>::N; ++i) {
         const FusedShape sh = FusedTable<T>::shape[i];
         const int cap = (sh.nld * LF < sh.nsb * SBF) ? sh.nld * LF : sh.nsb * SBF;
         int64_t n = (p + cap - 1) / cap;
         if (n > 1) n = (n + 3) / 4 * 4;              // same number of waves on each of the 4 SIMDs
         if (n > sh.maxw) continue;
+        if (n > 1 && (sh.flags & SHAPE_SINGLE_WAVE)) continue;
+        if (n > 1 && has_c && (sh.flags & SHAPE_NO_C_MULTI)) continue;
         int f = (int)((p + n - 1) / n);
         f = (f + VEC - 1) / VEC * VEC;
         if (f > cap) continue;
@@ -1236,14 +1238,24 @@ template <typename T, int MODE> static hipError_t fused_launch_mode(RowsArgs a, 
     if (i < 0) return hipErrorInvalidValue;
     a.fw = fw;
     const size_t lds = fused_lds_bytes<T>(nw, fw, TB::shape[i].nld, TB::shape[i].maxw, a.K, has_c);
+#define SSN_FUSED_SHAPE(I, W) fused_launch_inst<T, MODE, TB::shape[I].nld, TB::shape[I].nsb, W>(a, grid, nw, lds, st)
     if (nw == 1) {      // single-wave workgroups: no cross-wave reduction compiled in
-        if (i == 0) return fused_launch_inst<T, MODE, TB::shape[0].nld, TB::shape[0].nsb, 1>(a, grid, nw, lds, st);
-        if (i == 1) return fused_launch_inst<T, MODE, TB::shape[1].nld, TB::shape[1].nsb, 1>(a, grid, nw, lds, st);
-        return fused_launch_inst<T, MODE, TB::shape[2].nld, TB::shape[2].nsb, 1>(a, grid, nw, lds, st);
+        if (i == 0) return SSN_FUSED_SHAPE(0, 1);
+        if (i == 1) return SSN_FUSED_SHAPE(1, 1);
+        if (i == 2) return SSN_FUSED_SHAPE(2, 1);
+        if constexpr (TB::N > 3) return SSN_FUSED_SHAPE(TB::N - 1, 1);
+        return hipErrorInvalidValue;
     }
-    if (i == 0) return fused_launch_inst<T, MODE, TB::shape[0].nld, TB::shape[0].nsb, TB::shape[0].maxw>(a, grid, nw, lds, st);
-    if (i == 1) return fused_launch_inst<T, MODE, TB::shape[1].nld, TB::shape[1].nsb, TB::shape[1].maxw>(a, grid, nw, lds, st);
-    return fused_launch_inst<T, MODE, TB::shape[2].nld, TB::shape[2].nsb, TB::shape[2].maxw>(a, grid, nw, lds, st);
+    if constexpr (!(TB::shape[0].flags & SHAPE_SINGLE_WAVE)) {
+        if (i == 0) return SSN_FUSED_SHAPE(0, TB::shape[0].maxw);
+    }
+    if (i == 1) return SSN_FUSED_SHAPE(1, TB::shape[1].maxw);
+    if (i == 2) return SSN_FUSED_SHAPE(2, TB::shape[2].maxw);
+    if constexpr (TB::N > 3) {
+        if (i == 3) return SSN_FUSED_SHAPE(TB::N - 1, TB::shape[TB::N - 1].maxw);
+    }
+    return hipErrorInvalidValue;
+#undef SSN_FUSED_SHAPE
 }
 
 template <typename T> static hipError_t fused_dispatch(const RowsArgs &a, int grid, hipStream_t st)
