@@ -86,13 +86,23 @@ typedef struct {
     double gnorm;             /* ||g||                                                           */
 } ssn_cg_info;
 
+/* ssn_params.flags.  By default ssn_solve evaluates the first line-search trial (alpha = 1) with the
+ * gradient pass, which returns F and grad F from one read of the data; when that trial is accepted -- the
+ * usual case for a Newton-type step -- the trial point is the next iterate and its gradient is already
+ * there, so the iteration costs one pass over the data less.  The iterates, F values and step lengths are
+ * those of Alg. 1 and Alg. 3 either way (the two passes add the same row terms in a different order, so F
+ * may differ in the last bits); only the phase times move: the gradient's time is then reported inside
+ * ms_linesearch of the previous iteration.  After a rejected first trial the plain objective pass is used
+ * until a first trial is accepted again.  Not used with a sub-sampled gradient.  This flag turns it off. */
+#define SSN_SOLVE_NO_LOOKAHEAD 1
+
 /* Parameters of ssn_solve (Alg. 1, 2, 3).  The paper gives no numeric values for beta, rho,
  * i_max; textbook values are the defaults chosen by callers. */
 typedef struct {
     int32_t iters;            /* SSN iterations to run (the paper ran a fixed count)             */
     int32_t T;                /* max CG products per iteration                                   */
     int32_t imax;             /* line search: give up after more than imax step reductions       */
-    int32_t reserved;
+    int32_t flags;            /* 0, or SSN_SOLVE_NO_LOOKAHEAD                                    */
     int64_t nS;               /* Hessian sample size per iteration                               */
     double eps;               /* stop when ||g|| < eps                                           */
     double theta;             /* CG relative residual tolerance                                  */

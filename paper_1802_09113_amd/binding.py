@@ -16,6 +16,7 @@ SSN_F32, SSN_F64 = 0, 1
 SSN_DENSE_ROWMAJOR, SSN_CSR = 0, 1
 SSN_SCALE_MEAN, SSN_SCALE_SUM = 0, 1
 SSN_OK = 0
+SSN_SOLVE_NO_LOOKAHEAD = 1
 SSN_E_INVALID_ARG, SSN_E_BAD_LABEL, SSN_E_BAD_INDEX, SSN_E_NOT_PREPARED = -1, -2, -3, -4
 SSN_E_ALLOC, SSN_E_HIP, SSN_E_NONFINITE, SSN_E_UNSUPPORTED = -5, -6, -7, -8
 
@@ -46,7 +47,7 @@ class ssn_cg_info(ctypes.Structure):
 
 class ssn_params(ctypes.Structure):
     _fields_ = [
-        ("iters", ctypes.c_int32), ("T", ctypes.c_int32), ("imax", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("iters", ctypes.c_int32), ("T", ctypes.c_int32), ("imax", ctypes.c_int32), ("flags", ctypes.c_int32),
         ("nS", ctypes.c_int64),
         ("eps", ctypes.c_double), ("theta", ctypes.c_double), ("beta", ctypes.c_double), ("rho", ctypes.c_double),
         ("S_all", ctypes.c_void_p), ("test", ctypes.c_void_p),
@@ -275,9 +276,10 @@ class Context:
         self._check(lib().ssn_time_kernel(self._h, which, self._blk(M), reps, ctypes.byref(ms)))
         return ms.value
 
-    def ssn_solve(self, W, S_all, eps=0.0, theta=1e-4, T=10, beta=1e-4, rho=0.5, imax=10, test=None, Sg_all=None):
+    def ssn_solve(self, W, S_all, eps=0.0, theta=1e-4, T=10, beta=1e-4, rho=0.5, imax=10, test=None, Sg_all=None,
+                  lookahead=True):
         """S_all: (iters, nS) int32 device tensor; Sg_all (optional): (iters, nSg) gradient samples.  W is updated
-        in place; returns (records, iterations done)."""
+        in place; returns (records, iterations done).  lookahead=False sets SSN_SOLVE_NO_LOOKAHEAD."""
         assert S_all.is_cuda and S_all.dtype == torch.int32 and S_all.is_contiguous() and S_all.dim() == 2
         pr = ssn_params()
         if Sg_all is not None:
@@ -287,6 +289,7 @@ class Context:
         pr.iters, pr.nS = S_all.shape
         pr.T, pr.imax, pr.eps, pr.theta, pr.beta, pr.rho = T, imax, eps, theta, beta, rho
         pr.S_all = S_all.data_ptr()
+        pr.flags = 0 if lookahead else SSN_SOLVE_NO_LOOKAHEAD
         pr.test = test._h if test is not None else None
         log = (ssn_iter_record * max(int(pr.iters), 1))()
         done = ctypes.c_int32()

@@ -53,6 +53,7 @@ struct ssn_ctx {
     // CG / line-search vectors (p x ldw each)
     void *cg_p = nullptr, *cg_r = nullptr, *cg_s = nullptr, *trial = nullptr;
     void *grad = nullptr, *dir = nullptr;      // ssn_solve's gradient and direction
+    void *grad_next = nullptr;                 // gradient at the first line-search trial (look-ahead of ssn_solve)
     CgSlot *slots = nullptr;
     int slots_cap = 0;
     double *trace_dev = nullptr;
@@ -502,7 +503,7 @@ int ssn_destroy(ssn_ctx *c)
     if (!c) return SSN_E_INVALID_ARG;
     (void)hipStreamSynchronize(c->st);
     void *dev[] = {c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->red_c, c->scal_dev, c->int_dev,
-                   c->cg_p, c->cg_r, c->cg_s, c->trial, c->grad, c->dir, c->slots, c->trace_dev};
+                   c->cg_p, c->cg_r, c->cg_s, c->trial, c->grad, c->grad_next, c->dir, c->slots, c->trace_dev};
     for (void *p : dev)
         if (p) (void)hipFree(p);
     if (c->host_pin) (void)hipHostFree(c->host_pin);
@@ -769,7 +770,7 @@ static int enqueue_slope(ssn_ctx *c, const void *P, const void *G)
 }
 
 int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
-                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok);
+                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok, void *G_first = nullptr);
 
 int ssn_linesearch(ssn_ctx *c, const void *W, const void *P, const void *G, double fW, double beta, double rho,
                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok)
@@ -781,16 +782,18 @@ int ssn_linesearch(ssn_ctx *c, const void *W, const void *P, const void *G, doub
     return linesearch_impl(c, W, P, fW, slope, beta, rho, imax, alpha_out, f_new, n_eval, ok);
 }
 
-// Alg. 3 with the slope <P, G> already on the host
+// Alg. 3 with the slope <P, G> already on the host.  G_first (nullable): the first trial, alpha = 1, is
+// evaluated by the gradient pass, which leaves grad f(W + P) there next to the same F(W + P); when that
+// trial is accepted the caller already holds the gradient of the next iterate.
 int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
-                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok)
+                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok, void *G_first)
 {
     if (!c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
     double alpha = 1.0, ft = 0.0;
     int i = 0, evals = 0, good = 0;
     for (;;) {
         SSN_HIP(c, launch_axpy(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, c->trial, c->d.ldw, c->st));
-        const int s = objective_impl(c, c->trial, &ft);
+        const int s = (G_first && i == 0) ? gradient_impl(c, c->trial, G_first, &ft) : objective_impl(c, c->trial, &ft);
         if (s != SSN_OK && s != SSN_E_NONFINITE) return s;
         ++evals;
         if (s == SSN_OK && !(ft > fW + alpha * beta * slope)) { good = 1; break; }
@@ -847,6 +850,15 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
     // carried over from the accepted line-search trial
     double f_carry = 0.0;
     if (pr->Sg_all && pr->iters > 0) SSN_TRY(objective_impl(c, W, &f_carry));
+    // Look-ahead (full gradient only): a Newton-type step is accepted at alpha = 1 most of the time, and the
+    // accepted trial point is the next iterate.  So the first trial of the line search is evaluated by the
+    // gradient pass (F and grad F from one read of the data), and when it is accepted the next iteration
+    // starts with its gradient in hand: one pass over the data less per iteration, the same numbers.  After
+    // a rejected first trial the plain objective pass is used until a first trial is accepted again.
+    const bool look = !pr->Sg_all && !(pr->flags & SSN_SOLVE_NO_LOOKAHEAD);
+    if (look && !c->grad_next) SSN_TRY(vec_bytes_alloc(c, &c->grad_next));
+    bool look_on = look, have_next = false;
+    double f_next = 0.0;
     // Phase times come from events on the stream; the host waits for the device once per iteration (f, |g|,
     // the slope and the CG state come back together) plus once per line-search evaluation.  The last two
     // phases of an iteration are read one synchronisation later.
@@ -858,7 +870,6 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         float t = 0.f;
         return hipEventElapsedTime(&t, a, b) == hipSuccess ? (double)t : std::nan("");
     };
-    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
     int status = SSN_OK;
     int pending = -1;                        // iteration whose line-search / update times are still to be read
     ssn_iter_record pend_rec{};
@@ -891,27 +902,24 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         rec.test_acc = std::nan("");
         SOLVE_HIP(hipEventRecord(E[0], c->st));
         if (pr->Sg_all) SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, false, pr->Sg_all + (int64_t)k * pr->nSg, pr->nSg));
-        else SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, true));
-        SOLVE_HIP(launch_dot_part(c->d.dtype, c->d.p, c->K, c->grad, c->d.ldw, c->grad, c->d.ldw, c->red_a, vb, nullptr,
-                                  c->st));
-        SOLVE_HIP(launch_combine(c->red_a, vb, 1.0, nullptr, 0, 0.0, c->scal_dev + 2, c->st));
+        else if (!have_next) SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, true));
         SOLVE_HIP(hipEventRecord(E[1], c->st));
         SOLVE_TRY(hess_prepare_impl(c, W, pr->S_all + (int64_t)k * pr->nS, pr->nS, false));
         SOLVE_HIP(hipEventRecord(E[2], c->st));
         SOLVE_TRY(cg_enqueue(c, c->grad, pr->theta, pr->T, c->dir));
         SOLVE_TRY(enqueue_slope(c, c->dir, c->grad));
         SOLVE_HIP(hipEventRecord(E[3], c->st));
-        // one round trip: f, <dir, g>, g.g and the final CG state
-        SOLVE_HIP(hipMemcpyAsync(c->host_pin, c->scal_dev, 3 * sizeof(double), hipMemcpyDeviceToHost, c->st));
+        // one round trip: f, <dir, g> and the final CG state (which carries ||g||)
+        SOLVE_HIP(hipMemcpyAsync(c->host_pin, c->scal_dev, 2 * sizeof(double), hipMemcpyDeviceToHost, c->st));
         SOLVE_HIP(hipMemcpyAsync(c->host_pin + 8, c->slots + pr->T, sizeof(CgSlot), hipMemcpyDeviceToHost, c->st));
         SOLVE_HIP(hipStreamSynchronize(c->st));
         flush_pending();
         {
-            rec.f = pr->Sg_all ? f_carry : c->host_pin[0];
+            rec.f = pr->Sg_all ? f_carry : (have_next ? f_next : c->host_pin[0]);
             const double slope = c->host_pin[1];
-            rec.gnorm = std::sqrt(c->host_pin[2]);
             CgSlot fin;
             memcpy(&fin, c->host_pin + 8, sizeof(CgSlot));
+            rec.gnorm = fin.gnorm;
             rec.ms_grad = ms_between(E[0], E[1]);
             rec.ms_prepare = ms_between(E[1], E[2]);
             rec.ms_cg = ms_between(E[2], E[3]);
@@ -929,9 +937,17 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
             rec.cg_iters = info.iters;
             rec.cg_rel_res = info.rel_res;
             double fn = 0.0;
+            const bool ahead = look_on && k + 1 < pr->iters;
             SOLVE_TRY(linesearch_impl(c, W, c->dir, rec.f, slope, pr->beta, pr->rho, pr->imax, &rec.alpha, &fn, &rec.ls_evals,
-                                      &rec.ls_ok));
+                                      &rec.ls_ok, ahead ? c->grad_next : nullptr));
             f_carry = fn;
+            const bool first_accepted = rec.ls_ok && rec.ls_evals == 1;
+            have_next = ahead && first_accepted;
+            if (have_next) {
+                std::swap(c->grad, c->grad_next);
+                f_next = fn;
+            }
+            look_on = look && first_accepted;
         }
         SOLVE_HIP(hipEventRecord(E[4], c->st));
         SOLVE_TRY(ssn_axpy(c, rec.alpha, c->dir, W));

@@ -184,6 +184,38 @@ def test_ssn_fixed_schedule_tiny_config(tiny, dtype):
     tpair.close()
 
 
+@pytest.mark.parametrize("nS", [400, 12], ids=["accepted_then_rejected", "rejected_with_some_accepted"])
+def test_ssn_gradient_look_ahead_changes_no_number(tiny, nS):
+    # By default the first line-search trial is evaluated by the gradient pass and an accepted trial hands its
+    # gradient to the next iteration.  With 400 sampled rows the first six first trials are accepted and the rest
+    # rejected; with 12 the direction is poor, most first trials are rejected and a few accepted, so the
+    # look-ahead is switched off and on again.
+    # Either way the run is the oracle's, and the same as with the look-ahead turned off.
+    d = tiny
+    pair = Pair(d, F64)
+    iters = 10
+    S_all = synth.sample_schedule(2000, nS, iters)
+    W0h, Wa = pair.block(np.zeros((pair.p, pair.K)))
+    _, Wb = pair.block(np.zeros((pair.p, pair.K)))
+    Wref, log_ref, done_ref = pair.oracle.ssn(W0h, S_all, theta=1e-4, T=d["T"])
+    Sd = torch.from_numpy(S_all).cuda()
+    ra, done_a = pair.gpu.ssn_solve(Wa, Sd, theta=1e-4, T=d["T"])
+    rb, done_b = pair.gpu.ssn_solve(Wb, Sd, theta=1e-4, T=d["T"], lookahead=False)
+    torch.cuda.synchronize()
+    assert done_a == done_b == done_ref == iters
+    alphas = list(log_ref[:, 4])
+    assert alphas.count(1.0) >= 2 and min(alphas) < 1.0      # the schedule does exercise both outcomes
+    for recs, W in ((ra, Wa), (rb, Wb)):
+        assert [r["alpha"] for r in recs] == alphas
+        assert [r["cg_iters"] for r in recs] == [int(x) for x in log_ref[:, 2]]
+        np.testing.assert_allclose([r["f"] for r in recs], log_ref[:, 0], rtol=1e-9)
+        np.testing.assert_allclose([r["gnorm"] for r in recs], log_ref[:, 1], rtol=1e-7)
+        assert rel_err(pair.host(W), Wref) <= 1e-7
+    assert [r["ls_evals"] for r in ra] == [r["ls_evals"] for r in rb]
+    assert rel_err(pair.host(Wa), pair.host(Wb)) <= 1e-10
+    pair.close()
+
+
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 def test_ssn_with_sub_sampled_gradient(tiny, dtype):
     # Alg. 1 with eq. (2a) and eq. (2b): 20 % of the rows for g, 5 % for H
