@@ -95,6 +95,9 @@ typedef struct {
  * ms_linesearch of the previous iteration.  After a rejected first trial the plain objective pass is used
  * until a first trial is accepted again.  Not used with a sub-sampled gradient.  This flag turns it off. */
 #define SSN_SOLVE_NO_LOOKAHEAD 1
+/* Leave out the six stream events per iteration behind the ms_* fields of the iteration records (which then
+ * hold NaN): each record costs a few microseconds of device time. */
+#define SSN_SOLVE_NO_PHASE_TIMES 2
 
 /* Parameters of ssn_solve (Alg. 1, 2, 3).  The paper gives no numeric values for beta, rho,
  * i_max; textbook values are the defaults chosen by callers. */
@@ -102,7 +105,7 @@ typedef struct {
     int32_t iters;            /* SSN iterations to run (the paper ran a fixed count)             */
     int32_t T;                /* max CG products per iteration                                   */
     int32_t imax;             /* line search: give up after more than imax step reductions       */
-    int32_t flags;            /* 0, or SSN_SOLVE_NO_LOOKAHEAD                                    */
+    int32_t flags;            /* 0, or SSN_SOLVE_NO_LOOKAHEAD | SSN_SOLVE_NO_PHASE_TIMES         */
     int64_t nS;               /* Hessian sample size per iteration                               */
     double eps;               /* stop when ||g|| < eps                                           */
     double theta;             /* CG relative residual tolerance                                  */
@@ -122,7 +125,8 @@ typedef struct {
     double cg_rel_res;        /* relative residual of the direction taken                        */
     double alpha;             /* step length                                                     */
     double test_acc;          /* accuracy on params.test after the update (NaN if none)          */
-    double ms_grad, ms_prepare, ms_cg, ms_linesearch, ms_update;   /* host wall-clock per phase  */
+    double ms_grad, ms_prepare, ms_cg, ms_linesearch, ms_update;   /* device time per phase, from
+                                 stream events (NaN with SSN_SOLVE_NO_PHASE_TIMES)                */
     int32_t cg_iters;         /* Hessian-vector products                                         */
     int32_t ls_evals;         /* objective evaluations in the line search                        */
     int32_t ls_ok;            /* 1 iff the Armijo condition held at the returned step            */

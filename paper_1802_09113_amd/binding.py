@@ -17,6 +17,7 @@ SSN_DENSE_ROWMAJOR, SSN_CSR = 0, 1
 SSN_SCALE_MEAN, SSN_SCALE_SUM = 0, 1
 SSN_OK = 0
 SSN_SOLVE_NO_LOOKAHEAD = 1
+SSN_SOLVE_NO_PHASE_TIMES = 2
 SSN_E_INVALID_ARG, SSN_E_BAD_LABEL, SSN_E_BAD_INDEX, SSN_E_NOT_PREPARED = -1, -2, -3, -4
 SSN_E_ALLOC, SSN_E_HIP, SSN_E_NONFINITE, SSN_E_UNSUPPORTED = -5, -6, -7, -8
 
@@ -277,9 +278,10 @@ class Context:
         return ms.value
 
     def ssn_solve(self, W, S_all, eps=0.0, theta=1e-4, T=10, beta=1e-4, rho=0.5, imax=10, test=None, Sg_all=None,
-                  lookahead=True):
+                  lookahead=True, phase_times=True):
         """S_all: (iters, nS) int32 device tensor; Sg_all (optional): (iters, nSg) gradient samples.  W is updated
-        in place; returns (records, iterations done).  lookahead=False sets SSN_SOLVE_NO_LOOKAHEAD."""
+        in place; returns (records, iterations done).  lookahead=False sets SSN_SOLVE_NO_LOOKAHEAD,
+        phase_times=False SSN_SOLVE_NO_PHASE_TIMES."""
         assert S_all.is_cuda and S_all.dtype == torch.int32 and S_all.is_contiguous() and S_all.dim() == 2
         pr = ssn_params()
         if Sg_all is not None:
@@ -289,7 +291,7 @@ class Context:
         pr.iters, pr.nS = S_all.shape
         pr.T, pr.imax, pr.eps, pr.theta, pr.beta, pr.rho = T, imax, eps, theta, beta, rho
         pr.S_all = S_all.data_ptr()
-        pr.flags = 0 if lookahead else SSN_SOLVE_NO_LOOKAHEAD
+        pr.flags = (0 if lookahead else SSN_SOLVE_NO_LOOKAHEAD) | (0 if phase_times else SSN_SOLVE_NO_PHASE_TIMES)
         pr.test = test._h if test is not None else None
         log = (ssn_iter_record * max(int(pr.iters), 1))()
         done = ctypes.c_int32()

@@ -46,6 +46,8 @@ struct ssn_ctx {
     double *host_pin = nullptr;   // pinned staging for scalar results
     double *f_host = nullptr;     // host-visible word kernels write objective values to (inside host_pin's allocation)
     double *f_host_dev = nullptr; // its device address
+    double *pub_host = nullptr;   // host-visible block ssn_solve's per-iteration scalars and CG state are written to
+    double *pub_dev = nullptr;    // its device address (null: not mappable, copies are used instead)
     // prepared Hessian sample
     const int32_t *S = nullptr;
     int64_t nS = 0;
@@ -321,23 +323,29 @@ int read_objective(ssn_ctx *c, bool mirrored, double *f)
     return SSN_OK;
 }
 
-int objective_impl(ssn_ctx *c, const void *W, double *f)
+// enqueue F(W) over all rows into scal_dev[0] (and the host-visible word when *mirrored comes back true)
+int objective_enqueue(ssn_ctx *c, const void *W, bool *mirrored)
 {
     RowsArgs a = rows_base(c);
     a.nrows = c->d.n;
     a.M = W;
     a.mode = ROW_OBJ;
     int nparts = 0;
-    bool mirrored = false;
     SSN_TRY(launch_rows(c, a, &nparts));
-    SSN_TRY(enqueue_objective_value(c, W, nparts, 0, -1.0, &mirrored));
+    return enqueue_objective_value(c, W, nparts, 0, -1.0, mirrored);
+}
+
+int objective_impl(ssn_ctx *c, const void *W, double *f)
+{
+    bool mirrored = false;
+    SSN_TRY(objective_enqueue(c, W, &mirrored));
     return read_objective(c, mirrored, f);
 }
 
 // defer_f: leave f(W) in scal_dev[0] without reading it back (the caller synchronises later).
 // S (nullable): the sub-sampled gradient of eq. (2a) on the nS rows S, with its sample scaling.
 int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f, bool defer_f = false, const int32_t *S = nullptr,
-                  int64_t nS = 0)
+                  int64_t nS = 0, bool *mirrored_out = nullptr)
 {
     const int64_t nrows = S ? nS : c->d.n;
     const double scale = S ? scale_rows(c, nS) : scale_full(c);
@@ -364,6 +372,7 @@ int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f, bool defer_f = 
     bool mirrored = false;
     if (f || defer_f) SSN_TRY(enqueue_objective_value(c, W, nparts, 0, scale, &mirrored));
     if (f && !defer_f) SSN_TRY(read_objective(c, mirrored, f));
+    if (mirrored_out) *mirrored_out = mirrored;
     return SSN_OK;
 }
 
@@ -571,6 +580,9 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
     {
         void *dp = nullptr;
         if (hipHostGetDevicePointer(&dp, c->f_host, 0) == hipSuccess) c->f_host_dev = (double *)dp;
+        c->pub_host = c->host_pin + 128;                             // bytes 1024..2047
+        dp = nullptr;
+        if (hipHostGetDevicePointer(&dp, c->pub_host, 0) == hipSuccess) c->pub_dev = (double *)dp;
     }
     if (d->layout == SSN_DENSE_ROWMAJOR) {
         const int64_t nft = (d->p + 63) / 64;
@@ -770,7 +782,8 @@ static int enqueue_slope(ssn_ctx *c, const void *P, const void *G)
 }
 
 int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
-                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok, void *G_first = nullptr);
+                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok, void *G_first = nullptr,
+                    const bool *first_enqueued = nullptr);
 
 int ssn_linesearch(ssn_ctx *c, const void *W, const void *P, const void *G, double fW, double beta, double rho,
                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok)
@@ -782,18 +795,31 @@ int ssn_linesearch(ssn_ctx *c, const void *W, const void *P, const void *G, doub
     return linesearch_impl(c, W, P, fW, slope, beta, rho, imax, alpha_out, f_new, n_eval, ok);
 }
 
-// Alg. 3 with the slope <P, G> already on the host.  G_first (nullable): the first trial, alpha = 1, is
-// evaluated by the gradient pass, which leaves grad f(W + P) there next to the same F(W + P); when that
-// trial is accepted the caller already holds the gradient of the next iterate.
-int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
-                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok, void *G_first)
+// The trial point W + alpha P into c->trial and F there enqueued (into scal_dev[0]; *mirrored: also into the
+// host-visible word).  G_first (nullable): evaluate with the gradient pass, which leaves grad F there too.
+int trial_enqueue(ssn_ctx *c, const void *W, const void *P, double alpha, void *G_first, bool *mirrored)
 {
     if (!c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
+    SSN_HIP(c, launch_axpy(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, c->trial, c->d.ldw, c->st));
+    if (G_first) return gradient_impl(c, c->trial, G_first, nullptr, true, nullptr, 0, mirrored);
+    return objective_enqueue(c, c->trial, mirrored);
+}
+
+// Alg. 3 with the slope <P, G> already on the host.  G_first (nullable): the first trial, alpha = 1, is
+// evaluated by the gradient pass, which leaves grad f(W + P) there next to the same F(W + P); when that
+// trial is accepted the caller already holds the gradient of the next iterate.  first_enqueued (nullable):
+// the caller has already enqueued the first trial with trial_enqueue; *first_enqueued is its `mirrored`.
+int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
+                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok, void *G_first,
+                    const bool *first_enqueued)
+{
     double alpha = 1.0, ft = 0.0;
     int i = 0, evals = 0, good = 0;
     for (;;) {
-        SSN_HIP(c, launch_axpy(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, c->trial, c->d.ldw, c->st));
-        const int s = (G_first && i == 0) ? gradient_impl(c, c->trial, G_first, &ft) : objective_impl(c, c->trial, &ft);
+        bool mirrored = false;
+        if (i == 0 && first_enqueued) mirrored = *first_enqueued;
+        else SSN_TRY(trial_enqueue(c, W, P, alpha, i == 0 ? G_first : nullptr, &mirrored));
+        const int s = read_objective(c, mirrored, &ft);
         if (s != SSN_OK && s != SSN_E_NONFINITE) return s;
         ++evals;
         if (s == SSN_OK && !(ft > fW + alpha * beta * slope)) { good = 1; break; }
@@ -859,13 +885,18 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
     if (look && !c->grad_next) SSN_TRY(vec_bytes_alloc(c, &c->grad_next));
     bool look_on = look, have_next = false;
     double f_next = 0.0;
-    // Phase times come from events on the stream; the host waits for the device once per iteration (f, |g|,
-    // the slope and the CG state come back together) plus once per line-search evaluation.  The last two
-    // phases of an iteration are read one synchronisation later.
+    // Phase times come from events on the stream (six records per iteration; SSN_SOLVE_NO_PHASE_TIMES leaves
+    // them out).  The host waits for the device once per iteration -- f, |g|, the slope, the CG state and the
+    // first line-search trial come back together -- plus once per further trial.  The last two phases of an
+    // iteration are read one synchronisation later.
     constexpr int NE = 6;
-    hipEvent_t ev[2][NE];
-    for (auto &set : ev)
-        for (auto &e : set) SSN_HIP(c, hipEventCreate(&e));
+    const bool timing = !(pr->flags & SSN_SOLVE_NO_PHASE_TIMES);
+    hipEvent_t ev[2][NE] = {};
+    if (timing)
+        for (auto &set : ev)
+            for (auto &e : set) SSN_HIP(c, hipEventCreate(&e));
+    auto mark = [&](hipEvent_t e) { return timing ? hipEventRecord(e, c->st) : hipSuccess; };
+    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
     auto ms_between = [&](hipEvent_t a, hipEvent_t b) {
         float t = 0.f;
         return hipEventElapsedTime(&t, a, b) == hipSuccess ? (double)t : std::nan("");
@@ -876,8 +907,8 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
     auto flush_pending = [&]() {
         if (pending < 0) return;
         hipEvent_t *E = ev[pending & 1];
-        pend_rec.ms_linesearch = ms_between(E[3], E[4]);
-        pend_rec.ms_update = ms_between(E[4], E[5]);
+        pend_rec.ms_linesearch = timing ? ms_between(E[3], E[4]) : std::nan("");
+        pend_rec.ms_update = timing ? ms_between(E[4], E[5]) : std::nan("");
         if (log && pending < max_log) log[pending] = pend_rec;
         pending = -1;
     };
@@ -900,35 +931,50 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         hipEvent_t *E = ev[k & 1];
         ssn_iter_record rec{};
         rec.test_acc = std::nan("");
-        SOLVE_HIP(hipEventRecord(E[0], c->st));
+        SOLVE_HIP(mark(E[0]));
         if (pr->Sg_all) SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, false, pr->Sg_all + (int64_t)k * pr->nSg, pr->nSg));
         else if (!have_next) SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, true));
-        SOLVE_HIP(hipEventRecord(E[1], c->st));
+        SOLVE_HIP(mark(E[1]));
         SOLVE_TRY(hess_prepare_impl(c, W, pr->S_all + (int64_t)k * pr->nS, pr->nS, false));
-        SOLVE_HIP(hipEventRecord(E[2], c->st));
+        SOLVE_HIP(mark(E[2]));
         SOLVE_TRY(cg_enqueue(c, c->grad, pr->theta, pr->T, c->dir));
-        SOLVE_TRY(enqueue_slope(c, c->dir, c->grad));
-        SOLVE_HIP(hipEventRecord(E[3], c->st));
-        // one round trip: f, <dir, g> and the final CG state (which carries ||g||)
-        SOLVE_HIP(hipMemcpyAsync(c->host_pin, c->scal_dev, 2 * sizeof(double), hipMemcpyDeviceToHost, c->st));
-        SOLVE_HIP(hipMemcpyAsync(c->host_pin + 8, c->slots + pr->T, sizeof(CgSlot), hipMemcpyDeviceToHost, c->st));
+        // F(x_k), <dir, g> and the final CG state (which carries ||g||) reach the host through host-visible
+        // memory written by one small kernel; without a device mapping of it, through two copies
+        SOLVE_HIP(launch_dot_part(c->d.dtype, c->d.p, c->K, c->dir, c->d.ldw, c->grad, c->d.ldw, c->red_a, vb, nullptr,
+                                  c->st));
+        double *pub = c->pub_dev ? c->pub_host : c->host_pin;
+        if (c->pub_dev) {
+            SOLVE_HIP(launch_solve_publish(c->red_a, vb, c->scal_dev, c->slots + pr->T, c->scal_dev + 1, c->pub_dev, c->st));
+        } else {
+            SOLVE_HIP(launch_combine(c->red_a, vb, 1.0, nullptr, 0, 0.0, c->scal_dev + 1, c->st));
+            SOLVE_HIP(hipMemcpyAsync(pub, c->scal_dev, 2 * sizeof(double), hipMemcpyDeviceToHost, c->st));
+            SOLVE_HIP(hipMemcpyAsync(pub + 2, c->slots + pr->T, sizeof(CgSlot), hipMemcpyDeviceToHost, c->st));
+        }
+        SOLVE_HIP(mark(E[3]));
+        // The first trial of the line search is x_k + dir whatever the host reads back, so it is enqueued
+        // before the host waits: one wait per iteration covers the CG results and the trial's F.
+        const bool ahead = look_on && k + 1 < pr->iters;
+        bool first_mirrored = false;
+        SOLVE_TRY(trial_enqueue(c, W, c->dir, 1.0, ahead ? c->grad_next : nullptr, &first_mirrored));
         SOLVE_HIP(hipStreamSynchronize(c->st));
         flush_pending();
         {
-            rec.f = pr->Sg_all ? f_carry : (have_next ? f_next : c->host_pin[0]);
-            const double slope = c->host_pin[1];
+            rec.f = pr->Sg_all ? f_carry : (have_next ? f_next : pub[0]);
+            const double slope = pub[1];
             CgSlot fin;
-            memcpy(&fin, c->host_pin + 8, sizeof(CgSlot));
+            memcpy(&fin, pub + 2, sizeof(CgSlot));
             rec.gnorm = fin.gnorm;
-            rec.ms_grad = ms_between(E[0], E[1]);
-            rec.ms_prepare = ms_between(E[1], E[2]);
-            rec.ms_cg = ms_between(E[2], E[3]);
+            if (timing) {
+                rec.ms_grad = ms_between(E[0], E[1]);
+                rec.ms_prepare = ms_between(E[1], E[2]);
+                rec.ms_cg = ms_between(E[2], E[3]);
+            }
             if (!std::isfinite(rec.f)) {
                 status = fail(c, SSN_E_NONFINITE, "objective is not finite");
                 goto done;
             }
-            if (rec.gnorm < pr->eps) {       // converged: the direction computed above is discarded
-                rec.ms_prepare = rec.ms_cg = 0.0;
+            if (rec.gnorm < pr->eps) {       // converged: the direction and the trial computed above are discarded
+                rec.ms_prepare = rec.ms_cg = timing ? 0.0 : std::nan("");
                 if (log && k < max_log) log[k] = rec;
                 break;
             }
@@ -937,9 +983,8 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
             rec.cg_iters = info.iters;
             rec.cg_rel_res = info.rel_res;
             double fn = 0.0;
-            const bool ahead = look_on && k + 1 < pr->iters;
             SOLVE_TRY(linesearch_impl(c, W, c->dir, rec.f, slope, pr->beta, pr->rho, pr->imax, &rec.alpha, &fn, &rec.ls_evals,
-                                      &rec.ls_ok, ahead ? c->grad_next : nullptr));
+                                      &rec.ls_ok, nullptr, &first_mirrored));
             f_carry = fn;
             const bool first_accepted = rec.ls_ok && rec.ls_evals == 1;
             have_next = ahead && first_accepted;
@@ -949,14 +994,14 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
             }
             look_on = look && first_accepted;
         }
-        SOLVE_HIP(hipEventRecord(E[4], c->st));
+        SOLVE_HIP(mark(E[4]));
         SOLVE_TRY(ssn_axpy(c, rec.alpha, c->dir, W));
         if (pr->test) {
             // the held-out context runs on its own stream: wait for the update first
             SOLVE_HIP(hipStreamSynchronize(c->st));
             SOLVE_TRY(ssn_predict(pr->test, W, nullptr, &rec.test_acc));
         }
-        SOLVE_HIP(hipEventRecord(E[5], c->st));
+        SOLVE_HIP(mark(E[5]));
         pending = k;
         pend_rec = rec;
     }
@@ -965,8 +1010,9 @@ done:
 #undef SOLVE_HIP
     (void)hipStreamSynchronize(c->st);
     flush_pending();
-    for (auto &set : ev)
-        for (auto &e : set) (void)hipEventDestroy(e);
+    if (timing)
+        for (auto &set : ev)
+            for (auto &e : set) (void)hipEventDestroy(e);
     if (iters_done) *iters_done = k;
     return status;
 }

@@ -123,6 +123,8 @@ hipError_t launch_objective_value(int dtype, const double *loss_part, int nparts
 constexpr int64_t OBJ_VALUE_ELEMS = 32768;
 hipError_t launch_combine(const double *a, int na, double scale, const double *b, int nb, double coef,
                           double *out, hipStream_t st);
+hipError_t launch_solve_publish(const double *slope_part, int n, const double *f_dev, const CgSlot *fin, double *slope_dev,
+                                double *host_out, hipStream_t st);
 // streaming read of `bytes` (multiple of 16, 16-byte aligned); one checksum partial per block
 hipError_t launch_stream_read(const void *src, int64_t bytes, double *part, int blocks, hipStream_t st);
 hipError_t launch_sum_int(const int32_t *a, int na, int32_t *out, hipStream_t st);

@@ -382,6 +382,29 @@ hipError_t launch_objective_value(int dtype, const double *loss_part, int nparts
     return hipGetLastError();
 }
 
+// What the host needs after the CG solve of an SSN iteration, in one launch and without a copy: the slope
+// <P, G> from its partials (also left in *slope_dev), F(x_k) from *f_dev and the final CG state, written to
+// host-visible memory (host_out: two doubles, then the CgSlot).  The caller only waits for the stream.
+__global__ __launch_bounds__(VEC_BLOCK) void solve_publish_kernel(const double *slope_part, int n, const double *f_dev,
+                                                                   const CgSlot *fin, double *slope_dev, double *host_out)
+{
+    const double slope = sum_parts(slope_part, n);
+    if (threadIdx.x == 0) {
+        *slope_dev = slope;
+        host_out[0] = *f_dev;
+        host_out[1] = slope;
+    }
+    constexpr int NWORDS = (int)(sizeof(CgSlot) / sizeof(int32_t));
+    if ((int)threadIdx.x < NWORDS) ((int32_t *)(host_out + 2))[threadIdx.x] = ((const int32_t *)fin)[threadIdx.x];
+}
+
+hipError_t launch_solve_publish(const double *slope_part, int n, const double *f_dev, const CgSlot *fin, double *slope_dev,
+                                double *host_out, hipStream_t st)
+{
+    hipLaunchKernelGGL(solve_publish_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, slope_part, n, f_dev, fin, slope_dev, host_out);
+    return hipGetLastError();
+}
+
 hipError_t launch_combine(const double *a, int na, double scale, const double *b, int nb, double coef, double *out,
                           hipStream_t st)
 {
