@@ -92,6 +92,43 @@ __global__ __launch_bounds__(VEC_BLOCK) void csc_piece_start_kernel(const int32_
     }
 }
 
+// ---- support of the view: the distinct columns, and the view in their coordinates ----------------------
+// head[t] = 1 where a new column starts in the sorted entry list
+__global__ __launch_bounds__(VEC_BLOCK) void csc_head_flag_kernel(const int32_t *key, int64_t nnz, int32_t *head)
+{
+    for (int64_t t = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; t < nnz; t += (int64_t)gridDim.x * VEC_BLOCK)
+        head[t] = (t == 0 || key[t] != key[t - 1]) ? 1 : 0;
+}
+
+// rank[t] (exclusive scan of head, so rank + head - 1 is the position of entry t's column among the distinct
+// columns) -> cols[position] = column; ccol[e] = position for the entry's place e in row order (idx[t]);
+// *ncols_out = number of distinct columns
+__global__ __launch_bounds__(VEC_BLOCK) void csc_support_kernel(const int32_t *key, const int32_t *head, const int32_t *rank,
+                                                                const int32_t *idx, int64_t nnz, int32_t *cols, int32_t *ccol,
+                                                                int32_t *ncols_out)
+{
+    for (int64_t t = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; t < nnz; t += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int32_t pos = rank[t] + head[t] - 1;
+        if (head[t]) cols[pos] = key[t];
+        ccol[idx[t]] = pos;
+        if (t == nnz - 1) *ncols_out = pos + 1;
+    }
+}
+
+// piece_cpos[k] = position of piece k's column among the distinct columns (four sentinels -1 at the end)
+__global__ __launch_bounds__(VEC_BLOCK) void csc_piece_cpos_kernel(const int32_t *piece_start, const int32_t *head,
+                                                                   const int32_t *rank, int32_t npieces, int32_t *piece_cpos)
+{
+    for (int64_t k = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; k < npieces + 4; k += (int64_t)gridDim.x * VEC_BLOCK) {
+        if (k < npieces) {
+            const int32_t t = piece_start[k];
+            piece_cpos[k] = rank[t] + head[t] - 1;
+        } else {
+            piece_cpos[k] = -1;
+        }
+    }
+}
+
 static int grid_for(int64_t n)
 {
     int64_t b = (n + VEC_BLOCK - 1) / VEC_BLOCK;
@@ -121,7 +158,7 @@ static hipError_t grow(void **ptr, int64_t *cap, int64_t need, size_t elem)
 void csc_free(CscView *v)
 {
     void *all[] = {v->key, v->row, v->val, v->piece_start, v->piece_col, v->piece_part, v->off, v->key_in, v->idx_in, v->idx_out,
-                   v->row_in, v->val_in, v->flag, v->pid, v->cub_tmp, v->count_dev};
+                   v->row_in, v->val_in, v->flag, v->pid, v->cub_tmp, v->count_dev, v->cols, v->ccol, v->piece_cpos};
     for (void *q : all)
         if (q) (void)hipFree(q);
     *v = CscView{};
@@ -140,12 +177,17 @@ void csc_free_scratch(CscView *v)
 
 // Build the view of rows S[0..nrows) (S == nullptr: rows 0..nrows-1) of the CSR matrix.  Synchronises the
 // stream twice (entry count and piece count come back to size the buffers).
+// support: also list the distinct columns of the view (cols, ncols) and express the selected rows in their
+// coordinates: (off, ccol, val_in) is then a CSR matrix of nrows rows and ncols columns, and piece_cpos the
+// pieces' columns in the same coordinates.  The construction scratch must be kept for that.
 hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t *colidx, const void *vals,
-                     const int32_t *S, int64_t nrows, int64_t p, int K, hipStream_t st)
+                     const int32_t *S, int64_t nrows, int64_t p, int K, hipStream_t st, bool support)
 {
     const size_t es = dtype == SSN_F32 ? 4 : 8;
     v->nnz = 0;
     v->npieces = 0;
+    v->ncols = 0;
+    v->has_support = false;
     if (!v->count_dev) CSC_HIP(hipMalloc((void **)&v->count_dev, 2 * sizeof(int32_t)));
 
     auto cub_need = [&](size_t bytes) -> hipError_t {
@@ -173,7 +215,10 @@ hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t
     CSC_HIP(hipStreamSynchronize(st));
     const int64_t nnz = total32;
     if (nnz < 0) return hipErrorInvalidValue;          // more than 2^31 entries selected
-    if (nnz == 0) return hipSuccess;
+    if (nnz == 0) {
+        v->has_support = support;          // no entries: no columns, every selected row is empty (off is all zero)
+        return hipSuccess;
+    }
 
     // 2. expand (column, position, sample row, value), sort by column (stable: rows stay in sample order)
     CSC_HIP(grow((void **)&v->key, &v->cap, nnz, sizeof(int32_t)));
@@ -225,10 +270,31 @@ hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t
     CSC_HIP(grow((void **)&v->piece_col, &v->cap_pcol, nnz + 4, sizeof(int32_t)));
     hipLaunchKernelGGL(csc_piece_start_kernel, dim3(grid_for(nnz)), dim3(VEC_BLOCK), 0, st, v->flag, v->pid, v->key, nnz,
                        v->piece_start, v->piece_col, v->count_dev);
-    int32_t np = 0;
-    CSC_HIP(hipMemcpyAsync(&np, v->count_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    if (support) {
+        // key_in / idx_in are free once the sort is done: they take the column-head flags and their scan
+        CSC_HIP(grow((void **)&v->cols, &v->cap_cols, nnz, sizeof(int32_t)));
+        CSC_HIP(grow((void **)&v->ccol, &v->cap_ccol, nnz, sizeof(int32_t)));
+        hipLaunchKernelGGL(csc_head_flag_kernel, dim3(grid_for(nnz)), dim3(VEC_BLOCK), 0, st, v->key, nnz, v->key_in);
+        bytes = 0;
+        CSC_HIP(hipcub::DeviceScan::ExclusiveSum(nullptr, bytes, v->key_in, v->idx_in, (int)nnz, st));
+        CSC_HIP(cub_need(bytes));
+        bytes = v->cub_bytes;
+        CSC_HIP(hipcub::DeviceScan::ExclusiveSum(v->cub_tmp, bytes, v->key_in, v->idx_in, (int)nnz, st));
+        hipLaunchKernelGGL(csc_support_kernel, dim3(grid_for(nnz)), dim3(VEC_BLOCK), 0, st, v->key, v->key_in, v->idx_in,
+                           v->idx_out, nnz, v->cols, v->ccol, v->count_dev + 1);
+    }
+    int32_t counts[2] = {0, 0};
+    CSC_HIP(hipMemcpyAsync(counts, v->count_dev, (support ? 2 : 1) * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     CSC_HIP(hipStreamSynchronize(st));
+    const int32_t np = counts[0];
     CSC_HIP(grow(&v->piece_part, &v->cap_part, (int64_t)np * K, es));
+    if (support) {
+        CSC_HIP(grow((void **)&v->piece_cpos, &v->cap_pcpos, (int64_t)np + 4, sizeof(int32_t)));
+        hipLaunchKernelGGL(csc_piece_cpos_kernel, dim3(grid_for((int64_t)np + 4)), dim3(VEC_BLOCK), 0, st, v->piece_start,
+                           v->key_in, v->idx_in, np, v->piece_cpos);
+        v->ncols = counts[1];
+        v->has_support = true;
+    }
     CSC_HIP(hipGetLastError());
     v->nnz = nnz;
     v->npieces = np;
@@ -250,6 +316,8 @@ struct CscApply {
     void *piece_part;
     const int32_t *skip;
 };
+// (piece_col may be the pieces' columns or their positions among the distinct columns: equal columns have
+// equal positions, and the result row written is whichever of the two the caller's `out` is indexed by)
 
 // lane group (slot) g of a wave = K lanes, one per class; NS = 64 / K groups per wave, one piece per group
 template <typename T> __global__ __launch_bounds__(256) void csc_piece_kernel(CscApply a)
@@ -331,13 +399,14 @@ template <typename T> __global__ __launch_bounds__(256) void csc_combine_kernel(
 // out += coef * X_view^T U  (out already holds whatever the product is added to: lambda * M, or the CG
 // residual).  K <= 64.
 hipError_t launch_csc_apply(int dtype, const CscView &v, int K, int KP, const void *U, double coef, void *out, int64_t ldo,
-                            const CgSlot *slot, const int32_t *skip, hipStream_t st)
+                            const CgSlot *slot, const int32_t *skip, hipStream_t st, bool support_coords)
 {
     if (v.npieces == 0) return hipSuccess;
+    if (support_coords && !v.has_support) return hipErrorInvalidValue;
     CscApply a{};
     a.row = v.row;
     a.piece_start = v.piece_start;
-    a.piece_col = v.piece_col;
+    a.piece_col = support_coords ? v.piece_cpos : v.piece_col;
     a.val = v.val;
     a.npieces = v.npieces;
     a.nnz = v.nnz;

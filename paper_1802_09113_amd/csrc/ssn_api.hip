@@ -55,6 +55,8 @@ struct ssn_ctx {
     // CG / line-search vectors (p x ldw each)
     void *cg_p = nullptr, *cg_r = nullptr, *cg_s = nullptr, *trial = nullptr;
     void *grad = nullptr, *dir = nullptr;      // ssn_solve's gradient and direction
+    void *cg_pb = nullptr;                     // CSR: best iterate on the sample's columns (cg_pb_cap elements)
+    int64_t cg_pb_cap = 0;
     void *grad_next = nullptr;                 // gradient at the first line-search trial (look-ahead of ssn_solve)
     CgSlot *slots = nullptr;
     int slots_cap = 0;
@@ -411,6 +413,16 @@ int cg_product_step(ssn_ctx *c, const CgVecs &v, CgSlot *cur, int n_ss, double *
     a.UP = c->Ubuf;
     a.skip = skip;
     a.part = c->part;
+    if (!is_dense(c)) {
+        // the sample's rows as a CSR matrix over the columns they touch (the CG vectors live there)
+        const CscView &sv = c->csc_samp;
+        a.S = nullptr;
+        a.rowptr = sv.off;
+        a.colidx = sv.ccol;
+        a.vals = sv.val_in;
+        a.p = v.p;
+        a.ldm = v.ld;
+    }
     int nparts = 0;
     SSN_TRY(launch_rows(c, a, &nparts));
     *p_pending = false;
@@ -452,9 +464,9 @@ int cg_product_step(ssn_ctx *c, const CgVecs &v, CgSlot *cur, int n_ss, double *
     }
     // CSR: alpha first, then the few entries of r the sample's columns touch, then one dense pass over r and s
     SSN_HIP(c, launch_cg_alpha(cur, c->loss_part, nparts, c->red_c, n_ss, scale_sample(c), c->d.lambda, trace_k, c->st));
-    SSN_HIP(c, launch_csc_apply(c->d.dtype, c->csc_samp, c->K, c->KP, c->Ubuf, scale_sample(c), v.r, c->d.ldw, cur, skip,
-                                c->st));
-    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+    SSN_HIP(c, launch_csc_apply(c->d.dtype, c->csc_samp, c->K, c->KP, c->Ubuf, scale_sample(c), v.r, v.ld, cur, skip,
+                                c->st, true));
+    const int vb = vec_blocks(v.p * (int64_t)c->K);
     SSN_HIP(c, launch_cg_r_update(c->d.dtype, v, cur, c->d.lambda, c->red_a, vb, c->st));
     *n_rr = vb;
     *p_pending = true;
@@ -512,7 +524,7 @@ int ssn_destroy(ssn_ctx *c)
     if (!c) return SSN_E_INVALID_ARG;
     (void)hipStreamSynchronize(c->st);
     void *dev[] = {c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->red_c, c->scal_dev, c->int_dev,
-                   c->cg_p, c->cg_r, c->cg_s, c->trial, c->grad, c->grad_next, c->dir, c->slots, c->trace_dev};
+                   c->cg_p, c->cg_r, c->cg_s, c->cg_pb, c->trial, c->grad, c->grad_next, c->dir, c->slots, c->trace_dev};
     for (void *p : dev)
         if (p) (void)hipFree(p);
     if (c->host_pin) (void)hipHostFree(c->host_pin);
@@ -661,7 +673,7 @@ static int hess_prepare_impl(ssn_ctx *c, const void *W, const int32_t *S, int64_
     a.UP = c->Pbuf;
     SSN_TRY(launch_rows(c, a, nullptr));
     if (!is_dense(c))
-        SSN_HIP(c, csc_build(&c->csc_samp, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.p, c->K, c->st));
+        SSN_HIP(c, csc_build(&c->csc_samp, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.p, c->K, c->st, true));
     c->S = S;
     c->nS = nS;
     c->prepared = true;
@@ -716,7 +728,6 @@ static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *
         SSN_HIP(c, hipMalloc((void **)&c->trace_dev, sizeof(double) * 3 * (size_t)(T + 1)));
         c->slots_cap = T + 1;
     }
-    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
     CgVecs v{};
     v.p = c->d.p;
     v.K = c->K;
@@ -726,17 +737,49 @@ static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *
     v.r = c->cg_r;
     v.s = c->cg_s;
     v.pbest = P_out;
-    SSN_HIP(c, launch_cg_init(c->d.dtype, v, c->red_a, c->red_c, vb, c->st));
-    SSN_HIP(c, launch_cg_init_state(c->red_a, vb, c->slots, c->st));
+    int vb = vec_blocks(c->d.p * (int64_t)c->K);
+    if (is_dense(c)) {
+        SSN_HIP(c, launch_cg_init(c->d.dtype, v, c->red_a, c->red_c, vb, c->st));
+        SSN_HIP(c, launch_cg_init_state(c->red_a, vb, c->slots, c->st));
+    } else {
+        // CSR: H_S = scale * X_S^T D X_S + lambda I acts as lambda I on every coordinate outside the columns the
+        // sample touches, so r, s, p stay multiples of g there (CgSlot::rho, sigma, pi) and the vectors of
+        // Alg. 2 are kept on the sample's columns only: a CG iteration moves ncols * K elements per vector
+        // instead of p * K.  The direction is expanded to all coordinates at the end.
+        const CscView &sv = c->csc_samp;
+        if (!sv.has_support) return fail(c, SSN_E_NOT_PREPARED, "internal: sample view without its support");
+        const int64_t need = (int64_t)sv.ncols * c->K;
+        if (c->cg_pb_cap < need) {
+            SSN_HIP(c, hipStreamSynchronize(c->st));
+            if (c->cg_pb) (void)hipFree(c->cg_pb);
+            c->cg_pb = nullptr;
+            c->cg_pb_cap = 0;
+            SSN_HIP(c, hipMalloc(&c->cg_pb, (size_t)(need + need / 8 + 64) * c->es));
+            c->cg_pb_cap = need + need / 8 + 64;
+        }
+        // g.g over all coordinates (red_b) next to g.g over the sample's columns (red_a)
+        SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, G, c->d.ldw, G, c->d.ldw, c->red_b, vb, nullptr, c->st));
+        const int vb_full = vb;
+        v.p = sv.ncols;
+        v.ld = c->K;
+        v.pbest = c->cg_pb;
+        vb = vec_blocks(v.p * (int64_t)c->K);
+        SSN_HIP(c, launch_cg_init_support(c->d.dtype, v, G, c->d.ldw, sv.cols, c->red_a, c->red_c, vb, c->st));
+        SSN_HIP(c, launch_cg_init_state(c->red_a, vb, c->slots, c->st, c->red_b, vb_full));
+    }
     for (int k = 0; k < T; ++k) {
         int n_rr = 0;
         bool p_pending = false;
         SSN_TRY(cg_product_step(c, v, c->slots + k, vb, c->trace_dev + 3 * k, &n_rr, &p_pending));
         SSN_HIP(c, launch_cg_step2(c->d.dtype, v, c->slots + k, c->slots + k + 1, c->red_a, n_rr, theta,
-                                   c->trace_dev + 3 * k, c->red_c, p_pending, vb, c->st));
+                                   c->trace_dev + 3 * k, c->red_c, p_pending, vb, c->st, c->d.lambda));
     }
-    // CSR path: the best iterate may still live only in p (it is copied lazily)
-    if (!is_dense(c) && T > 0) SSN_HIP(c, launch_cg_finish(c->d.dtype, v, c->slots + T, vb, c->st));
+    if (!is_dense(c)) {
+        // the best iterate may still live only in p (it is copied lazily); then all coordinates of the direction
+        if (T > 0) SSN_HIP(c, launch_cg_finish(c->d.dtype, v, c->slots + T, vb, c->st));
+        SSN_HIP(c, launch_cg_expand(c->d.dtype, c->d.p, c->K, G, c->d.ldw, P_out, c->d.ldw, c->slots + T, c->cg_pb,
+                                    c->csc_samp.cols, c->csc_samp.ncols, c->st));
+    }
     return SSN_OK;
 }
 

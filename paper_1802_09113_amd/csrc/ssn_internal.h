@@ -152,15 +152,25 @@ struct CscView {
     int32_t *count_dev = nullptr;
     int64_t cap = 0, cap_row = 0, cap_val = 0, cap_piece = 0, cap_pcol = 0, cap_part = 0, cap_off = 0, cap_in = 0,
             cap_flag = 0, cap_pid = 0;
+    // support of the view (csc_build with support = true): the ncols distinct columns in ascending order, the
+    // selected rows as a CSR matrix in those coordinates -- row pointers `off`, column positions `ccol`, values
+    // `val_in`, all in the row order of the selection -- and the pieces' column positions
+    bool has_support = false;
+    int32_t ncols = 0;
+    int32_t *cols = nullptr;         // ncols
+    int32_t *ccol = nullptr;         // nnz
+    int32_t *piece_cpos = nullptr;   // npieces + 4 (sentinels -1)
+    int64_t cap_cols = 0, cap_ccol = 0, cap_pcpos = 0;
 };
 hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t *colidx, const void *vals,
-                     const int32_t *S, int64_t nrows, int64_t p, int K, hipStream_t st);
+                     const int32_t *S, int64_t nrows, int64_t p, int K, hipStream_t st, bool support = false);
 void csc_free(CscView *v);
 void csc_free_scratch(CscView *v);
 // out += coef * X_view^T U (U rows indexed like the view's row selection); slot (nullable): multiply by
 // -slot->alpha and do nothing once that CG loop has ended
+// support_coords: `out` has one row per distinct column of the view (ncols rows) instead of one per column
 hipError_t launch_csc_apply(int dtype, const CscView &v, int K, int KP, const void *U, double coef, void *out, int64_t ldo,
-                            const CgSlot *slot, const int32_t *skip, hipStream_t st);
+                            const CgSlot *slot, const int32_t *skip, hipStream_t st, bool support_coords = false);
 
 // ---- unit-column-norm preprocessing (preprocess.hip); synchronises the stream ------------------------
 hipError_t normalize_columns(int layout, int dtype, int64_t n, int64_t p, void *X, int64_t ldx, const int32_t *rowptr,
@@ -178,6 +188,11 @@ struct CgSlot {          // state before product k
     double alpha;        // step length of product k, where a kernel of its own computes it (CSR path)
     int32_t best_cur;    // CSR path: the best iterate is the CURRENT p and has not been copied to p_best yet
     int32_t pad;
+    // CSR path: the CG vectors are kept on the columns the sample touches only.  On every other coordinate j
+    // H_S is lambda I, so r_j, s_j, p_j stay multiples of g_j; the multipliers and the sum of g_j^2 over those
+    // coordinates (goff; 0 on the dense paths, where the terms below vanish) are all that is needed of them.
+    double goff;
+    double rho, sigma, pi, pibest;   // r_j = rho g_j, s_j = sigma g_j, p_j = pi g_j, p_best_j = pibest g_j
 };
 
 struct CgVecs {
@@ -190,12 +205,20 @@ struct CgVecs {
 
 // ss_part (nullable) receives the same partials again: s_0 = -g
 hipError_t launch_cg_init(int dtype, const CgVecs &v, double *gg_part, double *ss_part, int blocks, hipStream_t st);
-hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0, hipStream_t st);
+// gg_full_part (nullable): partials of g.g over ALL coordinates when gg_part covers the sample's columns only
+hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0, hipStream_t st,
+                                const double *gg_full_part = nullptr, int n_full = 0);
+// CG on the support of the sample: the vectors of v (ld = K, v.p = ncols rows) start from the rows cols[] of G
+hipError_t launch_cg_init_support(int dtype, const CgVecs &v, const void *G, int64_t ldg, const int32_t *cols,
+                                  double *gg_part, double *ss_part, int blocks, hipStream_t st);
+// P_out = fin->pibest * G everywhere, then rows cols[] of it = the rows of pb (ncols x K, ld = K)
+hipError_t launch_cg_expand(int dtype, int64_t p, int K, const void *G, int64_t ldg, void *P_out, int64_t ldp,
+                            const CgSlot *fin, const void *pb, const int32_t *cols, int64_t ncols, hipStream_t st);
 // ss_part (nullable): one partial of s.s per block for the new direction; update_p: also p += cur->alpha * s,
 // and p_best is then kept lazily (CgSlot::best_cur): launch_cg_finish after the last product completes it
 hipError_t launch_cg_step2(int dtype, const CgVecs &v, const CgSlot *cur, CgSlot *next, const double *rr_part,
                            int n_rr, double theta, double *trace_k, double *ss_part, bool update_p, int blocks,
-                           hipStream_t st);
+                           hipStream_t st, double lambda = 0.0);
 // CSR path, lines 7-9 in pieces: cur->alpha from the partials of sum_i z_i . u_i and of s.s (one block); then the
 // sparse part of r -= alpha H s goes through launch_csr_scatter and the dense part, r -= alpha lambda s with the
 // partials of the new r.r, through launch_cg_r_update

@@ -528,11 +528,23 @@ hipError_t launch_cg_init(int dtype, const CgVecs &v, double *gg_part, double *s
     return hipGetLastError();
 }
 
-__global__ __launch_bounds__(VEC_BLOCK) void cg_init_state_kernel(const double *gg_part, int nparts, CgSlot *slot0)
+__global__ __launch_bounds__(VEC_BLOCK) void cg_init_state_kernel(const double *gg_part, int nparts, CgSlot *slot0,
+                                                                   const double *gg_full_part, int n_full)
 {
-    const double gg = sum_parts(gg_part, nparts);
+    const double gg_in = sum_parts(gg_part, nparts);
+    double goff = 0.0;
+    if (gg_full_part) {
+        goff = sum_parts(gg_full_part, n_full) - gg_in;
+        if (!(goff > 0.0)) goff = 0.0;
+    }
+    const double gg = gg_in + goff;
     if (threadIdx.x == 0) {
         CgSlot s;
+        s.goff = goff;
+        s.rho = -1.0;
+        s.sigma = -1.0;
+        s.pi = 0.0;
+        s.pibest = -1.0;
         s.rr = gg;
         s.rbest = sqrt(gg);
         s.gnorm = sqrt(gg);
@@ -547,9 +559,91 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_init_state_kernel(const double *
     }
 }
 
-hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0, hipStream_t st)
+hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0, hipStream_t st,
+                                const double *gg_full_part, int n_full)
 {
-    hipLaunchKernelGGL(cg_init_state_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, gg_part, nparts, slot0);
+    hipLaunchKernelGGL(cg_init_state_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, gg_part, nparts, slot0, gg_full_part, n_full);
+    return hipGetLastError();
+}
+
+// lines 1-5 on the columns the sample touches: row t of the vectors is row cols[t] of -g
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void cg_init_support_kernel(CgVecs v, const T *G, int64_t ldg, const int32_t *cols,
+                                                                     double *gg_part, double *ss_part)
+{
+    const int64_t total = v.p * v.K;
+    T *pv = (T *)v.pv, *r = (T *)v.r, *s = (T *)v.s, *pb = (T *)v.pbest;
+    double local = 0.0;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int64_t t = e / v.K;
+        const int c = (int)(e - t * v.K);
+        const T gv = G[(int64_t)cols[t] * ldg + c];
+        pv[e] = T(0);
+        r[e] = -gv;
+        s[e] = -gv;
+        pb[e] = -gv;
+        local += (double)gv * (double)gv;
+    }
+    const double sum = block_sum(local);
+    if (threadIdx.x == 0) {
+        gg_part[blockIdx.x] = sum;
+        if (ss_part) ss_part[blockIdx.x] = sum;
+    }
+}
+
+hipError_t launch_cg_init_support(int dtype, const CgVecs &v, const void *G, int64_t ldg, const int32_t *cols,
+                                  double *gg_part, double *ss_part, int blocks, hipStream_t st)
+{
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(cg_init_support_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, (const float *)G, ldg, cols,
+                           gg_part, ss_part);
+    else
+        hipLaunchKernelGGL(cg_init_support_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, (const double *)G, ldg,
+                           cols, gg_part, ss_part);
+    return hipGetLastError();
+}
+
+// The direction on all coordinates: pibest * g where the sample has no entry, the CG vector's rows elsewhere.
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void cg_expand_fill_kernel(int64_t p, int K, const T *G, int64_t ldg, T *P, int64_t ldp,
+                                                                    const CgSlot *fin)
+{
+    const double pibest = fin->pibest;
+    const int64_t total = p * K;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK)
+        P[off_of(e, K, ldp)] = (T)(pibest * (double)G[off_of(e, K, ldg)]);
+}
+
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void cg_expand_rows_kernel(int K, T *P, int64_t ldp, const T *pb, const int32_t *cols,
+                                                                    int64_t ncols)
+{
+    const int64_t total = ncols * K;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int64_t t = e / K;
+        const int c = (int)(e - t * K);
+        P[(int64_t)cols[t] * ldp + c] = pb[e];
+    }
+}
+
+hipError_t launch_cg_expand(int dtype, int64_t p, int K, const void *G, int64_t ldg, void *P_out, int64_t ldp,
+                            const CgSlot *fin, const void *pb, const int32_t *cols, int64_t ncols, hipStream_t st)
+{
+    const int b1 = vec_blocks(p * K) * 4 > 4096 ? 4096 : vec_blocks(p * K) * 4;
+    const int b2 = vec_blocks(ncols * K) * 4 > 4096 ? 4096 : vec_blocks(ncols * K) * 4;
+    if (dtype == SSN_F32) {
+        hipLaunchKernelGGL(cg_expand_fill_kernel<float>, dim3(b1), dim3(VEC_BLOCK), 0, st, p, K, (const float *)G, ldg,
+                           (float *)P_out, ldp, fin);
+        if (ncols > 0)
+            hipLaunchKernelGGL(cg_expand_rows_kernel<float>, dim3(b2), dim3(VEC_BLOCK), 0, st, K, (float *)P_out, ldp,
+                               (const float *)pb, cols, ncols);
+    } else {
+        hipLaunchKernelGGL(cg_expand_fill_kernel<double>, dim3(b1), dim3(VEC_BLOCK), 0, st, p, K, (const double *)G, ldg,
+                           (double *)P_out, ldp, fin);
+        if (ncols > 0)
+            hipLaunchKernelGGL(cg_expand_rows_kernel<double>, dim3(b2), dim3(VEC_BLOCK), 0, st, K, (double *)P_out, ldp,
+                               (const double *)pb, cols, ncols);
+    }
     return hipGetLastError();
 }
 
@@ -557,7 +651,7 @@ hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0
 template <typename T>
 __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgSlot *cur, CgSlot *next,
                                                               const double *rr_part, int n_rr, double theta,
-                                                              double *trace_k, double *ss_part, bool update_p)
+                                                              double *trace_k, double *ss_part, bool update_p, double lambda)
 {
     // the first element of every thread is fetched before anything waits: on the small blocks of the dense
     // workloads that is the only one, and the kernel is then two dependent round trips instead of three
@@ -579,7 +673,10 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgS
         }
         return;
     }
-    const double rr_new = sum_parts(rr_part, n_rr);
+    // coordinates outside the sample's columns (goff > 0 on the CSR path only): r_j = rho g_j there
+    const double rho_n = c.rho - c.alpha * lambda * c.sigma;
+    const double pi_n = c.pi + c.alpha * c.sigma;
+    const double rr_new = sum_parts(rr_part, n_rr) + rho_n * rho_n * c.goff;
     const double rnorm = sqrt(rr_new);
     const bool better = rnorm <= c.rbest;
     const bool stop = rnorm <= theta * c.gnorm;
@@ -639,20 +736,26 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgS
         n.alpha = 0.0;
         n.best_cur = update_p ? (better ? 1 : 0) : 0;
         n.pad = 0;
+        n.goff = c.goff;
+        n.rho = rho_n;
+        n.pi = pi_n;
+        n.pibest = better ? pi_n : c.pibest;
+        n.sigma = stop ? c.sigma : rho_n + b * c.sigma;
         *next = n;
         if (trace_k) trace_k[1] = rnorm;
     }
 }
 
 hipError_t launch_cg_step2(int dtype, const CgVecs &v, const CgSlot *cur, CgSlot *next, const double *rr_part, int n_rr,
-                           double theta, double *trace_k, double *ss_part, bool update_p, int blocks, hipStream_t st)
+                           double theta, double *trace_k, double *ss_part, bool update_p, int blocks, hipStream_t st,
+                           double lambda)
 {
     if (dtype == SSN_F32)
         hipLaunchKernelGGL(cg_step2_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, cur, next, rr_part, n_rr, theta,
-                           trace_k, ss_part, update_p);
+                           trace_k, ss_part, update_p, lambda);
     else
         hipLaunchKernelGGL(cg_step2_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, cur, next, rr_part, n_rr,
-                           theta, trace_k, ss_part, update_p);
+                           theta, trace_k, ss_part, update_p, lambda);
     return hipGetLastError();
 }
 
@@ -682,7 +785,7 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_alpha_kernel(CgSlot *cur, const 
     const CgSlot c = *cur;
     if (c.done) return;
     const double zu = sum_parts(zu_part, n_zu);
-    const double ss = sum_parts(ss_part, n_ss);
+    const double ss = sum_parts(ss_part, n_ss) + c.sigma * c.sigma * c.goff;
     const double sHs = scale * zu + lambda * ss;
     if (threadIdx.x != 0) return;
     if (!(sHs > 0.0)) {                      // not positive definite in floating point: stop, keep p_best

@@ -119,6 +119,69 @@ def test_csr_cg_best_iterate_when_the_residual_goes_up_and_down():
     pair.close()
 
 
+def _small_csr(n, p, C, seed, empty_rows):
+    """Seeded CSR stand-in: 1-6 entries per row at random columns, rows in empty_rows without entries."""
+    g = np.random.default_rng(seed)
+    rowptr = [0]
+    cols, vals = [], []
+    for i in range(n):
+        k = 0 if i in empty_rows else int(g.integers(1, 7))
+        c = np.sort(g.choice(p, size=k, replace=False))
+        cols.extend(c.tolist())
+        vals.extend(g.standard_normal(k).tolist())
+        rowptr.append(len(cols))
+    labels = g.integers(0, C, size=n).astype(np.int32)
+    return {"name": "small_csr", "layout": "csr", "n": n, "p": p, "C": C, "K": C - 1, "lam": 1e-2,
+            "rowptr": np.array(rowptr, dtype=np.int64), "colidx": np.array(cols, dtype=np.int32),
+            "vals": np.array(vals, dtype=np.float64), "labels": labels, "nnz": len(cols)}
+
+
+@pytest.mark.parametrize("ldw", [None, 8], ids=["packed", "padded_blocks"])
+def test_csr_cg_keeps_its_vectors_on_the_sample_columns(ldw):
+    # On the CSR path Alg. 2 runs on the columns the sample touches; every other coordinate follows g through
+    # three scalars.  Cases: a sample that touches a few of the columns, one whose rows are all empty (H_S =
+    # lambda I, the direction is -g / lambda after one product), one that touches every column, and a sample
+    # with a repeated row.  Each is followed against the oracle, which knows nothing of this.
+    n, p, C = 300, 500, 4
+    empty = set(range(0, 40))
+    d = _small_csr(n, p, C, seed=77, empty_rows=empty)
+    pair = Pair(d, F64, ldw=ldw)
+    Wh, Wd = pair.block(synth.probe(p, C - 1, sub=3, scale=0.2))
+    G_ref, _ = pair.oracle.gradient(Wh)
+    Gh, Gd = pair.block(G_ref)
+    samples = {
+        "few_columns": np.array([50, 60, 70, 80, 90, 100], dtype=np.int32),
+        "empty_rows_only": np.array([1, 5, 9, 30], dtype=np.int32),
+        "every_column": np.arange(n, dtype=np.int32),
+        "repeated_row": np.array([45, 45, 200, 45, 7, 210], dtype=np.int32),
+    }
+    touched = np.unique(d["colidx"]).size
+    for name, S in samples.items():
+        # budgets below the rank of the sampled term (4 distinct rows x 3 classes in the last case): past
+        # convergence the trajectory is rounding noise on both sides
+        for theta, T in ((1e-30, 8 if name == "repeated_row" else 12), (1e-3, 40), (1e-30, 0)):
+            if name == "empty_rows_only" and theta == 1e-30 and T > 0:
+                theta = 1e-10        # the residual after the one product is rounding noise: stop there on both sides
+            print(f"[case] csr support cg {name} theta={theta} T={T} ldw={ldw}", flush=True)
+            pair.gpu.ssn_hess_prepare(Wd, pair.idx(S))
+            ref = pair.oracle.cg(Wh, S, Gh, theta, T)
+            out = pair.gpu.ssn_cg(Gd, theta, T)
+            torch.cuda.synchronize()
+            assert out["iters"] == ref["iters"]
+            assert out["flags"] == ref["flags"]
+            np.testing.assert_allclose(out["alpha"], ref["alpha"], rtol=1e-8)
+            assert rel_err(pair.host(out["p"]), ref["p"]) <= 1e-8
+            if name == "empty_rows_only":
+                if T > 0:
+                    assert out["iters"] == 1 and out["rel_res"] <= 1e-14
+                    assert rel_err(pair.host(out["p"]), -Gh / d["lam"]) <= 1e-12
+                continue
+            np.testing.assert_allclose(out["rnorm"], ref["rnorm"], rtol=1e-8)
+            assert rel_scalar(out["rel_res"], ref["rel_res"]) <= 1e-8
+    assert touched < p          # some columns are touched by no row at all: always outside the support
+    pair.close()
+
+
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 def test_cg_zero_budget_and_zero_gradient(tiny, dtype):
     pair = Pair(tiny, dtype)
