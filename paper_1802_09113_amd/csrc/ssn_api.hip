@@ -41,6 +41,9 @@ struct ssn_ctx {
     int32_t *hit_part = nullptr;
     int wave_parts = 0;
     double *red_a = nullptr, *red_b = nullptr, *red_c = nullptr;
+    double *red_sq = nullptr;                  // partials of ||M||^2 left by the kernel that made the block sq_for
+    const void *sq_for = nullptr;
+    int n_sq = 0;
     double *scal_dev = nullptr;
     int32_t *int_dev = nullptr;
     double *host_pin = nullptr;   // pinned staging for scalar results
@@ -305,6 +308,12 @@ int enqueue_objective_value(ssn_ctx *c, const void *W, int nparts, int slot, dou
         if (mirrored) *mirrored = c->f_host_dev != nullptr;
         return SSN_OK;
     }
+    if (c->sq_for == W && c->n_sq > 0) {         // the kernel that wrote W left the partials of ||W||^2
+        c->sq_for = nullptr;
+        SSN_HIP(c, launch_combine(c->loss_part, nparts, scale, c->red_sq, c->n_sq, 0.5 * c->d.lambda, c->scal_dev + slot,
+                                  c->st));
+        return SSN_OK;
+    }
     const int vb = vec_blocks(c->d.p * (int64_t)c->K);
     SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, W, c->d.ldw, W, c->d.ldw, c->red_a, vb, nullptr, c->st));
     SSN_HIP(c, launch_combine(c->loss_part, nparts, scale, c->red_a, vb, 0.5 * c->d.lambda, c->scal_dev + slot,
@@ -523,7 +532,7 @@ int ssn_destroy(ssn_ctx *c)
 {
     if (!c) return SSN_E_INVALID_ARG;
     (void)hipStreamSynchronize(c->st);
-    void *dev[] = {c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->red_c, c->scal_dev, c->int_dev,
+    void *dev[] = {c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->red_c, c->red_sq, c->scal_dev, c->int_dev,
                    c->cg_p, c->cg_r, c->cg_s, c->cg_pb, c->trial, c->grad, c->grad_next, c->dir, c->slots, c->trace_dev};
     for (void *p : dev)
         if (p) (void)hipFree(p);
@@ -584,6 +593,7 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
     CREATE_HIP(hipMalloc((void **)&c->red_a, sizeof(double) * RED_MAX_PARTS));
     CREATE_HIP(hipMalloc((void **)&c->red_b, sizeof(double) * RED_MAX_PARTS));
     CREATE_HIP(hipMalloc((void **)&c->red_c, sizeof(double) * RED_MAX_PARTS));
+    CREATE_HIP(hipMalloc((void **)&c->red_sq, sizeof(double) * RED_MAX_PARTS));
     CREATE_HIP(hipMalloc((void **)&c->scal_dev, sizeof(double) * 8));
     CREATE_HIP(hipMalloc((void **)&c->int_dev, sizeof(int32_t) * 8));
     CREATE_HIP(hipHostMalloc((void **)&c->host_pin, 4096));
@@ -711,8 +721,11 @@ int ssn_hessvec(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS, const v
 }
 
 // every launch of Alg. 2; the final state waits in slots[T]
-static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out)
+// n_slope (nullable): on the CSR path the partials of <P_out, G> over the sample's columns are left in red_a,
+// *n_slope of them (the rest of the product is CgSlot::pibest * CgSlot::goff); 0 where they are not made
+static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out, int *n_slope = nullptr)
 {
+    if (n_slope) *n_slope = 0;
     if (!c->cg_p) {
         SSN_TRY(vec_bytes_alloc(c, &c->cg_p));
         SSN_TRY(vec_bytes_alloc(c, &c->cg_r));
@@ -778,7 +791,7 @@ static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *
         // the best iterate may still live only in p (it is copied lazily); then all coordinates of the direction
         if (T > 0) SSN_HIP(c, launch_cg_finish(c->d.dtype, v, c->slots + T, vb, c->st));
         SSN_HIP(c, launch_cg_expand(c->d.dtype, c->d.p, c->K, G, c->d.ldw, P_out, c->d.ldw, c->slots + T, c->cg_pb,
-                                    c->csc_samp.cols, c->csc_samp.ncols, c->st));
+                                    c->csc_samp.cols, c->csc_samp.ncols, n_slope ? c->red_a : nullptr, n_slope, c->st));
     }
     return SSN_OK;
 }
@@ -843,7 +856,17 @@ int ssn_linesearch(ssn_ctx *c, const void *W, const void *P, const void *G, doub
 int trial_enqueue(ssn_ctx *c, const void *W, const void *P, double alpha, void *G_first, bool *mirrored)
 {
     if (!c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
-    SSN_HIP(c, launch_axpy(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, c->trial, c->d.ldw, c->st));
+    c->sq_for = nullptr;
+    if (c->d.p * (int64_t)c->K > OBJ_VALUE_ELEMS) {
+        // a large block: ||trial||^2 for the regulariser comes out of the pass that writes the trial point
+        const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+        SSN_HIP(c, launch_axpy_sq(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, c->trial, c->d.ldw, c->red_sq,
+                                  vb, c->st));
+        c->sq_for = c->trial;
+        c->n_sq = vb;
+    } else {
+        SSN_HIP(c, launch_axpy(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, c->trial, c->d.ldw, c->st));
+    }
     if (G_first) return gradient_impl(c, c->trial, G_first, nullptr, true, nullptr, 0, mirrored);
     return objective_enqueue(c, c->trial, mirrored);
 }
@@ -980,14 +1003,18 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         SOLVE_HIP(mark(E[1]));
         SOLVE_TRY(hess_prepare_impl(c, W, pr->S_all + (int64_t)k * pr->nS, pr->nS, false));
         SOLVE_HIP(mark(E[2]));
-        SOLVE_TRY(cg_enqueue(c, c->grad, pr->theta, pr->T, c->dir));
+        // CSR with a device mapping of the host block: CG leaves the slope's partials (n_slope > 0)
+        int n_slope = 0;
+        SOLVE_TRY(cg_enqueue(c, c->grad, pr->theta, pr->T, c->dir, c->pub_dev ? &n_slope : nullptr));
         // F(x_k), <dir, g> and the final CG state (which carries ||g||) reach the host through host-visible
         // memory written by one small kernel; without a device mapping of it, through two copies
-        SOLVE_HIP(launch_dot_part(c->d.dtype, c->d.p, c->K, c->dir, c->d.ldw, c->grad, c->d.ldw, c->red_a, vb, nullptr,
-                                  c->st));
+        if (n_slope == 0)
+            SOLVE_HIP(launch_dot_part(c->d.dtype, c->d.p, c->K, c->dir, c->d.ldw, c->grad, c->d.ldw, c->red_a, vb, nullptr,
+                                      c->st));
         double *pub = c->pub_dev ? c->pub_host : c->host_pin;
         if (c->pub_dev) {
-            SOLVE_HIP(launch_solve_publish(c->red_a, vb, c->scal_dev, c->slots + pr->T, c->scal_dev + 1, c->pub_dev, c->st));
+            SOLVE_HIP(launch_solve_publish(c->red_a, n_slope ? n_slope : vb, c->scal_dev, c->slots + pr->T, c->scal_dev + 1,
+                                           c->pub_dev, n_slope > 0, c->st));
         } else {
             SOLVE_HIP(launch_combine(c->red_a, vb, 1.0, nullptr, 0, 0.0, c->scal_dev + 1, c->st));
             SOLVE_HIP(hipMemcpyAsync(pub, c->scal_dev, 2 * sizeof(double), hipMemcpyDeviceToHost, c->st));

@@ -115,6 +115,9 @@ hipError_t launch_dot_part(int dtype, int64_t p, int K, const void *A, int64_t l
 // Y = alpha * X + Z (Y may alias Z)
 hipError_t launch_axpy(int dtype, int64_t p, int K, double alpha, const void *X, int64_t ldx_,
                        const void *Z, int64_t ldz, void *Y, int64_t ldy, hipStream_t st);
+// Y = alpha X + Z with one partial of ||Y||^2 per block (blocks <= RED_MAX_PARTS)
+hipError_t launch_axpy_sq(int dtype, int64_t p, int K, double alpha, const void *X, int64_t ldx, const void *Z, int64_t ldz,
+                          void *Y, int64_t ldy, double *sq_part, int blocks, hipStream_t st);
 // *out = scale * sum(a[0..na)) + coef * sum(b[0..nb))   (single block, fixed order)
 // *out (and *out_host, nullable, host-visible) = scale * sum(loss_part) + half_lambda * ||W||_F^2 ; one block, for
 // blocks of up to OBJ_VALUE_ELEMS elements
@@ -124,7 +127,7 @@ constexpr int64_t OBJ_VALUE_ELEMS = 32768;
 hipError_t launch_combine(const double *a, int na, double scale, const double *b, int nb, double coef,
                           double *out, hipStream_t st);
 hipError_t launch_solve_publish(const double *slope_part, int n, const double *f_dev, const CgSlot *fin, double *slope_dev,
-                                double *host_out, hipStream_t st);
+                                double *host_out, bool support_only, hipStream_t st);
 // streaming read of `bytes` (multiple of 16, 16-byte aligned); one checksum partial per block
 hipError_t launch_stream_read(const void *src, int64_t bytes, double *part, int blocks, hipStream_t st);
 hipError_t launch_sum_int(const int32_t *a, int na, int32_t *out, hipStream_t st);
@@ -212,8 +215,10 @@ hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0
 hipError_t launch_cg_init_support(int dtype, const CgVecs &v, const void *G, int64_t ldg, const int32_t *cols,
                                   double *gg_part, double *ss_part, int blocks, hipStream_t st);
 // P_out = fin->pibest * G everywhere, then rows cols[] of it = the rows of pb (ncols x K, ld = K)
+// dot_part (nullable): partials of <pb, rows cols[] of G>, *n_dot of them (<= RED_MAX_PARTS)
 hipError_t launch_cg_expand(int dtype, int64_t p, int K, const void *G, int64_t ldg, void *P_out, int64_t ldp,
-                            const CgSlot *fin, const void *pb, const int32_t *cols, int64_t ncols, hipStream_t st);
+                            const CgSlot *fin, const void *pb, const int32_t *cols, int64_t ncols, double *dot_part,
+                            int *n_dot, hipStream_t st);
 // ss_part (nullable): one partial of s.s per block for the new direction; update_p: also p += cur->alpha * s,
 // and p_best is then kept lazily (CgSlot::best_cur): launch_cg_finish after the last product completes it
 hipError_t launch_cg_step2(int dtype, const CgVecs &v, const CgSlot *cur, CgSlot *next, const double *rr_part,

@@ -317,6 +317,34 @@ __global__ __launch_bounds__(VEC_BLOCK) void axpy_kernel(int64_t p, int K, doubl
         Y[off_of(e, K, ldy)] = (T)(alpha * (double)X[off_of(e, K, ldx)] + (double)Z[off_of(e, K, ldz)]);
 }
 
+// the same, leaving one partial of ||Y||^2 per block: the objective at Y needs it and Y is in registers here
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void axpy_sq_kernel(int64_t p, int K, double alpha, const T *X, int64_t ldx,
+                                                             const T *Z, int64_t ldz, T *Y, int64_t ldy, double *sq_part)
+{
+    const int64_t total = p * K;
+    double local = 0.0;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
+        const T y = (T)(alpha * (double)X[off_of(e, K, ldx)] + (double)Z[off_of(e, K, ldz)]);
+        Y[off_of(e, K, ldy)] = y;
+        local += (double)y * (double)y;
+    }
+    const double sum = block_sum(local);
+    if (threadIdx.x == 0) sq_part[blockIdx.x] = sum;
+}
+
+hipError_t launch_axpy_sq(int dtype, int64_t p, int K, double alpha, const void *X, int64_t ldx_, const void *Z,
+                          int64_t ldz, void *Y, int64_t ldy, double *sq_part, int blocks, hipStream_t st)
+{
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(axpy_sq_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, p, K, alpha, (const float *)X, ldx_,
+                           (const float *)Z, ldz, (float *)Y, ldy, sq_part);
+    else
+        hipLaunchKernelGGL(axpy_sq_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, p, K, alpha, (const double *)X,
+                           ldx_, (const double *)Z, ldz, (double *)Y, ldy, sq_part);
+    return hipGetLastError();
+}
+
 hipError_t launch_axpy(int dtype, int64_t p, int K, double alpha, const void *X, int64_t ldx_, const void *Z,
                        int64_t ldz, void *Y, int64_t ldy, hipStream_t st)
 {
@@ -386,9 +414,12 @@ hipError_t launch_objective_value(int dtype, const double *loss_part, int nparts
 // <P, G> from its partials (also left in *slope_dev), F(x_k) from *f_dev and the final CG state, written to
 // host-visible memory (host_out: two doubles, then the CgSlot).  The caller only waits for the stream.
 __global__ __launch_bounds__(VEC_BLOCK) void solve_publish_kernel(const double *slope_part, int n, const double *f_dev,
-                                                                   const CgSlot *fin, double *slope_dev, double *host_out)
+                                                                   const CgSlot *fin, double *slope_dev, double *host_out,
+                                                                   int support_only)
 {
-    const double slope = sum_parts(slope_part, n);
+    // support_only: the partials cover the sample's columns; elsewhere the direction is pibest * g
+    double slope = sum_parts(slope_part, n);
+    if (support_only) slope += fin->pibest * fin->goff;
     if (threadIdx.x == 0) {
         *slope_dev = slope;
         host_out[0] = *f_dev;
@@ -399,9 +430,10 @@ __global__ __launch_bounds__(VEC_BLOCK) void solve_publish_kernel(const double *
 }
 
 hipError_t launch_solve_publish(const double *slope_part, int n, const double *f_dev, const CgSlot *fin, double *slope_dev,
-                                double *host_out, hipStream_t st)
+                                double *host_out, bool support_only, hipStream_t st)
 {
-    hipLaunchKernelGGL(solve_publish_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, slope_part, n, f_dev, fin, slope_dev, host_out);
+    hipLaunchKernelGGL(solve_publish_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, slope_part, n, f_dev, fin, slope_dev, host_out,
+                       support_only ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -614,35 +646,44 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_expand_fill_kernel(int64_t p, in
         P[off_of(e, K, ldp)] = (T)(pibest * (double)G[off_of(e, K, ldg)]);
 }
 
+// rows cols[] of P = the rows of pb; dot_part (nullable): one partial per block of <pb, rows cols[] of G>
 template <typename T>
 __global__ __launch_bounds__(VEC_BLOCK) void cg_expand_rows_kernel(int K, T *P, int64_t ldp, const T *pb, const int32_t *cols,
-                                                                    int64_t ncols)
+                                                                    int64_t ncols, const T *G, int64_t ldg, double *dot_part)
 {
     const int64_t total = ncols * K;
+    double local = 0.0;
     for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
         const int64_t t = e / K;
         const int c = (int)(e - t * K);
-        P[(int64_t)cols[t] * ldp + c] = pb[e];
+        const int64_t col = cols[t];
+        const T v = pb[e];
+        P[col * ldp + c] = v;
+        if (dot_part) local += (double)v * (double)G[col * ldg + c];
+    }
+    if (dot_part) {
+        const double sum = block_sum(local);
+        if (threadIdx.x == 0) dot_part[blockIdx.x] = sum;
     }
 }
 
 hipError_t launch_cg_expand(int dtype, int64_t p, int K, const void *G, int64_t ldg, void *P_out, int64_t ldp,
-                            const CgSlot *fin, const void *pb, const int32_t *cols, int64_t ncols, hipStream_t st)
+                            const CgSlot *fin, const void *pb, const int32_t *cols, int64_t ncols, double *dot_part,
+                            int *n_dot, hipStream_t st)
 {
     const int b1 = vec_blocks(p * K) * 4 > 4096 ? 4096 : vec_blocks(p * K) * 4;
-    const int b2 = vec_blocks(ncols * K) * 4 > 4096 ? 4096 : vec_blocks(ncols * K) * 4;
+    const int b2 = vec_blocks(ncols * K);                  // <= RED_MAX_PARTS: one partial per block
+    if (n_dot) *n_dot = b2;
     if (dtype == SSN_F32) {
         hipLaunchKernelGGL(cg_expand_fill_kernel<float>, dim3(b1), dim3(VEC_BLOCK), 0, st, p, K, (const float *)G, ldg,
                            (float *)P_out, ldp, fin);
-        if (ncols > 0)
-            hipLaunchKernelGGL(cg_expand_rows_kernel<float>, dim3(b2), dim3(VEC_BLOCK), 0, st, K, (float *)P_out, ldp,
-                               (const float *)pb, cols, ncols);
+        hipLaunchKernelGGL(cg_expand_rows_kernel<float>, dim3(b2), dim3(VEC_BLOCK), 0, st, K, (float *)P_out, ldp,
+                           (const float *)pb, cols, ncols, (const float *)G, ldg, dot_part);
     } else {
         hipLaunchKernelGGL(cg_expand_fill_kernel<double>, dim3(b1), dim3(VEC_BLOCK), 0, st, p, K, (const double *)G, ldg,
                            (double *)P_out, ldp, fin);
-        if (ncols > 0)
-            hipLaunchKernelGGL(cg_expand_rows_kernel<double>, dim3(b2), dim3(VEC_BLOCK), 0, st, K, (double *)P_out, ldp,
-                               (const double *)pb, cols, ncols);
+        hipLaunchKernelGGL(cg_expand_rows_kernel<double>, dim3(b2), dim3(VEC_BLOCK), 0, st, K, (double *)P_out, ldp,
+                           (const double *)pb, cols, ncols, (const double *)G, ldg, dot_part);
     }
     return hipGetLastError();
 }
