@@ -328,34 +328,60 @@ template <typename T> __global__ __launch_bounds__(256) void csc_piece_kernel(Cs
         if (a.slot->done || a.slot->brk) return;
         coef *= -a.slot->alpha;
     }
+    // no lane leaves before the shuffles below: a lane without a piece (spare lanes of the wave, groups past the
+    // last piece) walks through them with an empty piece
     const int lane = threadIdx.x & 63;
     const int K = a.K, NS = 64 / K;
     const int s = lane / K, c = lane - s * K;
-    if (s >= NS) return;
     const int64_t pid = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * NS + s;
-    if (pid >= a.npieces) return;
+    const bool active = s < NS && pid < a.npieces;
     const T *val = (const T *)a.val;
     const T *U = (const T *)a.U;
-    const int64_t t0 = a.piece_start[pid], t1 = a.piece_start[pid + 1];
-    const int col = a.piece_col[pid];
-    const bool head = (pid == 0) || (a.piece_col[pid - 1] != col);
-    const bool more = a.piece_col[pid + 1] == col;
+    const int64_t t0 = active ? a.piece_start[pid] : 0, t1 = active ? a.piece_start[pid + 1] : 0;
+    const int col = active ? a.piece_col[pid] : 0;
+    const bool head = active && ((pid == 0) || (a.piece_col[pid - 1] != col));
+    const bool more = active && a.piece_col[pid + 1] == col;
+    // the result element this piece adds into (a whole column in one piece) is fetched now: its trip to memory
+    // then overlaps the gathers below instead of following them
+    T *o = (T *)a.out + (int64_t)col * a.ldo + c;
+    const T oval = (head && !more) ? *o : T(0);
+    // Entries are fetched K at a time, one per lane of the group (one coalesced load of row positions and one
+    // of values instead of K broadcast loads each), and handed round the group by lane shuffles; the gathers
+    // of U, four in flight, are then the only loads in the loop.  The groups of a wave have different piece
+    // lengths, so the loops run to the longest and the shorter groups add zeros.
     T a0 = 0, a1 = 0, a2 = 0, a3 = 0;
-    int64_t t = t0;
-    for (; t + 3 < t1; t += 4) {             // four independent gathers in flight
-        const int64_t r0 = a.row[t], r1 = a.row[t + 1], r2 = a.row[t + 2], r3 = a.row[t + 3];
-        const T v0 = val[t], v1 = val[t + 1], v2 = val[t + 2], v3 = val[t + 3];
-        const T u0 = U[r0 * a.KP + c], u1 = U[r1 * a.KP + c], u2 = U[r2 * a.KP + c], u3 = U[r3 * a.KP + c];
-        a0 += v0 * u0;
-        a1 += v1 * u1;
-        a2 += v2 * u2;
-        a3 += v3 * u3;
+    const int gbase = s * K;
+    const int len = (int)(t1 - t0);
+    int maxlen = len;
+    for (int off = 32; off > 0; off >>= 1) maxlen = max(maxlen, __shfl_xor(maxlen, off));
+    for (int b = 0; b < maxlen; b += K) {
+        const int mine = b + c;
+        const bool have = mine < len;
+        const int rmine = have ? a.row[t0 + mine] : 0;
+        const T vmine = have ? val[t0 + mine] : T(0);
+        const int nb = min(K, maxlen - b);                       // uniform over the wave
+        for (int j = 0; j < nb; j += 4) {
+            int r[4];
+            T v[4], u[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int src = gbase + ((j + k < K) ? j + k : 0);
+                r[k] = __shfl(rmine, src);
+                v[k] = __shfl(vmine, src);
+                if (j + k >= nb || b + j + k >= len) v[k] = T(0), r[k] = r[0];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) u[k] = U[(int64_t)r[k] * a.KP + c];
+            a0 += v[0] * u[0];
+            a1 += v[1] * u[1];
+            a2 += v[2] * u[2];
+            a3 += v[3] * u[3];
+        }
     }
-    for (; t < t1; ++t) a0 += val[t] * U[(int64_t)a.row[t] * a.KP + c];
     const T acc = (a0 + a1) + (a2 + a3);
+    if (!active) return;
     if (head && !more) {
-        T *o = (T *)a.out + (int64_t)col * a.ldo + c;
-        *o = (T)((double)*o + coef * (double)acc);
+        *o = (T)((double)oval + coef * (double)acc);
     } else {
         ((T *)a.piece_part)[pid * K + c] = acc;
     }
@@ -380,6 +406,8 @@ template <typename T> __global__ __launch_bounds__(256) void csc_combine_kernel(
     const bool head = (pid == 0) || (a.piece_col[pid - 1] != col);
     if (!head || a.piece_col[pid + 1] != col) return;
     const T *pp = (const T *)a.piece_part;
+    T *o = (T *)a.out + (int64_t)col * a.ldo + c;
+    const T oval = *o;                       // fetched before the partial sums, not after them
     T acc = pp[pid * K + c];
     for (int64_t j = pid + 1;; j += 4) {     // four pieces per round; the adds keep the piece order
         const bool m0 = a.piece_col[j] == col, m1 = m0 && a.piece_col[j + 1] == col;
@@ -392,8 +420,7 @@ template <typename T> __global__ __launch_bounds__(256) void csc_combine_kernel(
         acc += p3;
         if (!m3) break;
     }
-    T *o = (T *)a.out + (int64_t)col * a.ldo + c;
-    *o = (T)((double)*o + coef * (double)acc);
+    *o = (T)((double)oval + coef * (double)acc);
 }
 
 // out += coef * X_view^T U  (out already holds whatever the product is added to: lambda * M, or the CG
