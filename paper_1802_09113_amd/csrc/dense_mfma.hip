@@ -42,27 +42,37 @@ template <typename T, int VEC> struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; 
 // logarithm of alpha in [1, C].  On those ranges short fp64 routines (argument reduction + Taylor /
 // atanh series, errors of a few 1e-16) need far fewer registers than the general library calls, which
 // matters inside the MFMA kernels.
-__device__ __forceinline__ double exp_nonpos(double x)
+// `zero` is 0.0 that the compiler cannot see through (see opaque_zero): added to every coefficient it keeps the
+// sixteen 64-bit constants from being set up once before the caller's loop and held in registers across it.
+// The fp64 gradient kernel has no register for that; it would spill one, and a kernel that touches scratch
+// memory at all pays ~14 us per launch on this machine.  Adding 0.0 changes no value.
+__device__ __forceinline__ double exp_nonpos(double x, double zero)
 {
     if (x < -745.2) return 0.0;                                   // underflow, and -inf
-    const double n = rint(x * 1.4426950408889634);
-    double r = fma(n, -6.93147180369123816490e-01, x);            // x - n*ln2, ln2 split in two parts
-    r = fma(n, -1.90821492927058770002e-10, r);
-    double t = 1.0 / 6227020800.0;                                // sum_{k<=13} r^k / k!, |r| <= ln2/2
-    t = fma(t, r, 1.0 / 479001600.0);
-    t = fma(t, r, 1.0 / 39916800.0);
-    t = fma(t, r, 1.0 / 3628800.0);
-    t = fma(t, r, 1.0 / 362880.0);
-    t = fma(t, r, 1.0 / 40320.0);
-    t = fma(t, r, 1.0 / 5040.0);
-    t = fma(t, r, 1.0 / 720.0);
-    t = fma(t, r, 1.0 / 120.0);
-    t = fma(t, r, 1.0 / 24.0);
-    t = fma(t, r, 1.0 / 6.0);
+    const double n = rint(x * (1.4426950408889634 + zero));
+    double r = fma(n, -6.93147180369123816490e-01 + zero, x);     // x - n*ln2, ln2 split in two parts
+    r = fma(n, -1.90821492927058770002e-10 + zero, r);
+    double t = 1.0 / 6227020800.0 + zero;                         // sum_{k<=13} r^k / k!, |r| <= ln2/2
+    t = fma(t, r, 1.0 / 479001600.0 + zero);
+    t = fma(t, r, 1.0 / 39916800.0 + zero);
+    t = fma(t, r, 1.0 / 3628800.0 + zero);
+    t = fma(t, r, 1.0 / 362880.0 + zero);
+    t = fma(t, r, 1.0 / 40320.0 + zero);
+    t = fma(t, r, 1.0 / 5040.0 + zero);
+    t = fma(t, r, 1.0 / 720.0 + zero);
+    t = fma(t, r, 1.0 / 120.0 + zero);
+    t = fma(t, r, 1.0 / 24.0 + zero);
+    t = fma(t, r, 1.0 / 6.0 + zero);
     t = fma(t, r, 0.5);
     t = fma(t, r, 1.0);
     t = fma(t, r, 1.0);
     return ldexp(t, (int)n);
+}
+__device__ __forceinline__ double opaque_zero()
+{
+    double z = 0.0;
+    asm volatile("" : "+v"(z));
+    return z;
 }
 __device__ __forceinline__ double log_ge1(double a)
 {
@@ -84,8 +94,9 @@ __device__ __forceinline__ double log_ge1(double a)
     t = fma(t, s2, 1.0);
     return fma((double)k, 0.69314718055994530942, 2.0 * s * t);
 }
-__device__ __forceinline__ float t_exp(float x) { return expf(x); }
-__device__ __forceinline__ double t_exp(double x) { return exp_nonpos(x); }
+// TIGHT: the caller has no registers to spare (see exp_nonpos)
+template <bool TIGHT> __device__ __forceinline__ float t_exp(float x) { return expf(x); }
+template <bool TIGHT> __device__ __forceinline__ double t_exp(double x) { return exp_nonpos(x, TIGHT ? opaque_zero() : 0.0); }
 __device__ __forceinline__ float t_log(float x) { return logf(x); }
 __device__ __forceinline__ double t_log(double x) { return log_ge1(x); }
 
@@ -147,7 +158,7 @@ __device__ __forceinline__ float fast_rcp(float a)
 // Per-row work on ONE accumulator element of a 16-row block (K <= 16): the 16 lanes of a row group hold the
 // 16 class columns of sample row sv.  lab / pin are that row's label and this lane's probability,
 // loaded by the caller.  Returns U (ROW_GRAD: eq. (6) residual p - y; ROW_APPLY: eq. (12)).
-template <typename T, int MODE>
+template <typename T, int MODE, bool TIGHT = false>
 __device__ __forceinline__ T slot_epilogue(T z, const RowsArgs &a, int64_t sv, int q, int lab, T pin, double &loss,
                                            double &lprod, int &hits)
 {
@@ -181,9 +192,9 @@ __device__ __forceinline__ T slot_epilogue(T z, const RowsArgs &a, int64_t sv, i
     const bool ce = ref_lane ? (q <= K) : cv;
     const T zmax = row16_max(ce ? zz : NEG);
     const T Mx = ref_lane ? zmax : fmax(T(0), zmax);
-    const T e = ce ? t_exp(zz - Mx) : T(0);
+    const T e = ce ? t_exp<TIGHT>(zz - Mx) : T(0);
     T alpha = row16_sum(e);
-    if (!ref_lane) alpha += t_exp(-Mx);
+    if (!ref_lane) alpha += t_exp<TIGHT>(-Mx);
     const T inv = fast_rcp(alpha);
     if constexpr (MODE == ROW_PREP) {
         ((T *)a.UP)[sv * a.KP + q] = (valid && cv) ? e * inv : T(0);
@@ -283,11 +294,11 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
         T se = 0;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            e[nb] = cv[nb] ? t_exp(z[nb] - Mx) : T(0);
+            e[nb] = cv[nb] ? t_exp<false>(z[nb] - Mx) : T(0);
             se += e[nb];
         }
         se = row16_sum(se);
-        const T alpha = t_exp(-Mx) + se;
+        const T alpha = t_exp<false>(-Mx) + se;
         if constexpr (MODE == ROW_PREP) {
             T *P = (T *)a.UP;
 #pragma unroll
@@ -356,7 +367,11 @@ __global__ __launch_bounds__(SPLIT ? 1024 : 64 * ROWS_WAVES_PER_BLOCK) void dens
     int hits = 0;
     const int64_t nblk = (a.nrows + 15) / 16;
     constexpr int STEP = 4 * VEC;     // features consumed per vector load (4 k-groups of VEC)
-    constexpr int UNR = 4;
+    // Loads in flight per trip.  A 16-wave workgroup leaves 128 registers per lane; with four vector loads and
+    // their W operands in flight some variants spilled, and a kernel that uses scratch memory at all pays
+    // ~14 us per launch on this machine, more than a whole sampled product: those variants take fewer.
+    constexpr bool EXPS = (MODE == ROW_OBJ || MODE == ROW_GRAD);      // fp64 exp / log routines in the epilogue
+    constexpr int UNR = !SPLIT ? 4 : (sizeof(T) == 8 && NB == 2 && EXPS) ? 1 : (sizeof(T) == 4 || NB == 2 || EXPS) ? 2 : 4;
 
     constexpr int RB = PAIR ? 2 : 1;
     for (int64_t rb0 = wave * RB; rb0 < nblk; rb0 += nwaves * RB) {
@@ -738,6 +753,11 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     T *zpart = wl + ((size_t)ws * K + VEC - 1) / VEC * VEC;  // MAXW x 4 x 64 partial margins (16-byte aligned)
     T *zfull = zpart + (size_t)MAXW * 256 * (HAS_C ? 1 : 2); // U of the block (modes with a transposed product)
     T *scr = zfull + 256 + (size_t)w * 16 * STR;             // wave-private transposition scratch
+    // The fp64 multi-wave kernels with a transposed product have no register to spare, and the running loss sum
+    // and alpha product are touched once per row block by four of the waves: they live in LDS there (a kernel
+    // that spills even a few registers uses scratch memory, which costs ~14 us per launch on this machine).
+    constexpr bool LDS_ACC = HAS_C && sizeof(T) == 8 && MAXW > 1;
+    double *acc_l = (double *)(zfull + 256 + (size_t)(HAS_C ? blockDim.x >> 6 : 0) * 16 * STR) + (w & 3) * 128 + lane;
 
     const T *X = (const T *)a.X;
     const int fs = w * fw;
@@ -768,12 +788,15 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     auto load_one = [&](const T *xbase, int64_t room, int j, pack(&x)[NLD]) {
         if (LF * j + VEC <= room) x[j] = *(const pack *)(xbase + LF * j);
     };
+    // this lane's elements LF * j + m of the tile are inside the wave's slice for LF * j + m < nval (one 32-bit
+    // register against constants: 64-bit feature indices here cost a register pair per load)
+    const int nval = (int)(fend - fs) - VEC * g;
     auto mask_block = [&](pack(&x)[NLD]) {
+        const int nv = nval;
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
-            const int64_t f = fs + LF * j + VEC * g;
 #pragma unroll
-            for (int m = 0; m < VEC; ++m) x[j].v[m] = (f + m < fend) ? x[j].v[m] : T(0);
+            for (int m = 0; m < VEC; ++m) x[j].v[m] = (LF * j + m < nv) ? x[j].v[m] : T(0);
         }
     };
 
@@ -910,6 +933,12 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
 #pragma unroll
     for (int t = 0; t < (HAS_C ? NT : 1); ++t) G[t] = v4{0, 0, 0, 0};
     double loss = 0.0, lprod = 1.0;         // sum of the row terms without log(alpha); product of the alphas
+    if constexpr (LDS_ACC) {
+        if (w < 4) {
+            acc_l[0] = 0.0;
+            acc_l[64] = 1.0;
+        }
+    }
     int hits = 0;
     int it = 0;
 
@@ -958,25 +987,29 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
         // phase A (fp32: two accumulators break the dependent MFMA chain; fp64 has no registers to spare)
         constexpr bool TWO_ACC = sizeof(T) == 4;
         v4 z0 = v4{0, 0, 0, 0}, z1 = v4{0, 0, 0, 0};
-        // W operands come from LDS two steps ahead of the MFMAs that use them (a ring of three register sets)
-        T bq[3][VEC];
+        // W operands come from LDS ahead of the MFMAs that use them, through a ring of register sets: two steps
+        // ahead where registers allow, one step (a step is VEC MFMAs, longer than an LDS read) in the fp64
+        // kernels with a transposed product, which have none to spare
+        constexpr int AHEAD = (HAS_C && sizeof(T) == 8) ? 1 : 2;
+        constexpr int RING = AHEAD + 1;
+        T bq[RING][VEC];
         if constexpr (!ONE) {
 #pragma unroll
-            for (int jj = 0; jj < 2 && jj < NLD; ++jj)
+            for (int jj = 0; jj < AHEAD && jj < NLD; ++jj)
 #pragma unroll
                 for (int m = 0; m < VEC; ++m) bq[jj][m] = wlane[LF * jj + m];
         }
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             if constexpr (!ONE) {
-                if (j + 2 < NLD) {
+                if (j + AHEAD < NLD) {
 #pragma unroll
-                    for (int m = 0; m < VEC; ++m) bq[(j + 2) % 3][m] = wlane[LF * (j + 2) + m];
+                    for (int m = 0; m < VEC; ++m) bq[(j + AHEAD) % RING][m] = wlane[LF * (j + AHEAD) + m];
                 }
             }
 #pragma unroll
             for (int m = 0; m < VEC; ++m) {
-                const T b = ONE ? bd[j][m] : (cvalid ? bq[j % 3][m] : T(0));
+                const T b = ONE ? bd[j][m] : (cvalid ? bq[j % RING][m] : T(0));
                 if (TWO_ACC && ((j * VEC + m) & 1)) z1 = mfma16(xc[j].v[m], b, z1);
                 else z0 = mfma16(xc[j].v[m], b, z0);
             }
@@ -987,6 +1020,16 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
         }
         v4 z = TWO_ACC ? (z0 + z1) : z0, u = v4{0, 0, 0, 0};
         SSN_TICK(2);
+        // sub-block h of the tile goes through the wave's scratch for the transposed product: rows in, columns
+        // out.  The first sub-block is written here, before the per-row work, so that its registers are free
+        // during it (the fp64 gradient has none to spare).
+        auto scr_write = [&](int h) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                if (4 * h + jj < NLD) *(pack *)(scr + q * STR + LF * jj + VEC * g) = xc[4 * h + jj];
+                else *(pack *)(scr + q * STR + LF * jj + VEC * g) = pack{};
+        };
+        if constexpr (HAS_C) scr_write(0);
         if constexpr (MAXW == 1) {
 #pragma unroll
             for (int v = 0; v < 4; ++v)
@@ -1007,8 +1050,16 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
                         const T val = zp[v * 64 + lane + ww * 256];      // slots of absent waves hold stale data
                         sacc += (ww < nw) ? val : T(0);
                     }
-                    const T uv = slot_epilogue<T, MODE>(sacc, a, rb * 16 + d_row<T>(g, v), q, lab_pre[k], pin_pre[k],
-                                                        loss, lprod, hits);
+                    T uv;
+                    if constexpr (LDS_ACC) {
+                        double l = acc_l[0], lp = acc_l[64];
+                        uv = slot_epilogue<T, MODE, true>(sacc, a, rb * 16 + d_row<T>(g, v), q, lab_pre[k], pin_pre[k], l, lp, hits);
+                        acc_l[0] = l;
+                        acc_l[64] = lp;
+                    } else {
+                        uv = slot_epilogue<T, MODE>(sacc, a, rb * 16 + d_row<T>(g, v), q, lab_pre[k], pin_pre[k], loss, lprod,
+                                                    hits);
+                    }
                     if constexpr (HAS_C) zfull[v * 64 + lane] = uv;
                 }
             }
@@ -1026,13 +1077,6 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
             // sub-block h of the tile goes through the wave's scratch: rows in, columns out.  LDS serves a wave's
             // requests in order, so sub-block h+1 is written as soon as the reads of h are issued and its trip
             // overlaps the MFMAs of h.
-            auto scr_write = [&](int h) {
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
-                    if (4 * h + jj < NLD) *(pack *)(scr + q * STR + LF * jj + VEC * g) = xc[4 * h + jj];
-                    else *(pack *)(scr + q * STR + LF * jj + VEC * g) = pack{};
-            };
-            scr_write(0);
 #pragma unroll
             for (int h = 0; h < NSB; ++h) {
                 __builtin_amdgcn_wave_barrier();
@@ -1062,9 +1106,13 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     if constexpr (HAS_C) {
         // feature of accumulator element v of tile (h, m): fs + h*SBF + VEC*d_row(g, v) + m; the lane part of it
         // goes into one base pointer, the rest is a uniform offset
-        const int lane_row = d_row<T>(g, 0);                 // d_row(g, v) = lane_row + d_row(0, v)
-        T *pl = (T *)a.part + (int64_t)blockIdx.x * p * K + ((int64_t)fs + VEC * lane_row) * K + q;
-        const int64_t flane = fs + VEC * lane_row;
+        // (computed from an opaque copy of the lane's group so that nothing of it is prepared before the loop and
+        // carried through it: the fp64 kernels have no register for that, and would spill it to scratch memory)
+        int g_out = g, fs_out = fs;
+        asm volatile("" : "+v"(g_out), "+v"(fs_out));
+        const int lane_row = d_row<T>(g_out, 0);             // d_row(g, v) = lane_row + d_row(0, v)
+        T *pl = (T *)a.part + (int64_t)blockIdx.x * p * K + ((int64_t)fs_out + VEC * lane_row) * K + q;
+        const int64_t flane = fs_out + VEC * lane_row;
 #pragma unroll
         for (int h = 0; h < NSB; ++h) {
 #pragma unroll
@@ -1080,6 +1128,10 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     // four partials per workgroup: wave w < 4 owns the rows of accumulator element w
     if (w < 4) {
         if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_APPLY) {
+            if constexpr (LDS_ACC) {
+                loss = acc_l[0];
+                lprod = acc_l[64];
+            }
             if constexpr (MODE != ROW_APPLY) loss += log(lprod);
             for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off);
             if (lane == 0) a.loss_part[blockIdx.x * 4 + w] = loss;
@@ -1155,7 +1207,9 @@ template <typename T> static size_t fused_lds_bytes(int nw, int fw, int nld, int
     const size_t ws = ((size_t)(nw - 1) * fw + (size_t)nld * LF) | 1;
     size_t elems = (ws * K + VEC - 1) / VEC * VEC + (size_t)maxw * 256 * (has_c ? 1 : 2) + 256;
     if (has_c) elems += (size_t)nw * 16 * STR;
-    return elems * sizeof(T);
+    size_t bytes = elems * sizeof(T);
+    if (has_c && sizeof(T) == 8 && maxw > 1) bytes += 4 * 128 * sizeof(double);      // loss sums / alpha products of four waves
+    return bytes;
 }
 
 template <typename T> static bool fused_ok(const RowsArgs &a)

@@ -58,6 +58,8 @@ struct ssn_ctx {
     // CG / line-search vectors (p x ldw each)
     void *cg_p = nullptr, *cg_r = nullptr, *cg_s = nullptr, *trial = nullptr;
     void *grad = nullptr, *dir = nullptr;      // ssn_solve's gradient and direction
+    void *cg_hs = nullptr;                     // dense paths: H s, kept by recurrence (see finalize_cg_kernel)
+    double *cg_parts = nullptr;                // dense paths: 2 x 2 x RED_MAX_PARTS partials of r.r and r.(H s), double-buffered
     void *cg_pb = nullptr;                     // CSR: best iterate on the sample's columns (cg_pb_cap elements)
     int64_t cg_pb_cap = 0;
     void *grad_next = nullptr;                 // gradient at the first line-search trial (look-ahead of ssn_solve)
@@ -405,18 +407,25 @@ int hess_apply_impl(ssn_ctx *c, const void *V, void *HV, bool want_dot, int *ndo
     return transposed_product(c, c->S, c->nS, scale_sample(c), V, HV, want_dot, ndot, skip);
 }
 
-// Product k of the CG loop with lines 7-9 of Alg. 2 behind it: alpha, r -= alpha H s and, on the dense
-// paths, p += alpha s (the CSR path leaves that to step 2, *p_pending).  H s is never stored.  The
-// curvature s^T H s = scale * sum_i z_i . u_i + lambda * s.s comes from the per-wave partials the rows
-// kernel leaves in loss_part and the partials of s.s in red_c (n_ss of them).  On return red_a holds *n_rr
-// partials of the new r.r.
-int cg_product_step(ssn_ctx *c, const CgVecs &v, CgSlot *cur, int n_ss, double *trace_k, int *n_rr, bool *p_pending)
+// Product k of the CG loop with the vector updates of Alg. 2 behind it.  H s is never formed by a product of
+// its own.  Dense paths: the product is applied to r_k and finalize_cg_kernel does lines 7-12 (two launches
+// per iteration on the one-pass path); the state before product k is completed in slots[k] by that kernel.
+// CSR path: alpha, r -= alpha H s here, p and s in step 2 (*p_pending); the curvature
+// s^T H s = scale * sum_i z_i . u_i + lambda * s.s comes from the per-wave partials the rows kernel leaves in
+// loss_part and the partials of s.s in red_c (n_ss of them); on return red_a holds *n_rr partials of the new r.r.
+int cg_product_step(ssn_ctx *c, const CgVecs &v, CgSlot *slots, int k, double theta, int n_ss, double *trace, int *n_rr,
+                    bool *p_pending)
 {
-    const int32_t *skip = (const int32_t *)((const char *)cur + offsetof(CgSlot, done));
+    CgSlot *cur = slots + k;
+    // dense paths: the theta test for r_k is made by product k's own finalize, so the flag the product's
+    // launches look at is the one before it
+    const CgSlot *flag_slot = (is_dense(c) && k > 0) ? slots + (k - 1) : cur;
+    const int32_t *skip = (const int32_t *)((const char *)flag_slot + offsetof(CgSlot, done));
+    double *trace_k = trace + 3 * k;
     RowsArgs a = rows_base(c);
     a.S = c->S;
     a.nrows = c->nS;
-    a.M = v.s;
+    a.M = is_dense(c) ? v.r : v.s;
     a.mode = ROW_APPLY;
     a.Pin = c->Pbuf;
     a.UP = c->Ubuf;
@@ -454,19 +463,29 @@ int cg_product_step(ssn_ctx *c, const CgVecs &v, CgSlot *cur, int n_ss, double *
         f.K = c->K;
         f.scale = scale_sample(c);
         f.lambda = c->d.lambda;
-        f.M = v.s;
         f.ldm = c->d.ldw;
+        const int fb = finalize_blocks(c->d.p, c->K);
+        double *in = c->cg_parts + (size_t)((k + 1) & 1) * 2 * RED_MAX_PARTS;
+        double *out = c->cg_parts + (size_t)(k & 1) * 2 * RED_MAX_PARTS;
         FinCgArgs g{};
+        g.prev = k > 0 ? slots + (k - 1) : nullptr;
         g.cur = cur;
+        g.first = k == 0;
+        g.theta = theta;
         g.pv = v.pv;
         g.r = v.r;
+        g.s = v.s;
+        g.hs = c->cg_hs;
+        g.pbest = v.pbest;
         g.zu_part = c->loss_part;
         g.n_zu = nparts;
-        g.ss_part = c->red_c;
-        g.n_ss = n_ss;
-        g.rr_part = c->red_a;
-        g.trace_k = trace_k;
-        const int fb = finalize_blocks(c->d.p, c->K);
+        g.rr_in = in;
+        g.rhs_in = in + RED_MAX_PARTS;
+        g.n_in = fb;
+        g.rr_out = out;
+        g.rhs_out = out + RED_MAX_PARTS;
+        g.trace = trace;
+        g.k = k;
         SSN_HIP(c, launch_finalize_cg(c->d.dtype, f, g, fb, c->st));
         *n_rr = fb;
         return SSN_OK;
@@ -533,7 +552,7 @@ int ssn_destroy(ssn_ctx *c)
     if (!c) return SSN_E_INVALID_ARG;
     (void)hipStreamSynchronize(c->st);
     void *dev[] = {c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->red_c, c->red_sq, c->scal_dev, c->int_dev,
-                   c->cg_p, c->cg_r, c->cg_s, c->cg_pb, c->trial, c->grad, c->grad_next, c->dir, c->slots, c->trace_dev};
+                   c->cg_p, c->cg_r, c->cg_s, c->cg_hs, c->cg_parts, c->cg_pb, c->trial, c->grad, c->grad_next, c->dir, c->slots, c->trace_dev};
     for (void *p : dev)
         if (p) (void)hipFree(p);
     if (c->host_pin) (void)hipHostFree(c->host_pin);
@@ -731,6 +750,10 @@ static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *
         SSN_TRY(vec_bytes_alloc(c, &c->cg_r));
         SSN_TRY(vec_bytes_alloc(c, &c->cg_s));
     }
+    if (is_dense(c) && !c->cg_hs) {
+        SSN_TRY(vec_bytes_alloc(c, &c->cg_hs));
+        SSN_HIP(c, hipMalloc((void **)&c->cg_parts, sizeof(double) * 4 * RED_MAX_PARTS));
+    }
     if (c->slots_cap < T + 1) {
         SSN_HIP(c, hipStreamSynchronize(c->st));
         if (c->slots) (void)hipFree(c->slots);
@@ -783,9 +806,15 @@ static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *
     for (int k = 0; k < T; ++k) {
         int n_rr = 0;
         bool p_pending = false;
-        SSN_TRY(cg_product_step(c, v, c->slots + k, vb, c->trace_dev + 3 * k, &n_rr, &p_pending));
-        SSN_HIP(c, launch_cg_step2(c->d.dtype, v, c->slots + k, c->slots + k + 1, c->red_a, n_rr, theta,
-                                   c->trace_dev + 3 * k, c->red_c, p_pending, vb, c->st, c->d.lambda));
+        SSN_TRY(cg_product_step(c, v, c->slots, k, theta, vb, c->trace_dev, &n_rr, &p_pending));
+        if (!is_dense(c))
+            SSN_HIP(c, launch_cg_step2(c->d.dtype, v, c->slots + k, c->slots + k + 1, c->red_a, n_rr, theta,
+                                       c->trace_dev + 3 * k, c->red_c, p_pending, vb, c->st, c->d.lambda));
+    }
+    if (is_dense(c) && T > 0) {
+        const double *last = c->cg_parts + (size_t)((T - 1) & 1) * 2 * RED_MAX_PARTS;
+        SSN_HIP(c, launch_cg_tail(c->d.dtype, v, c->slots + (T - 1), c->slots + T, last, finalize_blocks(c->d.p, c->K), theta,
+                                  c->trace_dev, T, vb, c->st));
     }
     if (!is_dense(c)) {
         // the best iterate may still live only in p (it is copied lazily); then all coordinates of the direction

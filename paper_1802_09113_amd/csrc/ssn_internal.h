@@ -190,7 +190,8 @@ struct CgSlot {          // state before product k
     int32_t brk;         // set during product k when s^T H s <= 0
     double alpha;        // step length of product k, where a kernel of its own computes it (CSR path)
     int32_t best_cur;    // CSR path: the best iterate is the CURRENT p and has not been copied to p_best yet
-    int32_t pad;
+    int32_t best_pending;// dense paths: r_k was the best so far, p_best <- p_k is still to be done (by the next pass over p)
+    double sHs;          // dense paths: curvature s_k^T H s_k of product k (written with alpha by that product's finalize)
     // CSR path: the CG vectors are kept on the columns the sample touches only.  On every other coordinate j
     // H_S is lambda I, so r_j, s_j, p_j stay multiples of g_j; the multipliers and the sum of g_j^2 over those
     // coordinates (goff; 0 on the dense paths, where the terms below vanish) are all that is needed of them.
@@ -234,17 +235,24 @@ hipError_t launch_cg_alpha(CgSlot *cur, const double *zu_part, int n_zu, const d
 hipError_t launch_cg_r_update(int dtype, const CgVecs &v, const CgSlot *cur, double lambda, double *rr_part, int blocks,
                               hipStream_t st);
 
-// one-pass path: sum of the product's partials fused with lines 7-9 (see finalize_cg_kernel)
+// Dense paths: the sum of the product's partials fused with lines 7-12 of Alg. 2 (see finalize_cg_kernel).
 struct FinCgArgs {
-    CgSlot *cur;
-    void *pv, *r;            // on the leading dimension FinArgs::ldm, like s = FinArgs::M
-    const double *zu_part;   // per-wave partials of sum_i z_i . u_i left by the product's launch
+    const CgSlot *prev;      // state before product k-1 (k >= 1), completed by that product's finalize
+    CgSlot *cur;             // state before product k: read (k == 0, from the initialisation) or written by block 0
+    int32_t first;           // k == 0
+    double theta;
+    void *pv, *r, *s, *hs, *pbest;   // CG vectors on the leading dimension FinArgs::ldm (FinArgs::M is not used)
+    const double *zu_part;   // per-wave partials of sum_i z_i . u_i left by the product's launch (operand r_k)
     int n_zu;
-    const double *ss_part;   // partials of s.s
-    int n_ss;
-    double *rr_part;         // out: one partial of the new r.r per block
-    double *trace_k;         // nullable
+    const double *rr_in, *rhs_in;    // partials of r_k.r_k and r_k.(H s_{k-1}) from the previous finalize (k >= 1)
+    int n_in;
+    double *rr_out, *rhs_out;        // out: one partial per block of r_{k+1}.r_{k+1} and r_{k+1}.(H s_k)
+    double *trace;           // nullable: 3 doubles per product (alpha, ||r_new||, s^T H s)
+    int32_t k;
 };
 hipError_t launch_finalize_cg(int dtype, const FinArgs &a, const FinCgArgs &g, int blocks, hipStream_t st);
+// after the last product: the test of lines 10-11 for r_T, the pending p_best copy, the final state
+hipError_t launch_cg_tail(int dtype, const CgVecs &v, const CgSlot *prev, CgSlot *fin, const double *rr_in, int n_in,
+                          double theta, double *trace, int k, int blocks, hipStream_t st);
 
 }  // namespace ssn

@@ -159,30 +159,102 @@ hipError_t launch_finalize(int dtype, const FinArgs &a, int blocks, hipStream_t 
     return hipGetLastError();
 }
 
-// The sum of the one-pass kernel's partials and lines 7-9 of Alg. 2 in one launch.  The curvature
-// s^T H s does not wait for H s: with Z = X_S s and U the rows of eq. (12), s^T (X_S^T U) is the sum over
-// the sample rows of z_i . u_i, which the product's own launch leaves as per-wave partials (zu_part), and
-// s^T s comes as partials from the kernel that made s.  Each block therefore knows alpha before it adds
-// up its elements of H s = scale * sum part + lambda s, and updates p and r for them at once; H s itself
-// is not stored.
+// State before product k from the state before product k-1 and r_k.r_k: lines 10-11 of Alg. 2 for the
+// residual product k-1 left (best-iterate test, theta test).  Every thread of every block computes the same.
+__device__ __forceinline__ CgSlot cg_advance(const CgSlot &prev, double rr_new, double theta)
+{
+    const bool ended = prev.done || prev.brk;
+    const bool broke = prev.brk && !prev.done;
+    const double rnorm = sqrt(rr_new);
+    const bool better = !ended && rnorm <= prev.rbest;
+    const bool stop = !ended && rnorm <= theta * prev.gnorm;
+    CgSlot n;                                       // every field by selects (no branch, no copy of the struct)
+    n.rr = ended ? prev.rr : rr_new;
+    n.rbest = better ? rnorm : prev.rbest;
+    n.gnorm = prev.gnorm;
+    n.done = (ended || stop) ? 1 : 0;
+    n.iters = (ended && !broke) ? prev.iters : prev.iters + 1;
+    n.flags = prev.flags | (stop ? 1 : 0) | (broke ? 2 : 0);
+    n.brk = 0;
+    n.alpha = 0.0;
+    n.best_cur = 0;
+    n.best_pending = better ? 1 : 0;
+    n.sHs = prev.sHs;
+    n.goff = 0.0;
+    n.rho = n.sigma = n.pi = n.pibest = 0.0;
+    return n;
+}
+
+// three sums at once (same order of operations as block_sum for each)
+__device__ __forceinline__ void block_sum3(double a, double b, double c, double &ra, double &rb, double &rc)
+{
+    __shared__ double sm3[3 * (VEC_BLOCK / 64)];
+    for (int off = 32; off > 0; off >>= 1) {
+        a += __shfl_xor(a, off);
+        b += __shfl_xor(b, off);
+        c += __shfl_xor(c, off);
+    }
+    constexpr int NWV = VEC_BLOCK / 64;
+    if ((threadIdx.x & 63) == 0) {
+        sm3[threadIdx.x >> 6] = a;
+        sm3[NWV + (threadIdx.x >> 6)] = b;
+        sm3[2 * NWV + (threadIdx.x >> 6)] = c;
+    }
+    __syncthreads();
+    ra = sm3[0];
+    rb = sm3[NWV];
+    rc = sm3[2 * NWV];
+#pragma unroll
+    for (int k = 1; k < NWV; ++k) {
+        ra += sm3[k];
+        rb += sm3[NWV + k];
+        rc += sm3[2 * NWV + k];
+    }
+    __syncthreads();
+}
+
+// Dense paths: the sum of the product's partials and lines 7-12 of Alg. 2 in one launch, two launches per
+// CG iteration (product, this).  Two things make that possible.
+//
+// The product is applied to the residual, not to the search direction.  H is linear, so with
+// s_k = r_k + beta s_{k-1} (line 12)  H s_k = H r_k + beta H s_{k-1}: the product's launch needs r_k only,
+// which the previous finalize has already written, and never waits for beta; H s_k is kept as a vector
+// and updated here, next to s_k itself.
+//
+// No dot product waits for a vector either.  With Z = X_S r and U the rows of eq. (12),
+// r^T (X_S^T U) = sum_i z_i . u_i, which the product's own launch leaves as per-wave partials; the previous
+// finalize left the partials of r_k.r_k and r_k.(H s_{k-1}).  So every block knows, before it touches its
+// elements: beta = r_k.r_k / r_{k-1}.r_{k-1}, r_k^T H r_k = scale * sum z.u + lambda r_k.r_k,
+// s_k^T H s_k = r^T H r + 2 beta r_k.(H s_{k-1}) + beta^2 s_{k-1}^T H s_{k-1}, alpha, and the outcome of the
+// tests of lines 10-11 for r_k.  It then sums its elements of X_S^T U and updates H s, s, p_best, p, r for
+// them in one go.  Block 0 records the state for the host and for the launches that follow.
+//
+// The theta test for r_k is only known here, after product k has been launched: when the loop stops, that
+// one product has run for nothing (the launches after it see the flag and return at once).
 template <typename T, int EL> __global__ __launch_bounds__(VEC_BLOCK) void finalize_cg_kernel(FinArgs a, FinCgArgs g)
 {
-    // Loads first: the state slot, this thread's share of the z.u and s.s partials and the first batch of the
-    // block's chunk partials are all independent, so they go out together and the kernel waits once.
+    // Loads first: the state, this thread's share of the partial sums and the first batch of the block's chunk
+    // partials are all independent, so they go out together and the kernel waits once.
     constexpr int CLN = VEC_BLOCK / EL;
     const int el = threadIdx.x % EL, cl = threadIdx.x / EL;
     const int64_t total = a.p * a.K;
     const T *part = (const T *)a.part;
-    const CgSlot c = *g.cur;
-    double vz = 0.0, vs = 0.0, tfirst = 0.0;     // tfirst: chunks cl, cl + CLN, .. (first eight) of the block's first group
+    const CgSlot prev = g.first ? *g.cur : *g.prev;
+    double vz = 0.0, vr = 0.0, vh = 0.0, tfirst = 0.0;   // tfirst: chunks cl, cl + CLN, .. (first eight) of the first group
     {
-        double z4[4], s1;
+        double z4[4], r2[2], h2[2];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int i = threadIdx.x + u * VEC_BLOCK;
             z4[u] = g.zu_part[i < g.n_zu ? i : 0];
         }
-        s1 = g.ss_part[(int)threadIdx.x < g.n_ss ? threadIdx.x : 0];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int i = threadIdx.x + u * VEC_BLOCK;
+            const bool in = !g.first && i < g.n_in;
+            r2[u] = in ? g.rr_in[i] : 0.0;
+            h2[u] = in ? g.rhs_in[i] : 0.0;
+        }
         T first[8];
         const int64_t ef = (int64_t)blockIdx.x * EL + el;
 #pragma unroll
@@ -193,55 +265,100 @@ template <typename T, int EL> __global__ __launch_bounds__(VEC_BLOCK) void final
 #pragma unroll
         for (int u = 0; u < 4; ++u) vz += (threadIdx.x + u * VEC_BLOCK < (unsigned)g.n_zu) ? z4[u] : 0.0;
         for (int i = threadIdx.x + 4 * VEC_BLOCK; i < g.n_zu; i += VEC_BLOCK) vz += g.zu_part[i];
-        vs = ((int)threadIdx.x < g.n_ss) ? s1 : 0.0;
-        for (int i = threadIdx.x + VEC_BLOCK; i < g.n_ss; i += VEC_BLOCK) vs += g.ss_part[i];
+        vr = r2[0] + r2[1];
+        vh = h2[0] + h2[1];
+        if (!g.first)
+            for (int i = threadIdx.x + 2 * VEC_BLOCK; i < g.n_in; i += VEC_BLOCK) {
+                vr += g.rr_in[i];
+                vh += g.rhs_in[i];
+            }
 #pragma unroll
         for (int u = 0; u < 8; ++u) tfirst += (cl + u * CLN < a.nchunks) ? (double)first[u] : 0.0;
     }
-    if (c.done) return;
-    double zu, ss;
-    block_sum2(vz, vs, zu, ss);
-    const double sHs = a.scale * zu + a.lambda * ss;
-    if (!(sHs > 0.0)) {                      // not positive definite in floating point: stop, keep p_best
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            g.cur->brk = 1;                  // read only by step 2 of this product
-            if (g.trace_k) { g.trace_k[0] = 0.0; g.trace_k[1] = sqrt(c.rr); g.trace_k[2] = sHs; }
-        }
-        return;
+    double zu, rr_sum, rhs;
+    block_sum3(vz, vr, vh, zu, rr_sum, rhs);
+    CgSlot c = cg_advance(prev, rr_sum, g.theta);
+    if (g.first) {                                    // the state before product 0 is the initialisation's, as it is
+        c.rr = prev.rr;
+        c.rbest = prev.rbest;
+        c.done = prev.done;
+        c.iters = prev.iters;
+        c.flags = prev.flags;
+        c.best_pending = 0;
     }
-    const double alpha = c.rr / sHs;
+    const double beta = (g.first || c.done) ? 0.0 : c.rr / prev.rr;
+    const double rHr = a.scale * zu + a.lambda * c.rr;
+    const double sHs = g.first ? rHr : rHr + 2.0 * beta * rhs + beta * beta * prev.sHs;
+    const bool brk = !c.done && !(sHs > 0.0);        // not positive definite in floating point: stop, keep p_best
+    const double alpha = (c.done || brk) ? 0.0 : c.rr / sHs;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        CgSlot *w = g.cur;                            // field by field: a struct temporary would live in scratch memory
+        w->rr = c.rr;
+        w->rbest = c.rbest;
+        w->gnorm = c.gnorm;
+        w->done = c.done;
+        w->iters = c.iters;
+        w->flags = c.flags;
+        w->brk = brk ? 1 : 0;
+        w->alpha = alpha;
+        w->best_cur = 0;
+        w->best_pending = c.best_pending;
+        w->sHs = sHs;
+        w->goff = 0.0;
+        w->rho = w->sigma = w->pi = w->pibest = 0.0;
+        if (g.trace) {
+            if (!g.first && !prev.done && !prev.brk) g.trace[3 * (g.k - 1) + 1] = sqrt(rr_sum);
+            if (!c.done) {
+                g.trace[3 * g.k] = alpha;
+                g.trace[3 * g.k + 2] = sHs;
+                if (brk) g.trace[3 * g.k + 1] = sqrt(c.rr);
+            }
+        }
+    }
+    if (!c.best_pending && (c.done || brk)) return;
     __shared__ double sm[VEC_BLOCK];
     const int64_t ngroups = (total + EL - 1) / EL;
-    const T *sv = (const T *)a.M;
-    T *pv = (T *)g.pv, *r = (T *)g.r;
-    double local = 0.0;
+    T *pv = (T *)g.pv, *r = (T *)g.r, *sv = (T *)g.s, *hsv = (T *)g.hs, *pb = (T *)g.pbest;
+    const bool update = !c.done && !brk;
+    double lrr = 0.0, lrh = 0.0;
     for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
         const int64_t e = grp * EL + el;
         double t = 0.0;
-        if (e < total) {
+        if (update && e < total) {
             if (grp == blockIdx.x) t = chunk_sum<T, CLN>(part, a.nchunks, total, e, cl, 8, tfirst);
             else t = chunk_sum<T, CLN>(part, a.nchunks, total, e, cl);
         }
         sm[threadIdx.x] = t;
         __syncthreads();
         if (cl == 0 && e < total) {
-            double tt = 0.0;
-#pragma unroll
-            for (int k = 0; k < CLN; ++k) tt += sm[k * EL + el];
             const int64_t o = off_of(e, a.K, a.ldm);
-            const double m = (double)sv[o];
-            const T hs = (T)(a.scale * tt + a.lambda * m);           // the element of H s, rounded as if stored
-            pv[o] = (T)((double)pv[o] + alpha * m);
-            const T rn = (T)((double)r[o] - alpha * (double)hs);
-            r[o] = rn;
-            local += (double)rn * (double)rn;
+            const T pe = pv[o];
+            if (c.best_pending) pb[o] = pe;                           // line 10 for the iterate the last product left
+            if (update) {
+                double tt = 0.0;
+#pragma unroll
+                for (int k = 0; k < CLN; ++k) tt += sm[k * EL + el];
+                const double re = (double)r[o];
+                const T hr = (T)(a.scale * tt + a.lambda * re);       // the element of H r, rounded as if stored
+                const T hs = g.first ? hr : (T)((double)hr + beta * (double)hsv[o]);
+                const T sn = g.first ? (T)re : (T)(re + beta * (double)sv[o]);      // line 12
+                hsv[o] = hs;
+                sv[o] = sn;
+                pv[o] = (T)((double)pe + alpha * (double)sn);         // line 8
+                const T rn = (T)(re - alpha * (double)hs);            // line 9
+                r[o] = rn;
+                lrr += (double)rn * (double)rn;
+                lrh += (double)rn * (double)hs;
+            }
         }
         __syncthreads();
     }
-    const double rr = block_sum(local);
+    if (!update) return;
+    double rr_o, rh_o;
+    block_sum2(lrr, lrh, rr_o, rh_o);
     if (threadIdx.x == 0) {
-        g.rr_part[blockIdx.x] = rr;
-        if (blockIdx.x == 0 && g.trace_k) { g.trace_k[0] = alpha; g.trace_k[2] = sHs; }
+        g.rr_out[blockIdx.x] = rr_o;
+        g.rhs_out[blockIdx.x] = rh_o;
     }
 }
 
@@ -257,6 +374,51 @@ hipError_t launch_finalize_cg(int dtype, const FinArgs &a, const FinCgArgs &g, i
 {
     if (dtype == SSN_F32) finalize_cg_launch<float>(a, g, blocks, st);
     else finalize_cg_launch<double>(a, g, blocks, st);
+    return hipGetLastError();
+}
+
+// After the last product of the dense paths: lines 10-11 for r_T, the pending copy p_best <- p, the final state.
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void cg_tail_kernel(CgVecs v, const CgSlot *prev_p, CgSlot *fin, const double *rr_in,
+                                                             int n_in, double theta, double *trace, int k)
+{
+    const CgSlot prev = *prev_p;
+    const double rr_sum = sum_parts(rr_in, n_in);
+    const CgSlot c = cg_advance(prev, rr_sum, theta);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        fin->rr = c.rr;
+        fin->rbest = c.rbest;
+        fin->gnorm = c.gnorm;
+        fin->done = c.done;
+        fin->iters = c.iters;
+        fin->flags = c.flags;
+        fin->brk = 0;
+        fin->alpha = 0.0;
+        fin->best_cur = 0;
+        fin->best_pending = 0;
+        fin->sHs = c.sHs;
+        fin->goff = 0.0;
+        fin->rho = fin->sigma = fin->pi = fin->pibest = 0.0;
+        if (trace && !prev.done && !prev.brk) trace[3 * (k - 1) + 1] = sqrt(rr_sum);
+    }
+    if (!c.best_pending) return;
+    const int64_t total = v.p * v.K;
+    const T *pw = (const T *)v.pv;
+    T *pb = (T *)v.pbest;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int64_t o = off_of(e, v.K, v.ld);
+        pb[o] = pw[o];
+    }
+}
+
+hipError_t launch_cg_tail(int dtype, const CgVecs &v, const CgSlot *prev, CgSlot *fin, const double *rr_in, int n_in,
+                          double theta, double *trace, int k, int blocks, hipStream_t st)
+{
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(cg_tail_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, prev, fin, rr_in, n_in, theta, trace, k);
+    else
+        hipLaunchKernelGGL(cg_tail_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, prev, fin, rr_in, n_in, theta, trace,
+                           k);
     return hipGetLastError();
 }
 
@@ -586,7 +748,8 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_init_state_kernel(const double *
         s.brk = 0;
         s.alpha = 0.0;
         s.best_cur = 0;
-        s.pad = 0;
+        s.best_pending = 0;
+        s.sHs = 0.0;
         *slot0 = s;
     }
 }
@@ -776,7 +939,8 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgS
         n.brk = 0;
         n.alpha = 0.0;
         n.best_cur = update_p ? (better ? 1 : 0) : 0;
-        n.pad = 0;
+        n.best_pending = 0;
+        n.sHs = 0.0;
         n.goff = c.goff;
         n.rho = rho_n;
         n.pi = pi_n;
