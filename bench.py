@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X datasheet HBM3E bandwidth
 # Counters cannot be read from inside this script; other workloads / dtypes report null.
 MEASURED_TRAFFIC = {
     ("image_like", "f64", "dense_fused_kernel<OBJ>"): 377.5e6,
-    ("image_like", "f64", "dense_fused_kernel<GRAD>"): 393.1e6 + 18.7e6,
+    ("image_like", "f64", "dense_fused_kernel<GRAD>"): 377.8e6 + 14.5e6,
     ("image_like", "f64", "dense_fused_kernel<APPLY>"): 19.8e6 + 10.6e6,
 }
 
