@@ -18,8 +18,9 @@
  *     HOST pointers.  The library owns only the workspace inside ssn_ctx.
  *   - Work is enqueued on the context's stream (a hipStream_t passed as
  *     void*; NULL = the default stream).  Calls that return a scalar through
- *     a [host] pointer wait for the stream before returning; all other calls
- *     are asynchronous.
+ *     a [host] pointer return once everything they enqueued has completed
+ *     (they wait for the last kernel's result to arrive in host memory, or
+ *     for the stream); all other calls are asynchronous.
  *   - Element type T is float (SSN_F32) or double (SSN_F64) for X/vals, W, V,
  *     G, HV, P.  Sums over rows are carried in fp64 in both cases.
  *   - W, V, G, HV, P (direction) are p-by-K, row-major, class index fastest,

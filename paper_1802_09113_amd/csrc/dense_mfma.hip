@@ -371,7 +371,7 @@ __global__ __launch_bounds__(SPLIT ? 1024 : 64 * ROWS_WAVES_PER_BLOCK) void dens
     // their W operands in flight some variants spilled, and a kernel that uses scratch memory at all pays
     // ~14 us per launch on this machine, more than a whole sampled product: those variants take fewer.
     constexpr bool EXPS = (MODE == ROW_OBJ || MODE == ROW_GRAD);      // fp64 exp / log routines in the epilogue
-    constexpr int UNR = !SPLIT ? 4 : (sizeof(T) == 8 && NB == 2 && EXPS) ? 1 : (sizeof(T) == 4 || NB == 2 || EXPS) ? 2 : 4;
+    constexpr int UNR = !SPLIT ? 4 : (sizeof(T) == 8 && NB == 2 && (EXPS || MODE == ROW_PREP)) ? 1 : (sizeof(T) == 4 || NB == 2 || EXPS) ? 2 : 4;
 
     constexpr int RB = PAIR ? 2 : 1;
     for (int64_t rb0 = wave * RB; rb0 < nblk; rb0 += nwaves * RB) {
@@ -1301,14 +1301,18 @@ template <typename T, int MODE> static hipError_t fused_launch_mode(RowsArgs a, 
         if constexpr (TB::N > 3) return SSN_FUSED_SHAPE(TB::N - 1, 1);
         return hipErrorInvalidValue;
     }
-    if constexpr (!(TB::shape[0].flags & SHAPE_SINGLE_WAVE)) {
-        if (i == 0) return SSN_FUSED_SHAPE(0, TB::shape[0].maxw);
+    // multi-wave workgroups: only the (shape, mode) pairs fused_shape can pick are compiled
+#define SSN_FUSED_MULTI(I)                                                                                              \
+    if constexpr (!(TB::shape[I].flags & SHAPE_SINGLE_WAVE) && !(has_c && (TB::shape[I].flags & SHAPE_NO_C_MULTI))) {  \
+        if (i == I) return SSN_FUSED_SHAPE(I, TB::shape[I].maxw);                                                       \
     }
-    if (i == 1) return SSN_FUSED_SHAPE(1, TB::shape[1].maxw);
-    if (i == 2) return SSN_FUSED_SHAPE(2, TB::shape[2].maxw);
+    SSN_FUSED_MULTI(0)
+    SSN_FUSED_MULTI(1)
+    SSN_FUSED_MULTI(2)
     if constexpr (TB::N > 3) {
-        if (i == 3) return SSN_FUSED_SHAPE(TB::N - 1, TB::shape[TB::N - 1].maxw);
+        SSN_FUSED_MULTI(TB::N - 1)
     }
+#undef SSN_FUSED_MULTI
     return hipErrorInvalidValue;
 #undef SSN_FUSED_SHAPE
 }

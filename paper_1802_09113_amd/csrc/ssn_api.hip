@@ -49,6 +49,9 @@ struct ssn_ctx {
     double *host_pin = nullptr;   // pinned staging for scalar results
     double *f_host = nullptr;     // host-visible word kernels write objective values to (inside host_pin's allocation)
     double *f_host_dev = nullptr; // its device address
+    unsigned long long *f_ticket = nullptr, *f_ticket_dev = nullptr;   // ticket word next to f_host: the kernel posts the
+                                  // value, then the ticket of its enqueue; the host spins on it instead of synchronising
+    unsigned long long f_seq = 0; // ticket of the last enqueue
     double *pub_host = nullptr;   // host-visible block ssn_solve's per-iteration scalars and CG state are written to
     double *pub_dev = nullptr;    // its device address (null: not mappable, copies are used instead)
     // prepared Hessian sample
@@ -304,30 +307,48 @@ int enqueue_objective_value(ssn_ctx *c, const void *W, int nparts, int slot, dou
 {
     if (scale < 0.0) scale = scale_full(c);
     if (mirrored) *mirrored = false;
+    // the host-visible copy and its ticket go with slot 0 only (the value a caller is about to wait for)
+    const bool post = slot == 0 && c->f_host_dev != nullptr;
+    double *oh = post ? c->f_host_dev : nullptr;
+    unsigned long long *th = post ? c->f_ticket_dev : nullptr;
+    const unsigned long long ticket = post ? ++c->f_seq : 0;
+    if (mirrored) *mirrored = post;
     if (c->d.p * (int64_t)c->K <= OBJ_VALUE_ELEMS) {
         SSN_HIP(c, launch_objective_value(c->d.dtype, c->loss_part, nparts, scale, W, c->d.p, c->K, c->d.ldw,
-                                          0.5 * c->d.lambda, c->scal_dev + slot, c->f_host_dev, c->st));
-        if (mirrored) *mirrored = c->f_host_dev != nullptr;
+                                          0.5 * c->d.lambda, c->scal_dev + slot, oh, th, ticket, c->st));
         return SSN_OK;
     }
     if (c->sq_for == W && c->n_sq > 0) {         // the kernel that wrote W left the partials of ||W||^2
         c->sq_for = nullptr;
         SSN_HIP(c, launch_combine(c->loss_part, nparts, scale, c->red_sq, c->n_sq, 0.5 * c->d.lambda, c->scal_dev + slot,
-                                  c->st));
+                                  c->st, oh, th, ticket));
         return SSN_OK;
     }
     const int vb = vec_blocks(c->d.p * (int64_t)c->K);
     SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, W, c->d.ldw, W, c->d.ldw, c->red_a, vb, nullptr, c->st));
     SSN_HIP(c, launch_combine(c->loss_part, nparts, scale, c->red_a, vb, 0.5 * c->d.lambda, c->scal_dev + slot,
-                              c->st));
+                              c->st, oh, th, ticket));
     return SSN_OK;
 }
+
+double now_ms();
 
 // wait for f(W) enqueued by enqueue_objective_value into scal_dev[0]
 int read_objective(ssn_ctx *c, bool mirrored, double *f)
 {
     if (mirrored) {
-        SSN_HIP(c, hipStreamSynchronize(c->st));
+        // Spin on the ticket the value kernel posts behind the value.  Everything enqueued before that kernel
+        // has completed by then (one stream), and the host is back a microsecond or two after the store instead
+        // of a stream synchronisation's wake-up later.  A ticket that does not come (a failed launch, a fault)
+        // ends in the synchronisation, which reports it.
+        const unsigned long long want = c->f_seq;
+        const double t_give_up = now_ms() + 2000.0;
+        bool seen = false;
+        for (unsigned spin = 0;; ++spin) {
+            if (__atomic_load_n(c->f_ticket, __ATOMIC_ACQUIRE) == want) { seen = true; break; }
+            if ((spin & 0x3ff) == 0x3ff && now_ms() > t_give_up) break;
+        }
+        if (!seen) SSN_HIP(c, hipStreamSynchronize(c->st));
         *f = *(volatile double *)c->f_host;
     } else {
         SSN_TRY(read_scalar(c, c->scal_dev, f));
@@ -621,6 +642,9 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
     {
         void *dp = nullptr;
         if (hipHostGetDevicePointer(&dp, c->f_host, 0) == hipSuccess) c->f_host_dev = (double *)dp;
+        c->f_ticket = (unsigned long long *)(c->host_pin + 257);
+        *c->f_ticket = 0;
+        if (c->f_host_dev) c->f_ticket_dev = (unsigned long long *)(c->f_host_dev + 1);
         c->pub_host = c->host_pin + 128;                             // bytes 1024..2047
         dp = nullptr;
         if (hipHostGetDevicePointer(&dp, c->pub_host, 0) == hipSuccess) c->pub_dev = (double *)dp;
@@ -868,7 +892,7 @@ static int enqueue_slope(ssn_ctx *c, const void *P, const void *G)
 
 int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
                     int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok, void *G_first = nullptr,
-                    const bool *first_enqueued = nullptr);
+                    const double *first_f = nullptr, int first_status = SSN_OK);
 
 int ssn_linesearch(ssn_ctx *c, const void *W, const void *P, const void *G, double fW, double beta, double rho,
                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok)
@@ -902,19 +926,24 @@ int trial_enqueue(ssn_ctx *c, const void *W, const void *P, double alpha, void *
 
 // Alg. 3 with the slope <P, G> already on the host.  G_first (nullable): the first trial, alpha = 1, is
 // evaluated by the gradient pass, which leaves grad f(W + P) there next to the same F(W + P); when that
-// trial is accepted the caller already holds the gradient of the next iterate.  first_enqueued (nullable):
-// the caller has already enqueued the first trial with trial_enqueue; *first_enqueued is its `mirrored`.
+// trial is accepted the caller already holds the gradient of the next iterate.  first_f (nullable): the
+// caller has already evaluated the first trial (trial_enqueue + read_objective): its value and status.
 int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
                     int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok, void *G_first,
-                    const bool *first_enqueued)
+                    const double *first_f, int first_status)
 {
     double alpha = 1.0, ft = 0.0;
     int i = 0, evals = 0, good = 0;
     for (;;) {
-        bool mirrored = false;
-        if (i == 0 && first_enqueued) mirrored = *first_enqueued;
-        else SSN_TRY(trial_enqueue(c, W, P, alpha, i == 0 ? G_first : nullptr, &mirrored));
-        const int s = read_objective(c, mirrored, &ft);
+        int s;
+        if (i == 0 && first_f) {
+            ft = *first_f;
+            s = first_status;
+        } else {
+            bool mirrored = false;
+            SSN_TRY(trial_enqueue(c, W, P, alpha, i == 0 ? G_first : nullptr, &mirrored));
+            s = read_objective(c, mirrored, &ft);
+        }
         if (s != SSN_OK && s != SSN_E_NONFINITE) return s;
         ++evals;
         if (s == SSN_OK && !(ft > fW + alpha * beta * slope)) { good = 1; break; }
@@ -1055,7 +1084,12 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         const bool ahead = look_on && k + 1 < pr->iters;
         bool first_mirrored = false;
         SOLVE_TRY(trial_enqueue(c, W, c->dir, 1.0, ahead ? c->grad_next : nullptr, &first_mirrored));
-        SOLVE_HIP(hipStreamSynchronize(c->st));
+        double f_first = 0.0;
+        const int first_status = read_objective(c, first_mirrored, &f_first);       // the one wait of the iteration
+        if (first_status != SSN_OK && first_status != SSN_E_NONFINITE) {
+            status = first_status;
+            goto done;
+        }
         flush_pending();
         {
             rec.f = pr->Sg_all ? f_carry : (have_next ? f_next : pub[0]);
@@ -1083,7 +1117,7 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
             rec.cg_rel_res = info.rel_res;
             double fn = 0.0;
             SOLVE_TRY(linesearch_impl(c, W, c->dir, rec.f, slope, pr->beta, pr->rho, pr->imax, &rec.alpha, &fn, &rec.ls_evals,
-                                      &rec.ls_ok, nullptr, &first_mirrored));
+                                      &rec.ls_ok, nullptr, &f_first, first_status));
             f_carry = fn;
             const bool first_accepted = rec.ls_ok && rec.ls_evals == 1;
             have_next = ahead && first_accepted;

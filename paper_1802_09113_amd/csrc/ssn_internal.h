@@ -122,10 +122,13 @@ hipError_t launch_axpy_sq(int dtype, int64_t p, int K, double alpha, const void 
 // *out (and *out_host, nullable, host-visible) = scale * sum(loss_part) + half_lambda * ||W||_F^2 ; one block, for
 // blocks of up to OBJ_VALUE_ELEMS elements
 hipError_t launch_objective_value(int dtype, const double *loss_part, int nparts, double scale, const void *W, int64_t p,
-                                  int K, int64_t ldw, double half_lambda, double *out, double *out_host, hipStream_t st);
+                                  int K, int64_t ldw, double half_lambda, double *out, double *out_host,
+                                  unsigned long long *ticket_host, unsigned long long ticket, hipStream_t st);
 constexpr int64_t OBJ_VALUE_ELEMS = 32768;
-hipError_t launch_combine(const double *a, int na, double scale, const double *b, int nb, double coef,
-                          double *out, hipStream_t st);
+// out_host / ticket_host (nullable): also post the value to host-visible memory, then the ticket (see post_to_host)
+hipError_t launch_combine(const double *a, int na, double scale, const double *b, int nb, double coef, double *out,
+                          hipStream_t st, double *out_host = nullptr, unsigned long long *ticket_host = nullptr,
+                          unsigned long long ticket = 0);
 hipError_t launch_solve_publish(const double *slope_part, int n, const double *f_dev, const CgSlot *fin, double *slope_dev,
                                 double *host_out, bool support_only, hipStream_t st);
 // streaming read of `bytes` (multiple of 16, 16-byte aligned); one checksum partial per block
