@@ -35,6 +35,14 @@ struct ssn_ctx {
     // CSR: column-sorted views for the transposed products (whole matrix: built at the first gradient;
     // sample: rebuilt by every ssn_hess_prepare)
     CscView csc_full, csc_samp, csc_grad;      // csc_grad: the sample of the last sub-sampled gradient
+    // ssn_solve builds the view of the NEXT iteration's sample (it depends on the sample only, not on the
+    // iterate) on a stream of its own while the current iteration's line search runs
+    CscView csc_next;
+    hipStream_t st_aux = nullptr;
+    hipEvent_t ev_aux = nullptr;
+    const int32_t *next_S = nullptr;
+    int64_t next_nS = 0;
+    bool next_ready = false;
     bool csc_full_built = false;
     // reduction scratch
     double *loss_part = nullptr;
@@ -580,6 +588,9 @@ int ssn_destroy(ssn_ctx *c)
     csc_free(&c->csc_full);
     csc_free(&c->csc_samp);
     csc_free(&c->csc_grad);
+    csc_free(&c->csc_next);
+    if (c->ev_aux) (void)hipEventDestroy(c->ev_aux);
+    if (c->st_aux) (void)hipStreamDestroy(c->st_aux);
     delete c;
     return SSN_OK;
 }
@@ -706,7 +717,23 @@ int ssn_gradient(ssn_ctx *c, const void *W, void *G, double *f)
 }
 
 // validate: check the sample indices first (one pass and one synchronisation)
-static int hess_prepare_impl(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS, bool validate)
+// CSR, inside ssn_solve: the column-sorted view (and support) of the sample S, built on the auxiliary stream
+static int prebuild_sample_view(ssn_ctx *c, const int32_t *S, int64_t nS)
+{
+    c->next_ready = false;
+    if (!c->st_aux) {
+        SSN_HIP(c, hipStreamCreateWithFlags(&c->st_aux, hipStreamNonBlocking));
+        SSN_HIP(c, hipEventCreateWithFlags(&c->ev_aux, hipEventDisableTiming));
+    }
+    SSN_HIP(c, csc_build(&c->csc_next, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.p, c->K, c->st_aux, true));
+    SSN_HIP(c, hipEventRecord(c->ev_aux, c->st_aux));
+    c->next_S = S;
+    c->next_nS = nS;
+    c->next_ready = true;
+    return SSN_OK;
+}
+
+static int hess_prepare_impl(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS, bool validate, bool use_prebuilt = false)
 {
     c->prepared = false;
     if (validate) {
@@ -725,8 +752,15 @@ static int hess_prepare_impl(ssn_ctx *c, const void *W, const int32_t *S, int64_
     a.mode = ROW_PREP;
     a.UP = c->Pbuf;
     SSN_TRY(launch_rows(c, a, nullptr));
-    if (!is_dense(c))
-        SSN_HIP(c, csc_build(&c->csc_samp, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.p, c->K, c->st, true));
+    if (!is_dense(c)) {
+        if (use_prebuilt && c->next_ready && c->next_S == S && c->next_nS == nS) {
+            std::swap(c->csc_samp, c->csc_next);
+            SSN_HIP(c, hipStreamWaitEvent(c->st, c->ev_aux, 0));
+        } else {
+            SSN_HIP(c, csc_build(&c->csc_samp, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.p, c->K, c->st, true));
+        }
+        c->next_ready = false;
+    }
     c->S = S;
     c->nS = nS;
     c->prepared = true;
@@ -1059,7 +1093,7 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         if (pr->Sg_all) SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, false, pr->Sg_all + (int64_t)k * pr->nSg, pr->nSg));
         else if (!have_next) SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, true));
         SOLVE_HIP(mark(E[1]));
-        SOLVE_TRY(hess_prepare_impl(c, W, pr->S_all + (int64_t)k * pr->nS, pr->nS, false));
+        SOLVE_TRY(hess_prepare_impl(c, W, pr->S_all + (int64_t)k * pr->nS, pr->nS, false, true));
         SOLVE_HIP(mark(E[2]));
         // CSR with a device mapping of the host block: CG leaves the slope's partials (n_slope > 0)
         int n_slope = 0;
@@ -1084,6 +1118,8 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         const bool ahead = look_on && k + 1 < pr->iters;
         bool first_mirrored = false;
         SOLVE_TRY(trial_enqueue(c, W, c->dir, 1.0, ahead ? c->grad_next : nullptr, &first_mirrored));
+        // CSR: while the device works through the queue above, the view of the next sample is built beside it
+        if (!is_dense(c) && k + 1 < pr->iters) SOLVE_TRY(prebuild_sample_view(c, pr->S_all + (int64_t)(k + 1) * pr->nS, pr->nS));
         double f_first = 0.0;
         const int first_status = read_objective(c, first_mirrored, &f_first);       // the one wait of the iteration
         if (first_status != SSN_OK && first_status != SSN_E_NONFINITE) {
@@ -1142,6 +1178,8 @@ done:
 #undef SOLVE_TRY
 #undef SOLVE_HIP
     (void)hipStreamSynchronize(c->st);
+    if (c->st_aux) (void)hipStreamSynchronize(c->st_aux);
+    c->next_ready = false;                   // a view built ahead is only good inside this call
     flush_pending();
     if (timing)
         for (auto &set : ev)
