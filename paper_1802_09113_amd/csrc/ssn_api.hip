@@ -800,9 +800,15 @@ int ssn_hessvec(ssn_ctx *c, const void *W, const int32_t *S, int64_t nS, const v
 // every launch of Alg. 2; the final state waits in slots[T]
 // n_slope (nullable): on the CSR path the partials of <P_out, G> over the sample's columns are left in red_a,
 // *n_slope of them (the rest of the product is CgSlot::pibest * CgSlot::goff); 0 where they are not made
-static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out, int *n_slope = nullptr)
+// solve_W / solve_trial / solve_pub (ssn_solve, nullable): on the dense paths with a small block and T > 0 the tail
+// launch also forms the slope, the first trial point solve_W + P_out (into solve_trial) and publishes F(x_k), the
+// slope and the final state to the host block solve_pub [dev]; *solve_fused tells whether that happened.
+static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *P_out, int *n_slope = nullptr,
+                      const void *solve_W = nullptr, void *solve_trial = nullptr, double *solve_pub = nullptr,
+                      bool *solve_fused = nullptr)
 {
     if (n_slope) *n_slope = 0;
+    if (solve_fused) *solve_fused = false;
     if (!c->cg_p) {
         SSN_TRY(vec_bytes_alloc(c, &c->cg_p));
         SSN_TRY(vec_bytes_alloc(c, &c->cg_r));
@@ -832,7 +838,12 @@ static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *
     v.s = c->cg_s;
     v.pbest = P_out;
     int vb = vec_blocks(c->d.p * (int64_t)c->K);
-    if (is_dense(c)) {
+    // one block does it all only where each thread has a handful of elements: a single block walking thousands of
+    // elements is a chain of dependent round trips and loses more than the launches it saves
+    const bool small = c->d.p * (int64_t)c->K <= 8 * VEC_BLOCK;
+    if (is_dense(c) && small) {
+        SSN_HIP(c, launch_cg_init_small(c->d.dtype, v, c->slots, c->st));
+    } else if (is_dense(c)) {
         SSN_HIP(c, launch_cg_init(c->d.dtype, v, c->red_a, c->red_c, vb, c->st));
         SSN_HIP(c, launch_cg_init_state(c->red_a, vb, c->slots, c->st));
     } else {
@@ -871,8 +882,15 @@ static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *
     }
     if (is_dense(c) && T > 0) {
         const double *last = c->cg_parts + (size_t)((T - 1) & 1) * 2 * RED_MAX_PARTS;
-        SSN_HIP(c, launch_cg_tail(c->d.dtype, v, c->slots + (T - 1), c->slots + T, last, finalize_blocks(c->d.p, c->K), theta,
-                                  c->trace_dev, T, vb, c->st));
+        if (solve_W && solve_trial && solve_pub && c->d.p * (int64_t)c->K <= OBJ_VALUE_ELEMS) {
+            SSN_HIP(c, launch_cg_tail_solve(c->d.dtype, v, c->slots + (T - 1), c->slots + T, last, finalize_blocks(c->d.p, c->K),
+                                            theta, c->trace_dev, T, solve_W, solve_trial, c->scal_dev, c->scal_dev + 1,
+                                            solve_pub, c->red_a, small ? 1 : vb, c->st));
+            if (solve_fused) *solve_fused = true;
+        } else {
+            SSN_HIP(c, launch_cg_tail(c->d.dtype, v, c->slots + (T - 1), c->slots + T, last, finalize_blocks(c->d.p, c->K),
+                                      theta, c->trace_dev, T, vb, c->st));
+        }
     }
     if (!is_dense(c)) {
         // the best iterate may still live only in p (it is copied lazily); then all coordinates of the direction
@@ -940,11 +958,13 @@ int ssn_linesearch(ssn_ctx *c, const void *W, const void *P, const void *G, doub
 
 // The trial point W + alpha P into c->trial and F there enqueued (into scal_dev[0]; *mirrored: also into the
 // host-visible word).  G_first (nullable): evaluate with the gradient pass, which leaves grad F there too.
-int trial_enqueue(ssn_ctx *c, const void *W, const void *P, double alpha, void *G_first, bool *mirrored)
+// formed: c->trial already holds the trial point (the CG tail of ssn_solve wrote it)
+int trial_enqueue(ssn_ctx *c, const void *W, const void *P, double alpha, void *G_first, bool *mirrored, bool formed = false)
 {
     if (!c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
     c->sq_for = nullptr;
-    if (c->d.p * (int64_t)c->K > OBJ_VALUE_ELEMS) {
+    if (formed) {
+    } else if (c->d.p * (int64_t)c->K > OBJ_VALUE_ELEMS) {
         // a large block: ||trial||^2 for the regulariser comes out of the pass that writes the trial point
         const int vb = vec_blocks(c->d.p * (int64_t)c->K);
         SSN_HIP(c, launch_axpy_sq(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, c->trial, c->d.ldw, c->red_sq,
@@ -1097,14 +1117,18 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         SOLVE_HIP(mark(E[2]));
         // CSR with a device mapping of the host block: CG leaves the slope's partials (n_slope > 0)
         int n_slope = 0;
-        SOLVE_TRY(cg_enqueue(c, c->grad, pr->theta, pr->T, c->dir, c->pub_dev ? &n_slope : nullptr));
+        bool tail_fused = false;             // small dense blocks: the CG tail has formed slope, trial point and publication
+        if (!c->trial) SOLVE_TRY(vec_bytes_alloc(c, &c->trial));
+        SOLVE_TRY(cg_enqueue(c, c->grad, pr->theta, pr->T, c->dir, c->pub_dev ? &n_slope : nullptr, W, c->trial, c->pub_dev,
+                             &tail_fused));
         // F(x_k), <dir, g> and the final CG state (which carries ||g||) reach the host through host-visible
         // memory written by one small kernel; without a device mapping of it, through two copies
-        if (n_slope == 0)
+        if (n_slope == 0 && !tail_fused)
             SOLVE_HIP(launch_dot_part(c->d.dtype, c->d.p, c->K, c->dir, c->d.ldw, c->grad, c->d.ldw, c->red_a, vb, nullptr,
                                       c->st));
         double *pub = c->pub_dev ? c->pub_host : c->host_pin;
-        if (c->pub_dev) {
+        if (tail_fused) {
+        } else if (c->pub_dev) {
             SOLVE_HIP(launch_solve_publish(c->red_a, n_slope ? n_slope : vb, c->scal_dev, c->slots + pr->T, c->scal_dev + 1,
                                            c->pub_dev, n_slope > 0, c->st));
         } else {
@@ -1117,7 +1141,7 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         // before the host waits: one wait per iteration covers the CG results and the trial's F.
         const bool ahead = look_on && k + 1 < pr->iters;
         bool first_mirrored = false;
-        SOLVE_TRY(trial_enqueue(c, W, c->dir, 1.0, ahead ? c->grad_next : nullptr, &first_mirrored));
+        SOLVE_TRY(trial_enqueue(c, W, c->dir, 1.0, ahead ? c->grad_next : nullptr, &first_mirrored, tail_fused));
         // CSR: while the device works through the queue above, the view of the next sample is built beside it
         if (!is_dense(c) && k + 1 < pr->iters) SOLVE_TRY(prebuild_sample_view(c, pr->S_all + (int64_t)(k + 1) * pr->nS, pr->nS));
         double f_first = 0.0;

@@ -254,6 +254,14 @@ struct FinCgArgs {
     int32_t k;
 };
 hipError_t launch_finalize_cg(int dtype, const FinArgs &a, const FinCgArgs &g, int blocks, hipStream_t st);
+// small blocks: lines 1-5 and the initial state in one launch (one block)
+hipError_t launch_cg_init_small(int dtype, const CgVecs &v, CgSlot *slot0, hipStream_t st);
+// inside ssn_solve: the tail, the slope <p_best, G>, the trial point W + p_best and the publication of F(x_k) (*f_dev),
+// the slope and the final state to host-visible memory; one launch with blocks == 1, else two (slope_part: blocks
+// partials)
+hipError_t launch_cg_tail_solve(int dtype, const CgVecs &v, const CgSlot *prev, CgSlot *fin, const double *rr_in, int n_in,
+                                double theta, double *trace, int k, const void *W, void *trial, const double *f_dev,
+                                double *slope_dev, double *host_out, double *slope_part, int blocks, hipStream_t st);
 // after the last product: the test of lines 10-11 for r_T, the pending p_best copy, the final state
 hipError_t launch_cg_tail(int dtype, const CgVecs &v, const CgSlot *prev, CgSlot *fin, const double *rr_in, int n_in,
                           double theta, double *trace, int k, int blocks, hipStream_t st);

@@ -411,6 +411,88 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_tail_kernel(CgVecs v, const CgSl
     }
 }
 
+// The tail for ssn_solve: the final state and the pending p_best copy as in cg_tail_kernel, then what the iteration
+// does next with the direction -- the slope <p_best, g> and the first trial point W + p_best, all from one pass over
+// the vectors.  One block (blocks of a few hundred elements) also publishes F(x_k), the slope and the state to
+// host-visible memory; several blocks leave slope partials and solve_publish_kernel follows.
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void cg_tail_solve_kernel(CgVecs v, const CgSlot *prev_p, CgSlot *fin,
+                                                                   const double *rr_in, int n_in, double theta, double *trace,
+                                                                   int k, const T *W, T *trial, const double *f_dev,
+                                                                   double *slope_dev, double *host_out, double *slope_part)
+{
+    const CgSlot prev = *prev_p;
+    const double rr_sum = sum_parts(rr_in, n_in);
+    const CgSlot c = cg_advance(prev, rr_sum, theta);
+    const int64_t total = v.p * v.K;
+    const T *pw = (const T *)v.pv, *G = (const T *)v.G;
+    T *pb = (T *)v.pbest;
+    double local = 0.0;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int64_t o = off_of(e, v.K, v.ld);
+        T d;
+        if (c.best_pending) {
+            d = pw[o];
+            pb[o] = d;
+        } else {
+            d = pb[o];
+        }
+        trial[o] = (T)(1.0 * (double)d + (double)W[o]);       // the arithmetic of the axpy kernel at alpha = 1
+        local += (double)d * (double)G[o];
+    }
+    const double slope = block_sum(local);
+    if (threadIdx.x == 0 && gridDim.x > 1) slope_part[blockIdx.x] = slope;       // several blocks: solve_publish_kernel follows
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        fin->rr = c.rr;
+        fin->rbest = c.rbest;
+        fin->gnorm = c.gnorm;
+        fin->done = c.done;
+        fin->iters = c.iters;
+        fin->flags = c.flags;
+        fin->brk = 0;
+        fin->alpha = 0.0;
+        fin->best_cur = 0;
+        fin->best_pending = 0;
+        fin->sHs = c.sHs;
+        fin->goff = 0.0;
+        fin->rho = fin->sigma = fin->pi = fin->pibest = 0.0;
+        if (trace && !prev.done && !prev.brk) trace[3 * (k - 1) + 1] = sqrt(rr_sum);
+        if (gridDim.x > 1) return;
+        *slope_dev = slope;
+        host_out[0] = *f_dev;
+        host_out[1] = slope;
+        // the state for the host, field by field (the struct above may not be visible to this thread's loads yet)
+        CgSlot *h = (CgSlot *)(host_out + 2);
+        h->rr = c.rr;
+        h->rbest = c.rbest;
+        h->gnorm = c.gnorm;
+        h->done = c.done;
+        h->iters = c.iters;
+        h->flags = c.flags;
+        h->brk = 0;
+        h->alpha = 0.0;
+        h->best_cur = 0;
+        h->best_pending = 0;
+        h->sHs = c.sHs;
+        h->goff = 0.0;
+        h->rho = h->sigma = h->pi = h->pibest = 0.0;
+    }
+}
+
+hipError_t launch_cg_tail_solve(int dtype, const CgVecs &v, const CgSlot *prev, CgSlot *fin, const double *rr_in, int n_in,
+                                double theta, double *trace, int k, const void *W, void *trial, const double *f_dev,
+                                double *slope_dev, double *host_out, double *slope_part, int blocks, hipStream_t st)
+{
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(cg_tail_solve_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, prev, fin, rr_in, n_in, theta,
+                           trace, k, (const float *)W, (float *)trial, f_dev, slope_dev, host_out, slope_part);
+    else
+        hipLaunchKernelGGL(cg_tail_solve_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, v, prev, fin, rr_in, n_in, theta,
+                           trace, k, (const double *)W, (double *)trial, f_dev, slope_dev, host_out, slope_part);
+    if (blocks > 1) return launch_solve_publish(slope_part, blocks, f_dev, fin, slope_dev, host_out, false, st);
+    return hipGetLastError();
+}
+
 hipError_t launch_cg_tail(int dtype, const CgVecs &v, const CgSlot *prev, CgSlot *fin, const double *rr_in, int n_in,
                           double theta, double *trace, int k, int blocks, hipStream_t st)
 {
@@ -775,6 +857,51 @@ __global__ __launch_bounds__(VEC_BLOCK) void cg_init_state_kernel(const double *
         s.sHs = 0.0;
         *slot0 = s;
     }
+}
+
+// lines 1-5 and the initial state in one launch of one block, for blocks small enough (dense workloads: a few
+// thousand elements); saves a launch boundary, which costs as much as the kernel
+template <typename T> __global__ __launch_bounds__(VEC_BLOCK) void cg_init_small_kernel(CgVecs v, CgSlot *slot0)
+{
+    const int64_t total = v.p * v.K;
+    const T *G = (const T *)v.G;
+    T *pv = (T *)v.pv, *r = (T *)v.r, *s = (T *)v.s, *pb = (T *)v.pbest;
+    double local = 0.0;
+    for (int64_t e = threadIdx.x; e < total; e += VEC_BLOCK) {
+        const int64_t o = off_of(e, v.K, v.ld);
+        const T gv = G[o];
+        pv[o] = T(0);
+        r[o] = -gv;
+        s[o] = -gv;
+        pb[o] = -gv;
+        local += (double)gv * (double)gv;
+    }
+    const double gg = block_sum(local);
+    if (threadIdx.x == 0) {
+        slot0->rr = gg;
+        slot0->rbest = sqrt(gg);
+        slot0->gnorm = sqrt(gg);
+        slot0->done = (gg == 0.0) ? 1 : 0;
+        slot0->iters = 0;
+        slot0->flags = 0;
+        slot0->brk = 0;
+        slot0->alpha = 0.0;
+        slot0->best_cur = 0;
+        slot0->best_pending = 0;
+        slot0->sHs = 0.0;
+        slot0->goff = 0.0;
+        slot0->rho = -1.0;
+        slot0->sigma = -1.0;
+        slot0->pi = 0.0;
+        slot0->pibest = -1.0;
+    }
+}
+
+hipError_t launch_cg_init_small(int dtype, const CgVecs &v, CgSlot *slot0, hipStream_t st)
+{
+    if (dtype == SSN_F32) hipLaunchKernelGGL(cg_init_small_kernel<float>, dim3(1), dim3(VEC_BLOCK), 0, st, v, slot0);
+    else hipLaunchKernelGGL(cg_init_small_kernel<double>, dim3(1), dim3(VEC_BLOCK), 0, st, v, slot0);
+    return hipGetLastError();
 }
 
 hipError_t launch_cg_init_state(const double *gg_part, int nparts, CgSlot *slot0, hipStream_t st,
