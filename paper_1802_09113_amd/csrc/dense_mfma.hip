@@ -778,14 +778,17 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     // storage of ldx elements, so every issued load is in bounds and none depends on another
     auto load_block = [&](int64_t xr, pack(&x)[NLD]) {
         const T *xbase = X + xr * a.ldx + fs + VEC * g;
-        const int64_t room = a.ldx - fs - VEC * g;           // elements from xbase to the end of the row
+        // elements from xbase to the end of the row (32-bit: the comparisons below cost a register pair and
+        // several instructions each in 64 bits, and there is one per load)
+        const int64_t room64 = a.ldx - fs - VEC * g;
+        const int room = room64 > 0x7fffffff ? 0x7fffffff : (int)room64;
 #pragma unroll
         for (int j = 0; j < NLD; ++j)
             if (LF * j + VEC <= room) x[j] = *(const pack *)(xbase + LF * j);
     };
     // one vector of the next tile; issued one at a time between the MFMAs of the current block, because a
     // compute unit cannot hold a whole tile of outstanding loads and a wave stalls at issue when it is full
-    auto load_one = [&](const T *xbase, int64_t room, int j, pack(&x)[NLD]) {
+    auto load_one = [&](const T *xbase, int room, int j, pack(&x)[NLD]) {
         if (LF * j + VEC <= room) x[j] = *(const pack *)(xbase + LF * j);
     };
     // this lane's elements LF * j + m of the tile are inside the wave's slice for LF * j + m < nval (one 32-bit
@@ -856,13 +859,14 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     // ONE: this lane's W operands, M[fs + LF*j + VEC*g + m][qc], zero beyond p
     T bd[ONE ? NLD : 1][VEC];
     if constexpr (ONE) {
-        const int64_t f0 = fs + VEC * g;
+        // 32-bit offsets from the uniform base (the launcher admits the one-pass kernel only where p * ldm fits)
+        const int f0 = fs + VEC * g, ldm32 = (int)a.ldm, p32 = (int)p;
 #pragma unroll
         for (int j = 0; j < NLD; ++j)
 #pragma unroll
             for (int m = 0; m < VEC; ++m) {
-                const int64_t ff = f0 + LF * j + m;
-                bd[j][m] = M[(ff < p) ? (ff * a.ldm + qc) : 0];
+                const int ff = f0 + LF * j + m;
+                bd[j][m] = M[(unsigned)((ff < p32) ? (ff * ldm32 + qc) : 0)];
             }
     } else {
         w_load();
@@ -978,7 +982,8 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
             xr_n = (rbn + gridDim.x < nblk) ? block_row(rbn + gridDim.x) : 0;
         }
         const T *xbase_n = X + xr_next * a.ldx + fs + VEC * g;
-        const int64_t room_n = has_next ? (a.ldx - fs - VEC * g) : 0;      // no next block: every load is skipped
+        const int64_t room64_n = a.ldx - fs - VEC * g;
+        const int room_n = !has_next ? 0 : (room64_n > 0x7fffffff ? 0x7fffffff : (int)room64_n);   // no next block: every load is skipped
         // issued during phase A, the rest in phase C (all of them in phase A, or a quarter, is 2-8 % slower)
         constexpr int LOADS_A = HAS_C ? (NLD + 1) / 2 : NLD;
         constexpr int LOADS_C = (NLD - LOADS_A + NSB - 1) / NSB;          // per transposition sub-block
@@ -1112,7 +1117,7 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
         asm volatile("" : "+v"(g_out), "+v"(fs_out));
         const int lane_row = d_row<T>(g_out, 0);             // d_row(g, v) = lane_row + d_row(0, v)
         T *pl = (T *)a.part + (int64_t)blockIdx.x * p * K + ((int64_t)fs_out + VEC * lane_row) * K + q;
-        const int64_t flane = fs_out + VEC * lane_row;
+        const int nout = (int)(fend - fs_out) - VEC * lane_row;      // this lane's rows fo of the slice are inside it for fo < nout
 #pragma unroll
         for (int h = 0; h < NSB; ++h) {
 #pragma unroll
@@ -1120,7 +1125,7 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int fo = h * SBF + VEC * d_row<T>(0, v) + m;       // uniform
-                    if (flane + fo < fend && q < K) pl[(int64_t)fo * K] = G[h * VEC + m][v];
+                    if (fo < nout && q < K) pl[(int64_t)fo * K] = G[h * VEC + m][v];
                 }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -1216,6 +1221,7 @@ template <typename T> static bool fused_ok(const RowsArgs &a)
 {
     constexpr int VEC = 16 / sizeof(T);
     if (a.K > 16 || !vec_ok<T>(a.X, a.ldx)) return false;
+    if ((a.p + 256) * a.ldm >= ((int64_t)1 << 31)) return false;         // 32-bit offsets into the p x K operand
     // whole-vector loads must stay inside a row's storage
     if (a.p % VEC != 0 && a.ldx < (a.p + VEC - 1) / VEC * VEC) return false;
     for (int c = 0; c < 2; ++c) {            // both kernel families (with / without transposed product) must fit
