@@ -193,8 +193,17 @@ int ssn_hessvec(ssn_ctx *ctx, const void *W, const int32_t *S, int64_t nS, const
  * G [dev] right-hand side gradient; P_out [dev] receives p_best; at most T products.
  * trace [host, nullable, 3*T doubles]: per product k the step alpha_k, ||r_{k+1}||, s_k^T H s_k.
  * The whole loop runs on the device without host round trips; the call synchronises once at
- * the end to fill info / trace.  The curvature s^T H s is formed as s_S * sum_i z_i . u_i + lambda s.s
- * (Z = X_S s, U of eq. (12)), the same number as s^T (H s) up to rounding, and H s itself is not stored. */
+ * the end to fill info / trace.  The iterates are those of Alg. 2 up to rounding; how they are formed:
+ *   - No inner product waits for a vector: with Z = X_S v and U the rows of eq. (12), v^T (X_S^T U) is the
+ *     sum over the sample of z_i . u_i, which the product's own launch leaves as partial sums.
+ *   - Dense layouts: the product is applied to the residual r_k (H is linear, so with line 12
+ *     H s_k = H r_k + beta H s_{k-1}; H s is kept as a vector and updated), and
+ *     s_k^T H s_k = r_k^T H r_k + 2 beta r_k^T H s_{k-1} + beta^2 s_{k-1}^T H s_{k-1}: two launches per product.
+ *     The theta test for r_k is made after product k has been enqueued, so a run that stops early has made
+ *     one product more than info.iters reports (its result is discarded).
+ *   - CSR layout: H_S acts as lambda I on every coordinate whose column no sampled row touches, so r, s, p
+ *     stay multiples of g there; the vectors of Alg. 2 are kept on the sampled columns only, three scalars
+ *     carry the rest, and P_out is assembled at the end. */
 int ssn_cg(ssn_ctx *ctx, const void *G, double theta, int32_t T, void *P_out,
            ssn_cg_info *info, double *trace);
 
