@@ -944,7 +944,7 @@ static int enqueue_slope(ssn_ctx *c, const void *P, const void *G)
 
 int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
                     int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok, void *G_first = nullptr,
-                    const double *first_f = nullptr, int first_status = SSN_OK);
+                    const double *first_f = nullptr, int first_status = SSN_OK, void *trial_dst = nullptr);
 
 int ssn_linesearch(ssn_ctx *c, const void *W, const void *P, const void *G, double fW, double beta, double rho,
                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok)
@@ -958,33 +958,39 @@ int ssn_linesearch(ssn_ctx *c, const void *W, const void *P, const void *G, doub
 
 // The trial point W + alpha P into c->trial and F there enqueued (into scal_dev[0]; *mirrored: also into the
 // host-visible word).  G_first (nullable): evaluate with the gradient pass, which leaves grad F there too.
-// formed: c->trial already holds the trial point (the CG tail of ssn_solve wrote it)
-int trial_enqueue(ssn_ctx *c, const void *W, const void *P, double alpha, void *G_first, bool *mirrored, bool formed = false)
+// formed: dst already holds the trial point (the CG tail of ssn_solve wrote it).  dst == nullptr: c->trial.
+int trial_enqueue(ssn_ctx *c, const void *W, const void *P, double alpha, void *G_first, bool *mirrored, bool formed = false,
+                  void *dst = nullptr)
 {
-    if (!c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
+    if (!dst) {
+        if (!c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
+        dst = c->trial;
+    }
     c->sq_for = nullptr;
     if (formed) {
     } else if (c->d.p * (int64_t)c->K > OBJ_VALUE_ELEMS) {
         // a large block: ||trial||^2 for the regulariser comes out of the pass that writes the trial point
         const int vb = vec_blocks(c->d.p * (int64_t)c->K);
-        SSN_HIP(c, launch_axpy_sq(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, c->trial, c->d.ldw, c->red_sq,
-                                  vb, c->st));
-        c->sq_for = c->trial;
+        SSN_HIP(c, launch_axpy_sq(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, dst, c->d.ldw, c->red_sq, vb,
+                                  c->st));
+        c->sq_for = dst;
         c->n_sq = vb;
     } else {
-        SSN_HIP(c, launch_axpy(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, c->trial, c->d.ldw, c->st));
+        SSN_HIP(c, launch_axpy(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, dst, c->d.ldw, c->st));
     }
-    if (G_first) return gradient_impl(c, c->trial, G_first, nullptr, true, nullptr, 0, mirrored);
-    return objective_enqueue(c, c->trial, mirrored);
+    if (G_first) return gradient_impl(c, dst, G_first, nullptr, true, nullptr, 0, mirrored);
+    return objective_enqueue(c, dst, mirrored);
 }
 
 // Alg. 3 with the slope <P, G> already on the host.  G_first (nullable): the first trial, alpha = 1, is
 // evaluated by the gradient pass, which leaves grad f(W + P) there next to the same F(W + P); when that
 // trial is accepted the caller already holds the gradient of the next iterate.  first_f (nullable): the
 // caller has already evaluated the first trial (trial_enqueue + read_objective): its value and status.
+// On return the trial buffer (trial_dst, or c->trial) holds W + alpha P for the alpha returned: the last point
+// evaluated is the one the caller moves to, whether the Armijo test held there or the reductions ran out.
 int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
                     int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok, void *G_first,
-                    const double *first_f, int first_status)
+                    const double *first_f, int first_status, void *trial_dst)
 {
     double alpha = 1.0, ft = 0.0;
     int i = 0, evals = 0, good = 0;
@@ -995,7 +1001,7 @@ int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double 
             s = first_status;
         } else {
             bool mirrored = false;
-            SSN_TRY(trial_enqueue(c, W, P, alpha, i == 0 ? G_first : nullptr, &mirrored));
+            SSN_TRY(trial_enqueue(c, W, P, alpha, i == 0 ? G_first : nullptr, &mirrored, false, trial_dst));
             s = read_objective(c, mirrored, &ft);
         }
         if (s != SSN_OK && s != SSN_E_NONFINITE) return s;
@@ -1037,6 +1043,7 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         return fail(c, SSN_E_INVALID_ARG, "ssn_solve: bad argument");
     if (!c->grad) SSN_TRY(vec_bytes_alloc(c, &c->grad));
     if (!c->dir) SSN_TRY(vec_bytes_alloc(c, &c->dir));
+    if (!c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
     if (pr->Sg_all && pr->nSg < 1) return fail(c, SSN_E_INVALID_ARG, "ssn_solve: gradient sample size < 1");
     // the whole sample schedule is checked once, not sample by sample
     if (pr->iters > 0) {
@@ -1090,6 +1097,9 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         if (log && pending < max_log) log[pending] = pend_rec;
         pending = -1;
     };
+    // The iterate lives alternately in the caller's block and in the trial buffer: a step is a change of roles
+    // (see the end of the loop), and the caller's block receives the final iterate at the end if it is not there.
+    void *cur = W, *oth = c->trial;
     int k = 0;
 #define SOLVE_TRY(expr)                     \
     do {                                    \
@@ -1110,16 +1120,15 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         ssn_iter_record rec{};
         rec.test_acc = std::nan("");
         SOLVE_HIP(mark(E[0]));
-        if (pr->Sg_all) SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, false, pr->Sg_all + (int64_t)k * pr->nSg, pr->nSg));
-        else if (!have_next) SOLVE_TRY(gradient_impl(c, W, c->grad, nullptr, true));
+        if (pr->Sg_all) SOLVE_TRY(gradient_impl(c, cur, c->grad, nullptr, false, pr->Sg_all + (int64_t)k * pr->nSg, pr->nSg));
+        else if (!have_next) SOLVE_TRY(gradient_impl(c, cur, c->grad, nullptr, true));
         SOLVE_HIP(mark(E[1]));
-        SOLVE_TRY(hess_prepare_impl(c, W, pr->S_all + (int64_t)k * pr->nS, pr->nS, false, true));
+        SOLVE_TRY(hess_prepare_impl(c, cur, pr->S_all + (int64_t)k * pr->nS, pr->nS, false, true));
         SOLVE_HIP(mark(E[2]));
         // CSR with a device mapping of the host block: CG leaves the slope's partials (n_slope > 0)
         int n_slope = 0;
         bool tail_fused = false;             // small dense blocks: the CG tail has formed slope, trial point and publication
-        if (!c->trial) SOLVE_TRY(vec_bytes_alloc(c, &c->trial));
-        SOLVE_TRY(cg_enqueue(c, c->grad, pr->theta, pr->T, c->dir, c->pub_dev ? &n_slope : nullptr, W, c->trial, c->pub_dev,
+        SOLVE_TRY(cg_enqueue(c, c->grad, pr->theta, pr->T, c->dir, c->pub_dev ? &n_slope : nullptr, cur, oth, c->pub_dev,
                              &tail_fused));
         // F(x_k), <dir, g> and the final CG state (which carries ||g||) reach the host through host-visible
         // memory written by one small kernel; without a device mapping of it, through two copies
@@ -1141,7 +1150,7 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         // before the host waits: one wait per iteration covers the CG results and the trial's F.
         const bool ahead = look_on && k + 1 < pr->iters;
         bool first_mirrored = false;
-        SOLVE_TRY(trial_enqueue(c, W, c->dir, 1.0, ahead ? c->grad_next : nullptr, &first_mirrored, tail_fused));
+        SOLVE_TRY(trial_enqueue(c, cur, c->dir, 1.0, ahead ? c->grad_next : nullptr, &first_mirrored, tail_fused, oth));
         // CSR: while the device works through the queue above, the view of the next sample is built beside it
         if (!is_dense(c) && k + 1 < pr->iters) SOLVE_TRY(prebuild_sample_view(c, pr->S_all + (int64_t)(k + 1) * pr->nS, pr->nS));
         double f_first = 0.0;
@@ -1176,8 +1185,8 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
             rec.cg_iters = info.iters;
             rec.cg_rel_res = info.rel_res;
             double fn = 0.0;
-            SOLVE_TRY(linesearch_impl(c, W, c->dir, rec.f, slope, pr->beta, pr->rho, pr->imax, &rec.alpha, &fn, &rec.ls_evals,
-                                      &rec.ls_ok, nullptr, &f_first, first_status));
+            SOLVE_TRY(linesearch_impl(c, cur, c->dir, rec.f, slope, pr->beta, pr->rho, pr->imax, &rec.alpha, &fn, &rec.ls_evals,
+                                      &rec.ls_ok, nullptr, &f_first, first_status, oth));
             f_carry = fn;
             const bool first_accepted = rec.ls_ok && rec.ls_evals == 1;
             have_next = ahead && first_accepted;
@@ -1188,11 +1197,13 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
             look_on = look && first_accepted;
         }
         SOLVE_HIP(mark(E[4]));
-        SOLVE_TRY(ssn_axpy(c, rec.alpha, c->dir, W));
+        // line 7 of Alg. 1, x_{k+1} = x_k + alpha p_k: the trial buffer already holds exactly that (the last point
+        // the line search evaluated, formed by the same arithmetic), so the two buffers change roles
+        std::swap(cur, oth);
         if (pr->test) {
             // the held-out context runs on its own stream: wait for the update first
             SOLVE_HIP(hipStreamSynchronize(c->st));
-            SOLVE_TRY(ssn_predict(pr->test, W, nullptr, &rec.test_acc));
+            SOLVE_TRY(ssn_predict(pr->test, cur, nullptr, &rec.test_acc));
         }
         SOLVE_HIP(mark(E[5]));
         pending = k;
@@ -1201,6 +1212,13 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
 done:
 #undef SOLVE_TRY
 #undef SOLVE_HIP
+    if (cur != W) {                          // the final iterate into the caller's block
+        const hipError_t ce = launch_scale_copy(c->d.dtype, c->d.p, c->K, 1.0, cur, c->d.ldw, W, c->d.ldw, nullptr, c->st);
+        if (ce != hipSuccess && status == SSN_OK) {
+            c->err = std::string("copy of the final iterate: ") + hipGetErrorString(ce);
+            status = SSN_E_HIP;
+        }
+    }
     (void)hipStreamSynchronize(c->st);
     if (c->st_aux) (void)hipStreamSynchronize(c->st_aux);
     c->next_ready = false;                   // a view built ahead is only good inside this call
