@@ -312,6 +312,27 @@ def test_ssn_on_the_sparse_layout(dtype, nS):
     pair.close()
 
 
+@pytest.mark.parametrize("T", [0, 1, 3])
+def test_ssn_with_tiny_cg_budgets_and_an_odd_number_of_steps(tiny, T):
+    # T = 0: Alg. 2 returns its initial p_best = -g and the iteration is a steepest-descent step with back-tracking;
+    # T = 1, 3: the shortest loops of the two-launch CG.  Three iterations: the iterate ends in the solver's own
+    # buffer and has to be copied back into the caller's block.
+    d = tiny
+    pair = Pair(d, F64, ldw=8)                                # padded blocks: K = 2 of 8 columns in use
+    S_all = synth.sample_schedule(2000, d["nS"], 3)
+    W0h, W0d = pair.block(np.zeros((pair.p, pair.K)))
+    Wref, log_ref, done_ref = pair.oracle.ssn(W0h, S_all, theta=1e-4, T=T)
+    recs, done = pair.gpu.ssn_solve(W0d, torch.from_numpy(S_all).cuda(), theta=1e-4, T=T)
+    torch.cuda.synchronize()
+    assert done == done_ref == 3
+    assert [r["alpha"] for r in recs] == list(log_ref[:, 4])
+    assert [r["cg_iters"] for r in recs] == [int(x) for x in log_ref[:, 2]]
+    np.testing.assert_allclose([r["f"] for r in recs], log_ref[:, 0], rtol=1e-10)
+    assert rel_err(pair.host(W0d), Wref) <= 1e-9
+    assert torch.isnan(W0d[:, pair.K:]).all()                 # the padding columns of the caller's block are untouched
+    pair.close()
+
+
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 def test_ssn_with_sub_sampled_gradient(tiny, dtype):
     # Alg. 1 with eq. (2a) and eq. (2b): 20 % of the rows for g, 5 % for H
