@@ -223,14 +223,15 @@ hipError_t launch_cg_init_support(int dtype, const CgVecs &v, const void *G, int
 hipError_t launch_cg_expand(int dtype, int64_t p, int K, const void *G, int64_t ldg, void *P_out, int64_t ldp,
                             const CgSlot *fin, const void *pb, const int32_t *cols, int64_t ncols, double *dot_part,
                             int *n_dot, hipStream_t st);
-// ss_part (nullable): one partial of s.s per block for the new direction; update_p: also p += cur->alpha * s,
-// and p_best is then kept lazily (CgSlot::best_cur): launch_cg_finish after the last product completes it
+// CSR path, lines 10-12 (the dense paths do all of lines 7-12 in finalize_cg_kernel).  ss_part (nullable): one partial
+// of s.s per block for the new direction; update_p: also p += cur->alpha * s, and p_best is then kept lazily
+// (CgSlot::best_cur): launch_cg_finish after the last product completes it; lambda: for the off-support scalars
 hipError_t launch_cg_step2(int dtype, const CgVecs &v, const CgSlot *cur, CgSlot *next, const double *rr_part,
                            int n_rr, double theta, double *trace_k, double *ss_part, bool update_p, int blocks,
                            hipStream_t st, double lambda = 0.0);
 // CSR path, lines 7-9 in pieces: cur->alpha from the partials of sum_i z_i . u_i and of s.s (one block); then the
-// sparse part of r -= alpha H s goes through launch_csr_scatter and the dense part, r -= alpha lambda s with the
-// partials of the new r.r, through launch_cg_r_update
+// sparse part of r -= alpha H s goes through the column-sorted gather (launch_csc_apply) and the rest,
+// r -= alpha lambda s with the partials of the new r.r, through launch_cg_r_update
 // p_best = p where the final state says the best iterate is still only in p
 hipError_t launch_cg_finish(int dtype, const CgVecs &v, const CgSlot *fin, int blocks, hipStream_t st);
 hipError_t launch_cg_alpha(CgSlot *cur, const double *zu_part, int n_zu, const double *ss_part, int n_ss, double scale,

@@ -1001,14 +1001,14 @@ hipError_t launch_cg_expand(int dtype, int64_t p, int K, const void *G, int64_t 
     return hipGetLastError();
 }
 
-// lines 10-12: best-iterate memory, theta test, new search direction
+// CSR path, lines 10-12: best-iterate memory, theta test, new search direction (and, with update_p, line 8)
 template <typename T>
 __global__ __launch_bounds__(VEC_BLOCK) void cg_step2_kernel(CgVecs v, const CgSlot *cur, CgSlot *next,
                                                               const double *rr_part, int n_rr, double theta,
                                                               double *trace_k, double *ss_part, bool update_p, double lambda)
 {
-    // the first element of every thread is fetched before anything waits: on the small blocks of the dense
-    // workloads that is the only one, and the kernel is then two dependent round trips instead of three
+    // the first element of every thread is fetched before anything waits: on small blocks that is the only
+    // one, and the kernel is then two dependent round trips instead of three
     const int64_t total = v.p * v.K;
     const int64_t stride = (int64_t)gridDim.x * VEC_BLOCK;
     const int64_t e0 = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x;
