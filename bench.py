@@ -250,15 +250,21 @@ def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
 def pmc_sequence(data, dtype_name):
     """Three launches of each hot kernel plus two calibration kernels of known traffic (read n*p*e bytes;
     read and write n*p*e bytes), for per-dispatch hardware counters."""
+    import numpy as np
     import torch
     from paper_1802_09113_amd import synth
     from paper_1802_09113_amd.binding import Context
     tdt = torch.float64 if dtype_name == "f64" else torch.float32
     n, p, C, K, nS = data["n"], data["p"], data["C"], data["K"], data["nS"]
-    assert data["layout"] == "dense", "the counter sequence covers the dense workloads"
-    X = torch.from_numpy(data["X"]).to("cuda:0").to(tdt)
     labels = torch.from_numpy(data["labels"]).to("cuda:0")
-    ctx = Context(labels, C, data["lam"], X=X)
+    if data["layout"] == "csr":
+        # calibration kernels: a streaming read of the values, and a copy of them
+        X = torch.from_numpy(data["vals"]).to("cuda:0").to(tdt)
+        csr = (torch.from_numpy(data["rowptr"].astype(np.int32)).to("cuda:0"), torch.from_numpy(data["colidx"]).to("cuda:0"), X)
+        ctx = Context(labels, C, data["lam"], csr=csr, p=p)
+    else:
+        X = torch.from_numpy(data["X"]).to("cuda:0").to(tdt)
+        ctx = Context(labels, C, data["lam"], X=X)
     W = torch.from_numpy(synth.probe(p, K, sub=1, scale=0.05)).to("cuda:0").to(tdt)
     V = torch.from_numpy(synth.probe(p, K, sub=2)).to("cuda:0").to(tdt)
     ctx.ssn_hess_prepare(W, torch.from_numpy(synth.sample_rows(n, nS)).to("cuda:0"))
