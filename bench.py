@@ -28,6 +28,17 @@ MEASURED_TRAFFIC = {
     ("image_like", "f64", "dense_fused_kernel<OBJ>"): 377.5e6,
     ("image_like", "f64", "dense_fused_kernel<GRAD>"): 377.8e6 + 14.5e6,
     ("image_like", "f64", "dense_fused_kernel<APPLY>"): 19.8e6 + 10.6e6,
+    # profiles/dense_two_kernel_wide_f64_hbm_traffic_pmc.md, profiles/csr_sparse_f64_hbm_traffic_pmc.md
+    ("wide", "f64", "dense_rows_kernel<OBJ>"): 1234.7e6,
+    ("wide", "f64", "dense_rows_kernel<GRAD>"): 1235.6e6 + 6.4e6,
+    ("wide", "f64", "dense_xtu_kernel (n rows)"): 1283.4e6 + 9.5e6,
+    ("wide", "f64", "dense_rows_kernel<APPLY>"): 63.6e6 + 0.3e6,
+    ("wide", "f64", "dense_xtu_kernel (|S| rows)"): 64.2e6 + 8.8e6,
+    ("sparse_csr", "f64", "csr_rows_kernel<OBJ>"): 887.9e6,
+    ("sparse_csr", "f64", "csr_rows_kernel<GRAD>"): 879.6e6 + 3.1e6,
+    ("sparse_csr", "f64", "csc_piece_kernel + csc_combine_kernel (n rows)"): 524.1e6 + 57.0e6 + 152.4e6 + 7.8e6,
+    ("sparse_csr", "f64", "csr_rows_kernel<APPLY>"): 54.9e6 + 0.2e6,
+    ("sparse_csr", "f64", "csc_piece_kernel + csc_combine_kernel (|S| rows)"): 42.3e6 + 4.4e6 + 22.1e6 + 0.5e6,
 }
 
 
