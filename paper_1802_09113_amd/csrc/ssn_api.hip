@@ -76,6 +76,7 @@ struct ssn_ctx {
     void *grad_next = nullptr;                 // gradient at the first line-search trial (look-ahead of ssn_solve)
     CgSlot *slots = nullptr;
     int slots_cap = 0;
+    int cg_gg_parts = 0;                       // dense CG: partials of g.g in red_a the first finalize forms slot 0 from (0: slot 0 is set)
     double *trace_dev = nullptr;
 };
 
@@ -450,6 +451,8 @@ int cg_product_step(ssn_ctx *c, const CgVecs &v, CgSlot *slots, int k, double th
     // launches look at is the one before it
     const CgSlot *flag_slot = (is_dense(c) && k > 0) ? slots + (k - 1) : cur;
     const int32_t *skip = (const int32_t *)((const char *)flag_slot + offsetof(CgSlot, done));
+    const bool form_state = is_dense(c) && k == 0 && c->cg_gg_parts > 0;     // slot 0 is written behind product 0
+    if (form_state) skip = nullptr;
     double *trace_k = trace + 3 * k;
     RowsArgs a = rows_base(c);
     a.S = c->S;
@@ -500,6 +503,8 @@ int cg_product_step(ssn_ctx *c, const CgVecs &v, CgSlot *slots, int k, double th
         g.prev = k > 0 ? slots + (k - 1) : nullptr;
         g.cur = cur;
         g.first = k == 0;
+        g.gg_part = form_state ? c->red_a : nullptr;
+        g.n_gg = form_state ? c->cg_gg_parts : 0;
         g.theta = theta;
         g.pv = v.pv;
         g.r = v.r;
@@ -826,6 +831,7 @@ static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *
         c->trace_dev = nullptr;
         SSN_HIP(c, hipMalloc((void **)&c->slots, sizeof(CgSlot) * (size_t)(T + 1)));
         SSN_HIP(c, hipMalloc((void **)&c->trace_dev, sizeof(double) * 3 * (size_t)(T + 1)));
+        SSN_HIP(c, hipMemsetAsync(c->slots, 0, sizeof(CgSlot) * (size_t)(T + 1), c->st));
         c->slots_cap = T + 1;
     }
     CgVecs v{};
@@ -838,6 +844,7 @@ static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *
     v.s = c->cg_s;
     v.pbest = P_out;
     int vb = vec_blocks(c->d.p * (int64_t)c->K);
+    c->cg_gg_parts = 0;
     // one block does it all only where each thread has a handful of elements: a single block walking thousands of
     // elements is a chain of dependent round trips and loses more than the launches it saves
     const bool small = c->d.p * (int64_t)c->K <= 8 * VEC_BLOCK;
@@ -845,7 +852,9 @@ static int cg_enqueue(ssn_ctx *c, const void *G, double theta, int32_t T, void *
         SSN_HIP(c, launch_cg_init_small(c->d.dtype, v, c->slots, c->st));
     } else if (is_dense(c)) {
         SSN_HIP(c, launch_cg_init(c->d.dtype, v, c->red_a, c->red_c, vb, c->st));
-        SSN_HIP(c, launch_cg_init_state(c->red_a, vb, c->slots, c->st));
+        // the initial state is one more reduction of g.g: product 0's finalize does it (no launch of its own)
+        if (T > 0) c->cg_gg_parts = vb;
+        else SSN_HIP(c, launch_cg_init_state(c->red_a, vb, c->slots, c->st));
     } else {
         // CSR: H_S = scale * X_S^T D X_S + lambda I acts as lambda I on every coordinate outside the columns the
         // sample touches, so r, s, p stay multiples of g there (CgSlot::rho, sigma, pi) and the vectors of

@@ -242,8 +242,10 @@ hipError_t launch_cg_r_update(int dtype, const CgVecs &v, const CgSlot *cur, dou
 // Dense paths: the sum of the product's partials fused with lines 7-12 of Alg. 2 (see finalize_cg_kernel).
 struct FinCgArgs {
     const CgSlot *prev;      // state before product k-1 (k >= 1), completed by that product's finalize
-    CgSlot *cur;             // state before product k: read (k == 0, from the initialisation) or written by block 0
+    CgSlot *cur;             // state before product k, written by block 0 (k == 0 with n_gg == 0: the initialisation's, read)
     int32_t first;           // k == 0
+    const double *gg_part;   // k == 0: n_gg partials of g.g; the initial state (line 1 of Alg. 2) is formed from them here
+    int n_gg;                //         0: slot *cur already holds the initial state
     double theta;
     void *pv, *r, *s, *hs, *pbest;   // CG vectors on the leading dimension FinArgs::ldm (FinArgs::M is not used)
     const double *zu_part;   // per-wave partials of sum_i z_i . u_i left by the product's launch (operand r_k)

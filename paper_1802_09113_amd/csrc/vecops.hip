@@ -239,7 +239,9 @@ template <typename T, int EL> __global__ __launch_bounds__(VEC_BLOCK) void final
     const int el = threadIdx.x % EL, cl = threadIdx.x / EL;
     const int64_t total = a.p * a.K;
     const T *part = (const T *)a.part;
-    const CgSlot prev = g.first ? *g.cur : *g.prev;
+    const CgSlot prev = g.first ? *g.cur : *g.prev;    // k == 0 with n_gg > 0: not the state yet, every use is overridden
+    const double *rin = g.first ? g.gg_part : g.rr_in;
+    const int nin = g.first ? g.n_gg : g.n_in;
     double vz = 0.0, vr = 0.0, vh = 0.0, tfirst = 0.0;   // tfirst: chunks cl, cl + CLN, .. (first eight) of the first group
     {
         double z4[4], r2[2], h2[2];
@@ -251,9 +253,9 @@ template <typename T, int EL> __global__ __launch_bounds__(VEC_BLOCK) void final
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int i = threadIdx.x + u * VEC_BLOCK;
-            const bool in = !g.first && i < g.n_in;
-            r2[u] = in ? g.rr_in[i] : 0.0;
-            h2[u] = in ? g.rhs_in[i] : 0.0;
+            const bool in = i < nin;
+            r2[u] = in ? rin[i] : 0.0;
+            h2[u] = (in && !g.first) ? g.rhs_in[i] : 0.0;
         }
         T first[8];
         const int64_t ef = (int64_t)blockIdx.x * EL + el;
@@ -267,23 +269,25 @@ template <typename T, int EL> __global__ __launch_bounds__(VEC_BLOCK) void final
         for (int i = threadIdx.x + 4 * VEC_BLOCK; i < g.n_zu; i += VEC_BLOCK) vz += g.zu_part[i];
         vr = r2[0] + r2[1];
         vh = h2[0] + h2[1];
-        if (!g.first)
-            for (int i = threadIdx.x + 2 * VEC_BLOCK; i < g.n_in; i += VEC_BLOCK) {
-                vr += g.rr_in[i];
-                vh += g.rhs_in[i];
-            }
+        for (int i = threadIdx.x + 2 * VEC_BLOCK; i < nin; i += VEC_BLOCK) {
+            vr += rin[i];
+            if (!g.first) vh += g.rhs_in[i];
+        }
 #pragma unroll
         for (int u = 0; u < 8; ++u) tfirst += (cl + u * CLN < a.nchunks) ? (double)first[u] : 0.0;
     }
     double zu, rr_sum, rhs;
     block_sum3(vz, vr, vh, zu, rr_sum, rhs);
     CgSlot c = cg_advance(prev, rr_sum, g.theta);
-    if (g.first) {                                    // the state before product 0 is the initialisation's, as it is
-        c.rr = prev.rr;
-        c.rbest = prev.rbest;
-        c.done = prev.done;
-        c.iters = prev.iters;
-        c.flags = prev.flags;
+    if (g.first) {                                    // the state before product 0: line 1 of Alg. 2 (r_0 = -g)
+        const bool fresh = g.n_gg > 0;                // from the partials of g.g, else the initialisation's as it is
+        const double gn = sqrt(rr_sum);
+        c.rr = fresh ? rr_sum : prev.rr;
+        c.rbest = fresh ? gn : prev.rbest;
+        c.gnorm = fresh ? gn : prev.gnorm;
+        c.done = fresh ? (rr_sum == 0.0 ? 1 : 0) : prev.done;
+        c.iters = fresh ? 0 : prev.iters;
+        c.flags = fresh ? 0 : prev.flags;
         c.best_pending = 0;
     }
     const double beta = (g.first || c.done) ? 0.0 : c.rr / prev.rr;
