@@ -585,6 +585,7 @@ int ssn_destroy(ssn_ctx *c)
 {
     if (!c) return SSN_E_INVALID_ARG;
     (void)hipStreamSynchronize(c->st);
+    if (c->st_aux) (void)hipStreamSynchronize(c->st_aux);      // a view of the next sample may still be in the making
     void *dev[] = {c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->red_c, c->red_sq, c->scal_dev, c->int_dev,
                    c->cg_p, c->cg_r, c->cg_s, c->cg_hs, c->cg_parts, c->cg_pb, c->trial, c->grad, c->grad_next, c->dir, c->slots, c->trace_dev};
     for (void *p : dev)
