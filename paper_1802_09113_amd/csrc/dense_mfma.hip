@@ -1228,7 +1228,7 @@ template <typename T> static bool fused_ok(const RowsArgs &a)
         int nw, fw;
         const int i = fused_shape<T>(a.p, c == 1, &nw, &fw);
         if (i < 0) return false;
-        if (fused_lds_bytes<T>(nw, fw, FusedTable<T>::shape[i].nld, FusedTable<T>::shape[i].maxw, a.K, c == 1) > 160 * 1024)
+        if (fused_lds_bytes<T>(nw, fw, FusedTable<T>::shape[i].nld, nw == 1 ? 1 : FusedTable<T>::shape[i].maxw, a.K, c == 1) > 160 * 1024)
             return false;
     }
     return true;
@@ -1239,6 +1239,15 @@ template <typename T> static bool fused_ok(const RowsArgs &a)
 bool dense_fused_supported(int dtype, const RowsArgs &a)
 {
     return dtype == SSN_F32 ? fused_ok<float>(a) : fused_ok<double>(a);
+}
+
+// dynamic LDS of the launch fused_launch_mode would make (0: no shape fits)
+template <typename T> static size_t fused_grid_lds(int64_t p, int K, bool has_c)
+{
+    int nw, fw;
+    const int i = fused_shape<T>(p, has_c, &nw, &fw);
+    if (i < 0) return 0;
+    return fused_lds_bytes<T>(nw, fw, FusedTable<T>::shape[i].nld, nw == 1 ? 1 : FusedTable<T>::shape[i].maxw, K, has_c);
 }
 
 // waves per workgroup the one-pass kernel would use for a.mode
@@ -1258,6 +1267,14 @@ int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus)
     if (dtype == SSN_F32) fused_shape<float>(a.p, has_c, &nw, &fw);
     else fused_shape<double>(a.p, has_c, &nw, &fw);
     int per_cu = 8 / nw;                          // aim at 8 or more waves per compute unit
+    if (per_cu < 1) per_cu = 1;
+    // single-wave workgroups without a transposed product fit three to a SIMD (at most 150 registers), and a
+    // streaming pass over a narrow matrix wants them all
+    if (nw == 1 && !has_c) per_cu = 12;
+    // never more workgroups than stay resident together: the rest would start when the first ones end, as a
+    // second, thinly occupied round
+    const size_t lds = (dtype == SSN_F32) ? fused_grid_lds<float>(a.p, a.K, has_c) : fused_grid_lds<double>(a.p, a.K, has_c);
+    if (lds > 0 && (size_t)per_cu * lds > 160 * 1024) per_cu = (int)(160 * 1024 / lds);
     if (per_cu < 1) per_cu = 1;
     const int64_t nblk = (a.nrows + 15) / 16;
     int64_t grid = (int64_t)num_cus * per_cu;
@@ -1298,7 +1315,9 @@ template <typename T, int MODE> static hipError_t fused_launch_mode(RowsArgs a, 
     const int i = fused_shape<T>(a.p, has_c, &nw, &fw);
     if (i < 0) return hipErrorInvalidValue;
     a.fw = fw;
-    const size_t lds = fused_lds_bytes<T>(nw, fw, TB::shape[i].nld, TB::shape[i].maxw, a.K, has_c);
+    // single-wave workgroups run the MAXW = 1 instantiation: sized for the table's MAXW, its LDS would let only
+    // 6 of the 8 workgroups a compute unit is given be resident, and the grid would run in two rounds
+    const size_t lds = fused_grid_lds<T>(a.p, a.K, has_c);
 #define SSN_FUSED_SHAPE(I, W) fused_launch_inst<T, MODE, TB::shape[I].nld, TB::shape[I].nsb, W>(a, grid, nw, lds, st)
     if (nw == 1) {      // single-wave workgroups: no cross-wave reduction compiled in
         if (i == 0) return SSN_FUSED_SHAPE(0, 1);

@@ -175,13 +175,17 @@ XtuArgs xtu_base(const ssn_ctx *c)
 }
 
 // The one-pass kernel serves a launch when the shape allows it and it pays: always for the modes with a
-// transposed product; for the margins-only modes only with a multi-wave feature split (for narrow
-// matrices the wave-per-row-block kernel is faster).
+// transposed product; for the margins-only modes with a multi-wave feature split, or on enough rows to
+// give every single-wave workgroup a row block (on fewer rows of a narrow matrix the wave-per-row-block
+// kernel is faster).
 bool use_fused(const ssn_ctx *c, const RowsArgs &a)
 {
     if (!c->fused) return false;
     if (a.mode == ROW_GRAD || a.mode == ROW_APPLY) return true;
-    return dense_fused_waves(c->d.dtype, a) > 1;
+    if (dense_fused_waves(c->d.dtype, a) > 1) return true;
+    // narrow matrix, margins only: the one-pass kernel's single-wave workgroups win once every one of them has a
+    // row block of its own to stream (workload 3, fp64 objective: 78 -> 62 us); on fewer rows the plain kernel does
+    return a.nrows >= (int64_t)16 * 12 * c->num_cus;
 }
 
 int launch_rows(ssn_ctx *c, const RowsArgs &a, int *nparts)
@@ -644,7 +648,7 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
         if (e_ != hipSuccess) return bail(e_ == hipErrorOutOfMemory ? SSN_E_ALLOC : SSN_E_HIP);   \
     } while (0)
 
-    c->wave_parts = c->num_cus * 8 * ROWS_WAVES_PER_BLOCK;
+    c->wave_parts = c->num_cus * 16 * ROWS_WAVES_PER_BLOCK;
     CREATE_HIP(hipMalloc((void **)&c->loss_part, sizeof(double) * c->wave_parts));
     CREATE_HIP(hipMalloc((void **)&c->hit_part, sizeof(int32_t) * c->wave_parts));
     CREATE_HIP(hipMalloc((void **)&c->red_a, sizeof(double) * RED_MAX_PARTS));

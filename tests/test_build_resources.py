@@ -31,3 +31,18 @@ def test_no_kernel_of_the_library_uses_scratch_memory():
     assert len(own) > 100
     offenders = {name: res["scratch"] for (_, name), res in own.items() if res.get("scratch", 0) != 0}
     assert not offenders, f"kernels using scratch memory (bytes per lane): {offenders}"
+
+
+def test_single_wave_one_pass_kernels_fit_the_residency_their_grid_assumes():
+    """The launcher gives a compute unit 12 single-wave workgroups of the margin-only modes (three per SIMD: at
+    most 512 / 3 registers, allocated in eights) and 8 of the modes with a transposed product (two per SIMD)."""
+    import re
+    seen = 0
+    for (_, name), res in _kernels().items():
+        m = re.match(r"_ZN3ssn18dense_fused_kernelI[df]Li(\d+)ELi\d+ELi\d+ELi1ELb0EE", name)
+        if not m:
+            continue
+        seen += 1
+        margins_only = int(m.group(1)) in (0, 2, 4)          # objective, prepare, predict
+        assert res["vgprs"] <= (168 if margins_only else 256), (name, res)
+    assert seen >= 20
