@@ -14,7 +14,9 @@
  *     ssn_last_error() returns the context's last detailed message.
  *   - Pointers marked [dev] are DEVICE pointers owned by the caller and only
  *     borrowed: X / CSR arrays / labels for the life of the context, all other
- *     arguments for the duration of the call.  Pointers marked [host] are
+ *     arguments for the duration of the call.  The data must not change while
+ *     the context exists: it keeps views derived from them (the column-sorted
+ *     entries of a CSR matrix, a padded copy of the last dense row).  Pointers marked [host] are
  *     HOST pointers.  The library owns only the workspace inside ssn_ctx.
  *   - Work is enqueued on the context's stream (a hipStream_t passed as
  *     void*; NULL = the default stream).  Calls that return a scalar through
@@ -68,8 +70,9 @@ typedef struct {
     int32_t layout;           /* ssn_layout                                                      */
     int32_t scale;            /* ssn_scale                                                       */
     double lambda;            /* L2 regularisation, >= 0                                         */
-    const void *X;            /* [dev] dense: n-by-p row-major, element (i,j) at [i*ldx + j]     */
-    int64_t ldx;              /*       leading dimension in elements, >= p                       */
+    const void *X;            /* [dev] dense: n-by-p row-major, element (i,j) at [i*ldx + j];    */
+    int64_t ldx;              /*       leading dimension in elements, >= p; storage of n*ldx     */
+                              /*       elements, or (n-1)*ldx + p when ldx == p                  */
     const int32_t *rowptr;    /* [dev] CSR: n+1 offsets                                          */
     const int32_t *colidx;    /* [dev] CSR: nnz column ids in [0,p), ascending inside a row      */
     const void *vals;         /* [dev] CSR: nnz values of type T                                 */
@@ -244,7 +247,8 @@ int ssn_axpy(ssn_ctx *ctx, double alpha, const void *P, void *W_inout);
 int ssn_time_kernel(ssn_ctx *ctx, int32_t which, const void *M, int32_t reps, double *ms);
 
 /* Which kernels serve this context: 0 = CSR, 1 = dense two-kernel path (margins, then X^T U), 2 = dense
- * one-pass path (every row of X read once per product; needs K <= 16, p <= 1024, 16-byte aligned rows).
+ * one-pass path (every row of X read once per product; needs K <= 16 and p <= 1024; rows need no alignment
+ * beyond their element's).
  * The environment variable SSN_DENSE_PATH=split forces 1 at ssn_create (for measurements). */
 int ssn_dense_path(const ssn_ctx *ctx);
 

@@ -776,20 +776,36 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
     // tile load: one base address per lane, constant offsets per load; a load is skipped (register keeps its
     // old, finite-or-not contents, which mask_block then replaces) only where it would leave the row's
     // storage of ldx elements, so every issued load is in bounds and none depends on another
+    // Rows need no alignment beyond their element's: a vector load of the tile is declared with that alignment
+    // (the hardware takes dword-aligned wide loads).  Whole vectors are read, so the last one of a row whose length
+    // is not a multiple of the vector width reaches past the row: into the next row on every row but the last of
+    // the matrix, which is read from a zero-padded copy the launcher passes (a.tail_row, a.tail_len elements).
+    struct __attribute__((packed, aligned(sizeof(T)))) upack { T v[VEC]; };
+    // Elements from a lane's first element of a row that may be read: the row's own storage and, where its
+    // length is not a multiple of the vector width, the first elements of the next row (32-bit: the comparisons
+    // against it cost a register pair and several instructions each in 64 bits, and there is one per load).
+    // The last row of the matrix is read from the launcher's copy of it, which is that long.
+    const int room = a.tail_len - fs - VEC * g;
+    const int last_row = (int)(a.n - 1);                          // row numbers fit 31 bits
+    auto row_base = [&](int64_t xr) -> const T * {
+        const T *b = ((int)xr == last_row) ? (const T *)a.tail_row : X + xr * a.ldx;
+        return b + fs + VEC * g;
+    };
+    auto load_vec = [&](const T *src, pack &dst) {
+        const upack u = *(const upack *)src;
+#pragma unroll
+        for (int m = 0; m < VEC; ++m) dst.v[m] = u.v[m];
+    };
     auto load_block = [&](int64_t xr, pack(&x)[NLD]) {
-        const T *xbase = X + xr * a.ldx + fs + VEC * g;
-        // elements from xbase to the end of the row (32-bit: the comparisons below cost a register pair and
-        // several instructions each in 64 bits, and there is one per load)
-        const int64_t room64 = a.ldx - fs - VEC * g;
-        const int room = room64 > 0x7fffffff ? 0x7fffffff : (int)room64;
+        const T *xbase = row_base(xr);
 #pragma unroll
         for (int j = 0; j < NLD; ++j)
-            if (LF * j + VEC <= room) x[j] = *(const pack *)(xbase + LF * j);
+            if (LF * j + VEC <= room) load_vec(xbase + LF * j, x[j]);
     };
     // one vector of the next tile; issued one at a time between the MFMAs of the current block, because a
     // compute unit cannot hold a whole tile of outstanding loads and a wave stalls at issue when it is full
     auto load_one = [&](const T *xbase, int room, int j, pack(&x)[NLD]) {
-        if (LF * j + VEC <= room) x[j] = *(const pack *)(xbase + LF * j);
+        if (LF * j + VEC <= room) load_vec(xbase + LF * j, x[j]);
     };
     // this lane's elements LF * j + m of the tile are inside the wave's slice for LF * j + m < nval (one 32-bit
     // register against constants: 64-bit feature indices here cost a register pair per load)
@@ -981,9 +997,8 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
             load_meta(rbn);
             xr_n = (rbn + gridDim.x < nblk) ? block_row(rbn + gridDim.x) : 0;
         }
-        const T *xbase_n = X + xr_next * a.ldx + fs + VEC * g;
-        const int64_t room64_n = a.ldx - fs - VEC * g;
-        const int room_n = !has_next ? 0 : (room64_n > 0x7fffffff ? 0x7fffffff : (int)room64_n);   // no next block: every load is skipped
+        const T *xbase_n = row_base(xr_next);
+        const int room_n = has_next ? room : 0;                 // no next block: every load is skipped
         // issued during phase A, the rest in phase C (all of them in phase A, or a quarter, is 2-8 % slower)
         constexpr int LOADS_A = HAS_C ? (NLD + 1) / 2 : NLD;
         constexpr int LOADS_C = (NLD - LOADS_A + NSB - 1) / NSB;          // per transposition sub-block
@@ -1220,10 +1235,11 @@ template <typename T> static size_t fused_lds_bytes(int nw, int fw, int nld, int
 template <typename T> static bool fused_ok(const RowsArgs &a)
 {
     constexpr int VEC = 16 / sizeof(T);
-    if (a.K > 16 || !vec_ok<T>(a.X, a.ldx)) return false;
+    if (a.K > 16 || (uintptr_t)a.X % sizeof(T) != 0) return false;
     if ((a.p + 256) * a.ldm >= ((int64_t)1 << 31)) return false;         // 32-bit offsets into the p x K operand
-    // whole-vector loads must stay inside a row's storage
-    if (a.p % VEC != 0 && a.ldx < (a.p + VEC - 1) / VEC * VEC) return false;
+    // whole-vector loads: the last vector of a row may reach VEC - 1 elements into the next row, which must exist
+    // (the last row's copy, RowsArgs::tail_row, covers the end of the matrix)
+    if (a.ldx < VEC) return false;
     for (int c = 0; c < 2; ++c) {            // both kernel families (with / without transposed product) must fit
         int nw, fw;
         const int i = fused_shape<T>(a.p, c == 1, &nw, &fw);
@@ -1234,7 +1250,7 @@ template <typename T> static bool fused_ok(const RowsArgs &a)
     return true;
 }
 
-// Can the one-pass kernel serve this shape?  (one 16-column class tile, 16-byte aligned rows, a feature
+// Can the one-pass kernel serve this shape?  (one 16-column class tile, rows of at least one vector, a feature
 // split that fits one of the compiled register footprints, LDS within the 160 KB of a gfx950 compute unit)
 bool dense_fused_supported(int dtype, const RowsArgs &a)
 {
@@ -1358,6 +1374,7 @@ template <typename T> static hipError_t fused_dispatch(const RowsArgs &a, int gr
 // ROW_OBJ / ROW_GRAD 4 * `grid` loss partials (ROW_APPLY: of sum_i z_i . u_i there), ROW_PRED 4 * `grid` hit partials.
 hipError_t launch_dense_fused(int dtype, const RowsArgs &a, int grid, hipStream_t st)
 {
+    if (!a.tail_row || a.tail_len < a.p) return hipErrorInvalidValue;       // the kernel reads row n-1 from this copy
     return dtype == SSN_F32 ? fused_dispatch<float>(a, grid, st) : fused_dispatch<double>(a, grid, st);
 }
 

@@ -76,6 +76,8 @@ struct ssn_ctx {
     void *grad_next = nullptr;                 // gradient at the first line-search trial (look-ahead of ssn_solve)
     CgSlot *slots = nullptr;
     int slots_cap = 0;
+    void *tail_row = nullptr;                  // dense one-pass path: zero-padded copy of row n-1 (tail_len elements)
+    int tail_len = 0;
     int cg_gg_parts = 0;                       // dense CG: partials of g.g in red_a the first finalize forms slot 0 from (0: slot 0 is set)
     double *trace_dev = nullptr;
 };
@@ -155,6 +157,8 @@ RowsArgs rows_base(const ssn_ctx *c)
     a.ldm = c->d.ldw;
     a.loss_part = c->loss_part;
     a.hit_part = c->hit_part;
+    a.tail_row = c->tail_row;
+    a.tail_len = c->tail_len;
     return a;
 }
 
@@ -591,7 +595,8 @@ int ssn_destroy(ssn_ctx *c)
     (void)hipStreamSynchronize(c->st);
     if (c->st_aux) (void)hipStreamSynchronize(c->st_aux);      // a view of the next sample may still be in the making
     void *dev[] = {c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->red_c, c->red_sq, c->scal_dev, c->int_dev,
-                   c->cg_p, c->cg_r, c->cg_s, c->cg_hs, c->cg_parts, c->cg_pb, c->trial, c->grad, c->grad_next, c->dir, c->slots, c->trace_dev};
+                   c->cg_p, c->cg_r, c->cg_s, c->cg_hs, c->cg_parts, c->cg_pb, c->trial, c->grad, c->grad_next, c->dir, c->slots, c->trace_dev,
+                   c->tail_row};
     for (void *p : dev)
         if (p) (void)hipFree(p);
     if (c->host_pin) (void)hipHostFree(c->host_pin);
@@ -681,6 +686,17 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
         if (c->fused) {
             const int g = dense_fused_grid(d->dtype, probe, c->num_cus);
             if (g > c->max_chunks) c->max_chunks = g;
+            // the one-pass kernel reads whole vectors, up to tail_len elements from the start of a row: on the
+            // last row that may leave the matrix, so it gets that row as a zero-padded copy
+            const int64_t vec = 16 / c->es;
+            int64_t len = (d->p + vec - 1) / vec * vec;
+            if (d->ldx > len) len = d->ldx;
+            if (len > d->p + 1024) len = d->p + 1024;          // no lane starts a load that far behind the last feature
+            c->tail_len = (int)len;
+            CREATE_HIP(hipMalloc(&c->tail_row, (size_t)len * c->es));
+            CREATE_HIP(hipMemsetAsync(c->tail_row, 0, (size_t)len * c->es, c->st));
+            CREATE_HIP(hipMemcpyAsync(c->tail_row, (const char *)d->X + (size_t)(d->n - 1) * d->ldx * c->es, (size_t)d->p * c->es,
+                                      hipMemcpyDeviceToDevice, c->st));
         }
         c->part_elems = (int64_t)c->max_chunks * d->p * K;
         CREATE_HIP(hipMalloc(&c->part, (size_t)c->part_elems * c->es));

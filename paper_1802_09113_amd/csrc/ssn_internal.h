@@ -49,6 +49,11 @@ struct RowsArgs {
     const int32_t *skip; // nullable device flag: non-zero -> the launch does nothing
     void *part;          // one-pass kernel only: per-workgroup p x K partial sums of X^T U
     int32_t fw;          // one-pass kernel only: features per wave (set by the launcher)
+    // one-pass kernel only: zero-padded copy of row n-1, tail_len elements = what the kernel may read from the
+    // start of a row (max(ldx, p rounded up to the vector width), capped where no lane reaches): it reads whole
+    // vectors, which on every other row stay inside the row's storage or reach into the next row
+    const void *tail_row;
+    int32_t tail_len;
 };
 
 // Arguments of the transposed product: part[chunk] = X_rows(chunk)^T * U(chunk).

@@ -27,7 +27,7 @@ def rel_scalar(a, b):
 class Pair:
     """One workload on both sides.  For fp32 the oracle reads the fp32-rounded data widened to fp64."""
 
-    def __init__(self, data, dtype, scale="mean", ldw=None, ldx=None, lam=None, dev="cuda"):
+    def __init__(self, data, dtype, scale="mean", ldw=None, ldx=None, lam=None, dev="cuda", xoff=0):
         self.dtype = dtype
         nd = np_dtype(dtype)
         self.C, self.K = data["C"], data["C"] - 1
@@ -40,7 +40,13 @@ class Pair:
         if data["layout"] == "dense":
             Xr = data["X"].astype(nd)
             self.oracle = Problem(labels, self.C, lam, X=Xr.astype(np.float64), scale=scale)
-            if ldx is None:
+            if xoff:
+                # rows packed tightly behind `xoff` elements of a flat allocation that ends with the last row: the
+                # matrix starts at an address aligned to its element only
+                flat = torch.full((xoff + self.n * self.p,), float("nan"), dtype=dtype, device=dev)
+                Xd = flat[xoff:].view(self.n, self.p)
+                Xd.copy_(torch.from_numpy(Xr).to(dev))
+            elif ldx is None:
                 Xd = torch.from_numpy(Xr).to(dev)
             else:
                 buf = torch.full((self.n, ldx), float("nan"), dtype=dtype, device=dev)

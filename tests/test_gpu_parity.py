@@ -187,6 +187,31 @@ def test_scaling_modes_and_padded_leading_dimensions(data_cache, scale, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+@pytest.mark.parametrize("xoff", [0, 1, 3])
+def test_rows_aligned_to_their_element_only(data_cache, xoff, dtype):
+    # 54 features: fp32 rows of 216 bytes; with xoff the matrix itself starts 4 / 8 (12 / 24) bytes into its allocation, and
+    # the allocation ends with the last row (whole-vector loads of that row's end must not leave it)
+    d = data_cache(3, 1003)
+    pair = Pair(d, dtype, xoff=xoff)
+    print(f"[case] element-aligned rows xoff={xoff} dtype={dtype}", flush=True)
+    Wh, Wd = _weights(pair, 3, 0.2)
+    Vh, Vd = _weights(pair, 4, 1.0)
+    S = np.concatenate([synth.sample_rows(1003, 60, it=2), np.array([1002, 1002, 0], dtype=np.int32)])   # the last row, twice
+    f = pair.gpu.ssn_objective(Wd)
+    G, fg = pair.gpu.ssn_gradient(Wd)
+    HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+    _, acc = pair.gpu.ssn_predict(Wd)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert rel_scalar(f, pair.oracle.objective(Wh)) <= tol
+    assert rel_scalar(fg, pair.oracle.objective(Wh)) <= tol
+    assert rel_err(pair.host(G), pair.oracle.gradient(Wh)[0]) <= tol
+    assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
+    assert abs(acc - pair.oracle.accuracy(Wh)) <= (1e-12 if dtype == F64 else 2e-3)
+    pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 @pytest.mark.parametrize("C", [2, 17, 18, 33])
 def test_class_counts_across_mfma_tile_boundaries(C, dtype):
     g = np.random.default_rng(C)
