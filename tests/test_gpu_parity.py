@@ -141,8 +141,8 @@ def test_hessvec_sample_of_several_row_blocks_per_workgroup(data_cache, dtype):
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 def test_wide_matrix_with_many_row_blocks(data_cache, dtype):
-    # 9001 rows of the 3072-feature workload: more row blocks than the workgroup-per-block variant takes, so
-    # the wave-per-block kernel runs in its two-blocks-per-trip form, with a ragged last block
+    # 9001 rows of the 3072-feature workload: more row blocks than the chip has places for workgroups of 8 or 16
+    # waves, so four waves share a row block, with a ragged last block
     d = data_cache(2, 9001)
     pair = Pair(d, dtype)
     tol = TOL[dtype]
@@ -184,6 +184,34 @@ def test_scaling_modes_and_padded_leading_dimensions(data_cache, scale, dtype):
         assert rel_err(pair.host(G), pair.oracle.gradient(Wh)[0]) <= tol
         assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
         pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_medium_width_matrix_two_row_blocks_per_trip(dtype):
+    # 1200 features: too wide for the one-pass kernel, narrower than the 2048 from which a workgroup shares a row
+    # block on full passes; 8211 rows are 514 row blocks (one ragged), so the wave-per-block kernel runs in its
+    # two-blocks-per-trip form
+    g = np.random.default_rng(1200)
+    n, p, C = 8211, 1200, 6
+    X = g.standard_normal((n, p)) * (g.random((n, p)) < 0.3)
+    labels = g.integers(0, C, size=n).astype(np.int32)
+    d = dict(layout="dense", X=X, labels=labels, C=C, p=p, n=n, lam=1e-3)
+    pair = Pair(d, dtype)
+    assert pair.gpu.ssn_dense_path() == 1
+    Wh, Wd = pair.block(0.05 * g.standard_normal((p, C - 1)))
+    Vh, Vd = pair.block(g.standard_normal((p, C - 1)))
+    S = g.integers(0, n, size=700).astype(np.int32)
+    print(f"[case] medium width dtype={dtype}", flush=True)
+    f = pair.gpu.ssn_objective(Wd)
+    G, f2 = pair.gpu.ssn_gradient(Wd)
+    HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    G_ref, f_ref = pair.oracle.gradient(Wh)
+    assert rel_scalar(f, f_ref) <= tol and rel_scalar(f2, f_ref) <= tol
+    assert rel_err(pair.host(G), G_ref) <= tol
+    assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
+    pair.close()
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
