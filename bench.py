@@ -29,9 +29,9 @@ MEASURED_TRAFFIC = {
     ("image_like", "f64", "dense_fused_kernel<GRAD>"): 377.8e6 + 14.5e6,
     ("image_like", "f64", "dense_fused_kernel<APPLY>"): 19.8e6 + 10.6e6,
     # profiles/dense_two_kernel_wide_f64_hbm_traffic_pmc.md, profiles/csr_sparse_f64_hbm_traffic_pmc.md
-    ("wide", "f64", "dense_rows_kernel<OBJ>"): 1234.7e6,
-    ("wide", "f64", "dense_rows_kernel<GRAD>"): 1235.6e6 + 6.4e6,
-    ("wide", "f64", "dense_xtu_kernel (n rows)"): 1283.4e6 + 9.5e6,
+    ("wide", "f64", "dense_rows_kernel<OBJ>"): 1240.8e6 + 0.1e6,
+    ("wide", "f64", "dense_rows_kernel<GRAD>"): 1240.0e6 + 6.5e6,
+    ("wide", "f64", "dense_xtu_kernel (n rows)"): 1283.0e6 + 9.5e6,
     ("wide", "f64", "dense_rows_kernel<APPLY>"): 63.6e6 + 0.3e6,
     ("wide", "f64", "dense_xtu_kernel (|S| rows)"): 64.2e6 + 8.8e6,
     ("sparse_csr", "f64", "csr_rows_kernel<OBJ>"): 887.9e6,
