@@ -187,6 +187,38 @@ def test_scaling_modes_and_padded_leading_dimensions(data_cache, scale, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+@pytest.mark.parametrize("p,C", [(300, 17), (200, 4), (416, 9)])
+def test_one_pass_kernel_with_four_waves_per_workgroup(p, C, dtype):
+    # between the single-wave shapes (up to 128 features) and the eight-wave ones: four waves split the features,
+    # two workgroups share a compute unit where their LDS allows (16 class columns: it does not)
+    g = np.random.default_rng(p + C)
+    n = 9000 + 7
+    X = g.standard_normal((n, p)) * (g.random((n, p)) < 0.5)
+    labels = g.integers(0, C, size=n).astype(np.int32)
+    d = dict(layout="dense", X=X, labels=labels, C=C, p=p, n=n, lam=1e-3)
+    pair = Pair(d, dtype)
+    assert pair.gpu.ssn_dense_path() == 2
+    Wh, Wd = pair.block(0.1 * g.standard_normal((p, C - 1)))
+    Vh, Vd = pair.block(g.standard_normal((p, C - 1)))
+    S = g.integers(0, n, size=450).astype(np.int32)
+    print(f"[case] four-wave one-pass p={p} C={C} dtype={dtype}", flush=True)
+    f = pair.gpu.ssn_objective(Wd)
+    G, f2 = pair.gpu.ssn_gradient(Wd)
+    HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+    HVall = pair.gpu.ssn_hessvec(Wd, pair.idx(np.arange(n, dtype=np.int32)), Vd)
+    _, acc = pair.gpu.ssn_predict(Wd)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    G_ref, f_ref = pair.oracle.gradient(Wh)
+    assert rel_scalar(f, f_ref) <= tol and rel_scalar(f2, f_ref) <= tol
+    assert rel_err(pair.host(G), G_ref) <= tol
+    assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
+    assert rel_err(pair.host(HVall), pair.oracle.hessvec(Wh, np.arange(n), Vh)) <= tol
+    assert abs(acc - pair.oracle.accuracy(Wh)) <= (1e-12 if dtype == F64 else 2e-3)
+    pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 def test_medium_width_matrix_two_row_blocks_per_trip(dtype):
     # 1200 features: too wide for the one-pass kernel, narrower than the 2048 from which a workgroup shares a row
     # block on full passes; 8211 rows are 514 row blocks (one ragged), so the wave-per-block kernel runs in its
