@@ -5,15 +5,16 @@
 // stored entries are processed per step, lane (s,c) gathers M[col_s, c] -- the K values of one feature
 // are contiguous (feature-major weights), so one stored entry fetches one contiguous K-vector.
 #include "ssn_internal.h"
+#include "ssn_math.h"
 
 #include <limits>
 
 namespace ssn {
 
 __device__ __forceinline__ float c_exp(float x) { return expf(x); }
-__device__ __forceinline__ double c_exp(double x) { return exp(x); }
+__device__ __forceinline__ double c_exp(double x) { return exp_nonpos(x, opaque_zero()); }      // arguments are <= 0 here
 __device__ __forceinline__ float c_log(float x) { return logf(x); }
-__device__ __forceinline__ double c_log(double x) { return log(x); }
+__device__ __forceinline__ double c_log(double x) { return log_ge1(x, opaque_zero()); }           // alpha >= 1
 
 template <typename T> __device__ __forceinline__ T wave_sum(T x)
 {
