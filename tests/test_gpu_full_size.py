@@ -63,3 +63,45 @@ def test_wide_full():
 
 def test_sparse_full():
     _check(4, [F64, F32])
+
+
+@pytest.mark.parametrize("p,reps", [(512, 1000), (3072, 170)], ids=["one_pass", "two_kernel"])
+def test_matrices_of_more_than_2_to_the_31_elements(p, reps):
+    """Maximum sizes: element offsets into X beyond 32 bits.  The big matrix is a block of m rows repeated `reps`
+    times (built on the device), so with the mean scaling f, grad f and the accuracy equal the block's, which the
+    oracle computes, and a product on sampled rows near the end equals the product on the same rows of the block."""
+    from paper_1802_09113_amd.binding import Context
+    from oracle.oracle import Problem
+
+    g = np.random.default_rng(31 + p)
+    m, C, lam = 4400 + 7, 5, 1e-3
+    K = C - 1
+    Xb = (g.standard_normal((m, p)) * (g.random((m, p)) < 0.4)).astype(np.float32)
+    lab_b = g.integers(0, C, size=m).astype(np.int32)
+    n = m * reps
+    assert n * p > 2 ** 31
+    print(f"[case] big matrix n={n} p={p} ({n * p * 4 / 2 ** 30:.1f} GiB)", flush=True)
+    X = torch.from_numpy(Xb).cuda().repeat(reps, 1)
+    labels = torch.from_numpy(lab_b).cuda().repeat(reps)
+    W = (0.1 * g.standard_normal((p, K))).astype(np.float32)
+    V = g.standard_normal((p, K)).astype(np.float32)
+    Wd, Vd = torch.from_numpy(W).cuda(), torch.from_numpy(V).cuda()
+    big = Context(labels, C, lam, X=X)
+    small = Problem(lab_b, C, lam, X=Xb.astype(np.float64))
+    tol = TOL[F32]
+    f = big.ssn_objective(Wd)
+    G, f2 = big.ssn_gradient(Wd)
+    torch.cuda.synchronize()
+    G_ref, f_ref = small.gradient(W.astype(np.float64))
+    assert rel_scalar(f, f_ref) <= tol and rel_scalar(f2, f_ref) <= tol
+    assert rel_err(G.double().cpu().numpy(), G_ref) <= tol
+    # rows of the last repetitions: their offsets into X do not fit 32 bits
+    Sb = g.integers(0, m, size=300).astype(np.int64)
+    S = (Sb + m * (reps - 1 - (np.arange(300) % 3))).astype(np.int32)
+    assert int(S.min()) * p > 2 ** 31
+    HV = big.ssn_hessvec(Wd, torch.from_numpy(S).cuda(), Vd)
+    _, acc = big.ssn_predict(Wd, want_pred=False)
+    torch.cuda.synchronize()
+    assert rel_err(HV.double().cpu().numpy(), small.hessvec(W.astype(np.float64), Sb.astype(np.int32), V.astype(np.float64))) <= tol
+    assert abs(acc - small.accuracy(W.astype(np.float64))) <= 1e-3
+    big.close()
