@@ -272,10 +272,13 @@ def test_rows_aligned_to_their_element_only(data_cache, xoff, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+@pytest.mark.parametrize("p", [45, 54])
 @pytest.mark.parametrize("C", [2, 17, 18, 33])
-def test_class_counts_across_mfma_tile_boundaries(C, dtype):
+def test_class_counts_across_mfma_tile_boundaries(C, p, dtype):
+    # more than 16 weight columns go to the two-kernel path, whose loads follow the rows' alignment: 45 features are
+    # element-aligned rows (scalar loads), 54 fp32 features 8-byte aligned ones (two-element loads)
     g = np.random.default_rng(C)
-    n, p = 777, 45
+    n = 777
     X = g.standard_normal((n, p))
     labels = g.integers(0, C, size=n).astype(np.int32)
     d = dict(layout="dense", X=X, labels=labels, C=C, p=p, n=n, lam=1e-3)
@@ -283,7 +286,7 @@ def test_class_counts_across_mfma_tile_boundaries(C, dtype):
     Wh, Wd = pair.block(0.3 * g.standard_normal((p, C - 1)))
     Vh, Vd = pair.block(g.standard_normal((p, C - 1)))
     S = np.sort(g.choice(n, 100, replace=False)).astype(np.int32)
-    print(f"[case] C={C} dtype={dtype}", flush=True)
+    print(f"[case] C={C} p={p} dtype={dtype}", flush=True)
     f = pair.gpu.ssn_objective(Wd)
     G, _ = pair.gpu.ssn_gradient(Wd)
     HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
