@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 F64, F32 = torch.float64, torch.float32
 
 
-def _check(cfg, dtypes, grad=True):
+def _check(cfg, dtypes, grad=True, all_rows=False):
     print(f"[gen] full-size workload {cfg}", flush=True)
     d = synth.make(cfg)
     S = synth.sample_rows(d["n"], d["nS"])
@@ -46,15 +46,22 @@ def _check(cfg, dtypes, grad=True):
         assert np.sum(Vh * hv) >= pair.oracle.lam * np.sum(Vh * Vh) * (1 - 10 * tol)
         pred, acc = pair.gpu.ssn_predict(Wd, want_pred=False)
         assert abs(acc - pair.oracle.accuracy(Wh)) <= (0.0 if dtype == F64 else 1e-3)
+        if all_rows:
+            # the FullNewton shape: prepare and product on every row (the many-row-block forms of both kernels)
+            Sall = np.arange(pair.n, dtype=np.int32)
+            pair.gpu.ssn_hess_prepare(Wd, pair.idx(Sall))
+            HVa = pair.gpu.ssn_hess_apply(Vd)
+            torch.cuda.synchronize()
+            assert rel_err(pair.host(HVa), pair.oracle.hessvec(Wh, Sall, Vh)) <= tol
         pair.close()
 
 
 def test_image_like_full():
-    _check(1, [F64, F32])
+    _check(1, [F64, F32], all_rows=True)
 
 
 def test_tall_narrow_full():
-    _check(3, [F64, F32])
+    _check(3, [F64, F32], all_rows=True)
 
 
 def test_wide_full():
