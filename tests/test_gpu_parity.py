@@ -187,10 +187,11 @@ def test_scaling_modes_and_padded_leading_dimensions(data_cache, scale, dtype):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
-@pytest.mark.parametrize("p,C", [(300, 17), (200, 4), (416, 9)])
-def test_one_pass_kernel_with_four_waves_per_workgroup(p, C, dtype):
-    # between the single-wave shapes (up to 128 features) and the eight-wave ones: four waves split the features,
-    # two workgroups share a compute unit where their LDS allows (16 class columns: it does not)
+@pytest.mark.parametrize("p,C", [(300, 17), (200, 4), (416, 9), (1000, 6), (90, 3), (70, 12)])
+def test_one_pass_kernel_shapes_between_the_workloads(p, C, dtype):
+    # the register footprints the workloads do not reach: four waves per workgroup (200-416 features; two workgroups
+    # share a compute unit where their LDS allows, which 16 class columns do not), the widest eight-wave shape
+    # (1000 features), and the single-wave shapes of 57-104 features
     g = np.random.default_rng(p + C)
     n = 9000 + 7
     X = g.standard_normal((n, p)) * (g.random((n, p)) < 0.5)
@@ -201,7 +202,7 @@ def test_one_pass_kernel_with_four_waves_per_workgroup(p, C, dtype):
     Wh, Wd = pair.block(0.1 * g.standard_normal((p, C - 1)))
     Vh, Vd = pair.block(g.standard_normal((p, C - 1)))
     S = g.integers(0, n, size=450).astype(np.int32)
-    print(f"[case] four-wave one-pass p={p} C={C} dtype={dtype}", flush=True)
+    print(f"[case] one-pass shape p={p} C={C} dtype={dtype}", flush=True)
     f = pair.gpu.ssn_objective(Wd)
     G, f2 = pair.gpu.ssn_gradient(Wd)
     HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
