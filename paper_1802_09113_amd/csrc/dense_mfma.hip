@@ -163,6 +163,80 @@ __device__ __forceinline__ T slot_epilogue(T z, const RowsArgs &a, int64_t sv, i
     return T(0);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Two accumulator elements at once for K <= 7 (ROW_OBJ / ROW_GRAD): with at most seven weight columns plus the
+// reference class a row needs 8 of its 16 lanes, so lanes 8..15 take the row of a second accumulator element
+// (DPP rotation by 8 inside the 16-lane row) and the exponentials, reciprocals and reductions of both rows cost
+// one pass.  In the kernels whose workgroup is a single wave this per-row work is about half of the time.
+template <int CTRL> __device__ __forceinline__ int dpp_mov(int x)
+{
+    return __builtin_amdgcn_update_dpp(x, x, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL> __device__ __forceinline__ float dpp_val(float x) { return __int_as_float(dpp_mov<CTRL>(__float_as_int(x))); }
+template <int CTRL> __device__ __forceinline__ double dpp_val(double x)
+{
+    return __hiloint2double(dpp_mov<CTRL>(__double2hiint(x)), dpp_mov<CTRL>(__double2loint(x)));
+}
+// reductions over the 8 lanes of a half row: neighbours, pairs (quad permutations 1032 and 2301), then the
+// mirror image inside the half row; every lane of the half row ends with the result
+template <typename T> __device__ __forceinline__ T half8_sum(T x)
+{
+    x += dpp_val<0xB1>(x);
+    x += dpp_val<0x4E>(x);
+    x += dpp_val<0x141>(x);
+    return x;
+}
+template <typename T> __device__ __forceinline__ T half8_max(T x)
+{
+    x = fmax(x, dpp_val<0xB1>(x));
+    x = fmax(x, dpp_val<0x4E>(x));
+    x = fmax(x, dpp_val<0x141>(x));
+    return x;
+}
+// za / zb: the lane's margins of elements a and b (class q of rows sva / svb, labels laba / labb); ub receives
+// element b's result, the return value is element a's (both zero in lanes 8..15, which hold no class of theirs)
+template <typename T, int MODE>
+__device__ __forceinline__ T slot_epilogue_pair(T za, T zb, T &ub, const RowsArgs &a, int64_t sva, int64_t svb, int q, int laba,
+                                                int labb, double &loss, double &lprod)
+{
+    static_assert(MODE == ROW_OBJ || MODE == ROW_GRAD, "paired per-row work: loss modes only");
+    const int K = a.K;                                   // <= 7: lane K of the half row is free for the reference class
+    const bool hi = q >= 8;
+    const int qh = q & 7;
+    const T zb_up = dpp_val<0x128>(zb);                  // rotation by 8 inside the row: lane q takes lane q +- 8
+    const T z = hi ? zb_up : za;
+    const int64_t sv = hi ? svb : sva;
+    const int lab = hi ? labb : laba;
+    const bool valid = sv < a.nrows;
+    const bool cv = qh < K;
+    const T NEG = -std::numeric_limits<T>::infinity();
+    // eqs. (8), (9) as in slot_epilogue, on half rows
+    const T zz = (qh == K) ? T(0) : z;
+    const bool ce = qh <= K;
+    const T Mx = half8_max(ce ? zz : NEG);
+    const T e = ce ? t_exp<false>(zz - Mx) : T(0);
+    const T alpha = half8_sum(e);
+    const T inv = fast_rcp(alpha);
+    const T zl = __shfl(z, (threadIdx.x & 56) | (lab & 7));          // same row group, same half row
+    const T lin = (lab < K) ? zl : T(0);
+    if (valid && qh == 0) {
+        loss += (double)Mx - (double)lin;
+        lprod *= (double)alpha;
+    }
+    if (lprod > 1e250) {
+        loss += log(lprod);
+        lprod = 1.0;
+    }
+    if constexpr (MODE == ROW_GRAD) {
+        const T u = (valid && cv) ? (e * inv - ((qh == lab) ? T(1) : T(0))) : T(0);
+        const T u_dn = dpp_val<0x128>(u);
+        ub = hi ? T(0) : u_dn;
+        return hi ? T(0) : u;
+    }
+    ub = T(0);
+    return T(0);
+}
+
 // Per-row work on a 16-row block of margins held in MFMA accumulator layout:
 // acc[nb][v] = z(row d_row<T>(lane/16, v), class 16*nb + lane%16).  With one class tile (K <= 16) the
 // modes that exponentiate go through slot_epilogue, element by element.
@@ -173,6 +247,23 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
     const int q = lane & 15, g = lane >> 4;
     const int K = a.K;
     const T NEG = -std::numeric_limits<T>::infinity();
+    if constexpr (NB == 1 && (MODE == ROW_OBJ || MODE == ROW_GRAD)) {
+        if (K <= 7) {                                    // two accumulator elements per pass
+#pragma unroll
+            for (int v = 0; v < 4; v += 2) {
+                const int64_t sva = rb * 16 + d_row<T>(g, v), svb = rb * 16 + d_row<T>(g, v + 1);
+                const int64_t ca = sva < a.nrows ? sva : a.nrows - 1, cb = svb < a.nrows ? svb : a.nrows - 1;
+                const int laba = a.labels[a.S ? a.S[ca] : ca], labb = a.labels[a.S ? a.S[cb] : cb];
+                T ub;
+                const T ua = slot_epilogue_pair<T, MODE>(acc[0][v], acc[0][v + 1], ub, a, sva, svb, q, laba, labb, loss, lprod);
+                if constexpr (MODE == ROW_GRAD) {
+                    ((T *)a.UP)[sva * a.KP + q] = ua;
+                    ((T *)a.UP)[svb * a.KP + q] = ub;
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const int64_t sv = rb * 16 + d_row<T>(g, v);
@@ -1004,9 +1095,24 @@ __global__ __launch_bounds__(64 * MAXW) void dense_fused_kernel(RowsArgs a)
         };
         if constexpr (HAS_C) scr_write(0);
         if constexpr (MAXW == 1) {
+            bool paired = false;
+            if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD) {
+                if (K <= 7) {                            // two accumulator elements per pass
+                    paired = true;
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                u[v] = slot_epilogue<T, MODE>(z[v], a, rb * 16 + d_row<T>(g, v), q, lab_pre[v], pin_pre[v], loss, lprod, hits);
+                    for (int v = 0; v < 4; v += 2) {
+                        T ub;
+                        u[v] = slot_epilogue_pair<T, MODE>(z[v], z[v + 1], ub, a, rb * 16 + d_row<T>(g, v),
+                                                           rb * 16 + d_row<T>(g, v + 1), q, lab_pre[v], lab_pre[v + 1], loss, lprod);
+                        u[v + 1] = ub;
+                    }
+                }
+            }
+            if (!paired) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    u[v] = slot_epilogue<T, MODE>(z[v], a, rb * 16 + d_row<T>(g, v), q, lab_pre[v], pin_pre[v], loss, lprod, hits);
+            }
         } else {
             T *zp = zpart + (HAS_C ? 0 : (size_t)(it & 1) * MAXW * 256);
 #pragma unroll
