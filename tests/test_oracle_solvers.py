@@ -149,3 +149,64 @@ def test_ssn_subsampled_schedule_and_eps_stop():
     # a huge eps stops before the first update
     W2, log2, done2 = pr.ssn(np.zeros((pr.p, pr.K)), S_all, eps=1e9)
     assert done2 == 0 and np.all(W2 == 0)
+
+
+def _krylov_iterates(H, gv, T):
+    """p_1..p_T of CG on H p = -g without CG's recurrences: p_k minimises the quadratic over the Krylov space
+    span{g, Hg, .., H^(k-1) g}, built here with an orthonormal basis (Gram-Schmidt, twice) and a dense solve."""
+    Q = np.zeros((gv.size, 0))
+    v = gv.copy()
+    out = []
+    for _ in range(T):
+        for _ in range(2):
+            v = v - Q @ (Q.T @ v)
+        Q = np.concatenate([Q, (v / np.linalg.norm(v))[:, None]], axis=1)
+        y = np.linalg.solve(Q.T @ H @ Q, -Q.T @ gv)
+        out.append(Q @ y)
+        v = H @ Q[:, -1]
+    return out
+
+
+@pytest.mark.parametrize("seed", [31, 37, 43, 47])
+def test_cg_keeps_the_iterate_of_smallest_residual_when_the_residual_rises(seed):
+    """Best-iterate memory of Alg. 2 on ill-conditioned systems whose residual norm goes up and down: for every
+    budget T the direction returned is the p_k (k <= T) of smallest ||H p_k + g||, not the last one, and it is
+    the start value s_0 = -g while no iterate has a residual at most ||g||."""
+    g = np.random.default_rng(seed)
+    n, p, C = 60, 6, 3
+    X = g.standard_normal((n, p)) * np.array([0.2, 0.5, 1.0, 2.0, 5.0, 10.0])
+    Wt = g.standard_normal((p, C))
+    labels = np.argmax(X @ Wt + g.gumbel(size=(n, C)), axis=1).astype(np.int32)
+    pr = Problem(labels, C, 1e-3, X=X)
+    W = 0.3 * g.standard_normal((p, C - 1))
+    S = np.sort(g.choice(n, 40, replace=False)).astype(np.int32)
+    grad, _ = pr.gradient(W)
+    gv = grad.reshape(-1)
+    gn = np.linalg.norm(gv)
+    H = explicit_hessian(X, W, S, pr.lam, 1.0 / S.size)
+    Tmax = 8
+    iterates = _krylov_iterates(H, gv, Tmax)
+    res = np.array([np.linalg.norm(H @ pk + gv) for pk in iterates])
+    full = pr.cg(W, S, grad, theta=1e-30, T=Tmax)
+    # the residual norms of the oracle's trace are those of the Krylov minimisers, and they do rise
+    np.testing.assert_allclose(full["rnorm"], res, rtol=1e-6)
+    assert np.any(np.diff(np.concatenate([[gn], res])) > 0)
+    saw_not_last = saw_start = False
+    for T in range(1, Tmax + 1):
+        out = pr.cg(W, S, grad, theta=1e-30, T=T)
+        assert out["iters"] == T
+        best = int(np.argmin(res[:T]))
+        pv = out["p"].reshape(-1)
+        if res[best] <= gn:
+            assert np.linalg.norm(pv - iterates[best]) <= 1e-6 * np.linalg.norm(iterates[best])
+            assert out["rel_res"] == pytest.approx(res[best] / gn, rel=1e-6)
+            if best != T - 1:
+                saw_not_last = True
+                assert np.linalg.norm(pv - iterates[T - 1]) > 1e-3 * np.linalg.norm(iterates[T - 1])
+        else:
+            saw_start = True
+            np.testing.assert_array_equal(out["p"], -grad)
+            assert out["rel_res"] == 1.0
+    assert saw_not_last
+    if seed in (31, 43):
+        assert saw_start          # the first residual of these systems is larger than ||g||
