@@ -140,7 +140,7 @@ typedef struct {
 const char *ssn_strerror(int status);
 const char *ssn_last_error(const ssn_ctx *ctx);
 
-/* Preprocessing of Sec. 4 ("each column of the data matrix has Euclidean norm one"), in place on the
+/* Preprocessing of Sec. 4 (unit column norms), in place on the
  * device, before ssn_create: dense X [dev] n-by-p with leading dimension ldx, or CSR rowptr / colidx /
  * vals [dev] with nnz stored entries (the other layout's pointers are ignored).  colnorm [dev, p doubles]
  * receives the column norms before scaling; a column of norm zero is left as it is.  Column indices of a
@@ -169,6 +169,15 @@ int ssn_objective(ssn_ctx *ctx, const void *W, double *f);
  * W [dev], G [dev] p-by-K out; f [host], may be NULL -- if given, also receives f(W) from the
  * same pass and the call synchronises. */
 int ssn_gradient(ssn_ctx *ctx, const void *W, void *G, double *f);
+
+/* The same two calls with the scalar left on the device (the function-pointer style F(.) of Alg. 2 / Alg. 3
+ * for callers that keep their control flow on the device, and the problem statement of Sec. 3.3 otherwise
+ * unchanged): f_dev [dev] receives f(W); kernels are enqueued only, nothing is read back and the host does
+ * not wait, so the call may be recorded into a HIP graph on the context's stream (dense layouts; the first
+ * gradient on a CSR context builds its column-sorted view and waits for the stream once).  A non-finite
+ * value is stored as it is (no SSN_E_NONFINITE). */
+int ssn_objective_dev(ssn_ctx *ctx, const void *W, double *f_dev);
+int ssn_gradient_dev(ssn_ctx *ctx, const void *W, void *G, double *f_dev);
 
 /* Sub-sampled gradient, eq. (2a), on the index multiset S [dev] (nS entries in [0,n), repeats allowed):
  *   G = s_S * X_S^T (P_S - Y_S) + lambda W,  s_S = 1/nS (mean scaling) or n/nS (sum scaling).
@@ -221,6 +230,21 @@ int ssn_linesearch(ssn_ctx *ctx, const void *W, const void *P, const void *G, do
  * class index.  pred [dev, nullable] n int32; acc [host, nullable] = mean(pred == labels). */
 int ssn_predict(ssn_ctx *ctx, const void *W, int32_t *pred, double *acc);
 
+/* Accuracy of the classification rule (end of Sec. 3.3) on held-out rows: test [host] describes them like
+ * an ssn_desc for ssn_create (X or CSR arrays and labels [dev]; n of its own; p, C, dtype and ldw equal to the
+ * context's; lambda, scale and stream are ignored).  acc [host] = mean(argmax == label).  Validates the
+ * description like ssn_create, allocates a temporary workspace and synchronises the stream; callers that
+ * evaluate the same held-out rows many times keep a second context and call ssn_predict on it instead
+ * (ssn_params.test does that inside ssn_solve). */
+int ssn_accuracy(ssn_ctx *ctx, const ssn_desc *test, const void *W, double *acc);
+
+/* The paper stacks the K weight columns into one d-vector, x = [x_1; ...; x_K] (Sec. 3.3, eq. (5)): element
+ * c*p + j of vec is element (j, c) of the p-by-K block used everywhere in this library.  These two calls
+ * convert between the orderings on the device (vec [dev]: p*K elements of type T; block [dev]: p-by-K with
+ * leading dimension ldw; the two must not overlap).  Asynchronous. */
+int ssn_vec_to_rowmajor(ssn_ctx *ctx, const void *vec, void *block);
+int ssn_rowmajor_to_vec(ssn_ctx *ctx, const void *block, void *vec);
+
 /* Sub-sampled Newton, Alg. 1 with the full gradient and a sampled Hessian:
  * per iteration f,g at W; stop if ||g|| < eps; prepare H_S; CG; line search; W += alpha P.
  * With params.Sg_all the gradient is the sub-sampled one of eq. (2a); the Armijo test still compares the
@@ -232,25 +256,6 @@ int ssn_solve(ssn_ctx *ctx, void *W_inout, const ssn_params *params,
 
 /* y = a*x + y style helper used by callers that drive Alg. 1 themselves: W += alpha * P. */
 int ssn_axpy(ssn_ctx *ctx, double alpha, const void *P, void *W_inout);
-
-/* Measurement aid for benchmarks: launches ONE kernel of the hot path `reps` times back to back on the
- * context's stream between two HIP events and returns the mean duration of a launch in milliseconds.
- *   which = 0  the kernel of ssn_objective (margins + loss over all rows)
- *           1  first kernel of ssn_gradient: two-kernel path margins + U = P - Y; one-pass path margins,
- *              U and the per-workgroup partials of X^T U in a single sweep over X
- *           2  second kernel of ssn_gradient: two-kernel path X^T U per-chunk partials; one-pass path the
- *              fixed-order sum of the partials (+ lambda W)
- *           3, 4  the same two kernels of ssn_hess_apply on the prepared sample
- *           5  a plain streaming read of the whole data matrix (no arithmetic): the practical HBM ceiling
- * M [dev] is the p-by-K right operand (W or V).  which = 2 / 4 reuse what which = 1 / 3 left behind, so
- * call those first.  ms [host].  Synchronises the stream. */
-int ssn_time_kernel(ssn_ctx *ctx, int32_t which, const void *M, int32_t reps, double *ms);
-
-/* Which kernels serve this context: 0 = CSR, 1 = dense two-kernel path (margins, then X^T U), 2 = dense
- * one-pass path (every row of X read once per product; needs K <= 16 and p <= 1024; rows need no alignment
- * beyond their element's).
- * The environment variable SSN_DENSE_PATH=split forces 1 at ssn_create (for measurements). */
-int ssn_dense_path(const ssn_ctx *ctx);
 
 #ifdef __cplusplus
 }

@@ -17,6 +17,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ssn_oracle.c")
 _LIB = os.path.join(_HERE, "libssn_oracle.so")
+_LIB_OMP = os.path.join(_HERE, "libssn_oracle_omp.so")      # the same source with -fopenmp (row loops on all cores)
+CFLAGS = ["-O2", "-std=c99", "-fPIC", "-shared"]
 
 _c_double_p = ctypes.POINTER(ctypes.c_double)
 _c_int32_p = ctypes.POINTER(ctypes.c_int32)
@@ -35,28 +37,36 @@ class _Problem(ctypes.Structure):
 
 
 def build(force=False):
-    """Compile the oracle with gcc -O2 (no fast-math) into oracle/libssn_oracle.so."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"])
+    """Compile the oracle with gcc -O2 (no fast-math) into oracle/libssn_oracle.so, and once more with -fopenmp
+    into oracle/libssn_oracle_omp.so."""
+    for lib, extra in ((_LIB, []), (_LIB_OMP, ["-fopenmp"])):
+        if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+            subprocess.check_call(["gcc"] + CFLAGS + extra + ["-o", lib, _SRC, "-lm"])
     return _LIB
 
 
-_lib = None
+_libs = {}
 
 
-def _load():
-    global _lib
-    if _lib is None:
+def _load(threads=False):
+    """threads=False: the plain single-thread build; True: the OpenMP build of the same source."""
+    if threads not in _libs:
         build()
-        lib = ctypes.CDLL(_LIB)
+        lib = ctypes.CDLL(_LIB_OMP if threads else _LIB)
         lib.orc_objective.restype = ctypes.c_double
         lib.orc_accuracy.restype = ctypes.c_double
         lib.orc_cg.restype = ctypes.c_int
         lib.orc_linesearch.restype = ctypes.c_int
         lib.orc_ssn.restype = ctypes.c_int
         lib.orc_ssn_sg.restype = ctypes.c_int
-        _lib = lib
-    return _lib
+        lib.orc_threads.restype = ctypes.c_int
+        _libs[threads] = lib
+    return _libs[threads]
+
+
+def threads_of(threads):
+    """Threads the row loops of that build use (1 for the plain build)."""
+    return int(_load(threads).orc_threads())
 
 
 def _f64(a):
@@ -70,7 +80,8 @@ def _ptr(a):
 class Problem:
     """Holds the data of one logistic-regression problem for the oracle."""
 
-    def __init__(self, labels, C, lam, X=None, csr=None, p=None, scale="mean"):
+    def __init__(self, labels, C, lam, X=None, csr=None, p=None, scale="mean", threads=False):
+        self.threads = bool(threads)
         self.labels = np.ascontiguousarray(labels, dtype=np.int32)
         self.n = int(self.labels.shape[0])
         self.C = int(C)
@@ -109,13 +120,13 @@ class Problem:
     # ---- eq. (5), Alg. 5 -------------------------------------------------
     def objective(self, W):
         W = self._w(W)
-        return float(_load().orc_objective(self._ref(), _ptr(W)))
+        return float(_load(self.threads).orc_objective(self._ref(), _ptr(W)))
 
     def row_parts(self, W):
         """maxPart, sumExpPart, linearPart, logPart of Alg. 5 (eqs. 14-17), one value per row."""
         W = self._w(W)
         out = [np.empty(self.n) for _ in range(4)]
-        _load().orc_row_parts(self._ref(), _ptr(W), *[_ptr(o) for o in out])
+        _load(self.threads).orc_row_parts(self._ref(), _ptr(W), *[_ptr(o) for o in out])
         return tuple(out)
 
     # ---- eq. (6), Alg. 6 -------------------------------------------------
@@ -123,7 +134,7 @@ class Problem:
         W = self._w(W)
         G = np.empty_like(W)
         f = ctypes.c_double()
-        _load().orc_gradient(self._ref(), _ptr(W), _ptr(G), ctypes.byref(f))
+        _load(self.threads).orc_gradient(self._ref(), _ptr(W), _ptr(G), ctypes.byref(f))
         return G, f.value
 
     # ---- eq. (2a): sub-sampled gradient ----------------------------------
@@ -134,7 +145,7 @@ class Problem:
         assert S.size > 0 and S.min() >= 0 and S.max() < self.n
         G = np.empty_like(W)
         f = ctypes.c_double()
-        _load().orc_gradient_sampled(self._ref(), _ptr(W), _ptr(S), ctypes.c_int64(S.shape[0]), _ptr(G), ctypes.byref(f))
+        _load(self.threads).orc_gradient_sampled(self._ref(), _ptr(W), _ptr(S), ctypes.c_int64(S.shape[0]), _ptr(G), ctypes.byref(f))
         return G, f.value
 
     # ---- eqs. (10)-(13), Alg. 7/8 ---------------------------------------
@@ -142,7 +153,7 @@ class Problem:
         W = self._w(W)
         S = np.ascontiguousarray(S, dtype=np.int32)
         P = np.empty((S.shape[0], self.K))
-        _load().orc_sample_probs(self._ref(), _ptr(W), _ptr(S), ctypes.c_int64(S.shape[0]), _ptr(P))
+        _load(self.threads).orc_sample_probs(self._ref(), _ptr(W), _ptr(S), ctypes.c_int64(S.shape[0]), _ptr(P))
         return P
 
     def hessvec(self, W, S, V):
@@ -150,19 +161,19 @@ class Problem:
         S = np.ascontiguousarray(S, dtype=np.int32)
         assert S.size > 0 and S.min() >= 0 and S.max() < self.n
         HV = np.empty_like(W)
-        _load().orc_hessvec(self._ref(), _ptr(W), _ptr(S), ctypes.c_int64(S.shape[0]), _ptr(V), _ptr(HV))
+        _load(self.threads).orc_hessvec(self._ref(), _ptr(W), _ptr(S), ctypes.c_int64(S.shape[0]), _ptr(V), _ptr(HV))
         return HV
 
     # ---- classification rule --------------------------------------------
     def predict(self, W):
         W = self._w(W)
         pred = np.empty(self.n, dtype=np.int32)
-        _load().orc_predict(self._ref(), _ptr(W), _ptr(pred))
+        _load(self.threads).orc_predict(self._ref(), _ptr(W), _ptr(pred))
         return pred
 
     def accuracy(self, W):
         W = self._w(W)
-        return float(_load().orc_accuracy(self._ref(), _ptr(W)))
+        return float(_load(self.threads).orc_accuracy(self._ref(), _ptr(W)))
 
     # ---- Alg. 2 ------------------------------------------------------------
     def cg(self, W, S, g, theta, T):
@@ -173,7 +184,7 @@ class Problem:
         rel = ctypes.c_double()
         flags = ctypes.c_int32()
         trace = np.zeros((max(T, 1), 3))
-        it = _load().orc_cg(self._ref(), _ptr(W), _ptr(S), ctypes.c_int64(S.shape[0]), _ptr(g),
+        it = _load(self.threads).orc_cg(self._ref(), _ptr(W), _ptr(S), ctypes.c_int64(S.shape[0]), _ptr(g),
                             ctypes.c_double(theta), ctypes.c_int(T), _ptr(p_best),
                             ctypes.byref(rel), ctypes.byref(flags), _ptr(trace))
         return dict(p=p_best, iters=int(it), rel_res=rel.value, flags=flags.value,
@@ -184,7 +195,7 @@ class Problem:
         W, P, g = self._w(W), self._w(P), self._w(g)
         alpha, fnew = ctypes.c_double(), ctypes.c_double()
         ok = ctypes.c_int32()
-        ev = _load().orc_linesearch(self._ref(), _ptr(W), _ptr(P), _ptr(g), ctypes.c_double(fW),
+        ev = _load(self.threads).orc_linesearch(self._ref(), _ptr(W), _ptr(P), _ptr(g), ctypes.c_double(fW),
                                     ctypes.c_double(beta), ctypes.c_double(rho), ctypes.c_int(imax),
                                     ctypes.byref(alpha), ctypes.byref(fnew), ctypes.byref(ok))
         return dict(alpha=alpha.value, f_new=fnew.value, n_eval=int(ev), ok=int(ok.value))
@@ -196,7 +207,7 @@ class Problem:
         S_all = np.ascontiguousarray(S_all, dtype=np.int32)
         iters, nS = S_all.shape
         log = np.zeros((iters, 6))
-        done = _load().orc_ssn(self._ref(), _ptr(W), ctypes.c_int(iters), _ptr(S_all), ctypes.c_int64(nS),
+        done = _load(self.threads).orc_ssn(self._ref(), _ptr(W), ctypes.c_int(iters), _ptr(S_all), ctypes.c_int64(nS),
                                ctypes.c_double(eps), ctypes.c_double(theta), ctypes.c_int(T),
                                ctypes.c_double(beta), ctypes.c_double(rho), ctypes.c_int(imax), _ptr(log))
         return W, log, int(done)
@@ -209,7 +220,7 @@ class Problem:
         iters, nS = S_all.shape
         assert Sg_all.shape[0] == iters
         log = np.zeros((iters, 6))
-        done = _load().orc_ssn_sg(self._ref(), _ptr(W), ctypes.c_int(iters), _ptr(Sg_all), ctypes.c_int64(Sg_all.shape[1]),
+        done = _load(self.threads).orc_ssn_sg(self._ref(), _ptr(W), ctypes.c_int(iters), _ptr(Sg_all), ctypes.c_int64(Sg_all.shape[1]),
                                   _ptr(S_all), ctypes.c_int64(nS), ctypes.c_double(eps), ctypes.c_double(theta),
                                   ctypes.c_int(T), ctypes.c_double(beta), ctypes.c_double(rho), ctypes.c_int(imax),
                                   _ptr(log))

@@ -2,9 +2,15 @@
  * CPU oracle for sub-sampled Newton on L2-regularised multinomial logistic
  * regression ("GPU Accelerated Sub-Sampled Newton's Method", arXiv 1802.09113).
  *
- * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, single
- * threaded fp64 implementation whose only job is to be obviously correct so
- * that the GPU library can be checked against it.  Only the test-suite, the
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow fp64
+ * implementation whose only job is to be obviously correct so that the GPU
+ * library can be checked against it.  Built as it is, it runs on one thread.
+ * Built with -fopenmp (a second library, for the all-cores timing of the
+ * benchmark and the long full-size test cases) the loops over rows of
+ * objective, gradient and Hessian-vector product are cut into one contiguous
+ * chunk of rows per thread, every thread sums its chunk exactly as the
+ * single-thread loop would, and the per-thread sums are added in thread order;
+ * tests/test_oracle_threads.py pins that build to the single-thread one.  Only the test-suite, the
  * smoke check and the benchmark's cpu_baseline leg may load it.  It shares no
  * code, header, table or helper with the HIP library.
  *
@@ -46,6 +52,53 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Threads for a loop over `rows` rows with a d-element long-double accumulator per thread (0 if none):
+ * all the OpenMP build is given, but never more than there are rows, and never more accumulators than
+ * fit 2 GiB.  1 without OpenMP. */
+static int loop_threads(int64_t rows, int64_t d)
+{
+#ifdef _OPENMP
+    int64_t nt = omp_get_max_threads();
+    if (nt > rows) nt = rows;
+    if (d > 0) {
+        const int64_t fit = ((int64_t)1 << 31) / (d * (int64_t)sizeof(long double));
+        if (nt > fit) nt = fit;
+    }
+    return nt < 1 ? 1 : (int)nt;
+#else
+    (void)rows; (void)d;
+    return 1;
+#endif
+}
+
+static int this_thread(void)
+{
+#ifdef _OPENMP
+    return omp_get_thread_num();
+#else
+    return 0;
+#endif
+}
+
+/* rows [lo, hi) of thread t of nt: contiguous chunks in row order */
+static void thread_rows(int64_t rows, int nt, int t, int64_t *lo, int64_t *hi)
+{
+    const int64_t per = (rows + nt - 1) / nt;
+    *lo = per * t < rows ? per * t : rows;
+    *hi = *lo + per < rows ? *lo + per : rows;
+}
+
+/* acc[0..d) += acc[t*d .. (t+1)*d) for t = 1..nt-1, in that order */
+static void fold_threads(long double *acc, int64_t d, int nt)
+{
+    for (int t = 1; t < nt; ++t)
+        for (int64_t e = 0; e < d; ++e)
+            acc[e] += acc[(int64_t)t * d + e];
+}
 
 typedef struct {
     int64_t n, p;
@@ -158,17 +211,29 @@ void orc_row_parts(const orc_problem *pr, const double *W,
 double orc_objective(const orc_problem *pr, const double *W)
 {
     const int K = pr->C - 1;
-    double *z = (double *)malloc(sizeof(double) * (size_t)K);
-    long double total = 0.0L;
-    for (int64_t i = 0; i < pr->n; ++i) {
-        row_margins(pr, i, W, z);
-        double alpha;
-        const double M = stable_softmax(K, z, &alpha, NULL);
-        const int b = pr->labels[i];
-        const double lin = (b < K) ? z[b] : 0.0;
-        total += (long double)M + (long double)log(alpha) - (long double)lin;
+    const int nt = loop_threads(pr->n, 0);
+    long double *tot = (long double *)calloc((size_t)nt, sizeof(long double));
+#pragma omp parallel num_threads(nt)
+    {
+        const int t = this_thread();
+        int64_t lo, hi;
+        thread_rows(pr->n, nt, t, &lo, &hi);
+        double *z = (double *)malloc(sizeof(double) * (size_t)K);
+        long double total = 0.0L;
+        for (int64_t i = lo; i < hi; ++i) {
+            row_margins(pr, i, W, z);
+            double alpha;
+            const double M = stable_softmax(K, z, &alpha, NULL);
+            const int b = pr->labels[i];
+            const double lin = (b < K) ? z[b] : 0.0;
+            total += (long double)M + (long double)log(alpha) - (long double)lin;
+        }
+        tot[t] = total;
+        free(z);
     }
-    free(z);
+    fold_threads(tot, 1, nt);
+    const long double total = tot[0];
+    free(tot);
     return (double)((long double)data_scale_full(pr) * total + half_lambda_sqnorm(pr, W));
 }
 
@@ -177,25 +242,37 @@ void orc_gradient(const orc_problem *pr, const double *W, double *G, double *f_o
 {
     const int K = pr->C - 1;
     const int64_t d = pr->p * (int64_t)K;
-    double *z = (double *)malloc(sizeof(double) * (size_t)K);
-    double *prob = (double *)malloc(sizeof(double) * (size_t)K);
-    long double *acc = (long double *)calloc((size_t)d, sizeof(long double));
-    long double total = 0.0L;
-    for (int64_t i = 0; i < pr->n; ++i) {
-        row_margins(pr, i, W, z);
-        double alpha;
-        const double M = stable_softmax(K, z, &alpha, prob);
-        const int b = pr->labels[i];
-        total += (long double)M + (long double)log(alpha) - (long double)((b < K) ? z[b] : 0.0);
-        if (b < K) prob[b] -= 1.0;          /* BInd_ic = p_ic - 1(b_i = c) */
-        row_outer_add(pr, i, prob, acc);
+    const int nt = loop_threads(pr->n, d);
+    long double *acc = (long double *)calloc((size_t)d * (size_t)nt, sizeof(long double));
+    long double *tot = (long double *)calloc((size_t)nt, sizeof(long double));
+#pragma omp parallel num_threads(nt)
+    {
+        const int t = this_thread();
+        int64_t lo, hi;
+        thread_rows(pr->n, nt, t, &lo, &hi);
+        double *z = (double *)malloc(sizeof(double) * (size_t)K);
+        double *prob = (double *)malloc(sizeof(double) * (size_t)K);
+        long double total = 0.0L;
+        for (int64_t i = lo; i < hi; ++i) {
+            row_margins(pr, i, W, z);
+            double alpha;
+            const double M = stable_softmax(K, z, &alpha, prob);
+            const int b = pr->labels[i];
+            total += (long double)M + (long double)log(alpha) - (long double)((b < K) ? z[b] : 0.0);
+            if (b < K) prob[b] -= 1.0;          /* BInd_ic = p_ic - 1(b_i = c) */
+            row_outer_add(pr, i, prob, acc + (int64_t)t * d);
+        }
+        tot[t] = total;
+        free(prob); free(z);
     }
+    fold_threads(acc, d, nt);
+    fold_threads(tot, 1, nt);
     const long double s = (long double)data_scale_full(pr);
     for (int64_t t = 0; t < d; ++t)
         G[t] = (double)(s * acc[t] + (long double)pr->lambda * (long double)W[t]);
     if (f_out)
-        *f_out = (double)(s * total + half_lambda_sqnorm(pr, W));
-    free(acc); free(prob); free(z);
+        *f_out = (double)(s * tot[0] + half_lambda_sqnorm(pr, W));
+    free(tot); free(acc);
 }
 
 /* Sub-sampled gradient, eq. (2a): G = scale_S * sum_{i in S} a_i (p_i - y_i)^T + lambda W with the
@@ -207,26 +284,38 @@ void orc_gradient_sampled(const orc_problem *pr, const double *W, const int32_t 
 {
     const int K = pr->C - 1;
     const int64_t d = pr->p * (int64_t)K;
-    double *z = (double *)malloc(sizeof(double) * (size_t)K);
-    double *prob = (double *)malloc(sizeof(double) * (size_t)K);
-    long double *acc = (long double *)calloc((size_t)d, sizeof(long double));
-    long double total = 0.0L;
-    for (int64_t s = 0; s < nS; ++s) {
-        const int64_t i = S[s];
-        row_margins(pr, i, W, z);
-        double alpha;
-        const double M = stable_softmax(K, z, &alpha, prob);
-        const int b = pr->labels[i];
-        total += (long double)M + (long double)log(alpha) - (long double)((b < K) ? z[b] : 0.0);
-        if (b < K) prob[b] -= 1.0;
-        row_outer_add(pr, i, prob, acc);
+    const int nt = loop_threads(nS, d);
+    long double *acc = (long double *)calloc((size_t)d * (size_t)nt, sizeof(long double));
+    long double *tot = (long double *)calloc((size_t)nt, sizeof(long double));
+#pragma omp parallel num_threads(nt)
+    {
+        const int t = this_thread();
+        int64_t lo, hi;
+        thread_rows(nS, nt, t, &lo, &hi);
+        double *z = (double *)malloc(sizeof(double) * (size_t)K);
+        double *prob = (double *)malloc(sizeof(double) * (size_t)K);
+        long double total = 0.0L;
+        for (int64_t s = lo; s < hi; ++s) {
+            const int64_t i = S[s];
+            row_margins(pr, i, W, z);
+            double alpha;
+            const double M = stable_softmax(K, z, &alpha, prob);
+            const int b = pr->labels[i];
+            total += (long double)M + (long double)log(alpha) - (long double)((b < K) ? z[b] : 0.0);
+            if (b < K) prob[b] -= 1.0;
+            row_outer_add(pr, i, prob, acc + (int64_t)t * d);
+        }
+        tot[t] = total;
+        free(prob); free(z);
     }
+    fold_threads(acc, d, nt);
+    fold_threads(tot, 1, nt);
     const long double sc = (long double)data_scale_sample(pr, nS);
     for (int64_t t = 0; t < d; ++t)
         G[t] = (double)(sc * acc[t] + (long double)pr->lambda * (long double)W[t]);
     if (f_out)
-        *f_out = (double)(sc * total + half_lambda_sqnorm(pr, W));
-    free(acc); free(prob); free(z);
+        *f_out = (double)(sc * tot[0] + half_lambda_sqnorm(pr, W));
+    free(tot); free(acc);
 }
 
 /* Probabilities of the sampled rows: P is nS x K row-major (the matrix W of eq. (11)). */
@@ -250,28 +339,37 @@ void orc_hessvec(const orc_problem *pr, const double *W, const int32_t *S, int64
 {
     const int K = pr->C - 1;
     const int64_t d = pr->p * (int64_t)K;
-    double *z = (double *)malloc(sizeof(double) * (size_t)K);
-    double *prob = (double *)malloc(sizeof(double) * (size_t)K);
-    double *vhat = (double *)malloc(sizeof(double) * (size_t)K);
-    double *u = (double *)malloc(sizeof(double) * (size_t)K);
-    long double *acc = (long double *)calloc((size_t)d, sizeof(long double));
-    for (int64_t s = 0; s < nS; ++s) {
-        const int64_t i = S[s];
-        row_margins(pr, i, W, z);
-        double alpha;
-        (void)stable_softmax(K, z, &alpha, prob);
-        row_margins(pr, i, V, vhat);
-        double t = 0.0;
-        for (int c = 0; c < K; ++c)
-            t += vhat[c] * prob[c];
-        for (int c = 0; c < K; ++c)
-            u[c] = vhat[c] * prob[c] - prob[c] * t;
-        row_outer_add(pr, i, u, acc);
+    const int nt = loop_threads(nS, d);
+    long double *acc = (long double *)calloc((size_t)d * (size_t)nt, sizeof(long double));
+#pragma omp parallel num_threads(nt)
+    {
+        const int th = this_thread();
+        int64_t lo, hi;
+        thread_rows(nS, nt, th, &lo, &hi);
+        double *z = (double *)malloc(sizeof(double) * (size_t)K);
+        double *prob = (double *)malloc(sizeof(double) * (size_t)K);
+        double *vhat = (double *)malloc(sizeof(double) * (size_t)K);
+        double *u = (double *)malloc(sizeof(double) * (size_t)K);
+        for (int64_t s = lo; s < hi; ++s) {
+            const int64_t i = S[s];
+            row_margins(pr, i, W, z);
+            double alpha;
+            (void)stable_softmax(K, z, &alpha, prob);
+            row_margins(pr, i, V, vhat);
+            double t = 0.0;
+            for (int c = 0; c < K; ++c)
+                t += vhat[c] * prob[c];
+            for (int c = 0; c < K; ++c)
+                u[c] = vhat[c] * prob[c] - prob[c] * t;
+            row_outer_add(pr, i, u, acc + (int64_t)th * d);
+        }
+        free(u); free(vhat); free(prob); free(z);
     }
+    fold_threads(acc, d, nt);
     const long double sc = (long double)data_scale_sample(pr, nS);
     for (int64_t t = 0; t < d; ++t)
         HV[t] = (double)(sc * acc[t] + (long double)pr->lambda * (long double)V[t]);
-    free(acc); free(u); free(vhat); free(prob); free(z);
+    free(acc);
 }
 
 /* argmax over [z_0 .. z_{K-1}, 0]; ties go to the lowest class index. */
@@ -316,6 +414,12 @@ static long double ldot(int64_t d, const double *a, const double *b)
  * trace (optional, 3*T doubles): per product k the step alpha_k, ||r_{k+1}|| and
  * s_k^T H s_k.  flags bit0: stopped by the theta test; bit1: s^T H s <= 0 met.
  */
+/* Threads the row loops use: what the OpenMP build was given (OMP_NUM_THREADS), 1 in the plain build. */
+int orc_threads(void)
+{
+    return loop_threads((int64_t)1 << 40, 0);
+}
+
 int orc_cg(const orc_problem *pr, const double *W, const int32_t *S, int64_t nS,
            const double *g, double theta, int T, double *p_best,
            double *rel_res_best, int32_t *flags, double *trace)

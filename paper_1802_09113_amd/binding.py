@@ -24,8 +24,10 @@ SSN_E_ALLOC, SSN_E_HIP, SSN_E_NONFINITE, SSN_E_UNSUPPORTED = -5, -6, -7, -8
 EXPORTS = [
     "ssn_strerror", "ssn_last_error", "ssn_create", "ssn_destroy", "ssn_set_stream", "ssn_objective",
     "ssn_gradient", "ssn_gradient_sampled", "ssn_hess_prepare", "ssn_hess_apply", "ssn_hessvec", "ssn_cg", "ssn_linesearch",
-    "ssn_predict", "ssn_solve", "ssn_axpy", "ssn_time_kernel", "ssn_dense_path", "ssn_normalize_columns",
+    "ssn_predict", "ssn_solve", "ssn_axpy", "ssn_normalize_columns", "ssn_objective_dev", "ssn_gradient_dev",
+    "ssn_accuracy", "ssn_vec_to_rowmajor", "ssn_rowmajor_to_vec",
 ]
+BENCH_EXPORTS = ["ssn_time_kernel", "ssn_dense_path"]          # include/ssn_bench.h
 
 
 class ssn_desc(ctypes.Structure):
@@ -100,7 +102,12 @@ def lib():
         L.ssn_dense_path.argtypes = [vp]
         L.ssn_normalize_columns.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_int64,
                                             vp, vp, vp, ctypes.c_int64, vp, vp]
-        for name in EXPORTS:
+        L.ssn_objective_dev.argtypes = [vp, vp, vp]
+        L.ssn_gradient_dev.argtypes = [vp, vp, vp, vp]
+        L.ssn_accuracy.argtypes = [vp, ctypes.POINTER(ssn_desc), vp, dp]
+        L.ssn_vec_to_rowmajor.argtypes = [vp, vp, vp]
+        L.ssn_rowmajor_to_vec.argtypes = [vp, vp, vp]
+        for name in EXPORTS + BENCH_EXPORTS:
             fn = getattr(L, name)
             if fn.restype is not ctypes.c_char_p:
                 fn.restype = ctypes.c_int
@@ -141,35 +148,42 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else None
 
 
+def make_desc(labels, C, lam, X=None, csr=None, p=None, scale="mean", ldw=None, stream=None):
+    """An ssn_desc for device tensors (and the list of tensors it borrows, to be kept alive by the caller)."""
+    assert labels.is_cuda and labels.dtype == torch.int32
+    keep = [labels]
+    d = ssn_desc()
+    d.n, d.C, d.lam = labels.shape[0], C, lam
+    d.scale = {"mean": SSN_SCALE_MEAN, "sum": SSN_SCALE_SUM}[scale]
+    d.labels = labels.data_ptr()
+    if X is not None:
+        assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
+        d.layout, d.X, d.ldx, d.p = SSN_DENSE_ROWMAJOR, X.data_ptr(), X.stride(0), X.shape[1]
+        tdtype = X.dtype
+        keep.append(X)
+    else:
+        rowptr, colidx, vals = csr
+        assert rowptr.dtype == torch.int32 and colidx.dtype == torch.int32
+        d.layout, d.p, d.nnz = SSN_CSR, p, vals.shape[0]
+        d.rowptr, d.colidx, d.vals = rowptr.data_ptr(), colidx.data_ptr(), vals.data_ptr()
+        tdtype = vals.dtype
+        keep += [rowptr, colidx, vals]
+    d.dtype = {torch.float32: SSN_F32, torch.float64: SSN_F64}[tdtype]
+    d.ldw = int(ldw) if ldw is not None else int(C) - 1
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    d.stream = stream
+    return d, keep
+
+
 class Context:
     """One data set resident on the GPU.  Methods carry the names of the C entry points."""
 
     def __init__(self, labels, C, lam, X=None, csr=None, p=None, scale="mean", ldw=None, stream=None):
-        assert labels.is_cuda and labels.dtype == torch.int32
-        self._keep = [labels]
-        d = ssn_desc()
-        d.n, d.C, d.lam = labels.shape[0], C, lam
-        d.scale = {"mean": SSN_SCALE_MEAN, "sum": SSN_SCALE_SUM}[scale]
-        d.labels = labels.data_ptr()
-        if X is not None:
-            assert X.is_cuda and X.dim() == 2 and X.stride(1) == 1
-            d.layout, d.X, d.ldx, d.p = SSN_DENSE_ROWMAJOR, X.data_ptr(), X.stride(0), X.shape[1]
-            self.tdtype = X.dtype
-            self._keep.append(X)
-        else:
-            rowptr, colidx, vals = csr
-            assert rowptr.dtype == torch.int32 and colidx.dtype == torch.int32
-            d.layout, d.p, d.nnz = SSN_CSR, p, vals.shape[0]
-            d.rowptr, d.colidx, d.vals = rowptr.data_ptr(), colidx.data_ptr(), vals.data_ptr()
-            self.tdtype = vals.dtype
-            self._keep += [rowptr, colidx, vals]
-        d.dtype = {torch.float32: SSN_F32, torch.float64: SSN_F64}[self.tdtype]
+        d, self._keep = make_desc(labels, C, lam, X=X, csr=csr, p=p, scale=scale, ldw=ldw, stream=stream)
+        self.tdtype = X.dtype if X is not None else csr[2].dtype
         self.n, self.p, self.C, self.K = int(d.n), int(d.p), int(C), int(C) - 1
-        self.ldw = int(ldw) if ldw is not None else self.K
-        d.ldw = self.ldw
-        if stream is None:
-            stream = torch.cuda.current_stream().cuda_stream
-        d.stream = stream
+        self.ldw = int(d.ldw)
         self.device = labels.device
         self._h = ctypes.c_void_p()
         st = lib().ssn_create(ctypes.byref(self._h), ctypes.byref(d))
@@ -214,6 +228,32 @@ class Context:
         f = ctypes.c_double()
         self._check(lib().ssn_gradient(self._h, self._blk(W), self._blk(G), ctypes.byref(f) if want_f else None))
         return G, (f.value if want_f else None)
+
+    def ssn_objective_dev(self, W, f_dev):
+        """f_dev: a one-element float64 device tensor that receives f(W); nothing is read back."""
+        assert f_dev.is_cuda and f_dev.dtype == torch.float64
+        self._check(lib().ssn_objective_dev(self._h, self._blk(W), _ptr(f_dev)))
+
+    def ssn_gradient_dev(self, W, G, f_dev):
+        assert f_dev.is_cuda and f_dev.dtype == torch.float64
+        self._check(lib().ssn_gradient_dev(self._h, self._blk(W), self._blk(G), _ptr(f_dev)))
+
+    def ssn_accuracy(self, test_desc, W):
+        acc = ctypes.c_double()
+        self._check(lib().ssn_accuracy(self._h, ctypes.byref(test_desc), self._blk(W), ctypes.byref(acc)))
+        return acc.value
+
+    def ssn_vec_to_rowmajor(self, vec, block=None):
+        assert vec.is_cuda and vec.dtype == self.tdtype and vec.is_contiguous() and vec.numel() == self.p * self.K
+        block = self.new_block() if block is None else block
+        self._check(lib().ssn_vec_to_rowmajor(self._h, _ptr(vec), self._blk(block)))
+        return block
+
+    def ssn_rowmajor_to_vec(self, block, vec=None):
+        vec = torch.empty(self.p * self.K, dtype=self.tdtype, device=self.device) if vec is None else vec
+        assert vec.is_cuda and vec.dtype == self.tdtype and vec.is_contiguous() and vec.numel() == self.p * self.K
+        self._check(lib().ssn_rowmajor_to_vec(self._h, self._blk(block), _ptr(vec)))
+        return vec
 
     def ssn_gradient_sampled(self, W, S, G=None, want_f=True):
         assert S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()

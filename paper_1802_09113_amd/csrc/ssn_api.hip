@@ -2,6 +2,7 @@
 // ownership, kernel sequencing, and the host-side control flow of Alg. 1 and Alg. 3.  Every arithmetic
 // step runs in the kernels of dense_mfma.hip / csr.hip / csc.hip / vecops.hip / preprocess.hip.
 #include "ssn_internal.h"
+#include "ssn_bench.h"
 
 #include <chrono>
 #include <cmath>
@@ -61,7 +62,7 @@ struct ssn_ctx {
                                   // value, then the ticket of its enqueue; the host spins on it instead of synchronising
     unsigned long long f_seq = 0; // ticket of the last enqueue
     double *pub_host = nullptr;   // host-visible block ssn_solve's per-iteration scalars and CG state are written to
-    double *pub_dev = nullptr;    // its device address (null: not mappable, copies are used instead)
+    double *pub_dev = nullptr;    // its device address
     // prepared Hessian sample
     const int32_t *S = nullptr;
     int64_t nS = 0;
@@ -320,31 +321,33 @@ int read_int(ssn_ctx *c, const int32_t *dev, int32_t *host_out)
 // enqueue f(W) into scal_dev[slot]; loss partials must already be in loss_part[0..nparts)
 // f(W) into scal_dev[slot] from the loss partials the rows kernel left.  *mirrored (nullable) tells whether the
 // value also lands in the host-visible word c->f_host (small blocks: one launch does everything).
-int enqueue_objective_value(ssn_ctx *c, const void *W, int nparts, int slot, double scale = -1.0, bool *mirrored = nullptr)
+// dst (nullable): the caller's device word receives the value instead of scal_dev[slot], and nothing is posted to the host
+int enqueue_objective_value(ssn_ctx *c, const void *W, int nparts, int slot, double scale = -1.0, bool *mirrored = nullptr,
+                            double *dst = nullptr)
 {
     if (scale < 0.0) scale = scale_full(c);
     if (mirrored) *mirrored = false;
     // the host-visible copy and its ticket go with slot 0 only (the value a caller is about to wait for)
-    const bool post = slot == 0 && c->f_host_dev != nullptr;
+    const bool post = slot == 0 && !dst;
+    if (!dst) dst = c->scal_dev + slot;
     double *oh = post ? c->f_host_dev : nullptr;
     unsigned long long *th = post ? c->f_ticket_dev : nullptr;
     const unsigned long long ticket = post ? ++c->f_seq : 0;
     if (mirrored) *mirrored = post;
     if (c->d.p * (int64_t)c->K <= OBJ_VALUE_ELEMS) {
         SSN_HIP(c, launch_objective_value(c->d.dtype, c->loss_part, nparts, scale, W, c->d.p, c->K, c->d.ldw,
-                                          0.5 * c->d.lambda, c->scal_dev + slot, oh, th, ticket, c->st));
+                                          0.5 * c->d.lambda, dst, oh, th, ticket, c->st));
         return SSN_OK;
     }
     if (c->sq_for == W && c->n_sq > 0) {         // the kernel that wrote W left the partials of ||W||^2
         c->sq_for = nullptr;
-        SSN_HIP(c, launch_combine(c->loss_part, nparts, scale, c->red_sq, c->n_sq, 0.5 * c->d.lambda, c->scal_dev + slot,
-                                  c->st, oh, th, ticket));
+        SSN_HIP(c, launch_combine(c->loss_part, nparts, scale, c->red_sq, c->n_sq, 0.5 * c->d.lambda, dst, c->st, oh, th,
+                                  ticket));
         return SSN_OK;
     }
     const int vb = vec_blocks(c->d.p * (int64_t)c->K);
     SSN_HIP(c, launch_dot_part(c->d.dtype, c->d.p, c->K, W, c->d.ldw, W, c->d.ldw, c->red_a, vb, nullptr, c->st));
-    SSN_HIP(c, launch_combine(c->loss_part, nparts, scale, c->red_a, vb, 0.5 * c->d.lambda, c->scal_dev + slot,
-                              c->st, oh, th, ticket));
+    SSN_HIP(c, launch_combine(c->loss_part, nparts, scale, c->red_a, vb, 0.5 * c->d.lambda, dst, c->st, oh, th, ticket));
     return SSN_OK;
 }
 
@@ -395,8 +398,9 @@ int objective_impl(ssn_ctx *c, const void *W, double *f)
 
 // defer_f: leave f(W) in scal_dev[0] without reading it back (the caller synchronises later).
 // S (nullable): the sub-sampled gradient of eq. (2a) on the nS rows S, with its sample scaling.
+// f_dev (nullable): f(W) goes to that device word instead (nothing is read back, nothing posted to the host).
 int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f, bool defer_f = false, const int32_t *S = nullptr,
-                  int64_t nS = 0, bool *mirrored_out = nullptr)
+                  int64_t nS = 0, bool *mirrored_out = nullptr, double *f_dev = nullptr)
 {
     const int64_t nrows = S ? nS : c->d.n;
     const double scale = S ? scale_rows(c, nS) : scale_full(c);
@@ -421,6 +425,7 @@ int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f, bool defer_f = 
         SSN_TRY(transposed_product(c, S, nrows, scale, W, G, false, nullptr, nullptr, view));
     }
     bool mirrored = false;
+    if (f_dev) return enqueue_objective_value(c, W, nparts, 0, scale, nullptr, f_dev);
     if (f || defer_f) SSN_TRY(enqueue_objective_value(c, W, nparts, 0, scale, &mirrored));
     if (f && !defer_f) SSN_TRY(read_objective(c, mirrored, f));
     if (mirrored_out) *mirrored_out = mirrored;
@@ -666,14 +671,18 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
     c->f_host = c->host_pin + 256;                                   // bytes 2048.. of the pinned page
     *c->f_host = 0.0;
     {
+        // kernels post scalar results straight into this page: without a device mapping of it the context is
+        // not created (there is no second, copy-based route to keep in step with the first)
         void *dp = nullptr;
-        if (hipHostGetDevicePointer(&dp, c->f_host, 0) == hipSuccess) c->f_host_dev = (double *)dp;
+        CREATE_HIP(hipHostGetDevicePointer(&dp, c->host_pin, 0));
+        if (!dp) return bail(SSN_E_HIP);
+        double *pin_dev = (double *)dp;
+        c->f_host_dev = pin_dev + 256;
         c->f_ticket = (unsigned long long *)(c->host_pin + 257);
         *c->f_ticket = 0;
-        if (c->f_host_dev) c->f_ticket_dev = (unsigned long long *)(c->f_host_dev + 1);
+        c->f_ticket_dev = (unsigned long long *)(c->f_host_dev + 1);
         c->pub_host = c->host_pin + 128;                             // bytes 1024..2047
-        dp = nullptr;
-        if (hipHostGetDevicePointer(&dp, c->pub_host, 0) == hipSuccess) c->pub_dev = (double *)dp;
+        c->pub_dev = pin_dev + 128;
     }
     if (d->layout == SSN_DENSE_ROWMAJOR) {
         const int64_t nft = (d->p + 63) / 64;
@@ -700,6 +709,16 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
         }
         c->part_elems = (int64_t)c->max_chunks * d->p * K;
         CREATE_HIP(hipMalloc(&c->part, (size_t)c->part_elems * c->es));
+    }
+
+    // per-row buffers for samples of up to n rows, so that no product call has to (re)allocate them; a multiset
+    // sample longer than that grows them (ensure_rows)
+    {
+        const int64_t rows = round_up(d->n, 16);
+        CREATE_HIP(hipMalloc(&c->Ubuf, (size_t)rows * (size_t)c->KP * c->es));
+        c->U_rows = rows;
+        CREATE_HIP(hipMalloc(&c->Pbuf, (size_t)rows * (size_t)c->KP * c->es));
+        c->P_rows = rows;
     }
 
     // validation: one device pass over the labels and, for CSR, over the index arrays
@@ -740,6 +759,38 @@ int ssn_gradient(ssn_ctx *c, const void *W, void *G, double *f)
 {
     if (!c || !W || !G || W == G) return fail(c, SSN_E_INVALID_ARG, "ssn_gradient: null or aliased argument");
     return gradient_impl(c, W, G, f);
+}
+
+int ssn_objective_dev(ssn_ctx *c, const void *W, double *f_dev)
+{
+    if (!c || !W || !f_dev) return fail(c, SSN_E_INVALID_ARG, "ssn_objective_dev: null argument");
+    RowsArgs a = rows_base(c);
+    a.nrows = c->d.n;
+    a.M = W;
+    a.mode = ROW_OBJ;
+    int nparts = 0;
+    SSN_TRY(launch_rows(c, a, &nparts));
+    return enqueue_objective_value(c, W, nparts, 0, -1.0, nullptr, f_dev);
+}
+
+int ssn_gradient_dev(ssn_ctx *c, const void *W, void *G, double *f_dev)
+{
+    if (!c || !W || !G || !f_dev || W == G) return fail(c, SSN_E_INVALID_ARG, "ssn_gradient_dev: null or aliased argument");
+    return gradient_impl(c, W, G, nullptr, false, nullptr, 0, nullptr, f_dev);
+}
+
+int ssn_vec_to_rowmajor(ssn_ctx *c, const void *vec, void *block)
+{
+    if (!c || !vec || !block || vec == block) return fail(c, SSN_E_INVALID_ARG, "ssn_vec_to_rowmajor: null or aliased argument");
+    SSN_HIP(c, launch_vec_layout(c->d.dtype, c->d.p, c->K, (void *)vec, block, c->d.ldw, true, c->st));
+    return SSN_OK;
+}
+
+int ssn_rowmajor_to_vec(ssn_ctx *c, const void *block, void *vec)
+{
+    if (!c || !vec || !block || vec == block) return fail(c, SSN_E_INVALID_ARG, "ssn_rowmajor_to_vec: null or aliased argument");
+    SSN_HIP(c, launch_vec_layout(c->d.dtype, c->d.p, c->K, vec, (void *)block, c->d.ldw, false, c->st));
+    return SSN_OK;
 }
 
 // validate: check the sample indices first (one pass and one synchronisation)
@@ -1067,6 +1118,24 @@ int ssn_predict(ssn_ctx *c, const void *W, int32_t *pred, double *acc)
     return SSN_OK;
 }
 
+int ssn_accuracy(ssn_ctx *c, const ssn_desc *test, const void *W, double *acc)
+{
+    if (!c || !test || !W || !acc) return fail(c, SSN_E_INVALID_ARG, "ssn_accuracy: null argument");
+    if (test->p != c->d.p || test->C != c->d.C || test->dtype != c->d.dtype || test->ldw != c->d.ldw)
+        return fail(c, SSN_E_INVALID_ARG, "ssn_accuracy: the held-out rows must share p, C, dtype and ldw with the context");
+    // the held-out rows get a context of their own for the duration of the call (labels and indices validated as
+    // at ssn_create), on the caller's stream: W is then ordered behind whatever the context has enqueued
+    ssn_desc td = *test;
+    td.stream = (void *)c->st;
+    ssn_ctx *t = nullptr;
+    const int s = ssn_create(&t, &td);
+    if (s != SSN_OK) return fail(c, s, "ssn_accuracy: the description of the held-out rows was rejected");
+    const int r = ssn_predict(t, W, nullptr, acc);
+    if (r != SSN_OK) c->err = "ssn_accuracy: " + t->err;
+    ssn_destroy(t);
+    return r;
+}
+
 int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, int32_t max_log, int32_t *iters_done)
 {
     if (!c || !W || !pr || !pr->S_all || pr->nS < 1 || pr->iters < 0)
@@ -1155,26 +1224,19 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
         SOLVE_HIP(mark(E[1]));
         SOLVE_TRY(hess_prepare_impl(c, cur, pr->S_all + (int64_t)k * pr->nS, pr->nS, false, true));
         SOLVE_HIP(mark(E[2]));
-        // CSR with a device mapping of the host block: CG leaves the slope's partials (n_slope > 0)
+        // CSR: CG leaves the slope's partials (n_slope > 0)
         int n_slope = 0;
         bool tail_fused = false;             // small dense blocks: the CG tail has formed slope, trial point and publication
-        SOLVE_TRY(cg_enqueue(c, c->grad, pr->theta, pr->T, c->dir, c->pub_dev ? &n_slope : nullptr, cur, oth, c->pub_dev,
-                             &tail_fused));
+        SOLVE_TRY(cg_enqueue(c, c->grad, pr->theta, pr->T, c->dir, &n_slope, cur, oth, c->pub_dev, &tail_fused));
         // F(x_k), <dir, g> and the final CG state (which carries ||g||) reach the host through host-visible
-        // memory written by one small kernel; without a device mapping of it, through two copies
+        // memory written by one small kernel
         if (n_slope == 0 && !tail_fused)
             SOLVE_HIP(launch_dot_part(c->d.dtype, c->d.p, c->K, c->dir, c->d.ldw, c->grad, c->d.ldw, c->red_a, vb, nullptr,
                                       c->st));
-        double *pub = c->pub_dev ? c->pub_host : c->host_pin;
-        if (tail_fused) {
-        } else if (c->pub_dev) {
+        const double *pub = c->pub_host;
+        if (!tail_fused)
             SOLVE_HIP(launch_solve_publish(c->red_a, n_slope ? n_slope : vb, c->scal_dev, c->slots + pr->T, c->scal_dev + 1,
                                            c->pub_dev, n_slope > 0, c->st));
-        } else {
-            SOLVE_HIP(launch_combine(c->red_a, vb, 1.0, nullptr, 0, 0.0, c->scal_dev + 1, c->st));
-            SOLVE_HIP(hipMemcpyAsync(pub, c->scal_dev, 2 * sizeof(double), hipMemcpyDeviceToHost, c->st));
-            SOLVE_HIP(hipMemcpyAsync(pub + 2, c->slots + pr->T, sizeof(CgSlot), hipMemcpyDeviceToHost, c->st));
-        }
         SOLVE_HIP(mark(E[3]));
         // The first trial of the line search is x_k + dir whatever the host reads back, so it is enqueued
         // before the host waits: one wait per iteration covers the CG results and the trial's F.

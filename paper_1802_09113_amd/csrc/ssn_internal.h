@@ -117,6 +117,12 @@ hipError_t launch_scale_copy(int dtype, int64_t p, int K, double lambda, const v
 // partials of <A, B> over the p x K block: part[b] for b < blocks
 hipError_t launch_dot_part(int dtype, int64_t p, int K, const void *A, int64_t lda, const void *B, int64_t ldb,
                            double *part, int blocks, const int32_t *skip, hipStream_t st);
+// to_block: block (p x K row-major, leading dimension ld) <- vec (class-major d-vector, element c * p + j);
+// otherwise vec <- block
+hipError_t launch_vec_layout(int dtype, int64_t p, int K, void *vec, void *block, int64_t ld, bool to_block,
+                             hipStream_t st);
+// dst[0..len) = src[0..n) followed by zeros
+hipError_t launch_pad_copy(int dtype, const void *src, int64_t n, void *dst, int64_t len, hipStream_t st);
 // Y = alpha * X + Z (Y may alias Z)
 hipError_t launch_axpy(int dtype, int64_t p, int K, double alpha, const void *X, int64_t ldx_,
                        const void *Z, int64_t ldz, void *Y, int64_t ldy, hipStream_t st);

@@ -570,6 +570,49 @@ hipError_t launch_dot_part(int dtype, int64_t p, int K, const void *A, int64_t l
     return hipGetLastError();
 }
 
+template <typename T> __global__ __launch_bounds__(VEC_BLOCK) void pad_copy_kernel(const T *src, int64_t n, T *dst, int64_t len)
+{
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < len; e += (int64_t)gridDim.x * VEC_BLOCK)
+        dst[e] = e < n ? src[e] : T(0);
+}
+
+hipError_t launch_pad_copy(int dtype, const void *src, int64_t n, void *dst, int64_t len, hipStream_t st)
+{
+    const int blocks = (int)((len + VEC_BLOCK - 1) / VEC_BLOCK);
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(pad_copy_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, (const float *)src, n, (float *)dst, len);
+    else
+        hipLaunchKernelGGL(pad_copy_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, (const double *)src, n, (double *)dst, len);
+    return hipGetLastError();
+}
+
+// The paper stacks the weight columns, x = [x_1; ...; x_K] (Sec. 3.3): element (j, c) of the p x K block is
+// element c * p + j of that d-vector.
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void vec_layout_kernel(int64_t p, int K, T *vec, T *block, int64_t ld, int to_block)
+{
+    const int64_t total = p * K;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int64_t j = e / K;
+        const int c = (int)(e - j * K);
+        if (to_block) block[j * ld + c] = vec[(int64_t)c * p + j];
+        else vec[(int64_t)c * p + j] = block[j * ld + c];
+    }
+}
+
+hipError_t launch_vec_layout(int dtype, int64_t p, int K, void *vec, void *block, int64_t ld, bool to_block,
+                             hipStream_t st)
+{
+    const int blocks = vec_blocks(p * (int64_t)K);
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(vec_layout_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, p, K, (float *)vec, (float *)block, ld,
+                           to_block ? 1 : 0);
+    else
+        hipLaunchKernelGGL(vec_layout_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, p, K, (double *)vec, (double *)block,
+                           ld, to_block ? 1 : 0);
+    return hipGetLastError();
+}
+
 template <typename T>
 __global__ __launch_bounds__(VEC_BLOCK) void axpy_kernel(int64_t p, int K, double alpha, const T *X, int64_t ldx,
                                                           const T *Z, int64_t ldz, T *Y, int64_t ldy)

@@ -15,9 +15,13 @@ def np_dtype(dt):
 
 
 def rel_err(a, b):
+    """The larger of the norm-wise error ||a - b|| / ||b|| and the element-wise one max|a - b| / max|b|: a block
+    passes a tolerance only if no single entry is off by more than that fraction of the largest entry."""
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
-    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+    normwise = float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+    elementwise = float(np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-300)) if a.size else 0.0
+    return max(normwise, elementwise)
 
 
 def rel_scalar(a, b):

@@ -1,4 +1,4 @@
-"""The C-ABI library loads on a machine without a GPU and exports every symbol include/ssn.h declares."""
+"""The C-ABI library loads on a machine without a GPU and exports every symbol include/*.h declares."""
 import ctypes
 import os
 import re
@@ -8,14 +8,20 @@ from paper_1802_09113_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "ssn.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ssn_[a-z_0-9]+)\s*\(", text)))
+def declared_symbols(header=None):
+    names = ["ssn.h", "ssn_bench.h"] if header is None else [header]
+    out = set()
+    for name in names:
+        text = open(os.path.join(ROOT, "include", name)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        out |= set(re.findall(r"\b(ssn_[a-z_0-9]+)\s*\(", text))
+    return sorted(out)
 
 
 def test_header_and_binding_agree():
-    assert declared_symbols() == sorted(binding.EXPORTS)
+    assert declared_symbols("ssn.h") == sorted(binding.EXPORTS)
+    assert declared_symbols("ssn_bench.h") == sorted(binding.BENCH_EXPORTS)
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["ssn.h", "ssn_bench.h"]
 
 
 def test_library_exports_every_declared_symbol():
@@ -38,3 +44,6 @@ def test_status_strings_and_null_arguments_without_a_gpu():
     assert L.ssn_create(ctypes.byref(h), ctypes.byref(d)) == binding.SSN_E_INVALID_ARG
     assert L.ssn_destroy(None) == binding.SSN_E_INVALID_ARG
     assert L.ssn_objective(None, None, None) == binding.SSN_E_INVALID_ARG
+    assert L.ssn_objective_dev(None, None, None) == binding.SSN_E_INVALID_ARG
+    assert L.ssn_accuracy(None, None, None, None) == binding.SSN_E_INVALID_ARG
+    assert L.ssn_vec_to_rowmajor(None, None, None) == binding.SSN_E_INVALID_ARG

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 F64, F32 = torch.float64, torch.float32
 
 
-def _check(cfg, dtypes, grad=True, all_rows=False):
+def _check(cfg, dtypes, grad=True, all_rows=False, cg=False):
     print(f"[gen] full-size workload {cfg}", flush=True)
     d = synth.make(cfg)
     S = synth.sample_rows(d["n"], d["nS"])
@@ -46,6 +46,18 @@ def _check(cfg, dtypes, grad=True, all_rows=False):
         assert np.sum(Vh * hv) >= pair.oracle.lam * np.sum(Vh * Vh) * (1 - 10 * tol)
         pred, acc = pair.gpu.ssn_predict(Wd, want_pred=False)
         assert abs(acc - pair.oracle.accuracy(Wh)) <= (0.0 if dtype == F64 else 1e-3)
+        if cg and dtype == F64:
+            # Alg. 2 on the full-size sample, followed product by product
+            print(f"[case] full cfg={cfg}: CG trajectory", flush=True)
+            Gh, Gd = pair.block(G_ref)
+            ref = pair.oracle.cg(Wh, S, Gh, 1e-4, d["T"])
+            out = pair.gpu.ssn_cg(Gd, 1e-4, d["T"])
+            torch.cuda.synchronize()
+            assert out["iters"] == ref["iters"] and out["flags"] == ref["flags"]
+            np.testing.assert_allclose(out["alpha"], ref["alpha"], rtol=1e-8)
+            np.testing.assert_allclose(out["rnorm"], ref["rnorm"], rtol=1e-8)
+            np.testing.assert_allclose(out["sHs"], ref["sHs"], rtol=1e-8)
+            assert rel_err(pair.host(out["p"]), ref["p"]) <= 1e-8
         if all_rows:
             # the FullNewton shape: prepare and product on every row (the many-row-block forms of both kernels)
             Sall = np.arange(pair.n, dtype=np.int32)
@@ -65,11 +77,11 @@ def test_tall_narrow_full():
 
 
 def test_wide_full():
-    _check(2, [F32, F64])
+    _check(2, [F32, F64], all_rows=True, cg=True)
 
 
 def test_sparse_full():
-    _check(4, [F64, F32])
+    _check(4, [F64, F32], all_rows=True, cg=True)
 
 
 @pytest.mark.parametrize("p,reps", [(512, 1000), (3072, 170)], ids=["one_pass", "two_kernel"])

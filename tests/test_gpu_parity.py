@@ -389,3 +389,42 @@ def test_predict_and_accuracy(data_cache, cfg, n, dtype):
         assert abs(acc - pair.oracle.accuracy(Wh)) <= 1e-3
     assert acc == pytest.approx(float(np.mean(got == pair.labels)), abs=1e-12)
     pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+@pytest.mark.parametrize("C", [34, 40, 65])
+def test_csr_with_more_than_32_weight_columns(C, dtype):
+    # the CSR kernels split a wave's lanes into (stored entry, class) groups of K lanes: with K in (32, 64] a
+    # wave holds a single group with spare lanes.  Objective, gradient, sampled gradient, product, CG, accuracy.
+    from tests.test_gpu_solvers import _small_csr
+    n, p = 700, 900
+    d = _small_csr(n, p, C, seed=100 + C, empty_rows={5, 699})
+    pair = Pair(d, dtype)
+    tol = TOL[dtype]
+    Wh, Wd = pair.block(synth.probe(p, C - 1, sub=1, scale=0.3))
+    Vh, Vd = pair.block(synth.probe(p, C - 1, sub=2))
+    print(f"[case] csr C={C} dtype={dtype}", flush=True)
+    G, f = pair.gpu.ssn_gradient(Wd)
+    torch.cuda.synchronize()
+    G_ref, f_ref = pair.oracle.gradient(Wh)
+    assert rel_scalar(f, f_ref) <= tol and rel_scalar(pair.gpu.ssn_objective(Wd), f_ref) <= tol
+    assert rel_err(pair.host(G), G_ref) <= tol
+    S = synth.sample_rows(n, 120)
+    S[:3] = S[3]                                     # a repeated row
+    HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+    Gs, fs = pair.gpu.ssn_gradient_sampled(Wd, pair.idx(S))
+    torch.cuda.synchronize()
+    assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
+    Gs_ref, fs_ref = pair.oracle.gradient_sampled(Wh, S)
+    assert rel_err(pair.host(Gs), Gs_ref) <= tol and rel_scalar(fs, fs_ref) <= tol
+    Gh, Gd = pair.block(G_ref)
+    ref = pair.oracle.cg(Wh, S, Gh, 1e-4, 8)
+    out = pair.gpu.ssn_cg(Gd, 1e-4, 8)
+    torch.cuda.synchronize()
+    ttol = 1e-8 if dtype == F64 else 5e-3
+    assert out["iters"] == ref["iters"]
+    np.testing.assert_allclose(out["alpha"], ref["alpha"], rtol=ttol)
+    assert rel_err(pair.host(out["p"]), ref["p"]) <= ttol
+    _, acc = pair.gpu.ssn_predict(Wd, want_pred=False)
+    assert abs(acc - pair.oracle.accuracy(Wh)) <= (0.0 if dtype == F64 else 2e-3)
+    pair.close()
