@@ -59,7 +59,8 @@ enum {
     SSN_E_ALLOC = -5,         /* device allocation failed                                        */
     SSN_E_HIP = -6,           /* a HIP runtime call failed                                       */
     SSN_E_NONFINITE = -7,     /* objective evaluated to NaN/Inf                                  */
-    SSN_E_UNSUPPORTED = -8    /* shape outside the supported range (e.g. C too large)            */
+    SSN_E_UNSUPPORTED = -8,   /* shape outside the supported range (e.g. C too large)            */
+    SSN_E_TOO_LARGE = -9      /* ssn_hessvec_static: the problem needs more than the fixed workspace */
 };
 
 /* Problem description.  Copied by ssn_create; the arrays it points to are borrowed. */
@@ -256,6 +257,21 @@ int ssn_solve(ssn_ctx *ctx, void *W_inout, const ssn_params *params,
 
 /* y = a*x + y style helper used by callers that drive Alg. 1 themselves: W += alpha * P. */
 int ssn_axpy(ssn_ctx *ctx, double alpha, const void *P, void *W_inout);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the product of ssn_hessvec on a dense matrix without a context and
+ * without any allocation.  d [host] describes the data as for ssn_create (layout SSN_DENSE_ROWMAJOR only);
+ * W, V [dev] in, HV [dev] out (p-by-K, leading dimension d->ldw, HV must not alias V or W); S [dev] nS
+ * indices in [0, d->n), repeats allowed.  The probabilities of the sampled rows, the per-workgroup partial
+ * sums and a padded copy of the last row live in a fixed workspace of SSN_STATIC_WORKSPACE_BYTES inside the
+ * library's device image (one copy per GPU, held until the process ends): a problem that needs more returns
+ * SSN_E_TOO_LARGE, CSR or K > 32 SSN_E_UNSUPPORTED, a bad description SSN_E_INVALID_ARG, a failed launch
+ * SSN_E_HIP.  Nothing is validated on the device: labels are not read, and the indices in S are the
+ * caller's responsibility (ssn_hessvec checks them).  Kernels are enqueued on d->stream and the call returns
+ * without waiting.  Every call on a GPU uses that GPU's one workspace, so two calls whose kernels may
+ * overlap on the same GPU (different streams, or threads) race; calls on one stream are safe. */
+#define SSN_STATIC_WORKSPACE_BYTES (48u << 20)
+int ssn_hessvec_static(const ssn_desc *d, const void *W, const int32_t *S, int64_t nS, const void *V, void *HV);
 
 #ifdef __cplusplus
 }

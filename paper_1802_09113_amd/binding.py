@@ -19,13 +19,14 @@ SSN_OK = 0
 SSN_SOLVE_NO_LOOKAHEAD = 1
 SSN_SOLVE_NO_PHASE_TIMES = 2
 SSN_E_INVALID_ARG, SSN_E_BAD_LABEL, SSN_E_BAD_INDEX, SSN_E_NOT_PREPARED = -1, -2, -3, -4
-SSN_E_ALLOC, SSN_E_HIP, SSN_E_NONFINITE, SSN_E_UNSUPPORTED = -5, -6, -7, -8
+SSN_E_ALLOC, SSN_E_HIP, SSN_E_NONFINITE, SSN_E_UNSUPPORTED, SSN_E_TOO_LARGE = -5, -6, -7, -8, -9
+SSN_STATIC_WORKSPACE_BYTES = 48 << 20
 
 EXPORTS = [
     "ssn_strerror", "ssn_last_error", "ssn_create", "ssn_destroy", "ssn_set_stream", "ssn_objective",
     "ssn_gradient", "ssn_gradient_sampled", "ssn_hess_prepare", "ssn_hess_apply", "ssn_hessvec", "ssn_cg", "ssn_linesearch",
     "ssn_predict", "ssn_solve", "ssn_axpy", "ssn_normalize_columns", "ssn_objective_dev", "ssn_gradient_dev",
-    "ssn_accuracy", "ssn_vec_to_rowmajor", "ssn_rowmajor_to_vec",
+    "ssn_accuracy", "ssn_vec_to_rowmajor", "ssn_rowmajor_to_vec", "ssn_hessvec_static",
 ]
 BENCH_EXPORTS = ["ssn_time_kernel", "ssn_dense_path"]          # include/ssn_bench.h
 
@@ -107,6 +108,7 @@ def lib():
         L.ssn_accuracy.argtypes = [vp, ctypes.POINTER(ssn_desc), vp, dp]
         L.ssn_vec_to_rowmajor.argtypes = [vp, vp, vp]
         L.ssn_rowmajor_to_vec.argtypes = [vp, vp, vp]
+        L.ssn_hessvec_static.argtypes = [ctypes.POINTER(ssn_desc), vp, vp, ctypes.c_int64, vp, vp]
         for name in EXPORTS + BENCH_EXPORTS:
             fn = getattr(L, name)
             if fn.restype is not ctypes.c_char_p:
@@ -174,6 +176,13 @@ def make_desc(labels, C, lam, X=None, csr=None, p=None, scale="mean", ldw=None, 
         stream = torch.cuda.current_stream().cuda_stream
     d.stream = stream
     return d, keep
+
+
+def ssn_hessvec_static(desc, W, S, V, HV):
+    """The product of Context.ssn_hessvec without a context and without any allocation: desc from make_desc,
+    W, V, HV p x ldw device blocks, S int32 device indices.  Returns the status (0 = ok)."""
+    assert S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()
+    return lib().ssn_hessvec_static(ctypes.byref(desc), _ptr(W), _ptr(S), S.shape[0], _ptr(V), _ptr(HV))
 
 
 class Context:

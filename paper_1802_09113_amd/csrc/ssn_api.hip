@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -570,6 +571,7 @@ const char *ssn_strerror(int status)
     case SSN_E_HIP: return "HIP runtime error";
     case SSN_E_NONFINITE: return "non-finite objective";
     case SSN_E_UNSUPPORTED: return "unsupported shape";
+    case SSN_E_TOO_LARGE: return "problem exceeds the fixed workspace of ssn_hessvec_static";
     default: return "unknown status";
     }
 }
@@ -1321,6 +1323,118 @@ done:
     if (iters_done) *iters_done = k;
     return status;
 }
+
+}  // extern "C"
+
+// ---- ssn_hessvec_static: the product for callers that cannot allocate --------------------------------------
+// Its workspace is this array in the library's device image.  The name below is a host-side stand-in, not a
+// device address: host code uses the address hipGetSymbolAddress returns for the current device (each GPU holds
+// its own copy of the array), looked up once per device and kept in static_dev[].
+static __device__ __align__(256) unsigned char scratch[SSN_STATIC_WORKSPACE_BYTES];
+
+namespace {
+struct StaticDev {
+    unsigned char *ptr = nullptr;     // device address of `scratch` on this GPU
+    int num_cus = 0;
+};
+constexpr int STATIC_MAX_DEVICES = 64;
+StaticDev static_dev[STATIC_MAX_DEVICES];
+std::mutex static_mu;
+
+// first call on a device (that device current): the array's address there and the device's compute-unit count
+int static_setup(int dev, StaticDev *out)
+{
+    std::lock_guard<std::mutex> lock(static_mu);
+    StaticDev &sd = static_dev[dev];
+    if (!sd.ptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SSN_E_HIP;
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return SSN_E_HIP;
+        sd.num_cus = cus;
+        sd.ptr = (unsigned char *)ptr;
+    }
+    *out = sd;
+    return SSN_OK;
+}
+}  // namespace
+
+extern "C" int ssn_hessvec_static(const ssn_desc *d, const void *W, const int32_t *S, int64_t nS, const void *V, void *HV)
+{
+    if (!d || !W || !S || !V || !HV || nS < 1 || V == HV || W == HV) return SSN_E_INVALID_ARG;
+    if (d->n < 1 || d->p < 1 || d->C < 2 || !(d->lambda >= 0.0)) return SSN_E_INVALID_ARG;
+    if (d->dtype != SSN_F32 && d->dtype != SSN_F64) return SSN_E_INVALID_ARG;
+    if (d->scale != SSN_SCALE_MEAN && d->scale != SSN_SCALE_SUM) return SSN_E_INVALID_ARG;
+    if (d->layout == SSN_CSR) return SSN_E_UNSUPPORTED;          // its column-sorted view is built with allocations
+    if (d->layout != SSN_DENSE_ROWMAJOR) return SSN_E_INVALID_ARG;
+    const int K = d->C - 1;
+    if (!d->X || d->ldx < d->p || d->ldw < K) return SSN_E_INVALID_ARG;
+    if (K > 32 || d->n >= (int64_t)1 << 31 || d->p >= (int64_t)1 << 31 || nS >= (int64_t)1 << 31) return SSN_E_UNSUPPORTED;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return SSN_E_HIP;
+    StaticDev sd;
+    SSN_TRY(static_setup(dev, &sd));
+
+    // a context on the stack whose workspace pointers are carved out of the fixed array: the entry points' own
+    // code paths then run unchanged (same kernels, same grids as ssn_hessvec on a created context)
+    ssn_ctx c;
+    c.d = *d;
+    c.K = K;
+    c.es = d->dtype == SSN_F32 ? 4 : 8;
+    c.KP = (K + 15) / 16 * 16;
+    c.st = (hipStream_t)d->stream;
+    c.num_cus = sd.num_cus;
+    c.wave_parts = c.num_cus * 16 * ROWS_WAVES_PER_BLOCK;
+    const int64_t rows = round_up(nS, 16);
+    RowsArgs probe = rows_base(&c);
+    probe.nrows = nS;
+    probe.mode = ROW_APPLY;
+    const char *force = getenv("SSN_DENSE_PATH");
+    c.fused = dense_fused_supported(d->dtype, probe) && !(force && strcmp(force, "split") == 0);
+    if (c.fused) {
+        c.max_chunks = dense_fused_grid(d->dtype, probe, c.num_cus);
+        probe.mode = ROW_PREP;                 // writes no partials, but its grid is checked against the same bound
+        const int gp = dense_fused_grid(d->dtype, probe, c.num_cus);
+        if (gp > c.max_chunks) c.max_chunks = gp;
+        const int64_t vec = 16 / c.es;
+        int64_t len = (d->p + vec - 1) / vec * vec;
+        if (d->ldx > len) len = d->ldx;
+        if (len > d->p + 1024) len = d->p + 1024;
+        c.tail_len = (int)len;
+    } else {
+        const int64_t nft = (d->p + 63) / 64;
+        int64_t mc = ((int64_t)c.num_cus * xtu_waves_per_cu(d->p) + nft - 1) / nft;
+        if (mc > rows / 16) mc = rows / 16;
+        c.max_chunks = (int)mc;
+    }
+    // layout of the workspace (every piece 256-byte aligned)
+    size_t off = 0;
+    auto carve = [&](size_t bytes) {
+        unsigned char *q = sd.ptr + off;
+        off += (bytes + 255) / 256 * 256;
+        return (void *)q;
+    };
+    const size_t row_bytes = (size_t)rows * (size_t)c.KP * c.es;
+    const size_t part_bytes = (size_t)c.max_chunks * (size_t)d->p * (size_t)K * c.es;
+    const size_t need = round_up(sizeof(double) * c.wave_parts, 256) + round_up((int64_t)c.tail_len * (int64_t)c.es, 256)
+                        + 2 * round_up((int64_t)row_bytes, 256) + round_up((int64_t)part_bytes, 256);
+    if (need > (size_t)SSN_STATIC_WORKSPACE_BYTES) return SSN_E_TOO_LARGE;
+    c.loss_part = (double *)carve(sizeof(double) * c.wave_parts);
+    if (c.fused) c.tail_row = carve((size_t)c.tail_len * c.es);
+    c.Pbuf = carve(row_bytes);
+    c.P_rows = rows;
+    c.Ubuf = carve(row_bytes);
+    c.U_rows = rows;
+    c.part = carve(part_bytes);
+    c.part_elems = (int64_t)c.max_chunks * d->p * K;
+    if (c.fused)      // zero-padded copy of the last row (a kernel, not a memset: the call may be under graph capture)
+        SSN_HIP(&c, launch_pad_copy(d->dtype, (const char *)d->X + (size_t)(d->n - 1) * d->ldx * c.es, d->p, c.tail_row,
+                                    c.tail_len, c.st));
+    SSN_TRY(hess_prepare_impl(&c, W, S, nS, false));
+    return hess_apply_impl(&c, V, HV, false, nullptr, nullptr);
+}
+
+extern "C" {
 
 int ssn_time_kernel(ssn_ctx *c, int32_t which, const void *M, int32_t reps, double *ms)
 {

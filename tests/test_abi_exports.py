@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
 def test_status_strings_and_null_arguments_without_a_gpu():
     L = binding.lib()
     assert L.ssn_strerror(0) == b"ok"
-    for code in range(-8, 0):
+    for code in range(-9, 0):
         assert L.ssn_strerror(code) not in (b"ok", b"unknown status")
     assert L.ssn_strerror(-99) == b"unknown status"
     # argument checks come before any device work
@@ -47,3 +47,8 @@ def test_status_strings_and_null_arguments_without_a_gpu():
     assert L.ssn_objective_dev(None, None, None) == binding.SSN_E_INVALID_ARG
     assert L.ssn_accuracy(None, None, None, None) == binding.SSN_E_INVALID_ARG
     assert L.ssn_vec_to_rowmajor(None, None, None) == binding.SSN_E_INVALID_ARG
+    # the entry point without allocations checks its description before it touches the device
+    assert L.ssn_hessvec_static(None, None, None, 0, None, None) == binding.SSN_E_INVALID_ARG
+    d.n, d.p, d.C, d.layout, d.ldw = 10, 4, 3, binding.SSN_CSR, 2
+    one = ctypes.c_void_p(16)
+    assert L.ssn_hessvec_static(ctypes.byref(d), one, one, 1, one, ctypes.c_void_p(32)) == binding.SSN_E_UNSUPPORTED
