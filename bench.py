@@ -1,16 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the sub-sampled Newton hot path on one MI355X.
 
-A step is one full SSN iteration on the image-like dense workload (60000 x 784, C = 10): full gradient
-and objective, Hessian sample of 5 % of the rows, <= 10 CG products H_S v, Armijo line search, update.
-Headline value: sub-sampled Hessian-vector products per second (back-to-back ssn_hess_apply on resident
-data).  Also reported: time per SSN iteration, the HBM roofline of the dominant kernel (HIP events inside
-the library), call-level effective bandwidth of objective / gradient / H_S v, and the CPU oracle timed on
-a bounded sample of the same workload.
+A step is one full SSN iteration on the wide dense workload (50000 x 3072, C = 10: the largest of the
+benchmark's workloads, 1.23 GB in fp64): full gradient and objective, Hessian sample of 5 % of the rows,
+<= 10 CG products H_S v, Armijo line search, update.  Headline value: sub-sampled Hessian-vector products per
+second (back-to-back ssn_hess_apply on resident data).  Also reported in the same JSON line: time per SSN
+iteration, the HBM roofline of the dominant STREAMING kernel (the gradient pass over all rows; HIP events inside
+the library on its own stream) next to the cache-resident sampled product, call-level effective bandwidth of
+objective / gradient / H_S v, the same figures for the other workloads, and the CPU oracle timed on one core
+and on all cores.
 """
 import argparse
 import json
 import os
+import platform
 import statistics
 import sys
 import time
@@ -21,25 +24,20 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X datasheet HBM3E bandwidth
 
-# HBM bytes per launch (fetched + written) measured with `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` on the
-# default workload, scaled by the calibration kernels (profiles/dense_one_pass_image_like_f64_hbm_traffic_pmc.md).
-# Counters cannot be read from inside this script; other workloads / dtypes report null.
-MEASURED_TRAFFIC = {
-    ("image_like", "f64", "dense_fused_kernel<OBJ>"): 377.5e6,
-    ("image_like", "f64", "dense_fused_kernel<GRAD>"): 377.8e6 + 14.5e6,
-    ("image_like", "f64", "dense_fused_kernel<APPLY>"): 19.8e6 + 10.6e6,
-    # profiles/dense_two_kernel_wide_f64_hbm_traffic_pmc.md, profiles/csr_sparse_f64_hbm_traffic_pmc.md
-    ("wide", "f64", "dense_rows_kernel<OBJ>"): 1240.8e6 + 0.1e6,
-    ("wide", "f64", "dense_rows_kernel<GRAD>"): 1240.0e6 + 6.5e6,
-    ("wide", "f64", "dense_xtu_kernel (n rows)"): 1283.0e6 + 9.5e6,
-    ("wide", "f64", "dense_rows_kernel<APPLY>"): 63.6e6 + 0.3e6,
-    ("wide", "f64", "dense_xtu_kernel (|S| rows)"): 64.2e6 + 8.8e6,
-    ("sparse_csr", "f64", "csr_rows_kernel<OBJ>"): 887.9e6,
-    ("sparse_csr", "f64", "csr_rows_kernel<GRAD>"): 879.6e6 + 3.1e6,
-    ("sparse_csr", "f64", "csc_piece_kernel + csc_combine_kernel (n rows)"): 524.1e6 + 57.0e6 + 152.4e6 + 7.8e6,
-    ("sparse_csr", "f64", "csr_rows_kernel<APPLY>"): 54.9e6 + 0.2e6,
-    ("sparse_csr", "f64", "csc_piece_kernel + csc_combine_kernel (|S| rows)"): 42.3e6 + 4.4e6 + 22.1e6 + 0.5e6,
-}
+# HBM bytes per launch (fetched + written) measured with `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` and scaled by
+# the calibration kernels: kept in profiles/hbm_traffic.json next to the summaries they come from (counters cannot
+# be read from inside this script).  A kernel without an entry reports null.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def measured_traffic(workload, dtype, kernel):
+    try:
+        with open(TRAFFIC_FILE) as fh:
+            table = json.load(fh)
+    except OSError:
+        return None
+    ent = table.get(workload, {}).get(dtype, {}).get(kernel)
+    return None if ent is None else ent["fetch_bytes"] + ent["write_bytes"]
 
 
 def parse():
@@ -48,7 +46,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--dtype", choices=["f64", "f32"], default="f64")
-    ap.add_argument("--config", type=int, default=1, help="index into the workload list (1 = image-like dense)")
+    ap.add_argument("--config", type=int, default=2, help="index into the workload list (2 = wide dense, the largest)")
+    ap.add_argument("--no-other-workloads", action="store_true", help="skip the summary of the other workloads")
     ap.add_argument("--n", type=int, default=None, help="override the number of rows (debugging)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-other-dtype", action="store_true", help="skip the secondary-dtype figures")
@@ -288,33 +287,80 @@ def pmc_sequence(data, dtype_name):
     ctx.close()
 
 
-def cpu_baseline(data, budget_s=12.0):
-    """The oracle as it stands, single thread, on a bounded sample of the same workload."""
+def _cpu_model():
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return platform.processor() or "unknown"
+
+
+def cpu_baseline(data):
+    """The oracle as it stands on the GPU machine's host, on a bounded sample of the workload: the plain single-thread
+    build, and the OpenMP build of the same source on all the cores the process is given.  Median of 3 repetitions
+    of each call; gradient and objective on the first n/8 rows (scaled to n for the per-call figures)."""
     import numpy as np
+    from oracle import oracle
     from oracle.oracle import Problem
     from paper_1802_09113_amd import synth
-    if data["layout"] == "csr":
-        pr = Problem(data["labels"], data["C"], data["lam"], csr=(data["rowptr"], data["colidx"], data["vals"]), p=data["p"])
-    else:
-        pr = Problem(data["labels"], data["C"], data["lam"], X=data["X"])
-    W = np.zeros((pr.p, pr.K))
-    S = synth.sample_rows(pr.n, data["nS"])
-    V = synth.probe(pr.p, pr.K, sub=10)
-    t0 = time.perf_counter()
-    pr.hessvec(W, S, V)
-    one = time.perf_counter() - t0
-    reps = max(3, min(100, int(budget_s * 0.6 / max(one, 1e-6))))
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        pr.hessvec(W, S, V)
-    hv_s = reps / (time.perf_counter() - t0)
-    t0 = time.perf_counter()
-    pr.ssn(W, S[None, :], theta=1e-4, T=data["T"])
-    iter_s = time.perf_counter() - t0
-    return {"value": hv_s, "unit": "Hess-vec products/s", "cores": 1, "kind": "oracle",
-            "sample": f"{reps} products H_S v (|S|={S.size} of n={pr.n}, p={pr.p}, C={pr.C}) at W=0, plus one full "
-                      f"SSN iteration of the same workload ({iter_s:.2f} s); gcc -O2, fp64 with long-double row sums",
-            "ssn_iteration_s": iter_s}
+    n, nS = data["n"], data["nS"]
+    sub = max(nS, n // 8)
+    S = synth.sample_rows(n, nS)
+
+    def problem(rows, threads):
+        if data["layout"] == "csr":
+            rp = data["rowptr"][: rows + 1]
+            return Problem(data["labels"][:rows], data["C"], data["lam"], threads=threads, p=data["p"],
+                           csr=(rp, data["colidx"][: rp[-1]], data["vals"][: rp[-1]]))
+        return Problem(data["labels"][:rows], data["C"], data["lam"], X=data["X"][:rows], threads=threads)
+
+    def med3(fn):
+        ts = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            fn()
+            ts.append(time.perf_counter() - t0)
+        return statistics.median(ts)
+
+    legs = {}
+    for name, threads in (("single_thread", False), ("all_cores", True)):
+        full, part = problem(n, threads), problem(sub, threads)
+        W = np.zeros((full.p, full.K))
+        V = synth.probe(full.p, full.K, sub=10)
+        t_hv = med3(lambda: full.hessvec(W, S, V))
+        t_grad = med3(lambda: part.gradient(W)) * n / sub
+        t_obj = med3(lambda: part.objective(W)) * n / sub
+        legs[name] = {"cores": oracle.threads_of(threads), "hessvec_s": t_hv, "hv_per_s": 1.0 / t_hv,
+                      "gradient_s_scaled_to_n": t_grad, "objective_s_scaled_to_n": t_obj,
+                      # one SSN iteration = gradient + T products + one line-search trial (the usual case)
+                      "ssn_iteration_s_estimate": t_grad + data["T"] * t_hv + t_obj}
+    one = legs["single_thread"]
+    return {"value": one["hv_per_s"], "unit": "Hess-vec products/s", "cores": 1, "kind": "oracle",
+            "sample": f"median of 3: product H_S v on the workload's sample (|S|={nS} of n={n}, p={data['p']}, C={data['C']}) "
+                      f"at W=0; gradient and objective on the first {sub} rows, scaled to n",
+            "single_thread": one, "all_cores": legs["all_cores"],
+            "nproc": os.cpu_count(), "cpu_model": _cpu_model(),
+            "compiler": "gcc " + " ".join(oracle.CFLAGS) + " (no fast-math; all-cores build adds -fopenmp), fp64 with "
+                        "long-double row sums"}
+
+
+def summary(data, res, dtype):
+    """The headline figures of one workload, for the list of the other workloads."""
+    return {"workload": f"{data['name']}: {data['layout']} {data['n']}x{data['p']}, C={data['C']}, |S|={data['nS']}",
+            "dtype": dtype, "hv_per_s": res["hv_per_s"], "hv_per_s_inside_cg": res["hv_per_s_inside_cg"],
+            "ms_per_ssn_iteration": res["ms_per_step"], "calls": res["calls"],
+            "hess_apply_all_rows": res["hess_apply_all_rows"], "stream_read": res["stream_read"],
+            "kernels": {v["kernel"]: {kk: vv for kk, vv in v.items() if kk != "kernel"} for v in res["kernels"].values()}}
+
+
+def kernel_roofline(data, dtype, k, which, note):
+    ent = k[which]
+    return {"bound": "hbm", "kernel": ent["kernel"], "achieved": ent["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": ent["frac"], "traffic": measured_traffic(data["name"], dtype, ent["kernel"]),
+            "ms_per_launch": ent["ms"], "algorithmic_bytes_per_launch": ent["algorithmic_GB"] * 1e9, "what": note}
 
 
 def main():
@@ -340,19 +386,35 @@ def main():
         other = measure(data, od, args.steps, args.warmup, args.hv_calls)
         sys.stderr.write(f"[bench] {od} measured\n")
     cpu = None if args.no_cpu else cpu_baseline(data)
+    sys.stderr.write("[bench] cpu baseline done\n")
+    others = []
+    if not args.no_other_workloads and args.n is None:
+        for cfg in range(1, len(synth.CONFIGS)):
+            if cfg == args.config:
+                continue
+            od = synth.make(cfg)
+            others.append(summary(od, measure(od, args.dtype, min(args.steps, 5), min(args.warmup, 2), 100), args.dtype))
+            sys.stderr.write(f"[bench] workload {od['name']} measured\n")
+            del od
 
-    # dominant kernel of a step: the launch with the largest share of the step's kernel time
+    # The roofline entry is the dominant STREAMING kernel of a step: the pass over all rows with the largest share
+    # of the step's kernel time (gradient or objective; on the one-pass path the gradient kernel reads X once for
+    # both products).  The sampled product runs on |S| rows that stay cache-resident between the products of an
+    # iteration: its figure is reported beside it and is a latency figure, not an HBM stream.
     k = main_res["kernels"]
     per_step = {0: main_res["ls_evals_mean"] * k[0]["ms"], 1: k[1]["ms"], 2: k[2]["ms"],
                 3: data["T"] * k[3]["ms"], 4: data["T"] * k[4]["ms"]}
-    dom = max((w for w in per_step if "GBps" in k[w]), key=per_step.get)
-    roof = {"bound": "hbm", "kernel": k[dom]["kernel"], "achieved": k[dom]["GBps"], "peak": HBM_PEAK_GBS,
-            "unit": "GB/s", "frac": k[dom]["frac"],
-            "traffic": MEASURED_TRAFFIC.get((data["name"], args.dtype, k[dom]["kernel"])) if args.n is None else None,
-            "ms_per_launch": k[dom]["ms"], "algorithmic_bytes_per_launch": k[dom]["algorithmic_GB"] * 1e9,
-            "share_of_step_kernel_time": per_step[dom] / sum(per_step.values()),
-            "stream_read_GBps": main_res["stream_read"]["GBps"],
-            "frac_of_stream_read": k[dom]["GBps"] / main_res["stream_read"]["GBps"]}
+    stream = max((w for w in (0, 1, 2) if "GBps" in k[w]), key=per_step.get)
+    roof = kernel_roofline(data, args.dtype, k, stream,
+                           "dominant streaming kernel of an SSN iteration (all n rows from HBM)")
+    roof.update({"share_of_step_kernel_time": per_step[stream] / sum(per_step.values()),
+                 "stream_read_GBps": main_res["stream_read"]["GBps"],
+                 "frac_of_stream_read": k[stream]["GBps"] / main_res["stream_read"]["GBps"]})
+    sampled = max((w for w in (3, 4) if "GBps" in k[w]), key=per_step.get)
+    roof_sampled = kernel_roofline(data, args.dtype, k, sampled,
+                                   "sampled product kernel: X_S is cache-resident after the first product of an iteration, "
+                                   "so this is a latency figure, not an HBM stream")
+    roof_sampled["share_of_step_kernel_time"] = per_step[sampled] / sum(per_step.values())
     line = {
         "metric": "sub-sampled Hess-vec products/s", "value": main_res["hv_per_s"], "unit": "products/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
@@ -363,6 +425,7 @@ def main():
                                f"|S|={data['nS']} (5%), CG T={data['T']}, theta=1e-4, Armijo beta=1e-4 rho=0.5; "
                                f"step = one SSN iteration", "config_index": args.config},
         "roofline": roof,
+        "roofline_sampled_product": roof_sampled,
         "cpu_baseline": cpu,
         "time_per_ssn_iteration_ms": main_res["ms_per_step"],
         "hv_per_s_inside_cg": main_res["hv_per_s_inside_cg"],
@@ -379,13 +442,9 @@ def main():
     }
     if other is not None:
         od = "f32" if args.dtype == "f64" else "f64"
-        line["other_dtype"] = {"dtype": od, "hv_per_s": other["hv_per_s"], "ms_per_step": other["ms_per_step"],
-                               "calls": other["calls"],
-                               "stream_read": other["stream_read"],
-                               "hess_apply_all_rows": other["hess_apply_all_rows"],
-                               "phase_ms": other["phase_ms"],
-                               "kernels": {v["kernel"]: {kk: vv for kk, vv in v.items() if kk != "kernel"}
-                                           for v in other["kernels"].values()}}
+        line["other_dtype"] = summary(data, other, od)
+    if others:
+        line["other_workloads"] = others
     print(json.dumps(line))
 
 
