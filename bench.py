@@ -114,6 +114,8 @@ KERNEL_NAMES = {
         3: "dense_rows_kernel<APPLY>", 4: "dense_xtu_kernel (|S| rows)"},
     2: {0: "dense_fused_kernel<OBJ>", 1: "dense_fused_kernel<GRAD>", 2: "finalize_kernel (gradient partials)",
         3: "dense_fused_kernel<APPLY>", 4: "finalize_kernel (H_S v partials)"},
+    3: {0: "binary_rows_kernel<OBJ>", 1: "binary_rows_kernel<GRAD>", 2: "binary_xtu_kernel (n rows)",
+        3: "binary_rows_kernel<APPLY>", 4: "binary_xtu_kernel (|S| rows)"},
 }
 
 

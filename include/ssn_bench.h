@@ -26,7 +26,8 @@ int ssn_time_kernel(ssn_ctx *ctx, int32_t which, const void *M, int32_t reps, do
 
 /* Which kernels serve this context: 0 = CSR, 1 = dense two-kernel path (margins, then X^T U), 2 = dense
  * one-pass path (every row of X read once per product; needs K <= 16 and p <= 1024; rows need no alignment
- * beyond their element's).
+ * beyond their element's), 3 = dense binary path (C = 2, at least 128 features: matrix-vector kernels on the
+ * vector units, margins then X^T u).
  * The environment variable SSN_DENSE_PATH=split forces 1 at ssn_create (for measurements). */
 int ssn_dense_path(const ssn_ctx *ctx);
 

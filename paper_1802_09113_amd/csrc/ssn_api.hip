@@ -34,6 +34,7 @@ struct ssn_ctx {
     int64_t part_elems = 0;
     int max_chunks = 0;
     bool fused = false;           // dense: the one-pass kernel serves this shape
+    bool binary = false;          // dense, K = 1: the matrix-vector kernels of dense_binary.hip serve every mode
     // CSR: column-sorted views for the transposed products (whole matrix: built at the first gradient;
     // sample: rebuilt by every ssn_hess_prepare)
     CscView csc_full, csc_samp, csc_grad;      // csc_grad: the sample of the last sub-sampled gradient
@@ -194,8 +195,29 @@ bool use_fused(const ssn_ctx *c, const RowsArgs &a)
     return a.nrows >= (int64_t)16 * 12 * c->num_cus;
 }
 
+// K = 1 on a dense matrix of at least 128 features: matrix-vector kernels instead of the 16-column matrix-core tiles
+// (narrower matrices keep the tiles: a wave per row would idle most of its lanes).  SSN_BINARY_PATH=mfma turns it off
+// (for measurements).
+bool binary_path(const ssn_desc *d)
+{
+    const char *force = getenv("SSN_BINARY_PATH");
+    return d->layout == SSN_DENSE_ROWMAJOR && d->C == 2 && d->p >= 128 && !(force && strcmp(force, "mfma") == 0);
+}
+
+hipError_t launch_xtu(const ssn_ctx *c, const XtuArgs &x)
+{
+    return c->binary ? launch_binary_xtu(c->d.dtype, x, c->st) : launch_dense_xtu(c->d.dtype, x, c->st);
+}
+
 int launch_rows(ssn_ctx *c, const RowsArgs &a, int *nparts)
 {
+    if (c->binary) {
+        const int blocks = binary_rows_blocks(a.nrows, c->num_cus);
+        if (blocks * ROWS_WAVES_PER_BLOCK > c->wave_parts) return fail(c, SSN_E_INVALID_ARG, "internal: wave partial overflow");
+        SSN_HIP(c, launch_binary_rows(c->d.dtype, a, blocks, c->st));
+        if (nparts) *nparts = blocks * ROWS_WAVES_PER_BLOCK;
+        return SSN_OK;
+    }
     if (use_fused(c, a)) {
         const int grid = dense_fused_grid(c->d.dtype, a, c->num_cus);
         if (grid * 4 > c->wave_parts || grid > c->max_chunks) return fail(c, SSN_E_INVALID_ARG, "internal: partial overflow");
@@ -223,6 +245,19 @@ int xtu_waves_per_cu(int64_t p) { return p <= 128 ? 32 : 8; }
 // choose the row chunking of the dense transposed product
 void choose_chunks(const ssn_ctx *c, int64_t nrows, int64_t *rpc, int *nch)
 {
+    if (c->binary) {
+        // a block of the matrix-vector kernel covers 256 sixteen-byte vectors of features; aim at 8 blocks per
+        // compute unit, chunks of at least 8 rows
+        const int64_t tiles = (c->d.p * (int64_t)c->es + 4095) / 4096;
+        int64_t n = ((int64_t)c->num_cus * 8 + tiles - 1) / tiles;
+        if (n > (nrows + 7) / 8) n = (nrows + 7) / 8;
+        if (n > c->max_chunks) n = c->max_chunks;
+        if (n < 1) n = 1;
+        const int64_t r = (nrows + n - 1) / n;
+        *rpc = r;
+        *nch = (int)((nrows + r - 1) / r);
+        return;
+    }
     const int64_t nft = (c->d.p + 63) / 64;
     const int64_t target = (int64_t)c->num_cus * xtu_waves_per_cu(c->d.p);
     int64_t n = (target + nft - 1) / nft;
@@ -287,7 +322,7 @@ int transposed_product(ssn_ctx *c, const int32_t *S, int64_t nrows, double scale
     x.skip = skip;
     if (is_dense(c)) {
         choose_chunks(c, nrows, &x.rows_per_chunk, &x.nchunks);
-        SSN_HIP(c, launch_dense_xtu(c->d.dtype, x, c->st));
+        SSN_HIP(c, launch_xtu(c, x));
         SSN_TRY(finalize_dense(c, x.nchunks, scale, M, out, want_dot, ndot, skip));
     } else {
         const CscView *view = view_in;
@@ -499,7 +534,7 @@ int cg_product_step(ssn_ctx *c, const CgVecs &v, CgSlot *slots, int k, double th
             x.U = c->Ubuf;
             x.skip = skip;
             choose_chunks(c, c->nS, &x.rows_per_chunk, &x.nchunks);
-            SSN_HIP(c, launch_dense_xtu(c->d.dtype, x, c->st));
+            SSN_HIP(c, launch_xtu(c, x));
             nchunks = x.nchunks;
         }
         FinArgs f{};
@@ -693,7 +728,12 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
         probe.nrows = (int64_t)1 << 40;
         probe.mode = ROW_GRAD;                                 // the family that writes partials
         const char *force = getenv("SSN_DENSE_PATH");          // "split" forces the two-kernel path
-        c->fused = dense_fused_supported(d->dtype, probe) && !(force && strcmp(force, "split") == 0);
+        c->binary = binary_path(d);
+        if (c->binary) {
+            c->KP = 1;                                         // per-row buffers hold one value per row
+            if (c->max_chunks < c->num_cus * 8) c->max_chunks = c->num_cus * 8;
+        }
+        c->fused = !c->binary && dense_fused_supported(d->dtype, probe) && !(force && strcmp(force, "split") == 0);
         if (c->fused) {
             const int g = dense_fused_grid(d->dtype, probe, c->num_cus);
             if (g > c->max_chunks) c->max_chunks = g;
@@ -1390,8 +1430,12 @@ extern "C" int ssn_hessvec_static(const ssn_desc *d, const void *W, const int32_
     probe.nrows = nS;
     probe.mode = ROW_APPLY;
     const char *force = getenv("SSN_DENSE_PATH");
-    c.fused = dense_fused_supported(d->dtype, probe) && !(force && strcmp(force, "split") == 0);
-    if (c.fused) {
+    c.binary = binary_path(d);
+    if (c.binary) c.KP = 1;
+    c.fused = !c.binary && dense_fused_supported(d->dtype, probe) && !(force && strcmp(force, "split") == 0);
+    if (c.binary) {
+        c.max_chunks = (int)(rows / 8 < (int64_t)c.num_cus * 8 ? rows / 8 : (int64_t)c.num_cus * 8);
+    } else if (c.fused) {
         c.max_chunks = dense_fused_grid(d->dtype, probe, c.num_cus);
         probe.mode = ROW_PREP;                 // writes no partials, but its grid is checked against the same bound
         const int gp = dense_fused_grid(d->dtype, probe, c.num_cus);
@@ -1487,7 +1531,7 @@ int ssn_time_kernel(ssn_ctx *c, int32_t which, const void *M, int32_t reps, doub
     for (int r = 0; r < reps && status == SSN_OK && he == hipSuccess; ++r) {
         if (which == 2 || which == 4) {
             if (c->fused) status = finalize_dense(c, fused_parts, sampled ? scale_sample(c) : scale_full(c), M, c->trial, false, nullptr, nullptr);
-            else if (is_dense(c)) he = launch_dense_xtu(c->d.dtype, x, c->st);
+            else if (is_dense(c)) he = launch_xtu(c, x);
             else {
                 const CscView *view = nullptr;
                 status = csc_view_for(c, a.S, &view);
@@ -1515,6 +1559,7 @@ int ssn_dense_path(const ssn_ctx *c)
 {
     if (!c) return SSN_E_INVALID_ARG;
     if (!is_dense(c)) return 0;
+    if (c->binary) return 3;
     return c->fused ? 2 : 1;
 }
 

@@ -108,6 +108,10 @@ int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus);
 int dense_fused_waves(int dtype, const RowsArgs &a);
 hipError_t launch_dense_fused(int dtype, const RowsArgs &a, int grid, hipStream_t st);
 hipError_t launch_csr_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
+// binary problem (K = 1) on a dense matrix: matrix-vector kernels on the vector units (dense_binary.hip)
+int binary_rows_blocks(int64_t nrows, int num_cus);
+hipError_t launch_binary_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
+hipError_t launch_binary_xtu(int dtype, const XtuArgs &a, hipStream_t st);
 hipError_t launch_finalize(int dtype, const FinArgs &a, int blocks, hipStream_t st);
 
 // out = lambda * M (p x K), with optional <.,.> partials disabled; used by the CSR path before scattering

@@ -14,6 +14,9 @@ Workloads (index = position in the benchmark's config list):
   2 wide dense        50000 x 3072   C=10  U[0,1), rows mean-centred
   3 tall-narrow dense 581012 x 54    C=7   10 N(0,1) columns + 44 Bernoulli(0.05) columns, skewed class prior
   4 sparse CSR        20000 x 1355191 C=20 ~450 nnz/row, Zipf(1.1) column ids, lognormal values, unit-norm rows
+Binary workloads (C = 2) shaped like the two binary data sets of Table 1 (not in the benchmark's config list):
+  5 binary dense      6000 x 5000    C=2   ~13% non-zeros U[0,1) (Gisette-shaped)
+  6 binary sparse CSR 65078 x 20958  C=2   ~57 nnz/row, recipe of workload 4 (Real-Sim-shaped)
 """
 import numpy as np
 
@@ -29,6 +32,8 @@ CONFIGS = [
     dict(name="tall_narrow", n=581012, p=54, C=7, lam=1e-5, frac=0.01, T=10, iters=10, layout="dense"),
     dict(name="sparse_csr", n=20000, p=1355191, C=20, lam=1e-4, frac=0.05, T=10, iters=10, layout="csr",
          nnz_row=450),
+    dict(name="binary_dense", n=6000, p=5000, C=2, lam=1e-4, frac=0.05, T=10, iters=10, layout="dense"),
+    dict(name="binary_sparse_csr", n=65078, p=20958, C=2, lam=1e-4, frac=0.05, T=10, iters=10, layout="csr", nnz_row=57),
 ]
 
 
@@ -58,6 +63,10 @@ def _dense_rows(cfg_idx, n, p, g):
         X = np.empty((n, p))
         X[:, :10] = g.standard_normal((n, 10))
         X[:, 10:] = (g.random((n, p - 10)) < 0.05).astype(np.float64)
+        return X
+    if cfg_idx == 5:
+        X = g.random((n, p))
+        X *= (g.random((n, p)) < 0.13)
         return X
     raise ValueError(cfg_idx)
 
@@ -131,6 +140,8 @@ def make(cfg_idx, n=None, p=None, seed=SEED, part="train"):
             scores = X @ W_true
         elif cfg_idx in (1, 2):
             scores = X @ W_true / np.sqrt(p)
+        elif cfg_idx == 5:
+            scores = X @ W_true * (4.0 / np.sqrt(0.13 * p / 3.0))        # score spread of about 4: learnable labels
         else:
             prior = np.array([36, 49, 6, 0.5, 1.6, 3, 3.5])
             scores = X @ (0.5 * W_true) + np.log(prior / prior.sum())

@@ -86,3 +86,24 @@ class Pair:
 
 def workload(cfg, n, **kw):
     return synth.make(cfg, n=n, **kw)
+
+
+def oracle_sensitivity(pair, data, W0h, S_all, T, rel_noise, theta=1e-4):
+    """How far the oracle's SSN run moves when the data are perturbed by relative noise of size rel_noise (1e-14:
+    what a different order of summation in fp64 amounts to; 1e-6: fp32 products): the running maximum of the
+    relative deviation of the objective per iteration, and the relative deviation of the final iterate.  The
+    Krylov process behind Alg. 2 can amplify such perturbations by many orders of magnitude, so an end-to-end
+    comparison is only as sharp as this figure."""
+    o = pair.oracle
+    g = np.random.default_rng(5)
+    if data["layout"] == "dense":
+        base = Problem(data["labels"], o.C, o.lam, X=o.X, threads=True)
+        pert = Problem(data["labels"], o.C, o.lam, X=o.X * (1.0 + rel_noise * g.standard_normal(o.X.shape)), threads=True)
+    else:
+        base = Problem(data["labels"], o.C, o.lam, csr=(o.rowptr, o.colidx, o.vals), p=o.p, threads=True)
+        pert = Problem(data["labels"], o.C, o.lam, p=o.p, threads=True,
+                       csr=(o.rowptr, o.colidx, o.vals * (1.0 + rel_noise * g.standard_normal(o.vals.shape))))
+    Wa, la, _ = base.ssn(W0h, S_all, theta=theta, T=T)
+    Wb, lb, _ = pert.ssn(W0h, S_all, theta=theta, T=T)
+    f_dev = np.maximum.accumulate(np.abs(lb[:, 0] / la[:, 0] - 1.0))
+    return f_dev, rel_err(Wb, Wa), np.array_equal(la[:, 4], lb[:, 4])
