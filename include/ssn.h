@@ -103,6 +103,11 @@ typedef struct {
 /* Leave out the six stream events per iteration behind the ms_* fields of the iteration records (which then
  * hold NaN): each record costs a few microseconds of device time. */
 #define SSN_SOLVE_NO_PHASE_TIMES 2
+/* Back-tracking trials of the line search (every trial after the first) are evaluated on cached margins:
+ * X (W + alpha P) = X W + alpha X P, so one pass over the data leaves X W and X P (n rows of 2K numbers) and each
+ * further trial is a pass over those instead of over X.  The same F up to rounding; Alg. 3's trial sequence and
+ * exit rules are unchanged.  This flag makes every trial a pass over the data, as Alg. 3 is written. */
+#define SSN_SOLVE_NO_MARGIN_CACHE 4
 
 /* Parameters of ssn_solve (Alg. 1, 2, 3).  The paper gives no numeric values for beta, rho,
  * i_max; textbook values are the defaults chosen by callers. */
@@ -222,7 +227,10 @@ int ssn_cg(ssn_ctx *ctx, const void *G, double theta, int32_t T, void *P_out,
 
 /* Back-tracking line search, Alg. 3 / eq. (3c): alpha = 1; while f(W + alpha P) > fW +
  * alpha*beta*<P,G>: if i > imax stop; i++; alpha *= rho.
- * W, P, G [dev]; alpha, f_new, n_eval, ok [host] outputs (ok = 1 iff Armijo held at exit). */
+ * W, P, G [dev]; alpha, f_new, n_eval, ok [host] outputs (ok = 1 iff Armijo held at exit).
+ * The trials are evaluated on cached margins (one pass over the data for X W and X P, then n*2K numbers per
+ * trial; see SSN_SOLVE_NO_MARGIN_CACHE), except on dense matrices with more than 16 weight columns.  The first
+ * call allocates the cache (n * 2K elements). */
 int ssn_linesearch(ssn_ctx *ctx, const void *W, const void *P, const void *G, double fW,
                    double beta, double rho, int32_t imax,
                    double *alpha, double *f_new, int32_t *n_eval, int32_t *ok);

@@ -18,6 +18,7 @@ SSN_SCALE_MEAN, SSN_SCALE_SUM = 0, 1
 SSN_OK = 0
 SSN_SOLVE_NO_LOOKAHEAD = 1
 SSN_SOLVE_NO_PHASE_TIMES = 2
+SSN_SOLVE_NO_MARGIN_CACHE = 4
 SSN_E_INVALID_ARG, SSN_E_BAD_LABEL, SSN_E_BAD_INDEX, SSN_E_NOT_PREPARED = -1, -2, -3, -4
 SSN_E_ALLOC, SSN_E_HIP, SSN_E_NONFINITE, SSN_E_UNSUPPORTED, SSN_E_TOO_LARGE = -5, -6, -7, -8, -9
 SSN_STATIC_WORKSPACE_BYTES = 48 << 20
@@ -327,7 +328,7 @@ class Context:
         return ms.value
 
     def ssn_solve(self, W, S_all, eps=0.0, theta=1e-4, T=10, beta=1e-4, rho=0.5, imax=10, test=None, Sg_all=None,
-                  lookahead=True, phase_times=True):
+                  lookahead=True, phase_times=True, margin_cache=True):
         """S_all: (iters, nS) int32 device tensor; Sg_all (optional): (iters, nSg) gradient samples.  W is updated
         in place; returns (records, iterations done).  lookahead=False sets SSN_SOLVE_NO_LOOKAHEAD,
         phase_times=False SSN_SOLVE_NO_PHASE_TIMES."""
@@ -340,7 +341,8 @@ class Context:
         pr.iters, pr.nS = S_all.shape
         pr.T, pr.imax, pr.eps, pr.theta, pr.beta, pr.rho = T, imax, eps, theta, beta, rho
         pr.S_all = S_all.data_ptr()
-        pr.flags = (0 if lookahead else SSN_SOLVE_NO_LOOKAHEAD) | (0 if phase_times else SSN_SOLVE_NO_PHASE_TIMES)
+        pr.flags = ((0 if lookahead else SSN_SOLVE_NO_LOOKAHEAD) | (0 if phase_times else SSN_SOLVE_NO_PHASE_TIMES)
+                    | (0 if margin_cache else SSN_SOLVE_NO_MARGIN_CACHE))
         pr.test = test._h if test is not None else None
         log = (ssn_iter_record * max(int(pr.iters), 1))()
         done = ctypes.c_int32()

@@ -93,6 +93,16 @@ template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER
     for (int64_t sv = wave; sv < a.nrows; sv += nwaves) {
         const int64_t row = a.S ? a.S[sv] : sv;
         const T z = csr_row_margin<T>(a, row, lane, K, NS);
+        if constexpr (MODE == ROW_MARGIN) {              // margins of both operands, [X M | X M2], 2K values per row
+            RowsArgs b = a;
+            b.M = a.M2;
+            const T z2 = csr_row_margin<T>(b, row, lane, K, NS);
+            if (cv) {
+                ((T *)a.UP)[sv * a.KP + lane] = z;
+                ((T *)a.UP)[sv * a.KP + K + lane] = z2;
+            }
+            continue;
+        }
         if constexpr (MODE == ROW_APPLY) {
             const T pin = cv ? ((const T *)a.Pin)[sv * a.KP + lane] : T(0);
             const T t = wave_sum(pin * z);
@@ -142,6 +152,7 @@ template <typename T> static hipError_t csr_rows_dispatch(const RowsArgs &a, int
     case ROW_PREP: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_PREP>), grid, block, 0, st, a); break;
     case ROW_APPLY: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_APPLY>), grid, block, 0, st, a); break;
     case ROW_PRED: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_PRED>), grid, block, 0, st, a); break;
+    case ROW_MARGIN: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_MARGIN>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

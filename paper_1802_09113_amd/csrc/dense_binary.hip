@@ -76,6 +76,9 @@ template <typename T, int VEC, int MODE> __global__ __launch_bounds__(256) void 
     const int64_t nwaves = (int64_t)gridDim.x * 4, wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const T *X = (const T *)a.X;
     const T *w = (const T *)a.M;             // p weights, stride a.ldm
+    // ROW_MARGIN: the margins of a second operand ride along (the same loads of X serve both)
+    constexpr bool TWO = MODE == ROW_MARGIN;
+    const T *w2 = TWO ? (const T *)a.M2 : w;
     const int64_t p = a.p, ldm = a.ldm;
     const int64_t pv = p / VEC * VEC;        // features covered by whole vectors
     double loss = 0.0;
@@ -85,7 +88,7 @@ template <typename T, int VEC, int MODE> __global__ __launch_bounds__(256) void 
         const int64_t s1 = two ? s0 + 1 : s0;
         const int64_t r0 = a.S ? (int64_t)a.S[s0] : s0, r1 = a.S ? (int64_t)a.S[s1] : s1;
         const T *x0 = X + r0 * a.ldx, *x1 = X + r1 * a.ldx;
-        T z0 = 0, z1 = 0;
+        T z0 = 0, z1 = 0, y0 = 0, y1 = 0;
         int64_t f = (int64_t)lane * VEC;
         for (; f + (int64_t)(UNR - 1) * 64 * VEC < pv; f += (int64_t)UNR * 64 * VEC) {
             pack xa[UNR], xb[UNR];
@@ -103,6 +106,11 @@ template <typename T, int VEC, int MODE> __global__ __launch_bounds__(256) void 
                 for (int m = 0; m < VEC; ++m) {
                     z0 += xa[u].v[m] * wv[u][m];
                     z1 += xb[u].v[m] * wv[u][m];
+                    if constexpr (TWO) {
+                        const T w2m = w2[(f + (int64_t)u * 64 * VEC + m) * ldm];
+                        y0 += xa[u].v[m] * w2m;
+                        y1 += xb[u].v[m] * w2m;
+                    }
                 }
         }
         for (; f < pv; f += 64 * VEC) {
@@ -112,15 +120,39 @@ template <typename T, int VEC, int MODE> __global__ __launch_bounds__(256) void 
                 const T wm = w[(f + m) * ldm];
                 z0 += xa.v[m] * wm;
                 z1 += xb.v[m] * wm;
+                if constexpr (TWO) {
+                    const T w2m = w2[(f + m) * ldm];
+                    y0 += xa.v[m] * w2m;
+                    y1 += xb.v[m] * w2m;
+                }
             }
         }
         for (int64_t g = pv + lane; g < p; g += 64) {          // features beyond the last whole vector
             const T wm = w[g * ldm];
             z0 += x0[g] * wm;
             z1 += x1[g] * wm;
+            if constexpr (TWO) {
+                const T w2m = w2[g * ldm];
+                y0 += x0[g] * w2m;
+                y1 += x1[g] * w2m;
+            }
         }
         z0 = wave_sum64(z0);
         z1 = wave_sum64(z1);
+        if constexpr (TWO) {                 // [x.w, x.w2] per row
+            y0 = wave_sum64(y0);
+            y1 = wave_sum64(y1);
+            if (lane == 0) {
+                T *Z = (T *)a.UP;
+                Z[s0 * a.KP] = z0;
+                Z[s0 * a.KP + 1] = y0;
+                if (two) {
+                    Z[s1 * a.KP] = z1;
+                    Z[s1 * a.KP + 1] = y1;
+                }
+            }
+            continue;
+        }
         binary_row<T, MODE>(a, s0, r0, z0, lane, loss, hits);
         if (two) binary_row<T, MODE>(a, s1, r1, z1, lane, loss, hits);
     }
@@ -187,6 +219,7 @@ template <typename T, int VEC> hipError_t rows_mode(const RowsArgs &a, int block
     case ROW_PREP: hipLaunchKernelGGL((binary_rows_kernel<T, VEC, ROW_PREP>), grid, block, 0, st, a); break;
     case ROW_APPLY: hipLaunchKernelGGL((binary_rows_kernel<T, VEC, ROW_APPLY>), grid, block, 0, st, a); break;
     case ROW_PRED: hipLaunchKernelGGL((binary_rows_kernel<T, VEC, ROW_PRED>), grid, block, 0, st, a); break;
+    case ROW_MARGIN: hipLaunchKernelGGL((binary_rows_kernel<T, VEC, ROW_MARGIN>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

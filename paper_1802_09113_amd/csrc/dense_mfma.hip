@@ -247,6 +247,17 @@ __device__ __forceinline__ void row_epilogue(const typename V4<T>::type (&acc)[N
     const int q = lane & 15, g = lane >> 4;
     const int K = a.K;
     const T NEG = -std::numeric_limits<T>::infinity();
+    if constexpr (MODE == ROW_MARGIN) {                  // the margins of both operands, 2K values per row
+        T *Z = (T *)a.UP;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int64_t sv = rb * 16 + d_row<T>(g, v);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                if (sv < a.nrows && nb * 16 + q < 2 * K) Z[sv * a.KP + nb * 16 + q] = acc[nb][v];
+        }
+        return;
+    }
     if constexpr (NB == 1 && (MODE == ROW_OBJ || MODE == ROW_GRAD)) {
         if (K <= 7) {                                    // two accumulator elements per pass
 #pragma unroll
@@ -391,13 +402,19 @@ __global__ __launch_bounds__(SPLIT ? 1024 : 64 * ROWS_WAVES_PER_BLOCK) void dens
     const int K = a.K;
     const int64_t p = a.p, ldm = a.ldm;
 
+    // this lane's column of the right operand; ROW_MARGIN: columns K..2K-1 are the columns of the second operand
     bool cval[NB];
     const T *mcol[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int c = nb * 16 + q;
-        cval[nb] = c < K;
-        mcol[nb] = M + (cval[nb] ? c : K - 1);
+        if constexpr (MODE == ROW_MARGIN) {
+            cval[nb] = c < 2 * K;
+            mcol[nb] = (c >= K && cval[nb]) ? (const T *)a.M2 + (c - K) : M + (c < K ? c : K - 1);
+        } else {
+            cval[nb] = c < K;
+            mcol[nb] = M + (cval[nb] ? c : K - 1);
+        }
     }
 
     double loss = 0.0, lprod = 1.0;         // sum of the row terms without log(alpha); product of the alphas
@@ -668,7 +685,7 @@ template <typename T, int MODE>
 static hipError_t rows_dispatch_mode(const RowsArgs &a, int blocks, int split_waves, hipStream_t st)
 {
     constexpr int VEC = 16 / sizeof(T);
-    const int nb = (a.K + 15) / 16;
+    const int nb = ((MODE == ROW_MARGIN ? 2 * a.K : a.K) + 15) / 16;
     const bool v = vec_ok<T>(a.X, a.ldx);
     if (nb != 1 && nb != 2) return hipErrorInvalidValue;
     if (split_waves > 0 && v) {
@@ -706,6 +723,7 @@ template <typename T> static hipError_t rows_dispatch(const RowsArgs &a, int blo
     case ROW_PREP: return rows_dispatch_mode<T, ROW_PREP>(a, blocks, split_waves, st);
     case ROW_APPLY: return rows_dispatch_mode<T, ROW_APPLY>(a, blocks, split_waves, st);
     case ROW_PRED: return rows_dispatch_mode<T, ROW_PRED>(a, blocks, split_waves, st);
+    case ROW_MARGIN: return a.M2 ? rows_dispatch_mode<T, ROW_MARGIN>(a, blocks, split_waves, st) : hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
     }
 }

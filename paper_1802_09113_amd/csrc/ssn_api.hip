@@ -83,6 +83,9 @@ struct ssn_ctx {
     int tail_len = 0;
     int cg_gg_parts = 0;                       // dense CG: partials of g.g in red_a the first finalize forms slot 0 from (0: slot 0 is set)
     double *trace_dev = nullptr;
+    // line search on cached margins: Z = [X W | X P] (n rows of 2K values) and the partials of W.W, W.P, P.P
+    void *Zbuf = nullptr;
+    double *ls_dots = nullptr;
 };
 
 namespace {
@@ -187,7 +190,7 @@ XtuArgs xtu_base(const ssn_ctx *c)
 // kernel is faster).
 bool use_fused(const ssn_ctx *c, const RowsArgs &a)
 {
-    if (!c->fused) return false;
+    if (!c->fused || a.mode == ROW_MARGIN) return false;
     if (a.mode == ROW_GRAD || a.mode == ROW_APPLY) return true;
     if (dense_fused_waves(c->d.dtype, a) > 1) return true;
     // narrow matrix, margins only: the one-pass kernel's single-wave workgroups win once every one of them has a
@@ -229,7 +232,7 @@ int launch_rows(ssn_ctx *c, const RowsArgs &a, int *nparts)
     int blocks = rows_grid_blocks(is_dense(c) ? a.nrows : a.nrows * 16, c->num_cus), split_waves = 0;
     // few row blocks of a wide matrix: a workgroup per row block (needs 16-byte aligned rows)
     if (is_dense(c) && (uintptr_t)c->d.X % 16 == 0 && (c->d.ldx * (int64_t)c->es) % 16 == 0)
-        dense_rows_plan(c->d.dtype, a.nrows, c->d.p, c->K, c->num_cus, &blocks, &split_waves);
+        dense_rows_plan(c->d.dtype, a.nrows, c->d.p, a.mode == ROW_MARGIN ? 2 * c->K : c->K, c->num_cus, &blocks, &split_waves);
     if (blocks * ROWS_WAVES_PER_BLOCK > c->wave_parts) return fail(c, SSN_E_INVALID_ARG, "internal: wave partial overflow");
     if (is_dense(c)) SSN_HIP(c, launch_dense_rows(c->d.dtype, a, blocks, split_waves, c->st));
     else SSN_HIP(c, launch_csr_rows(c->d.dtype, a, blocks, c->st));
@@ -636,7 +639,7 @@ int ssn_destroy(ssn_ctx *c)
     if (!c) return SSN_E_INVALID_ARG;
     (void)hipStreamSynchronize(c->st);
     if (c->st_aux) (void)hipStreamSynchronize(c->st_aux);      // a view of the next sample may still be in the making
-    void *dev[] = {c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->red_c, c->red_sq, c->scal_dev, c->int_dev,
+    void *dev[] = {c->Zbuf, c->ls_dots, c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->red_c, c->red_sq, c->scal_dev, c->int_dev,
                    c->cg_p, c->cg_r, c->cg_s, c->cg_hs, c->cg_parts, c->cg_pb, c->trial, c->grad, c->grad_next, c->dir, c->slots, c->trace_dev,
                    c->tail_row};
     for (void *p : dev)
@@ -1067,7 +1070,8 @@ static int enqueue_slope(ssn_ctx *c, const void *P, const void *G)
 
 int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
                     int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok, void *G_first = nullptr,
-                    const double *first_f = nullptr, int first_status = SSN_OK, void *trial_dst = nullptr);
+                    const double *first_f = nullptr, int first_status = SSN_OK, void *trial_dst = nullptr,
+                    bool margin_cache = true);
 
 int ssn_linesearch(ssn_ctx *c, const void *W, const void *P, const void *G, double fW, double beta, double rho,
                    int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok)
@@ -1105,6 +1109,44 @@ int trial_enqueue(ssn_ctx *c, const void *W, const void *P, double alpha, void *
     return objective_enqueue(c, dst, mirrored);
 }
 
+// The trials of Alg. 3 on cached margins: X (W + alpha P) = X W + alpha X P, so after ONE pass over the data that
+// leaves Z = [X W | X P] (n rows of 2K numbers) every trial is a pass over Z; the regulariser of the trial point
+// comes from W.W, W.P and P.P.  The same F(W + alpha P) up to rounding (the margins are formed as a sum of two
+// products instead of one).  Served: every layout; dense matrices with more than 16 weight columns (two class
+// tiles per operand) keep the plain trials.
+bool margin_cache_ok(const ssn_ctx *c) { return !is_dense(c) || c->binary || 2 * c->K <= 32; }
+
+int margins_enqueue(ssn_ctx *c, const void *W, const void *P)
+{
+    if (!c->Zbuf) {
+        SSN_HIP(c, hipMalloc(&c->Zbuf, (size_t)c->d.n * (size_t)(2 * c->K) * c->es));
+        SSN_HIP(c, hipMalloc((void **)&c->ls_dots, sizeof(double) * 3 * RED_MAX_PARTS));
+    }
+    RowsArgs a = rows_base(c);
+    a.nrows = c->d.n;
+    a.M = W;
+    a.M2 = P;
+    a.mode = ROW_MARGIN;
+    a.UP = c->Zbuf;
+    a.KP = 2 * c->K;
+    SSN_TRY(launch_rows(c, a, nullptr));
+    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+    SSN_HIP(c, launch_dot3_part(c->d.dtype, c->d.p, c->K, W, c->d.ldw, P, c->d.ldw, c->ls_dots, vb, c->st));
+    return SSN_OK;
+}
+
+// F(W + alpha P) from the cached margins into scal_dev[0] and the host-visible word
+int cached_trial_enqueue(ssn_ctx *c, double alpha)
+{
+    int64_t b = (c->d.n + VEC_BLOCK - 1) / VEC_BLOCK;
+    if (b > RED_MAX_PARTS) b = RED_MAX_PARTS;
+    SSN_HIP(c, launch_ls_trial(c->d.dtype, c->Zbuf, 2 * c->K, c->d.n, c->K, c->d.labels, alpha, c->loss_part, (int)b, c->st));
+    const int vb = vec_blocks(c->d.p * (int64_t)c->K);
+    SSN_HIP(c, launch_ls_value(c->loss_part, (int)b, scale_full(c), c->ls_dots, vb, alpha, 0.5 * c->d.lambda, c->scal_dev,
+                               c->f_host_dev, c->f_ticket_dev, ++c->f_seq, c->st));
+    return SSN_OK;
+}
+
 // Alg. 3 with the slope <P, G> already on the host.  G_first (nullable): the first trial, alpha = 1, is
 // evaluated by the gradient pass, which leaves grad f(W + P) there next to the same F(W + P); when that
 // trial is accepted the caller already holds the gradient of the next iterate.  first_f (nullable): the
@@ -1113,15 +1155,25 @@ int trial_enqueue(ssn_ctx *c, const void *W, const void *P, double alpha, void *
 // evaluated is the one the caller moves to, whether the Armijo test held there or the reductions ran out.
 int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double slope, double beta, double rho,
                     int32_t imax, double *alpha_out, double *f_new, int32_t *n_eval, int32_t *ok, void *G_first,
-                    const double *first_f, int first_status, void *trial_dst)
+                    const double *first_f, int first_status, void *trial_dst, bool margin_cache)
 {
     double alpha = 1.0, ft = 0.0;
     int i = 0, evals = 0, good = 0;
+    // trials this function evaluates itself go through the cached margins (the first of them pays for the pass that
+    // fills the cache); a first trial the caller asked to be evaluated with the gradient pass (G_first) keeps that pass
+    const bool cache = margin_cache && margin_cache_ok(c);
+    bool cached = false, formed = true;
     for (;;) {
         int s;
         if (i == 0 && first_f) {
             ft = *first_f;
             s = first_status;
+        } else if (cache && !(i == 0 && G_first)) {
+            if (!cached) SSN_TRY(margins_enqueue(c, W, P));
+            cached = true;
+            SSN_TRY(cached_trial_enqueue(c, alpha));
+            s = read_objective(c, true, &ft);
+            formed = false;
         } else {
             bool mirrored = false;
             SSN_TRY(trial_enqueue(c, W, P, alpha, i == 0 ? G_first : nullptr, &mirrored, false, trial_dst));
@@ -1133,6 +1185,15 @@ int linesearch_impl(ssn_ctx *c, const void *W, const void *P, double fW, double 
         if (i > imax) break;
         ++i;
         alpha *= rho;
+    }
+    if (!formed) {      // the point the caller moves to: W + alpha P for the step returned
+        void *dst = trial_dst;
+        if (!dst) {
+            if (!c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
+            dst = c->trial;
+        }
+        c->sq_for = nullptr;
+        SSN_HIP(c, launch_axpy(c->d.dtype, c->d.p, c->K, alpha, P, c->d.ldw, W, c->d.ldw, dst, c->d.ldw, c->st));
     }
     *alpha_out = alpha;
     *f_new = ft;
@@ -1320,7 +1381,7 @@ int ssn_solve(ssn_ctx *c, void *W, const ssn_params *pr, ssn_iter_record *log, i
             rec.cg_rel_res = info.rel_res;
             double fn = 0.0;
             SOLVE_TRY(linesearch_impl(c, cur, c->dir, rec.f, slope, pr->beta, pr->rho, pr->imax, &rec.alpha, &fn, &rec.ls_evals,
-                                      &rec.ls_ok, nullptr, &f_first, first_status, oth));
+                                      &rec.ls_ok, nullptr, &f_first, first_status, oth, !(pr->flags & SSN_SOLVE_NO_MARGIN_CACHE)));
             f_carry = fn;
             const bool first_accepted = rec.ls_ok && rec.ls_evals == 1;
             have_next = ahead && first_accepted;

@@ -18,7 +18,8 @@ enum RowMode : int {
     ROW_GRAD = 1,   // loss + U = P - Y                            (Alg. 6)
     ROW_PREP = 2,   // store P                                     (eq. (11))
     ROW_APPLY = 3,  // U = P .* Vhat - P .* ((P .* Vhat) e e^T)    (eq. (12), Alg. 8)
-    ROW_PRED = 4    // argmax classification + hit count
+    ROW_PRED = 4,   // argmax classification + hit count
+    ROW_MARGIN = 5  // store the margins of two operands, Z = [X M | X M2] (row stride KP): the line search's cache
 };
 
 // Arguments of the "rows" kernels: Z = X_rows * M followed by a per-row epilogue.
@@ -37,6 +38,7 @@ struct RowsArgs {
     // right operand, p x K, leading dimension ldm
     const void *M;
     int64_t ldm;
+    const void *M2;      // ROW_MARGIN: second right operand (same leading dimension)
     // per-row buffers with row stride KP (padded K): Pin read by ROW_APPLY, UP written by GRAD/PREP/APPLY
     const void *Pin;
     void *UP;
@@ -133,6 +135,18 @@ hipError_t launch_axpy(int dtype, int64_t p, int K, double alpha, const void *X,
 // Y = alpha X + Z with one partial of ||Y||^2 per block (blocks <= RED_MAX_PARTS)
 hipError_t launch_axpy_sq(int dtype, int64_t p, int K, double alpha, const void *X, int64_t ldx, const void *Z, int64_t ldz,
                           void *Y, int64_t ldy, double *sq_part, int blocks, hipStream_t st);
+// partials of A.A, A.B, B.B (blocks entries each, one after the other) from one pass over the two p x K blocks
+hipError_t launch_dot3_part(int dtype, int64_t p, int K, const void *A, int64_t lda, const void *B, int64_t ldb, double *part,
+                            int blocks, hipStream_t st);
+// Line search on cached margins (Alg. 3 with X (W + alpha P) = X W + alpha X P): Z holds n rows [X W | X P] of 2K
+// values (row stride kp); one loss partial per block for the trial step alpha
+hipError_t launch_ls_trial(int dtype, const void *Z, int kp, int64_t n, int K, const int32_t *labels, double alpha,
+                           double *loss_part, int blocks, hipStream_t st);
+// *out (and the host-visible word, then the ticket) = scale * sum(loss) + half_lambda * (ww + 2 alpha wp + alpha^2 pp)
+// with ww, wp, pp the sums of three partial arrays of nd entries each (dots[0..nd), [nd..2nd), [2nd..3nd))
+hipError_t launch_ls_value(const double *loss_part, int nparts, double scale, const double *dots, int nd, double alpha,
+                           double half_lambda, double *out, double *out_host, unsigned long long *ticket_host,
+                           unsigned long long ticket, hipStream_t st);
 // *out = scale * sum(a[0..na)) + coef * sum(b[0..nb))   (single block, fixed order)
 // *out (and *out_host, nullable, host-visible) = scale * sum(loss_part) + half_lambda * ||W||_F^2 ; one block, for
 // blocks of up to OBJ_VALUE_ELEMS elements

@@ -5,6 +5,7 @@
 // partials in one fixed order.  Scalars of Alg. 2 never visit the host: each kernel of product k reads
 // the state slot k and block 0 writes slot k+1, so no slot is read and written by the same launch.
 #include "ssn_internal.h"
+#include "ssn_math.h"
 
 namespace ssn {
 
@@ -733,6 +734,103 @@ hipError_t launch_objective_value(int dtype, const double *loss_part, int nparts
     else
         hipLaunchKernelGGL(objective_value_kernel<double>, dim3(1), dim3(VEC_BLOCK), 0, st, loss_part, nparts, scale,
                            (const double *)W, p, K, ldw, half_lambda, out, out_host, ticket_host, ticket);
+    return hipGetLastError();
+}
+
+// ---- line search on cached margins -----------------------------------------------------------------------
+// F(W + alpha P) needs the margins X (W + alpha P) = X W + alpha X P: with Z = [X W | X P] kept from one pass over
+// the data, a trial of Alg. 3 is a pass over n x 2K numbers instead of over X.  A thread takes a row: eqs. (8), (9),
+// (14)-(17) in fp64 on z = zw + alpha zp; one loss partial per block.
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void ls_trial_kernel(const T *Z, int kp, int64_t n, int K, const int32_t *labels,
+                                                              double alpha, double *loss_part)
+{
+    double local = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; i < n; i += (int64_t)gridDim.x * VEC_BLOCK) {
+        const T *z = Z + i * kp;
+        const int lab = labels[i];
+        double Mx = 0.0, lin = 0.0;
+        for (int c = 0; c < K; ++c) {
+            const double zc = (double)z[c] + alpha * (double)z[K + c];
+            Mx = fmax(Mx, zc);
+            lin = (c == lab) ? zc : lin;
+        }
+        double al = exp_nonpos(-Mx, 0.0);
+        for (int c = 0; c < K; ++c) al += exp_nonpos((double)z[c] + alpha * (double)z[K + c] - Mx, 0.0);
+        local += Mx + log_ge1(al) - lin;
+    }
+    const double r = block_sum(local);
+    if (threadIdx.x == 0) loss_part[blockIdx.x] = r;
+}
+
+hipError_t launch_ls_trial(int dtype, const void *Z, int kp, int64_t n, int K, const int32_t *labels, double alpha,
+                           double *loss_part, int blocks, hipStream_t st)
+{
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(ls_trial_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, (const float *)Z, kp, n, K, labels, alpha,
+                           loss_part);
+    else
+        hipLaunchKernelGGL(ls_trial_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, (const double *)Z, kp, n, K, labels,
+                           alpha, loss_part);
+    return hipGetLastError();
+}
+
+// partials of A.A, A.B and B.B from one pass over the two blocks: part[b], part[nb + b], part[2 nb + b]
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void dot3_part_kernel(int64_t p, int K, const T *A, int64_t lda, const T *B, int64_t ldb,
+                                                               double *part)
+{
+    const int64_t total = p * K;
+    double aa = 0.0, ab = 0.0, bb = 0.0;
+    for (int64_t e = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; e < total; e += (int64_t)gridDim.x * VEC_BLOCK) {
+        const double x = (double)A[off_of(e, K, lda)], y = (double)B[off_of(e, K, ldb)];
+        aa += x * x;
+        ab += x * y;
+        bb += y * y;
+    }
+    double raa, rab;
+    block_sum2(aa, ab, raa, rab);
+    const double rbb = block_sum(bb);
+    if (threadIdx.x == 0) {
+        part[blockIdx.x] = raa;
+        part[gridDim.x + blockIdx.x] = rab;
+        part[2 * gridDim.x + blockIdx.x] = rbb;
+    }
+}
+
+hipError_t launch_dot3_part(int dtype, int64_t p, int K, const void *A, int64_t lda, const void *B, int64_t ldb, double *part,
+                            int blocks, hipStream_t st)
+{
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(dot3_part_kernel<float>, dim3(blocks), dim3(VEC_BLOCK), 0, st, p, K, (const float *)A, lda,
+                           (const float *)B, ldb, part);
+    else
+        hipLaunchKernelGGL(dot3_part_kernel<double>, dim3(blocks), dim3(VEC_BLOCK), 0, st, p, K, (const double *)A, lda,
+                           (const double *)B, ldb, part);
+    return hipGetLastError();
+}
+
+// ||W + alpha P||^2 = W.W + 2 alpha W.P + alpha^2 P.P from the partials of the three products
+__global__ __launch_bounds__(VEC_BLOCK) void ls_value_kernel(const double *loss_part, int nparts, double scale,
+                                                              const double *dots, int nd, double alpha, double half_lambda,
+                                                              double *out, double *out_host, unsigned long long *ticket_host,
+                                                              unsigned long long ticket)
+{
+    const double sl = sum_parts(loss_part, nparts);
+    const double ww = sum_parts(dots, nd), wp = sum_parts(dots + nd, nd), pp = sum_parts(dots + 2 * nd, nd);
+    if (threadIdx.x == 0) {
+        const double f = scale * sl + half_lambda * (ww + 2.0 * alpha * wp + alpha * alpha * pp);
+        *out = f;
+        post_to_host(f, out_host, ticket_host, ticket);
+    }
+}
+
+hipError_t launch_ls_value(const double *loss_part, int nparts, double scale, const double *dots, int nd, double alpha,
+                           double half_lambda, double *out, double *out_host, unsigned long long *ticket_host,
+                           unsigned long long ticket, hipStream_t st)
+{
+    hipLaunchKernelGGL(ls_value_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, loss_part, nparts, scale, dots, nd, alpha, half_lambda,
+                       out, out_host, ticket_host, ticket);
     return hipGetLastError();
 }
 
