@@ -42,6 +42,11 @@ def build(force=False):
     for lib, extra in ((_LIB, []), (_LIB_OMP, ["-fopenmp"])):
         if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
             subprocess.check_call(["gcc"] + CFLAGS + extra + ["-o", lib, _SRC, "-lm"])
+    # the sanitizer driver, here without sanitizers (tests/test_oracle_sanitizers.py builds it with them)
+    drv = os.path.join(_HERE, "sanitize_check.c")
+    exe = os.path.join(_HERE, "sanitize_check")
+    if force or not os.path.exists(exe) or os.path.getmtime(exe) < max(os.path.getmtime(_SRC), os.path.getmtime(drv)):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-o", exe, _SRC, drv, "-lm"])
     return _LIB
 
 
