@@ -28,7 +28,9 @@ int ssn_time_kernel(ssn_ctx *ctx, int32_t which, const void *M, int32_t reps, do
  * one-pass path (every row of X read once per product; needs K <= 16 and p <= 1024; rows need no alignment
  * beyond their element's), 3 = dense binary path (C = 2, at least 128 features: matrix-vector kernels on the
  * vector units, margins then X^T u).
- * The environment variable SSN_DENSE_PATH=split forces 1 at ssn_create (for measurements). */
+ * The environment variable SSN_DENSE_PATH=split forces 1 at ssn_create, SSN_BINARY_PATH=mfma keeps a binary
+ * problem on the matrix-core paths, and SSN_SAMPLED_SLICES=0 turns off the feature-sliced margins of sampled
+ * products on wide matrices (all three for measurements). */
 int ssn_dense_path(const ssn_ctx *ctx);
 
 #ifdef __cplusplus

@@ -533,7 +533,11 @@ __global__ __launch_bounds__(SPLIT ? 1024 : 64 * ROWS_WAVES_PER_BLOCK) void dens
 // Block = 4 waves, each wave owns 64 consecutive features; blockIdx.y = row chunk.
 // A vector load of VEC consecutive features per lane feeds VEC MFMAs whose output rows are the
 // features {base + VEC*i + m : i = 0..15}.
-template <typename T, int NB, int VEC>
+// FROMZ (one class tile): the rows of U are not read but formed here from the partial margins of a.nslices feature
+// slices and the probabilities, eq. (12): the 16 lanes of a row group hold the 16 class columns of a row, as in the
+// per-row work of the rows kernels.  Every feature tile's workgroup forms the same U (a few loads and a row
+// reduction per four rows); the workgroup of the first tile also leaves the chunk's sum of z_i . u_i.
+template <typename T, int NB, int VEC, bool FROMZ = false>
 __global__ __launch_bounds__(256) void dense_xtu_kernel(XtuArgs a)
 {
     if (a.skip && *a.skip) return;
@@ -553,6 +557,26 @@ __global__ __launch_bounds__(256) void dense_xtu_kernel(XtuArgs a)
     const T *X = (const T *)a.X;
     const T *U = (const T *)a.U;
     const bool full = (f0 + FT) <= p;
+    double zu_sum = 0.0;
+    // FROMZ: u of sample row sc, class q, from the row's margin z and probability pin (all 64 lanes take part: the
+    // row sums are DPP rotations inside the row group)
+    constexpr int MAXS = 4;                           // feature slices at most (the launcher's plan keeps to it)
+    auto load_z = [&](int64_t sc, T (&zs)[MAXS], T &pin) {
+        const T *zp = (const T *)a.Zpart + sc * 16 + q;
+#pragma unroll
+        for (int s = 0; s < MAXS; ++s) zs[s] = zp[(int64_t)(s < a.nslices ? s : 0) * a.zrows * 16];
+        pin = ((const T *)a.Pin)[sc * a.KP + q];      // zero in padded columns
+    };
+    auto form_u = [&](const T (&zs)[MAXS], T pin, bool rv) -> T {
+        T z = zs[0];
+#pragma unroll
+        for (int s = 1; s < MAXS; ++s) z += (s < a.nslices) ? zs[s] : T(0);      // slices in a fixed order
+        const T t = row16_sum(pin * z);
+        const T u = rv ? (pin * z - pin * t) : T(0);
+        const T zu = row16_sum(z * u);
+        if (q == 0) zu_sum += (double)zu;
+        return u;
+    };
 
     v4 acc[NL * VEC][NB];
 #pragma unroll
@@ -568,6 +592,7 @@ __global__ __launch_bounds__(256) void dense_xtu_kernel(XtuArgs a)
         for (; r0 + 4 * RU <= r_end; r0 += 4 * RU) {
             pack xv[RU][NL];
             T ub[RU][NB];
+            T zsl[FROMZ ? RU : 1][MAXS], pinv[FROMZ ? RU : 1];
 #pragma unroll
             for (int u = 0; u < RU; ++u) {
                 const int64_t sc = r0 + 4 * u + g;
@@ -575,8 +600,16 @@ __global__ __launch_bounds__(256) void dense_xtu_kernel(XtuArgs a)
                 const T *xrow = X + xr * a.ldx + f0 + VEC * q;
 #pragma unroll
                 for (int ld = 0; ld < NL; ++ld) xv[u][ld] = *(const pack *)(xrow + ld * 16 * VEC);
+                if constexpr (FROMZ) {
+                    load_z(sc, zsl[u], pinv[u]);      // every load of the trip is issued before the first row sum
+                } else {
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) ub[u][nb] = U[sc * a.KP + nb * 16 + q];
+                    for (int nb = 0; nb < NB; ++nb) ub[u][nb] = U[sc * a.KP + nb * 16 + q];
+                }
+            }
+            if constexpr (FROMZ) {
+#pragma unroll
+                for (int u = 0; u < RU; ++u) ub[u][0] = form_u(zsl[u], pinv[u], true);
             }
 #pragma unroll
             for (int u = 0; u < RU; ++u)
@@ -596,10 +629,16 @@ __global__ __launch_bounds__(256) void dense_xtu_kernel(XtuArgs a)
         const int64_t xr = a.S ? a.S[sc] : sc;
         const T *xrow = X + xr * a.ldx + f0;
         T ub[NB];
+        if constexpr (FROMZ) {
+            T zs1[MAXS], pin1;
+            load_z(sc, zs1, pin1);
+            ub[0] = form_u(zs1, pin1, rv);
+        } else {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const T u = U[sc * a.KP + nb * 16 + q];
-            ub[nb] = rv ? u : T(0);
+            for (int nb = 0; nb < NB; ++nb) {
+                const T u = U[sc * a.KP + nb * 16 + q];
+                ub[nb] = rv ? u : T(0);
+            }
         }
 #pragma unroll
         for (int ld = 0; ld < NL; ++ld) {
@@ -620,6 +659,12 @@ __global__ __launch_bounds__(256) void dense_xtu_kernel(XtuArgs a)
         }
     }
 
+    if constexpr (FROMZ) {
+        if (blockIdx.x == 0 && wib == 0) {           // one sum of z_i . u_i per chunk, from the first feature tile's wave
+            for (int off = 32; off > 0; off >>= 1) zu_sum += __shfl_xor(zu_sum, off);
+            if (lane == 0) a.zu_part[chunk] = zu_sum;
+        }
+    }
     T *part = (T *)a.part + chunk * p * K;
 #pragma unroll
     for (int ld = 0; ld < NL; ++ld)
@@ -655,6 +700,90 @@ template <typename T> static bool vec_ok(const void *X, int64_t ldx)
 {
     constexpr int VEC = 16 / sizeof(T);
     return ((uintptr_t)X % 16 == 0) && (ldx % VEC == 0);
+}
+
+// Partial margins of feature slices, for products on a sample of a few thousand rows of a wide matrix: such a sample
+// has fewer 16-row blocks than the chip has compute units, so a workgroup per row block leaves a third of them idle
+// and each workgroup walks all p features.  Here a workgroup of eight waves takes one (row block, feature slice)
+// pair; its waves take the slice's feature groups in turn and add their partial margins through LDS in wave order;
+// the slices' partial margins Zpart[s][row][16] are added up, and eq. (12) applied, by the transposed-product kernel
+// that follows (dense_xtu_kernel with FROMZ).
+template <typename T, int VEC>
+__global__ __launch_bounds__(512) void dense_zpart_kernel(RowsArgs a, T *Zpart, int nslices, int64_t fper)
+{
+    if (a.skip && *a.skip) return;
+    typedef typename V4<T>::type v4;
+    typedef Pack<T, VEC> pack;
+    __shared__ T zs[8 * 256];
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6, nsw = blockDim.x >> 6;
+    const int q = lane & 15, g = lane >> 4;
+    const int64_t rb = blockIdx.x / nslices;
+    const int sl = blockIdx.x - (int)rb * nslices;
+    const int64_t zrows = (a.nrows + 15) / 16 * 16;
+    const T *X = (const T *)a.X;
+    const int K = a.K;
+    const int64_t p = a.p, ldm = a.ldm;
+    const int64_t fbeg = (int64_t)sl * fper, fend = (fbeg + fper < p) ? fbeg + fper : p;
+    const bool cval = q < K;
+    const T *mcol = (const T *)a.M + (cval ? q : K - 1);
+    int64_t si = rb * 16 + q;
+    if (si >= a.nrows) si = a.nrows - 1;              // rows beyond the sample: computed, never used
+    const T *xrow = X + (a.S ? (int64_t)a.S[si] : si) * a.ldx;
+    constexpr int STEP = 4 * VEC, UNR = 4;
+    v4 acc = v4{0, 0, 0, 0};
+    int64_t f0 = fbeg + (int64_t)wib * (STEP * UNR);
+    for (; f0 + STEP * UNR <= fend; f0 += (int64_t)nsw * (STEP * UNR)) {
+        pack xv[UNR];
+        T wv[UNR][VEC];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t f = f0 + u * STEP + VEC * g;
+            xv[u] = *(const pack *)(xrow + f);
+#pragma unroll
+            for (int m = 0; m < VEC; ++m) wv[u][m] = mcol[(f + m) * ldm];
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+#pragma unroll
+            for (int m = 0; m < VEC; ++m) acc = mfma16(xv[u].v[m], cval ? wv[u][m] : T(0), acc);
+    }
+    if (wib == 0) {                                   // the slice's last, incomplete group of features
+        for (f0 = fbeg + (fend - fbeg) / (STEP * UNR) * (STEP * UNR); f0 < fend; f0 += STEP) {
+            const int64_t f = f0 + VEC * g;
+#pragma unroll
+            for (int m = 0; m < VEC; ++m) {
+                const bool ok = (f + m) < fend;
+                const T w = (ok && cval) ? mcol[(f + m) * ldm] : T(0);
+                const T x = ok ? xrow[f + m] : T(0);
+                acc = mfma16(x, w, acc);
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) zs[(wib * 4 + v) * 64 + lane] = acc[v];
+    __syncthreads();
+    if (wib == 0) {
+        for (int ww = 1; ww < nsw; ++ww)              // fixed order
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[v] += zs[(ww * 4 + v) * 64 + lane];
+        T *zp = Zpart + ((int64_t)sl * zrows + rb * 16) * 16;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) zp[d_row<T>(g, v) * 16 + q] = acc[v];
+    }
+}
+
+hipError_t launch_dense_zpart(int dtype, const RowsArgs &a, void *Zpart, int nslices, int64_t fper, hipStream_t st)
+{
+    if (a.K > 16 || nslices < 1 || fper < 1) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)(((a.nrows + 15) / 16) * nslices);
+    if (dtype == SSN_F32) {
+        if (!vec_ok<float>(a.X, a.ldx) || fper % 64) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((dense_zpart_kernel<float, 4>), dim3(grid), dim3(512), 0, st, a, (float *)Zpart, nslices, fper);
+    } else {
+        if (!vec_ok<double>(a.X, a.ldx) || fper % 32) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((dense_zpart_kernel<double, 2>), dim3(grid), dim3(512), 0, st, a, (double *)Zpart, nslices, fper);
+    }
+    return hipGetLastError();
 }
 
 // Workgroups and waves per workgroup of the wave-per-row-block kernel: *split_waves == 0 is the plain
@@ -739,6 +868,11 @@ template <typename T> static hipError_t xtu_dispatch(const XtuArgs &a, hipStream
     const int nb = (a.K + 15) / 16;
     const bool v = vec_ok<T>(a.X, a.ldx);
     dim3 grid((unsigned)((a.p + 255) / 256), (unsigned)a.nchunks), block(256);
+    if (a.Zpart) {
+        if (!v || nb != 1 || !a.Pin || !a.zu_part || a.nslices < 1) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((dense_xtu_kernel<T, 1, VEC, true>), grid, block, 0, st, a);
+        return hipGetLastError();
+    }
     if constexpr (sizeof(T) == 4) {
         if (!v && nb == 1 && half_vec_ok(4, a.X, a.ldx)) {
             hipLaunchKernelGGL((dense_xtu_kernel<T, 1, 2>), grid, block, 0, st, a);

@@ -35,6 +35,10 @@ struct ssn_ctx {
     int max_chunks = 0;
     bool fused = false;           // dense: the one-pass kernel serves this shape
     bool binary = false;          // dense, K = 1: the matrix-vector kernels of dense_binary.hip serve every mode
+    // sampled product on few row blocks of a wide matrix (two-kernel path): the last ROW_APPLY launch left partial
+    // margins of z_slices feature slices in Ubuf instead of U, and the transposed product that follows forms U itself
+    bool z_active = false;
+    int z_slices = 0;
     // CSR: column-sorted views for the transposed products (whole matrix: built at the first gradient;
     // sample: rebuilt by every ssn_hess_prepare)
     CscView csc_full, csc_samp, csc_grad;      // csc_grad: the sample of the last sub-sampled gradient
@@ -212,8 +216,53 @@ hipError_t launch_xtu(const ssn_ctx *c, const XtuArgs &x)
     return c->binary ? launch_binary_xtu(c->d.dtype, x, c->st) : launch_dense_xtu(c->d.dtype, x, c->st);
 }
 
+// A product on a sample with fewer row blocks than twice the compute units, on a wide matrix of the two-kernel path:
+// the margins are computed per (row block, feature slice) so that every compute unit has work, and the transposed
+// product forms U from the slices' partial margins (dense_zpart_kernel, dense_xtu_kernel<FROMZ>).  Returns the number
+// of slices (0: the plain kernels serve) and the features per slice.
+int zpart_plan(const ssn_ctx *c, int64_t nrows, int64_t *fper)
+{
+    static const bool off = [] { const char *e = getenv("SSN_SAMPLED_SLICES"); return e && e[0] == '0'; }();
+    if (off || !is_dense(c) || c->fused || c->binary || c->K > 16 || c->d.p < 512) return 0;
+    if ((uintptr_t)c->d.X % 16 != 0 || (c->d.ldx * (int64_t)c->es) % 16 != 0) return 0;
+    const int64_t nblk = (nrows + 15) / 16;
+    if (nblk > (int64_t)c->num_cus * 2) return 0;
+    int64_t slices = ((int64_t)c->num_cus * 2) / nblk;
+    if (slices > c->d.p / 256) slices = c->d.p / 256;            // at least 256 features per slice
+    if (slices > 4) slices = 4;                                  // what the transposed-product kernel adds up
+    if (slices < 2) return 0;
+    const int64_t per = round_up((c->d.p + slices - 1) / slices, 64);
+    slices = (c->d.p + per - 1) / per;
+    if (slices < 2 || slices * round_up(nrows, 16) > c->U_rows) return 0;      // the partial margins live in the U buffer
+    *fper = per;
+    return (int)slices;
+}
+
+// the transposed product after a ROW_APPLY launch: U from the buffer, or formed from the slices' partial margins
+void xtu_after_apply(const ssn_ctx *c, XtuArgs *x)
+{
+    x->U = c->Ubuf;
+    if (!c->z_active) return;
+    x->Zpart = c->Ubuf;
+    x->nslices = c->z_slices;
+    x->zrows = round_up(x->nrows, 16);
+    x->Pin = c->Pbuf;
+    x->zu_part = c->loss_part;
+}
+
 int launch_rows(ssn_ctx *c, const RowsArgs &a, int *nparts)
 {
+    if (a.mode == ROW_APPLY) {
+        int64_t fper = 0;
+        const int slices = zpart_plan(c, a.nrows, &fper);
+        c->z_active = slices > 0;
+        c->z_slices = slices;
+        if (slices > 0) {
+            SSN_HIP(c, launch_dense_zpart(c->d.dtype, a, c->Ubuf, slices, fper, c->st));
+            if (nparts) *nparts = 0;         // the sums of z_i . u_i come from the transposed product: one per row chunk
+            return SSN_OK;
+        }
+    }
     if (c->binary) {
         const int blocks = binary_rows_blocks(a.nrows, c->num_cus);
         if (blocks * ROWS_WAVES_PER_BLOCK > c->wave_parts) return fail(c, SSN_E_INVALID_ARG, "internal: wave partial overflow");
@@ -315,8 +364,10 @@ int csc_view_for(ssn_ctx *c, const int32_t *S, const CscView **view)
 }
 
 // out = scale * X_rows^T U + lambda * M ; optionally partials of <out, M> into red_b (count in *ndot)
+// after_apply: the rows kernel before it was a ROW_APPLY launch (see xtu_after_apply)
 int transposed_product(ssn_ctx *c, const int32_t *S, int64_t nrows, double scale, const void *M, void *out,
-                       bool want_dot, int *ndot, const int32_t *skip, const CscView *view_in = nullptr)
+                       bool want_dot, int *ndot, const int32_t *skip, const CscView *view_in = nullptr,
+                       bool after_apply = false)
 {
     XtuArgs x = xtu_base(c);
     x.S = S;
@@ -325,6 +376,7 @@ int transposed_product(ssn_ctx *c, const int32_t *S, int64_t nrows, double scale
     x.skip = skip;
     if (is_dense(c)) {
         choose_chunks(c, nrows, &x.rows_per_chunk, &x.nchunks);
+        if (after_apply) xtu_after_apply(c, &x);
         SSN_HIP(c, launch_xtu(c, x));
         SSN_TRY(finalize_dense(c, x.nchunks, scale, M, out, want_dot, ndot, skip));
     } else {
@@ -486,7 +538,7 @@ int hess_apply_impl(ssn_ctx *c, const void *V, void *HV, bool want_dot, int *ndo
     int nparts = 0;
     SSN_TRY(launch_rows(c, a, &nparts));
     if (c->fused) return finalize_dense(c, nparts / 4, scale_sample(c), V, HV, want_dot, ndot, skip);
-    return transposed_product(c, c->S, c->nS, scale_sample(c), V, HV, want_dot, ndot, skip);
+    return transposed_product(c, c->S, c->nS, scale_sample(c), V, HV, want_dot, ndot, skip, nullptr, true);
 }
 
 // Product k of the CG loop with the vector updates of Alg. 2 behind it.  H s is never formed by a product of
@@ -534,11 +586,12 @@ int cg_product_step(ssn_ctx *c, const CgVecs &v, CgSlot *slots, int k, double th
             XtuArgs x = xtu_base(c);
             x.S = c->S;
             x.nrows = c->nS;
-            x.U = c->Ubuf;
             x.skip = skip;
             choose_chunks(c, c->nS, &x.rows_per_chunk, &x.nchunks);
+            xtu_after_apply(c, &x);
             SSN_HIP(c, launch_xtu(c, x));
             nchunks = x.nchunks;
+            if (c->z_active) nparts = nchunks;       // one sum of z_i . u_i per row chunk
         }
         FinArgs f{};
         f.part = c->part;
@@ -1582,6 +1635,7 @@ int ssn_time_kernel(ssn_ctx *c, int32_t which, const void *M, int32_t reps, doub
     x.nrows = nrows;
     x.U = c->Ubuf;
     if (is_dense(c)) choose_chunks(c, nrows, &x.rows_per_chunk, &x.nchunks);
+    if (which == 4 && is_dense(c) && !c->fused) xtu_after_apply(c, &x);      // as the last which = 3 launch left it
     if ((!is_dense(c) || c->fused) && (which == 2 || which == 4) && !c->trial) SSN_TRY(vec_bytes_alloc(c, &c->trial));
     const int fused_parts = c->fused ? dense_fused_grid(c->d.dtype, a, c->num_cus) : 0;
     hipEvent_t e0, e1;

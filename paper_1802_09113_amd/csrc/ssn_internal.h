@@ -74,6 +74,14 @@ struct XtuArgs {
     int64_t rows_per_chunk;
     int32_t nchunks;
     const int32_t *skip;
+    // Sampled product on few row blocks of a wide matrix: U is not read but formed here, eq. (12), from the partial
+    // margins of `nslices` feature slices (Zpart[s][row][16], zrows rows per slice) and the probabilities Pin (row
+    // stride KP); the chunk's sum of z_i . u_i goes to zu_part[chunk].  Zpart == nullptr: U is read.
+    const void *Zpart;
+    int32_t nslices;
+    int64_t zrows;
+    const void *Pin;
+    double *zu_part;
 };
 
 // out = scale * sum_chunks part + lambda * M ; optional per-block partials of <out, M>.
@@ -105,6 +113,9 @@ int finalize_blocks(int64_t p, int K);
 void dense_rows_plan(int dtype, int64_t nrows, int64_t p, int K, int num_cus, int *blocks, int *split_waves);
 hipError_t launch_dense_rows(int dtype, const RowsArgs &a, int blocks, int split_waves, hipStream_t st);
 hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st);
+// partial margins of feature slices: Zpart[s][row][16] = X_rows[:, slice s] * M[slice s, :] for `nslices` slices of
+// `fper` features (a multiple of 32), a workgroup of eight waves per (row block, slice); K <= 16, 16-byte aligned rows
+hipError_t launch_dense_zpart(int dtype, const RowsArgs &a, void *Zpart, int nslices, int64_t fper, hipStream_t st);
 bool dense_fused_supported(int dtype, const RowsArgs &a);
 int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus);
 int dense_fused_waves(int dtype, const RowsArgs &a);
