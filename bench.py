@@ -223,12 +223,20 @@ def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
     path = ctx.ssn_dense_path()
     out["dense_path"] = path
     kb = csr_kernel_bytes(n, p, K, nS, e, nnz, nnzS) if sparse else kernel_bytes(n, p, K, nS, e, path)
+    names = dict(KERNEL_NAMES[path])
     kern = {}
     for which in (0, 1, 2, 3, 4):
         reps = 20 if which < 3 else 200
         ctx.ssn_time_kernel(which, V[0] if which >= 3 else W, 3)
         ms = ctx.ssn_time_kernel(which, V[0] if which >= 3 else W, reps)
-        ent = {"kernel": KERNEL_NAMES[path][which], "ms": ms}
+        if which == 3 and ctx.ssn_sampled_slices() > 0:
+            # sampled product on a wide matrix: margins per (row block, feature slice), U formed by the second kernel
+            sl = ctx.ssn_sampled_slices()
+            out["sampled_slices"] = sl
+            names[3], names[4] = "dense_zpart_kernel (|S| rows)", "dense_xtu_kernel<from partial margins> (|S| rows)"
+            kb[3] = nS * p * e + 4 * nS + p * K * e + sl * nS * 16 * e
+            kb[4] = nS * p * e + sl * nS * 16 * e + nS * K * e
+        ent = {"kernel": names[which], "ms": ms}
         if kb[which] is not None:
             ent.update({"algorithmic_GB": kb[which] / 1e9, "GBps": kb[which] / ms / 1e6,
                         "frac": kb[which] / ms / 1e6 / HBM_PEAK_GBS})

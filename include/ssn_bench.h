@@ -33,6 +33,10 @@ int ssn_time_kernel(ssn_ctx *ctx, int32_t which, const void *M, int32_t reps, do
  * products on wide matrices (all three for measurements). */
 int ssn_dense_path(const ssn_ctx *ctx);
 
+/* Feature slices of the last sampled product's margins kernel on the two-kernel dense path (dense_zpart_kernel, with
+ * dense_xtu_kernel forming U from the slices' partial margins); 0: the plain kernels served it. */
+int ssn_sampled_slices(const ssn_ctx *ctx);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,7 +29,7 @@ EXPORTS = [
     "ssn_predict", "ssn_solve", "ssn_axpy", "ssn_normalize_columns", "ssn_objective_dev", "ssn_gradient_dev",
     "ssn_accuracy", "ssn_vec_to_rowmajor", "ssn_rowmajor_to_vec", "ssn_hessvec_static",
 ]
-BENCH_EXPORTS = ["ssn_time_kernel", "ssn_dense_path"]          # include/ssn_bench.h
+BENCH_EXPORTS = ["ssn_time_kernel", "ssn_dense_path", "ssn_sampled_slices"]          # include/ssn_bench.h
 
 
 class ssn_desc(ctypes.Structure):
@@ -102,6 +102,7 @@ def lib():
         L.ssn_axpy.argtypes = [vp, ctypes.c_double, vp, vp]
         L.ssn_time_kernel.argtypes = [vp, ctypes.c_int32, vp, ctypes.c_int32, dp]
         L.ssn_dense_path.argtypes = [vp]
+        L.ssn_sampled_slices.argtypes = [vp]
         L.ssn_normalize_columns.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_int64,
                                             vp, vp, vp, ctypes.c_int64, vp, vp]
         L.ssn_objective_dev.argtypes = [vp, vp, vp]
@@ -321,6 +322,9 @@ class Context:
 
     def ssn_dense_path(self):
         return lib().ssn_dense_path(self._h)
+
+    def ssn_sampled_slices(self):
+        return lib().ssn_sampled_slices(self._h)
 
     def ssn_time_kernel(self, which, M, reps):
         ms = ctypes.c_double()

@@ -1670,6 +1670,12 @@ int ssn_time_kernel(ssn_ctx *c, int32_t which, const void *M, int32_t reps, doub
     return SSN_OK;
 }
 
+int ssn_sampled_slices(const ssn_ctx *c)
+{
+    if (!c) return SSN_E_INVALID_ARG;
+    return c->z_active ? c->z_slices : 0;
+}
+
 int ssn_dense_path(const ssn_ctx *c)
 {
     if (!c) return SSN_E_INVALID_ARG;
