@@ -352,6 +352,39 @@ template <typename T> __global__ __launch_bounds__(256) void csc_piece_kernel(Cs
     T a0 = 0, a1 = 0, a2 = 0, a3 = 0;
     const int gbase = s * K;
     const int len = (int)(t1 - t0);
+    if (K < 4) {
+        // Groups this narrow would fetch one to three entries per round of the exchange below, a chain of index ->
+        // gather round trips per entry.  Every lane of the group reads the entries itself instead (the same
+        // addresses across the group), eight in flight.
+        for (int b = 0; b < len; b += 8) {
+            int r[8];
+            T v[8], u[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const bool have = b + k < len;
+                r[k] = have ? a.row[t0 + b + k] : -1;
+                v[k] = have ? val[t0 + b + k] : T(0);
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) u[k] = (r[k] >= 0) ? U[(int64_t)r[k] * a.KP + c] : T(0);
+            a0 += v[0] * u[0];
+            a1 += v[1] * u[1];
+            a2 += v[2] * u[2];
+            a3 += v[3] * u[3];
+            a0 += v[4] * u[4];
+            a1 += v[5] * u[5];
+            a2 += v[6] * u[6];
+            a3 += v[7] * u[7];
+        }
+        if (!active) return;
+        const T accn = (a0 + a1) + (a2 + a3);
+        if (head && !more) {
+            *o = (T)((double)oval + coef * (double)accn);
+        } else {
+            ((T *)a.piece_part)[pid * K + c] = accn;
+        }
+        return;
+    }
     int maxlen = len;
     for (int off = 32; off > 0; off >>= 1) maxlen = max(maxlen, __shfl_xor(maxlen, off));
     for (int b = 0; b < maxlen; b += K) {

@@ -68,11 +68,14 @@ __device__ __forceinline__ T csr_row_margin(const RowsArgs &a, int64_t row, int 
         for (int u = 1; u < U; ++u) av[0] += av[u];
         acc = av[0];
     }
-    // fold the NS slots onto slot 0
+    // fold the NS slots onto slot 0: a tree over the slots (log2 NS steps in a fixed order; with one weight column a
+    // wave holds 64 slots, and adding them one after the other was most of a short row's time)
+    int top = 1;
+    while (top < NS) top <<= 1;
     T tot = acc;
-    for (int k = 1; k < NS; ++k) {
-        const T o = __shfl(acc, (lane + k * K) & 63);
-        tot += o;
+    for (int h = top >> 1; h >= 1; h >>= 1) {
+        const T o = __shfl(tot, (lane + h * K) & 63);
+        if (s + h < NS) tot += o;
     }
     return (lane < K) ? tot : T(0);
 }
