@@ -287,7 +287,7 @@ hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t
     CSC_HIP(hipMemcpyAsync(counts, v->count_dev, (support ? 2 : 1) * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     CSC_HIP(hipStreamSynchronize(st));
     const int32_t np = counts[0];
-    CSC_HIP(grow(&v->piece_part, &v->cap_part, (int64_t)np * K, es));
+    CSC_HIP(grow(&v->piece_part, &v->cap_part, (int64_t)np * K * 2, es));       // piece sums, then run sums
     if (support) {
         CSC_HIP(grow((void **)&v->piece_cpos, &v->cap_pcpos, (int64_t)np + 4, sizeof(int32_t)));
         hipLaunchKernelGGL(csc_piece_cpos_kernel, dim3(grid_for((int64_t)np + 4)), dim3(VEC_BLOCK), 0, st, v->piece_start,
@@ -298,6 +298,7 @@ hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t
     CSC_HIP(hipGetLastError());
     v->nnz = nnz;
     v->npieces = np;
+    v->nrows = nrows;
     return hipSuccess;
 }
 
@@ -314,6 +315,8 @@ struct CscApply {
     double coef;
     const CgSlot *slot;      // nullable: coef *= -slot->alpha; nothing happens once that CG loop has ended
     void *piece_part;
+    void *run_part;          // sums of runs of pieces (grouped combine), laid out like piece_part
+    int32_t look;            // pieces a wave of the run / combine kernels looks at (a power of two, 4..64)
     const int32_t *skip;
 };
 // (piece_col may be the pieces' columns or their positions among the distinct columns: equal columns have
@@ -385,6 +388,29 @@ template <typename T> __global__ __launch_bounds__(256) void csc_piece_kernel(Cs
         }
         return;
     }
+    // Waves whose pieces all have at most four entries -- most of them, on text-like data, where most columns
+    // appear in a handful of the selected rows -- take them without the exchange: every lane of the group reads
+    // the (up to four) entries itself, all at once, and the gathers follow.
+    if (!__any(len > 4)) {
+        int r[4];
+        T v[4], u[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const bool have = k < len;
+            r[k] = have ? a.row[t0 + k] : -1;
+            v[k] = have ? val[t0 + k] : T(0);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) u[k] = (r[k] >= 0) ? U[(int64_t)r[k] * a.KP + c] : T(0);
+        if (!active) return;
+        const T accs = (v[0] * u[0] + v[1] * u[1]) + (v[2] * u[2] + v[3] * u[3]);
+        if (head && !more) {
+            *o = (T)((double)oval + coef * (double)accs);
+        } else {
+            ((T *)a.piece_part)[pid * K + c] = accs;
+        }
+        return;
+    }
     int maxlen = len;
     for (int off = 32; off > 0; off >>= 1) maxlen = max(maxlen, __shfl_xor(maxlen, off));
     for (int b = 0; b < maxlen; b += K) {
@@ -420,8 +446,70 @@ template <typename T> __global__ __launch_bounds__(256) void csc_piece_kernel(Cs
     }
 }
 
-// columns of several pieces: the group of the column's first piece adds the partial sums in piece order
-template <typename T> __global__ __launch_bounds__(256) void csc_combine_kernel(CscApply a)
+// Columns of several pieces: a lane group adds the column's partial sums in piece order and adds the result into
+// the output.  Most pieces are whole columns with nothing to combine, so a wave first looks at up to 64 pieces, one
+// per lane, and its lane groups then take the pieces that have work, NS at a time (a group per piece from the start
+// was twenty times the waves, nearly all of which looked at three numbers and left).
+// GROUPED: the pieces of a column are first added in runs that end at every CSC_RUN-th piece (csc_run_kernel, any
+// number of runs at a time), and the first piece's group adds the runs: a column present in most of 20 000 rows has
+// some 300 pieces, and adding them one after the other is a chain of 80 round trips to memory.
+constexpr int CSC_RUN = 16;
+
+// the lane (0..63) whose piece group s of the wave takes next, or -1; *mask loses the NS lowest set bits
+__device__ __forceinline__ int csc_take(unsigned long long *mask, int s, int NS)
+{
+    unsigned long long m = *mask;
+    int mine = -1;
+    for (int i = 0; i < NS && m; ++i) {
+        if (i == s) mine = __ffsll((long long)m) - 1;
+        m &= m - 1;
+    }
+    *mask = m;
+    return mine;
+}
+
+template <typename T> __global__ __launch_bounds__(256) void csc_run_kernel(CscApply a)
+{
+    if (a.skip && *a.skip) return;
+    if (a.slot && (a.slot->done || a.slot->brk)) return;
+    const int lane = threadIdx.x & 63;
+    const int K = a.K, NS = 64 / K;
+    const int s = lane / K, c = lane - s * K;
+    const int64_t base = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * a.look;
+    bool starts = false;                       // a run starts at a column's first piece and at every CSC_RUN-th
+    {                                          // piece; whole columns have none
+        const int64_t pid = base + lane;
+        if (lane < a.look && pid < a.npieces) {
+            const int col = a.piece_col[pid];
+            const bool head = (pid == 0) || (a.piece_col[pid - 1] != col);
+            starts = head ? (a.piece_col[pid + 1] == col) : (pid % CSC_RUN == 0);
+        }
+    }
+    unsigned long long mask = __ballot(starts);
+    const T *pp = (const T *)a.piece_part;
+    while (mask) {
+        const int mine = csc_take(&mask, s, NS);
+        if (s >= NS || mine < 0) continue;
+        const int64_t pid = base + mine;
+        const int col = a.piece_col[pid];
+        T acc = pp[pid * K + c];
+        for (int64_t j = pid + 1; j % CSC_RUN != 0; j += 4) {      // four pieces per round; the adds keep the order
+            const bool m0 = a.piece_col[j] == col, m1 = m0 && (j + 1) % CSC_RUN != 0 && a.piece_col[j + 1] == col;
+            const bool m2 = m1 && (j + 2) % CSC_RUN != 0 && a.piece_col[j + 2] == col;
+            const bool m3 = m2 && (j + 3) % CSC_RUN != 0 && a.piece_col[j + 3] == col;
+            const T p0 = m0 ? pp[j * K + c] : T(0), p1 = m1 ? pp[(j + 1) * K + c] : T(0);
+            const T p2 = m2 ? pp[(j + 2) * K + c] : T(0), p3 = m3 ? pp[(j + 3) * K + c] : T(0);
+            acc += p0;
+            acc += p1;
+            acc += p2;
+            acc += p3;
+            if (!m3 || (j + 4) % CSC_RUN == 0) break;
+        }
+        ((T *)a.run_part)[pid * K + c] = acc;
+    }
+}
+
+template <typename T, bool GROUPED> __global__ __launch_bounds__(256) void csc_combine_kernel(CscApply a)
 {
     if (a.skip && *a.skip) return;
     double coef = a.coef;
@@ -432,28 +520,58 @@ template <typename T> __global__ __launch_bounds__(256) void csc_combine_kernel(
     const int lane = threadIdx.x & 63;
     const int K = a.K, NS = 64 / K;
     const int s = lane / K, c = lane - s * K;
-    if (s >= NS) return;
-    const int64_t pid = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * NS + s;
-    if (pid >= a.npieces) return;
-    const int col = a.piece_col[pid];
-    const bool head = (pid == 0) || (a.piece_col[pid - 1] != col);
-    if (!head || a.piece_col[pid + 1] != col) return;
-    const T *pp = (const T *)a.piece_part;
-    T *o = (T *)a.out + (int64_t)col * a.ldo + c;
-    const T oval = *o;                       // fetched before the partial sums, not after them
-    T acc = pp[pid * K + c];
-    for (int64_t j = pid + 1;; j += 4) {     // four pieces per round; the adds keep the piece order
-        const bool m0 = a.piece_col[j] == col, m1 = m0 && a.piece_col[j + 1] == col;
-        const bool m2 = m1 && a.piece_col[j + 2] == col, m3 = m2 && a.piece_col[j + 3] == col;
-        const T p0 = m0 ? pp[j * K + c] : T(0), p1 = m1 ? pp[(j + 1) * K + c] : T(0);
-        const T p2 = m2 ? pp[(j + 2) * K + c] : T(0), p3 = m3 ? pp[(j + 3) * K + c] : T(0);
-        acc += p0;
-        acc += p1;
-        acc += p2;
-        acc += p3;
-        if (!m3) break;
+    const int64_t base = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * a.look;
+    bool first = false;                        // first piece of a column of several
+    {
+        const int64_t pid = base + lane;
+        if (lane < a.look && pid < a.npieces) {
+            const int col = a.piece_col[pid];
+            const bool head = (pid == 0) || (a.piece_col[pid - 1] != col);
+            first = head && a.piece_col[pid + 1] == col;
+        }
     }
-    *o = (T)((double)oval + coef * (double)acc);
+    unsigned long long mask = __ballot(first);
+    while (mask) {
+        const int mine = csc_take(&mask, s, NS);
+        if (s >= NS || mine < 0) continue;
+        const int64_t pid = base + mine;
+        const int col = a.piece_col[pid];
+        T *o = (T *)a.out + (int64_t)col * a.ldo + c;
+        const T oval = *o;                       // fetched before the partial sums, not after them
+        T acc;
+        if constexpr (GROUPED) {
+            const T *rp = (const T *)a.run_part;
+            acc = rp[pid * K + c];
+            const int64_t np = a.npieces;
+            for (int64_t j = (pid / CSC_RUN + 1) * CSC_RUN;; j += 4 * CSC_RUN) {     // four runs per round, in order
+                const int64_t j1 = j + CSC_RUN, j2 = j + 2 * CSC_RUN, j3 = j + 3 * CSC_RUN;
+                const bool m0 = j < np && a.piece_col[j] == col, m1 = m0 && j1 < np && a.piece_col[j1] == col;
+                const bool m2 = m1 && j2 < np && a.piece_col[j2] == col, m3 = m2 && j3 < np && a.piece_col[j3] == col;
+                const T p0 = m0 ? rp[j * K + c] : T(0), p1 = m1 ? rp[j1 * K + c] : T(0);
+                const T p2 = m2 ? rp[j2 * K + c] : T(0), p3 = m3 ? rp[j3 * K + c] : T(0);
+                acc += p0;
+                acc += p1;
+                acc += p2;
+                acc += p3;
+                if (!m3) break;
+            }
+        } else {
+            const T *pp = (const T *)a.piece_part;
+            acc = pp[pid * K + c];
+            for (int64_t j = pid + 1;; j += 4) {     // four pieces per round; the adds keep the piece order
+                const bool m0 = a.piece_col[j] == col, m1 = m0 && a.piece_col[j + 1] == col;
+                const bool m2 = m1 && a.piece_col[j + 2] == col, m3 = m2 && a.piece_col[j + 3] == col;
+                const T p0 = m0 ? pp[j * K + c] : T(0), p1 = m1 ? pp[(j + 1) * K + c] : T(0);
+                const T p2 = m2 ? pp[(j + 2) * K + c] : T(0), p3 = m3 ? pp[(j + 3) * K + c] : T(0);
+                acc += p0;
+                acc += p1;
+                acc += p2;
+                acc += p3;
+                if (!m3) break;
+            }
+        }
+        *o = (T)((double)oval + coef * (double)acc);
+    }
 }
 
 // out += coef * X_view^T U  (out already holds whatever the product is added to: lambda * M, or the CG
@@ -478,16 +596,37 @@ hipError_t launch_csc_apply(int dtype, const CscView &v, int K, int KP, const vo
     a.coef = coef;
     a.slot = slot;
     a.piece_part = v.piece_part;
+    const size_t es = dtype == SSN_F32 ? 4 : 8;
+    a.run_part = (char *)v.piece_part + (size_t)v.npieces * K * es;
     a.skip = skip;
     const int NS = 64 / K;
     const int64_t waves = ((int64_t)v.npieces + NS - 1) / NS;
     const unsigned blocks = (unsigned)((waves + 3) / 4);
+    // a column has at most one entry per selected row: views of few rows have short columns everywhere, and the
+    // run kernel would only add a launch to each of their products
+    const bool grouped = v.nrows > (int64_t)PIECE_LEN * 2 * CSC_RUN;
+    // a wave of the run / combine kernels looks at `look` pieces: 64 on large views; fewer on small ones, whose
+    // pieces with work would otherwise queue up in too few waves
+    int look = 64;
+    while (look > 4 && (int64_t)v.npieces / look < 8192) look >>= 1;
+    a.look = look;
+    const unsigned cblocks = (unsigned)((((int64_t)v.npieces + look - 1) / look + 3) / 4);
     if (dtype == SSN_F32) {
         hipLaunchKernelGGL(csc_piece_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
-        hipLaunchKernelGGL(csc_combine_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
+        if (grouped) {
+            hipLaunchKernelGGL(csc_run_kernel<float>, dim3(cblocks), dim3(256), 0, st, a);
+            hipLaunchKernelGGL((csc_combine_kernel<float, true>), dim3(cblocks), dim3(256), 0, st, a);
+        } else {
+            hipLaunchKernelGGL((csc_combine_kernel<float, false>), dim3(cblocks), dim3(256), 0, st, a);
+        }
     } else {
         hipLaunchKernelGGL(csc_piece_kernel<double>, dim3(blocks), dim3(256), 0, st, a);
-        hipLaunchKernelGGL(csc_combine_kernel<double>, dim3(blocks), dim3(256), 0, st, a);
+        if (grouped) {
+            hipLaunchKernelGGL(csc_run_kernel<double>, dim3(cblocks), dim3(256), 0, st, a);
+            hipLaunchKernelGGL((csc_combine_kernel<double, true>), dim3(cblocks), dim3(256), 0, st, a);
+        } else {
+            hipLaunchKernelGGL((csc_combine_kernel<double, false>), dim3(cblocks), dim3(256), 0, st, a);
+        }
     }
     return hipGetLastError();
 }

@@ -188,7 +188,8 @@ struct CscView {
     void *val = nullptr;
     int32_t *piece_start = nullptr;  // npieces + 1
     int32_t *piece_col = nullptr;    // npieces + 4 (sentinels -1)
-    void *piece_part = nullptr;      // npieces x K partial sums of the pieces of multi-piece columns
+    int64_t nrows = 0;               // rows selected
+    void *piece_part = nullptr;      // 2 x npieces x K: partial sums of the pieces of multi-piece columns, then of runs of them
     // construction scratch (kept by the sample view, which is rebuilt at every ssn_hess_prepare)
     int32_t *off = nullptr, *key_in = nullptr, *idx_in = nullptr, *idx_out = nullptr, *row_in = nullptr;
     void *val_in = nullptr;
