@@ -63,7 +63,20 @@ __device__ __forceinline__ T csr_row_margin(const RowsArgs &a, int64_t row, int 
 #pragma unroll
             for (int u = 0; u < U; ++u) av[u] += vv[u] * mm[u];
         }
-        for (; t < e; t += NS) av[0] += vals[t] * M[(int64_t)a.colidx[t] * a.ldm + c];
+        if (t + NS < e) {          // two or more entries left for this lane: the same round with lanes switched off
+            int64_t cc[U];
+            T vv[U], mm[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) cc[u] = (t + u * NS < e) ? (int64_t)a.colidx[t + u * NS] : (int64_t)-1;
+#pragma unroll
+            for (int u = 0; u < U; ++u) vv[u] = (t + u * NS < e) ? vals[t + u * NS] : T(0);
+#pragma unroll
+            for (int u = 0; u < U; ++u) mm[u] = (cc[u] >= 0) ? M[cc[u] * a.ldm + c] : T(0);
+#pragma unroll
+            for (int u = 0; u < U; ++u) av[u] += vv[u] * mm[u];
+        } else if (t < e) {
+            av[0] += vals[t] * M[(int64_t)a.colidx[t] * a.ldm + c];
+        }
 #pragma unroll
         for (int u = 1; u < U; ++u) av[0] += av[u];
         acc = av[0];
