@@ -108,7 +108,7 @@ def call_bytes(n, p, K, nS, e, nnz=None, nnzS=None):
 
 
 KERNEL_NAMES = {
-    0: {0: "csr_rows_kernel<OBJ>", 1: "csr_rows_kernel<GRAD>", 2: "csc_piece_kernel + csc_combine_kernel (n rows)",
+    0: {0: "csr_rows_kernel<OBJ>", 1: "csr_rows_kernel<GRAD>", 2: "csc_piece_kernel + csc_run_kernel + csc_combine_kernel (n rows)",
         3: "csr_rows_kernel<APPLY>", 4: "csc_piece_kernel + csc_combine_kernel (|S| rows)"},
     1: {0: "dense_rows_kernel<OBJ>", 1: "dense_rows_kernel<GRAD>", 2: "dense_xtu_kernel (n rows)",
         3: "dense_rows_kernel<APPLY>", 4: "dense_xtu_kernel (|S| rows)"},
