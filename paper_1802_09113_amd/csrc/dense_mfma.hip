@@ -732,20 +732,38 @@ __global__ __launch_bounds__(512) void dense_zpart_kernel(RowsArgs a, T *Zpart, 
     constexpr int STEP = 4 * VEC, UNR = 4;
     v4 acc = v4{0, 0, 0, 0};
     int64_t f0 = fbeg + (int64_t)wib * (STEP * UNR);
-    for (; f0 + STEP * UNR <= fend; f0 += (int64_t)nsw * (STEP * UNR)) {
-        pack xv[UNR];
-        T wv[UNR][VEC];
+    // the loads of the wave's next feature group are issued before the matrix instructions of the current one: a
+    // wave has only a handful of groups, and waiting out a trip to memory between each two was most of its time
+    auto fetch = [&](int64_t at, pack (&xv)[UNR], T (&wv)[UNR][VEC]) {
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            const int64_t f = f0 + u * STEP + VEC * g;
+            const int64_t f = at + u * STEP + VEC * g;
             xv[u] = *(const pack *)(xrow + f);
 #pragma unroll
             for (int m = 0; m < VEC; ++m) wv[u][m] = mcol[(f + m) * ldm];
         }
+    };
+    auto multiply = [&](const pack (&xv)[UNR], const T (&wv)[UNR][VEC]) {
 #pragma unroll
         for (int u = 0; u < UNR; ++u)
 #pragma unroll
             for (int m = 0; m < VEC; ++m) acc = mfma16(xv[u].v[m], cval ? wv[u][m] : T(0), acc);
+    };
+    const int64_t stride = (int64_t)nsw * (STEP * UNR);
+    pack xa[UNR], xb[UNR];
+    T wa[UNR][VEC], wb[UNR][VEC];
+    bool have = f0 + STEP * UNR <= fend;
+    if (have) fetch(f0, xa, wa);
+    while (have) {
+        const bool more = f0 + stride + STEP * UNR <= fend;
+        if (more) fetch(f0 + stride, xb, wb);
+        multiply(xa, wa);
+        if (!more) break;
+        const bool again = f0 + 2 * stride + STEP * UNR <= fend;
+        if (again) fetch(f0 + 2 * stride, xa, wa);
+        multiply(xb, wb);
+        have = again;
+        f0 += 2 * stride;
     }
     if (wib == 0) {                                   // the slice's last, incomplete group of features
         for (f0 = fbeg + (fend - fbeg) / (STEP * UNR) * (STEP * UNR); f0 < fend; f0 += STEP) {
