@@ -1516,6 +1516,9 @@ int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus)
     // single-wave workgroups without a transposed product fit three to a SIMD (at most 150 registers), and a
     // streaming pass over a narrow matrix wants them all
     if (nw == 1 && !has_c) per_cu = 12;
+    // with a transposed product: three fp32 waves to a SIMD still help (581012 x 54 gradient 53 -> 49 us); in fp64 two
+    // are the best (75 us against 80 with three)
+    if (nw == 1 && has_c && dtype == SSN_F32) per_cu = 12;
     // never more workgroups than stay resident together: the rest would start when the first ones end, as a
     // second, thinly occupied round
     const size_t lds = (dtype == SSN_F32) ? fused_grid_lds<float>(a.p, a.K, has_c) : fused_grid_lds<double>(a.p, a.K, has_c);
