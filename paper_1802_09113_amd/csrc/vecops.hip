@@ -890,16 +890,24 @@ hipError_t launch_sum_int(const int32_t *a, int na, int32_t *out, hipStream_t st
 }
 
 // ---- plain streaming read of a buffer: the practical HBM ceiling next to which the kernels are judged ----
+// Every workgroup walks a contiguous share of the buffer, eight 4 KB tiles per trip.  (Workgroups that stride over the
+// whole buffer together, four loads 8 MB apart per thread, read 1.23 GB at 5.3 TB/s; this form reads it at 6.7 TB/s.)
 __global__ __launch_bounds__(VEC_BLOCK) void stream_read_kernel(const uint4 *src, int64_t nvec, double *part)
 {
+    constexpr int U = 8;
     unsigned acc = 0;
-    const int64_t stride = (int64_t)gridDim.x * VEC_BLOCK;
-    int64_t i = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x;
-    for (; i + 3 * stride < nvec; i += 4 * stride) {
-        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        acc += (a.x ^ a.y ^ a.z ^ a.w) + (b.x ^ b.y ^ b.z ^ b.w) + (c.x ^ c.y ^ c.z ^ c.w) + (d.x ^ d.y ^ d.z ^ d.w);
+    const int64_t per = (nvec / gridDim.x) / (VEC_BLOCK * U) * (VEC_BLOCK * U);
+    const uint4 *p = src + (int64_t)blockIdx.x * per + threadIdx.x;
+    for (int64_t i = 0; i < per; i += VEC_BLOCK * U) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = p[i + u * VEC_BLOCK];
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
-    for (; i < nvec; i += stride) {
+    // what the equal shares leave over
+    for (int64_t i = (int64_t)gridDim.x * per + (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; i < nvec;
+         i += (int64_t)gridDim.x * VEC_BLOCK) {
         const uint4 a = src[i];
         acc += a.x ^ a.y ^ a.z ^ a.w;
     }
