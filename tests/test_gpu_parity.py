@@ -428,3 +428,44 @@ def test_csr_with_more_than_32_weight_columns(C, dtype):
     _, acc = pair.gpu.ssn_predict(Wd, want_pred=False)
     assert abs(acc - pair.oracle.accuracy(Wh)) <= (0.0 if dtype == F64 else 2e-3)
     pair.close()
+
+
+@pytest.mark.parametrize("C", [2, 4, 20], ids=["K1", "K3", "K19"])
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_csr_columns_at_the_piece_and_run_boundaries_of_the_transposed_product(C, dtype):
+    """The transposed product cuts every column into pieces of 64 entries and, on views of more than 2048 rows, adds
+    the pieces of a column in runs that end at every 16th piece: columns of exactly 64 / 65, 1023 / 1024 / 1025 and
+    2048 entries, one present in every row, and cheap ones in between so that the long columns start at different
+    places of the piece list.  Gradient over all rows (runs) and a product on a sample of 1500 rows (no runs)."""
+    g = np.random.default_rng(77 + C)
+    n, p = 4100, 40
+    counts = {0: n, 3: 64, 4: 65, 7: 1023, 8: 1024, 9: 1025, 15: 2048, 16: 1, 21: 130, 22: 2049, 30: 63, 39: 1040}
+    member = np.zeros((n, p), dtype=bool)
+    for j in range(p):
+        k = counts.get(j, int(g.integers(1, 40)))
+        member[g.choice(n, size=k, replace=False), j] = True
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    cols, vals = [], []
+    for i in range(n):
+        nz = np.nonzero(member[i])[0]
+        cols.append(nz)
+        vals.append(g.standard_normal(nz.size))
+        rowptr[i + 1] = rowptr[i] + nz.size
+    d = dict(layout="csr", rowptr=rowptr, colidx=np.concatenate(cols).astype(np.int32), vals=np.concatenate(vals),
+             labels=g.integers(0, C, size=n).astype(np.int32), C=C, p=p, n=n, lam=1e-3)
+    print(f"[case] csr run boundaries C={C} dtype={dtype}", flush=True)
+    pair = Pair(d, dtype)
+    Wh, Wd = pair.block(0.3 * g.standard_normal((p, C - 1)))
+    Vh, Vd = pair.block(g.standard_normal((p, C - 1)))
+    S = np.sort(g.choice(n, size=1500, replace=False)).astype(np.int32)
+    G, f = pair.gpu.ssn_gradient(Wd)
+    HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+    HVall = pair.gpu.ssn_hessvec(Wd, pair.idx(np.arange(n, dtype=np.int32)), Vd)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    Go, fo = pair.oracle.gradient(Wh)
+    assert rel_scalar(f, fo) <= tol
+    assert rel_err(pair.host(G), Go) <= tol
+    assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
+    assert rel_err(pair.host(HVall), pair.oracle.hessvec(Wh, np.arange(n, dtype=np.int32), Vh)) <= tol
+    pair.close()
