@@ -469,3 +469,39 @@ def test_csr_columns_at_the_piece_and_run_boundaries_of_the_transposed_product(C
     assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
     assert rel_err(pair.host(HVall), pair.oracle.hessvec(Wh, np.arange(n, dtype=np.int32), Vh)) <= tol
     pair.close()
+
+
+@pytest.mark.parametrize("C", [2, 4, 20, 41], ids=["K1", "K3", "K19", "K40"])
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_csr_row_lengths_around_the_rounds_of_the_rows_kernel(C, dtype):
+    """A wave of the CSR rows kernel takes 64 / K stored entries per step and eight steps per round, the last round
+    with lanes switched off: rows whose lengths sit at and next to the multiples of a step and of a round for
+    K = 1, 3, 19 and 40 (64, 21, 3 and 1 entries per step), empty rows included."""
+    g = np.random.default_rng(310 + C)
+    p = 1300
+    lengths = [0, 1, 2, 3, 4, 7, 8, 9, 20, 21, 22, 23, 24, 25, 26, 47, 48, 49, 63, 64, 65, 127, 128, 129, 167, 168, 169, 170,
+               335, 336, 337, 511, 512, 513, 514, 575, 576, 577, 1023, 1024, 1025, 1300, 0, 5]
+    n = len(lengths)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    cols, vals = [], []
+    for i, L in enumerate(lengths):
+        nz = np.sort(g.choice(p, size=L, replace=False))
+        cols.append(nz)
+        vals.append(g.standard_normal(L))
+        rowptr[i + 1] = rowptr[i] + L
+    d = dict(layout="csr", rowptr=rowptr, colidx=np.concatenate(cols).astype(np.int32), vals=np.concatenate(vals),
+             labels=g.integers(0, C, size=n).astype(np.int32), C=C, p=p, n=n, lam=1e-3)
+    print(f"[case] csr row lengths C={C} dtype={dtype}", flush=True)
+    pair = Pair(d, dtype)
+    Wh, Wd = pair.block(0.1 * g.standard_normal((p, C - 1)))
+    Vh, Vd = pair.block(g.standard_normal((p, C - 1)))
+    S = np.arange(n, dtype=np.int32)
+    f = pair.gpu.ssn_objective(Wd)
+    G, _ = pair.gpu.ssn_gradient(Wd)
+    HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert rel_scalar(f, pair.oracle.objective(Wh)) <= tol
+    assert rel_err(pair.host(G), pair.oracle.gradient(Wh)[0]) <= tol
+    assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
+    pair.close()
