@@ -505,3 +505,30 @@ def test_csr_row_lengths_around_the_rounds_of_the_rows_kernel(C, dtype):
     assert rel_err(pair.host(G), pair.oracle.gradient(Wh)[0]) <= tol
     assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
     pair.close()
+
+
+@pytest.mark.parametrize("p,C", [(1040, 10), (1536, 17), (2084, 10), (3080, 5)], ids=["p1040", "p1536-K16", "p2084", "p3080"])
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_sampled_product_on_feature_slices(p, C, dtype):
+    """Samples of few row blocks of a wide matrix: the margins are computed per (row block, feature slice) by waves
+    that keep the loads of their next feature group in flight, and the transposed product adds the slices up.
+    Widths that leave a wave with no, one, two or three feature groups and an incomplete last one; samples of one
+    row, of a ragged last block, and of enough blocks that only two slices are taken."""
+    g = np.random.default_rng(p + C)
+    n = 2600
+    X = g.standard_normal((n, p)) * (g.random((n, p)) < 0.5)
+    d = dict(layout="dense", X=X, labels=g.integers(0, C, size=n).astype(np.int32), C=C, p=p, n=n, lam=1e-3)
+    pair = Pair(d, dtype)
+    Wh, Wd = pair.block(0.05 * g.standard_normal((p, C - 1)))
+    Vh, Vd = pair.block(g.standard_normal((p, C - 1)))
+    tol = TOL[dtype]
+    seen = set()
+    for nS in (1, 17, 500, 1001, 2600):
+        S = np.sort(g.choice(n, size=nS, replace=False)).astype(np.int32)
+        print(f"[case] sliced sampled product p={p} C={C} nS={nS} dtype={dtype}", flush=True)
+        HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+        torch.cuda.synchronize()
+        seen.add(pair.gpu.ssn_sampled_slices())
+        assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
+    assert max(seen) >= 2, "the sliced path did not run"
+    pair.close()
