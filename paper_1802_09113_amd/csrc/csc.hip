@@ -158,7 +158,8 @@ static hipError_t grow(void **ptr, int64_t *cap, int64_t need, size_t elem)
 void csc_free(CscView *v)
 {
     void *all[] = {v->key, v->row, v->val, v->piece_start, v->piece_col, v->piece_part, v->off, v->key_in, v->idx_in, v->idx_out,
-                   v->row_in, v->val_in, v->flag, v->pid, v->cub_tmp, v->count_dev, v->cols, v->ccol, v->piece_cpos};
+                   v->row_in, v->val_in, v->flag, v->pid, v->cub_tmp, v->count_dev, v->cols, v->ccol, v->piece_cpos,
+                   v->cnt, v->head, v->next, v->tsum, v->toff, v->ftoff, v->len, v->bitmap, v->eidx, v->csr_pos};
     for (void *q : all)
         if (q) (void)hipFree(q);
     *v = CscView{};
@@ -171,7 +172,7 @@ void csc_free_scratch(CscView *v)
         if (q) (void)hipFree(q);
     v->key_in = v->idx_in = v->idx_out = v->row_in = v->flag = v->pid = nullptr;
     v->val_in = v->cub_tmp = nullptr;
-    v->cap_in = v->cap_flag = v->cap_pid = 0;
+    v->cap_in = v->cap_flag = v->cap_pid = v->cap_valin = 0;
     v->cub_bytes = 0;
 }
 
@@ -188,7 +189,7 @@ hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t
     v->npieces = 0;
     v->ncols = 0;
     v->has_support = false;
-    if (!v->count_dev) CSC_HIP(hipMalloc((void **)&v->count_dev, 2 * sizeof(int32_t)));
+    if (!v->count_dev) CSC_HIP(hipMalloc((void **)&v->count_dev, 4 * sizeof(int32_t)));
 
     auto cub_need = [&](size_t bytes) -> hipError_t {
         if (bytes <= v->cub_bytes) return hipSuccess;
@@ -225,13 +226,14 @@ hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t
     CSC_HIP(grow((void **)&v->row, &v->cap_row, nnz, sizeof(int32_t)));
     CSC_HIP(grow(&v->val, &v->cap_val, nnz, es));
     {
-        int64_t c0 = v->cap_in, c1 = v->cap_in, c2 = v->cap_in, c3 = v->cap_in, c4 = v->cap_in;
+        int64_t c0 = v->cap_in, c1 = v->cap_in, c2 = v->cap_in, c3 = v->cap_in, c4 = v->cap_valin;
         CSC_HIP(grow((void **)&v->key_in, &c0, nnz, sizeof(int32_t)));
         CSC_HIP(grow((void **)&v->idx_in, &c1, nnz, sizeof(int32_t)));
         CSC_HIP(grow((void **)&v->idx_out, &c2, nnz, sizeof(int32_t)));
         CSC_HIP(grow((void **)&v->row_in, &c3, nnz, sizeof(int32_t)));
         CSC_HIP(grow(&v->val_in, &c4, nnz, es));
         v->cap_in = c0;
+        v->cap_valin = c4;
     }
     CSC_HIP(grow((void **)&v->flag, &v->cap_flag, nnz, sizeof(int32_t)));
     CSC_HIP(grow((void **)&v->pid, &v->cap_pid, nnz, sizeof(int32_t)));
@@ -299,6 +301,523 @@ hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t
     v->nnz = nnz;
     v->npieces = np;
     v->nrows = nrows;
+    return hipSuccess;
+}
+
+// ---- the view of a sample, filtered out of the whole matrix's view -------------------------------------
+// The whole matrix's entries are already sorted by (column, row).  A sample's view is the sub-list of the entries
+// whose row is sampled (an entry of a row sampled m times appears m times), in the same order: no sort, one
+// counting pass and one copying pass over the whole view's row indices (4 bytes per stored entry) and prefix sums
+// written here.  Equal rows of a sample have equal rows of U, so the order of their entries inside a column does
+// not change any sum.
+
+constexpr int SCAN_ITEMS = 8;
+constexpr int SCAN_TILE = VEC_BLOCK * SCAN_ITEMS;
+
+// exclusive prefix sum of the calling block's VEC_BLOCK values; *total receives their sum
+__device__ __forceinline__ int block_exclusive_scan(int x, int *total)
+{
+    __shared__ int wsum[VEC_BLOCK / 64];
+    __shared__ int wtot;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int incl = x;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int y = __shfl_up(incl, off);
+        if (lane >= off) incl += y;
+    }
+    __syncthreads();                        // a previous call's readers are done with wsum / wtot
+    if (lane == 63) wsum[w] = incl;
+    __syncthreads();
+    int base = 0;
+#pragma unroll
+    for (int k = 0; k < VEC_BLOCK / 64; ++k)
+        if (k < w) base += wsum[k];
+    if (threadIdx.x == VEC_BLOCK - 1) wtot = base + incl;
+    __syncthreads();
+    *total = wtot;
+    return base + incl - x;
+}
+
+// Prefix sums of one or two arrays of the same length in the same launches: out[a][0..n) = exclusive prefix sum
+// of in[a][0..n), out[a][n] = the total, also written to total[a] when given.  tsum / toff: per-tile scratch.
+struct ScanArgs {
+    const int32_t *in[2];
+    int32_t *out[2];
+    int32_t *tsum[2], *toff[2];
+    int32_t *total[2];
+    int32_t na;
+    int64_t n;
+};
+
+__global__ __launch_bounds__(VEC_BLOCK) void scan_tile_sum_kernel(ScanArgs a)
+{
+    const int64_t b0 = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    for (int j = 0; j < a.na; ++j) {
+        int s = 0;
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k)
+            if (b0 + k < a.n) s += a.in[j][b0 + k];
+        int tot;
+        (void)block_exclusive_scan(s, &tot);
+        if (threadIdx.x == 0) a.tsum[j][blockIdx.x] = tot;
+    }
+}
+
+// one block: out[0..n) = exclusive prefix sum of in[0..n), out[n] = the total (also to *t1 / *t2 when given)
+__device__ __forceinline__ void scan_by_one_block(const int32_t *in, int64_t n, int32_t *out, int32_t *t1, int32_t *t2)
+{
+    int carry = 0;
+    for (int64_t t0 = 0; t0 < n; t0 += SCAN_TILE) {
+        const int64_t b0 = t0 + (int64_t)threadIdx.x * SCAN_ITEMS;
+        int v[SCAN_ITEMS];
+        int s = 0;
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k) {
+            v[k] = (b0 + k < n) ? in[b0 + k] : 0;
+            s += v[k];
+        }
+        int tot;
+        int run = carry + block_exclusive_scan(s, &tot);
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k) {
+            if (b0 + k < n) out[b0 + k] = run;
+            run += v[k];
+        }
+        carry += tot;
+    }
+    if (threadIdx.x == 0) {
+        out[n] = carry;
+        if (t1) *t1 = carry;
+        if (t2) *t2 = carry;
+    }
+}
+// the arrays themselves (short ones)
+__global__ __launch_bounds__(VEC_BLOCK) void scan_one_block_kernel(ScanArgs a)
+{
+    for (int j = 0; j < a.na; ++j) scan_by_one_block(a.in[j], a.n, a.out[j], a.total[j], nullptr);
+}
+// the tile sums of long arrays: tile offsets, and the grand total to out[n] and total
+__global__ __launch_bounds__(VEC_BLOCK) void scan_tiles_kernel(ScanArgs a, int64_t nt)
+{
+    for (int j = 0; j < a.na; ++j) scan_by_one_block(a.tsum[j], nt, a.toff[j], a.out[j] ? a.out[j] + a.n : nullptr, a.total[j]);
+}
+
+__global__ __launch_bounds__(VEC_BLOCK) void scan_tile_apply_kernel(ScanArgs a)
+{
+    const int64_t b0 = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    for (int j = 0; j < a.na; ++j) {
+        int v[SCAN_ITEMS];
+        int s = 0;
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k) {
+            v[k] = (b0 + k < a.n) ? a.in[j][b0 + k] : 0;
+            s += v[k];
+        }
+        int tot;
+        int run = a.toff[j][blockIdx.x] + block_exclusive_scan(s, &tot);
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k) {
+            if (b0 + k < a.n) a.out[j][b0 + k] = run;
+            run += v[k];
+        }
+    }
+}
+
+// scratch: two areas of at least n / SCAN_TILE + 2 elements per array
+static void own_scan(ScanArgs a, int32_t *scratch, int64_t area, hipStream_t st)
+{
+    if (a.n <= 8 * SCAN_TILE) {
+        hipLaunchKernelGGL(scan_one_block_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, a);
+        return;
+    }
+    const int64_t nt = (a.n + SCAN_TILE - 1) / SCAN_TILE;
+    for (int j = 0; j < a.na; ++j) {
+        a.tsum[j] = scratch + (2 * j) * area;
+        a.toff[j] = scratch + (2 * j + 1) * area;
+    }
+    hipLaunchKernelGGL(scan_tile_sum_kernel, dim3((unsigned)nt), dim3(VEC_BLOCK), 0, st, a);
+    hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, a, nt);
+    hipLaunchKernelGGL(scan_tile_apply_kernel, dim3((unsigned)nt), dim3(VEC_BLOCK), 0, st, a);
+}
+static void own_scan1(const int32_t *in, int64_t n, int32_t *out, int32_t *total, int32_t *scratch, int64_t area, hipStream_t st)
+{
+    ScanArgs a{};
+    a.in[0] = in;
+    a.out[0] = out;
+    a.total[0] = total;
+    a.na = 1;
+    a.n = n;
+    own_scan(a, scratch, area, st);
+}
+
+// zeroes the multiplicities and the bitmap of sampled rows, empties the rows' lists of sample positions
+__global__ __launch_bounds__(VEC_BLOCK) void samp_fill_kernel(int32_t *cnt, int32_t *head, int64_t n, uint32_t *bitmap, int64_t nwords)
+{
+    for (int64_t i = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; i < n; i += (int64_t)gridDim.x * VEC_BLOCK) {
+        cnt[i] = 0;
+        head[i] = -1;
+        if (i < nwords) bitmap[i] = 0u;
+    }
+}
+// cnt[r] = how often row r is sampled; bit r of the bitmap = whether it is; head[r], next[head[r]], .. = its sample
+// positions (a list per row, in no particular order); len[s] = entries of the row at sample position s
+__global__ __launch_bounds__(VEC_BLOCK) void samp_mark_kernel(const int32_t *S, int64_t nS, const int32_t *rowptr, int32_t *cnt,
+                                                               uint32_t *bitmap, int32_t *head, int32_t *next, int32_t *len)
+{
+    for (int64_t s = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; s < nS; s += (int64_t)gridDim.x * VEC_BLOCK) {
+        const int32_t r = S[s];
+        atomicAdd(&cnt[r], 1);
+        atomicOr(&bitmap[r >> 5], 1u << (r & 31));
+        next[s] = atomicExch(&head[r], (int32_t)s);
+        if (len) len[s] = rowptr[r + 1] - rowptr[r];
+    }
+}
+
+// The two passes over the whole view's row indices: a thread takes SCAN_ITEMS consecutive entries (two 16-byte
+// loads) and asks the bitmap of sampled rows -- copied to LDS when it fits (lds_words > 0), a few KB for tens of
+// thousands of rows -- about each; only for the sampled ones does it go on to the multiplicity.
+struct SampScan {
+    const int32_t *frow;
+    int64_t fnnz;
+    const uint32_t *bitmap;
+    int32_t lds_words;
+    const int32_t *cnt;
+};
+__device__ __forceinline__ void samp_tile_rows(const SampScan &q, const uint32_t *bm_lds, int64_t b0, int (&r)[SCAN_ITEMS],
+                                               int (&m)[SCAN_ITEMS])
+{
+    if (b0 + SCAN_ITEMS <= q.fnnz) {
+        const int4 lo = *(const int4 *)(q.frow + b0), hi = *(const int4 *)(q.frow + b0 + 4);
+        r[0] = lo.x, r[1] = lo.y, r[2] = lo.z, r[3] = lo.w, r[4] = hi.x, r[5] = hi.y, r[6] = hi.z, r[7] = hi.w;
+    } else {
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k) r[k] = (b0 + k < q.fnnz) ? q.frow[b0 + k] : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        m[k] = 0;
+        if (r[k] >= 0) {
+            const uint32_t w = q.lds_words ? bm_lds[r[k] >> 5] : q.bitmap[r[k] >> 5];
+            if ((w >> (r[k] & 31)) & 1u) m[k] = q.cnt[r[k]];
+        }
+    }
+}
+__device__ __forceinline__ const uint32_t *samp_bitmap_to_lds(const SampScan &q, uint32_t *lds)
+{
+    for (int i = threadIdx.x; i < q.lds_words; i += VEC_BLOCK) lds[i] = q.bitmap[i];
+    __syncthreads();
+    return lds;
+}
+// tsum[tile] = number of sample entries that the tile's entries of the whole view produce
+__global__ __launch_bounds__(VEC_BLOCK) void samp_tile_count_kernel(SampScan q, int32_t *tsum)
+{
+    static_assert(SCAN_ITEMS == 8, "two 16-byte loads per thread");
+    extern __shared__ uint32_t samp_lds[];
+    const uint32_t *bm = samp_bitmap_to_lds(q, samp_lds);
+    const int64_t b0 = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    int r[SCAN_ITEMS], m[SCAN_ITEMS];
+    samp_tile_rows(q, bm, b0, r, m);
+    int s = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) s += m[k];
+    int tot;
+    (void)block_exclusive_scan(s, &tot);
+    if (threadIdx.x == 0) tsum[blockIdx.x] = tot;
+}
+// copies the sampled entries of the tile to their places (cap: capacity of the output arrays, never exceeded).
+// With `off` (support): also the entry's place in the row-ordered list of the sample's entries, eidx, from its
+// place in the CSR arrays (fpos), and its value there (val_in).  The loads of a thread's sampled entries are issued
+// together, level by level (entry, first sample position, that position's row pointer): one after the other they
+// were a chain of two dozen trips to memory per thread.
+// Of the whole view only the places in the CSR arrays (fpos) are read for the sampled entries; column and value
+// come from the CSR arrays themselves, where a sampled row's entries are neighbours (a few MB that stay in L2),
+// while the view's own column and value arrays would be read at one entry in twenty, i.e. nearly every line of them.
+template <typename T>
+__global__ __launch_bounds__(VEC_BLOCK) void samp_copy_kernel(SampScan q, const int32_t *colidx, const T *vals, const int32_t *fpos,
+                                                              const int32_t *head, const int32_t *next, const int32_t *toff,
+                                                              int64_t cap, int32_t *key, int32_t *row, T *val,
+                                                              const int32_t *rowptr, const int32_t *off, int32_t *eidx, T *val_in)
+{
+    extern __shared__ uint32_t samp_lds[];
+    const int64_t tile_off = toff[blockIdx.x];
+    const uint32_t *bm = samp_bitmap_to_lds(q, samp_lds);
+    const int64_t b0 = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    int r[SCAN_ITEMS], m[SCAN_ITEMS];
+    if (b0 + SCAN_ITEMS <= q.fnnz) {
+        const int4 lo = *(const int4 *)(q.frow + b0), hi = *(const int4 *)(q.frow + b0 + 4);
+        r[0] = lo.x, r[1] = lo.y, r[2] = lo.z, r[3] = lo.w, r[4] = hi.x, r[5] = hi.y, r[6] = hi.z, r[7] = hi.w;
+    } else {
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k) r[k] = (b0 + k < q.fnnz) ? q.frow[b0 + k] : -1;
+    }
+    // everything that depends on the row alone is asked for in one go: the multiplicity, the entry's place in the
+    // CSR arrays, the row's first sample position, its row pointer
+    int32_t col[SCAN_ITEMS], sp[SCAN_ITEMS], within[SCAN_ITEMS], ob[SCAN_ITEMS], rp[SCAN_ITEMS];
+    T x[SCAN_ITEMS];
+    int s = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        m[k] = 0, col[k] = 0, sp[k] = 0, within[k] = 0, ob[k] = 0, rp[k] = 0, x[k] = T(0);
+        if (r[k] >= 0) {
+            const uint32_t w = q.lds_words ? bm[r[k] >> 5] : q.bitmap[r[k] >> 5];
+            if ((w >> (r[k] & 31)) & 1u) {
+                m[k] = q.cnt[r[k]];
+                within[k] = fpos[b0 + k];                // place in the CSR arrays, for now
+                sp[k] = head[r[k]];
+                if (off) rp[k] = rowptr[r[k]];
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) s += m[k];
+    int tot;
+    int64_t o = tile_off + block_exclusive_scan(s, &tot);
+    if (s == 0) return;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        if (m[k]) {
+            col[k] = colidx[within[k]];
+            x[k] = vals[within[k]];
+            if (off) {
+                within[k] -= rp[k];                      // place of the entry in its row
+                ob[k] = off[sp[k]];
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        if (m[k] == 0) continue;
+        int32_t spj = sp[k], obj = ob[k];
+        for (int j = 0; j < m[k]; ++j, ++o) {
+            if (j > 0) {                                 // a row sampled more than once: its next sample position
+                spj = next[spj];
+                if (off) obj = off[spj];
+            }
+            if (o >= cap) continue;
+            key[o] = col[k];
+            row[o] = spj;
+            val[o] = x[k];
+            if (off) {
+                const int64_t e = (int64_t)obj + within[k];
+                if (e < cap) {
+                    eidx[o] = (int32_t)e;
+                    val_in[e] = x[k];
+                } else {
+                    eidx[o] = 0;
+                }
+            }
+        }
+    }
+}
+
+// Pieces and distinct columns of the copied list (bound >= *nnz entries): a piece starts at the first entry of a
+// column and at every PIECE_LEN-th entry, a column at its first entry.  Both flags are formed from the columns on
+// the fly, counted per tile here ...
+__device__ __forceinline__ void samp_tile_flags(const int32_t *key, int64_t nnz, int64_t b0, int (&kk)[SCAN_ITEMS],
+                                                bool (&pf)[SCAN_ITEMS], bool (&hf)[SCAN_ITEMS])
+{
+    int prev = (b0 > 0 && b0 - 1 < nnz) ? key[b0 - 1] : -1;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        const int64_t t = b0 + k;
+        const bool in = t < nnz;
+        kk[k] = in ? key[t] : -1;
+        hf[k] = in && (t == 0 || kk[k] != prev);
+        pf[k] = hf[k] || (in && (t % PIECE_LEN) == 0);
+        prev = kk[k];
+    }
+}
+__global__ __launch_bounds__(VEC_BLOCK) void samp_piece_count_kernel(const int32_t *key, const int32_t *nnz_dev, int32_t *tsum_p,
+                                                                      int32_t *tsum_h)
+{
+    const int64_t nnz = *nnz_dev;
+    const int64_t b0 = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    int kk[SCAN_ITEMS];
+    bool pf[SCAN_ITEMS], hf[SCAN_ITEMS];
+    samp_tile_flags(key, nnz, b0, kk, pf, hf);
+    int sp = 0, sh = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) sp += pf[k], sh += hf[k];
+    int tp, th;
+    (void)block_exclusive_scan(sp, &tp);
+    (void)block_exclusive_scan(sh, &th);
+    if (threadIdx.x == 0) {
+        tsum_p[blockIdx.x] = tp;
+        tsum_h[blockIdx.x] = th;
+    }
+}
+// ... and numbered here: piece_start / piece_col of every piece (and the sentinels behind the last), and with
+// `support` the distinct columns cols[], the pieces' places among them piece_cpos[], and every entry's place among
+// them written at the entry's place in row order: ccol[eidx[t]]
+__global__ __launch_bounds__(VEC_BLOCK) void samp_piece_write_kernel(const int32_t *key, const int32_t *nnz_dev, const int32_t *np_dev,
+                                                                      const int32_t *toff_p, const int32_t *toff_h, bool support,
+                                                                      const int32_t *eidx, int32_t *piece_start, int32_t *piece_col,
+                                                                      int32_t *piece_cpos, int32_t *cols, int32_t *ccol)
+{
+    const int64_t nnz = *nnz_dev;
+    const int64_t b0 = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    int kk[SCAN_ITEMS];
+    bool pf[SCAN_ITEMS], hf[SCAN_ITEMS];
+    samp_tile_flags(key, nnz, b0, kk, pf, hf);
+    int sp = 0, sh = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) sp += pf[k], sh += hf[k];
+    int tp, th;
+    int pid = toff_p[blockIdx.x] + block_exclusive_scan(sp, &tp);
+    int rank = toff_h[blockIdx.x] + block_exclusive_scan(sh, &th);
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        const int64_t t = b0 + k;
+        if (t < nnz) {
+            const int32_t pos = rank + (hf[k] ? 1 : 0) - 1;      // place of the entry's column among the distinct ones
+            if (pf[k]) {
+                piece_start[pid] = (int32_t)t;
+                piece_col[pid] = kk[k];
+                if (support) piece_cpos[pid] = pos;
+            }
+            if (support) {
+                if (hf[k]) cols[pos] = kk[k];
+                ccol[eidx[t]] = pos;
+            }
+        }
+        pid += pf[k] ? 1 : 0;
+        rank += hf[k] ? 1 : 0;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 4) {          // the sentinels behind the last piece
+        const int32_t np = *np_dev;
+        if (threadIdx.x == 0) piece_start[np] = (int32_t)nnz;
+        piece_col[np + threadIdx.x] = -1;
+        if (support) piece_cpos[np + threadIdx.x] = -1;
+    }
+}
+
+__global__ __launch_bounds__(VEC_BLOCK) void csr_max_len_kernel(const int32_t *rowptr, int64_t n, int32_t *out)
+{
+    int m = 0;
+    for (int64_t i = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x; i < n; i += (int64_t)gridDim.x * VEC_BLOCK)
+        m = max(m, rowptr[i + 1] - rowptr[i]);
+    for (int off = 32; off > 0; off >>= 1) m = max(m, __shfl_xor(m, off));
+    if ((threadIdx.x & 63) == 0) atomicMax(out, m);
+}
+
+hipError_t csr_max_row_len(const int32_t *rowptr, int64_t n, int32_t *scratch_dev, int32_t *out, hipStream_t st)
+{
+    CSC_HIP(hipMemsetAsync(scratch_dev, 0, sizeof(int32_t), st));
+    if (n > 0) hipLaunchKernelGGL(csr_max_len_kernel, dim3(grid_for(n)), dim3(VEC_BLOCK), 0, st, rowptr, n, scratch_dev);
+    CSC_HIP(hipMemcpyAsync(out, scratch_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    return hipStreamSynchronize(st);
+}
+
+// The view of rows S[0..nS) (with repeats) as a filter of `full`, the view of all rows of the same matrix, which
+// must have kept its entries' places in the CSR arrays (csr_pos).  max_len: the longest row of the matrix
+// (nS * max_len bounds the sample's entries and sizes the buffers, so that nothing is allocated here once a
+// sample of this many rows has been seen).  One wait for the stream, at the end, for the three counts.  Returns
+// hipErrorNotSupported when the bound is too loose to be worth it (more than eight times the average); the
+// caller then sorts (csc_build).
+hipError_t csc_build_filtered(CscView *v, const CscView &full, int dtype, const int32_t *rowptr, const int32_t *colidx,
+                              const void *vals, const int32_t *S, int64_t nS, int64_t n, int32_t max_len, int K,
+                              hipStream_t st, bool support)
+{
+    const size_t es = dtype == SSN_F32 ? 4 : 8;
+    v->nnz = 0;
+    v->npieces = 0;
+    v->ncols = 0;
+    v->has_support = false;
+    v->nrows = nS;
+    const int64_t bound = nS * (int64_t)max_len;
+    if (bound == 0 || full.nnz == 0) {
+        if (support) {                       // every selected row is empty: row pointers all zero
+            CSC_HIP(grow((void **)&v->off, &v->cap_off, nS + 1, sizeof(int32_t)));
+            CSC_HIP(hipMemsetAsync(v->off, 0, (size_t)(nS + 1) * sizeof(int32_t), st));
+        }
+        v->has_support = support;
+        return hipSuccess;
+    }
+    if (!full.csr_pos) return hipErrorNotSupported;
+    if (bound >= ((int64_t)1 << 31) - 8 || bound > 8 * (full.nnz / (n > 0 ? n : 1) + 1) * nS) return hipErrorNotSupported;
+    if (!v->count_dev) CSC_HIP(hipMalloc((void **)&v->count_dev, 4 * sizeof(int32_t)));
+    const int64_t ftiles = (full.nnz + SCAN_TILE - 1) / SCAN_TILE;
+    int64_t area = ftiles;                                            // tiles of the longest array scanned here
+    if ((bound + SCAN_TILE - 1) / SCAN_TILE > area) area = (bound + SCAN_TILE - 1) / SCAN_TILE;
+    if ((n + SCAN_TILE - 1) / SCAN_TILE > area) area = (n + SCAN_TILE - 1) / SCAN_TILE;
+    area += 2;
+    const int64_t nwords = (n + 31) / 32;
+    CSC_HIP(grow((void **)&v->cnt, &v->cap_cnt, n, sizeof(int32_t)));
+    CSC_HIP(grow((void **)&v->head, &v->cap_head, n, sizeof(int32_t)));
+    CSC_HIP(grow((void **)&v->bitmap, &v->cap_bitmap, nwords, sizeof(int32_t)));
+    CSC_HIP(grow((void **)&v->next, &v->cap_next, nS, sizeof(int32_t)));
+    CSC_HIP(grow((void **)&v->tsum, &v->cap_tsum, ftiles + 2, sizeof(int32_t)));
+    CSC_HIP(grow((void **)&v->toff, &v->cap_toff, 4 * area, sizeof(int32_t)));        // four scratch areas of the prefix sums
+    CSC_HIP(grow((void **)&v->ftoff, &v->cap_ftoff, ftiles + 2, sizeof(int32_t)));
+    CSC_HIP(grow((void **)&v->key, &v->cap, bound, sizeof(int32_t)));
+    CSC_HIP(grow((void **)&v->row, &v->cap_row, bound, sizeof(int32_t)));
+    CSC_HIP(grow(&v->val, &v->cap_val, bound, es));
+    CSC_HIP(grow((void **)&v->piece_start, &v->cap_piece, bound + 1, sizeof(int32_t)));
+    CSC_HIP(grow((void **)&v->piece_col, &v->cap_pcol, bound + 4, sizeof(int32_t)));
+    // every piece may leave a partial sum and every run of pieces another
+    CSC_HIP(grow(&v->piece_part, &v->cap_part, bound * K * 2, es));
+    if (support) {
+        CSC_HIP(grow((void **)&v->off, &v->cap_off, nS + 1, sizeof(int32_t)));
+        CSC_HIP(grow((void **)&v->len, &v->cap_len, nS + 1, sizeof(int32_t)));
+        CSC_HIP(grow((void **)&v->eidx, &v->cap_eidx, bound, sizeof(int32_t)));
+        CSC_HIP(grow((void **)&v->cols, &v->cap_cols, bound, sizeof(int32_t)));
+        CSC_HIP(grow((void **)&v->ccol, &v->cap_ccol, bound, sizeof(int32_t)));
+        CSC_HIP(grow(&v->val_in, &v->cap_valin, bound, es));
+        CSC_HIP(grow((void **)&v->piece_cpos, &v->cap_pcpos, bound + 4, sizeof(int32_t)));
+    }
+    int32_t *nnz_dev = v->count_dev, *np_dev = v->count_dev + 1, *nc_dev = v->count_dev + 2;
+
+    // 1. how often each row is sampled and at which sample positions; the row pointers of the sample's own CSR form
+    hipLaunchKernelGGL(samp_fill_kernel, dim3(grid_for(n)), dim3(VEC_BLOCK), 0, st, v->cnt, v->head, n, (uint32_t *)v->bitmap, nwords);
+    hipLaunchKernelGGL(samp_mark_kernel, dim3(grid_for(nS)), dim3(VEC_BLOCK), 0, st, S, nS, rowptr, v->cnt, (uint32_t *)v->bitmap,
+                       v->head, v->next, support ? v->len : nullptr);
+    if (support) own_scan1(v->len, nS, v->off, nullptr, v->toff, area, st);
+    // 2. count per tile of the whole view, places of the tiles, copy
+    SampScan q{};
+    q.frow = full.row;
+    q.fnnz = full.nnz;
+    q.bitmap = (const uint32_t *)v->bitmap;
+    q.lds_words = nwords <= 12288 ? (int32_t)nwords : 0;          // up to 48 KB of LDS
+    q.cnt = v->cnt;
+    const size_t lds = (size_t)q.lds_words * sizeof(uint32_t);
+    hipLaunchKernelGGL(samp_tile_count_kernel, dim3((unsigned)ftiles), dim3(VEC_BLOCK), lds, st, q, v->tsum);
+    own_scan1(v->tsum, ftiles, v->ftoff, nnz_dev, v->toff, area, st);
+    if (dtype == SSN_F32)
+        hipLaunchKernelGGL(samp_copy_kernel<float>, dim3((unsigned)ftiles), dim3(VEC_BLOCK), lds, st, q, colidx,
+                           (const float *)vals, full.csr_pos, v->head, v->next, v->ftoff, bound, v->key, v->row,
+                           (float *)v->val, rowptr, support ? v->off : nullptr, v->eidx, (float *)v->val_in);
+    else
+        hipLaunchKernelGGL(samp_copy_kernel<double>, dim3((unsigned)ftiles), dim3(VEC_BLOCK), lds, st, q, colidx,
+                           (const double *)vals, full.csr_pos, v->head, v->next, v->ftoff, bound, v->key, v->row,
+                           (double *)v->val, rowptr, support ? v->off : nullptr, v->eidx, (double *)v->val_in);
+    // 3. pieces, distinct columns: flags counted per tile, the tiles' counts summed up, everything numbered
+    {
+        const int64_t stiles = (bound + SCAN_TILE - 1) / SCAN_TILE;
+        ScanArgs a{};
+        a.n = bound;
+        a.na = 2;
+        for (int j = 0; j < 2; ++j) {
+            a.tsum[j] = v->toff + (2 * j) * area;
+            a.toff[j] = v->toff + (2 * j + 1) * area;
+        }
+        a.total[0] = np_dev;
+        a.total[1] = nc_dev;
+        hipLaunchKernelGGL(samp_piece_count_kernel, dim3((unsigned)stiles), dim3(VEC_BLOCK), 0, st, v->key, nnz_dev, a.tsum[0],
+                           a.tsum[1]);
+        hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(VEC_BLOCK), 0, st, a, stiles);
+        hipLaunchKernelGGL(samp_piece_write_kernel, dim3((unsigned)stiles), dim3(VEC_BLOCK), 0, st, v->key, nnz_dev, np_dev,
+                           a.toff[0], a.toff[1], support, v->eidx, v->piece_start, v->piece_col, v->piece_cpos, v->cols, v->ccol);
+    }
+    CSC_HIP(hipGetLastError());
+    int32_t counts[3] = {0, 0, 0};
+    CSC_HIP(hipMemcpyAsync(counts, v->count_dev, 3 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    CSC_HIP(hipStreamSynchronize(st));
+    if (counts[0] < 0 || counts[0] > bound) return hipErrorInvalidValue;
+    v->nnz = counts[0];
+    v->npieces = counts[0] ? counts[1] : 0;
+    v->ncols = (support && counts[0]) ? counts[2] : 0;
+    v->has_support = support;
     return hipSuccess;
 }
 

@@ -51,6 +51,7 @@ struct ssn_ctx {
     int64_t next_nS = 0;
     bool next_ready = false;
     bool csc_full_built = false;
+    int32_t csr_max_len = 0;      // longest row of the CSR matrix (read when the whole matrix's view is built)
     // reduction scratch
     double *loss_part = nullptr;
     int32_t *hit_part = nullptr;
@@ -364,10 +365,34 @@ int csc_view_for(ssn_ctx *c, const int32_t *S, const CscView **view)
     if (!c->csc_full_built) {
         SSN_HIP(c, csc_build(&c->csc_full, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, nullptr, c->d.n, c->d.p, c->K,
                              c->st));
+        // the sort's permutation (sorted place -> place in the CSR arrays) stays: samples' views are filtered out
+        // of this one and need it
+        c->csc_full.csr_pos = c->csc_full.idx_out;
+        c->csc_full.idx_out = nullptr;
         csc_free_scratch(&c->csc_full);
+        SSN_HIP(c, csr_max_row_len(c->d.rowptr, c->d.n, c->int_dev, &c->csr_max_len, c->st));
         c->csc_full_built = true;
     }
     *view = &c->csc_full;
+    return SSN_OK;
+}
+
+// CSR: the column-sorted view of a sample.  Filtered out of the whole matrix's view (no sort; built first if it
+// is not there yet) unless the row lengths are too uneven for that path's buffer bound or SSN_CSR_VIEW=sort asks
+// for the sorting construction.
+static int build_sample_view(ssn_ctx *c, CscView *v, const int32_t *S, int64_t nS, hipStream_t st, bool support)
+{
+    const char *env = getenv("SSN_CSR_VIEW");       // read at every call: tests switch between the constructions
+    const bool force_sort = env && env[0] == 's';
+    if (!force_sort) {
+        const CscView *full = nullptr;
+        SSN_TRY(csc_view_for(c, nullptr, &full));
+        const hipError_t e = csc_build_filtered(v, *full, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.n,
+                                                c->csr_max_len, c->K, st, support);
+        if (e == hipSuccess) return SSN_OK;
+        if (e != hipErrorNotSupported) SSN_HIP(c, e);
+    }
+    SSN_HIP(c, csc_build(v, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.p, c->K, st, support));
     return SSN_OK;
 }
 
@@ -518,7 +543,7 @@ int gradient_impl(ssn_ctx *c, const void *W, void *G, double *f, bool defer_f = 
     } else {
         const CscView *view = nullptr;
         if (!is_dense(c) && S) {             // a view of its own: the prepared Hessian sample keeps csc_samp
-            SSN_HIP(c, csc_build(&c->csc_grad, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.p, c->K, c->st));
+            SSN_TRY(build_sample_view(c, &c->csc_grad, S, nS, c->st, false));
             view = &c->csc_grad;
         }
         SSN_TRY(transposed_product(c, S, nrows, scale, W, G, false, nullptr, nullptr, view));
@@ -908,7 +933,7 @@ static int prebuild_sample_view(ssn_ctx *c, const int32_t *S, int64_t nS)
         SSN_HIP(c, hipStreamCreateWithFlags(&c->st_aux, hipStreamNonBlocking));
         SSN_HIP(c, hipEventCreateWithFlags(&c->ev_aux, hipEventDisableTiming));
     }
-    SSN_HIP(c, csc_build(&c->csc_next, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.p, c->K, c->st_aux, true));
+    SSN_TRY(build_sample_view(c, &c->csc_next, S, nS, c->st_aux, true));
     SSN_HIP(c, hipEventRecord(c->ev_aux, c->st_aux));
     c->next_S = S;
     c->next_nS = nS;
@@ -940,7 +965,7 @@ static int hess_prepare_impl(ssn_ctx *c, const void *W, const int32_t *S, int64_
             std::swap(c->csc_samp, c->csc_next);
             SSN_HIP(c, hipStreamWaitEvent(c->st, c->ev_aux, 0));
         } else {
-            SSN_HIP(c, csc_build(&c->csc_samp, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.p, c->K, c->st, true));
+            SSN_TRY(build_sample_view(c, &c->csc_samp, S, nS, c->st, true));
         }
         c->next_ready = false;
     }

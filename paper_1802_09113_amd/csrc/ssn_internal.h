@@ -207,10 +207,26 @@ struct CscView {
     int32_t *cols = nullptr;         // ncols
     int32_t *ccol = nullptr;         // nnz
     int32_t *piece_cpos = nullptr;   // npieces + 4 (sentinels -1)
-    int64_t cap_cols = 0, cap_ccol = 0, cap_pcpos = 0;
+    int64_t cap_cols = 0, cap_ccol = 0, cap_pcpos = 0, cap_valin = 0;
+    // scratch of csc_build_filtered: sample multiplicity of every row of the matrix, bitmap of the sampled rows, the
+    // rows' lists of sample positions (head per row, next per sample position), tile sums and offsets of the prefix
+    // sums, row lengths of the sample, every sorted entry's place in row order
+    int32_t *cnt = nullptr, *head = nullptr, *next = nullptr, *tsum = nullptr, *toff = nullptr, *ftoff = nullptr, *len = nullptr,
+            *bitmap = nullptr, *eidx = nullptr;
+    int64_t cap_cnt = 0, cap_head = 0, cap_next = 0, cap_tsum = 0, cap_toff = 0, cap_ftoff = 0, cap_len = 0, cap_bitmap = 0,
+            cap_eidx = 0;
+    // the view of all rows only: place of entry t in the CSR arrays (kept for csc_build_filtered)
+    int32_t *csr_pos = nullptr;
 };
 hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t *colidx, const void *vals,
                      const int32_t *S, int64_t nrows, int64_t p, int K, hipStream_t st, bool support = false);
+// the same view for a sample S[0..nS) of the n rows, filtered out of `full` (the view of all rows) without a sort;
+// hipErrorNotSupported: the row lengths are too uneven for its buffer bound, use csc_build
+hipError_t csc_build_filtered(CscView *v, const CscView &full, int dtype, const int32_t *rowptr, const int32_t *colidx,
+                              const void *vals, const int32_t *S, int64_t nS, int64_t n, int32_t max_len, int K,
+                              hipStream_t st, bool support);
+// longest row of a CSR matrix (synchronises the stream)
+hipError_t csr_max_row_len(const int32_t *rowptr, int64_t n, int32_t *scratch_dev, int32_t *out, hipStream_t st);
 void csc_free(CscView *v);
 void csc_free_scratch(CscView *v);
 // out += coef * X_view^T U (U rows indexed like the view's row selection); slot (nullable): multiply by
