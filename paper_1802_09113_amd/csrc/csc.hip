@@ -2,18 +2,20 @@
 //
 // The transposed product of eq. (13) / Alg. 6 adds x_ij * u_i into row j of the result for every stored
 // entry.  Scattering from the CSR rows would need floating-point atomics (an order of summation that
-// changes from run to run); instead the entries of the selected rows are sorted by column once -- when
-// the context first needs the whole matrix, and at every ssn_hess_prepare for the sample -- and each
-// product then GATHERS: the entries of a column are consecutive, rows of U are read, and every result
-// element has exactly one writer and one order of summation.
+// changes from run to run); instead the entries of the selected rows are kept sorted by column -- the
+// whole matrix is sorted once, when the context first needs it, and a sample's list is filtered out of
+// that at every ssn_hess_prepare -- and each product then GATHERS: the entries of a column are
+// consecutive, rows of U are read, and every result element has exactly one writer and one order of
+// summation.
 //
 // Work is cut into pieces: a piece ends where the column changes and at every PIECE_LEN-th entry, so hot
 // columns (a few appear in almost every row of text-like data) are spread over many lane groups.  A
 // piece that is a whole column adds into the result directly; the pieces of a longer column leave
 // partial sums that a second kernel adds in piece order.
 //
-// The one-off construction uses hipCUB's device radix sort and prefix sums; the product kernels are
-// hand-written.
+// The one-off sort of the whole matrix (and the fallback construction for samples of matrices with very
+// uneven row lengths) uses hipCUB's device radix sort and prefix sums; the construction of a sample's
+// view from the whole matrix's and the product kernels are hand-written.
 #include "ssn_internal.h"
 
 #include <hipcub/hipcub.hpp>
