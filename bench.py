@@ -224,6 +224,9 @@ def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
     out["dense_path"] = path
     kb = csr_kernel_bytes(n, p, K, nS, e, nnz, nnzS) if sparse else kernel_bytes(n, p, K, nS, e, path)
     names = dict(KERNEL_NAMES[path])
+    if (path == 2 and p <= 64 and p % 2 == 0 and K <= 10 and n >= 65536 and os.environ.get("SSN_NARROW_PATH") != "off"):
+        # long gradient / product passes over a narrow matrix go through the vector-unit kernel (dense_narrow.hip)
+        names[1] = "dense_narrow_kernel<GRAD>"
     kern = {}
     for which in (0, 1, 2, 3, 4):
         reps = 20 if which < 3 else 200

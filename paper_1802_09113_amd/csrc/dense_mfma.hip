@@ -1498,6 +1498,7 @@ template <typename T> static size_t fused_grid_lds(int64_t p, int K, bool has_c)
 // waves per workgroup the one-pass kernel would use for a.mode
 int dense_fused_waves(int dtype, const RowsArgs &a)
 {
+    if (dense_narrow_applies(dtype, a)) return 1;
     int nw = 1, fw = 0;
     const bool has_c = (a.mode == ROW_GRAD || a.mode == ROW_APPLY);
     if (dtype == SSN_F32) fused_shape<float>(a.p, has_c, &nw, &fw);
@@ -1507,6 +1508,7 @@ int dense_fused_waves(int dtype, const RowsArgs &a)
 
 int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus)
 {
+    if (dense_narrow_applies(dtype, a)) return dense_narrow_grid(dtype, a, num_cus);
     int nw = 1, fw = 0;
     const bool has_c = (a.mode == ROW_GRAD || a.mode == ROW_APPLY);
     if (dtype == SSN_F32) fused_shape<float>(a.p, has_c, &nw, &fw);
@@ -1606,6 +1608,8 @@ template <typename T> static hipError_t fused_dispatch(const RowsArgs &a, int gr
 // ROW_OBJ / ROW_GRAD 4 * `grid` loss partials (ROW_APPLY: of sum_i z_i . u_i there), ROW_PRED 4 * `grid` hit partials.
 hipError_t launch_dense_fused(int dtype, const RowsArgs &a, int grid, hipStream_t st)
 {
+    // long passes over narrow matrices: the vector-unit kernel (dense_narrow.hip)
+    if (dense_narrow_applies(dtype, a)) return launch_dense_narrow(dtype, a, grid, st);
     if (!a.tail_row || a.tail_len < a.p) return hipErrorInvalidValue;       // the kernel reads row n-1 from this copy
     return dtype == SSN_F32 ? fused_dispatch<float>(a, grid, st) : fused_dispatch<double>(a, grid, st);
 }

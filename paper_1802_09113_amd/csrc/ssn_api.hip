@@ -197,6 +197,7 @@ bool use_fused(const ssn_ctx *c, const RowsArgs &a)
 {
     if (!c->fused || a.mode == ROW_MARGIN) return false;
     if (a.mode == ROW_GRAD || a.mode == ROW_APPLY) return true;
+    if (dense_narrow_applies(c->d.dtype, a)) return true;        // long pass over a narrow matrix: the vector-unit kernel
     if (dense_fused_waves(c->d.dtype, a) > 1) return true;
     // narrow matrix, margins only: the one-pass kernel's single-wave workgroups win once every one of them has a
     // row block of its own to stream (workload 3, fp64 objective: 78 -> 62 us); on fewer rows the plain kernel does
@@ -824,7 +825,9 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
         }
         c->fused = !c->binary && dense_fused_supported(d->dtype, probe) && !(force && strcmp(force, "split") == 0);
         if (c->fused) {
-            const int g = dense_fused_grid(d->dtype, probe, c->num_cus);
+            int g = dense_fused_grid(d->dtype, probe, c->num_cus);
+            const int gn = dense_narrow_max_grid(d->p, c->num_cus);
+            if (gn > g) g = gn;
             if (g > c->max_chunks) c->max_chunks = g;
             // the one-pass kernel reads whole vectors, up to tail_len elements from the start of a row: on the
             // last row that may leave the matrix, so it gets that row as a zero-padded copy

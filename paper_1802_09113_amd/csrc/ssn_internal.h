@@ -120,6 +120,12 @@ bool dense_fused_supported(int dtype, const RowsArgs &a);
 int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus);
 int dense_fused_waves(int dtype, const RowsArgs &a);
 hipError_t launch_dense_fused(int dtype, const RowsArgs &a, int grid, hipStream_t st);
+// long passes over narrow matrices on the vector units (dense_narrow.hip); the three calls above route to it when
+// it applies, with the same contract: `grid` partials in a.part, 4 * `grid` loss partials
+bool dense_narrow_applies(int dtype, const RowsArgs &a);
+int dense_narrow_grid(int dtype, const RowsArgs &a, int num_cus);
+int dense_narrow_max_grid(int64_t p, int num_cus);       // 0: no narrow launch on matrices of p features
+hipError_t launch_dense_narrow(int dtype, const RowsArgs &a, int grid, hipStream_t st);
 hipError_t launch_csr_rows(int dtype, const RowsArgs &a, int blocks, hipStream_t st);
 // binary problem (K = 1) on a dense matrix: matrix-vector kernels on the vector units (dense_binary.hip)
 int binary_rows_blocks(int64_t nrows, int num_cus);
