@@ -1,4 +1,4 @@
-// Preprocessing of Sec. 4: every column of the data matrix scaled to Euclidean norm one, in place, on the
+// Preprocessing of Sec. 4 (unit column norms): every column of X is divided by its 2-norm, in place, on the
 // device.  A set-up step (it runs once per data set, before ssn_create), kept deterministic like the rest:
 // dense columns are summed per row chunk and the chunk sums added in order; CSR columns are summed through
 // the same column-sorted gather as the transposed products (csc.hip) applied to the squared values.
