@@ -164,8 +164,7 @@ __global__ __launch_bounds__(64) void dense_narrow_kernel(RowsArgs a)
     while (rb < nblk) {
         const int sv = rb * NARROW_ROWS + lane;              // sample position of this lane's row
         const bool valid = sv < nrows;
-        // the block after this one (the wave's last block stands in for itself: its loads are then repeated for
-        // nothing, which keeps every load below unconditional)
+        // the block after this one (the wave's last block stands in for itself where a row number is needed)
         const int rbn = rb + (int)gridDim.x;
         const bool more = rbn < nblk;
         const int rown = block_row(more ? rbn : rb);
@@ -199,8 +198,10 @@ __global__ __launch_bounds__(64) void dense_narrow_kernel(RowsArgs a)
         __builtin_amdgcn_wave_barrier();
         if constexpr (!HAS_C) {
             // nothing reads the registers of this block again: the next block's loads go out now
+            if (more) {
 #pragma unroll
-            for (int j = 0; j < NLD; ++j) load_one(rown, j);
+                for (int j = 0; j < NLD; ++j) load_one(rown, j);
+            }
         }
         if (p2 > ph) margins(ph, p2);
 
@@ -267,8 +268,8 @@ __global__ __launch_bounds__(64) void dense_narrow_kernel(RowsArgs a)
             for (int c = 0; c < K; ++c) urow[c] = u[c];
             if constexpr (KU > K) urow[K] = T(0);
             __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int j = 0; j < NLD; ++j) {
+            // (the wave's last block has no next one: the same loop without the loads)
+            auto xtu_step = [&](int j) {
                 const T *ur = us + (2 * j + h) * KU;
                 const T x0 = xn[j].v[0], x1 = xn[j].v[1];     // lanes without features: sums nobody reads
 #pragma unroll
@@ -283,7 +284,16 @@ __global__ __launch_bounds__(64) void dense_narrow_kernel(RowsArgs a)
                         }
                     }
                 }
-                load_one(rown, j);
+            };
+            if (more) {
+#pragma unroll
+                for (int j = 0; j < NLD; ++j) {
+                    xtu_step(j);
+                    load_one(rown, j);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < NLD; ++j) xtu_step(j);
             }
         }
         if (!more) break;
@@ -425,7 +435,7 @@ bool dense_narrow_applies(int dtype, const RowsArgs &a)
 int dense_narrow_grid(int dtype, const RowsArgs &a, int num_cus)
 {
     int per_cu = narrow_resident_per_cu(dtype, a);
-    if (per_cu > 10) per_cu = 10;
+    if (per_cu > 12) per_cu = 12;
     const int64_t nblk = (a.nrows + NARROW_ROWS - 1) / NARROW_ROWS;
     const int64_t resident = (int64_t)num_cus * per_cu;
     if (nblk <= resident) return (int)(nblk < 1 ? 1 : nblk);
@@ -433,7 +443,7 @@ int dense_narrow_grid(int dtype, const RowsArgs &a, int num_cus)
     return (int)((nblk + rounds - 1) / rounds);
 }
 
-int dense_narrow_max_grid(int64_t p, int num_cus) { return (p >= 2 && p <= NARROW_MAX_P && !(p & 1)) ? num_cus * 10 : 0; }
+int dense_narrow_max_grid(int64_t p, int num_cus) { return (p >= 2 && p <= NARROW_MAX_P && !(p & 1)) ? num_cus * 12 : 0; }
 
 hipError_t launch_dense_narrow(int dtype, const RowsArgs &a, int grid, hipStream_t st)
 {
