@@ -25,7 +25,7 @@
  *   back-tracking line search ............ Alg. 3, eq. (3c)
  *   sub-sampled Newton iteration ......... Alg. 1, eq. (3a)
  *   classification rule .................. end of Sec. 3.3 (argmax over the C class probabilities)
- *   unit-column-norm preprocessing ....... Sec. 4 (every column of the data matrix scaled to Euclidean norm one)
+ *   unit-column-norm preprocessing ....... Sec. 4 (columns divided by their 2-norms)
  *
  * Conventions (interface choices, stated here because the paper leaves them open):
  *   - n rows, p features, C classes, K = C-1.  Labels are 0-based in [0,C);
