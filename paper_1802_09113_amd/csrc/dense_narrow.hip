@@ -411,12 +411,15 @@ int narrow_forced()
 }  // namespace
 
 // Does the vector-unit kernel serve this launch?  Shape: an even number of at most 64 features, at most ten weight
-// columns.  Size: passes of at least NARROW_MIN_ROWS rows; on fewer rows the matrix-core kernel's 16-row blocks give
-// more waves something to do.  Mode: the two with a transposed product (gradient 581012 x 54, fp64: 64 us against
-// 73 us, product on all rows 72 against 85 us); the margins-only passes are as fast (objective) or faster (the
-// probabilities of eq. (11), whose rows this kernel writes lane by lane) through the matrix-core kernel, and take
-// this one only where SSN_NARROW_PATH=on asks for it.
-constexpr int64_t NARROW_MIN_ROWS = 65536;
+// columns.  Mode: the two with a transposed product; the margins-only passes are as fast (objective) or faster (the
+// probabilities of eq. (11), whose rows this kernel writes lane by lane) through the matrix-core kernel and take this
+// one only where SSN_NARROW_PATH=on asks for it.  Size, measured on 54 / 48 / 30 features (gradient and product over n
+// rows, microseconds, this kernel / the matrix-core one): from NARROW_MIN_ROWS rows on -- on a few thousand sampled rows
+// a wave's single 64-row block is one long chain (product on 5810 rows 11.0 / 9.0, on 20000 rows 11.9 / 14.3, on 50000
+// rows 19.4 / 21.6 in fp64); and in fp64 with eight weight columns and more, whose accumulators leave one wave per
+// SIMD, only up to NARROW_BIG_K_ROWS rows (K = 10: 23.3 / 24.7 on 50000 rows, 80.3 / 69.3 on 400000; K = 8: gradient
+// 65.0 / 70.1 but product 59.2 / 56.5 on 400000 rows).  fp32 wins at every K (K = 10: 46.1 / 51.7 on 400000 rows).
+constexpr int64_t NARROW_MIN_ROWS = 16384, NARROW_BIG_K_ROWS = 100000;
 bool dense_narrow_applies(int dtype, const RowsArgs &a)
 {
     const int forced = narrow_forced();
@@ -427,7 +430,9 @@ bool dense_narrow_applies(int dtype, const RowsArgs &a)
     const size_t es = dtype == SSN_F32 ? 4 : 8;
     if ((uintptr_t)a.X % es != 0 || (uintptr_t)a.M % es != 0 || a.ldx * (int64_t)es >= ((int64_t)1 << 30)) return false;
     if (forced > 0) return true;
-    return (a.mode == ROW_GRAD || a.mode == ROW_APPLY) && a.nrows >= NARROW_MIN_ROWS;
+    if ((a.mode != ROW_GRAD && a.mode != ROW_APPLY) || a.nrows < NARROW_MIN_ROWS) return false;
+    if (dtype != SSN_F32 && a.nrows > NARROW_BIG_K_ROWS && (a.K >= 9 || (a.K == 8 && a.mode == ROW_APPLY))) return false;
+    return true;
 }
 
 // workgroups (single waves): as many as stay resident together (LDS bound, at most ten per compute unit), in

@@ -1,7 +1,8 @@
 """GPU parity of the vector-unit kernel for long passes over narrow dense matrices (an even number of at most 64
 features, at most ten weight columns; Table 1's Covertype- and Drive-Diagnostics-like shapes).  By default it serves
-passes of 65536 rows and more; SSN_NARROW_PATH=on makes it serve every pass the shape allows, so that the oracle can
-check it on sizes it finishes in seconds, and =off keeps the matrix-core kernels (the two are compared as well)."""
+gradient and product passes of 16384 rows and more; SSN_NARROW_PATH=on makes it serve every pass the shape allows, so
+that the oracle can check it on sizes it finishes in seconds, and =off keeps the matrix-core kernels (the two are
+compared as well)."""
 import os
 
 import numpy as np
