@@ -155,3 +155,52 @@ def test_narrow_kernel_takes_over_on_long_passes_and_agrees_with_the_matrix_core
         assert rel_err(HV, HV_ref) <= tol
     # the two kernels sum in different orders: equal to rounding, not bit for bit
     assert rel_err(out["default"][1], out["off"][1]) <= tol
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_cg_and_the_ssn_loop_through_the_narrow_kernel(narrow_on, dtype):
+    # Alg. 2 followed product by product (the kernel leaves the curvature sums of z_i . u_i that CG reads, and obeys the
+    # loop's stop flag), then Alg. 1 over a fixed schedule with full gradients and with sub-sampled ones, every gradient,
+    # product and trial objective going through the vector-unit kernel
+    from paper_1802_09113_amd import synth
+    n, p, C = 3001, 54, 7
+    d, g = _problem(n, p, C, seed=33)
+    pair = Pair(d, dtype)
+    Wh, Wd = pair.block(0.1 * g.standard_normal((p, C - 1)))
+    nS = 600
+    S = synth.sample_rows(n, nS)
+    G_ref, _ = pair.oracle.gradient(Wh)
+    Gh, Gd = pair.block(G_ref)
+    pair.gpu.ssn_hess_prepare(Wd, pair.idx(S))
+    ttol = 1e-8 if dtype == F64 else 5e-3
+    for theta, T in [(1e-4, 10), (0.3, 10), (1e-30, 3)]:
+        print(f"[case] narrow cg dtype={dtype} theta={theta} T={T}", flush=True)
+        ref = pair.oracle.cg(Wh, S, Gh, theta, T)
+        out = pair.gpu.ssn_cg(Gd, theta, T)
+        torch.cuda.synchronize()
+        assert out["iters"] == ref["iters"] and out["flags"] == ref["flags"]
+        np.testing.assert_allclose(out["alpha"], ref["alpha"], rtol=ttol)
+        np.testing.assert_allclose(out["rnorm"], ref["rnorm"], rtol=ttol)
+        np.testing.assert_allclose(out["sHs"], ref["sHs"], rtol=ttol)
+        assert rel_err(pair.host(out["p"]), ref["p"]) <= ttol
+    iters = 6
+    S_all = synth.sample_schedule(n, nS, iters)
+    W0 = 0.01 * g.standard_normal((p, C - 1))
+    for sub_sampled in (False, True):
+        print(f"[case] narrow ssn dtype={dtype} sub-sampled gradient={sub_sampled}", flush=True)
+        W0h, W0d = pair.block(W0)
+        kw = {}
+        if sub_sampled:
+            Sg_all = np.stack([synth.sample_rows(n, n // 5, seed=900 + it) for it in range(iters)]).astype(np.int32)
+            Wref, log_ref, done_ref = pair.oracle.ssn_sg(W0h, Sg_all, S_all, theta=1e-4, T=10)
+            kw["Sg_all"] = torch.from_numpy(Sg_all).cuda()
+        else:
+            Wref, log_ref, done_ref = pair.oracle.ssn(W0h, S_all, theta=1e-4, T=10)
+        recs, done = pair.gpu.ssn_solve(W0d, torch.from_numpy(S_all).cuda(), theta=1e-4, T=10, **kw)
+        torch.cuda.synchronize()
+        assert done == done_ref
+        np.testing.assert_allclose(np.array([r["f"] for r in recs]), log_ref[:done, 0], rtol=1e-8 if dtype == F64 else 1e-3)
+        assert [r["cg_iters"] for r in recs] == [int(x) for x in log_ref[:done, 2]]
+        assert [r["alpha"] for r in recs] == list(log_ref[:done, 4])
+        assert rel_err(pair.host(W0d), Wref) <= (1e-6 if dtype == F64 else 2e-2)
+    pair.close()
