@@ -33,14 +33,14 @@ __device__ __forceinline__ int wave_min_int(int x)
 }
 
 // z_c = sum over the row's stored entries of x * M[col, c]; result valid in lanes c < K.
+// (b, e: the row's range of stored entries, loaded by the caller one row ahead)
 template <typename T>
-__device__ __forceinline__ T csr_row_margin(const RowsArgs &a, int64_t row, int lane, int K, int NS)
+__device__ __forceinline__ T csr_row_margin(const RowsArgs &a, int64_t b, int64_t e, int lane, int K, int NS)
 {
     const int s = lane / K, c = lane - s * K;
     const bool act = s < NS;
     const T *vals = (const T *)a.vals;
     const T *M = (const T *)a.M;
-    const int64_t b = a.rowptr[row], e = a.rowptr[row + 1];
     // eight stored entries per lane in flight: a row's gathers depend on its column indices, and a single chain
     // of index -> gather round trips is what bounds a wave that owns a whole row (four in flight: the sampled
     // product's rows kernel took 26 us instead of 21 on the sparse workload, the fp32 objective 150 instead of 136)
@@ -106,13 +106,30 @@ template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER
     double loss = 0.0;
     int hits = 0;
 
-    for (int64_t sv = wave; sv < a.nrows; sv += nwaves) {
-        const int64_t row = a.S ? a.S[sv] : sv;
-        const T z = csr_row_margin<T>(a, row, lane, K, NS);
+    // A wave's rows are chains of dependent trips to memory (row pointers -> entries -> rows of M -> label): the
+    // pointers and the label of the NEXT row are requested before the current row's work, so that only the entries
+    // and the gathers of a row wait for each other.
+    int64_t sv = wave, svn = 0, row = 0, rown = 0, b = 0, e = 0, bn = 0, en = 0;
+    int lab = 0, labn = 0;
+    constexpr bool NEED_LAB = (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_PRED);
+    if (sv < a.nrows) {
+        row = a.S ? a.S[sv] : sv;
+        b = a.rowptr[row];
+        e = a.rowptr[row + 1];
+        if constexpr (NEED_LAB) lab = a.labels[row];
+    }
+    for (; sv < a.nrows; sv = svn, row = rown, b = bn, e = en, lab = labn) {
+        svn = sv + nwaves;
+        rown = row;
+        if (svn < a.nrows) rown = a.S ? a.S[svn] : svn;
+        bn = a.rowptr[rown];
+        en = a.rowptr[rown + 1];
+        if constexpr (NEED_LAB) labn = a.labels[rown];
+        const T z = csr_row_margin<T>(a, b, e, lane, K, NS);
         if constexpr (MODE == ROW_MARGIN) {              // margins of both operands, [X M | X M2], 2K values per row
-            RowsArgs b = a;
-            b.M = a.M2;
-            const T z2 = csr_row_margin<T>(b, row, lane, K, NS);
+            RowsArgs b2 = a;
+            b2.M = a.M2;
+            const T z2 = csr_row_margin<T>(b2, b, e, lane, K, NS);
             if (cv) {
                 ((T *)a.UP)[sv * a.KP + lane] = z;
                 ((T *)a.UP)[sv * a.KP + K + lane] = z2;
@@ -121,17 +138,17 @@ template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER
         }
         if constexpr (MODE == ROW_APPLY) {
             const T pin = cv ? ((const T *)a.Pin)[sv * a.KP + lane] : T(0);
-            const T t = wave_sum(pin * z);
+            const T t = (K == 1) ? pin * z : wave_sum(pin * z);       // one weight column: lane 0 has it all
             const T u = pin * z - pin * t;
             if (cv) ((T *)a.UP)[sv * a.KP + lane] = u;
             // z_i . u_i of the row: summed over the sample it is V^T (X_S^T U), the curvature term CG needs
-            const T zu = wave_sum(cv ? z * u : T(0));
+            const T zu = (K == 1) ? z * u : wave_sum(cv ? z * u : T(0));
             if (lane == 0) loss += (double)zu;
             continue;
         }
-        const T zmax = wave_max(cv ? z : NEG);
+        // one weight column: the row's margin sits in lane 0 and nothing has to be reduced over the wave
+        const T zmax = (K == 1) ? __shfl(z, 0) : wave_max(cv ? z : NEG);
         if constexpr (MODE == ROW_PRED) {
-            const int lab = a.labels[row];
             const int cand = wave_min_int((cv && z == zmax) ? lane : 0x7fffffff);
             const int pr = (T(0) > zmax) ? K : cand;
             if (lane == 0) {
@@ -142,13 +159,12 @@ template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER
         }
         const T Mx = fmax(T(0), zmax);
         const T ex = cv ? c_exp(z - Mx) : T(0);
-        const T alpha = c_exp(-Mx) + wave_sum(ex);
+        const T alpha = c_exp(-Mx) + ((K == 1) ? __shfl(ex, 0) : wave_sum(ex));
         if constexpr (MODE == ROW_PREP) {
             if (cv) ((T *)a.UP)[sv * a.KP + lane] = ex / alpha;
             continue;
         }
-        const int lab = a.labels[row];
-        const T lin = wave_sum((cv && lane == lab) ? z : T(0));
+        const T lin = (K == 1) ? ((lab == 0) ? zmax : T(0)) : wave_sum((cv && lane == lab) ? z : T(0));
         if (lane == 0) loss += (double)Mx + (double)c_log(alpha) - (double)lin;
         if (MODE == ROW_GRAD && cv) ((T *)a.UP)[sv * a.KP + lane] = ex / alpha - ((lane == lab) ? T(1) : T(0));
     }
