@@ -175,9 +175,98 @@ template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER
     }
 }
 
+// One weight column (the binary problem): a row's margin is a single number, and the per-row work on it (two
+// exponentials, a logarithm, a division in eqs. (8), (9), (14)-(17)) done row by row keeps all 64 lanes busy with
+// one row's arithmetic -- on rows of a few dozen entries that arithmetic, not the memory, is what the pass costs.
+// Here a wave parks the margins of its rows in its lanes, one row per lane, and does the per-row work for up to 64
+// rows at once.  Margins, prefetch and partial sums as in csr_rows_kernel; the loss of a wave is the sum of its lanes'
+// sums (fixed order).
+template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void csr_rows1_kernel(RowsArgs a)
+{
+    if (a.skip && *a.skip) return;
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const int64_t nwaves = (int64_t)gridDim.x * ROWS_WAVES_PER_BLOCK;
+    const int64_t wave = (int64_t)blockIdx.x * ROWS_WAVES_PER_BLOCK + wib;
+    double loss = 0.0;
+    int hits = 0;
+    // parked rows: lane i holds the margin, sample position and label of the i-th row since the last flush
+    T zl = T(0);
+    int64_t svl = 0;
+    int labl = 0, cnt = 0;
+    auto flush = [&]() {
+        if (lane < cnt) {
+            if constexpr (MODE == ROW_APPLY) {
+                const T pin = ((const T *)a.Pin)[svl * a.KP];
+                const T t = pin * zl;
+                const T u = pin * zl - pin * t;              // eq. (12) with one class
+                ((T *)a.UP)[svl * a.KP] = u;
+                loss += (double)(zl * u);                    // z_i u_i: the curvature term of Alg. 2
+            } else if constexpr (MODE == ROW_PRED) {
+                const int pr = (T(0) > zl) ? 1 : 0;          // the reference class wins only strictly
+                if (a.pred) a.pred[svl] = pr;
+                hits += (pr == labl);
+            } else {
+                const T Mx = fmax(T(0), zl);
+                const T ex = c_exp(zl - Mx);
+                const T alpha = c_exp(-Mx) + ex;
+                if constexpr (MODE == ROW_PREP) {
+                    ((T *)a.UP)[svl * a.KP] = ex / alpha;
+                } else {
+                    loss += (double)Mx + (double)c_log(alpha) - (double)((labl == 0) ? zl : T(0));
+                    if constexpr (MODE == ROW_GRAD) ((T *)a.UP)[svl * a.KP] = ex / alpha - ((labl == 0) ? T(1) : T(0));
+                }
+            }
+        }
+        cnt = 0;
+    };
+
+    int64_t sv = wave, svn = 0, row = 0, rown = 0, b = 0, e = 0, bn = 0, en = 0;
+    int lab = 0, labn = 0;
+    constexpr bool NEED_LAB = (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_PRED);
+    if (sv < a.nrows) {
+        row = a.S ? a.S[sv] : sv;
+        b = a.rowptr[row];
+        e = a.rowptr[row + 1];
+        if constexpr (NEED_LAB) lab = a.labels[row];
+    }
+    for (; sv < a.nrows; sv = svn, row = rown, b = bn, e = en, lab = labn) {
+        svn = sv + nwaves;
+        rown = row;
+        if (svn < a.nrows) rown = a.S ? a.S[svn] : svn;
+        bn = a.rowptr[rown];
+        en = a.rowptr[rown + 1];
+        if constexpr (NEED_LAB) labn = a.labels[rown];
+        const T z = __shfl(csr_row_margin<T>(a, b, e, lane, 1, 64), 0);
+        if (lane == cnt) {
+            zl = z;
+            svl = sv;
+            labl = lab;
+        }
+        if (++cnt == 64) flush();
+    }
+    flush();
+    if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_APPLY) {
+        loss = wave_sum(loss);
+        if (lane == 0) a.loss_part[wave] = loss;
+    } else if constexpr (MODE == ROW_PRED) {
+        for (int off = 32; off > 0; off >>= 1) hits += __shfl_xor(hits, off);
+        if (lane == 0) a.hit_part[wave] = hits;
+    }
+}
+
 template <typename T> static hipError_t csr_rows_dispatch(const RowsArgs &a, int blocks, hipStream_t st)
 {
     dim3 grid(blocks), block(64 * ROWS_WAVES_PER_BLOCK);
+    if (a.K == 1) {                      // one weight column: per-row work for up to 64 rows at once
+        switch (a.mode) {
+        case ROW_OBJ: hipLaunchKernelGGL((csr_rows1_kernel<T, ROW_OBJ>), grid, block, 0, st, a); return hipGetLastError();
+        case ROW_GRAD: hipLaunchKernelGGL((csr_rows1_kernel<T, ROW_GRAD>), grid, block, 0, st, a); return hipGetLastError();
+        case ROW_PREP: hipLaunchKernelGGL((csr_rows1_kernel<T, ROW_PREP>), grid, block, 0, st, a); return hipGetLastError();
+        case ROW_APPLY: hipLaunchKernelGGL((csr_rows1_kernel<T, ROW_APPLY>), grid, block, 0, st, a); return hipGetLastError();
+        case ROW_PRED: hipLaunchKernelGGL((csr_rows1_kernel<T, ROW_PRED>), grid, block, 0, st, a); return hipGetLastError();
+        default: break;                  // ROW_MARGIN: the general kernel
+        }
+    }
     switch (a.mode) {
     case ROW_OBJ: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_OBJ>), grid, block, 0, st, a); break;
     case ROW_GRAD: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_GRAD>), grid, block, 0, st, a); break;
