@@ -224,7 +224,7 @@ def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
     out["dense_path"] = path
     kb = csr_kernel_bytes(n, p, K, nS, e, nnz, nnzS) if sparse else kernel_bytes(n, p, K, nS, e, path)
     names = dict(KERNEL_NAMES[path])
-    if (path == 2 and p <= 64 and p % 2 == 0 and K <= 10 and n >= 16384 and (e == 4 or K <= 8 or n <= 100000)
+    if (path == 2 and p <= 64 and p % 2 == 0 and K <= 10 and n >= 16384 and (e == 4 or K <= 9 or n <= 100000)
             and os.environ.get("SSN_NARROW_PATH") != "off"):
         # long gradient / product passes over a narrow matrix go through the vector-unit kernel (dense_narrow.hip)
         names[1] = "dense_narrow_kernel<GRAD>"

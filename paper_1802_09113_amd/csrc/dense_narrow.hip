@@ -6,16 +6,18 @@
 // accumulator layout (a row spread over 16 lanes) costs more than both products.  Here a wave owns 64 rows at a
 // time and every quantity of a row lives in ONE lane:
 //   load    : the 64 x p block comes in with one 2-element vector per lane, half a wave per row (32 loads, each
-//             covering two whole rows, i.e. contiguous memory), into registers -- issued one block ahead -- and
-//             from there into the wave's own LDS tile;
-//   margins : lane r walks row r of the tile; z_rc += x_rf W_fc.  The W operands are the same for every lane, so
-//             they are scalar operands: lane f keeps row f of W in registers for the whole kernel and a lane read
-//             (v_readlane) puts an element into a scalar register -- no memory traffic of any kind for W;
+//             covering two whole rows, i.e. contiguous memory), into registers;
+//   margins : the block goes through the wave's own LDS tile in two halves of the features and lane r walks row r
+//             of the tile; z_rc += x_rf W_fc.  The W operands are the same for every lane, so they are scalar
+//             operands: scalar loads through the constant cache (W is a few KB here and stays there), two buffers,
+//             the request for step j + 1 placed by hand right behind the wait for step j's -- no vector-memory, LDS
+//             or lane traffic for W;
 //   row work: eqs. (8), (9), (11), (12), (14)-(17) for 64 rows at once, one row per lane, no cross-lane traffic;
-//   X^T U   : the rows of U go to LDS; lane (h, l) then holds features 2l, 2l+1 and walks the rows 2j + h of the
-//             tile, G_fc += x_rf u_rc with u_rc broadcast from LDS; the accumulators stay in registers over all
-//             the wave's blocks and leave as one p x K partial per workgroup (added by the finalize kernels in a
-//             fixed order: no atomics).
+//   X^T U   : the rows of U go to LDS; the transposed product runs from the REGISTERS the block was loaded into:
+//             lane (h, l) holds features 2l, 2l+1 of rows 2j + h, G_fc += x_rf u_rc with u_rc a half-wave
+//             broadcast from LDS; register j is free once its rows have been used, and the next block's load j goes
+//             out right there.  The accumulators stay in registers over all the wave's blocks and leave as one
+//             p x K partial per workgroup (added by the finalize kernels in a fixed order: no atomics).
 // A workgroup is one wave: nothing here needs a barrier.  Eq. (5), (6) / Alg. 5, 6 and eqs. (10)-(13) / Alg. 7, 8
 // as in the matrix-core kernels; results differ from theirs by the order of summation only.
 #include "ssn_internal.h"
@@ -30,7 +32,9 @@ namespace ssn {
 namespace {
 
 __device__ __forceinline__ float n_exp(float x) { return expf(x); }
-__device__ __forceinline__ double n_exp(double x) { return exp_nonpos(x, 0.0); }
+// (an opaque zero keeps the routine's sixteen 64-bit coefficients from being set up once and held in registers across
+// the kernel, whose fp64 forms have none to spare)
+__device__ __forceinline__ double n_exp(double x) { return exp_nonpos(x, opaque_zero()); }
 
 __device__ __forceinline__ double n_rcp(double a)          // a in [1, 17]: estimate plus two Newton steps
 {
@@ -171,14 +175,6 @@ __global__ __launch_bounds__(64) void dense_narrow_kernel(RowsArgs a)
         int labn = 0;
         if constexpr (NEED_LAB) labn = a.labels[rown];
 
-        // per-row data that does not depend on the margins
-        T pin[K];
-        if constexpr (MODE == ROW_APPLY) {
-            const T *pr = (const T *)a.Pin + (int64_t)(valid ? sv : 0) * a.KP;
-#pragma unroll
-            for (int c = 0; c < K; ++c) pin[c] = pr[c];
-        }
-
 #pragma unroll
         for (int c = 0; c < K; ++c) z[c] = T(0);
         // first half of the features -> LDS (the previous reads of the tile were issued before: LDS serves a wave
@@ -208,6 +204,12 @@ __global__ __launch_bounds__(64) void dense_narrow_kernel(RowsArgs a)
         // per-row work
         T u[K];
         if constexpr (MODE == ROW_APPLY) {
+            // (the probabilities are fetched here, not ahead of the margins: with nine and ten weight columns in fp64
+            // the registers they would hold through the margins are what keeps a second wave off the SIMD)
+            T pin[K];
+            const T *pr = (const T *)a.Pin + (int64_t)(valid ? sv : 0) * a.KP;
+#pragma unroll
+            for (int c = 0; c < K; ++c) pin[c] = pr[c];
             T t = T(0);
 #pragma unroll
             for (int c = 0; c < K; ++c) t = fma(pin[c], z[c], t);
@@ -249,7 +251,7 @@ __global__ __launch_bounds__(64) void dense_narrow_kernel(RowsArgs a)
                     lprod *= (double)alpha;
                 }
                 if (lprod > 1e250) {
-                    loss += log(lprod);
+                    loss += log_ge1(lprod, opaque_zero());
                     lprod = 1.0;
                 }
                 if constexpr (MODE == ROW_GRAD) {
@@ -319,7 +321,7 @@ __global__ __launch_bounds__(64) void dense_narrow_kernel(RowsArgs a)
         }
     }
     if constexpr (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_APPLY) {
-        if constexpr (MODE != ROW_APPLY) loss += log(lprod);
+        if constexpr (MODE != ROW_APPLY) loss += log_ge1(lprod, opaque_zero());
         for (int off = 32; off > 0; off >>= 1) loss += __shfl_xor(loss, off);
         // four partials per workgroup, as the multi-wave kernels leave them
         if (lane < 4) a.loss_part[blockIdx.x * 4 + lane] = (lane == 0) ? loss : 0.0;
@@ -416,9 +418,11 @@ int narrow_forced()
 // one only where SSN_NARROW_PATH=on asks for it.  Size, measured on 54 / 48 / 30 features (gradient and product over n
 // rows, microseconds, this kernel / the matrix-core one): from NARROW_MIN_ROWS rows on -- on a few thousand sampled rows
 // a wave's single 64-row block is one long chain (product on 5810 rows 11.0 / 9.0, on 20000 rows 11.9 / 14.3, on 50000
-// rows 19.4 / 21.6 in fp64); and in fp64 with eight weight columns and more, whose accumulators leave one wave per
-// SIMD, only up to NARROW_BIG_K_ROWS rows (K = 10: 23.3 / 24.7 on 50000 rows, 80.3 / 69.3 on 400000; K = 8: gradient
-// 65.0 / 70.1 but product 59.2 / 56.5 on 400000 rows).  fp32 wins at every K (K = 10: 46.1 / 51.7 on 400000 rows).
+// rows 19.4 / 21.6 in fp64); and in fp64 with many weight columns, where the accumulators and the block leave the
+// product one wave per SIMD (K >= 9) or little room (K = 8), only up to NARROW_BIG_K_ROWS rows: product with K = 8
+// 19.5 / 22.1 on 50000 rows but 59.7 / 57.4 on 400000, K = 10 22.6 / 22.5 and 73.0 / 57.3; gradient with K = 9 65.1 /
+// 68.8 on 400000 rows, K = 10 20.1 / 24.7 on 50000 and 70.9 / 69.6 on 400000.  fp32 wins at every K (K = 10: 46.1 /
+// 51.7 on 400000 rows).
 constexpr int64_t NARROW_MIN_ROWS = 16384, NARROW_BIG_K_ROWS = 100000;
 bool dense_narrow_applies(int dtype, const RowsArgs &a)
 {
@@ -431,7 +435,7 @@ bool dense_narrow_applies(int dtype, const RowsArgs &a)
     if ((uintptr_t)a.X % es != 0 || (uintptr_t)a.M % es != 0 || a.ldx * (int64_t)es >= ((int64_t)1 << 30)) return false;
     if (forced > 0) return true;
     if ((a.mode != ROW_GRAD && a.mode != ROW_APPLY) || a.nrows < NARROW_MIN_ROWS) return false;
-    if (dtype != SSN_F32 && a.nrows > NARROW_BIG_K_ROWS && (a.K >= 9 || (a.K == 8 && a.mode == ROW_APPLY))) return false;
+    if (dtype != SSN_F32 && a.nrows > NARROW_BIG_K_ROWS && a.K >= (a.mode == ROW_APPLY ? 8 : 10)) return false;
     return true;
 }
 
