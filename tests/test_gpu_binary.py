@@ -153,3 +153,43 @@ def test_dense_binary_at_full_size_and_without_allocations(dtype):
         torch.cuda.synchronize()
         assert st == binding.SSN_OK and rel_err(pair.host(HV2), ref) <= tol
     pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_sparse_binary_with_more_rows_per_wave_than_lanes(dtype):
+    # The one-weight-column CSR rows kernel parks a row's margin in a lane and does the per-row work when 64 rows are
+    # parked or the wave runs out of rows.  The launch never has more than 16 waves per compute unit, so only a matrix
+    # of more than a million rows fills a wave's lanes: 1.2 M rows of zero to four entries (empty rows included).
+    n, p = 1_200_000, 40
+    g = np.random.default_rng(7)
+    counts = g.integers(0, 5, size=n)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(counts, out=rowptr[1:])
+    nnz = int(rowptr[-1])
+    colidx = g.integers(0, p, size=nnz).astype(np.int32)
+    # distinct, ascending columns inside a row: offsets 0..4 times 8 plus a per-entry draw below 8
+    within = np.arange(nnz) - np.repeat(rowptr[:-1], counts)
+    colidx = (within * 8 + colidx % 8).astype(np.int32)
+    vals = g.standard_normal(nnz)
+    w_true = g.standard_normal(p)
+    scores = np.zeros(n)
+    np.add.at(scores, np.repeat(np.arange(n), counts), vals * w_true[colidx])
+    labels = (scores + g.logistic(size=n) < 0).astype(np.int32)
+    d = dict(layout="csr", rowptr=rowptr, colidx=colidx, vals=vals, labels=labels, C=2, K=1, p=p, n=n, lam=1e-3, nnz=nnz)
+    pair = Pair(d, dtype)
+    tol = TOL[dtype]
+    Wh, Wd = pair.block(0.5 * g.standard_normal((p, 1)))
+    Vh, Vd = pair.block(g.standard_normal((p, 1)))
+    print(f"[case] sparse binary, 1.2 M short rows dtype={dtype}", flush=True)
+    f = pair.gpu.ssn_objective(Wd)
+    G, f2 = pair.gpu.ssn_gradient(Wd)
+    S = np.arange(n, dtype=np.int32)
+    HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+    pred, acc = pair.gpu.ssn_predict(Wd)
+    torch.cuda.synchronize()
+    G_ref, f_ref = pair.oracle.gradient(Wh)
+    assert rel_scalar(f, f_ref) <= tol and rel_scalar(f2, f_ref) <= tol
+    assert rel_err(pair.host(G), G_ref) <= tol
+    assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
+    assert abs(acc - pair.oracle.accuracy(Wh)) <= (1e-12 if dtype == F64 else 2e-3)
+    pair.close()
