@@ -161,7 +161,7 @@ void csc_free(CscView *v)
 {
     void *all[] = {v->key, v->row, v->val, v->piece_start, v->piece_col, v->piece_part, v->off, v->key_in, v->idx_in, v->idx_out,
                    v->row_in, v->val_in, v->flag, v->pid, v->cub_tmp, v->count_dev, v->cols, v->ccol, v->piece_cpos,
-                   v->cnt, v->head, v->next, v->tsum, v->toff, v->ftoff, v->len, v->bitmap, v->eidx, v->csr_pos};
+                   v->cnt, v->head, v->next, v->tsum, v->toff, v->ftoff, v->len, v->bitmap, v->eidx, v->csr_pos, v->win_pid};
     for (void *q : all)
         if (q) (void)hipFree(q);
     *v = CscView{};
@@ -189,6 +189,7 @@ hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t
     const size_t es = dtype == SSN_F32 ? 4 : 8;
     v->nnz = 0;
     v->npieces = 0;
+    v->win_npieces = -1;                 // the window index of an earlier build is void
     v->ncols = 0;
     v->has_support = false;
     if (!v->count_dev) CSC_HIP(hipMalloc((void **)&v->count_dev, 4 * sizeof(int32_t)));
@@ -724,6 +725,7 @@ hipError_t csc_build_filtered(CscView *v, const CscView &full, int dtype, const 
     const size_t es = dtype == SSN_F32 ? 4 : 8;
     v->nnz = 0;
     v->npieces = 0;
+    v->win_npieces = -1;                 // the window index of an earlier build is void
     v->ncols = 0;
     v->has_support = false;
     v->nrows = nS;
@@ -839,6 +841,8 @@ struct CscApply {
     void *run_part;          // sums of runs of pieces (grouped combine), laid out like piece_part
     int32_t look;            // pieces a wave of the run / combine kernels looks at (a power of two, 4..64)
     const int32_t *skip;
+    const int32_t *key;      // column of every entry (csc1_window_kernel: where the pieces of a window start)
+    const int32_t *win_pid;  // piece that starts at entry 64 w (csc1_window_kernel)
 };
 // (piece_col may be the pieces' columns or their positions among the distinct columns: equal columns have
 // equal positions, and the result row written is whichever of the two the caller's `out` is indexed by)
@@ -965,6 +969,82 @@ template <typename T> __global__ __launch_bounds__(256) void csc_piece_kernel(Cs
     } else {
         ((T *)a.piece_part)[pid * K + c] = acc;
     }
+}
+
+// One weight column (the binary problem): the job of csc_piece_kernel with a lane per ENTRY instead of a lane per
+// piece.  With K = 1 a lane group is a single lane that walks its piece of up to 64 entries alone, so the lanes of a
+// wave read 64 different stretches of the entry arrays; here a wave takes one aligned window of 64 entries (pieces
+// start at every 64th entry, so a window holds whole pieces), reads rows, values and the gathered u coalesced, and
+// adds the products of each piece by a segmented reduction over the lanes (fixed order).  The piece's first lane
+// adds a whole column into the result or leaves the piece's partial sum, exactly as csc_piece_kernel does, and the
+// run / combine kernels follow unchanged.
+template <typename T> __global__ __launch_bounds__(256) void csc1_window_kernel(CscApply a)
+{
+    if (a.skip && *a.skip) return;
+    double coef = a.coef;
+    if (a.slot) {
+        if (a.slot->done || a.slot->brk) return;
+        coef *= -a.slot->alpha;
+    }
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w * 64 >= a.nnz) return;                                 // the whole wave
+    const int64_t e = w * 64 + lane;
+    const bool have = e < a.nnz;
+    const int col = have ? a.key[e] : -1;
+    const int r = have ? a.row[e] : 0;
+    const T v = have ? ((const T *)a.val)[e] : T(0);
+    T x = have ? v * ((const T *)a.U)[(int64_t)r * a.KP] : T(0);
+    const int prev = __shfl_up(col, 1);
+    const bool start = lane == 0 || col != prev;                 // a piece (or the padding behind the last entry) starts here
+    const unsigned long long starts = __ballot(start);
+    const unsigned long long above = (lane == 63) ? 0ull : ((starts >> (lane + 1)) << (lane + 1));
+    const int send = above ? (__ffsll((long long)above) - 2) : 63;       // last lane of this lane's piece
+    for (int d = 1; d < 64; d <<= 1) {
+        const T y = __shfl_down(x, d);
+        if (lane + d <= send) x += y;
+    }
+    if (start && have) {
+        const int64_t pid = (int64_t)a.win_pid[w] + __popcll(starts & ((1ull << lane) - 1ull));
+        const int ocol = a.piece_col[pid];
+        const bool head = (pid == 0) || (a.piece_col[pid - 1] != ocol);
+        const bool more = a.piece_col[pid + 1] == ocol;
+        if (head && !more) {
+            T *o = (T *)a.out + (int64_t)ocol * a.ldo;
+            *o = (T)((double)*o + coef * (double)x);
+        } else {
+            ((T *)a.piece_part)[pid] = x;
+        }
+    }
+}
+
+// win_pid[w] = the piece that starts at entry 64 w (every aligned 64th entry starts one)
+__global__ __launch_bounds__(VEC_BLOCK) void csc_window_index_kernel(const int32_t *piece_start, int32_t npieces, int32_t *win_pid)
+{
+    const int64_t k = (int64_t)blockIdx.x * VEC_BLOCK + threadIdx.x;
+    if (k >= npieces) return;
+    const int32_t t = piece_start[k];
+    if ((t & 63) == 0) win_pid[t >> 6] = (int32_t)k;
+}
+
+hipError_t csc_window_index(CscView *v, hipStream_t st)
+{
+    const int64_t nwin = (v->nnz + 63) / 64;
+    if (nwin > v->cap_win) {
+        if (v->win_pid) {
+            CSC_HIP(hipStreamSynchronize(st));
+            CSC_HIP(hipFree(v->win_pid));
+            v->win_pid = nullptr;
+        }
+        const int64_t cap = nwin + nwin / 4 + 16;
+        CSC_HIP(hipMalloc((void **)&v->win_pid, (size_t)cap * sizeof(int32_t)));
+        v->cap_win = cap;
+    }
+    v->win_npieces = v->npieces;
+    if (v->npieces > 0)
+        hipLaunchKernelGGL(csc_window_index_kernel, dim3((unsigned)((v->npieces + VEC_BLOCK - 1) / VEC_BLOCK)), dim3(VEC_BLOCK), 0, st,
+                           v->piece_start, v->npieces, v->win_pid);
+    return hipGetLastError();
 }
 
 // Columns of several pieces: a lane group adds the column's partial sums in piece order and adds the result into
@@ -1120,6 +1200,11 @@ hipError_t launch_csc_apply(int dtype, const CscView &v, int K, int KP, const vo
     const size_t es = dtype == SSN_F32 ? 4 : 8;
     a.run_part = (char *)v.piece_part + (size_t)v.npieces * K * es;
     a.skip = skip;
+    a.key = v.key;
+    a.win_pid = v.win_pid;
+    // one weight column: a lane per entry (csc1_window_kernel) where the view carries its window index
+    const bool windows = K == 1 && v.win_pid && v.win_npieces == v.npieces && v.key;
+    const unsigned wblocks = (unsigned)((((v.nnz + 63) / 64) + 3) / 4);
     const int NS = 64 / K;
     const int64_t waves = ((int64_t)v.npieces + NS - 1) / NS;
     const unsigned blocks = (unsigned)((waves + 3) / 4);
@@ -1133,7 +1218,8 @@ hipError_t launch_csc_apply(int dtype, const CscView &v, int K, int KP, const vo
     a.look = look;
     const unsigned cblocks = (unsigned)((((int64_t)v.npieces + look - 1) / look + 3) / 4);
     if (dtype == SSN_F32) {
-        hipLaunchKernelGGL(csc_piece_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
+        if (windows) hipLaunchKernelGGL(csc1_window_kernel<float>, dim3(wblocks), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL(csc_piece_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
         if (grouped) {
             hipLaunchKernelGGL(csc_run_kernel<float>, dim3(cblocks), dim3(256), 0, st, a);
             hipLaunchKernelGGL((csc_combine_kernel<float, true>), dim3(cblocks), dim3(256), 0, st, a);
@@ -1141,7 +1227,8 @@ hipError_t launch_csc_apply(int dtype, const CscView &v, int K, int KP, const vo
             hipLaunchKernelGGL((csc_combine_kernel<float, false>), dim3(cblocks), dim3(256), 0, st, a);
         }
     } else {
-        hipLaunchKernelGGL(csc_piece_kernel<double>, dim3(blocks), dim3(256), 0, st, a);
+        if (windows) hipLaunchKernelGGL(csc1_window_kernel<double>, dim3(wblocks), dim3(256), 0, st, a);
+        else hipLaunchKernelGGL(csc_piece_kernel<double>, dim3(blocks), dim3(256), 0, st, a);
         if (grouped) {
             hipLaunchKernelGGL(csc_run_kernel<double>, dim3(cblocks), dim3(256), 0, st, a);
             hipLaunchKernelGGL((csc_combine_kernel<double, true>), dim3(cblocks), dim3(256), 0, st, a);

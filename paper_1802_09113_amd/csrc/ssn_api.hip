@@ -372,6 +372,7 @@ int csc_view_for(ssn_ctx *c, const int32_t *S, const CscView **view)
         c->csc_full.idx_out = nullptr;
         csc_free_scratch(&c->csc_full);
         SSN_HIP(c, csr_max_row_len(c->d.rowptr, c->d.n, c->int_dev, &c->csr_max_len, c->st));
+        if (c->K == 1) SSN_HIP(c, csc_window_index(&c->csc_full, c->st));
         c->csc_full_built = true;
     }
     *view = &c->csc_full;
@@ -390,10 +391,14 @@ static int build_sample_view(ssn_ctx *c, CscView *v, const int32_t *S, int64_t n
         SSN_TRY(csc_view_for(c, nullptr, &full));
         const hipError_t e = csc_build_filtered(v, *full, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.n,
                                                 c->csr_max_len, c->K, st, support);
-        if (e == hipSuccess) return SSN_OK;
+        if (e == hipSuccess) {
+            if (c->K == 1) SSN_HIP(c, csc_window_index(v, st));
+            return SSN_OK;
+        }
         if (e != hipErrorNotSupported) SSN_HIP(c, e);
     }
     SSN_HIP(c, csc_build(v, c->d.dtype, c->d.rowptr, c->d.colidx, c->d.vals, S, nS, c->d.p, c->K, st, support));
+    if (c->K == 1) SSN_HIP(c, csc_window_index(v, st));
     return SSN_OK;
 }
 

@@ -223,6 +223,11 @@ struct CscView {
             cap_eidx = 0;
     // the view of all rows only: place of entry t in the CSR arrays (kept for csc_build_filtered)
     int32_t *csr_pos = nullptr;
+    // one weight column: the piece that starts at every aligned 64th entry (csc_window_index, after every build);
+    // win_npieces: the piece count it was made for
+    int32_t *win_pid = nullptr;
+    int64_t cap_win = 0;
+    int32_t win_npieces = -1;
 };
 hipError_t csc_build(CscView *v, int dtype, const int32_t *rowptr, const int32_t *colidx, const void *vals,
                      const int32_t *S, int64_t nrows, int64_t p, int K, hipStream_t st, bool support = false);
@@ -233,6 +238,8 @@ hipError_t csc_build_filtered(CscView *v, const CscView &full, int dtype, const 
                               hipStream_t st, bool support);
 // longest row of a CSR matrix (synchronises the stream)
 hipError_t csr_max_row_len(const int32_t *rowptr, int64_t n, int32_t *scratch_dev, int32_t *out, hipStream_t st);
+// one weight column: index of the view's 64-entry windows for the lane-per-entry product kernel (call after a build)
+hipError_t csc_window_index(CscView *v, hipStream_t st);
 void csc_free(CscView *v);
 void csc_free_scratch(CscView *v);
 // out += coef * X_view^T U (U rows indexed like the view's row selection); slot (nullable): multiply by
