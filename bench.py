@@ -229,9 +229,9 @@ def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
         # long gradient / product passes over a narrow matrix go through the vector-unit kernel (dense_narrow.hip)
         names[1] = "dense_narrow_kernel<GRAD>"
     if sparse and K == 1:
-        # one weight column: the first kernel of the column-sorted product is the lane-per-entry one
-        names[2] = names[2].replace("csc_piece_kernel", "csc1_window_kernel")
-        names[4] = names[4].replace("csc_piece_kernel", "csc1_window_kernel")
+        # one weight column: the column-sorted product is the lane-per-entry kernel and its lane-per-piece combine
+        names[2] = "csc1_window_kernel + csc1_combine_kernel (n rows)"
+        names[4] = "csc1_window_kernel + csc1_combine_kernel (|S| rows)"
     kern = {}
     for which in (0, 1, 2, 3, 4):
         reps = 20 if which < 3 else 200

@@ -1018,6 +1018,65 @@ template <typename T> __global__ __launch_bounds__(256) void csc1_window_kernel(
     }
 }
 
+// One weight column, second and last kernel: the partial sums of the columns of several pieces, added with a lane per
+// PIECE.  A wave takes 64 consecutive pieces and adds, by the same segmented reduction, the pieces of every column
+// that starts among them; a column that runs on behind the wave's last piece (only the last one can) is followed by
+// the whole wave, 64 pieces per step, until it ends -- a column present in most of 65 000 rows has a thousand pieces,
+// which one lane adding them one after the other would be a chain of as many trips to memory.  Fixed orders, one
+// writer per column.  (The columns of a single piece were added by csc1_window_kernel.)
+template <typename T> __global__ __launch_bounds__(256) void csc1_combine_kernel(CscApply a)
+{
+    if (a.skip && *a.skip) return;
+    double coef = a.coef;
+    if (a.slot) {
+        if (a.slot->done || a.slot->brk) return;
+        coef *= -a.slot->alpha;
+    }
+    const int lane = threadIdx.x & 63;
+    const int64_t base = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 64;
+    if (base >= a.npieces) return;                               // the whole wave
+    const int64_t pid = base + lane;
+    const bool have = pid < a.npieces;
+    const T *pp = (const T *)a.piece_part;
+    const int col = have ? a.piece_col[pid] : -1;
+    const int prevc = (have && pid > 0) ? a.piece_col[pid - 1] : -2;
+    const int nextc = have ? a.piece_col[pid + 1] : -3;          // (sentinels -1 behind the last piece)
+    const bool head = have && col != prevc, more = have && nextc == col;
+    const bool multi = have && !(head && !more);                 // piece of a column of several pieces: it left a partial sum
+    T x = multi ? pp[pid] : T(0);
+    const int below = __shfl_up(col, 1);                         // (every lane takes part in the exchange)
+    const bool start = lane == 0 || col != below;
+    const unsigned long long starts = __ballot(start);
+    const unsigned long long above = (lane == 63) ? 0ull : ((starts >> (lane + 1)) << (lane + 1));
+    const int send = above ? (__ffsll((long long)above) - 2) : 63;
+    for (int d = 1; d < 64; d <<= 1) {
+        const T y = __shfl_down(x, d);
+        if (lane + d <= send) x += y;
+    }
+    // The column of the wave's last piece may run on behind it; this wave follows it if the column starts here
+    // (the wave where it starts does otherwise).
+    const int lastcol = __shfl(col, 63);
+    const int lastnext = __shfl(nextc, 63);
+    const int laststart = 63 - __clzll(starts);                  // first lane of the last segment (lane 0 always starts one)
+    const int lasthead = __shfl((int)head, laststart);
+    T csum = T(0);
+    if (lastcol >= 0 && lastnext == lastcol && lasthead) {       // uniform over the wave
+        for (int64_t j0 = base + 64;; j0 += 64) {
+            const int64_t j = j0 + lane;
+            const bool m = j < a.npieces && a.piece_col[j] == lastcol;
+            T y = m ? pp[j] : T(0);
+            for (int off = 32; off > 0; off >>= 1) y += __shfl_xor(y, off);
+            csum += y;
+            if (!__all(m)) break;
+        }
+    }
+    if (start && head && more) {                                 // first piece of a column of several: the column's writer
+        const T total = (send == 63) ? x + csum : x;
+        T *o = (T *)a.out + (int64_t)col * a.ldo;
+        *o = (T)((double)*o + coef * (double)total);
+    }
+}
+
 // win_pid[w] = the piece that starts at entry 64 w (every aligned 64th entry starts one)
 __global__ __launch_bounds__(VEC_BLOCK) void csc_window_index_kernel(const int32_t *piece_start, int32_t npieces, int32_t *win_pid)
 {
@@ -1205,6 +1264,7 @@ hipError_t launch_csc_apply(int dtype, const CscView &v, int K, int KP, const vo
     // one weight column: a lane per entry (csc1_window_kernel) where the view carries its window index
     const bool windows = K == 1 && v.win_pid && v.win_npieces == v.npieces && v.key;
     const unsigned wblocks = (unsigned)((((v.nnz + 63) / 64) + 3) / 4);
+    const unsigned pblocks = (unsigned)(((((int64_t)v.npieces + 63) / 64) + 3) / 4);
     const int NS = 64 / K;
     const int64_t waves = ((int64_t)v.npieces + NS - 1) / NS;
     const unsigned blocks = (unsigned)((waves + 3) / 4);
@@ -1218,8 +1278,12 @@ hipError_t launch_csc_apply(int dtype, const CscView &v, int K, int KP, const vo
     a.look = look;
     const unsigned cblocks = (unsigned)((((int64_t)v.npieces + look - 1) / look + 3) / 4);
     if (dtype == SSN_F32) {
-        if (windows) hipLaunchKernelGGL(csc1_window_kernel<float>, dim3(wblocks), dim3(256), 0, st, a);
-        else hipLaunchKernelGGL(csc_piece_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
+        if (windows) {
+            hipLaunchKernelGGL(csc1_window_kernel<float>, dim3(wblocks), dim3(256), 0, st, a);
+            hipLaunchKernelGGL(csc1_combine_kernel<float>, dim3(pblocks), dim3(256), 0, st, a);
+            return hipGetLastError();
+        }
+        hipLaunchKernelGGL(csc_piece_kernel<float>, dim3(blocks), dim3(256), 0, st, a);
         if (grouped) {
             hipLaunchKernelGGL(csc_run_kernel<float>, dim3(cblocks), dim3(256), 0, st, a);
             hipLaunchKernelGGL((csc_combine_kernel<float, true>), dim3(cblocks), dim3(256), 0, st, a);
@@ -1227,8 +1291,12 @@ hipError_t launch_csc_apply(int dtype, const CscView &v, int K, int KP, const vo
             hipLaunchKernelGGL((csc_combine_kernel<float, false>), dim3(cblocks), dim3(256), 0, st, a);
         }
     } else {
-        if (windows) hipLaunchKernelGGL(csc1_window_kernel<double>, dim3(wblocks), dim3(256), 0, st, a);
-        else hipLaunchKernelGGL(csc_piece_kernel<double>, dim3(blocks), dim3(256), 0, st, a);
+        if (windows) {
+            hipLaunchKernelGGL(csc1_window_kernel<double>, dim3(wblocks), dim3(256), 0, st, a);
+            hipLaunchKernelGGL(csc1_combine_kernel<double>, dim3(pblocks), dim3(256), 0, st, a);
+            return hipGetLastError();
+        }
+        hipLaunchKernelGGL(csc_piece_kernel<double>, dim3(blocks), dim3(256), 0, st, a);
         if (grouped) {
             hipLaunchKernelGGL(csc_run_kernel<double>, dim3(cblocks), dim3(256), 0, st, a);
             hipLaunchKernelGGL((csc_combine_kernel<double, true>), dim3(cblocks), dim3(256), 0, st, a);
