@@ -193,3 +193,40 @@ def test_sparse_binary_with_more_rows_per_wave_than_lanes(dtype):
     assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
     assert abs(acc - pair.oracle.accuracy(Wh)) <= (1e-12 if dtype == F64 else 2e-3)
     pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_sparse_binary_columns_that_end_where_a_wave_of_pieces_ends(dtype):
+    # The column-sorted product with one weight column cuts the sorted entries into pieces of at most 64 and adds the
+    # pieces of a column with a lane per piece, 64 pieces per wave.  Here the pieces fall exactly on those edges:
+    # column 0 has 64 x 64 entries (the 64 pieces of the first wave and nothing else), column 1 one entry in every row
+    # (192 pieces: three whole waves, followed from the wave where it starts to a step that finds no piece of it),
+    # then a column of a single entry, one of 100 (two pieces) and one of 64 (one whole piece).
+    n, p = 12288, 7
+    rows = [np.arange(4096), np.arange(n), np.array([5]), np.arange(200, 300), np.arange(1000, 1064)]
+    cols = [0, 1, 2, 4, 6]                               # columns 3 and 5 stay empty
+    g = np.random.default_rng(11)
+    r = np.concatenate(rows)
+    c = np.concatenate([np.full(len(x), k) for x, k in zip(rows, cols)])
+    order = np.lexsort((c, r))
+    r, c = r[order], c[order].astype(np.int32)
+    vals = g.standard_normal(r.size)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(np.bincount(r, minlength=n), out=rowptr[1:])
+    labels = g.integers(0, 2, size=n).astype(np.int32)
+    d = dict(layout="csr", rowptr=rowptr, colidx=c, vals=vals, labels=labels, C=2, K=1, p=p, n=n, lam=1e-3, nnz=int(r.size))
+    pair = Pair(d, dtype)
+    tol = TOL[dtype]
+    Wh, Wd = pair.block(0.5 * g.standard_normal((p, 1)))
+    Vh, Vd = pair.block(g.standard_normal((p, 1)))
+    print(f"[case] sparse binary, columns on the edges of waves of pieces dtype={dtype}", flush=True)
+    G, f = pair.gpu.ssn_gradient(Wd)
+    torch.cuda.synchronize()
+    G_ref, f_ref = pair.oracle.gradient(Wh)
+    assert rel_scalar(f, f_ref) <= tol and rel_err(pair.host(G), G_ref) <= tol
+    # all rows; the first 4096 rows (column 1 then has exactly the pieces of one wave, behind column 0's); a multiset
+    for S in (np.arange(n, dtype=np.int32), np.arange(4096, dtype=np.int32), g.integers(0, n, size=5000).astype(np.int32)):
+        HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+        torch.cuda.synchronize()
+        assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
+    pair.close()
