@@ -571,7 +571,7 @@ int orc_ssn_sg(const orc_problem *pr, double *W, int iters, const int32_t *Sg_al
 }
 
 /*
- * Preprocessing of Sec. 4: scale every column of the data matrix to Euclidean norm one, in place.
+ * Preprocessing of Sec. 4: divide each feature (column) by its 2-norm, so that every non-zero column has length 1; in place.
  * Dense (X != NULL, n-by-p, leading dimension ldx) or CSR (rowptr / colidx / vals).  colnorm (p
  * doubles) receives the norms BEFORE scaling; a column whose norm is zero is left as it is.
  */

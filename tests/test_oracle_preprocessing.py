@@ -1,5 +1,5 @@
 """Pins for the CPU oracle's unit-column-norm preprocessing of Sec. 4 (no GPU): against numpy written out,
-the invariant it exists for (every non-zero column ends with Euclidean norm one), zero columns, and the
+the invariant it exists for (every non-zero column ends with 2-norm 1), zero columns, and the
 agreement of the dense and the CSR form on the same matrix."""
 import numpy as np
 
