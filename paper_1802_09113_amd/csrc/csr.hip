@@ -93,15 +93,24 @@ __device__ __forceinline__ T csr_row_margin(const RowsArgs &a, int64_t b, int64_
     return (lane < K) ? tot : T(0);
 }
 
-template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void csr_rows_kernel(RowsArgs a)
+// SPLIT: a pass over few, long rows (the sampled rows of a matrix with hundreds of entries per row) leaves most of
+// the chip idle with a wave per row, and each wave with a long chain of rounds.  There a WORKGROUP owns a row: its
+// four waves take a quarter of the row's entries each (whole rounds of NS entries), leave their partial margins in
+// LDS, and every wave adds the four in the same order; wave 0 does the row's stores and sums.  All waves of a
+// workgroup walk the same rows, so the barrier is reached by all; the partials alternate between two buffers, so one
+// barrier per row is enough.
+template <typename T, int MODE, bool SPLIT = false>
+__global__ __launch_bounds__(64 * ROWS_WAVES_PER_BLOCK) void csr_rows_kernel(RowsArgs a)
 {
     if (a.skip && *a.skip) return;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    const int64_t nwaves = (int64_t)gridDim.x * ROWS_WAVES_PER_BLOCK;
+    const int64_t nwaves = SPLIT ? (int64_t)gridDim.x : (int64_t)gridDim.x * ROWS_WAVES_PER_BLOCK;    // stride over the rows
     const int64_t wave = (int64_t)blockIdx.x * ROWS_WAVES_PER_BLOCK + wib;
     const int K = a.K;
     const int NS = 64 / K;
-    const bool cv = lane < K;
+    const bool cv = lane < K && (!SPLIT || wib == 0);            // lanes that hold (and store) a row's K values
+    __shared__ T zs[SPLIT ? 2 * ROWS_WAVES_PER_BLOCK * 64 : 1];
+    int par = 0;
     const T NEG = -std::numeric_limits<T>::infinity();
     double loss = 0.0;
     int hits = 0;
@@ -109,7 +118,7 @@ template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER
     // A wave's rows are chains of dependent trips to memory (row pointers -> entries -> rows of M -> label): the
     // pointers and the label of the NEXT row are requested before the current row's work, so that only the entries
     // and the gathers of a row wait for each other.
-    int64_t sv = wave, svn = 0, row = 0, rown = 0, b = 0, e = 0, bn = 0, en = 0;
+    int64_t sv = SPLIT ? (int64_t)blockIdx.x : wave, svn = 0, row = 0, rown = 0, b = 0, e = 0, bn = 0, en = 0;
     int lab = 0, labn = 0;
     constexpr bool NEED_LAB = (MODE == ROW_OBJ || MODE == ROW_GRAD || MODE == ROW_PRED);
     if (sv < a.nrows) {
@@ -125,7 +134,18 @@ template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER
         bn = a.rowptr[rown];
         en = a.rowptr[rown + 1];
         if constexpr (NEED_LAB) labn = a.labels[rown];
-        const T z = csr_row_margin<T>(a, b, e, lane, K, NS);
+        T z;
+        if constexpr (SPLIT) {
+            const int64_t per = ((e - b + ROWS_WAVES_PER_BLOCK * NS - 1) / (ROWS_WAVES_PER_BLOCK * NS)) * NS;
+            const int64_t wb = (b + wib * per < e) ? b + wib * per : e, we = (wb + per < e) ? wb + per : e;
+            T *zp = zs + par * (ROWS_WAVES_PER_BLOCK * 64);
+            zp[wib * 64 + lane] = csr_row_margin<T>(a, wb, we, lane, K, NS);
+            __syncthreads();
+            z = (zp[lane] + zp[64 + lane]) + (zp[128 + lane] + zp[192 + lane]);
+            par ^= 1;
+        } else {
+            z = csr_row_margin<T>(a, b, e, lane, K, NS);
+        }
         if constexpr (MODE == ROW_MARGIN) {              // margins of both operands, [X M | X M2], 2K values per row
             RowsArgs b2 = a;
             b2.M = a.M2;
@@ -265,6 +285,13 @@ template <typename T> static hipError_t csr_rows_dispatch(const RowsArgs &a, int
         case ROW_APPLY: hipLaunchKernelGGL((csr_rows1_kernel<T, ROW_APPLY>), grid, block, 0, st, a); return hipGetLastError();
         case ROW_PRED: hipLaunchKernelGGL((csr_rows1_kernel<T, ROW_PRED>), grid, block, 0, st, a); return hipGetLastError();
         default: break;                  // ROW_MARGIN: the general kernel
+        }
+    }
+    if (a.csr_split) {                   // a workgroup per row (the launcher asks for it on the modes below only)
+        switch (a.mode) {
+        case ROW_PREP: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_PREP, true>), grid, block, 0, st, a); return hipGetLastError();
+        case ROW_APPLY: hipLaunchKernelGGL((csr_rows_kernel<T, ROW_APPLY, true>), grid, block, 0, st, a); return hipGetLastError();
+        default: return hipErrorInvalidValue;
         }
     }
     switch (a.mode) {

@@ -290,6 +290,20 @@ int launch_rows(ssn_ctx *c, const RowsArgs &a, int *nparts)
         const int64_t cap = (int64_t)c->num_cus * 16, want = (a.nrows + ROWS_WAVES_PER_BLOCK - 1) / ROWS_WAVES_PER_BLOCK;
         blocks = (int)(want < cap ? want : cap);
         if (blocks < 1) blocks = 1;
+        // Few, long rows (the sampled rows of the products, on a matrix of hundreds of entries per row): a workgroup
+        // per row, whose four waves share the row's entries -- a wave per row would leave most SIMDs without a wave
+        // and give each wave a long chain of rounds.
+        if (c->K > 1 && (a.mode == ROW_APPLY || a.mode == ROW_PREP) && a.nrows <= (int64_t)c->num_cus * 8 &&
+            c->d.n > 0 && c->d.nnz / c->d.n >= 128) {
+            RowsArgs b = a;
+            b.csr_split = 1;
+            blocks = (int)(a.nrows < cap ? a.nrows : cap);
+            if (blocks < 1) blocks = 1;
+            if (blocks * ROWS_WAVES_PER_BLOCK > c->wave_parts) return fail(c, SSN_E_INVALID_ARG, "internal: wave partial overflow");
+            SSN_HIP(c, launch_csr_rows(c->d.dtype, b, blocks, c->st));
+            if (nparts) *nparts = blocks * ROWS_WAVES_PER_BLOCK;
+            return SSN_OK;
+        }
     }
     if (blocks * ROWS_WAVES_PER_BLOCK > c->wave_parts) return fail(c, SSN_E_INVALID_ARG, "internal: wave partial overflow");
     if (is_dense(c)) SSN_HIP(c, launch_dense_rows(c->d.dtype, a, blocks, split_waves, c->st));

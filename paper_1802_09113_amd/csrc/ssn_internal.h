@@ -56,6 +56,9 @@ struct RowsArgs {
     // vectors, which on every other row stay inside the row's storage or reach into the next row
     const void *tail_row;
     int32_t tail_len;
+    // CSR rows kernel only: non-zero -> a workgroup per row, the row's entries shared out among its four waves (set by
+    // the launcher for passes over few, long rows)
+    int32_t csr_split;
 };
 
 // Arguments of the transposed product: part[chunk] = X_rows(chunk)^T * U(chunk).

@@ -139,3 +139,45 @@ def test_uneven_row_lengths(long_row_len):
         assert rel_err(pair.host(gs), ref_g) <= 1e-10
         assert rel_scalar(fs, ref_f) <= 1e-10
     pair.close()
+
+
+@pytest.mark.parametrize("dtype", [F64, F32], ids=["f64", "f32"])
+@pytest.mark.parametrize("C", [4, 20, 33], ids=["K3", "K19", "K32"])
+def test_workgroup_per_row_passes_on_rows_of_every_length(C, dtype):
+    # Sampled passes over a CSR matrix with long rows on average (128 stored entries and more) give every row to a
+    # workgroup whose four waves share its entries.  Rows here are empty, shorter than one round of the four waves
+    # (so that some waves get nothing), ragged, and long; the sample repeats rows and is not sorted.
+    n, p = 600, 5000
+    g = np.random.default_rng(100 + C)
+    counts = g.integers(300, 700, size=n)
+    counts[::7] = 0
+    counts[1::7] = g.integers(1, 6, size=counts[1::7].size)
+    counts[2::7] = g.integers(60, 70, size=counts[2::7].size)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(counts, out=rowptr[1:])
+    nnz = int(rowptr[-1])
+    assert nnz // n >= 128
+    colidx = np.concatenate([np.sort(g.choice(p, size=k, replace=False)) for k in counts]).astype(np.int32)
+    vals = g.standard_normal(nnz) / 20.0
+    labels = g.integers(0, C, size=n).astype(np.int32)
+    d = dict(layout="csr", rowptr=rowptr, colidx=colidx, vals=vals, labels=labels, C=C, K=C - 1, p=p, n=n, lam=1e-3, nnz=nnz)
+    pair = Pair(d, dtype)
+    tol = TOL[dtype]
+    Wh, Wd = pair.block(0.3 * g.standard_normal((p, C - 1)))
+    Vh, Vd = pair.block(g.standard_normal((p, C - 1)))
+    for name, S in (("multiset", g.integers(0, n, size=250).astype(np.int32)), ("all rows", np.arange(n, dtype=np.int32)),
+                    ("short rows only", np.array([0, 1, 8, 7, 1, 2], dtype=np.int32))):
+        print(f"[case] workgroup per row C={C} dtype={dtype} sample={name}", flush=True)
+        HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+        torch.cuda.synchronize()
+        assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
+    S = g.integers(0, n, size=300).astype(np.int32)
+    Gh, Gd = pair.block(pair.oracle.gradient(Wh)[0])
+    pair.gpu.ssn_hess_prepare(Wd, pair.idx(S))
+    ref = pair.oracle.cg(Wh, S, Gh, 1e-4, 5)
+    out = pair.gpu.ssn_cg(Gd, 1e-4, 5)
+    torch.cuda.synchronize()
+    assert out["iters"] == ref["iters"]
+    np.testing.assert_allclose(out["alpha"], ref["alpha"], rtol=1e-8 if dtype == F64 else 5e-3)
+    assert rel_err(pair.host(out["p"]), ref["p"]) <= (1e-8 if dtype == F64 else 5e-3)
+    pair.close()
