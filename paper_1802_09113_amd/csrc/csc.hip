@@ -976,8 +976,8 @@ template <typename T> __global__ __launch_bounds__(256) void csc_piece_kernel(Cs
 // wave read 64 different stretches of the entry arrays; here a wave takes one aligned window of 64 entries (pieces
 // start at every 64th entry, so a window holds whole pieces), reads rows, values and the gathered u coalesced, and
 // adds the products of each piece by a segmented reduction over the lanes (fixed order).  The piece's first lane
-// adds a whole column into the result or leaves the piece's partial sum, exactly as csc_piece_kernel does, and the
-// run / combine kernels follow unchanged.
+// adds a whole column into the result or leaves the piece's partial sum, exactly as csc_piece_kernel does;
+// csc1_combine_kernel then adds the partial sums of the columns of several pieces.
 template <typename T> __global__ __launch_bounds__(256) void csc1_window_kernel(CscApply a)
 {
     if (a.skip && *a.skip) return;
