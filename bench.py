@@ -229,7 +229,9 @@ def measure(data, dtype_name, steps, warmup, hv_calls, full_step=True):
         # long gradient / product passes over a narrow matrix go through the vector-unit kernel (dense_narrow.hip)
         names[1] = "dense_narrow_kernel<GRAD>"
     if sparse and K == 1:
-        # one weight column: the column-sorted product is the lane-per-entry kernel and its lane-per-piece combine
+        # one weight column: full passes and the column-sorted product run with a lane per stored entry
+        names[0] = "csr1_flat_kernel + csr1_rowwork_kernel<OBJ>"
+        names[1] = "csr1_flat_kernel + csr1_rowwork_kernel<GRAD>"
         names[2] = "csc1_window_kernel + csc1_combine_kernel (n rows)"
         names[4] = "csc1_window_kernel + csc1_combine_kernel (|S| rows)"
     kern = {}

@@ -274,9 +274,161 @@ template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER
     }
 }
 
+// One weight column, passes over ALL rows of the matrix: a lane per stored ENTRY instead of a wave per row.  A row of
+// a few dozen entries gives a wave one short, dependent chain (pointers -> entries -> weights -> sum) and leaves half
+// its lanes idle; here a wave takes an aligned window of 64 consecutive entries of the CSR arrays -- coalesced, no
+// pointer chasing: the row of the window's first entry comes from an index built once (csr_window_rows_kernel), the
+// ends of that row and the 62 after it from one coalesced read of the row pointers, and every lane finds its row among
+// them by a search over the lanes.  The products x_e w_col are added per row by a segmented reduction over the lanes
+// (fixed order).  A row's first segment goes to zrow[row]; the leading segment of a window whose row began in an
+// earlier window goes to zhead[window]; csr1_rowwork_kernel adds a row's pieces (its first segment, then the leading
+// sums of the windows it runs into, in window order) and does the per-row work of eqs. (8), (9), (14)-(17) with a lane
+// per row.  Windows in which more than 63 rows end (runs of empty or one-entry rows) look their rows up in the row
+// pointers directly.
+__global__ __launch_bounds__(256) void csr_window_rows_kernel(const int32_t *rowptr, int64_t n, int64_t nwin, int32_t *rwin)
+{
+    const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= nwin) return;
+    const int64_t target = w * 64;
+    int64_t lo = 0, hi = n;                                  // rowptr[lo] <= target < rowptr[hi]
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (rowptr[mid] <= target) lo = mid;
+        else hi = mid;
+    }
+    rwin[w] = (int32_t)lo;
+}
+
+hipError_t launch_csr_window_rows(const int32_t *rowptr, int64_t n, int64_t nnz, int32_t *rwin, hipStream_t st)
+{
+    const int64_t nwin = (nnz + 63) / 64;
+    if (nwin < 1 || n < 1) return hipSuccess;
+    hipLaunchKernelGGL(csr_window_rows_kernel, dim3((unsigned)((nwin + 255) / 256)), dim3(256), 0, st, rowptr, n, nwin, rwin);
+    return hipGetLastError();
+}
+
+// (a wave takes FLAT_WINDOWS consecutive windows and requests the entries, row pointers and weights of all of them
+// before it works on the first: a single window is 768 bytes, far too little to have on the way per wave)
+constexpr int FLAT_WINDOWS = 4;
+template <typename T> __global__ __launch_bounds__(256) void csr1_flat_kernel(RowsArgs a)
+{
+    if (a.skip && *a.skip) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t w0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * FLAT_WINDOWS;
+    if (w0 * 64 >= a.nnz) return;                                // the whole wave
+    int col[FLAT_WINDOWS], r0[FLAT_WINDOWS], rp[FLAT_WINDOWS], rbeg0[FLAT_WINDOWS];
+    T v[FLAT_WINDOWS], m[FLAT_WINDOWS];
+#pragma unroll
+    for (int i = 0; i < FLAT_WINDOWS; ++i) {
+        const int64_t w = w0 + i, eg64 = w * 64 + lane;
+        const bool have = eg64 < a.nnz;
+        col[i] = have ? a.colidx[eg64] : 0;
+        v[i] = have ? ((const T *)a.vals)[eg64] : T(0);
+        r0[i] = (w * 64 < a.nnz) ? a.rwin[w] : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < FLAT_WINDOWS; ++i) {
+        const int64_t ri = ((int64_t)r0[i] + 1 + lane < a.n) ? (int64_t)r0[i] + 1 + lane : a.n;
+        rp[i] = a.rowptr[ri];                                    // end of row r0 + lane (the entry count behind the last row)
+        rbeg0[i] = a.rowptr[r0[i]];
+        m[i] = ((const T *)a.M)[(int64_t)col[i] * a.ldm];
+    }
+#pragma unroll
+    for (int i = 0; i < FLAT_WINDOWS; ++i) {
+        const int64_t w = w0 + i;
+        if (w * 64 >= a.nnz) break;                              // the whole wave
+        const int64_t eg64 = w * 64 + lane;
+        const bool have = eg64 < a.nnz;
+        const int eg = (int)eg64;                                // entry counts fit 31 bits
+        T x = have ? v[i] * m[i] : T(0);
+        // rows that end at or before this lane's entry, among rows r0 .. r0 + 62
+        int lo = 0;
+        for (int step = 32; step >= 1; step >>= 1) {
+            const int val = __shfl(rp[i], lo + step - 1);
+            if (val <= eg) lo += step;
+        }
+        const int rp63 = __shfl(rp[i], 63);
+        int rbeg = __shfl(rp[i], lo > 0 ? lo - 1 : 0);           // where this lane's row begins
+        if (lo == 0) rbeg = rbeg0[i];
+        int row = r0[i] + lo;
+        if (have && lo == 63 && rp63 <= eg) {                    // more than 63 rows end inside this window
+            int64_t l2 = (int64_t)r0[i] + 64, h2 = a.n;          // rowptr[l2] <= eg < rowptr[h2]
+            while (h2 - l2 > 1) {
+                const int64_t mid = (l2 + h2) >> 1;
+                if (a.rowptr[mid] <= eg) l2 = mid;
+                else h2 = mid;
+            }
+            row = (int)l2;
+            rbeg = a.rowptr[l2];
+        }
+        const int rowk = have ? row : -1;
+        const int below = __shfl_up(rowk, 1);                    // (every lane takes part in the exchange)
+        const bool start = lane == 0 || rowk != below;
+        const unsigned long long starts = __ballot(start);
+        const unsigned long long above = (lane == 63) ? 0ull : ((starts >> (lane + 1)) << (lane + 1));
+        const int send = above ? (__ffsll((long long)above) - 2) : 63;
+        for (int d = 1; d < 64; d <<= 1) {
+            const T y = __shfl_down(x, d);
+            if (lane + d <= send) x += y;
+        }
+        if (start && have) {
+            if (rbeg < eg) ((T *)a.zhead)[w] = x;                // lane 0 only: the row began in an earlier window
+            else ((T *)a.zrow)[row] = x;
+        }
+        if (lane == 0 && !(rbeg < eg)) ((T *)a.zhead)[w] = T(0);
+    }
+}
+
+template <typename T, int MODE> __global__ __launch_bounds__(256) void csr1_rowwork_kernel(RowsArgs a)
+{
+    if (a.skip && *a.skip) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * ROWS_WAVES_PER_BLOCK + (threadIdx.x >> 6);
+    double loss = 0.0;
+    int hits = 0;
+    const T *zrow = (const T *)a.zrow, *zhead = (const T *)a.zhead;
+    for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r < a.n; r += (int64_t)gridDim.x * 256) {
+        const int b = a.rowptr[r], e = a.rowptr[r + 1];
+        const int lab = a.labels[r];
+        T z = T(0);
+        if (e > b) {
+            z = zrow[r];
+            for (int w2 = b / 64 + 1; w2 <= (e - 1) / 64; ++w2) z += zhead[w2];
+        }
+        if constexpr (MODE == ROW_PRED) {
+            const int pr = (T(0) > z) ? 1 : 0;                   // the reference class wins only strictly
+            if (a.pred) a.pred[r] = pr;
+            hits += (pr == lab);
+        } else {
+            const T Mx = fmax(T(0), z);
+            const T ex = c_exp(z - Mx);
+            const T alpha = c_exp(-Mx) + ex;
+            loss += (double)Mx + (double)c_log(alpha) - (double)((lab == 0) ? z : T(0));
+            if constexpr (MODE == ROW_GRAD) ((T *)a.UP)[r * a.KP] = ex / alpha - ((lab == 0) ? T(1) : T(0));
+        }
+    }
+    if constexpr (MODE == ROW_PRED) {
+        for (int off = 32; off > 0; off >>= 1) hits += __shfl_xor(hits, off);
+        if (lane == 0) a.hit_part[wave] = hits;
+    } else {
+        loss = wave_sum(loss);
+        if (lane == 0) a.loss_part[wave] = loss;
+    }
+}
+
 template <typename T> static hipError_t csr_rows_dispatch(const RowsArgs &a, int blocks, hipStream_t st)
 {
     dim3 grid(blocks), block(64 * ROWS_WAVES_PER_BLOCK);
+    if (a.K == 1 && a.rwin && !a.S && a.nnz > 0 && (a.mode == ROW_OBJ || a.mode == ROW_GRAD || a.mode == ROW_PRED)) {
+        const unsigned fblocks = (unsigned)((((a.nnz + 63) / 64) + 4 * FLAT_WINDOWS - 1) / (4 * FLAT_WINDOWS));
+        hipLaunchKernelGGL(csr1_flat_kernel<T>, dim3(fblocks), dim3(256), 0, st, a);
+        switch (a.mode) {
+        case ROW_OBJ: hipLaunchKernelGGL((csr1_rowwork_kernel<T, ROW_OBJ>), grid, block, 0, st, a); break;
+        case ROW_GRAD: hipLaunchKernelGGL((csr1_rowwork_kernel<T, ROW_GRAD>), grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL((csr1_rowwork_kernel<T, ROW_PRED>), grid, block, 0, st, a); break;
+        }
+        return hipGetLastError();
+    }
     if (a.K == 1) {                      // one weight column: per-row work for up to 64 rows at once
         switch (a.mode) {
         case ROW_OBJ: hipLaunchKernelGGL((csr_rows1_kernel<T, ROW_OBJ>), grid, block, 0, st, a); return hipGetLastError();

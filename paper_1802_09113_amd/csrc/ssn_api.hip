@@ -52,6 +52,10 @@ struct ssn_ctx {
     bool next_ready = false;
     bool csc_full_built = false;
     int32_t csr_max_len = 0;      // longest row of the CSR matrix (read when the whole matrix's view is built)
+    // CSR with one weight column: what the lane-per-entry kernels of the full passes need (csr1_flat_kernel) -- the row
+    // of every 64th stored entry, the rows' margins, the windows' leading partial sums
+    int32_t *csr1_rwin = nullptr;
+    void *csr1_zrow = nullptr, *csr1_zhead = nullptr;
     // reduction scratch
     double *loss_part = nullptr;
     int32_t *hit_part = nullptr;
@@ -290,6 +294,19 @@ int launch_rows(ssn_ctx *c, const RowsArgs &a, int *nparts)
         const int64_t cap = (int64_t)c->num_cus * 16, want = (a.nrows + ROWS_WAVES_PER_BLOCK - 1) / ROWS_WAVES_PER_BLOCK;
         blocks = (int)(want < cap ? want : cap);
         if (blocks < 1) blocks = 1;
+        // one weight column, every row of the matrix: a lane per stored entry (csr1_flat_kernel)
+        if (c->K == 1 && c->csr1_rwin && !a.S && a.nrows == c->d.n && a.rowptr == c->d.rowptr && a.colidx == c->d.colidx &&
+            a.vals == c->d.vals && (a.mode == ROW_OBJ || a.mode == ROW_GRAD || a.mode == ROW_PRED)) {
+            RowsArgs b = a;
+            b.rwin = c->csr1_rwin;
+            b.zrow = c->csr1_zrow;
+            b.zhead = c->csr1_zhead;
+            b.nnz = c->d.nnz;
+            if (blocks * ROWS_WAVES_PER_BLOCK > c->wave_parts) return fail(c, SSN_E_INVALID_ARG, "internal: wave partial overflow");
+            SSN_HIP(c, launch_csr_rows(c->d.dtype, b, blocks, c->st));
+            if (nparts) *nparts = blocks * ROWS_WAVES_PER_BLOCK;
+            return SSN_OK;
+        }
         // Few, long rows (the sampled rows of the products, on a matrix of hundreds of entries per row): a workgroup
         // per row, whose four waves share the row's entries -- a wave per row would leave most SIMDs without a wave
         // and give each wave a long chain of rounds.
@@ -747,7 +764,7 @@ int ssn_destroy(ssn_ctx *c)
     if (c->st_aux) (void)hipStreamSynchronize(c->st_aux);      // a view of the next sample may still be in the making
     void *dev[] = {c->Zbuf, c->ls_dots, c->Ubuf, c->Pbuf, c->part, c->loss_part, c->hit_part, c->red_a, c->red_b, c->red_c, c->red_sq, c->scal_dev, c->int_dev,
                    c->cg_p, c->cg_r, c->cg_s, c->cg_hs, c->cg_parts, c->cg_pb, c->trial, c->grad, c->grad_next, c->dir, c->slots, c->trace_dev,
-                   c->tail_row};
+                   c->tail_row, c->csr1_rwin, c->csr1_zrow, c->csr1_zhead};
     for (void *p : dev)
         if (p) (void)hipFree(p);
     if (c->host_pin) (void)hipHostFree(c->host_pin);
@@ -887,6 +904,13 @@ int ssn_create(ssn_ctx **out, const ssn_desc *d)
             CREATE_HIP(launch_check_range(d->colidx, d->nnz, 0, d->p, c->int_dev, c->st));
             if (read_int(c, c->int_dev, &bad) != SSN_OK) return bail(SSN_E_HIP);
             if (bad) return bail(SSN_E_BAD_INDEX);
+        }
+        if (c->K == 1 && d->nnz > 0) {
+            const int64_t nwin = (d->nnz + 63) / 64;
+            CREATE_HIP(hipMalloc((void **)&c->csr1_rwin, sizeof(int32_t) * nwin));
+            CREATE_HIP(hipMalloc(&c->csr1_zrow, c->es * d->n));
+            CREATE_HIP(hipMalloc(&c->csr1_zhead, c->es * nwin));
+            CREATE_HIP(launch_csr_window_rows(d->rowptr, d->n, d->nnz, c->csr1_rwin, c->st));
         }
     }
 #undef CREATE_HIP

@@ -59,6 +59,11 @@ struct RowsArgs {
     // CSR rows kernel only: non-zero -> a workgroup per row, the row's entries shared out among its four waves (set by
     // the launcher for passes over few, long rows)
     int32_t csr_split;
+    // CSR, one weight column, full passes only (set by the launcher): the row that holds entry 64 w for every aligned
+    // window of 64 stored entries, the rows' margins (n values), the windows' leading partial sums, the entry count
+    const int32_t *rwin;
+    void *zrow, *zhead;
+    int64_t nnz;
 };
 
 // Arguments of the transposed product: part[chunk] = X_rows(chunk)^T * U(chunk).
@@ -118,6 +123,8 @@ hipError_t launch_dense_rows(int dtype, const RowsArgs &a, int blocks, int split
 hipError_t launch_dense_xtu(int dtype, const XtuArgs &a, hipStream_t st);
 // partial margins of feature slices: Zpart[s][row][16] = X_rows[:, slice s] * M[slice s, :] for `nslices` slices of
 // `fper` features (a multiple of 32), a workgroup of eight waves per (row block, slice); K <= 16, 16-byte aligned rows
+// rwin[w] = the row that holds stored entry 64 w (w < ceil(nnz / 64)); rows may be empty
+hipError_t launch_csr_window_rows(const int32_t *rowptr, int64_t n, int64_t nnz, int32_t *rwin, hipStream_t st);
 hipError_t launch_dense_zpart(int dtype, const RowsArgs &a, void *Zpart, int nslices, int64_t fper, hipStream_t st);
 bool dense_fused_supported(int dtype, const RowsArgs &a);
 int dense_fused_grid(int dtype, const RowsArgs &a, int num_cus);

@@ -230,3 +230,41 @@ def test_sparse_binary_columns_that_end_where_a_wave_of_pieces_ends(dtype):
         torch.cuda.synchronize()
         assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
     pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_sparse_binary_full_passes_with_a_lane_per_entry_on_odd_row_lengths(dtype):
+    # Full passes over a CSR matrix with one weight column take the stored entries in aligned windows of 64, a lane per
+    # entry, and find each entry's row among the 63 rows that follow the window's first.  Here most rows have no entry
+    # or one (far more than 63 rows end inside a window: the rows are looked up in the row pointers instead), a few
+    # have hundreds (one row runs through several windows), the last rows are empty, and one row ends exactly where
+    # a window ends.
+    n, p = 50_000, 300
+    g = np.random.default_rng(19)
+    counts = g.integers(0, 2, size=n)
+    counts[::997] = g.integers(150, 300, size=counts[::997].size)
+    counts[5] = 64 + (-int(counts[:5].sum())) % 64       # row 5 ends where a window ends
+    counts[-40:] = 0
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(counts, out=rowptr[1:])
+    assert rowptr[6] % 64 == 0 and counts[5] > 0
+    nnz = int(rowptr[-1])
+    colidx = np.concatenate([np.sort(g.choice(p, size=k, replace=False)) for k in counts if k]).astype(np.int32)
+    vals = g.standard_normal(nnz)
+    labels = g.integers(0, 2, size=n).astype(np.int32)
+    d = dict(layout="csr", rowptr=rowptr, colidx=colidx, vals=vals, labels=labels, C=2, K=1, p=p, n=n, lam=1e-3, nnz=nnz)
+    pair = Pair(d, dtype)
+    tol = TOL[dtype]
+    for scale in (0.0, 0.7):
+        Wh, Wd = pair.block(scale * g.standard_normal((p, 1)))
+        print(f"[case] sparse binary, lane per entry, odd row lengths dtype={dtype} scale={scale}", flush=True)
+        f = pair.gpu.ssn_objective(Wd)
+        G, f2 = pair.gpu.ssn_gradient(Wd)
+        pred, acc = pair.gpu.ssn_predict(Wd)
+        torch.cuda.synchronize()
+        G_ref, f_ref = pair.oracle.gradient(Wh)
+        assert rel_scalar(f, f_ref) <= tol and rel_scalar(f2, f_ref) <= tol
+        assert rel_err(pair.host(G), G_ref) <= tol
+        flips = int(np.count_nonzero(pred.cpu().numpy() != pair.oracle.predict(Wh)))
+        assert flips <= (0 if dtype == F64 else n // 500)
+    pair.close()
