@@ -17,6 +17,7 @@
 // uneven row lengths) uses hipCUB's device radix sort and prefix sums; the construction of a sample's
 // view from the whole matrix's and the product kernels are hand-written.
 #include "ssn_internal.h"
+#include "ssn_math.h"
 
 #include <hipcub/hipcub.hpp>
 
@@ -974,9 +975,11 @@ template <typename T> __global__ __launch_bounds__(256) void csc_piece_kernel(Cs
 // One weight column (the binary problem): the job of csc_piece_kernel with a lane per ENTRY instead of a lane per
 // piece.  With K = 1 a lane group is a single lane that walks its piece of up to 64 entries alone, so the lanes of a
 // wave read 64 different stretches of the entry arrays; here a wave takes one aligned window of 64 entries (pieces
-// start at every 64th entry, so a window holds whole pieces), reads rows, values and the gathered u coalesced, and
-// adds the products of each piece by a segmented reduction over the lanes (fixed order).  The piece's first lane
-// adds a whole column into the result or leaves the piece's partial sum, exactly as csc_piece_kernel does;
+// start at every 64th entry, so a window holds whole pieces) and reads rows, values and the gathered u coalesced.
+// The products are added along the wave by an inclusive scan on the vector units (fp64 in both precisions); then the
+// lanes change roles: lane j stands for the window's j-th piece, reads where it starts and ends (coalesced) and takes
+// its sum as the difference of the scan values at its last entry and before its first.  The piece's lane adds a
+// whole column into the result or leaves the piece's partial sum, exactly as csc_piece_kernel does;
 // csc1_combine_kernel then adds the partial sums of the columns of several pieces.
 template <typename T> __global__ __launch_bounds__(256) void csc1_window_kernel(CscApply a)
 {
@@ -991,29 +994,30 @@ template <typename T> __global__ __launch_bounds__(256) void csc1_window_kernel(
     if (w * 64 >= a.nnz) return;                                 // the whole wave
     const int64_t e = w * 64 + lane;
     const bool have = e < a.nnz;
-    const int col = have ? a.key[e] : -1;
     const int r = have ? a.row[e] : 0;
     const T v = have ? ((const T *)a.val)[e] : T(0);
-    T x = have ? v * ((const T *)a.U)[(int64_t)r * a.KP] : T(0);
-    const int prev = __shfl_up(col, 1);
-    const bool start = lane == 0 || col != prev;                 // a piece (or the padding behind the last entry) starts here
-    const unsigned long long starts = __ballot(start);
-    const unsigned long long above = (lane == 63) ? 0ull : ((starts >> (lane + 1)) << (lane + 1));
-    const int send = above ? (__ffsll((long long)above) - 2) : 63;       // last lane of this lane's piece
-    for (int d = 1; d < 64; d <<= 1) {
-        const T y = __shfl_down(x, d);
-        if (lane + d <= send) x += y;
-    }
-    if (start && have) {
-        const int64_t pid = (int64_t)a.win_pid[w] + __popcll(starts & ((1ull << lane) - 1ull));
-        const int ocol = a.piece_col[pid];
-        const bool head = (pid == 0) || (a.piece_col[pid - 1] != ocol);
-        const bool more = a.piece_col[pid + 1] == ocol;
+    // this lane's piece in its second role: the window's pieces are win_pid[w] .. (next window's first piece) - 1
+    const int64_t pid0 = a.win_pid[w];
+    const int64_t pend = ((w + 1) * 64 < a.nnz) ? (int64_t)a.win_pid[w + 1] : (int64_t)a.npieces;
+    const int64_t pid = pid0 + lane;
+    const bool piece = pid < pend;
+    const int64_t pq = piece ? pid : pid0;                       // (lanes without a piece read the first one's numbers)
+    const int ps = a.piece_start[pq], pe = a.piece_start[pq + 1];
+    const int ocol = a.piece_col[pq];
+    const int pcol = (pq > 0) ? a.piece_col[pq - 1] : -2;
+    const int ncol = a.piece_col[pq + 1];
+    const double x = have ? (double)v * (double)((const T *)a.U)[(int64_t)r * a.KP] : 0.0;
+    const double P = wave_inclusive_scan(x);
+    const int b = ps - (int)(w * 64), en = pe - (int)(w * 64);   // 0 <= b < en <= 64
+    const double Pe = __shfl(P, en - 1), Pb = __shfl(P, b > 0 ? b - 1 : 0);
+    if (piece) {
+        const T sum = (T)((b > 0) ? Pe - Pb : Pe);
+        const bool head = ocol != pcol, more = ncol == ocol;
         if (head && !more) {
             T *o = (T *)a.out + (int64_t)ocol * a.ldo;
-            *o = (T)((double)*o + coef * (double)x);
+            *o = (T)((double)*o + coef * (double)sum);
         } else {
-            ((T *)a.piece_part)[pid] = x;
+            ((T *)a.piece_part)[pid] = sum;
         }
     }
 }
@@ -1061,13 +1065,22 @@ template <typename T> __global__ __launch_bounds__(256) void csc1_combine_kernel
     const int lasthead = __shfl((int)head, laststart);
     T csum = T(0);
     if (lastcol >= 0 && lastnext == lastcol && lasthead) {       // uniform over the wave
-        for (int64_t j0 = base + 64;; j0 += 64) {
-            const int64_t j = j0 + lane;
-            const bool m = j < a.npieces && a.piece_col[j] == lastcol;
-            T y = m ? pp[j] : T(0);
-            for (int off = 32; off > 0; off >>= 1) y += __shfl_xor(y, off);
-            csum += y;
-            if (!__all(m)) break;
+        // 256 pieces per step, all their loads requested together (a piece that is not this column's is read and
+        // dropped); the step's sum is the last lane's value of a scan over the lanes
+        for (int64_t j0 = base + 64;; j0 += 256) {
+            T y[4];
+            bool m[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int64_t j = j0 + 64 * k + lane, jc = j < a.npieces ? j : (int64_t)a.npieces - 1;
+                const int c = a.piece_col[jc];
+                const T pv = pp[jc];
+                m[k] = j < a.npieces && c == lastcol;
+                y[k] = m[k] ? pv : T(0);
+            }
+            const double t = ((double)y[0] + (double)y[1]) + ((double)y[2] + (double)y[3]);
+            csum += (T)__shfl(wave_inclusive_scan(t), 63);
+            if (!__all(m[3])) break;
         }
     }
     if (start && head && more) {                                 // first piece of a column of several: the column's writer

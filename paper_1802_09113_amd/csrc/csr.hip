@@ -277,14 +277,16 @@ template <typename T, int MODE> __global__ __launch_bounds__(64 * ROWS_WAVES_PER
 // One weight column, passes over ALL rows of the matrix: a lane per stored ENTRY instead of a wave per row.  A row of
 // a few dozen entries gives a wave one short, dependent chain (pointers -> entries -> weights -> sum) and leaves half
 // its lanes idle; here a wave takes an aligned window of 64 consecutive entries of the CSR arrays -- coalesced, no
-// pointer chasing: the row of the window's first entry comes from an index built once (csr_window_rows_kernel), the
-// ends of that row and the 62 after it from one coalesced read of the row pointers, and every lane finds its row among
-// them by a search over the lanes.  The products x_e w_col are added per row by a segmented reduction over the lanes
-// (fixed order).  A row's first segment goes to zrow[row]; the leading segment of a window whose row began in an
-// earlier window goes to zhead[window]; csr1_rowwork_kernel adds a row's pieces (its first segment, then the leading
-// sums of the windows it runs into, in window order) and does the per-row work of eqs. (8), (9), (14)-(17) with a lane
-// per row.  Windows in which more than 63 rows end (runs of empty or one-entry rows) look their rows up in the row
-// pointers directly.
+// pointer chasing: the row of the window's first entry comes from an index built once (csr_window_rows_kernel).  The
+// products x_e w_col are added up along the wave by an inclusive scan on the vector units (lane shifts inside rows of
+// 16 lanes, then the two row broadcasts: no LDS traffic); then the lanes change roles -- lane j stands for row r0 + j,
+// reads that row's first and last entry from the row pointers (coalesced), and takes the row's sum inside the window
+// as the difference of two scan values fetched from the lanes of its last entry and of the entry before its first
+// (the scan runs in fp64 whatever the data's precision, so the difference costs the sum nothing that shows).  A row that begins in the window leaves its
+// sum in zrow[row] (coalesced), the leading part of a row that began in an earlier window goes to zhead[window];
+// csr1_rowwork_kernel adds a row's pieces (its own, then the leading sums of the windows it runs into, in window
+// order) and does the per-row work of eqs. (8), (9), (14)-(17) with a lane per row.  Windows that more than 64 rows
+// reach into (runs of empty or one-entry rows) take the rows 64 at a time.
 __global__ __launch_bounds__(256) void csr_window_rows_kernel(const int32_t *rowptr, int64_t n, int64_t nwin, int32_t *rwin)
 {
     const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -316,7 +318,7 @@ template <typename T> __global__ __launch_bounds__(256) void csr1_flat_kernel(Ro
     const int lane = threadIdx.x & 63;
     const int64_t w0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * FLAT_WINDOWS;
     if (w0 * 64 >= a.nnz) return;                                // the whole wave
-    int col[FLAT_WINDOWS], r0[FLAT_WINDOWS], rp[FLAT_WINDOWS], rbeg0[FLAT_WINDOWS];
+    int col[FLAT_WINDOWS], r0[FLAT_WINDOWS], rs[FLAT_WINDOWS], re[FLAT_WINDOWS];
     T v[FLAT_WINDOWS], m[FLAT_WINDOWS];
 #pragma unroll
     for (int i = 0; i < FLAT_WINDOWS; ++i) {
@@ -328,54 +330,38 @@ template <typename T> __global__ __launch_bounds__(256) void csr1_flat_kernel(Ro
     }
 #pragma unroll
     for (int i = 0; i < FLAT_WINDOWS; ++i) {
-        const int64_t ri = ((int64_t)r0[i] + 1 + lane < a.n) ? (int64_t)r0[i] + 1 + lane : a.n;
-        rp[i] = a.rowptr[ri];                                    // end of row r0 + lane (the entry count behind the last row)
-        rbeg0[i] = a.rowptr[r0[i]];
+        const int64_t r = (int64_t)r0[i] + lane;                 // this lane's row in its second role
+        rs[i] = a.rowptr[r < a.n ? r : a.n];                     // (the entry count behind the last row)
+        re[i] = a.rowptr[r + 1 < a.n ? r + 1 : a.n];
         m[i] = ((const T *)a.M)[(int64_t)col[i] * a.ldm];
     }
 #pragma unroll
     for (int i = 0; i < FLAT_WINDOWS; ++i) {
         const int64_t w = w0 + i;
         if (w * 64 >= a.nnz) break;                              // the whole wave
-        const int64_t eg64 = w * 64 + lane;
-        const bool have = eg64 < a.nnz;
-        const int eg = (int)eg64;                                // entry counts fit 31 bits
-        T x = have ? v[i] * m[i] : T(0);
-        // rows that end at or before this lane's entry, among rows r0 .. r0 + 62
-        int lo = 0;
-        for (int step = 32; step >= 1; step >>= 1) {
-            const int val = __shfl(rp[i], lo + step - 1);
-            if (val <= eg) lo += step;
-        }
-        const int rp63 = __shfl(rp[i], 63);
-        int rbeg = __shfl(rp[i], lo > 0 ? lo - 1 : 0);           // where this lane's row begins
-        if (lo == 0) rbeg = rbeg0[i];
-        int row = r0[i] + lo;
-        if (have && lo == 63 && rp63 <= eg) {                    // more than 63 rows end inside this window
-            int64_t l2 = (int64_t)r0[i] + 64, h2 = a.n;          // rowptr[l2] <= eg < rowptr[h2]
-            while (h2 - l2 > 1) {
-                const int64_t mid = (l2 + h2) >> 1;
-                if (a.rowptr[mid] <= eg) l2 = mid;
-                else h2 = mid;
+        const int wbeg = (int)(w * 64);                          // entry counts fit 31 bits
+        const int wend = (a.nnz - wbeg < 64) ? (int)a.nnz : wbeg + 64;
+        // (the scan runs in fp64 in both precisions: a difference of two fp32 prefix sums would lose the bits that
+        // the sums before the row have used up, and the line search near convergence compares objectives to the last)
+        const double P = wave_inclusive_scan((wbeg + lane < wend) ? (double)v[i] * (double)m[i] : 0.0);
+        int rsl = rs[i], rel = re[i];
+        for (int64_t base = r0[i];;) {
+            const int b = (rsl > wbeg ? rsl : wbeg) - wbeg, e = (rel < wend ? rel : wend) - wbeg;
+            const double Pe = __shfl(P, e > 0 ? e - 1 : 0), Pb = __shfl(P, b > 0 ? b - 1 : 0);
+            if (base + lane < a.n && e > b) {
+                const T sum = (T)((b > 0) ? Pe - Pb : Pe);
+                if (rsl < wbeg) ((T *)a.zhead)[w] = sum;         // (lane 0 of the first 64 rows only)
+                else ((T *)a.zrow)[base + lane] = sum;
             }
-            row = (int)l2;
-            rbeg = a.rowptr[l2];
+            if (base == r0[i] && lane == 0 && !(rsl < wbeg)) ((T *)a.zhead)[w] = T(0);
+            // the rows behind these 64 reach into the window too?
+            const int last_end = __shfl(rel, 63);
+            base += 64;
+            if (last_end >= wend || base >= a.n) break;          // uniform over the wave
+            const int64_t r = base + lane;
+            rsl = a.rowptr[r < a.n ? r : a.n];
+            rel = a.rowptr[r + 1 < a.n ? r + 1 : a.n];
         }
-        const int rowk = have ? row : -1;
-        const int below = __shfl_up(rowk, 1);                    // (every lane takes part in the exchange)
-        const bool start = lane == 0 || rowk != below;
-        const unsigned long long starts = __ballot(start);
-        const unsigned long long above = (lane == 63) ? 0ull : ((starts >> (lane + 1)) << (lane + 1));
-        const int send = above ? (__ffsll((long long)above) - 2) : 63;
-        for (int d = 1; d < 64; d <<= 1) {
-            const T y = __shfl_down(x, d);
-            if (lane + d <= send) x += y;
-        }
-        if (start && have) {
-            if (rbeg < eg) ((T *)a.zhead)[w] = x;                // lane 0 only: the row began in an earlier window
-            else ((T *)a.zrow)[row] = x;
-        }
-        if (lane == 0 && !(rbeg < eg)) ((T *)a.zhead)[w] = T(0);
     }
 }
 

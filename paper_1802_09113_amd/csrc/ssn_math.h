@@ -64,4 +64,25 @@ __device__ __forceinline__ double log_ge1(double a, double zero)
 }
 __device__ __forceinline__ double log_ge1(double a) { return log_ge1(a, 0.0); }
 
+// x shifted along the wave by a DPP control word, lanes without a source lane (and rows or banks masked out) get 0
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ double dpp_or_zero(double x)
+{
+    const long long b = __double_as_longlong(x);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffll), CTRL, ROW_MASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, ROW_MASK, 0xf, false);
+    return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned)lo);
+}
+// inclusive sum over the lanes of a wave: shifts by 1, 2, 4, 8 inside each row of 16 lanes, then lane 15 of rows 0 and
+// 2 is added to the rows behind them (row_bcast:15 into rows 1 and 3) and lane 31 to the upper half (row_bcast:31)
+__device__ __forceinline__ double wave_inclusive_scan(double x)
+{
+    x += dpp_or_zero<0x111, 0xf>(x);
+    x += dpp_or_zero<0x112, 0xf>(x);
+    x += dpp_or_zero<0x114, 0xf>(x);
+    x += dpp_or_zero<0x118, 0xf>(x);
+    x += dpp_or_zero<0x142, 0xa>(x);
+    x += dpp_or_zero<0x143, 0xc>(x);
+    return x;
+}
+
 }  // namespace ssn
