@@ -268,3 +268,40 @@ def test_sparse_binary_full_passes_with_a_lane_per_entry_on_odd_row_lengths(dtyp
         flips = int(np.count_nonzero(pred.cpu().numpy() != pair.oracle.predict(Wh)))
         assert flips <= (0 if dtype == F64 else n // 500)
     pair.close()
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+@pytest.mark.parametrize("counts", [[1], [0, 0, 0], [3, 0, 2], [1] * 70, [0] * 5 + [130] + [0] * 3, [64, 64, 1]],
+                         ids=["one_entry", "no_entries", "three_rows", "seventy_rows", "one_long_row", "whole_windows"])
+def test_sparse_binary_tiny_matrices(counts, dtype):
+    # degenerate shapes of the one-weight-column CSR kernels: a single stored entry, none at all, fewer entries than
+    # one window of 64, a last window that is not full, one row that is longer than two windows between empty rows,
+    # rows that fill windows exactly
+    counts = np.array(counts, dtype=np.int64)
+    n, p = counts.size, 140
+    g = np.random.default_rng(int(counts.sum()) + n)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(counts, out=rowptr[1:])
+    nnz = int(rowptr[-1])
+    colidx = (np.concatenate([np.sort(g.choice(p, size=k, replace=False)) for k in counts]).astype(np.int32)
+              if nnz else np.zeros(0, dtype=np.int32))
+    vals = g.standard_normal(nnz)
+    labels = g.integers(0, 2, size=n).astype(np.int32)
+    d = dict(layout="csr", rowptr=rowptr, colidx=colidx, vals=vals, labels=labels, C=2, K=1, p=p, n=n, lam=1e-2, nnz=nnz)
+    pair = Pair(d, dtype)
+    tol = TOL[dtype]
+    Wh, Wd = pair.block(0.5 * g.standard_normal((p, 1)))
+    Vh, Vd = pair.block(g.standard_normal((p, 1)))
+    print(f"[case] sparse binary tiny counts={counts.tolist()[:8]} dtype={dtype}", flush=True)
+    f = pair.gpu.ssn_objective(Wd)
+    G, f2 = pair.gpu.ssn_gradient(Wd)
+    S = np.arange(n, dtype=np.int32)
+    HV = pair.gpu.ssn_hessvec(Wd, pair.idx(S), Vd)
+    pred, acc = pair.gpu.ssn_predict(Wd)
+    torch.cuda.synchronize()
+    G_ref, f_ref = pair.oracle.gradient(Wh)
+    assert rel_scalar(f, f_ref) <= tol and rel_scalar(f2, f_ref) <= tol
+    assert rel_err(pair.host(G), G_ref) <= tol
+    assert rel_err(pair.host(HV), pair.oracle.hessvec(Wh, S, Vh)) <= tol
+    assert np.array_equal(pred.cpu().numpy(), pair.oracle.predict(Wh)) or dtype == F32
+    pair.close()
