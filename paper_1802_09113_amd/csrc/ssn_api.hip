@@ -302,6 +302,9 @@ int launch_rows(ssn_ctx *c, const RowsArgs &a, int *nparts)
             b.zrow = c->csr1_zrow;
             b.zhead = c->csr1_zhead;
             b.nnz = c->d.nnz;
+            // the per-row kernel takes a row per lane: a workgroup per 256 rows (and that many fewer partial sums)
+            const int64_t rb = (a.nrows + 64 * ROWS_WAVES_PER_BLOCK - 1) / (64 * ROWS_WAVES_PER_BLOCK);
+            if (rb < blocks) blocks = (int)(rb < 1 ? 1 : rb);
             if (blocks * ROWS_WAVES_PER_BLOCK > c->wave_parts) return fail(c, SSN_E_INVALID_ARG, "internal: wave partial overflow");
             SSN_HIP(c, launch_csr_rows(c->d.dtype, b, blocks, c->st));
             if (nparts) *nparts = blocks * ROWS_WAVES_PER_BLOCK;
