@@ -694,8 +694,11 @@ __global__ __launch_bounds__(VEC_BLOCK) void combine_kernel(const double *a, int
 // f = scale * sum(loss partials) + half_lambda * ||W||^2 in ONE launch for small blocks: the single block adds
 // up the squares of W itself (eight elements per thread in flight), and mirrors the value into host-visible
 // memory (nullable) so that the caller only has to wait for the stream, not for a copy
+// (sixteen waves: the block's one pass over W and over the partials is a chain of trips to memory, eight loads per
+// thread and trip, and with four waves a block of 27 648 weights took fourteen trips)
+constexpr int OBJ_BLOCK = 1024;
 template <typename T>
-__global__ __launch_bounds__(VEC_BLOCK) void objective_value_kernel(const double *loss_part, int nparts, double scale,
+__global__ __launch_bounds__(OBJ_BLOCK) void objective_value_kernel(const double *loss_part, int nparts, double scale,
                                                                      const T *W, int64_t p, int K, int64_t ldw,
                                                                      double half_lambda, double *out, double *out_host,
                                                                      unsigned long long *ticket_host,
@@ -703,21 +706,47 @@ __global__ __launch_bounds__(VEC_BLOCK) void objective_value_kernel(const double
 {
     const int64_t total = p * K;
     double sq = 0.0;
-    for (int64_t e0 = threadIdx.x; e0 < total; e0 += 8 * VEC_BLOCK) {
+    for (int64_t e0 = threadIdx.x; e0 < total; e0 += 8 * OBJ_BLOCK) {
         T w[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int64_t e = e0 + (int64_t)u * VEC_BLOCK;
+            const int64_t e = e0 + (int64_t)u * OBJ_BLOCK;
             w[u] = W[off_of(e < total ? e : e0, K, ldw)];
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            if (e0 + (int64_t)u * VEC_BLOCK < total) sq += (double)w[u] * (double)w[u];
+            if (e0 + (int64_t)u * OBJ_BLOCK < total) sq += (double)w[u] * (double)w[u];
     }
-    const double loss = thread_parts(loss_part, nparts);
-    double sl, ss;
-    block_sum2(loss, sq, sl, ss);
+    double loss = 0.0;
+    for (int i0 = threadIdx.x; i0 < nparts; i0 += 8 * OBJ_BLOCK) {
+        double t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * OBJ_BLOCK;
+            t[u] = loss_part[i < nparts ? i : i0];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (i0 + u * OBJ_BLOCK < nparts) loss += t[u];
+    }
+    // the block's two sums: over the lanes of a wave, then over the waves in wave order
+    __shared__ double sm[2 * (OBJ_BLOCK / 64)];
+    for (int off = 32; off > 0; off >>= 1) {
+        loss += __shfl_xor(loss, off);
+        sq += __shfl_xor(sq, off);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        sm[threadIdx.x >> 6] = loss;
+        sm[OBJ_BLOCK / 64 + (threadIdx.x >> 6)] = sq;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
+        double sl = sm[0], ss = sm[OBJ_BLOCK / 64];
+#pragma unroll
+        for (int k = 1; k < OBJ_BLOCK / 64; ++k) {
+            sl += sm[k];
+            ss += sm[OBJ_BLOCK / 64 + k];
+        }
         const double f = scale * sl + half_lambda * ss;
         *out = f;
         post_to_host(f, out_host, ticket_host, ticket);
@@ -729,10 +758,10 @@ hipError_t launch_objective_value(int dtype, const double *loss_part, int nparts
                                   unsigned long long *ticket_host, unsigned long long ticket, hipStream_t st)
 {
     if (dtype == SSN_F32)
-        hipLaunchKernelGGL(objective_value_kernel<float>, dim3(1), dim3(VEC_BLOCK), 0, st, loss_part, nparts, scale,
+        hipLaunchKernelGGL(objective_value_kernel<float>, dim3(1), dim3(OBJ_BLOCK), 0, st, loss_part, nparts, scale,
                            (const float *)W, p, K, ldw, half_lambda, out, out_host, ticket_host, ticket);
     else
-        hipLaunchKernelGGL(objective_value_kernel<double>, dim3(1), dim3(VEC_BLOCK), 0, st, loss_part, nparts, scale,
+        hipLaunchKernelGGL(objective_value_kernel<double>, dim3(1), dim3(OBJ_BLOCK), 0, st, loss_part, nparts, scale,
                            (const double *)W, p, K, ldw, half_lambda, out, out_host, ticket_host, ticket);
     return hipGetLastError();
 }
